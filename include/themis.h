@@ -1,0 +1,220 @@
+/*
+ * themis.h -- C ABI of the MI355X (gfx950) batched evaluator for the Themis
+ * collective chunk scheduler (arXiv 2110.04478).
+ *
+ * The library evaluates, for very large batches of independent scenarios,
+ *   (1) the bandwidth-aware greedy chunk scheduler (paper Alg. 1,
+ *       Sec. 4.2) that gives every chunk of a hierarchical All-Reduce its own
+ *       order of network dimensions, and
+ *   (2) the deterministic per-dimension queue simulation (paper Sec. 4.3
+ *       intra-dimension policy, Sec. 4.6.2 consistency simulation) that turns
+ *       such a plan into per-dimension execution orders and a completion time.
+ * Nothing is communicated between devices: the collective is modelled, as in
+ * the paper's own evaluation.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every pointer inside themis_batch_t and every array argument is a DEVICE
+ *    pointer (HBM of the current HIP device), caller-owned.  The library never
+ *    allocates or frees memory, keeps no global mutable state and is
+ *    re-entrant.  Outputs are fully overwritten.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue kernels on that stream and return; they do not
+ *    synchronise.
+ *  - Arrays are structure-of-arrays: a per-dimension field is laid out
+ *    [THEMIS_MAX_DIMS][n] (dimension-major), so a wavefront reads 64
+ *    consecutive scenarios' values in one coalesced access.
+ *  - Return value: THEMIS_OK (0) or a negative themis_status_t.  Argument
+ *    errors that the host can see (NULL pointers, n == 0 is allowed and is a
+ *    no-op, max_chunks out of range, ...) are reported without launching
+ *    anything.  Errors inside one scenario (ndims outside 1..4, P < 2, a
+ *    bandwidth / size / threshold that is not positive and finite, chunks
+ *    outside 1..max_chunks) do not fail the batch: that scenario's times are
+ *    written as NaN and its order codes / queue entries as all-ones bytes.
+ *  - All times are seconds in IEEE binary64, sizes are bytes, bandwidths
+ *    bytes/second (uni-directional, per NPU, per dimension).  Arithmetic is
+ *    unfused (no FMA contraction) and in the operation order documented at
+ *    each entry point, so results are reproducible bit for bit.
+ *
+ * Model (paper Sec. 2.1, 2.3, 4.5; A_K = 0, bandwidth term only)
+ * -------------------------------------------------------------
+ *   chunk      = size_bytes / chunks
+ *   coef[k]    = ((P_k - 1) / P_k) / bw_k          seconds per resident byte
+ *   A Reduce-Scatter stage on dimension k entered with x resident bytes costs
+ *   x * coef[k] and leaves x / P_k.  The All-Gather stage of the same chunk on
+ *   the same dimension moves the same bytes and costs the same time, and
+ *   multiplies the resident size by P_k.  A chunk runs D Reduce-Scatter stages
+ *   in its own dimension order, then D All-Gather stages in the reverse order.
+ */
+#ifndef THEMIS_H
+#define THEMIS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define THEMIS_MAX_DIMS 4
+/* Largest ChunksPerCollective accepted (the paper sweeps 4..512, Sec. 6.1). */
+#define THEMIS_MAX_CHUNKS 512
+
+typedef enum themis_status {
+  THEMIS_OK = 0,
+  THEMIS_ERR_INVALID_ARGUMENT = -1, /* NULL pointer, bad size or enum      */
+  THEMIS_ERR_UNSUPPORTED = -2,      /* a valid request this build lacks    */
+  THEMIS_ERR_DEVICE = -3,           /* a HIP call failed (launch, device)  */
+  THEMIS_ERR_WORKSPACE = -4         /* workspace missing or too small      */
+} themis_status_t;
+
+/* Inter-dimension scheduler of a scenario (paper Table 3). */
+enum { THEMIS_INTER_BASELINE = 0, THEMIS_INTER_THEMIS = 1 };
+/* Intra-dimension queue policy (paper Sec. 4.3): first-in-first-out, or
+ * Smallest-Chunk-First on the resident size before the stage. */
+enum { THEMIS_INTRA_FIFO = 0, THEMIS_INTRA_SCF = 1 };
+/* Meaning of threshold[] in line 19 of Alg. 1:
+ *   ABS: seconds.
+ *   REL: fraction f; Threshold = f * (time of a Reduce-Scatter of one whole
+ *        chunk on the currently least-loaded dimension).  The paper's default
+ *        (Sec. 5.3) is f = 1/16. */
+enum { THEMIS_THR_ABS = 0, THEMIS_THR_REL = 1 };
+
+/* Bits of themis_sweep's policy_mask, evaluated in ascending bit order. */
+enum {
+  THEMIS_SWEEP_BASELINE = 1u,    /* baseline order + FIFO   */
+  THEMIS_SWEEP_THEMIS_FIFO = 2u, /* Alg. 1 + FIFO           */
+  THEMIS_SWEEP_THEMIS_SCF = 4u   /* Alg. 1 + SCF            */
+};
+
+/*
+ * One batch of n independent scenarios (inputs of Alg. 1 plus the network:
+ * P_1 x ... x P_D with one bandwidth per dimension, Sec. 2.3).
+ * All pointers are device pointers; the struct itself lives on the host.
+ */
+typedef struct themis_batch {
+  uint64_t n;              /* number of scenarios                              */
+  uint32_t max_chunks;     /* row stride of `orders`; 1..THEMIS_MAX_CHUNKS;
+                              every chunks[i] must be <= max_chunks           */
+  uint32_t threshold_mode; /* THEMIS_THR_ABS or THEMIS_THR_REL (whole batch)   */
+  const uint8_t *ndims;    /* [n]    D, 1..THEMIS_MAX_DIMS                     */
+  const uint32_t *npus;    /* [4][n] P_k >= 2; rows k >= D are ignored         */
+  const double *bw;        /* [4][n] bytes/s, > 0 and finite                   */
+  const double *size_bytes;/* [n]    CollectiveSize S, > 0 and finite          */
+  const uint32_t *chunks;  /* [n]    ChunksPerCollective C                     */
+  const uint8_t *inter_policy; /* [n] THEMIS_INTER_*                           */
+  const uint8_t *intra_policy; /* [n] THEMIS_INTRA_* (used by simulate only)   */
+  const double *threshold; /* [n]    >= 0 (may be +inf in ABS mode)            */
+  /* Optional trace extension (several collectives sharing the per-dimension
+   * queues; NULL / 0 = one collective of size_bytes released at t = 0).
+   * When n_coll is non-NULL, scenario i issues n_coll[i] collectives; number q
+   * has coll_size[q*n + i] bytes, is planned on its own (the load tracker is
+   * reset per collective, Alg. 1 line 2) and releases all its chunks at
+   * release_time[q*n + i] seconds (NULL = all zero). */
+  uint32_t max_coll;          /* leading extent of coll_size / release_time    */
+  const uint32_t *n_coll;     /* [n]            1..max_coll                    */
+  const double *coll_size;    /* [max_coll][n]                                 */
+  const double *release_time; /* [max_coll][n]  >= 0, or NULL                  */
+} themis_batch_t;
+
+/* Library version as major*10000 + minor*100 + patch. */
+int themis_version(void);
+
+/* Static English description of a status code (never NULL). */
+const char *themis_status_string(int status);
+
+/*
+ * Order code of one chunk: byte o0 | o1<<2 | o2<<4 | o3<<6, the 0-based
+ * dimensions in the order its Reduce-Scatter stages visit them (fields at
+ * positions >= D are zero).  The All-Gather order is the reverse (Alg. 1
+ * line 8).  0xFF marks an invalid scenario or an unused chunk slot.
+ *
+ * Queue-order entry: (chunk_id << 1) | phase, phase 0 = Reduce-Scatter,
+ * 1 = All-Gather, listed per dimension in the order the dimension executed
+ * them (Sec. 4.6.2).  chunk_id is q*chunks + i in trace mode.  The entry is
+ * one byte when 2*slots <= 256 and two bytes (little endian uint16) otherwise,
+ * where slots = max_chunks * max(1, max_coll); themis_queue_entry_bytes()
+ * returns that width.  Unused entries are all-ones.
+ */
+int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
+
+/*
+ * Bytes of scratch that themis_simulate_batch / themis_sweep may need for the
+ * scenarios their fast path does not cover (any P_k that is not a power of
+ * two, or a size whose halvings would leave the normal binary64 range).
+ * Passing a smaller or NULL workspace is allowed: such scenarios then come
+ * back as NaN and the call returns THEMIS_ERR_WORKSPACE after enqueueing the
+ * rest.  The workspace must stay untouched until the stream has drained.
+ */
+size_t themis_workspace_bytes(uint64_t n, uint32_t max_chunks, uint32_t max_coll);
+
+/*
+ * themis_plan_batch -- Alg. 1 (Schedule_Collective + Scheduler.Schedule) for
+ * every scenario.
+ *
+ * Per scenario, with load[k] = 0 (A_K = 0, Sec. 4.5) and for chunk i = 0..C-1:
+ *   kmin = lowest index of the smallest load; lo = load[kmin]; hi = max load
+ *   Threshold = threshold (ABS) or threshold * (chunk * coef[kmin]) (REL)
+ *   order = 0,1,..,D-1 if inter_policy is BASELINE or (hi - lo) < Threshold,
+ *           else the dimensions sorted by load ascending, ties keeping the
+ *           lower index first (so equal loads give the baseline order)
+ *   x = chunk; for j = 0..D-1, k = order[j]:
+ *       t = x * coef[k]; load[k] = load[k] + (t + t); x = x / P_k
+ * (the tracker accumulates the Reduce-Scatter and the All-Gather time of the
+ * chunk on every dimension: the total communication time of the caption of
+ * the paper's scheduling figure).
+ *
+ *   orders : [n][max_chunks] uint8 order codes (slots >= chunks[i] = 0xFF).
+ *            In trace mode: [n][max_coll][max_chunks].
+ *   loads  : [4][n] final tracker contents in seconds (rows >= D are 0), or
+ *            NULL.  In trace mode: the loads of the last collective.
+ */
+int themis_plan_batch(const themis_batch_t *batch, uint8_t *orders,
+                      double *loads, void *stream);
+
+/*
+ * themis_simulate_batch -- deterministic execution of a plan (Sec. 4.3, 4.6.2).
+ *
+ * Every dimension is one non-preemptive, work-conserving server.  All chunks
+ * of a collective wait at the dimension of their first stage from the
+ * collective's release time.  Whenever a dimension is idle and chunks wait for
+ * it, it starts the one with the smallest key
+ *   FIFO: (arrival time at this dimension, chunk_id)
+ *   SCF : (resident size before the stage, arrival time, chunk_id)
+ * for the stage's time (see Model above); all completions that fall on the
+ * same instant are delivered before any dimension picks its next chunk.
+ *
+ *   orders      : [n][max_chunks] (trace: [n][max_coll][max_chunks]) order
+ *                 codes, e.g. themis_plan_batch's output; any permutation
+ *                 code is accepted, a malformed one invalidates the scenario.
+ *   t_done      : [n] completion time of the last stage.
+ *   queue_order : NULL, or [n][4][2*slots] entries (see above).
+ *   busy        : NULL, or [4][n] seconds each dimension spent serving.
+ *   workspace, workspace_bytes : see themis_workspace_bytes().
+ */
+int themis_simulate_batch(const themis_batch_t *batch, const uint8_t *orders,
+                          double *t_done, void *queue_order, double *busy,
+                          void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/*
+ * themis_sweep -- fused plan + simulate for every scenario x threshold x
+ * scheduler of policy_mask (the parameter studies of Sec. 6.1), keeping only
+ * completion times.  inter_policy / intra_policy / threshold of the batch are
+ * ignored.
+ *
+ *   thr        : n_thr thresholds (meaning per batch->threshold_mode); shared
+ *                by all scenarios ([n_thr], thr_per_scenario = 0) or one set
+ *                per scenario ([n_thr][n], thr_per_scenario != 0).
+ *   t_done     : [n][n_thr][n_pol], n_pol = popcount(policy_mask), schedulers
+ *                in ascending bit order.  THEMIS_SWEEP_BASELINE ignores the
+ *                threshold (its value repeats along n_thr).
+ */
+int themis_sweep(const themis_batch_t *batch, int n_thr, const double *thr,
+                 int thr_per_scenario, unsigned policy_mask, double *t_done,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THEMIS_H */

@@ -1,0 +1,461 @@
+/*
+ * themis_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, single-threaded CPU statement of what the batched Themis
+ * evaluator computes (arXiv 2110.04478): the latency model, the greedy chunk
+ * scheduler of Alg. 1 and the per-dimension queue simulation.  It exists so
+ * that the GPU library can be checked against it; only the tests, the smoke
+ * check and the benchmark's CPU-baseline leg may call it.  It shares no code,
+ * header, table or helper with the GPU path.
+ *
+ * Everything is IEEE binary64, round to nearest, compiled with
+ * -ffp-contract=off; no blocking, no reordering, no cleverness: each function
+ * walks the paper's steps in the paper's order.
+ *
+ * Pinning (tests/test_oracle_*.py): 1-D ring closed form 2(P-1)/P*S/B, the
+ * stage-time ratios and chunk orders of the paper's 4x4 worked example, load
+ * conservation, the balanced-bandwidth reduction to the baseline order, an
+ * independent time-stepped simulator on integer service times, and brute
+ * force over all per-chunk orders for tiny C.  The completion time that the
+ * paper's timing figure would show for Themis on the worked example is
+ * "parity unpinned": the figure is not available in text form.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define TO_MAX_DIMS 4
+
+enum { TO_INTER_BASELINE = 0, TO_INTER_THEMIS = 1 };
+enum { TO_INTRA_FIFO = 0, TO_INTRA_SCF = 1 };
+enum { TO_THR_ABS = 0, TO_THR_REL = 1 };
+
+/* ------------------------------------------------------------------------ */
+/* Latency model (Sec. 4.5: latency of chunk i on dim K is n_K^i * B_K, with
+ * n = (P-1)/P * resident size (footnote there) and B_K the per-byte latency,
+ * i.e. the inverse of the dimension's bandwidth).                           */
+/* ------------------------------------------------------------------------ */
+void to_latency_coef(int ndims, const uint32_t *npus, const double *bw,
+                     double *coef)
+{
+  for (int k = 0; k < ndims; ++k) {
+    double p = (double)npus[k];
+    coef[k] = ((double)(npus[k] - 1u) / p) / bw[k];
+  }
+}
+
+static int finite_positive(double v) { return isfinite(v) && v > 0.0; }
+
+/* A scenario is valid when the network and the collective make sense. */
+int to_network_valid(int ndims, const uint32_t *npus, const double *bw)
+{
+  if (ndims < 1 || ndims > TO_MAX_DIMS) return 0;
+  for (int k = 0; k < ndims; ++k) {
+    if (npus[k] < 2u) return 0;
+    if (!finite_positive(bw[k])) return 0;
+  }
+  return 1;
+}
+
+/* Decode an order code into dims[0..D-1]; returns 0 if it is not a
+ * permutation of 0..D-1 with zero upper fields. */
+int to_decode_order(int ndims, uint8_t code, int *dims)
+{
+  int seen = 0;
+  for (int j = 0; j < TO_MAX_DIMS; ++j) {
+    int k = (code >> (2 * j)) & 3;
+    if (j < ndims) {
+      if (k >= ndims || (seen & (1 << k))) return 0;
+      seen |= 1 << k;
+      dims[j] = k;
+    } else if (k != 0) {
+      return 0;
+    }
+  }
+  return 1;
+}
+
+static uint8_t encode_order(int ndims, const int *dims)
+{
+  unsigned code = 0;
+  for (int j = 0; j < ndims; ++j) code |= (unsigned)dims[j] << (2 * j);
+  return (uint8_t)code;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Alg. 1.  Plans one collective of `size_bytes` split into C equal chunks.
+ *   orders[C]        : order code of every chunk
+ *   loads[4]         : final Dim Load Tracker contents
+ *   stage_time[C][4] : (may be NULL) time of chunk i on dimension k
+ * Returns 1 on success, 0 if the inputs are invalid (nothing written).       */
+/* ------------------------------------------------------------------------ */
+int to_plan(int ndims, const uint32_t *npus, const double *bw,
+            double size_bytes, uint32_t C, int inter_policy,
+            int threshold_mode, double threshold, uint8_t *orders,
+            double *loads, double *stage_time)
+{
+  if (!to_network_valid(ndims, npus, bw)) return 0;
+  if (!finite_positive(size_bytes) || C < 1u) return 0;
+  if (!(threshold >= 0.0)) return 0; /* also rejects NaN */
+  if (threshold_mode == TO_THR_REL && !isfinite(threshold)) return 0;
+
+  double coef[TO_MAX_DIMS];
+  to_latency_coef(ndims, npus, bw, coef);
+
+  /* Splitter: equal chunks (Alg. 1 line 3). */
+  double chunk = size_bytes / (double)C;
+
+  /* Dim Load Tracker reset: A_K = 0 (Alg. 1 line 2, Sec. 4.5). */
+  double load[TO_MAX_DIMS] = {0.0, 0.0, 0.0, 0.0};
+
+  for (uint32_t i = 0; i < C; ++i) {
+    /* Scheduler.Schedule: current loads, their min and max (line 18-19). */
+    int kmin = 0;
+    double lo = load[0], hi = load[0];
+    for (int k = 1; k < ndims; ++k) {
+      if (load[k] < lo) { lo = load[k]; kmin = k; }
+      if (load[k] > hi) hi = load[k];
+    }
+    double thr = threshold;
+    if (threshold_mode == TO_THR_REL) thr = threshold * (chunk * coef[kmin]);
+
+    int order[TO_MAX_DIMS];
+    for (int k = 0; k < ndims; ++k) order[k] = k; /* baseline: dim1..dimD */
+    if (inter_policy != TO_INTER_BASELINE && !((hi - lo) < thr)) {
+      /* indices of the loads sorted ascending, stable: insertion sort that
+       * moves an element only past strictly larger loads. */
+      for (int a = 1; a < ndims; ++a) {
+        int k = order[a];
+        int b = a - 1;
+        while (b >= 0 && load[order[b]] > load[k]) {
+          order[b + 1] = order[b];
+          --b;
+        }
+        order[b + 1] = k;
+      }
+    }
+
+    /* Latency Model + tracker update (lines 28-30).  The chunk shrinks by
+     * P_k after its Reduce-Scatter on dimension k (Sec. 2.1); its All-Gather
+     * on k later moves the same bytes, so the dimension is charged twice. */
+    double x = chunk;
+    for (int j = 0; j < ndims; ++j) {
+      int k = order[j];
+      double t = x * coef[k];
+      if (stage_time) stage_time[(size_t)i * TO_MAX_DIMS + k] = t;
+      load[k] = load[k] + (t + t);
+      x = x / (double)npus[k];
+    }
+    orders[i] = encode_order(ndims, order);
+  }
+  for (int k = 0; k < TO_MAX_DIMS; ++k) loads[k] = (k < ndims) ? load[k] : 0.0;
+  return 1;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Queue simulation (Sec. 4.3 policies, Sec. 4.6.2 consistency simulation).
+ *
+ * n_coll collectives share the D servers.  Collective q has C chunks of
+ * coll_size[q]/C bytes, all released at release[q] (NULL = 0); chunk i of
+ * collective q has id g = q*C + i and order code orders[g].
+ *
+ *   t_done             : time the last stage of the last chunk ends
+ *   coll_done[n_coll]  : (may be NULL) same per collective
+ *   queue_order[4][2G] : (may be NULL) per dimension, the executed operations
+ *                        (g << 1 | phase) in execution order
+ *   busy[4]            : (may be NULL) total service time per dimension
+ * Returns 1 on success, 0 on invalid input.                                  */
+/* ------------------------------------------------------------------------ */
+typedef struct {
+  int stage;      /* 0..2D: next stage to run (2D = finished)              */
+  int running;    /* currently being served                                */
+  double size;    /* resident bytes before the next stage                  */
+  double arrival; /* when it joined the queue it is waiting in             */
+  int order[TO_MAX_DIMS];
+  double t[TO_MAX_DIMS]; /* service time on dimension k (RS == AG)          */
+} to_chunk;
+
+static int stage_dim(const to_chunk *c, int ndims)
+{
+  return (c->stage < ndims) ? c->order[c->stage]
+                            : c->order[2 * ndims - 1 - c->stage];
+}
+
+/* Does chunk a (id ga) go before chunk b (id gb) in one dimension's queue? */
+static int goes_first(int intra_policy, const to_chunk *a, uint32_t ga,
+                      const to_chunk *b, uint32_t gb)
+{
+  if (intra_policy == TO_INTRA_SCF) {
+    if (a->size < b->size) return 1;
+    if (a->size > b->size) return 0;
+  }
+  if (a->arrival < b->arrival) return 1;
+  if (a->arrival > b->arrival) return 0;
+  return ga < gb;
+}
+
+int to_simulate(int ndims, const uint32_t *npus, const double *bw,
+                uint32_t n_coll, const double *coll_size,
+                const double *release, uint32_t C, int intra_policy,
+                const uint8_t *orders, double *t_done, double *coll_done,
+                uint32_t *queue_order, double *busy)
+{
+  if (!to_network_valid(ndims, npus, bw)) return 0;
+  if (n_coll < 1u || C < 1u) return 0;
+  for (uint32_t q = 0; q < n_coll; ++q) {
+    if (!finite_positive(coll_size[q])) return 0;
+    if (release && !(isfinite(release[q]) && release[q] >= 0.0)) return 0;
+  }
+  uint32_t G = n_coll * C;
+
+  double coef[TO_MAX_DIMS];
+  to_latency_coef(ndims, npus, bw, coef);
+
+  to_chunk *ch = (to_chunk *)calloc(G, sizeof(to_chunk));
+  if (!ch) return 0;
+  for (uint32_t q = 0; q < n_coll; ++q) {
+    double chunk = coll_size[q] / (double)C;
+    for (uint32_t i = 0; i < C; ++i) {
+      uint32_t g = q * C + i;
+      to_chunk *c = &ch[g];
+      if (!to_decode_order(ndims, orders[g], c->order)) { free(ch); return 0; }
+      c->stage = 0;
+      c->running = 0;
+      c->size = chunk;
+      c->arrival = release ? release[q] : 0.0;
+      /* stage times exactly as the planner's latency model computes them */
+      double x = chunk;
+      for (int j = 0; j < ndims; ++j) {
+        int k = c->order[j];
+        c->t[k] = x * coef[k];
+        x = x / (double)npus[k];
+      }
+    }
+  }
+
+  int serving[TO_MAX_DIMS];      /* chunk id being served, or -1 */
+  double finish[TO_MAX_DIMS];
+  uint32_t executed[TO_MAX_DIMS] = {0, 0, 0, 0};
+  double busy_acc[TO_MAX_DIMS] = {0.0, 0.0, 0.0, 0.0};
+  for (int k = 0; k < TO_MAX_DIMS; ++k) { serving[k] = -1; finish[k] = 0.0; }
+  if (coll_done) for (uint32_t q = 0; q < n_coll; ++q) coll_done[q] = 0.0;
+
+  double now = 0.0;
+  double last_done = 0.0;
+  for (;;) {
+    /* (i) every idle dimension starts the best chunk waiting for it */
+    for (int k = 0; k < ndims; ++k) {
+      if (serving[k] >= 0) continue;
+      int best = -1;
+      for (uint32_t g = 0; g < G; ++g) {
+        const to_chunk *c = &ch[g];
+        if (c->stage >= 2 * ndims || c->running) continue;
+        if (stage_dim(c, ndims) != k) continue;
+        if (c->arrival > now) continue; /* not released yet */
+        if (best < 0 || goes_first(intra_policy, c, g, &ch[best], (uint32_t)best))
+          best = (int)g;
+      }
+      if (best < 0) continue;
+      to_chunk *c = &ch[best];
+      c->running = 1;
+      serving[k] = best;
+      finish[k] = now + c->t[k];
+      busy_acc[k] = busy_acc[k] + c->t[k];
+      if (queue_order) {
+        uint32_t phase = (c->stage >= ndims) ? 1u : 0u;
+        queue_order[(size_t)k * 2u * G + executed[k]] = ((uint32_t)best << 1) | phase;
+      }
+      executed[k]++;
+    }
+
+    /* (ii)+(iii) next instant at which something happens */
+    double next = INFINITY;
+    for (int k = 0; k < ndims; ++k)
+      if (serving[k] >= 0 && finish[k] < next) next = finish[k];
+    for (uint32_t g = 0; g < G; ++g) {
+      const to_chunk *c = &ch[g];
+      if (c->stage < 2 * ndims && !c->running && c->arrival > now &&
+          c->arrival < next)
+        next = c->arrival;
+    }
+    if (next == INFINITY) break;
+    now = next;
+
+    /* (iv) deliver every completion that falls on this instant */
+    for (int k = 0; k < ndims; ++k) {
+      if (serving[k] < 0 || finish[k] != now) continue;
+      uint32_t g = (uint32_t)serving[k];
+      to_chunk *c = &ch[g];
+      if (c->stage < ndims) c->size = c->size / (double)npus[k]; /* RS */
+      else                  c->size = c->size * (double)npus[k]; /* AG */
+      c->stage++;
+      c->running = 0;
+      c->arrival = now;
+      serving[k] = -1;
+      if (c->stage == 2 * ndims) {
+        last_done = now;
+        if (coll_done) coll_done[g / C] = now;
+      }
+    }
+  }
+
+  *t_done = last_done;
+  if (busy) for (int k = 0; k < TO_MAX_DIMS; ++k) busy[k] = busy_acc[k];
+  free(ch);
+  return 1;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Batch drivers over structure-of-arrays inputs (host pointers): scenario i
+ * of n, per-dimension fields laid out [4][n].  Only scenarios in
+ * [begin, end) are processed so that a caller may fan ranges out to threads. */
+/* ------------------------------------------------------------------------ */
+static void gather_network(uint64_t n, uint64_t i, const uint32_t *npus,
+                           const double *bw, uint32_t *p, double *b)
+{
+  for (int k = 0; k < TO_MAX_DIMS; ++k) {
+    p[k] = npus[(size_t)k * n + i];
+    b[k] = bw[(size_t)k * n + i];
+  }
+}
+
+/* orders: [n][slots] with slots = max_chunks * max(1,max_coll); loads [4][n]
+ * (may be NULL).  n_coll/coll_size NULL = one collective of size_bytes[i]. */
+void to_plan_batch(uint64_t n, uint64_t begin, uint64_t end,
+                   uint32_t max_chunks, int threshold_mode,
+                   const uint8_t *ndims, const uint32_t *npus,
+                   const double *bw, const double *size_bytes,
+                   const uint32_t *chunks, const uint8_t *inter_policy,
+                   const double *threshold, uint32_t max_coll,
+                   const uint32_t *n_coll, const double *coll_size,
+                   uint8_t *orders, double *loads)
+{
+  uint32_t mc = (n_coll && max_coll > 0u) ? max_coll : 1u;
+  size_t slots = (size_t)max_chunks * mc;
+  for (uint64_t i = begin; i < end; ++i) {
+    uint32_t p[TO_MAX_DIMS];
+    double b[TO_MAX_DIMS], ld[TO_MAX_DIMS] = {0, 0, 0, 0};
+    gather_network(n, i, npus, bw, p, b);
+    uint8_t *row = orders + (size_t)i * slots;
+    memset(row, 0xFF, slots);
+    uint32_t C = chunks[i];
+    uint32_t Q = n_coll ? n_coll[i] : 1u;
+    int ok = (C >= 1u && C <= max_chunks && Q >= 1u && Q <= mc);
+    for (uint32_t q = 0; ok && q < Q; ++q) {
+      double S = n_coll ? coll_size[(size_t)q * n + i] : size_bytes[i];
+      ok = to_plan((int)ndims[i], p, b, S, C, (int)inter_policy[i],
+                   threshold_mode, threshold[i],
+                   row + (size_t)q * max_chunks, ld, NULL);
+    }
+    if (!ok) {
+      memset(row, 0xFF, slots);
+      for (int k = 0; k < TO_MAX_DIMS; ++k) ld[k] = NAN;
+    }
+    if (loads)
+      for (int k = 0; k < TO_MAX_DIMS; ++k) loads[(size_t)k * n + i] = ld[k];
+  }
+}
+
+/* queue_order: NULL or [n][4][2*slots] uint16 (unused entries 0xFFFF);
+ * busy: NULL or [4][n]; t_done [n]. */
+void to_simulate_batch(uint64_t n, uint64_t begin, uint64_t end,
+                       uint32_t max_chunks, const uint8_t *ndims,
+                       const uint32_t *npus, const double *bw,
+                       const double *size_bytes, const uint32_t *chunks,
+                       const uint8_t *intra_policy, uint32_t max_coll,
+                       const uint32_t *n_coll, const double *coll_size,
+                       const double *release_time, const uint8_t *orders,
+                       double *t_done, uint16_t *queue_order, double *busy)
+{
+  uint32_t mc = (n_coll && max_coll > 0u) ? max_coll : 1u;
+  size_t slots = (size_t)max_chunks * mc;
+  uint32_t *qo = queue_order
+      ? (uint32_t *)malloc(sizeof(uint32_t) * TO_MAX_DIMS * 2u * slots) : NULL;
+  double *cs = (double *)malloc(sizeof(double) * mc);
+  double *rl = (double *)malloc(sizeof(double) * mc);
+  uint8_t *od = (uint8_t *)malloc(slots);
+  for (uint64_t i = begin; i < end; ++i) {
+    uint32_t p[TO_MAX_DIMS];
+    double b[TO_MAX_DIMS], bz[TO_MAX_DIMS] = {0, 0, 0, 0};
+    gather_network(n, i, npus, bw, p, b);
+    uint32_t C = chunks[i];
+    uint32_t Q = n_coll ? n_coll[i] : 1u;
+    int D = (int)ndims[i];
+    int ok = (C >= 1u && C <= max_chunks && Q >= 1u && Q <= mc);
+    double T = NAN;
+    if (ok) {
+      for (uint32_t q = 0; q < Q; ++q) {
+        cs[q] = n_coll ? coll_size[(size_t)q * n + i] : size_bytes[i];
+        rl[q] = (n_coll && release_time) ? release_time[(size_t)q * n + i] : 0.0;
+        /* compact the [max_coll][max_chunks] rows into q*C + i numbering */
+        memcpy(od + (size_t)q * C,
+               orders + (size_t)i * slots + (size_t)q * max_chunks, C);
+      }
+      ok = to_simulate(D, p, b, Q, cs, rl, C, (int)intra_policy[i], od, &T,
+                       NULL, qo, bz);
+    }
+    if (!ok) {
+      T = NAN;
+      for (int k = 0; k < TO_MAX_DIMS; ++k) bz[k] = NAN;
+    }
+    t_done[i] = T;
+    if (busy)
+      for (int k = 0; k < TO_MAX_DIMS; ++k) busy[(size_t)k * n + i] = bz[k];
+    if (queue_order) {
+      uint16_t *row = queue_order + (size_t)i * TO_MAX_DIMS * 2u * slots;
+      memset(row, 0xFF, sizeof(uint16_t) * TO_MAX_DIMS * 2u * slots);
+      if (ok) {
+        uint32_t G = Q * C;
+        for (int k = 0; k < D; ++k)
+          for (uint32_t e = 0; e < 2u * G; ++e)
+            row[(size_t)k * 2u * slots + e] = (uint16_t)qo[(size_t)k * 2u * G + e];
+      }
+    }
+  }
+  free(qo); free(cs); free(rl); free(od);
+}
+
+/* Fused plan + simulate for scenario x threshold x scheduler.
+ * policy_mask bits: 1 baseline+FIFO, 2 Themis+FIFO, 4 Themis+SCF, evaluated
+ * in ascending bit order.  thr: [n_thr] shared, or [n_thr][n] when
+ * thr_per_scenario.  t_done: [n][n_thr][n_pol]. */
+void to_sweep(uint64_t n, uint64_t begin, uint64_t end, uint32_t max_chunks,
+              int threshold_mode, const uint8_t *ndims, const uint32_t *npus,
+              const double *bw, const double *size_bytes,
+              const uint32_t *chunks, int n_thr, const double *thr,
+              int thr_per_scenario, unsigned policy_mask, double *t_done)
+{
+  int n_pol = 0;
+  for (int bit = 0; bit < 3; ++bit) if (policy_mask & (1u << bit)) ++n_pol;
+  uint8_t *od = (uint8_t *)malloc(max_chunks);
+  for (uint64_t i = begin; i < end; ++i) {
+    uint32_t p[TO_MAX_DIMS];
+    double b[TO_MAX_DIMS], ld[TO_MAX_DIMS];
+    gather_network(n, i, npus, bw, p, b);
+    uint32_t C = chunks[i];
+    for (int a = 0; a < n_thr; ++a) {
+      double th = thr_per_scenario ? thr[(size_t)a * n + i] : thr[a];
+      int col = 0;
+      for (int bit = 0; bit < 3; ++bit) {
+        if (!(policy_mask & (1u << bit))) continue;
+        int inter = (bit == 0) ? TO_INTER_BASELINE : TO_INTER_THEMIS;
+        int intra = (bit == 2) ? TO_INTRA_SCF : TO_INTRA_FIFO;
+        double T = NAN;
+        int ok = (C >= 1u && C <= max_chunks);
+        if (ok)
+          ok = to_plan((int)ndims[i], p, b, size_bytes[i], C, inter,
+                       threshold_mode, th, od, ld, NULL);
+        if (ok) {
+          double S = size_bytes[i];
+          ok = to_simulate((int)ndims[i], p, b, 1u, &S, NULL, C, intra, od,
+                           &T, NULL, NULL, NULL);
+        }
+        if (!ok) T = NAN;
+        t_done[((size_t)i * n_thr + a) * n_pol + col] = T;
+        ++col;
+      }
+    }
+  }
+  free(od);
+}
