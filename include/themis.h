@@ -132,7 +132,7 @@ const char *themis_status_string(int status);
  * Queue-order entry: (chunk_id << 1) | phase, phase 0 = Reduce-Scatter,
  * 1 = All-Gather, listed per dimension in the order the dimension executed
  * them (Sec. 4.6.2).  chunk_id is q*chunks + i in trace mode.  The entry is
- * one byte when 2*slots <= 256 and two bytes (little endian uint16) otherwise,
+ * one byte when slots <= 127 and two bytes (little endian uint16) otherwise,
  * where slots = max_chunks * max(1, max_coll); themis_queue_entry_bytes()
  * returns that width.  Unused entries are all-ones.
  */
@@ -142,9 +142,11 @@ int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
  * Bytes of scratch that themis_simulate_batch / themis_sweep may need for the
  * scenarios their fast path does not cover (any P_k that is not a power of
  * two, or a size whose halvings would leave the normal binary64 range).
- * Passing a smaller or NULL workspace is allowed: such scenarios then come
- * back as NaN and the call returns THEMIS_ERR_WORKSPACE after enqueueing the
- * rest.  The workspace must stay untouched until the stream has drained.
+ * Passing a smaller or NULL workspace is allowed: every scenario that would
+ * have needed it then comes back as NaN / all-ones, like an invalid one (the
+ * call cannot report this through its return value, because it does not wait
+ * for the device).  The workspace must stay untouched until the stream has
+ * drained, and two calls in flight at once need a workspace each.
  */
 size_t themis_workspace_bytes(uint64_t n, uint32_t max_chunks, uint32_t max_coll);
 

@@ -1,0 +1,303 @@
+// C ABI of the library (see include/themis.h) and the kernels behind it.
+#include <hip/hip_runtime.h>
+
+#include "themis.h"
+#include "themis_device.hpp"
+#include "themis_generic.hpp"
+
+namespace themis {
+
+struct TraceView {
+  bool on;
+  uint32_t mc;     // collectives per scenario row (1 without a trace)
+  uint32_t slots;  // chunk slots per scenario = max_chunks * mc
+};
+
+__host__ __device__ inline TraceView trace_view(const themis_batch_t& b) {
+  TraceView t;
+  t.on = b.n_coll != nullptr;
+  t.mc = t.on ? b.max_coll : 1u;
+  t.slots = b.max_chunks * t.mc;
+  return t;
+}
+
+__device__ __forceinline__ double collective_size(const themis_batch_t& b, const TraceView& tv,
+                                                  uint64_t i, uint32_t q) {
+  return tv.on ? b.coll_size[(size_t)q * b.n + i] : b.size_bytes[i];
+}
+
+__device__ __forceinline__ double collective_release(const themis_batch_t& b, const TraceView& tv,
+                                                     uint64_t i, uint32_t q) {
+  return (tv.on && b.release_time) ? b.release_time[(size_t)q * b.n + i] : 0.0;
+}
+
+// Checks the collectives of scenario i (count, sizes, release times).
+__device__ __forceinline__ bool collectives_ok(const themis_batch_t& b, const TraceView& tv,
+                                               uint64_t i, uint32_t& Q) {
+  Q = tv.on ? b.n_coll[i] : 1u;
+  if (Q < 1u || Q > tv.mc) { Q = 0; return false; }
+  bool ok = true;
+  for (uint32_t q = 0; q < Q; ++q) {
+    if (!finite_positive(collective_size(b, tv, i, q))) ok = false;
+    double r = collective_release(b, tv, i, q);
+    if (!(r >= 0.0 && r < inf64())) ok = false;
+  }
+  return ok;
+}
+
+__device__ __forceinline__ bool threshold_ok(double thr, bool rel) {
+  return thr >= 0.0 && (!rel || thr < inf64());
+}
+
+// ---------------------------------------------------------------------------
+// themis_plan_batch: Alg. 1 per scenario (hot-path steps a1-a5).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__ loads) {
+  uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= b.n) return;
+  const TraceView tv = trace_view(b);
+  Scenario s = load_scenario(b, i);
+  const bool rel = b.threshold_mode == THEMIS_THR_REL;
+  const double thr = b.threshold[i];
+  const bool themis_on = b.inter_policy[i] != THEMIS_INTER_BASELINE;
+  uint32_t Q;
+  bool ok = collectives_ok(b, tv, i, Q) && s.valid && threshold_ok(thr, rel);
+
+  uint8_t* row = orders + (size_t)i * tv.slots;
+  double load[kMaxDims] = {0.0, 0.0, 0.0, 0.0};
+  if (ok) {
+    for (uint32_t q = 0; q < tv.mc; ++q) {
+      uint8_t* r = row + (size_t)q * b.max_chunks;
+      if (q < Q) {
+        double chunk = collective_size(b, tv, i, q) / (double)s.C;
+#pragma unroll
+        for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? 0.0 : inf64();
+        for (uint32_t c = 0; c < s.C; ++c)
+          r[c] = (uint8_t)schedule_chunk(s, chunk, themis_on, rel, thr, load);
+        for (uint32_t c = s.C; c < b.max_chunks; ++c) r[c] = 0xFFu;
+      } else {
+        for (uint32_t c = 0; c < b.max_chunks; ++c) r[c] = 0xFFu;
+      }
+    }
+  } else {
+    for (uint32_t c = 0; c < tv.slots; ++c) row[c] = 0xFFu;
+  }
+  if (loads) {
+#pragma unroll
+    for (int k = 0; k < kMaxDims; ++k)
+      loads[(size_t)k * b.n + i] = ok ? ((k < s.D) ? load[k] : 0.0) : nan64();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// themis_simulate_batch, generic path (hot-path steps a6-a9).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
+                        double* __restrict__ t_done, void* __restrict__ queue_order,
+                        int entry_bytes, double* __restrict__ busy, Workspace w, bool have_ws) {
+  uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= b.n) return;
+  const TraceView tv = trace_view(b);
+  Scenario s = load_scenario(b, i);
+  const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
+  uint32_t Q;
+  bool ok = collectives_ok(b, tv, i, Q) && s.valid && have_ws;
+
+  SimOut out;
+  out.t_done = t_done + i;
+  out.busy = busy ? busy + i : nullptr;
+  out.busy_stride = b.n;
+  out.entry_bytes = entry_bytes;
+  out.slots = tv.slots;
+  out.queue_order = queue_order
+      ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
+      : nullptr;
+
+  const uint8_t* row = orders + (size_t)i * tv.slots;
+  bool has_release = false;
+  if (ok) {
+    // a6: every chunk waits at the dimension of its first stage
+    for (uint32_t q = 0; q < Q; ++q) {
+      double chunk = collective_size(b, tv, i, q) / (double)s.C;
+      double rel = collective_release(b, tv, i, q);
+      has_release |= rel > 0.0;
+      for (uint32_t c = 0; c < s.C; ++c) {
+        uint32_t code = row[(size_t)q * b.max_chunks + c];
+        if (!order_code_ok(code, s.D)) ok = false;
+        size_t at = (size_t)(q * s.C + c) * w.stride + i;
+        w.meta[at] = code << 8;
+        w.size[at] = chunk;
+        w.arrival[at] = rel;
+      }
+    }
+  }
+  if (!ok) { write_invalid(out); return; }
+  simulate_generic(
+      s, Q, scf, w, i,
+      [&](uint32_t q) { return collective_size(b, tv, i, q) / (double)s.C; },
+      [&](uint32_t q) { return collective_release(b, tv, i, q); }, has_release, out);
+}
+
+// ---------------------------------------------------------------------------
+// themis_sweep, generic path (hot-path step a10): one lane per
+// scenario x threshold x scheduler.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
+                     int thr_per_scenario, unsigned policy_mask, int n_pol,
+                     double* __restrict__ t_done, Workspace w, bool have_ws) {
+  uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
+  if (e >= total) return;
+  uint64_t i = e / ((uint64_t)n_thr * n_pol);
+  uint32_t rem = (uint32_t)(e - i * (uint64_t)n_thr * n_pol);
+  int a = (int)(rem / (uint32_t)n_pol);
+  int col = (int)(rem - (uint32_t)a * (uint32_t)n_pol);
+  // col-th set bit of the mask selects the scheduler
+  int bit = 0;
+  for (int seen = 0; bit < 3; ++bit)
+    if (policy_mask & (1u << bit)) { if (seen == col) break; ++seen; }
+  const bool themis_on = bit != 0;
+  const bool scf = bit == 2;
+
+  Scenario s = load_scenario(b, i);
+  const bool rel = b.threshold_mode == THEMIS_THR_REL;
+  const double th = thr_per_scenario ? thr[(size_t)a * b.n + i] : thr[a];
+  const double S = b.size_bytes[i];
+  bool ok = s.valid && finite_positive(S) && threshold_ok(th, rel) && have_ws;
+  if (!ok) { t_done[e] = nan64(); return; }
+
+  const double chunk = S / (double)s.C;
+  double load[kMaxDims];
+#pragma unroll
+  for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? 0.0 : inf64();
+  for (uint32_t c = 0; c < s.C; ++c) {
+    uint32_t code = schedule_chunk(s, chunk, themis_on, rel, th, load);
+    size_t at = (size_t)c * w.stride + e;
+    w.meta[at] = code << 8;
+    w.size[at] = chunk;
+    w.arrival[at] = 0.0;
+  }
+  SimOut out;
+  out.t_done = t_done + e;
+  out.busy = nullptr;
+  out.busy_stride = 0;
+  out.queue_order = nullptr;
+  out.entry_bytes = 1;
+  out.slots = b.max_chunks;
+  simulate_generic(
+      s, 1u, scf, w, e, [&](uint32_t) { return chunk; }, [&](uint32_t) { return 0.0; }, false,
+      out);
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+constexpr uint32_t kMaxSlots = 32767u;  // 16-bit queue entries, all-ones reserved
+
+static int check_batch(const themis_batch_t* b, bool need_intra, bool need_inter) {
+  if (!b) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (b->max_chunks < 1u || b->max_chunks > THEMIS_MAX_CHUNKS) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (b->threshold_mode != THEMIS_THR_ABS && b->threshold_mode != THEMIS_THR_REL)
+    return THEMIS_ERR_INVALID_ARGUMENT;
+  if (b->n == 0) return THEMIS_OK;
+  if (!b->ndims || !b->npus || !b->bw || !b->chunks) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (need_inter && (!b->inter_policy || !b->threshold)) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (need_intra && !b->intra_policy) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (b->n_coll) {
+    if (!b->coll_size || b->max_coll < 1u) return THEMIS_ERR_INVALID_ARGUMENT;
+    if ((uint64_t)b->max_coll * b->max_chunks > kMaxSlots) return THEMIS_ERR_UNSUPPORTED;
+  } else if (!b->size_bytes) {
+    return THEMIS_ERR_INVALID_ARGUMENT;
+  }
+  if (b->n > (uint64_t)0x7fffffff * kBlock) return THEMIS_ERR_UNSUPPORTED;
+  return THEMIS_OK;
+}
+
+static int launch_status() {
+  return hipGetLastError() == hipSuccess ? THEMIS_OK : THEMIS_ERR_DEVICE;
+}
+
+static unsigned blocks_for(uint64_t items) { return (unsigned)((items + kBlock - 1) / kBlock); }
+
+}  // namespace themis
+
+using namespace themis;
+
+extern "C" {
+
+int themis_version(void) { return 100; }
+
+const char* themis_status_string(int status) {
+  switch (status) {
+    case THEMIS_OK: return "success";
+    case THEMIS_ERR_INVALID_ARGUMENT: return "invalid argument";
+    case THEMIS_ERR_UNSUPPORTED: return "unsupported request";
+    case THEMIS_ERR_DEVICE: return "HIP device error";
+    case THEMIS_ERR_WORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+  }
+}
+
+int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll) {
+  uint64_t slots = (uint64_t)max_chunks * (max_coll ? max_coll : 1u);
+  return slots <= 127u ? 1 : 2;
+}
+
+size_t themis_workspace_bytes(uint64_t n, uint32_t max_chunks, uint32_t max_coll) {
+  return workspace_bytes(n, (uint64_t)max_chunks * (max_coll ? max_coll : 1u));
+}
+
+int themis_plan_batch(const themis_batch_t* batch, uint8_t* orders, double* loads, void* stream) {
+  int st = check_batch(batch, false, true);
+  if (st != THEMIS_OK) return st;
+  if (batch->n == 0) return THEMIS_OK;
+  if (!orders) return THEMIS_ERR_INVALID_ARGUMENT;
+  hipLaunchKernelGGL(plan_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+                     (hipStream_t)stream, *batch, orders, loads);
+  return launch_status();
+}
+
+int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, double* t_done,
+                          void* queue_order, double* busy, void* workspace,
+                          size_t workspace_bytes_given, void* stream) {
+  int st = check_batch(batch, true, false);
+  if (st != THEMIS_OK) return st;
+  if (batch->n == 0) return THEMIS_OK;
+  if (!orders || !t_done) return THEMIS_ERR_INVALID_ARGUMENT;
+  const TraceView tv = trace_view(*batch);
+  const bool have_ws =
+      workspace != nullptr && workspace_bytes_given >= workspace_bytes(batch->n, tv.slots);
+  Workspace w = carve_workspace(workspace, batch->n, tv.slots);
+  hipLaunchKernelGGL(simulate_generic_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+                     (hipStream_t)stream, *batch, orders, t_done, queue_order,
+                     themis_queue_entry_bytes(batch->max_chunks, tv.on ? batch->max_coll : 0u),
+                     busy, w, have_ws);
+  return launch_status();
+}
+
+int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int thr_per_scenario,
+                 unsigned policy_mask, double* t_done, void* workspace,
+                 size_t workspace_bytes_given, void* stream) {
+  int st = check_batch(batch, false, false);
+  if (st != THEMIS_OK) return st;
+  if (batch->n_coll) return THEMIS_ERR_UNSUPPORTED;  // sweeps are per single collective
+  if (n_thr < 1 || !thr || (policy_mask & 7u) == 0u || (policy_mask & ~7u) != 0u)
+    return THEMIS_ERR_INVALID_ARGUMENT;
+  if (batch->n == 0) return THEMIS_OK;
+  if (!t_done) return THEMIS_ERR_INVALID_ARGUMENT;
+  int n_pol = __builtin_popcount(policy_mask & 7u);
+  uint64_t evals = batch->n * (uint64_t)n_thr * (uint64_t)n_pol;
+  if (evals > (uint64_t)0x7fffffff * kBlock) return THEMIS_ERR_UNSUPPORTED;
+  const bool have_ws = workspace != nullptr &&
+                       workspace_bytes_given >= workspace_bytes(evals, batch->max_chunks);
+  Workspace w = carve_workspace(workspace, evals, batch->max_chunks);
+  hipLaunchKernelGGL(sweep_generic_kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
+                     (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
+                     n_pol, t_done, w, have_ws);
+  return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,63 @@
+"""The C ABI library builds, loads and exports every symbol the header
+declares (no compute calls: runs without a GPU)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "themis.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(themis_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_entry_points():
+    names = declared_functions()
+    for must in ("themis_plan_batch", "themis_simulate_batch", "themis_sweep"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2110_04478_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2110_04478_amd.csrc import build
+        build.build()
+    L = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(L, name), f"{name} is declared in themis.h but not exported"
+
+
+def test_host_side_helpers():
+    from paper_2110_04478_amd import binding
+    L = binding.lib()
+    assert binding.themis_version() >= 100
+    assert L.themis_status_string(0) == b"success"
+    assert L.themis_status_string(-1) and L.themis_status_string(-99)
+    assert binding.themis_queue_entry_bytes(64) == 1
+    assert binding.themis_queue_entry_bytes(127) == 1
+    assert binding.themis_queue_entry_bytes(128) == 2
+    assert binding.themis_queue_entry_bytes(64, 200) == 2
+    assert binding.themis_workspace_bytes(0, 64) == 0
+    assert binding.themis_workspace_bytes(1000, 64) >= 1000 * 64 * 8
+
+
+def test_argument_errors_are_reported_without_a_device():
+    """NULL / out-of-range arguments are rejected on the host before any HIP
+    call, so this needs no GPU."""
+    from paper_2110_04478_amd import binding
+    L = binding.lib()
+    assert L.themis_plan_batch(None, None, None, None) == -1
+    b = binding._Batch()
+    b.n, b.max_chunks, b.threshold_mode = 4, 0, 0
+    assert L.themis_plan_batch(ctypes.byref(b), None, None, None) == -1
+    b.max_chunks = 1024
+    assert L.themis_plan_batch(ctypes.byref(b), None, None, None) == -1
+    b.max_chunks, b.threshold_mode = 64, 7
+    assert L.themis_simulate_batch(ctypes.byref(b), None, None, None, None, None, 0, None) == -1
+    b.threshold_mode = 0
+    assert L.themis_plan_batch(ctypes.byref(b), None, None, None) == -1   # NULL arrays
+    b.n = 0
+    assert L.themis_plan_batch(ctypes.byref(b), None, None, None) == 0    # empty batch: no-op
+    assert L.themis_sweep(ctypes.byref(b), 0, None, 0, 7, None, None, 0, None) == -1

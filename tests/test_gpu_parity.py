@@ -1,0 +1,215 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Bar: order codes and per-dimension queue orders bit-exact; completion times,
+loads and busy times within 1e-12 relative (binary64, the tolerance the
+target states).
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-12
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the gpu-marked tests need an MI355X")
+    from paper_2110_04478_amd import binding
+    binding.lib()
+    return binding
+
+
+def w():
+    from paper_2110_04478_amd import workloads
+    return workloads
+
+
+def assert_close(name, got, want):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    assert got.shape == want.shape, name
+    nan_g, nan_w = np.isnan(got), np.isnan(want)
+    assert np.array_equal(nan_g, nan_w), f"{name}: NaN pattern differs"
+    g, x = got[~nan_g], want[~nan_w]
+    err = np.abs(g - x) / np.maximum(np.abs(x), np.finfo(np.float64).tiny)
+    err[(g == x)] = 0.0
+    assert err.size == 0 or err.max() <= REL_TOL, (
+        f"{name}: max rel err {err.max():.3e} at {int(err.argmax())}, "
+        f"{int((g != x).sum())} of {g.size} differ")
+
+
+def widen_queue(q):
+    q = q.cpu().numpy()
+    if q.dtype == np.uint8:
+        out = q.astype(np.uint16)
+        out[q == 0xFF] = 0xFFFF
+        return out
+    return q.astype(np.uint16)
+
+
+def run_gpu(gpu, batch, queue=True):
+    import torch
+    d = gpu.to_device(batch)
+    orders, loads = gpu.themis_plan_batch(d)
+    ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(
+        d.n, d.max_chunks, d.max_coll if d.n_coll is not None else 0))
+    t, qo, busy = gpu.themis_simulate_batch(d, orders, workspace=ws, want_queue_order=queue)
+    torch.cuda.synchronize()
+    return (orders.cpu().numpy(), loads.cpu().numpy(), t.cpu().numpy(),
+            widen_queue(qo) if queue else None, busy.cpu().numpy())
+
+
+def check_batch(gpu, oracle, batch, queue=True, threads=8):
+    o_orders, o_loads = oracle.plan_batch(batch, threads=threads)
+    o_t, o_qo, o_busy = oracle.simulate_batch(batch, o_orders, want_queue_order=queue,
+                                              threads=threads)
+    g_orders, g_loads, g_t, g_qo, g_busy = run_gpu(gpu, batch, queue)
+    bad = np.nonzero((g_orders != o_orders).any(axis=1))[0]
+    assert bad.size == 0, f"order codes differ in {bad.size} scenarios, first {bad[:5]}"
+    assert_close("loads", g_loads, o_loads)
+    if queue:
+        badq = np.nonzero((g_qo != o_qo).reshape(batch.n, -1).any(axis=1))[0]
+        assert badq.size == 0, f"queue orders differ in {badq.size} scenarios, first {badq[:5]}"
+    assert_close("t_done", g_t, o_t)
+    assert_close("busy", g_busy, o_busy)
+    return g_t
+
+
+def test_config1_single_scenario(gpu, oracle):
+    t = check_batch(gpu, oracle, w().config1())
+    assert t[0] == pytest.approx(713.03168e-6, rel=1e-9)
+
+
+@pytest.mark.parametrize("inter", [1, 0])
+def test_config2_shape(gpu, oracle, inter):
+    check_batch(gpu, oracle, w().config2(n=4096 + 37, inter=inter))
+
+
+def test_config3_shape(gpu, oracle):
+    check_batch(gpu, oracle, w().config3(n=8192 + 5))
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000])
+@pytest.mark.parametrize("thr_mode", [0, 1])
+def test_ragged_mixed_batches(gpu, oracle, n, thr_mode):
+    """D in 1..4, C in 1..64, both schedulers, both queue policies; batch
+    sizes around the 64-lane wavefront boundary."""
+    check_batch(gpu, oracle, w().mixed(n, seed=1234 + n, thr_mode=thr_mode))
+
+
+def test_non_power_of_two_npus(gpu, oracle):
+    check_batch(gpu, oracle, w().mixed(700, seed=77, pow2=False))
+
+
+def test_large_chunk_counts(gpu, oracle):
+    """C up to 512: 16-bit queue entries."""
+    check_batch(gpu, oracle, w().mixed(96, seed=5, max_chunks=512), threads=8)
+    check_batch(gpu, oracle, w().config4(n=70))
+
+
+def test_empty_batch(gpu):
+    import torch
+    b = w().mixed(0)
+    d = gpu.to_device(b)
+    orders, loads = gpu.themis_plan_batch(d)
+    t, qo, busy = gpu.themis_simulate_batch(d, orders)
+    torch.cuda.synchronize()
+    assert orders.shape[0] == 0 and t.shape[0] == 0
+
+
+def test_invalid_scenarios_come_back_as_nan(gpu, oracle):
+    b = w().mixed(256, seed=9)
+    b.npus[1, 3] = 1             # P < 2 (only matters if D > 1)
+    b.ndims[3] = 3
+    b.bw[0, 10] = float("nan")
+    b.bw[0, 11] = 0.0
+    b.bw[0, 12] = float("inf")
+    b.size_bytes[20] = -5.0
+    b.chunks[30] = 0
+    b.chunks[31] = b.max_chunks + 1
+    b.ndims[40] = 0
+    b.ndims[41] = 5
+    b.threshold[50] = -1.0
+    b.threshold[51] = float("nan")
+    t = check_batch(gpu, oracle, b)
+    for i in (3, 10, 11, 12, 20, 30, 31, 40, 41):
+        assert np.isnan(t[i])
+    assert np.isfinite(t[0])
+
+
+def test_arbitrary_orders_are_accepted_and_malformed_ones_rejected(gpu, oracle):
+    """themis_simulate_batch takes any valid permutation per chunk."""
+    import torch
+    b = w().mixed(300, seed=21)
+    rng = np.random.default_rng(3)
+    orders = np.full((b.n, b.slots), 0xFF, np.uint8)
+    for i in range(b.n):
+        D = int(b.ndims[i])
+        for c in range(int(b.chunks[i])):
+            perm = rng.permutation(D)
+            orders[i, c] = sum(int(k) << (2 * j) for j, k in enumerate(perm))
+    orders[7, 0] = 0xFF                      # malformed
+    orders[8, 0] = 0x00 if b.ndims[8] > 1 else 0x01
+    o_t, o_qo, o_busy = oracle.simulate_batch(b, orders, threads=8)
+    d = gpu.to_device(b)
+    ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(d.n, d.max_chunks, 0))
+    t, qo, busy = gpu.themis_simulate_batch(d, torch.from_numpy(orders).cuda(), workspace=ws)
+    torch.cuda.synchronize()
+    assert np.isnan(o_t[7]) and np.isnan(o_t[8])
+    assert_close("t_done", t.cpu().numpy(), o_t)
+    assert np.array_equal(widen_queue(qo), o_qo)
+    assert_close("busy", busy.cpu().numpy(), o_busy)
+
+
+def test_trace_of_collectives_sharing_queues(gpu, oracle):
+    b = w().config5(n=96, n_coll=6)
+    check_batch(gpu, oracle, b)
+    # staggered releases and ragged collective counts
+    rng = np.random.default_rng(11)
+    b = w().config5(n=70, n_coll=5)
+    b.release_time = np.ascontiguousarray(rng.integers(0, 6, b.coll_size.shape) * 1e-4)
+    b.n_coll = rng.integers(1, 6, b.n).astype(np.uint32)
+    check_batch(gpu, oracle, b)
+
+
+def test_sweep_matches_oracle(gpu, oracle):
+    import torch
+    W = w()
+    for b, thr, mask in (
+            (W.config2(n=600), np.array([0.0]), W.SWEEP_BASELINE | W.SWEEP_THEMIS_FIFO),
+            (W.config4(n=40), W.CONFIG4_THRESHOLDS, W.SWEEP_THEMIS_FIFO | W.SWEEP_THEMIS_SCF),
+            (W.mixed(500, seed=31), np.array([0.0, 1 / 16, 0.5]), 7)):
+        want = oracle.sweep(b, thr, mask, threads=8)
+        d = gpu.to_device(b)
+        n_pol = bin(mask).count("1")
+        ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(d.n * len(thr) * n_pol, d.max_chunks))
+        got = gpu.themis_sweep(d, torch.from_numpy(thr).cuda(), mask, workspace=ws)
+        torch.cuda.synchronize()
+        assert_close("sweep t_done", got.cpu().numpy(), want)
+    # per-scenario thresholds
+    b = W.mixed(300, seed=32)
+    thr = np.ascontiguousarray(np.random.default_rng(1).uniform(0, 0.3, (3, b.n)))
+    want = oracle.sweep(b, thr, 6, thr_per_scenario=True, threads=8)
+    d = gpu.to_device(b)
+    ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(d.n * 3 * 2, d.max_chunks))
+    got = gpu.themis_sweep(d, torch.from_numpy(thr).cuda(), 6, thr_per_scenario=True, workspace=ws)
+    torch.cuda.synchronize()
+    assert_close("sweep t_done (per-scenario thr)", got.cpu().numpy(), want)
+
+
+def test_determinism_and_permutation_invariance(gpu):
+    """The same scenario gives the same bits wherever it sits in the batch
+    (the consistency requirement of Sec. 4.6: every NPU must derive exactly
+    the same schedule)."""
+    b = w().config3(n=2048)
+    a = run_gpu(gpu, b)
+    perm = np.random.default_rng(0).permutation(b.n)
+    p = run_gpu(gpu, b.take(perm))
+    assert np.array_equal(a[0][perm], p[0])
+    assert np.array_equal(a[2][perm], p[2])
+    assert np.array_equal(a[3][perm], p[3])
+    again = run_gpu(gpu, b)
+    assert all(np.array_equal(x, y) for x, y in zip(a, again))
