@@ -1,0 +1,148 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched Themis evaluator on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic
+scenarios resident in HBM: themis_plan_batch (Alg. 1) followed by
+themis_simulate_batch (queue simulation) with every output requested (order
+codes, final loads, completion times, per-dimension queue orders, busy times).
+The workload is the 1,048,576-scenario 4-D configuration (P = (2,8,8,64),
+C = 64, Themis + SCF, relative threshold).  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 compute units x 4 SIMDs, 2.4 GHz; a wave64 vector instruction
+# occupies its SIMD's issue port for 4 cycles (16 lanes per cycle).
+PEAK_WAVE_INSTR_PER_S = 256 * 4 * 2.4e9 / 4
+PEAK_LANE_OPS_PER_S = PEAK_WAVE_INSTR_PER_S * 64
+
+
+def algorithmic_lane_ops(D, C):
+    """Lane-operations one scenario needs, per kernel: the planner does about
+    45 compare/select/flop operations per chunk (min/max over D loads, a
+    D-element stable sort, D multiplies, divides and adds); the simulation
+    handles 2*D*C chunk-stage events, each selecting the smallest key among
+    up to C waiting chunks (one comparison per chunk)."""
+    return {"plan": 45 * C, "simulate": 2 * D * C * C}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--scenarios", type=int, default=1 << 20,
+                    help="batch size (default: the 1M-scenario configuration)")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 20,
+                    help="scenarios the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-queue-order", action="store_true",
+                    help="do not request the per-dimension queue orders")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build evaluates one GPU's share on one GPU; "
+                 "run with --gpus 1 (scenarios are independent, see DESIGN.md on sharding)")
+
+    import numpy as np
+    import torch
+    from paper_2110_04478_amd import binding, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    n = args.scenarios
+    host = workloads.config3(n=n)
+    D, C = 4, 64
+    d = binding.to_device(host, "cuda:0")
+
+    # outputs and scratch are allocated once, outside the timed region
+    orders = torch.empty((n, d.slots), dtype=torch.uint8, device="cuda:0")
+    loads = torch.empty((4, n), dtype=torch.float64, device="cuda:0")
+    t_done = torch.empty(n, dtype=torch.float64, device="cuda:0")
+    busy = torch.empty((4, n), dtype=torch.float64, device="cuda:0")
+    qo = None if args.no_queue_order else torch.empty(
+        (n, 4, 2 * d.slots), dtype=torch.uint8, device="cuda:0")
+    ws = binding.alloc_workspace(binding.themis_workspace_bytes(n, d.max_chunks))
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        binding.themis_plan_batch(d, orders, loads)
+        if ev:
+            ev[1].record()
+        binding.themis_simulate_batch(d, orders, t_done, qo, busy, ws,
+                                      want_queue_order=False)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # HIP events on the stream the kernels are launched on (torch's current one)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)]
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    plan_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    sim_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    ms_per_step = wall * 1e3 / args.steps
+
+    ops = algorithmic_lane_ops(D, C)
+    achieved = ops["simulate"] * n / (sim_ms * 1e-3)
+    result = {
+        "metric": "scenarios_per_sec",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "scenarios/s",
+        "events_per_sec": n * 2 * D * C / (ms_per_step * 1e-3),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "kernel_ms": {"plan": plan_ms, "simulate": sim_ms},
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "config3: %d scenarios, 4-D P=(2,8,8,64), C=64, "
+                               "Themis+SCF, relative threshold U[0,0.1]" % n,
+                   "outputs": "orders,loads,t_done,busy" + ("" if qo is None else ",queue_order"),
+                   "chunk_stage_events_per_scenario": 2 * D * C},
+        "roofline": {
+            "bound": "alu", "kernel": "simulate",
+            "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS_PER_S / 1e12,
+            "unit": "Tlane-op/s", "frac": achieved / PEAK_LANE_OPS_PER_S,
+            "traffic": None,
+            "algorithmic_lane_ops_per_scenario": ops["simulate"],
+        },
+    }
+
+    if args.cpu_sample > 0:
+        from oracle import themis_oracle
+        m = min(args.cpu_sample, n)
+        sample = host.take(slice(0, m))
+        cores = min(os.cpu_count() or 1, 16)
+        c0 = time.perf_counter()
+        o_orders, _ = themis_oracle.plan_batch(sample, threads=cores)
+        o_t, _, _ = themis_oracle.simulate_batch(sample, o_orders, want_queue_order=qo is not None,
+                                                 threads=cores)
+        cpu_s = time.perf_counter() - c0
+        # parity spot check on the sample while we have both results
+        g_t = t_done[:m].cpu().numpy()
+        rel = float(np.max(np.abs(g_t - o_t) / o_t))
+        same_orders = bool(np.array_equal(orders[:m].cpu().numpy(), o_orders))
+        result["cpu_baseline"] = {
+            "value": m / cpu_s, "unit": "scenarios/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d scenarios of the same batch, plan+simulate, %d threads, %.1f s"
+                      % (m, cores, cpu_s),
+            "parity_on_sample": {"orders_equal": same_orders, "t_done_max_rel_err": rel},
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
