@@ -3,6 +3,7 @@
 
 #include "themis.h"
 #include "themis_device.hpp"
+#include "themis_fast.hpp"
 #include "themis_generic.hpp"
 
 namespace themis {
@@ -66,22 +67,44 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
 
   uint8_t* row = orders + (size_t)i * tv.slots;
   double load[kMaxDims] = {0.0, 0.0, 0.0, 0.0};
-  if (ok) {
+  if (!ok) {
+    for (uint32_t c = 0; c < tv.slots; ++c) row[c] = 0xFFu;
+  } else {
+    // rows are written four codes at a time when they are 4-byte aligned
+    const bool words = (b.max_chunks & 3u) == 0u;
     for (uint32_t q = 0; q < tv.mc; ++q) {
       uint8_t* r = row + (size_t)q * b.max_chunks;
+      uint32_t filled = 0;
       if (q < Q) {
-        double chunk = collective_size(b, tv, i, q) / (double)s.C;
+        const double chunk = collective_size(b, tv, i, q) / (double)s.C;
+        FastScenario fs;
+        if (fast_eligible(s, chunk, fs)) {
+          uint32_t acc = 0;
+          plan_fast(s, fs, themis_on, rel, thr, load, [&](uint32_t c, uint32_t code) {
+            if (words) {
+              acc |= code << (8u * (c & 3u));
+              if ((c & 3u) == 3u) { ((uint32_t*)r)[c >> 2] = acc; acc = 0; }
+            } else {
+              r[c] = (uint8_t)code;
+            }
+          });
+          if (words && (s.C & 3u)) {  // pad the last partial word with unused-slot marks
+            acc |= 0xFFFFFFFFu << (8u * (s.C & 3u));
+            ((uint32_t*)r)[s.C >> 2] = acc;
+            filled = (s.C | 3u) + 1u;
+          } else {
+            filled = s.C;
+          }
+        } else {
 #pragma unroll
-        for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? 0.0 : inf64();
-        for (uint32_t c = 0; c < s.C; ++c)
-          r[c] = (uint8_t)schedule_chunk(s, chunk, themis_on, rel, thr, load);
-        for (uint32_t c = s.C; c < b.max_chunks; ++c) r[c] = 0xFFu;
-      } else {
-        for (uint32_t c = 0; c < b.max_chunks; ++c) r[c] = 0xFFu;
+          for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? 0.0 : inf64();
+          for (uint32_t c = 0; c < s.C; ++c)
+            r[c] = (uint8_t)schedule_chunk(s, chunk, themis_on, rel, thr, load);
+          filled = s.C;
+        }
       }
+      for (uint32_t c = filled; c < b.max_chunks; ++c) r[c] = 0xFFu;
     }
-  } else {
-    for (uint32_t c = 0; c < tv.slots; ++c) row[c] = 0xFFu;
   }
   if (loads) {
 #pragma unroll
@@ -91,46 +114,27 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
 }
 
 // ---------------------------------------------------------------------------
-// themis_simulate_batch, generic path (hot-path steps a6-a9).
+// themis_simulate_batch (hot-path steps a6-a9): LDS fast path, with the
+// generic workspace path for the scenarios it does not cover.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlock)
-simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
-                        double* __restrict__ t_done, void* __restrict__ queue_order,
-                        int entry_bytes, double* __restrict__ busy, Workspace w, bool have_ws) {
-  uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= b.n) return;
-  const TraceView tv = trace_view(b);
-  Scenario s = load_scenario(b, i);
-  const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
-  uint32_t Q;
-  bool ok = collectives_ok(b, tv, i, Q) && s.valid && have_ws;
-
-  SimOut out;
-  out.t_done = t_done + i;
-  out.busy = busy ? busy + i : nullptr;
-  out.busy_stride = b.n;
-  out.entry_bytes = entry_bytes;
-  out.slots = tv.slots;
-  out.queue_order = queue_order
-      ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
-      : nullptr;
-
-  const uint8_t* row = orders + (size_t)i * tv.slots;
+__device__ __noinline__ void simulate_generic_scenario(const themis_batch_t& b, const TraceView& tv,
+                                                       const Scenario& s, uint32_t Q, uint64_t i,
+                                                       const uint8_t* row, bool scf,
+                                                       const Workspace& w, const SimOut& out) {
+  bool ok = true;
   bool has_release = false;
-  if (ok) {
-    // a6: every chunk waits at the dimension of its first stage
-    for (uint32_t q = 0; q < Q; ++q) {
-      double chunk = collective_size(b, tv, i, q) / (double)s.C;
-      double rel = collective_release(b, tv, i, q);
-      has_release |= rel > 0.0;
-      for (uint32_t c = 0; c < s.C; ++c) {
-        uint32_t code = row[(size_t)q * b.max_chunks + c];
-        if (!order_code_ok(code, s.D)) ok = false;
-        size_t at = (size_t)(q * s.C + c) * w.stride + i;
-        w.meta[at] = code << 8;
-        w.size[at] = chunk;
-        w.arrival[at] = rel;
-      }
+  // a6: every chunk waits at the dimension of its first stage
+  for (uint32_t q = 0; q < Q; ++q) {
+    double chunk = collective_size(b, tv, i, q) / (double)s.C;
+    double rel = collective_release(b, tv, i, q);
+    has_release |= rel > 0.0;
+    for (uint32_t c = 0; c < s.C; ++c) {
+      uint32_t code = row[(size_t)q * b.max_chunks + c];
+      if (!order_code_ok(code, s.D)) ok = false;
+      size_t at = (size_t)(q * s.C + c) * w.stride + i;
+      w.meta[at] = code << 8;
+      w.size[at] = chunk;
+      w.arrival[at] = rel;
     }
   }
   if (!ok) { write_invalid(out); return; }
@@ -140,14 +144,112 @@ simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       [&](uint32_t q) { return collective_release(b, tv, i, q); }, has_release, out);
 }
 
-// ---------------------------------------------------------------------------
-// themis_sweep, generic path (hot-path step a10): one lane per
-// scenario x threshold x scheduler.
-// ---------------------------------------------------------------------------
+template <bool kQueueOrder>
 __global__ void __launch_bounds__(kBlock)
-sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
-                     int thr_per_scenario, unsigned policy_mask, int n_pol,
-                     double* __restrict__ t_done, Workspace w, bool have_ws) {
+simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
+                double* __restrict__ t_done, void* __restrict__ queue_order, int entry_bytes,
+                double* __restrict__ busy, Workspace w, bool have_ws) {
+  __shared__ uint32_t lds_block[kLaneWords * kBlock];
+  uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= b.n) return;
+  const TraceView tv = trace_view(b);
+  Scenario s = load_scenario(b, i);
+  const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
+  uint32_t Q;
+  bool ok = collectives_ok(b, tv, i, Q) && s.valid;
+
+  SimOut out;
+  out.t_done = t_done + i;
+  out.busy = busy ? busy + i : nullptr;
+  out.busy_stride = b.n;
+  out.entry_bytes = entry_bytes;
+  out.slots = tv.slots;
+  out.queue_order = (kQueueOrder && queue_order)
+      ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
+      : nullptr;
+  if (!ok) { write_invalid(out); return; }
+
+  const uint8_t* row = orders + (size_t)i * tv.slots;
+  FastScenario fs;
+  bool fast = !tv.on && entry_bytes == 1 &&
+              fast_eligible(s, collective_size(b, tv, i, 0) / (double)s.C, fs);
+  if (fast) {
+    LaneLds lds;
+    lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+    // order codes -> chunk words (mask 0, Reduce-Scatter phase)
+    bool codes_ok = true;
+    if ((tv.slots & 3u) == 0u) {
+      const uint32_t* row4 = (const uint32_t*)row;
+      for (uint32_t c4 = 0; c4 < s.C; c4 += 4u) {
+        uint32_t v = row4[c4 >> 2];
+#pragma unroll
+        for (uint32_t j = 0; j < 4u; ++j) {
+          if (c4 + j < s.C) {
+            uint32_t code = (v >> (8u * j)) & 0xffu;
+            codes_ok = codes_ok && order_code_ok(code, s.D);
+            lds.w16(kOffW + 2u * (c4 + j), code);
+          }
+        }
+      }
+    } else {
+      for (uint32_t c = 0; c < s.C; ++c) {
+        uint32_t code = row[c];
+        codes_ok = codes_ok && order_code_ok(code, s.D);
+        lds.w16(kOffW + 2u * c, code);
+      }
+    }
+    if (!codes_ok) { write_invalid(out); return; }
+    FastOut fo;
+    fo.queue_order = (uint8_t*)out.queue_order;
+    fo.slots = tv.slots;
+    fo.want_busy = busy != nullptr;
+    FastResult r = simulate_fast<kQueueOrder>(s, fs, scf, lds, fo);
+    if (r.ok) {
+      t_done[i] = r.t_done;
+      if (busy) {
+#pragma unroll
+        for (int k = 0; k < kMaxDims; ++k) busy[(size_t)k * b.n + i] = r.busy[k];
+      }
+      if (kQueueOrder && out.queue_order) {
+        for (int k = 0; k < kMaxDims; ++k)
+          for (uint32_t e = (r.executed >> (8 * k)) & 0xffu; e < 2u * tv.slots; ++e)
+            fo.queue_order[(size_t)k * 2u * tv.slots + e] = 0xFFu;
+      }
+      return;
+    }
+  }
+  if (!have_ws) { write_invalid(out); return; }
+  simulate_generic_scenario(b, tv, s, Q, i, row, scf, w, out);
+}
+
+// ---------------------------------------------------------------------------
+// themis_sweep (hot-path step a10): one lane per scenario x threshold x
+// scheduler; the plan goes straight into LDS and only the time leaves.
+// ---------------------------------------------------------------------------
+__device__ __noinline__ void sweep_generic_evaluation(const Scenario& s, double chunk,
+                                                      bool themis_on, bool rel, double th,
+                                                      bool scf, uint64_t e, const Workspace& w,
+                                                      const SimOut& out) {
+  double load[kMaxDims];
+#pragma unroll
+  for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? 0.0 : inf64();
+  for (uint32_t c = 0; c < s.C; ++c) {
+    uint32_t code = schedule_chunk(s, chunk, themis_on, rel, th, load);
+    size_t at = (size_t)c * w.stride + e;
+    w.meta[at] = code << 8;
+    w.size[at] = chunk;
+    w.arrival[at] = 0.0;
+  }
+  simulate_generic(
+      s, 1u, scf, w, e, [&](uint32_t) { return chunk; }, [&](uint32_t) { return 0.0; }, false,
+      out);
+}
+
+__global__ void __launch_bounds__(kBlock)
+sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
+             unsigned policy_mask, int n_pol, double* __restrict__ t_done, Workspace w,
+             bool have_ws) {
+  __shared__ uint32_t lds_block[kLaneWords * kBlock];
   uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
   if (e >= total) return;
@@ -166,20 +268,25 @@ sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr
   const bool rel = b.threshold_mode == THEMIS_THR_REL;
   const double th = thr_per_scenario ? thr[(size_t)a * b.n + i] : thr[a];
   const double S = b.size_bytes[i];
-  bool ok = s.valid && finite_positive(S) && threshold_ok(th, rel) && have_ws;
+  bool ok = s.valid && finite_positive(S) && threshold_ok(th, rel);
   if (!ok) { t_done[e] = nan64(); return; }
 
   const double chunk = S / (double)s.C;
-  double load[kMaxDims];
-#pragma unroll
-  for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? 0.0 : inf64();
-  for (uint32_t c = 0; c < s.C; ++c) {
-    uint32_t code = schedule_chunk(s, chunk, themis_on, rel, th, load);
-    size_t at = (size_t)c * w.stride + e;
-    w.meta[at] = code << 8;
-    w.size[at] = chunk;
-    w.arrival[at] = 0.0;
+  FastScenario fs;
+  if (fast_eligible(s, chunk, fs)) {
+    LaneLds lds;
+    lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+    double load[kMaxDims];
+    plan_fast(s, fs, themis_on, rel, th, load,
+              [&](uint32_t c, uint32_t code) { lds.w16(kOffW + 2u * c, code); });
+    FastOut fo;
+    fo.queue_order = nullptr;
+    fo.slots = b.max_chunks;
+    fo.want_busy = false;
+    FastResult r = simulate_fast<false>(s, fs, scf, lds, fo);
+    if (r.ok) { t_done[e] = r.t_done; return; }
   }
+  if (!have_ws) { t_done[e] = nan64(); return; }
   SimOut out;
   out.t_done = t_done + e;
   out.busy = nullptr;
@@ -187,9 +294,7 @@ sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr
   out.queue_order = nullptr;
   out.entry_bytes = 1;
   out.slots = b.max_chunks;
-  simulate_generic(
-      s, 1u, scf, w, e, [&](uint32_t) { return chunk; }, [&](uint32_t) { return 0.0; }, false,
-      out);
+  sweep_generic_evaluation(s, chunk, themis_on, rel, th, scf, e, w, out);
 }
 
 // ---------------------------------------------------------------------------
@@ -271,10 +376,16 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   const bool have_ws =
       workspace != nullptr && workspace_bytes_given >= workspace_bytes(batch->n, tv.slots);
   Workspace w = carve_workspace(workspace, batch->n, tv.slots);
-  hipLaunchKernelGGL(simulate_generic_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
-                     (hipStream_t)stream, *batch, orders, t_done, queue_order,
-                     themis_queue_entry_bytes(batch->max_chunks, tv.on ? batch->max_coll : 0u),
-                     busy, w, have_ws);
+  const int entry_bytes =
+      themis_queue_entry_bytes(batch->max_chunks, tv.on ? batch->max_coll : 0u);
+  if (queue_order)
+    hipLaunchKernelGGL(simulate_kernel<true>, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
+                       busy, w, have_ws);
+  else
+    hipLaunchKernelGGL(simulate_kernel<false>, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
+                       busy, w, have_ws);
   return launch_status();
 }
 
@@ -294,7 +405,7 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   const bool have_ws = workspace != nullptr &&
                        workspace_bytes_given >= workspace_bytes(evals, batch->max_chunks);
   Workspace w = carve_workspace(workspace, evals, batch->max_chunks);
-  hipLaunchKernelGGL(sweep_generic_kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
+  hipLaunchKernelGGL(sweep_kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                      n_pol, t_done, w, have_ws);
   return launch_status();
