@@ -144,7 +144,7 @@ __device__ __noinline__ void simulate_generic_scenario(const themis_batch_t& b, 
       [&](uint32_t q) { return collective_release(b, tv, i, q); }, has_release, out);
 }
 
-template <bool kQueueOrder>
+template <int kQueueOrder, bool kBusy>
 __global__ void __launch_bounds__(kBlock)
 simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                 double* __restrict__ t_done, void* __restrict__ queue_order, int entry_bytes,
@@ -164,7 +164,7 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
   out.busy_stride = b.n;
   out.entry_bytes = entry_bytes;
   out.slots = tv.slots;
-  out.queue_order = (kQueueOrder && queue_order)
+  out.queue_order = (kQueueOrder != kNoQueueOrder && queue_order)
       ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
       : nullptr;
   if (!ok) { write_invalid(out); return; }
@@ -187,7 +187,7 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
           if (c4 + j < s.C) {
             uint32_t code = (v >> (8u * j)) & 0xffu;
             codes_ok = codes_ok && order_code_ok(code, s.D);
-            lds.w16(kOffW + 2u * (c4 + j), code);
+            lds.init_chunk(c4 + j, code);
           }
         }
       }
@@ -195,22 +195,21 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       for (uint32_t c = 0; c < s.C; ++c) {
         uint32_t code = row[c];
         codes_ok = codes_ok && order_code_ok(code, s.D);
-        lds.w16(kOffW + 2u * c, code);
+        lds.init_chunk(c, code);
       }
     }
     if (!codes_ok) { write_invalid(out); return; }
     FastOut fo;
     fo.queue_order = (uint8_t*)out.queue_order;
     fo.slots = tv.slots;
-    fo.want_busy = busy != nullptr;
-    FastResult r = simulate_fast<kQueueOrder>(s, fs, scf, lds, fo);
+    FastResult r = simulate_fast<kQueueOrder, kBusy>(s, fs, scf, lds, fo);
     if (r.ok) {
       t_done[i] = r.t_done;
       if (busy) {
 #pragma unroll
         for (int k = 0; k < kMaxDims; ++k) busy[(size_t)k * b.n + i] = r.busy[k];
       }
-      if (kQueueOrder && out.queue_order) {
+      if (kQueueOrder != kNoQueueOrder && out.queue_order) {
         for (int k = 0; k < kMaxDims; ++k)
           for (uint32_t e = (r.executed >> (8 * k)) & 0xffu; e < 2u * tv.slots; ++e)
             fo.queue_order[(size_t)k * 2u * tv.slots + e] = 0xFFu;
@@ -278,12 +277,11 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
     double load[kMaxDims];
     plan_fast(s, fs, themis_on, rel, th, load,
-              [&](uint32_t c, uint32_t code) { lds.w16(kOffW + 2u * c, code); });
+              [&](uint32_t c, uint32_t code) { lds.init_chunk(c, code); });
     FastOut fo;
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;
-    fo.want_busy = false;
-    FastResult r = simulate_fast<false>(s, fs, scf, lds, fo);
+    FastResult r = simulate_fast<kNoQueueOrder, false>(s, fs, scf, lds, fo);
     if (r.ok) { t_done[e] = r.t_done; return; }
   }
   if (!have_ws) { t_done[e] = nan64(); return; }
@@ -378,14 +376,15 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   Workspace w = carve_workspace(workspace, batch->n, tv.slots);
   const int entry_bytes =
       themis_queue_entry_bytes(batch->max_chunks, tv.on ? batch->max_coll : 0u);
-  if (queue_order)
-    hipLaunchKernelGGL(simulate_kernel<true>, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
-                       busy, w, have_ws);
-  else
-    hipLaunchKernelGGL(simulate_kernel<false>, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
-                       busy, w, have_ws);
+  // dword-buffered queue-order stores need 4-byte aligned rows of 2*slots bytes
+  const bool words = entry_bytes == 1 && (tv.slots & 1u) == 0u &&
+                     ((uintptr_t)queue_order & 3u) == 0u;
+  auto kernel =
+      !queue_order ? (busy ? simulate_kernel<kNoQueueOrder, true> : simulate_kernel<kNoQueueOrder, false>)
+      : words      ? (busy ? simulate_kernel<kWords, true> : simulate_kernel<kWords, false>)
+                   : (busy ? simulate_kernel<kBytes, true> : simulate_kernel<kBytes, false>);
+  hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0, (hipStream_t)stream,
+                     *batch, orders, t_done, queue_order, entry_bytes, busy, w, have_ws);
   return launch_status();
 }
 

@@ -28,27 +28,28 @@
 
 namespace themis {
 
-constexpr int kFastCap = 64;           // chunks per evaluation the LDS layout holds
-constexpr int kOffW = 0;               // u16 W[64] : code | mask<<8 | phase<<12
-constexpr int kOffNext = 128;          // u8  NX[64]: next chunk in the same list
-constexpr int kOffHead = 192;          // u8  H[4*16]: list heads
-constexpr int kOffTail = 256;          // u8  T[4*16]: list tails
-constexpr int kLaneBytes = 320;
-constexpr int kLaneWords = kLaneBytes / 4;
+constexpr int kFastCap = 64;      // chunks per evaluation the LDS layout holds
+// Per-lane LDS, in dwords:
+//   0..63   one dword per chunk c AND per list q (both run 0..63):
+//             byte 0  chunk c: reduced-dims mask | phase << 4
+//             byte 1  chunk c: next chunk in its list (0xFF = last)
+//             byte 2  chunk c: order code
+//             byte 3  list q = 16*dim + class: head chunk
+//   64..79  u8 tail[64]: last chunk of list q
+constexpr int kTailDword = 64;
+constexpr int kLaneWords = 80;
 constexpr int kFastLdsBytes = kLaneWords * 64 * 4;  // per wavefront
+constexpr uint32_t kEndOfList = 0xffu;
 
 struct LaneLds {
   uint8_t* base;  // LDS block of the wavefront + 4*lane
-  __device__ __forceinline__ uint32_t at(uint32_t byte) const {
-    return ((byte >> 2) << 8) | (byte & 3u);
+  // byte address of dword d of this lane (transposed layout: 256 B apart)
+  __device__ __forceinline__ uint8_t* dword(uint32_t d) const { return base + (d << 8); }
+  __device__ __forceinline__ uint8_t* tail(uint32_t q) const {
+    return base + (kTailDword << 8) + ((q >> 2) << 8) + (q & 3u);
   }
-  __device__ __forceinline__ uint32_t r8(uint32_t byte) const { return base[at(byte)]; }
-  __device__ __forceinline__ void w8(uint32_t byte, uint32_t v) const { base[at(byte)] = (uint8_t)v; }
-  __device__ __forceinline__ uint32_t r16(uint32_t byte) const {
-    return *(const uint16_t*)(base + at(byte));
-  }
-  __device__ __forceinline__ void w16(uint32_t byte, uint32_t v) const {
-    *(uint16_t*)(base + at(byte)) = (uint16_t)v;
+  __device__ __forceinline__ void init_chunk(uint32_t c, uint32_t code) const {
+    *(uint32_t*)dword(c) = (code << 16) | (kEndOfList << 8);  // mask 0, Reduce-Scatter phase
   }
 };
 
@@ -164,7 +165,6 @@ __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario&
 struct FastOut {
   uint8_t* queue_order;  // this evaluation's [4][2*slots] bytes, or null
   uint32_t slots;
-  bool want_busy;
 };
 
 struct FastResult {
@@ -192,12 +192,27 @@ __device__ __forceinline__ uint64_t build_rank_table(uint32_t epack, bool scf) {
   return tab;
 }
 
-// Chunk words W[c] must already be in LDS: code | 0<<8 (mask) | 0<<12 (phase).
-template <bool kQueueOrder>
+// min of two non-NaN doubles in one instruction (fmin() would first
+// canonicalise both operands).
+__device__ __forceinline__ double min_f64(double a, double b) {
+  double r;
+  asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+// How the per-dimension queue orders leave the kernel.  Every lane appends
+// bytes to its own four rows, so stores never coalesce across lanes; kWords
+// collects four entries per dimension in a register and stores them as one
+// aligned dword (a quarter of the memory transactions), and needs rows that
+// start on a 4-byte boundary (an even number of slots).
+enum QueueOrderMode { kNoQueueOrder = 0, kBytes = 1, kWords = 2 };
+
+// Chunk dwords must already be initialised with LaneLds::init_chunk().
+template <int kQueueOrder, bool kBusy>
 __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const FastScenario& fs,
                                                     bool scf, const LaneLds& lds,
                                                     const FastOut& out) {
-  const int D = s.D;
+  const uint32_t D = (uint32_t)s.D;
   const uint32_t C = s.C;
   const uint32_t full = (1u << D) - 1u;
   const uint64_t ranktab = build_rank_table(fs.epack, scf);
@@ -207,82 +222,95 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
   double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
   uint32_t serving = 0;   // chunk id per dimension, one byte each
   uint32_t executed = 0;  // operations started per dimension, one byte each
-  uint64_t nonempty = 0;  // bit 16*k + class
-  FastResult res;
-  res.ok = true;
+  uint64_t nonempty = 0;  // bit q = 16*dim + class: list q holds chunks
+  uint32_t work = 0;      // bit k: some list of dimension k holds chunks
+  uint32_t idle = full;   // bit k: dimension k serves nothing
+  bool stalled = false;   // a stage did not advance time: generic path decides
+  uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0;  // last four queue entries per dimension
+  const uint32_t row_len = 2u * out.slots;
 
-  auto push = [&](uint32_t k, uint32_t cls, uint32_t c) {
-    uint32_t q = 16u * k + cls;
+  // append chunk c to list q (branch-free: an empty list takes c as its head,
+  // otherwise the old tail's next field does)
+  auto push = [&](uint32_t q, uint32_t c) {
     uint64_t bit = 1ull << q;
-    if (nonempty & bit) {
-      uint32_t t = lds.r8(kOffTail + q);
-      lds.w8(kOffNext + t, c);
-    } else {
-      lds.w8(kOffHead + q, c);
-      nonempty |= bit;
-    }
-    lds.w8(kOffTail + q, c);
+    bool had = (nonempty & bit) != 0ull;
+    uint8_t* tp = lds.tail(q);
+    uint32_t t = *tp;
+    uint8_t* dst = had ? lds.dword(t) + 1 : lds.dword(q) + 3;
+    *dst = (uint8_t)c;
+    *tp = (uint8_t)c;
+    nonempty |= bit;
+    work |= 1u << (q >> 4);
   };
 
   // a6: every chunk waits at the dimension of its first stage, resident size
   // = chunk (mask 0, the lowest class), in chunk-id order
-  for (uint32_t c = 0; c < C; ++c) push(lds.r16(kOffW + 2u * c) & 3u, 0u, c);
+  for (uint32_t c = 0; c < C; ++c) push(16u * (lds.dword(c)[2] & 3u), c);
 
   double now = 0.0;
-  const uint32_t max_steps = 2u * (uint32_t)D * C + 8u;
+  const uint32_t max_steps = 2u * D * C + 8u;
   for (uint32_t step = 0; step <= max_steps; ++step) {
     // a7: every idle dimension with waiting chunks starts its first one
-    for (;;) {
-      uint32_t need = 0;
-      need |= (f0 == kInf && (nonempty & 0xffffull)) ? 1u : 0u;
-      need |= (f1 == kInf && (nonempty & 0xffff0000ull)) ? 2u : 0u;
-      need |= (f2 == kInf && (nonempty & 0xffff00000000ull)) ? 4u : 0u;
-      need |= (f3 == kInf && (nonempty & 0xffff000000000000ull)) ? 8u : 0u;
-      if (!need) break;
-      uint32_t k = (uint32_t)__builtin_ctz(need);
-      uint32_t field = (uint32_t)(nonempty >> (16u * k)) & 0xffffu;
-      uint32_t cls = 31u - (uint32_t)__clz((int)field);  // smallest resident size
-      uint32_t q = 16u * k + cls;
-      uint32_t h = lds.r8(kOffHead + q);
-      uint32_t tl = lds.r8(kOffTail + q);
-      uint32_t w = lds.r16(kOffW + 2u * h);
-      if (h == tl) nonempty &= ~(1ull << q);
-      else lds.w8(kOffHead + q, lds.r8(kOffNext + h));
-      uint32_t mask = (w >> 8) & 15u;
-      uint32_t phase = (w >> 12) & 1u;
+    for (uint32_t need = idle & work; need != 0u; need = idle & work) {
+      const uint32_t k = (uint32_t)__builtin_ctz(need);
+      const uint32_t field = (uint32_t)(nonempty >> (16u * k)) & 0xffffu;
+      const uint32_t cls = 31u - (uint32_t)__clz((int)field);  // smallest resident size
+      const uint32_t q = 16u * k + cls;
+      uint8_t* hp = lds.dword(q) + 3;
+      const uint32_t h = *hp;
+      const uint32_t w = *(const uint32_t*)lds.dword(h);
+      const uint32_t nx = (w >> 8) & 0xffu;
+      *hp = (uint8_t)nx;  // harmless when the list is now empty
+      const bool emptied = nx == kEndOfList;
+      nonempty &= ~(emptied ? (1ull << q) : 0ull);
+      const bool no_work = (field & ~((emptied ? 1u : 0u) << cls)) == 0u;
+      work &= ~((no_work ? 1u : 0u) << k);
+      idle &= ~(1u << k);
+
+      const uint32_t mask = w & 15u;
+      const uint32_t phase = (w >> 4) & 1u;
       // bytes moved on k = resident size before the chunk's Reduce-Scatter on
       // k; the All-Gather reuses it (mask still contains k then)
-      uint32_t ek = (fs.epack >> (8u * k)) & 0xffu;
-      uint32_t E = esum(fs.epack, mask) - (phase ? ek : 0u);
-      double x = scale_down(fs.chunk, E);
-      double t = x * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
-      double f = now + t;
-      if (!(f > now)) { res.ok = false; break; }  // time did not advance: generic path decides
-      f0 = (k == 0u) ? f : f0; f1 = (k == 1u) ? f : f1;
-      f2 = (k == 2u) ? f : f2; f3 = (k == 3u) ? f : f3;
-      if (out.want_busy) {
-        z0 = (k == 0u) ? z0 + t : z0; z1 = (k == 1u) ? z1 + t : z1;
-        z2 = (k == 2u) ? z2 + t : z2; z3 = (k == 3u) ? z3 + t : z3;
+      const uint32_t ek = (fs.epack >> (8u * k)) & 0xffu;
+      const uint32_t E = esum(fs.epack, mask) - (phase ? ek : 0u);
+      const double t = scale_down(fs.chunk, E) *
+                       sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+      const double f = now + t;
+      stalled |= !(f > now);
+      const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
+      f0 = k0 ? f : f0; f1 = k1 ? f : f1; f2 = k2 ? f : f2; f3 = k3 ? f : f3;
+      if (kBusy) {
+        z0 = k0 ? z0 + t : z0; z1 = k1 ? z1 + t : z1;
+        z2 = k2 ? z2 + t : z2; z3 = k3 ? z3 + t : z3;
       }
-      uint32_t sh = 8u * k;
+      const uint32_t sh = 8u * k;
       serving = (serving & ~(0xffu << sh)) | (h << sh);
-      if (kQueueOrder) {
-        uint32_t pos = (executed >> sh) & 0xffu;
-        if (pos < 2u * out.slots)  // always true for a consistent plan; keeps the store in bounds
-          out.queue_order[(size_t)k * 2u * out.slots + pos] = (uint8_t)((h << 1) | phase);
+      if (kQueueOrder != kNoQueueOrder) {
+        const uint32_t pos = (executed >> sh) & 0xffu;
+        const uint32_t entry = (h << 1) | phase;
+        // pos < row_len always holds for a consistent plan; it keeps the store in bounds
+        if (kQueueOrder == kBytes) {
+          if (pos < row_len) out.queue_order[k * row_len + pos] = (uint8_t)entry;
+        } else {
+          // shift the entry in from the top: after four entries the register
+          // holds them in memory (little-endian) order
+          const uint32_t a = __builtin_amdgcn_alignbit(entry, sel4((int)k, a0, a1, a2, a3), 8u);
+          a0 = k0 ? a : a0; a1 = k1 ? a : a1; a2 = k2 ? a : a2; a3 = k3 ? a : a3;
+          if ((pos & 3u) == 3u && pos < row_len)
+            *(uint32_t*)(out.queue_order + k * row_len + (pos & ~3u)) = a;
+        }
       }
       executed += 1u << sh;
     }
-    if (!res.ok) break;
 
     // a8: advance to the earliest completion
-    double next = fmin(fmin(f0, f1), fmin(f2, f3));
+    const double next = min_f64(min_f64(f0, f1), min_f64(f2, f3));
     if (!(next < kInf)) break;  // nothing running: every chunk is done
     now = next;
-    uint32_t done = (f0 == now ? 1u : 0u) | (f1 == now ? 2u : 0u) | (f2 == now ? 4u : 0u) |
-                    (f3 == now ? 8u : 0u);
-    f0 = (f0 == now) ? kInf : f0; f1 = (f1 == now) ? kInf : f1;
-    f2 = (f2 == now) ? kInf : f2; f3 = (f3 == now) ? kInf : f3;
+    const bool d0 = f0 == now, d1 = f1 == now, d2 = f2 == now, d3 = f3 == now;
+    uint32_t done = (d0 ? 1u : 0u) | (d1 ? 2u : 0u) | (d2 ? 4u : 0u) | (d3 ? 8u : 0u);
+    f0 = d0 ? kInf : f0; f1 = d1 ? kInf : f1; f2 = d2 ? kInf : f2; f3 = d3 ? kInf : f3;
+    idle |= done;
     // deliver all completions of this instant, lowest chunk id first, so that
     // equal arrival times are appended in chunk-id order
     do {
@@ -296,28 +324,43 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
         }
       }
       done &= ~(1u << k);
-      uint32_t c = (serving >> (8u * k)) & 0xffu;
-      uint32_t w = lds.r16(kOffW + 2u * c);
-      uint32_t code = w & 0xffu, mask = (w >> 8) & 15u, phase = (w >> 12) & 1u;
-      uint32_t kn;
-      bool finished = false;
-      if (!phase) {
-        mask |= 1u << k;
-        if (mask == full) { phase = 1u; kn = k; }              // last RS: AG starts on the same dim
-        else kn = (code >> (2u * __builtin_popcount(mask))) & 3u;
-      } else {
-        mask &= ~(1u << k);
-        finished = mask == 0u;
-        kn = finished ? 0u : (code >> (2u * (__builtin_popcount(mask) - 1u))) & 3u;
-      }
+      const uint32_t c = (serving >> (8u * k)) & 0xffu;
+      uint8_t* cp = lds.dword(c);
+      const uint32_t w = *(const uint32_t*)cp;
+      const uint32_t code = (w >> 16) & 0xffu;
+      uint32_t phase = (w >> 4) & 1u;
+      // a Reduce-Scatter sets the dimension's bit, an All-Gather clears it
+      const uint32_t mask = (w & 15u) ^ (1u << k);
+      const bool finished = phase != 0u && mask == 0u;
+      phase |= (mask == full) ? 1u : 0u;  // last Reduce-Scatter: All-Gather starts on the same dim
       if (!finished) {
-        lds.w16(kOffW + 2u * c, code | (mask << 8) | (phase << 12));
-        uint32_t cls = (uint32_t)(ranktab >> (4u * mask)) & 15u;
-        push(kn, cls, c);
+        // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
+        const uint32_t pos = (uint32_t)__builtin_popcount(mask) - phase;
+        const uint32_t kn = (code >> (2u * pos)) & 3u;
+        *(uint16_t*)cp = (uint16_t)(mask | (phase << 4) | (kEndOfList << 8));
+        const uint32_t cls = (uint32_t)(ranktab >> (4u * mask)) & 15u;
+        push(16u * kn + cls, c);
       }
     } while (done);
   }
 
+  if (kQueueOrder == kWords) {
+    // entries that did not fill a whole dword yet
+    const uint32_t acc[kMaxDims] = {a0, a1, a2, a3};
+#pragma unroll
+    for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) {
+      const uint32_t n = (executed >> (8u * k)) & 0xffu;
+      const uint32_t rem = n & 3u;
+      for (uint32_t j = 0; j < rem; ++j) {
+        const uint32_t pos = n - rem + j;
+        if (pos < row_len)
+          out.queue_order[k * row_len + pos] = (uint8_t)(acc[k] >> (8u * (4u - rem + j)));
+      }
+    }
+  }
+
+  FastResult res;
+  res.ok = !stalled;
   res.t_done = now;
   res.busy[0] = z0; res.busy[1] = z1; res.busy[2] = z2; res.busy[3] = z3;
   res.executed = executed;
