@@ -213,3 +213,43 @@ def test_determinism_and_permutation_invariance(gpu):
     assert np.array_equal(a[3][perm], p[3])
     again = run_gpu(gpu, b)
     assert all(np.array_equal(x, y) for x, y in zip(a, again))
+
+
+def test_full_size_config3_sampled_and_invariants(gpu, oracle):
+    """The 1,048,576-scenario configuration in the launch shape bench.py times:
+    sampled scenarios against the oracle, and properties that hold for every
+    scenario (Sec. 4.4: T >= max_K load_K; Table 3 Ideal: T >= S / sum B;
+    every dimension executes each (chunk, phase) exactly once)."""
+    import torch
+    W = w()
+    b = W.config3()
+    d = gpu.to_device(b)
+    orders, loads = gpu.themis_plan_batch(d)
+    ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(d.n, d.max_chunks))
+    t, qo, busy = gpu.themis_simulate_batch(d, orders, workspace=ws)
+    torch.cuda.synchronize()
+    # -- invariants over the whole batch, evaluated with torch on the device
+    assert bool(torch.isfinite(t).all())
+    assert bool((t >= loads.max(dim=0).values * (1 - 1e-12)).all())
+    ideal = d.size_bytes / d.bw.sum(dim=0)
+    assert bool((t >= ideal).all())
+    rel = ((busy - loads).abs() / loads).max().item()
+    assert rel <= 1e-12, f"busy vs planned loads: {rel:.3e}"
+    rows = torch.sort(qo.view(-1, 2 * d.slots), dim=1).values
+    want = torch.arange(2 * d.slots, dtype=torch.uint8, device=rows.device)
+    assert bool((rows == want).all()), "a dimension's executed list is not a permutation"
+    del rows
+    o = orders.to(torch.int32)
+    seen = (1 << (o & 3)) | (1 << ((o >> 2) & 3)) | (1 << ((o >> 4) & 3)) | (1 << ((o >> 6) & 3))
+    assert bool((seen == 15).all()), "an order code is not a permutation of the 4 dimensions"
+    # -- sampled scenarios against the oracle, element by element
+    idx = np.sort(np.random.default_rng(2110).choice(b.n, 4096, replace=False))
+    sub = b.take(idx)
+    o_orders, o_loads = oracle.plan_batch(sub, threads=8)
+    o_t, o_qo, o_busy = oracle.simulate_batch(sub, o_orders, threads=8)
+    sel = torch.from_numpy(idx).cuda()
+    assert np.array_equal(orders[sel].cpu().numpy(), o_orders)
+    assert np.array_equal(widen_queue(qo[sel]), o_qo)
+    assert_close("t_done", t[sel].cpu().numpy(), o_t)
+    assert_close("loads", loads[:, sel].cpu().numpy(), o_loads)
+    assert_close("busy", busy[:, sel].cpu().numpy(), o_busy)
