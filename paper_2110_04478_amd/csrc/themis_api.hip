@@ -78,7 +78,7 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
       if (q < Q) {
         const double chunk = collective_size(b, tv, i, q) / (double)s.C;
         FastScenario fs;
-        if (fast_eligible(s, chunk, fs)) {
+        if (fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs)) {
           uint32_t acc = 0;
           plan_fast(s, fs, themis_on, rel, thr, load, [&](uint32_t c, uint32_t code) {
             if (words) {
@@ -144,12 +144,18 @@ __device__ __noinline__ void simulate_generic_scenario(const themis_batch_t& b, 
       [&](uint32_t q) { return collective_release(b, tv, i, q); }, has_release, out);
 }
 
-template <int kQueueOrder, bool kBusy>
+template <int kQueueOrder>
+__device__ __forceinline__ void put_queue_entry(uint8_t* rows, uint32_t at, uint32_t v) {
+  if (kQueueOrder == kShorts) ((uint16_t*)rows)[at] = (uint16_t)v;
+  else rows[at] = (uint8_t)v;
+}
+
+template <typename L, int kQueueOrder, bool kBusy>
 __global__ void __launch_bounds__(kBlock)
 simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                 double* __restrict__ t_done, void* __restrict__ queue_order, int entry_bytes,
                 double* __restrict__ busy, Workspace w, bool have_ws) {
-  __shared__ uint32_t lds_block[kLaneWords * kBlock];
+  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= b.n) return;
   const TraceView tv = trace_view(b);
@@ -171,8 +177,8 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 
   const uint8_t* row = orders + (size_t)i * tv.slots;
   FastScenario fs;
-  bool fast = !tv.on && entry_bytes == 1 &&
-              fast_eligible(s, collective_size(b, tv, i, 0) / (double)s.C, fs);
+  bool fast = !tv.on &&
+              fast_eligible(s, collective_size(b, tv, i, 0) / (double)s.C, L::kCap, fs);
   if (fast) {
     LaneLds lds;
     lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
@@ -187,7 +193,7 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
           if (c4 + j < s.C) {
             uint32_t code = (v >> (8u * j)) & 0xffu;
             codes_ok = codes_ok && order_code_ok(code, s.D);
-            lds.init_chunk(c4 + j, code);
+            L::init_chunk(lds, c4 + j, code);
           }
         }
       }
@@ -195,14 +201,14 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       for (uint32_t c = 0; c < s.C; ++c) {
         uint32_t code = row[c];
         codes_ok = codes_ok && order_code_ok(code, s.D);
-        lds.init_chunk(c, code);
+        L::init_chunk(lds, c, code);
       }
     }
     if (!codes_ok) { write_invalid(out); return; }
     FastOut fo;
     fo.queue_order = (uint8_t*)out.queue_order;
     fo.slots = tv.slots;
-    FastResult r = simulate_fast<kQueueOrder, kBusy>(s, fs, scf, lds, fo);
+    FastResult r = simulate_fast<L, kQueueOrder, kBusy>(s, fs, scf, lds, fo);
     if (r.ok) {
       t_done[i] = r.t_done;
       if (busy) {
@@ -211,8 +217,8 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       }
       if (kQueueOrder != kNoQueueOrder && out.queue_order) {
         for (int k = 0; k < kMaxDims; ++k)
-          for (uint32_t e = (r.executed >> (8 * k)) & 0xffu; e < 2u * tv.slots; ++e)
-            fo.queue_order[(size_t)k * 2u * tv.slots + e] = 0xFFu;
+          for (uint32_t e = r.executed[k]; e < 2u * tv.slots; ++e)
+            put_queue_entry<kQueueOrder>(fo.queue_order, (uint32_t)k * 2u * tv.slots + e, 0xFFFFu);
       }
       return;
     }
@@ -244,11 +250,12 @@ __device__ __noinline__ void sweep_generic_evaluation(const Scenario& s, double 
       out);
 }
 
+template <typename L>
 __global__ void __launch_bounds__(kBlock)
 sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
              unsigned policy_mask, int n_pol, double* __restrict__ t_done, Workspace w,
              bool have_ws) {
-  __shared__ uint32_t lds_block[kLaneWords * kBlock];
+  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
   if (e >= total) return;
@@ -272,16 +279,16 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
 
   const double chunk = S / (double)s.C;
   FastScenario fs;
-  if (fast_eligible(s, chunk, fs)) {
+  if (fast_eligible(s, chunk, L::kCap, fs)) {
     LaneLds lds;
     lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
     double load[kMaxDims];
     plan_fast(s, fs, themis_on, rel, th, load,
-              [&](uint32_t c, uint32_t code) { lds.init_chunk(c, code); });
+              [&](uint32_t c, uint32_t code) { L::init_chunk(lds, c, code); });
     FastOut fo;
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;
-    FastResult r = simulate_fast<kNoQueueOrder, false>(s, fs, scf, lds, fo);
+    FastResult r = simulate_fast<L, kNoQueueOrder, false>(s, fs, scf, lds, fo);
     if (r.ok) { t_done[e] = r.t_done; return; }
   }
   if (!have_ws) { t_done[e] = nan64(); return; }
@@ -321,6 +328,35 @@ static int check_batch(const themis_batch_t* b, bool need_intra, bool need_inter
 
 static int launch_status() {
   return hipGetLastError() == hipSuccess ? THEMIS_OK : THEMIS_ERR_DEVICE;
+}
+
+using SimKernel = void (*)(themis_batch_t, const uint8_t*, double*, void*, int, double*, Workspace,
+                           bool);
+
+template <typename L>
+static SimKernel pick_mode(int mode, bool busy) {
+  constexpr bool small = L::kCap == 64u;
+  switch (mode) {
+    case kNoQueueOrder:
+      return busy ? simulate_kernel<L, kNoQueueOrder, true> : simulate_kernel<L, kNoQueueOrder, false>;
+    case kBytes:
+      return busy ? simulate_kernel<L, kBytes, true> : simulate_kernel<L, kBytes, false>;
+    case kWords:
+      if (!small) return nullptr;
+      return busy ? simulate_kernel<L, small ? kWords : kBytes, true>
+                  : simulate_kernel<L, small ? kWords : kBytes, false>;
+    case kShorts:
+      if (small) return nullptr;
+      return busy ? simulate_kernel<L, small ? kBytes : kShorts, true>
+                  : simulate_kernel<L, small ? kBytes : kShorts, false>;
+  }
+  return nullptr;
+}
+
+static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy) {
+  if (cap == 64u) return pick_mode<Layout64>(mode, busy);
+  if (cap == 128u) return pick_mode<LayoutWide<128>>(mode, busy);
+  return pick_mode<LayoutWide<512>>(mode, busy);
 }
 
 static unsigned blocks_for(uint64_t items) { return (unsigned)((items + kBlock - 1) / kBlock); }
@@ -376,15 +412,18 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   Workspace w = carve_workspace(workspace, batch->n, tv.slots);
   const int entry_bytes =
       themis_queue_entry_bytes(batch->max_chunks, tv.on ? batch->max_coll : 0u);
-  // dword-buffered queue-order stores need 4-byte aligned rows of 2*slots bytes
+  // 8-bit entries of the 64-chunk layout are stored four at a time when the
+  // rows (2*slots bytes each) start on 4-byte boundaries
   const bool words = entry_bytes == 1 && (tv.slots & 1u) == 0u &&
                      ((uintptr_t)queue_order & 3u) == 0u;
-  auto kernel =
-      !queue_order ? (busy ? simulate_kernel<kNoQueueOrder, true> : simulate_kernel<kNoQueueOrder, false>)
-      : words      ? (busy ? simulate_kernel<kWords, true> : simulate_kernel<kWords, false>)
-                   : (busy ? simulate_kernel<kBytes, true> : simulate_kernel<kBytes, false>);
-  hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0, (hipStream_t)stream,
-                     *batch, orders, t_done, queue_order, entry_bytes, busy, w, have_ws);
+  const int mode64 = !queue_order ? kNoQueueOrder : (words ? kWords : kBytes);
+  const int modew = !queue_order ? kNoQueueOrder : (entry_bytes == 2 ? kShorts : kBytes);
+  const uint32_t cap = (tv.on || batch->max_chunks > 128u) ? 512u : batch->max_chunks > 64u ? 128u : 64u;
+  SimKernel kernel = pick_simulate_kernel(cap, cap == 64u ? mode64 : modew, busy != nullptr);
+  if (!kernel) return THEMIS_ERR_DEVICE;
+  hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+                     (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
+                     w, have_ws);
   return launch_status();
 }
 
@@ -404,7 +443,10 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   const bool have_ws = workspace != nullptr &&
                        workspace_bytes_given >= workspace_bytes(evals, batch->max_chunks);
   Workspace w = carve_workspace(workspace, evals, batch->max_chunks);
-  hipLaunchKernelGGL(sweep_kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
+  const uint32_t cap = batch->max_chunks > 128u ? 512u : batch->max_chunks > 64u ? 128u : 64u;
+  auto kernel = cap == 64u ? sweep_kernel<Layout64>
+              : cap == 128u ? sweep_kernel<LayoutWide<128>> : sweep_kernel<LayoutWide<512>>;
+  hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                      n_pol, t_done, w, have_ws);
   return launch_status();

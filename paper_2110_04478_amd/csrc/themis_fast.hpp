@@ -28,28 +28,86 @@
 
 namespace themis {
 
-constexpr int kFastCap = 64;      // chunks per evaluation the LDS layout holds
-// Per-lane LDS, in dwords:
-//   0..63   one dword per chunk c AND per list q (both run 0..63):
-//             byte 0  chunk c: reduced-dims mask | phase << 4
-//             byte 1  chunk c: next chunk in its list (0xFF = last)
-//             byte 2  chunk c: order code
-//             byte 3  list q = 16*dim + class: head chunk
-//   64..79  u8 tail[64]: last chunk of list q
-constexpr int kTailDword = 64;
-constexpr int kLaneWords = 80;
-constexpr int kFastLdsBytes = kLaneWords * 64 * 4;  // per wavefront
-constexpr uint32_t kEndOfList = 0xffu;
-
 struct LaneLds {
   uint8_t* base;  // LDS block of the wavefront + 4*lane
   // byte address of dword d of this lane (transposed layout: 256 B apart)
   __device__ __forceinline__ uint8_t* dword(uint32_t d) const { return base + (d << 8); }
-  __device__ __forceinline__ uint8_t* tail(uint32_t q) const {
-    return base + (kTailDword << 8) + ((q >> 2) << 8) + (q & 3u);
+};
+
+// Four small per-dimension counters / ids packed in one register (pair).
+template <typename Word, int kBits>
+struct Pack4 {
+  Word v = 0;
+  static constexpr Word kMask = (Word(1) << kBits) - 1;
+  __device__ __forceinline__ uint32_t get(uint32_t k) const { return (uint32_t)((v >> (kBits * k)) & kMask); }
+  __device__ __forceinline__ void set(uint32_t k, uint32_t x) {
+    v = (v & ~(kMask << (kBits * k))) | (Word(x) << (kBits * k));
   }
-  __device__ __forceinline__ void init_chunk(uint32_t c, uint32_t code) const {
-    *(uint32_t*)dword(c) = (code << 16) | (kEndOfList << 8);  // mask 0, Reduce-Scatter phase
+  __device__ __forceinline__ void inc(uint32_t k) { v += Word(1) << (kBits * k); }
+};
+
+// Per-lane LDS layout for up to 64 chunks (80 dwords, 20 KiB per wavefront):
+//   dword c (0..63), one per chunk c AND per list q = 16*dim + class:
+//     byte 0  chunk c: reduced-dims mask | phase << 4
+//     byte 1  chunk c: next chunk in its list (0xFF = last)
+//     byte 2  chunk c: order code
+//     byte 3  list q: head chunk
+//   dwords 64..79  u8 tail[64]: last chunk of list q
+struct Layout64 {
+  static constexpr uint32_t kCap = 64;
+  static constexpr uint32_t kLaneWords = 80;
+  static constexpr uint32_t kEnd = 0xffu;
+  using Link = uint8_t;               // width of a chunk id in LDS
+  using Ids = Pack4<uint32_t, 8>;     // chunk id / operation count per dimension
+  static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code) {
+    *(uint32_t*)l.dword(c) = (code << 16) | (kEnd << 8);  // mask 0, Reduce-Scatter phase
+  }
+  static __device__ __forceinline__ uint32_t code(uint32_t w) { return (w >> 16) & 0xffu; }
+  static __device__ __forceinline__ uint32_t next(uint32_t w) { return (w >> 8) & 0xffu; }
+  static __device__ __forceinline__ uint32_t first_dim(const LaneLds& l, uint32_t c) {
+    return l.dword(c)[2] & 3u;
+  }
+  // new state of chunk c (whole dword w known), end of its list
+  static __device__ __forceinline__ void store_state(uint8_t* cp, uint32_t, uint32_t state) {
+    *(uint16_t*)cp = (uint16_t)(state | (kEnd << 8));
+  }
+  static __device__ __forceinline__ Link* next_ptr(const LaneLds& l, uint32_t c) { return l.dword(c) + 1; }
+  static __device__ __forceinline__ Link* head_ptr(const LaneLds& l, uint32_t q) { return l.dword(q) + 3; }
+  static __device__ __forceinline__ Link* tail_ptr(const LaneLds& l, uint32_t q) {
+    return l.base + ((64u + (q >> 2)) << 8) + (q & 3u);
+  }
+};
+
+// Layout for up to kChunks <= 512 chunks (kChunks + 64 dwords per lane):
+//   dword c: byte 0 mask | phase << 4, byte 1 order code, bytes 2-3 next
+//            chunk (0xFFFF = last)
+//   then u16 head[64] (32 dwords) and u16 tail[64] (32 dwords)
+template <uint32_t kChunks>
+struct LayoutWide {
+  static constexpr uint32_t kCap = kChunks;
+  static constexpr uint32_t kLaneWords = kChunks + 64;
+  static constexpr uint32_t kEnd = 0xffffu;
+  using Link = uint16_t;
+  using Ids = Pack4<uint64_t, 16>;
+  static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code) {
+    *(uint32_t*)l.dword(c) = (code << 8) | (kEnd << 16);
+  }
+  static __device__ __forceinline__ uint32_t code(uint32_t w) { return (w >> 8) & 0xffu; }
+  static __device__ __forceinline__ uint32_t next(uint32_t w) { return w >> 16; }
+  static __device__ __forceinline__ uint32_t first_dim(const LaneLds& l, uint32_t c) {
+    return l.dword(c)[1] & 3u;
+  }
+  static __device__ __forceinline__ void store_state(uint8_t* cp, uint32_t w, uint32_t state) {
+    *(uint32_t*)cp = state | (w & 0xff00u) | (kEnd << 16);
+  }
+  static __device__ __forceinline__ Link* next_ptr(const LaneLds& l, uint32_t c) {
+    return (Link*)(l.dword(c) + 2);
+  }
+  static __device__ __forceinline__ Link* head_ptr(const LaneLds& l, uint32_t q) {
+    return (Link*)(l.base + ((kChunks + (q >> 1)) << 8) + 2u * (q & 1u));
+  }
+  static __device__ __forceinline__ Link* tail_ptr(const LaneLds& l, uint32_t q) {
+    return (Link*)(l.base + ((kChunks + 32u + (q >> 1)) << 8) + 2u * (q & 1u));
   }
 };
 
@@ -63,8 +121,9 @@ struct FastScenario {
 __device__ __forceinline__ bool is_pow2(uint32_t p) { return (p & (p - 1u)) == 0u; }
 
 // Can this scenario take the fast path?  Fills fs when it can.
-__device__ __forceinline__ bool fast_eligible(const Scenario& s, double chunk, FastScenario& fs) {
-  bool ok = s.valid && s.C <= (uint32_t)kFastCap;
+__device__ __forceinline__ bool fast_eligible(const Scenario& s, double chunk, uint32_t cap,
+                                              FastScenario& fs) {
+  bool ok = s.valid && s.C <= cap;
   uint32_t ep = 0, et = 0;
 #pragma unroll
   for (int k = 0; k < kMaxDims; ++k) {
@@ -163,15 +222,15 @@ __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario&
 // Queue simulation.
 // ---------------------------------------------------------------------------
 struct FastOut {
-  uint8_t* queue_order;  // this evaluation's [4][2*slots] bytes, or null
+  uint8_t* queue_order;  // this evaluation's [4][2*slots] entries, or null
   uint32_t slots;
 };
 
 struct FastResult {
   double t_done;
   double busy[kMaxDims];
-  uint32_t executed;  // per-dimension operation counts, one byte each
-  bool ok;            // false: leave the answer to the generic path
+  uint32_t executed[kMaxDims];  // operations each dimension ran
+  bool ok;                      // false: leave the answer to the generic path
 };
 
 // Class (rank of the resident size) of every mask, 4 bits each: the number of
@@ -201,17 +260,19 @@ __device__ __forceinline__ double min_f64(double a, double b) {
 }
 
 // How the per-dimension queue orders leave the kernel.  Every lane appends
-// bytes to its own four rows, so stores never coalesce across lanes; kWords
-// collects four entries per dimension in a register and stores them as one
-// aligned dword (a quarter of the memory transactions), and needs rows that
-// start on a 4-byte boundary (an even number of slots).
-enum QueueOrderMode { kNoQueueOrder = 0, kBytes = 1, kWords = 2 };
+// entries to its own four rows, so stores never coalesce across lanes.
+// kBytes / kShorts store each 8- / 16-bit entry as it is produced; kWords
+// (8-bit entries) collects four entries per dimension in a register and
+// stores them as one aligned dword (a quarter of the memory transactions),
+// and needs rows that start on a 4-byte boundary (an even number of slots).
+enum QueueOrderMode { kNoQueueOrder = 0, kBytes = 1, kWords = 2, kShorts = 3 };
 
-// Chunk dwords must already be initialised with LaneLds::init_chunk().
-template <int kQueueOrder, bool kBusy>
+// Chunk dwords must already be initialised with L::init_chunk().
+template <typename L, int kQueueOrder, bool kBusy>
 __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const FastScenario& fs,
                                                     bool scf, const LaneLds& lds,
                                                     const FastOut& out) {
+  using Link = typename L::Link;
   const uint32_t D = (uint32_t)s.D;
   const uint32_t C = s.C;
   const uint32_t full = (1u << D) - 1u;
@@ -220,13 +281,13 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
 
   double f0 = kInf, f1 = kInf, f2 = kInf, f3 = kInf;  // finish time, +inf = idle
   double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
-  uint32_t serving = 0;   // chunk id per dimension, one byte each
-  uint32_t executed = 0;  // operations started per dimension, one byte each
+  typename L::Ids serving;   // chunk id per dimension
+  typename L::Ids executed;  // operations started per dimension
   uint64_t nonempty = 0;  // bit q = 16*dim + class: list q holds chunks
   uint32_t work = 0;      // bit k: some list of dimension k holds chunks
   uint32_t idle = full;   // bit k: dimension k serves nothing
   bool stalled = false;   // a stage did not advance time: generic path decides
-  uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0;  // last four queue entries per dimension
+  uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0;  // kWords: last four queue entries per dimension
   const uint32_t row_len = 2u * out.slots;
 
   // append chunk c to list q (branch-free: an empty list takes c as its head,
@@ -234,18 +295,18 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
   auto push = [&](uint32_t q, uint32_t c) {
     uint64_t bit = 1ull << q;
     bool had = (nonempty & bit) != 0ull;
-    uint8_t* tp = lds.tail(q);
+    Link* tp = L::tail_ptr(lds, q);
     uint32_t t = *tp;
-    uint8_t* dst = had ? lds.dword(t) + 1 : lds.dword(q) + 3;
-    *dst = (uint8_t)c;
-    *tp = (uint8_t)c;
+    Link* dst = had ? L::next_ptr(lds, t) : L::head_ptr(lds, q);
+    *dst = (Link)c;
+    *tp = (Link)c;
     nonempty |= bit;
     work |= 1u << (q >> 4);
   };
 
   // a6: every chunk waits at the dimension of its first stage, resident size
   // = chunk (mask 0, the lowest class), in chunk-id order
-  for (uint32_t c = 0; c < C; ++c) push(16u * (lds.dword(c)[2] & 3u), c);
+  for (uint32_t c = 0; c < C; ++c) push(16u * L::first_dim(lds, c), c);
 
   double now = 0.0;
   const uint32_t max_steps = 2u * D * C + 8u;
@@ -256,12 +317,12 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
       const uint32_t field = (uint32_t)(nonempty >> (16u * k)) & 0xffffu;
       const uint32_t cls = 31u - (uint32_t)__clz((int)field);  // smallest resident size
       const uint32_t q = 16u * k + cls;
-      uint8_t* hp = lds.dword(q) + 3;
+      Link* hp = L::head_ptr(lds, q);
       const uint32_t h = *hp;
       const uint32_t w = *(const uint32_t*)lds.dword(h);
-      const uint32_t nx = (w >> 8) & 0xffu;
-      *hp = (uint8_t)nx;  // harmless when the list is now empty
-      const bool emptied = nx == kEndOfList;
+      const uint32_t nx = L::next(w);
+      *hp = (Link)nx;  // harmless when the list is now empty
+      const bool emptied = nx == L::kEnd;
       nonempty &= ~(emptied ? (1ull << q) : 0ull);
       const bool no_work = (field & ~((emptied ? 1u : 0u) << cls)) == 0u;
       work &= ~((no_work ? 1u : 0u) << k);
@@ -283,14 +344,15 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
         z0 = k0 ? z0 + t : z0; z1 = k1 ? z1 + t : z1;
         z2 = k2 ? z2 + t : z2; z3 = k3 ? z3 + t : z3;
       }
-      const uint32_t sh = 8u * k;
-      serving = (serving & ~(0xffu << sh)) | (h << sh);
+      serving.set(k, h);
       if (kQueueOrder != kNoQueueOrder) {
-        const uint32_t pos = (executed >> sh) & 0xffu;
+        const uint32_t pos = executed.get(k);
         const uint32_t entry = (h << 1) | phase;
         // pos < row_len always holds for a consistent plan; it keeps the store in bounds
         if (kQueueOrder == kBytes) {
           if (pos < row_len) out.queue_order[k * row_len + pos] = (uint8_t)entry;
+        } else if (kQueueOrder == kShorts) {
+          if (pos < row_len) ((uint16_t*)out.queue_order)[k * row_len + pos] = (uint16_t)entry;
         } else {
           // shift the entry in from the top: after four entries the register
           // holds them in memory (little-endian) order
@@ -300,7 +362,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
             *(uint32_t*)(out.queue_order + k * row_len + (pos & ~3u)) = a;
         }
       }
-      executed += 1u << sh;
+      executed.inc(k);
     }
 
     // a8: advance to the earliest completion
@@ -316,18 +378,18 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
     do {
       uint32_t k = (uint32_t)__builtin_ctz(done);
       if (done & (done - 1u)) {
-        uint32_t best = 0xffffu;
+        uint32_t best = 0xffffffffu;
 #pragma unroll
         for (uint32_t kk = 0; kk < (uint32_t)kMaxDims; ++kk) {
-          uint32_t id = (serving >> (8u * kk)) & 0xffu;
+          uint32_t id = serving.get(kk);
           if ((done >> kk & 1u) && id < best) { best = id; k = kk; }
         }
       }
       done &= ~(1u << k);
-      const uint32_t c = (serving >> (8u * k)) & 0xffu;
+      const uint32_t c = serving.get(k);
       uint8_t* cp = lds.dword(c);
       const uint32_t w = *(const uint32_t*)cp;
-      const uint32_t code = (w >> 16) & 0xffu;
+      const uint32_t code = L::code(w);
       uint32_t phase = (w >> 4) & 1u;
       // a Reduce-Scatter sets the dimension's bit, an All-Gather clears it
       const uint32_t mask = (w & 15u) ^ (1u << k);
@@ -337,7 +399,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
         // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
         const uint32_t pos = (uint32_t)__builtin_popcount(mask) - phase;
         const uint32_t kn = (code >> (2u * pos)) & 3u;
-        *(uint16_t*)cp = (uint16_t)(mask | (phase << 4) | (kEndOfList << 8));
+        L::store_state(cp, w, mask | (phase << 4));
         const uint32_t cls = (uint32_t)(ranktab >> (4u * mask)) & 15u;
         push(16u * kn + cls, c);
       }
@@ -349,7 +411,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
     const uint32_t acc[kMaxDims] = {a0, a1, a2, a3};
 #pragma unroll
     for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) {
-      const uint32_t n = (executed >> (8u * k)) & 0xffu;
+      const uint32_t n = executed.get(k);
       const uint32_t rem = n & 3u;
       for (uint32_t j = 0; j < rem; ++j) {
         const uint32_t pos = n - rem + j;
@@ -363,7 +425,8 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
   res.ok = !stalled;
   res.t_done = now;
   res.busy[0] = z0; res.busy[1] = z1; res.busy[2] = z2; res.busy[3] = z3;
-  res.executed = executed;
+#pragma unroll
+  for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) res.executed[k] = executed.get(k);
   return res;
 }
 

@@ -105,9 +105,14 @@ def test_non_power_of_two_npus(gpu, oracle):
 
 
 def test_large_chunk_counts(gpu, oracle):
-    """C up to 512: 16-bit queue entries."""
+    """C up to 512: the wide LDS layouts, 8- and 16-bit queue entries, odd
+    row lengths."""
     check_batch(gpu, oracle, w().mixed(96, seed=5, max_chunks=512), threads=8)
     check_batch(gpu, oracle, w().config4(n=70))
+    check_batch(gpu, oracle, w().mixed(200, seed=6, max_chunks=100))
+    check_batch(gpu, oracle, w().mixed(200, seed=7, max_chunks=128))
+    check_batch(gpu, oracle, w().mixed(200, seed=8, max_chunks=127))
+    check_batch(gpu, oracle, w().mixed(200, seed=9, max_chunks=63))
 
 
 def test_empty_batch(gpu):
