@@ -33,6 +33,15 @@ def algorithmic_lane_ops(D, C):
     return {"plan": 45 * C, "simulate": 2 * D * C * C}
 
 
+# Copied from profiles/simulate_kernel_config3.md (rocprofv3 --pmc runs of this
+# file on the default workload); not measured live.  Only attached to the JSON
+# line when the run uses that workload.
+PROFILED = {
+    "traffic_bytes_per_launch": 4.89e9,   # FETCH_SIZE x2.0 + WRITE_SIZE x1.0, simulate kernel
+    "valu_issue_frac": 0.777,             # SQ_ACTIVE_INST_VALU / (256 CUs x busy cycles)
+}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,6 +53,9 @@ def main():
                     help="scenarios the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-queue-order", action="store_true",
                     help="do not request the per-dimension queue orders")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run a plain device copy of MIB MiB "
+                         "(known traffic, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build evaluates one GPU's share on one GPU; "
@@ -55,6 +67,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        src = torch.full((args.copy_probe << 20,), 7, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": src.numel(), "copy_probe_bytes_written": dst.numel()}))
+        return
     n = args.scenarios
     host = workloads.config3(n=n)
     D, C = 4, 64
@@ -96,6 +117,7 @@ def main():
     sim_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     ms_per_step = wall * 1e3 / args.steps
 
+    default_workload = n == (1 << 20) and qo is not None
     ops = algorithmic_lane_ops(D, C)
     achieved = ops["simulate"] * n / (sim_ms * 1e-3)
     result = {
@@ -116,10 +138,24 @@ def main():
             "bound": "alu", "kernel": "simulate",
             "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS_PER_S / 1e12,
             "unit": "Tlane-op/s", "frac": achieved / PEAK_LANE_OPS_PER_S,
-            "traffic": None,
+            "traffic": PROFILED["traffic_bytes_per_launch"] if default_workload else None,
             "algorithmic_lane_ops_per_scenario": ops["simulate"],
+            "valu_issue_frac_rocprof": PROFILED["valu_issue_frac"] if default_workload else None,
         },
     }
+
+    # the fused sweep entry point on the same batch (times only), for reference
+    thr = torch.full((1,), 1.0 / 16.0, dtype=torch.float64, device="cuda:0")
+    sw_out = torch.empty((n, 1, 1), dtype=torch.float64, device="cuda:0")
+    binding.themis_sweep(d, thr, workloads.SWEEP_THEMIS_SCF, t_done=sw_out)
+    torch.cuda.synchronize()
+    s0 = time.perf_counter()
+    for _ in range(args.steps):
+        binding.themis_sweep(d, thr, workloads.SWEEP_THEMIS_SCF, t_done=sw_out)
+    torch.cuda.synchronize()
+    sweep_ms = (time.perf_counter() - s0) * 1e3 / args.steps
+    result["sweep_times_only"] = {"ms": sweep_ms, "evaluations_per_sec": n / (sweep_ms * 1e-3),
+                                  "events_per_sec": n * 2 * D * C / (sweep_ms * 1e-3)}
 
     if args.cpu_sample > 0:
         from oracle import themis_oracle
