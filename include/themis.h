@@ -139,14 +139,21 @@ const char *themis_status_string(int status);
 int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
 
 /*
- * Bytes of scratch that themis_simulate_batch / themis_sweep may need for the
- * scenarios their fast path does not cover (any P_k that is not a power of
- * two, or a size whose halvings would leave the normal binary64 range).
+ * Bytes of scratch that themis_simulate_batch / themis_sweep may need:
+ *   - single collectives with power-of-two NPU counts and sizes whose
+ *     halvings stay in the normal binary64 range run entirely in registers
+ *     and LDS and need no workspace;
+ *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace;
+ *   - everything else (an NPU count that is not a power of two, extreme
+ *     magnitudes, staggered release times) runs on a generic path with
+ *     per-chunk state in the workspace.
+ * For themis_sweep pass n * n_thr * n_pol as n and max_coll = 0.
  * Passing a smaller or NULL workspace is allowed: every scenario that would
  * have needed it then comes back as NaN / all-ones, like an invalid one (the
  * call cannot report this through its return value, because it does not wait
- * for the device).  The workspace must stay untouched until the stream has
- * drained, and two calls in flight at once need a workspace each.
+ * for the device).  The workspace must be 16-byte aligned, must stay untouched
+ * until the stream has drained, and two calls in flight at once need a
+ * workspace each.
  */
 size_t themis_workspace_bytes(uint64_t n, uint32_t max_chunks, uint32_t max_coll);
 

@@ -5,6 +5,7 @@
 #include "themis_device.hpp"
 #include "themis_fast.hpp"
 #include "themis_generic.hpp"
+#include "themis_trace.hpp"
 
 namespace themis {
 
@@ -228,6 +229,83 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 }
 
 // ---------------------------------------------------------------------------
+// themis_simulate_batch for traces (several collectives sharing the queues):
+// the ranked-list path of themis_trace.hpp, else the generic path.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
+                      double* __restrict__ t_done, void* __restrict__ queue_order,
+                      int entry_bytes, double* __restrict__ busy, Workspace w, bool have_ws,
+                      uint8_t* __restrict__ trace_area, TraceLayout tl) {
+  __shared__ uint32_t lds_block[kTraceLdsWords * kBlock];
+  uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= b.n) return;
+  const TraceView tv = trace_view(b);
+  Scenario s = load_scenario(b, i);
+  const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
+  uint32_t Q;
+  bool ok = collectives_ok(b, tv, i, Q) && s.valid;
+
+  SimOut out;
+  out.t_done = t_done + i;
+  out.busy = busy ? busy + i : nullptr;
+  out.busy_stride = b.n;
+  out.entry_bytes = entry_bytes;
+  out.slots = tv.slots;
+  out.queue_order = queue_order
+      ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
+      : nullptr;
+  if (!ok) { write_invalid(out); return; }
+
+  const uint8_t* row = orders + (size_t)i * tv.slots;
+  bool fast = trace_area != nullptr && tl.bytes != 0u && Q <= tl.Q;
+  uint32_t epack = 0;
+  if (fast) {
+    TraceRegion rg;
+    rg.base = trace_area + (size_t)i * tl.bytes;
+    rg.t = tl;
+    // every collective must be in the range where halvings are exact, and
+    // released at t = 0
+    for (uint32_t q = 0; q < Q; ++q) {
+      FastScenario fs;
+      const double chunk = collective_size(b, tv, i, q) / (double)s.C;
+      fast = fast && fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs) &&
+             collective_release(b, tv, i, q) == 0.0;
+      epack = fs.epack;
+      rg.CH(q) = chunk;
+    }
+    bool codes_ok = true;
+    if (fast) {
+      for (uint32_t q = 0; q < Q; ++q)
+        for (uint32_t c = 0; c < s.C; ++c) {
+          const uint32_t code = row[(size_t)q * b.max_chunks + c];
+          codes_ok = codes_ok && order_code_ok(code, s.D);
+          rg.W(q * s.C + c) = trace_word(code);
+        }
+      if (!codes_ok) { write_invalid(out); return; }
+      LaneLds lds;
+      lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+      double T, z[kMaxDims];
+      uint32_t ex[kMaxDims];
+      if (simulate_trace_fast(s, Q, epack, scf, rg, lds, out, busy != nullptr, T, z, ex)) {
+        t_done[i] = T;
+        if (busy) {
+#pragma unroll
+          for (int k = 0; k < kMaxDims; ++k) busy[(size_t)k * b.n + i] = z[k];
+        }
+        if (out.queue_order) {
+          for (int k = 0; k < kMaxDims; ++k)
+            for (uint32_t e = ex[k]; e < 2u * tv.slots; ++e) put_entry(out, k, e, 0xFFFFu);
+        }
+        return;
+      }
+    }
+  }
+  if (!have_ws) { write_invalid(out); return; }
+  simulate_generic_scenario(b, tv, s, Q, i, row, scf, w, out);
+}
+
+// ---------------------------------------------------------------------------
 // themis_sweep (hot-path step a10): one lane per scenario x threshold x
 // scheduler; the plan goes straight into LDS and only the time leaves.
 // ---------------------------------------------------------------------------
@@ -359,6 +437,12 @@ static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy) {
   return pick_mode<LayoutWide<512>>(mode, busy);
 }
 
+// The generic area comes first in the workspace, rounded up so that the trace
+// regions behind it stay 16-byte aligned.
+static size_t generic_area_bytes(uint64_t evals, uint64_t slots) {
+  return (workspace_bytes(evals, slots) + 15u) & ~(size_t)15u;
+}
+
 static unsigned blocks_for(uint64_t items) { return (unsigned)((items + kBlock - 1) / kBlock); }
 
 }  // namespace themis
@@ -386,7 +470,9 @@ int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll) {
 }
 
 size_t themis_workspace_bytes(uint64_t n, uint32_t max_chunks, uint32_t max_coll) {
-  return workspace_bytes(n, (uint64_t)max_chunks * (max_coll ? max_coll : 1u));
+  size_t generic = generic_area_bytes(n, (uint64_t)max_chunks * (max_coll ? max_coll : 1u));
+  size_t trace = max_coll ? (size_t)n * trace_layout(max_chunks, max_coll).bytes : 0;
+  return generic + trace;
 }
 
 int themis_plan_batch(const themis_batch_t* batch, uint8_t* orders, double* loads, void* stream) {
@@ -419,6 +505,17 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   const int mode64 = !queue_order ? kNoQueueOrder : (words ? kWords : kBytes);
   const int modew = !queue_order ? kNoQueueOrder : (entry_bytes == 2 ? kShorts : kBytes);
   const uint32_t cap = (tv.on || batch->max_chunks > 128u) ? 512u : batch->max_chunks > 64u ? 128u : 64u;
+  if (tv.on) {
+    const TraceLayout tl = trace_layout(batch->max_chunks, batch->max_coll);
+    const size_t generic = generic_area_bytes(batch->n, tv.slots);
+    const bool have_trace = workspace != nullptr && tl.bytes != 0u &&
+                            workspace_bytes_given >= generic + (size_t)batch->n * tl.bytes;
+    uint8_t* trace_area = have_trace ? (uint8_t*)workspace + generic : nullptr;
+    hipLaunchKernelGGL(simulate_trace_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
+                       busy, w, have_ws, trace_area, tl);
+    return launch_status();
+  }
   SimKernel kernel = pick_simulate_kernel(cap, cap == 64u ? mode64 : modew, busy != nullptr);
   if (!kernel) return THEMIS_ERR_DEVICE;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,

@@ -1,0 +1,282 @@
+// Scalable queue simulation for traces: several collectives of different
+// sizes sharing the per-dimension queues (one lane per scenario, state in a
+// per-scenario region of the caller's HBM workspace).
+//
+// With thousands of chunks per scenario the state no longer fits LDS, and with
+// one chunk size per collective Smallest-Chunk-First has far more than 16
+// distinct resident sizes.  The structure is the same as in the LDS fast path,
+// scaled up: every distinct resident size chunk_q * 2^-E(mask) over all
+// (collective q, reduced-dims mask) pairs gets a rank (ascending size, equal
+// sizes share a rank), every dimension owns one FIFO list per rank, and a
+// two-level bitmap per dimension finds the lowest non-empty rank.  Each
+// chunk-stage event then costs a bounded number of memory operations instead
+// of a scan over all waiting chunks.
+//
+// Covered: power-of-two NPU counts, up to kTraceMaxColl collectives, all
+// released at t = 0.  Everything else stays on the generic path.
+#pragma once
+
+#include "themis_fast.hpp"
+
+namespace themis {
+
+constexpr uint32_t kTraceMaxColl = 256;   // ranks <= 4096: 128 bitmap leaves, 4 summary words
+constexpr uint32_t kTraceLeafWords = kTraceMaxColl * 16 / 32;
+constexpr uint32_t kTraceSumWords = 4;
+constexpr uint32_t kNoChunk = 0xffffu;
+
+// Byte offsets inside one scenario's region of the workspace.
+struct TraceLayout {
+  uint32_t G;   // chunk slots (max_chunks * max_coll)
+  uint32_t Q;   // collectives the region is sized for
+  uint32_t R;   // ranks per dimension = Q * 16
+  uint32_t off_ht, off_bm, off_sum, off_sr, off_ch, off_sq;
+  uint32_t bytes;  // multiple of 16; 0 if the batch cannot use this path
+};
+
+__host__ __device__ inline TraceLayout trace_layout(uint32_t max_chunks, uint32_t max_coll) {
+  TraceLayout t;
+  t.G = max_chunks * max_coll;
+  t.Q = max_coll;
+  t.R = max_coll * 16u;
+  if (max_coll == 0u || max_coll > kTraceMaxColl) { t.bytes = 0; return t; }
+  uint32_t o = t.G * 4u;                   // W: one dword per chunk
+  t.off_ht = o;  o += 4u * t.R * 4u;       // head | tail << 16 per (dimension, rank)
+  t.off_bm = o;  o += 4u * kTraceLeafWords * 4u;
+  t.off_sum = o; o += 4u * kTraceSumWords * 4u;
+  t.off_ch = (o + 7u) & ~7u; o = t.off_ch + t.Q * 8u;   // chunk bytes per collective
+  t.off_sr = o;  o += t.R * 2u;            // size rank per (collective, mask)
+  t.off_sq = o;  o += t.Q * 2u;            // collectives sorted by chunk size
+  t.bytes = (o + 15u) & ~15u;
+  return t;
+}
+
+// One scenario's region with bounds-clamped accessors: an index that a logic
+// error pushed out of range still stays inside the region.
+struct TraceRegion {
+  uint8_t* base;
+  TraceLayout t;
+  __device__ __forceinline__ uint32_t& W(uint32_t g) const {
+    return ((uint32_t*)base)[g < t.G ? g : t.G - 1u];
+  }
+  __device__ __forceinline__ uint32_t& HT(uint32_t k, uint32_t r) const {
+    return ((uint32_t*)(base + t.off_ht))[(k & 3u) * t.R + (r < t.R ? r : t.R - 1u)];
+  }
+  __device__ __forceinline__ uint32_t& BM(uint32_t k, uint32_t leaf) const {
+    return ((uint32_t*)(base + t.off_bm))[(k & 3u) * kTraceLeafWords + (leaf & (kTraceLeafWords - 1u))];
+  }
+  __device__ __forceinline__ uint32_t& SUM(uint32_t k, uint32_t sw) const {
+    return ((uint32_t*)(base + t.off_sum))[(k & 3u) * kTraceSumWords + (sw & (kTraceSumWords - 1u))];
+  }
+  __device__ __forceinline__ double& CH(uint32_t q) const {
+    return ((double*)(base + t.off_ch))[q < t.Q ? q : t.Q - 1u];
+  }
+  __device__ __forceinline__ uint16_t& SR(uint32_t q, uint32_t mask) const {
+    return ((uint16_t*)(base + t.off_sr))[(q < t.Q ? q : t.Q - 1u) * 16u + (mask & 15u)];
+  }
+  __device__ __forceinline__ uint16_t& SQ(uint32_t j) const {
+    return ((uint16_t*)(base + t.off_sq))[j < t.Q ? j : t.Q - 1u];
+  }
+};
+
+// Chunk dword: bits 0-3 reduced-dims mask, bit 4 phase, bits 8-15 order code,
+// bits 16-31 next chunk in its list (kNoChunk = last).
+__device__ __forceinline__ uint32_t trace_word(uint32_t code) { return (code << 8) | (kNoChunk << 16); }
+
+// Ranks of all resident sizes: a merge of the 2^D sorted lists
+// { chunk_q * 2^-E(mask) : q in ascending chunk order }, one list per mask.
+// Returns the number of distinct ranks.  lds: 48 dwords of this lane.
+__device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, uint32_t D,
+                                             uint32_t epack, const LaneLds& lds) {
+  // collectives in ascending (chunk bytes, index) order: insertion sort
+  for (uint32_t a = 0; a < Q; ++a) {
+    const double key = rg.CH(a);
+    uint32_t j = a;
+    while (j > 0u) {
+      const uint32_t qp = rg.SQ(j - 1u);
+      if (!(rg.CH(qp) > key)) break;
+      rg.SQ(j) = (uint16_t)qp;
+      --j;
+    }
+    rg.SQ(j) = (uint16_t)a;
+  }
+  // merge heads in LDS: value (dwords 2m, 2m+1) and position (dword 32 + m)
+  const uint32_t nm = 1u << D;
+  const double first = rg.CH(rg.SQ(0));
+  for (uint32_t m = 0; m < 16u; ++m) {
+    const double v = m < nm ? scale_down(first, esum(epack, m)) : inf64();
+    *(uint32_t*)lds.dword(2u * m) = (uint32_t)__double2loint(v);
+    *(uint32_t*)lds.dword(2u * m + 1u) = (uint32_t)__double2hiint(v);
+    *(uint32_t*)lds.dword(32u + m) = 0u;
+  }
+  uint32_t rank = 0;
+  double prev = -1.0;
+  const uint32_t total = Q * nm;
+  for (uint32_t out = 0; out < total; ++out) {
+    uint32_t mb = 0;
+    double vb = inf64();
+    for (uint32_t m = 0; m < nm; ++m) {
+      const double v = __hiloint2double((int)*(const uint32_t*)lds.dword(2u * m + 1u),
+                                        (int)*(const uint32_t*)lds.dword(2u * m));
+      if (v < vb) { vb = v; mb = m; }
+    }
+    if (out > 0u && vb > prev) ++rank;
+    prev = vb;
+    const uint32_t p = *(const uint32_t*)lds.dword(32u + mb);
+    rg.SR(rg.SQ(p), mb) = (uint16_t)rank;
+    const uint32_t pn = p + 1u;
+    const double vn = pn < Q ? scale_down(rg.CH(rg.SQ(pn)), esum(epack, mb)) : inf64();
+    *(uint32_t*)lds.dword(2u * mb) = (uint32_t)__double2loint(vn);
+    *(uint32_t*)lds.dword(2u * mb + 1u) = (uint32_t)__double2hiint(vn);
+    *(uint32_t*)lds.dword(32u + mb) = pn;
+  }
+  return rank + 1u;
+}
+
+constexpr uint32_t kTraceLdsWords = 48;  // per lane, for trace_build_ranks
+
+// Runs the simulation of one trace.  The region must hold CH[q] (chunk bytes
+// of every collective) and W[g] = trace_word(code) for g = q*C + i.
+// Returns false if time failed to advance somewhere (generic path decides).
+__device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
+                                           bool scf, const TraceRegion& rg, const LaneLds& lds,
+                                           const SimOut& out, bool want_busy, double& t_done,
+                                           double (&busy)[kMaxDims],
+                                           uint32_t (&executed_out)[kMaxDims]) {
+  const uint32_t D = (uint32_t)s.D;
+  const uint32_t C = s.C;
+  const uint32_t G = Q * C;
+  const uint32_t full = (1u << D) - 1u;
+  const double kInf = inf64();
+
+  if (scf) trace_build_ranks(rg, Q, D, epack, lds);
+  for (uint32_t k = 0; k < 4u; ++k) {
+    for (uint32_t l = 0; l < kTraceLeafWords; ++l) rg.BM(k, l) = 0u;
+    for (uint32_t l = 0; l < kTraceSumWords; ++l) rg.SUM(k, l) = 0u;
+  }
+
+  double f[kMaxDims] = {kInf, kInf, kInf, kInf};
+  double z[kMaxDims] = {0.0, 0.0, 0.0, 0.0};
+  uint32_t serving[kMaxDims] = {0u, 0u, 0u, 0u};
+  uint32_t executed[kMaxDims] = {0u, 0u, 0u, 0u};
+  uint32_t waiting[kMaxDims] = {0u, 0u, 0u, 0u};
+  bool stalled = false;
+
+  auto rank_of = [&](uint32_t g, uint32_t mask) -> uint32_t {
+    return scf ? (uint32_t)rg.SR(g / C, mask) : 0u;
+  };
+  auto push = [&](uint32_t k, uint32_t r, uint32_t g) {
+    const uint32_t leaf = r >> 5, bit = 1u << (r & 31u);
+    const uint32_t lw = rg.BM(k, leaf);
+    if (lw & bit) {
+      const uint32_t ht = rg.HT(k, r);
+      const uint32_t tl = ht >> 16;
+      rg.W(tl) = (rg.W(tl) & 0xffffu) | (g << 16);
+      rg.HT(k, r) = (ht & 0xffffu) | (g << 16);
+    } else {
+      rg.HT(k, r) = g | (g << 16);
+      rg.BM(k, leaf) = lw | bit;
+      rg.SUM(k, leaf >> 5) |= 1u << (leaf & 31u);
+    }
+#pragma unroll
+    for (uint32_t kk = 0; kk < 4u; ++kk) waiting[kk] += (kk == k) ? 1u : 0u;
+  };
+  // first chunk of the lowest non-empty rank (smallest resident size)
+  auto pop = [&](uint32_t k) -> uint32_t {
+    uint32_t leaf = 0;
+    for (uint32_t sw = 0; sw < kTraceSumWords; ++sw) {
+      const uint32_t v = rg.SUM(k, sw);
+      if (v) { leaf = sw * 32u + (uint32_t)__builtin_ctz(v); break; }
+    }
+    const uint32_t lw = rg.BM(k, leaf);
+    const uint32_t r = leaf * 32u + (lw ? (uint32_t)__builtin_ctz(lw) : 0u);
+    const uint32_t ht = rg.HT(k, r);
+    const uint32_t h = ht & 0xffffu, tl = ht >> 16;
+    if (h == tl) {
+      const uint32_t nlw = lw & ~(1u << (r & 31u));
+      rg.BM(k, leaf) = nlw;
+      if (!nlw) rg.SUM(k, leaf >> 5) &= ~(1u << (leaf & 31u));
+    } else {
+      rg.HT(k, r) = (rg.W(h) >> 16) | (tl << 16);
+    }
+#pragma unroll
+    for (uint32_t kk = 0; kk < 4u; ++kk) waiting[kk] -= (kk == k) ? 1u : 0u;
+    return h;
+  };
+
+  // a6: every chunk waits at the dimension of its first stage (mask 0)
+  for (uint32_t g = 0; g < G; ++g) push((rg.W(g) >> 8) & 3u, rank_of(g, 0u), g);
+
+  double now = 0.0;
+  const uint64_t max_steps = (uint64_t)2u * D * G + 8u;
+  for (uint64_t step = 0; step <= max_steps; ++step) {
+    // a7: every idle dimension with waiting chunks starts its first one
+    for (;;) {
+      uint32_t need = 0;
+#pragma unroll
+      for (uint32_t kk = 0; kk < 4u; ++kk) need |= (f[kk] == kInf && waiting[kk] != 0u) ? (1u << kk) : 0u;
+      if (!need) break;
+      const uint32_t k = (uint32_t)__builtin_ctz(need);
+      const uint32_t h = pop(k);
+      const uint32_t w = rg.W(h);
+      const uint32_t mask = w & 15u, phase = (w >> 4) & 1u;
+      const uint32_t ek = (epack >> (8u * k)) & 0xffu;
+      const uint32_t E = esum(epack, mask) - (phase ? ek : 0u);
+      const double t = scale_down(rg.CH(h / C), E) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+      const double fin = now + t;
+      stalled |= !(fin > now);
+      uint32_t pos = 0;
+#pragma unroll
+      for (uint32_t kk = 0; kk < 4u; ++kk) {
+        if (kk == k) {
+          f[kk] = fin;
+          z[kk] = z[kk] + t;
+          serving[kk] = h;
+          pos = executed[kk];
+          executed[kk] = pos + 1u;
+        }
+      }
+      if (out.queue_order && pos < 2u * out.slots) put_entry(out, (int)k, pos, (h << 1) | phase);
+    }
+    if (stalled) break;
+
+    // a8: advance to the earliest completion
+    const double next = min_f64(min_f64(f[0], f[1]), min_f64(f[2], f[3]));
+    if (!(next < kInf)) break;
+    now = next;
+    uint32_t done = 0;
+#pragma unroll
+    for (uint32_t kk = 0; kk < 4u; ++kk) {
+      if (f[kk] == now) { done |= 1u << kk; f[kk] = kInf; }
+    }
+    // deliver all completions of this instant, lowest chunk id first
+    do {
+      uint32_t k = 0, best = 0xffffffffu;
+#pragma unroll
+      for (uint32_t kk = 0; kk < 4u; ++kk)
+        if ((done >> kk & 1u) && serving[kk] < best) { best = serving[kk]; k = kk; }
+      done &= ~(1u << k);
+      const uint32_t g = best;
+      const uint32_t w = rg.W(g);
+      const uint32_t code = (w >> 8) & 0xffu;
+      uint32_t phase = (w >> 4) & 1u;
+      const uint32_t mask = (w & 15u) ^ (1u << k);
+      const bool finished = phase != 0u && mask == 0u;
+      phase |= (mask == full) ? 1u : 0u;
+      if (!finished) {
+        const uint32_t p = (uint32_t)__builtin_popcount(mask) - phase;
+        const uint32_t kn = (code >> ((2u * p) & 31u)) & 3u;
+        rg.W(g) = mask | (phase << 4) | (code << 8) | (kNoChunk << 16);
+        push(kn, rank_of(g, mask), g);
+      }
+    } while (done);
+  }
+
+  t_done = now;
+#pragma unroll
+  for (uint32_t kk = 0; kk < 4u; ++kk) { busy[kk] = z[kk]; executed_out[kk] = executed[kk]; }
+  (void)want_busy;
+  return !stalled;
+}
+
+}  // namespace themis

@@ -180,6 +180,51 @@ def test_trace_of_collectives_sharing_queues(gpu, oracle):
     check_batch(gpu, oracle, b)
 
 
+def _add_trace(b, rng, max_coll, pow2_sizes):
+    """Turn a single-collective batch into a trace batch (in place)."""
+    b.max_coll = max_coll
+    b.n_coll = rng.integers(1, max_coll + 1, b.n).astype(np.uint32)
+    if pow2_sizes:  # sizes a power of two apart: equal resident sizes across collectives
+        base = b.size_bytes[None, :]
+        b.coll_size = np.ascontiguousarray(base * 2.0 ** rng.integers(-3, 4, (max_coll, b.n)))
+    else:
+        b.coll_size = np.ascontiguousarray(np.floor(rng.uniform(2 ** 16, 2 ** 28, (max_coll, b.n))))
+    b.release_time = None
+    return b
+
+
+def test_traces_ranked_list_path(gpu, oracle):
+    """Traces released at t = 0 with power-of-two NPU counts take the ranked
+    list path: ragged D, C, collective counts, both policies, equal resident
+    sizes across collectives, and more collectives than the small tests."""
+    rng = np.random.default_rng(5)
+    b = _add_trace(w().mixed(200, seed=41, max_chunks=12), rng, 9, pow2_sizes=True)
+    check_batch(gpu, oracle, b)
+    b = _add_trace(w().mixed(130, seed=42, max_chunks=8), rng, 20, pow2_sizes=False)
+    check_batch(gpu, oracle, b)
+    b = w().config5(n=64, n_coll=24)
+    b.intra_policy[::2] = 0           # half FIFO
+    check_batch(gpu, oracle, b)
+    # non-power-of-two NPU counts in a trace stay on the generic path
+    b = _add_trace(w().mixed(100, seed=43, max_chunks=8, pow2=False), rng, 5, pow2_sizes=False)
+    check_batch(gpu, oracle, b)
+
+
+def test_trace_with_generic_only_workspace(gpu, oracle):
+    """A workspace that only covers the generic area still gives exact results."""
+    import torch
+    b = w().config5(n=70, n_coll=4)
+    d = gpu.to_device(b)
+    orders, _ = gpu.themis_plan_batch(d)
+    ws = gpu.alloc_workspace(d.n * d.slots * 20)
+    t, qo, busy = gpu.themis_simulate_batch(d, orders, workspace=ws)
+    torch.cuda.synchronize()
+    o_orders, _ = oracle.plan_batch(b, threads=8)
+    o_t, o_qo, o_busy = oracle.simulate_batch(b, o_orders, threads=8)
+    assert_close("t_done", t.cpu().numpy(), o_t)
+    assert np.array_equal(widen_queue(qo), o_qo)
+
+
 def test_sweep_matches_oracle(gpu, oracle):
     import torch
     W = w()
