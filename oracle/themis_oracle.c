@@ -45,7 +45,18 @@ void to_latency_coef(int ndims, const uint32_t *npus, const double *bw,
   }
 }
 
+
 static int finite_positive(double v) { return isfinite(v) && v > 0.0; }
+
+/* Fixed per-stage delays (A_K = steps * step latency, Sec. 4.5) are optional;
+ * when given they must be finite and not negative. */
+int to_fixed_delay_valid(int ndims, const double *fixed_delay)
+{
+  if (!fixed_delay) return 1;
+  for (int k = 0; k < ndims && k < TO_MAX_DIMS; ++k)
+    if (!(isfinite(fixed_delay[k]) && fixed_delay[k] >= 0.0)) return 0;
+  return 1;
+}
 
 /* A scenario is valid when the network and the collective make sense. */
 int to_network_valid(int ndims, const uint32_t *npus, const double *bw)
@@ -91,11 +102,12 @@ static uint8_t encode_order(int ndims, const int *dims)
  * Returns 1 on success, 0 if the inputs are invalid (nothing written).       */
 /* ------------------------------------------------------------------------ */
 int to_plan(int ndims, const uint32_t *npus, const double *bw,
-            double size_bytes, uint32_t C, int inter_policy,
-            int threshold_mode, double threshold, uint8_t *orders,
-            double *loads, double *stage_time)
+            const double *fixed_delay, double size_bytes, uint32_t C,
+            int inter_policy, int threshold_mode, double threshold,
+            uint8_t *orders, double *loads, double *stage_time)
 {
   if (!to_network_valid(ndims, npus, bw)) return 0;
+  if (!to_fixed_delay_valid(ndims, fixed_delay)) return 0;
   if (!finite_positive(size_bytes) || C < 1u) return 0;
   if (!(threshold >= 0.0)) return 0; /* also rejects NaN */
   if (threshold_mode == TO_THR_REL && !isfinite(threshold)) return 0;
@@ -106,8 +118,12 @@ int to_plan(int ndims, const uint32_t *npus, const double *bw,
   /* Splitter: equal chunks (Alg. 1 line 3). */
   double chunk = size_bytes / (double)C;
 
-  /* Dim Load Tracker reset: A_K = 0 (Alg. 1 line 2, Sec. 4.5). */
+  /* Dim Load Tracker reset to the fixed delay A_K of the collective type on
+   * each dimension (Alg. 1 line 2, Sec. 4.5): an All-Reduce pays the per-stage
+   * delay once for its Reduce-Scatter and once for its All-Gather. */
   double load[TO_MAX_DIMS] = {0.0, 0.0, 0.0, 0.0};
+  if (fixed_delay)
+    for (int k = 0; k < ndims; ++k) load[k] = fixed_delay[k] + fixed_delay[k];
 
   for (uint32_t i = 0; i < C; ++i) {
     /* Scheduler.Schedule: current loads, their min and max (line 18-19). */
@@ -165,6 +181,8 @@ int to_plan(int ndims, const uint32_t *npus, const double *bw,
  *   queue_order[4][2G] : (may be NULL) per dimension, the executed operations
  *                        (g << 1 | phase) in execution order
  *   busy[4]            : (may be NULL) total service time per dimension
+ * fixed_delay[4] (may be NULL) is added to every stage's time on that
+ * dimension (Sec. 4.5: A_K + N_K * B_K + idle_K).
  * Returns 1 on success, 0 on invalid input.                                  */
 /* ------------------------------------------------------------------------ */
 typedef struct {
@@ -196,12 +214,13 @@ static int goes_first(int intra_policy, const to_chunk *a, uint32_t ga,
 }
 
 int to_simulate(int ndims, const uint32_t *npus, const double *bw,
-                uint32_t n_coll, const double *coll_size,
+                const double *fixed_delay, uint32_t n_coll, const double *coll_size,
                 const double *release, uint32_t C, int intra_policy,
                 const uint8_t *orders, double *t_done, double *coll_done,
                 uint32_t *queue_order, double *busy)
 {
   if (!to_network_valid(ndims, npus, bw)) return 0;
+  if (!to_fixed_delay_valid(ndims, fixed_delay)) return 0;
   if (n_coll < 1u || C < 1u) return 0;
   for (uint32_t q = 0; q < n_coll; ++q) {
     if (!finite_positive(coll_size[q])) return 0;
@@ -260,8 +279,10 @@ int to_simulate(int ndims, const uint32_t *npus, const double *bw,
       to_chunk *c = &ch[best];
       c->running = 1;
       serving[k] = best;
-      finish[k] = now + c->t[k];
-      busy_acc[k] = busy_acc[k] + c->t[k];
+      /* stage time = fixed delay of one stage on k + bytes * per-byte latency */
+      double service = fixed_delay ? fixed_delay[k] + c->t[k] : c->t[k];
+      finish[k] = now + service;
+      busy_acc[k] = busy_acc[k] + service;
       if (queue_order) {
         uint32_t phase = (c->stage >= ndims) ? 1u : 0u;
         queue_order[(size_t)k * 2u * G + executed[k]] = ((uint32_t)best << 1) | phase;
@@ -320,6 +341,15 @@ static void gather_network(uint64_t n, uint64_t i, const uint32_t *npus,
   }
 }
 
+/* fixed_delay is [4][n] or NULL; returns a pointer to f[4] or NULL */
+static const double *gather_fixed(uint64_t n, uint64_t i,
+                                  const double *fixed_delay, double *f)
+{
+  if (!fixed_delay) return NULL;
+  for (int k = 0; k < TO_MAX_DIMS; ++k) f[k] = fixed_delay[(size_t)k * n + i];
+  return f;
+}
+
 /* orders: [n][slots] with slots = max_chunks * max(1,max_coll); loads [4][n]
  * (may be NULL).  n_coll/coll_size NULL = one collective of size_bytes[i]. */
 void to_plan_batch(uint64_t n, uint64_t begin, uint64_t end,
@@ -327,16 +357,17 @@ void to_plan_batch(uint64_t n, uint64_t begin, uint64_t end,
                    const uint8_t *ndims, const uint32_t *npus,
                    const double *bw, const double *size_bytes,
                    const uint32_t *chunks, const uint8_t *inter_policy,
-                   const double *threshold, uint32_t max_coll,
-                   const uint32_t *n_coll, const double *coll_size,
-                   uint8_t *orders, double *loads)
+                   const double *threshold, const double *fixed_delay,
+                   uint32_t max_coll, const uint32_t *n_coll,
+                   const double *coll_size, uint8_t *orders, double *loads)
 {
   uint32_t mc = (n_coll && max_coll > 0u) ? max_coll : 1u;
   size_t slots = (size_t)max_chunks * mc;
   for (uint64_t i = begin; i < end; ++i) {
     uint32_t p[TO_MAX_DIMS];
-    double b[TO_MAX_DIMS], ld[TO_MAX_DIMS] = {0, 0, 0, 0};
+    double b[TO_MAX_DIMS], ld[TO_MAX_DIMS] = {0, 0, 0, 0}, fx[TO_MAX_DIMS];
     gather_network(n, i, npus, bw, p, b);
+    const double *fixed = gather_fixed(n, i, fixed_delay, fx);
     uint8_t *row = orders + (size_t)i * slots;
     memset(row, 0xFF, slots);
     uint32_t C = chunks[i];
@@ -344,7 +375,7 @@ void to_plan_batch(uint64_t n, uint64_t begin, uint64_t end,
     int ok = (C >= 1u && C <= max_chunks && Q >= 1u && Q <= mc);
     for (uint32_t q = 0; ok && q < Q; ++q) {
       double S = n_coll ? coll_size[(size_t)q * n + i] : size_bytes[i];
-      ok = to_plan((int)ndims[i], p, b, S, C, (int)inter_policy[i],
+      ok = to_plan((int)ndims[i], p, b, fixed, S, C, (int)inter_policy[i],
                    threshold_mode, threshold[i],
                    row + (size_t)q * max_chunks, ld, NULL);
     }
@@ -363,9 +394,10 @@ void to_simulate_batch(uint64_t n, uint64_t begin, uint64_t end,
                        uint32_t max_chunks, const uint8_t *ndims,
                        const uint32_t *npus, const double *bw,
                        const double *size_bytes, const uint32_t *chunks,
-                       const uint8_t *intra_policy, uint32_t max_coll,
-                       const uint32_t *n_coll, const double *coll_size,
-                       const double *release_time, const uint8_t *orders,
+                       const uint8_t *intra_policy, const double *fixed_delay,
+                       uint32_t max_coll, const uint32_t *n_coll,
+                       const double *coll_size, const double *release_time,
+                       const uint8_t *orders,
                        double *t_done, uint16_t *queue_order, double *busy)
 {
   uint32_t mc = (n_coll && max_coll > 0u) ? max_coll : 1u;
@@ -377,8 +409,9 @@ void to_simulate_batch(uint64_t n, uint64_t begin, uint64_t end,
   uint8_t *od = (uint8_t *)malloc(slots);
   for (uint64_t i = begin; i < end; ++i) {
     uint32_t p[TO_MAX_DIMS];
-    double b[TO_MAX_DIMS], bz[TO_MAX_DIMS] = {0, 0, 0, 0};
+    double b[TO_MAX_DIMS], bz[TO_MAX_DIMS] = {0, 0, 0, 0}, fx[TO_MAX_DIMS];
     gather_network(n, i, npus, bw, p, b);
+    const double *fixed = gather_fixed(n, i, fixed_delay, fx);
     uint32_t C = chunks[i];
     uint32_t Q = n_coll ? n_coll[i] : 1u;
     int D = (int)ndims[i];
@@ -392,8 +425,8 @@ void to_simulate_batch(uint64_t n, uint64_t begin, uint64_t end,
         memcpy(od + (size_t)q * C,
                orders + (size_t)i * slots + (size_t)q * max_chunks, C);
       }
-      ok = to_simulate(D, p, b, Q, cs, rl, C, (int)intra_policy[i], od, &T,
-                       NULL, qo, bz);
+      ok = to_simulate(D, p, b, fixed, Q, cs, rl, C, (int)intra_policy[i], od,
+                       &T, NULL, qo, bz);
     }
     if (!ok) {
       T = NAN;
@@ -423,16 +456,18 @@ void to_simulate_batch(uint64_t n, uint64_t begin, uint64_t end,
 void to_sweep(uint64_t n, uint64_t begin, uint64_t end, uint32_t max_chunks,
               int threshold_mode, const uint8_t *ndims, const uint32_t *npus,
               const double *bw, const double *size_bytes,
-              const uint32_t *chunks, int n_thr, const double *thr,
-              int thr_per_scenario, unsigned policy_mask, double *t_done)
+              const uint32_t *chunks, const double *fixed_delay, int n_thr,
+              const double *thr, int thr_per_scenario, unsigned policy_mask,
+              double *t_done)
 {
   int n_pol = 0;
   for (int bit = 0; bit < 3; ++bit) if (policy_mask & (1u << bit)) ++n_pol;
   uint8_t *od = (uint8_t *)malloc(max_chunks);
   for (uint64_t i = begin; i < end; ++i) {
     uint32_t p[TO_MAX_DIMS];
-    double b[TO_MAX_DIMS], ld[TO_MAX_DIMS];
+    double b[TO_MAX_DIMS], ld[TO_MAX_DIMS], fx[TO_MAX_DIMS];
     gather_network(n, i, npus, bw, p, b);
+    const double *fixed = gather_fixed(n, i, fixed_delay, fx);
     uint32_t C = chunks[i];
     for (int a = 0; a < n_thr; ++a) {
       double th = thr_per_scenario ? thr[(size_t)a * n + i] : thr[a];
@@ -444,12 +479,12 @@ void to_sweep(uint64_t n, uint64_t begin, uint64_t end, uint32_t max_chunks,
         double T = NAN;
         int ok = (C >= 1u && C <= max_chunks);
         if (ok)
-          ok = to_plan((int)ndims[i], p, b, size_bytes[i], C, inter,
+          ok = to_plan((int)ndims[i], p, b, fixed, size_bytes[i], C, inter,
                        threshold_mode, th, od, ld, NULL);
         if (ok) {
           double S = size_bytes[i];
-          ok = to_simulate((int)ndims[i], p, b, 1u, &S, NULL, C, intra, od,
-                           &T, NULL, NULL, NULL);
+          ok = to_simulate((int)ndims[i], p, b, fixed, 1u, &S, NULL, C, intra,
+                           od, &T, NULL, NULL, NULL);
         }
         if (!ok) T = NAN;
         t_done[((size_t)i * n_thr + a) * n_pol + col] = T;
@@ -458,4 +493,50 @@ void to_sweep(uint64_t n, uint64_t begin, uint64_t end, uint32_t max_chunks,
     }
   }
   free(od);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Derived quantities of the paper's evaluation.
+ *   utilization : average bandwidth utilisation (Sec. 3): the utilisation of
+ *                 every dimension, N_K / (T * BW_K) with N_K = transfer_K *
+ *                 BW_K the bytes it moved, weighted by its bandwidth:
+ *                 sum_K transfer_K * BW_K / (T * sum_K BW_K)
+ *   ideal       : Table 3 "Ideal": collective size / total bandwidth
+ * transfer[4] are the seconds each dimension spent moving bytes (the
+ * bandwidth part of its load).                                              */
+/* ------------------------------------------------------------------------ */
+void to_metrics(int ndims, const double *bw, double total_bytes, double t_done,
+                const double *transfer, double *utilization, double *ideal)
+{
+  double num = 0.0, den = 0.0;
+  for (int k = 0; k < ndims; ++k) {
+    num = num + transfer[k] * bw[k];
+    den = den + bw[k];
+  }
+  *utilization = num / (t_done * den);
+  *ideal = total_bytes / den;
+}
+
+/* t_done [n], transfer [4][n] -> utilization [n], ideal [n] */
+void to_metrics_batch(uint64_t n, uint64_t begin, uint64_t end,
+                      const uint8_t *ndims, const double *bw,
+                      const double *size_bytes, uint32_t max_coll,
+                      const uint32_t *n_coll, const double *coll_size,
+                      const double *t_done, const double *transfer,
+                      double *utilization, double *ideal)
+{
+  (void)max_coll;
+  for (uint64_t i = begin; i < end; ++i) {
+    double b[TO_MAX_DIMS], tr[TO_MAX_DIMS];
+    for (int k = 0; k < TO_MAX_DIMS; ++k) {
+      b[k] = bw[(size_t)k * n + i];
+      tr[k] = transfer[(size_t)k * n + i];
+    }
+    double total = 0.0;
+    if (n_coll) for (uint32_t q = 0; q < n_coll[i]; ++q) total = total + coll_size[(size_t)q * n + i];
+    else total = size_bytes[i];
+    int D = (int)ndims[i];
+    if (D < 1 || D > TO_MAX_DIMS) { utilization[i] = NAN; ideal[i] = NAN; continue; }
+    to_metrics(D, b, total, t_done[i], tr, &utilization[i], &ideal[i]);
+  }
 }

@@ -28,27 +28,31 @@ def lib():
     if _lib is None:
         L = C.CDLL(_build.build())
         L.to_plan.restype = C.c_int
-        L.to_plan.argtypes = [C.c_int, _u32p, _f64p, C.c_double, C.c_uint32,
+        L.to_plan.argtypes = [C.c_int, _u32p, _f64p, _f64p, C.c_double, C.c_uint32,
                               C.c_int, C.c_int, C.c_double, _u8p, _f64p, _f64p]
         L.to_simulate.restype = C.c_int
-        L.to_simulate.argtypes = [C.c_int, _u32p, _f64p, C.c_uint32, _f64p,
+        L.to_simulate.argtypes = [C.c_int, _u32p, _f64p, _f64p, C.c_uint32, _f64p,
                                   _f64p, C.c_uint32, C.c_int, _u8p, _f64p,
                                   _f64p, _u32p, _f64p]
         L.to_plan_batch.restype = None
         L.to_plan_batch.argtypes = [
             C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, C.c_int, _u8p,
-            _u32p, _f64p, _f64p, _u32p, _u8p, _f64p, C.c_uint32, _u32p, _f64p,
-            _u8p, _f64p]
+            _u32p, _f64p, _f64p, _u32p, _u8p, _f64p, _f64p, C.c_uint32, _u32p,
+            _f64p, _u8p, _f64p]
         L.to_simulate_batch.restype = None
         L.to_simulate_batch.argtypes = [
             C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, _u8p, _u32p,
-            _f64p, _f64p, _u32p, _u8p, C.c_uint32, _u32p, _f64p, _f64p, _u8p,
-            _f64p, _u16p, _f64p]
+            _f64p, _f64p, _u32p, _u8p, _f64p, C.c_uint32, _u32p, _f64p, _f64p,
+            _u8p, _f64p, _u16p, _f64p]
         L.to_sweep.restype = None
         L.to_sweep.argtypes = [
             C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, C.c_int, _u8p,
-            _u32p, _f64p, _f64p, _u32p, C.c_int, _f64p, C.c_int, C.c_uint,
+            _u32p, _f64p, _f64p, _u32p, _f64p, C.c_int, _f64p, C.c_int, C.c_uint,
             _f64p]
+        L.to_metrics_batch.restype = None
+        L.to_metrics_batch.argtypes = [
+            C.c_uint64, C.c_uint64, C.c_uint64, _u8p, _f64p, _f64p, C.c_uint32,
+            _u32p, _f64p, _f64p, _f64p, _f64p, _f64p]
         L.to_latency_coef.restype = None
         L.to_latency_coef.argtypes = [C.c_int, _u32p, _f64p, _f64p]
         _lib = L
@@ -90,8 +94,16 @@ def latency_coef(npus, bw):
     return out
 
 
+def _fixed4(fixed_delay, D):
+    if fixed_delay is None:
+        return None
+    f = np.zeros(4)
+    f[:D] = fixed_delay
+    return f
+
+
 def plan(npus, bw, size_bytes, chunks, inter_policy=1, threshold_mode=0,
-         threshold=0.0):
+         threshold=0.0, fixed_delay=None):
     """Alg. 1 for one collective.  Returns (orders u8[C], loads f64[4],
     stage_time f64[C,4]) or None if the inputs are invalid."""
     D = len(npus)
@@ -100,14 +112,16 @@ def plan(npus, bw, size_bytes, chunks, inter_policy=1, threshold_mode=0,
     orders = np.zeros(chunks, np.uint8)
     loads = np.zeros(4)
     st = np.zeros((chunks, 4))
-    ok = lib().to_plan(D, _p(P, _u32p), _p(B, _f64p), float(size_bytes),
+    fx = _fixed4(fixed_delay, D)
+    ok = lib().to_plan(D, _p(P, _u32p), _p(B, _f64p), _p(fx, _f64p), float(size_bytes),
                        int(chunks), int(inter_policy), int(threshold_mode),
                        float(threshold), _p(orders, _u8p), _p(loads, _f64p),
                        _p(st, _f64p))
     return (orders, loads, st) if ok else None
 
 
-def simulate(npus, bw, coll_sizes, chunks, intra_policy, orders, release=None):
+def simulate(npus, bw, coll_sizes, chunks, intra_policy, orders, release=None,
+             fixed_delay=None):
     """Queue simulation of one scenario (one or several collectives).
     Returns dict(t_done, coll_done, queue_order[D][2G], busy[4]) or None."""
     D = len(npus)
@@ -123,7 +137,8 @@ def simulate(npus, bw, coll_sizes, chunks, intra_policy, orders, release=None):
     cd = np.zeros(Q)
     qo = np.zeros((4, 2 * G), np.uint32)
     busy = np.zeros(4)
-    ok = lib().to_simulate(D, _p(P, _u32p), _p(B, _f64p), Q, _p(cs, _f64p),
+    fx = _fixed4(fixed_delay, D)
+    ok = lib().to_simulate(D, _p(P, _u32p), _p(B, _f64p), _p(fx, _f64p), Q, _p(cs, _f64p),
                            _p(rl, _f64p), int(chunks), int(intra_policy),
                            _p(od, _u8p), C.byref(t), _p(cd, _f64p),
                            _p(qo, _u32p), _p(busy, _f64p))
@@ -133,6 +148,11 @@ def simulate(npus, bw, coll_sizes, chunks, intra_policy, orders, release=None):
 
 
 # -- batches ------------------------------------------------------------------
+def _fixed(b):
+    f = getattr(b, "fixed_delay", None)
+    return None if f is None else _arr(f, np.float64)
+
+
 def _trace(b):
     if getattr(b, "n_coll", None) is None:
         return 0, None, None, None
@@ -152,14 +172,15 @@ def plan_batch(b, threads=1):
              chunks=_arr(b.chunks, np.uint32),
              inter=_arr(b.inter_policy, np.uint8),
              thr=_arr(b.threshold, np.float64))
+    fx = _fixed(b)
 
     def run(lo, hi):
         lib().to_plan_batch(
             b.n, lo, hi, b.max_chunks, b.threshold_mode, _p(a["ndims"], _u8p),
             _p(a["npus"], _u32p), _p(a["bw"], _f64p), _p(a["size"], _f64p),
             _p(a["chunks"], _u32p), _p(a["inter"], _u8p), _p(a["thr"], _f64p),
-            mc, _p(ncoll, _u32p), _p(csize, _f64p), _p(orders, _u8p),
-            _p(loads, _f64p))
+            _p(fx, _f64p), mc, _p(ncoll, _u32p), _p(csize, _f64p),
+            _p(orders, _u8p), _p(loads, _f64p))
     _fan_out(run, b.n, threads)
     return orders, loads
 
@@ -177,12 +198,13 @@ def simulate_batch(b, orders, want_queue_order=True, threads=1):
              bw=_arr(b.bw, np.float64), size=_arr(b.size_bytes, np.float64),
              chunks=_arr(b.chunks, np.uint32),
              intra=_arr(b.intra_policy, np.uint8))
+    fx = _fixed(b)
 
     def run(lo, hi):
         lib().to_simulate_batch(
             b.n, lo, hi, b.max_chunks, _p(a["ndims"], _u8p),
             _p(a["npus"], _u32p), _p(a["bw"], _f64p), _p(a["size"], _f64p),
-            _p(a["chunks"], _u32p), _p(a["intra"], _u8p), mc,
+            _p(a["chunks"], _u32p), _p(a["intra"], _u8p), _p(fx, _f64p), mc,
             _p(ncoll, _u32p), _p(csize, _f64p), _p(rel, _f64p), _p(od, _u8p),
             _p(t, _f64p), _p(qo, _u16p), _p(busy, _f64p))
     _fan_out(run, b.n, threads)
@@ -198,12 +220,30 @@ def sweep(b, thr, policy_mask, thr_per_scenario=False, threads=1):
     a = dict(ndims=_arr(b.ndims, np.uint8), npus=_arr(b.npus, np.uint32),
              bw=_arr(b.bw, np.float64), size=_arr(b.size_bytes, np.float64),
              chunks=_arr(b.chunks, np.uint32))
+    fx = _fixed(b)
 
     def run(lo, hi):
         lib().to_sweep(
             b.n, lo, hi, b.max_chunks, b.threshold_mode, _p(a["ndims"], _u8p),
             _p(a["npus"], _u32p), _p(a["bw"], _f64p), _p(a["size"], _f64p),
-            _p(a["chunks"], _u32p), n_thr, _p(thr, _f64p),
+            _p(a["chunks"], _u32p), _p(fx, _f64p), n_thr, _p(thr, _f64p),
             1 if thr_per_scenario else 0, policy_mask, _p(out, _f64p))
     _fan_out(run, b.n, threads)
     return out
+
+
+def metrics_batch(b, t_done, transfer, threads=1):
+    """Average bandwidth utilisation and the Ideal time -> (util f64[n], ideal f64[n])."""
+    mc, ncoll, csize, _ = _trace(b)
+    t = _arr(t_done, np.float64)
+    tr = _arr(transfer, np.float64)
+    util = np.empty(b.n)
+    ideal = np.empty(b.n)
+    nd, bw, sz = _arr(b.ndims, np.uint8), _arr(b.bw, np.float64), _arr(b.size_bytes, np.float64)
+
+    def run(lo, hi):
+        lib().to_metrics_batch(b.n, lo, hi, _p(nd, _u8p), _p(bw, _f64p), _p(sz, _f64p), mc,
+                               _p(ncoll, _u32p), _p(csize, _f64p), _p(t, _f64p), _p(tr, _f64p),
+                               _p(util, _f64p), _p(ideal, _f64p))
+    _fan_out(run, b.n, threads)
+    return util, ideal

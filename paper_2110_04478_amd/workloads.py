@@ -47,6 +47,7 @@ class ScenarioBatch:
     n_coll: Optional[np.ndarray] = None        # u32 [n]
     coll_size: Optional[np.ndarray] = None     # f64 [max_coll, n]
     release_time: Optional[np.ndarray] = None  # f64 [max_coll, n]
+    fixed_delay: Optional[np.ndarray] = None   # f64 [4, n] seconds per stage, or None
 
     @property
     def slots(self) -> int:
@@ -70,12 +71,14 @@ class ScenarioBatch:
             threshold=self.threshold[idx].copy(),
             max_coll=self.max_coll,
             n_coll=None if self.n_coll is None else self.n_coll[idx].copy(),
-            coll_size=opt(self.coll_size), release_time=opt(self.release_time))
+            coll_size=opt(self.coll_size), release_time=opt(self.release_time),
+            fixed_delay=opt(self.fixed_delay))
 
 
 def make_batch(ndims, npus, bw, size_bytes, chunks, inter_policy, intra_policy,
                threshold, threshold_mode=THR_ABS, max_chunks=None,
-               n_coll=None, coll_size=None, release_time=None) -> ScenarioBatch:
+               n_coll=None, coll_size=None, release_time=None,
+               fixed_delay=None) -> ScenarioBatch:
     """Build a batch from per-scenario sequences; npus/bw are [n][<=4]."""
     ndims = np.asarray(ndims, dtype=np.uint8).reshape(-1)
     n = ndims.shape[0]
@@ -106,7 +109,19 @@ def make_batch(ndims, npus, bw, size_bytes, chunks, inter_policy, intra_policy,
         chunks=chunks, inter_policy=bc(inter_policy, np.uint8),
         intra_policy=bc(intra_policy, np.uint8),
         threshold=bc(threshold, np.float64), max_coll=mc, n_coll=n_coll,
-        coll_size=coll_size, release_time=release_time)
+        coll_size=coll_size, release_time=release_time,
+        fixed_delay=_fixed_rows(fixed_delay, n))
+
+
+def _fixed_rows(fixed_delay, n):
+    """[n][<=4] per-stage delays -> f64 [4, n] (missing dimensions 0)."""
+    if fixed_delay is None:
+        return None
+    F = np.zeros((MAX_DIMS, n))
+    for i in range(n):
+        row = list(fixed_delay[i])
+        F[:len(row), i] = row
+    return F
 
 
 # --------------------------------------------------------------------------
@@ -274,3 +289,47 @@ def mixed(n: int, seed: int = SEED_BASE + 99, max_chunks: int = 64,
         n=n, max_chunks=max_chunks, threshold_mode=thr_mode, ndims=D, npus=P,
         bw=B, size_bytes=S, chunks=C, inter_policy=inter, intra_policy=intra,
         threshold=thr)
+
+
+# --------------------------------------------------------------------------
+# the six 1024-NPU platforms of the paper's Table 2
+# --------------------------------------------------------------------------
+# name, sizes, per-dimension topology, aggregate bandwidth per NPU (Gb/s),
+# step latency (ns).  R = ring, F = fully connected, S = switch.
+TABLE2 = (
+    ("2D-SW_SW", (16, 64), "SS", (1200, 800), (700, 1700)),
+    ("3D-SW_SW_SW_homo", (16, 8, 8), "SSS", (800, 800, 800), (700, 700, 1700)),
+    ("3D-SW_SW_SW_hetero", (16, 8, 8), "SSS", (1600, 800, 400), (700, 700, 1700)),
+    ("3D-FC_Ring_SW", (8, 16, 8), "FRS", (1400, 800, 400), (700, 700, 1700)),
+    ("4D-Ring_SW_SW_SW", (4, 4, 8, 8), "RSSS", (2000, 1600, 800, 400), (20, 700, 700, 1700)),
+    ("4D-Ring_FC_Ring_SW", (4, 8, 4, 8), "RFRS", (3000, 1400, 1200, 800), (20, 700, 700, 1700)),
+)
+
+
+def stage_steps(topology: str, p: int) -> int:
+    """Steps of one Reduce-Scatter (or All-Gather) stage of the topology-aware
+    algorithm of the paper's Table 1: ring P-1 (so a ring All-Reduce takes
+    2P-2, Sec. 4.5), direct on a fully connected dimension 1, halving-doubling
+    on a switch log2 P."""
+    if topology == "R":
+        return p - 1
+    if topology == "F":
+        return 1
+    if topology == "S":
+        return int(p).bit_length() - 1
+    raise ValueError(topology)
+
+
+def table2(sizes_bytes=(100e6, 250e6, 500e6, 1000e6), chunks=64, inter=INTER_THEMIS,
+           intra=INTRA_SCF, threshold=1 / 16, with_latency=True) -> ScenarioBatch:
+    """One scenario per (Table 2 topology, All-Reduce size); fixed per-stage
+    delay = steps x step latency when with_latency."""
+    rows = [(t, s) for t in TABLE2 for s in sizes_bytes]
+    fixed = None
+    if with_latency:
+        fixed = [[stage_steps(k, p) * lat * 1e-9 for k, p, lat in zip(t[2], t[1], t[4])]
+                 for t, _ in rows]
+    return make_batch(
+        [len(t[1]) for t, _ in rows], [t[1] for t, _ in rows],
+        [[g * 1e9 / 8 for g in t[3]] for t, _ in rows], [s for _, s in rows], chunks,
+        inter, intra, threshold, THR_REL, fixed_delay=fixed)

@@ -29,7 +29,7 @@ def exact_stage_times(npus, bw, chunk, dims):
 
 
 def rebuild_and_check(npus, bw, coll_sizes, C, intra_policy, orders,
-                      queue_order, release=None):
+                      queue_order, release=None, fixed_delay=None):
     """Returns (T, busy[D]) as Fractions after asserting the schedule is a
     valid execution under the policy.  queue_order[k] lists (g<<1|phase)."""
     D = len(npus)
@@ -42,6 +42,8 @@ def rebuild_and_check(npus, bw, coll_sizes, C, intra_policy, orders,
         dims = order_dims(int(orders[g]), D)
         assert sorted(dims) == list(range(D))
         rs, xD = exact_stage_times(npus, bw, Fraction(coll_sizes[q]) / C, dims)
+        if fixed_delay is not None:  # A_K of Sec. 4.5: a fixed delay per stage on that dimension
+            rs = [(t + Fraction(fixed_delay[k]), x) for (t, x), k in zip(rs, dims)]
         st = [(dims[j], 0, rs[j][0], rs[j][1]) for j in range(D)]
         y = xD
         for j in reversed(range(D)):
