@@ -115,6 +115,13 @@ typedef struct themis_batch {
   const uint32_t *n_coll;     /* [n]            1..max_coll                    */
   const double *coll_size;    /* [max_coll][n]                                 */
   const double *release_time; /* [max_coll][n]  >= 0, or NULL                  */
+  /* Optional fixed delay A_K (Sec. 4.5: number of steps of the dimension's
+   * basic algorithm x step latency), in seconds per Reduce-Scatter or
+   * All-Gather stage on dimension k; NULL = 0.  The load tracker of Alg. 1
+   * then starts at fixed_delay[k] + fixed_delay[k] (one All-Reduce = one
+   * stage of each kind per dimension), and every stage on k takes
+   * fixed_delay[k] + bytes * per-byte latency in the simulation. */
+  const double *fixed_delay;  /* [4][n] >= 0 and finite, or NULL               */
 } themis_batch_t;
 
 /* Library version as major*10000 + minor*100 + patch. */
@@ -222,6 +229,23 @@ int themis_simulate_batch(const themis_batch_t *batch, const uint8_t *orders,
 int themis_sweep(const themis_batch_t *batch, int n_thr, const double *thr,
                  int thr_per_scenario, unsigned policy_mask, double *t_done,
                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * themis_metrics_batch -- the derived quantities of the paper's evaluation.
+ *
+ *   utilization[i] = sum_k transfer[k][i] * bw[k][i] / (t_done[i] * sum_k bw[k][i])
+ *       the average bandwidth utilisation of Sec. 3: each dimension's
+ *       utilisation (bytes it moved / (T * its bandwidth)) weighted by its
+ *       bandwidth.  transfer is the time each dimension spent moving bytes:
+ *       themis_plan_batch's loads or themis_simulate_batch's busy (minus the
+ *       fixed delays, if any were given).
+ *   ideal[i]       = total collective bytes / sum_k bw[k][i]   (Table 3 "Ideal")
+ * Sums run over k = 0..D-1 in ascending order.  Either output may be NULL.
+ * Invalid scenarios (ndims outside 1..4) give NaN.
+ */
+int themis_metrics_batch(const themis_batch_t *batch, const double *t_done,
+                         const double *transfer, double *utilization,
+                         double *ideal, void *stream);
 
 #ifdef __cplusplus
 }

@@ -29,6 +29,7 @@ class _Batch(C.Structure):
         ("ndims", _vp), ("npus", _vp), ("bw", _vp), ("size_bytes", _vp), ("chunks", _vp),
         ("inter_policy", _vp), ("intra_policy", _vp), ("threshold", _vp),
         ("max_coll", C.c_uint32), ("n_coll", _vp), ("coll_size", _vp), ("release_time", _vp),
+        ("fixed_delay", _vp),
     ]
 
 
@@ -56,6 +57,8 @@ def lib():
         L.themis_simulate_batch.restype = C.c_int
         L.themis_simulate_batch.argtypes = [C.POINTER(_Batch), _vp, _vp, _vp, _vp, _vp,
                                             C.c_size_t, _vp]
+        L.themis_metrics_batch.restype = C.c_int
+        L.themis_metrics_batch.argtypes = [C.POINTER(_Batch), _vp, _vp, _vp, _vp, _vp]
         L.themis_sweep.restype = C.c_int
         L.themis_sweep.argtypes = [C.POINTER(_Batch), C.c_int, _vp, C.c_int, C.c_uint, _vp,
                                    _vp, C.c_size_t, _vp]
@@ -100,6 +103,7 @@ class DeviceBatch:
     n_coll: Optional[torch.Tensor] = None
     coll_size: Optional[torch.Tensor] = None
     release_time: Optional[torch.Tensor] = None
+    fixed_delay: Optional[torch.Tensor] = None
 
     @property
     def slots(self) -> int:
@@ -114,7 +118,7 @@ class DeviceBatch:
                       _ptr(self.npus), _ptr(self.bw), _ptr(self.size_bytes), _ptr(self.chunks),
                       _ptr(self.inter_policy), _ptr(self.intra_policy), _ptr(self.threshold),
                       self.max_coll, _ptr(self.n_coll), _ptr(self.coll_size),
-                      _ptr(self.release_time))
+                      _ptr(self.release_time), _ptr(self.fixed_delay))
 
 
 def to_device(b, device="cuda:0") -> DeviceBatch:
@@ -133,7 +137,8 @@ def to_device(b, device="cuda:0") -> DeviceBatch:
         inter_policy=up(b.inter_policy, torch.uint8), intra_policy=up(b.intra_policy, torch.uint8),
         threshold=up(b.threshold, torch.float64), max_coll=int(b.max_coll),
         n_coll=up(b.n_coll, torch.uint32), coll_size=up(b.coll_size, torch.float64),
-        release_time=up(b.release_time, torch.float64))
+        release_time=up(b.release_time, torch.float64),
+        fixed_delay=up(getattr(b, "fixed_delay", None), torch.float64))
 
 
 def themis_version() -> int:
@@ -197,6 +202,20 @@ def themis_sweep(b: DeviceBatch, thr: torch.Tensor, policy_mask: int,
     _check(lib().themis_sweep(C.byref(s), n_thr, _ptr(thr), 1 if thr_per_scenario else 0,
                               policy_mask, _ptr(t_done), _ptr(workspace), ws_bytes, _stream()))
     return t_done
+
+
+def themis_metrics_batch(b: DeviceBatch, t_done: torch.Tensor, transfer: torch.Tensor,
+                         utilization: Optional[torch.Tensor] = None,
+                         ideal: Optional[torch.Tensor] = None):
+    """Average bandwidth utilisation and Ideal time -> (utilization f64[n], ideal f64[n])."""
+    if utilization is None:
+        utilization = torch.empty(b.n, dtype=torch.float64, device=b.device)
+    if ideal is None:
+        ideal = torch.empty(b.n, dtype=torch.float64, device=b.device)
+    s = b.c_struct()
+    _check(lib().themis_metrics_batch(C.byref(s), _ptr(t_done), _ptr(transfer), _ptr(utilization),
+                                      _ptr(ideal), _stream()))
+    return utilization, ideal
 
 
 def alloc_workspace(nbytes: int, device="cuda:0") -> Optional[torch.Tensor]:

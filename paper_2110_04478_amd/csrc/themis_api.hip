@@ -98,7 +98,7 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
           }
         } else {
 #pragma unroll
-          for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? 0.0 : inf64();
+          for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? s.fix[k] + s.fix[k] : inf64();
           for (uint32_t c = 0; c < s.C; ++c)
             r[c] = (uint8_t)schedule_chunk(s, chunk, themis_on, rel, thr, load);
           filled = s.C;
@@ -151,7 +151,7 @@ __device__ __forceinline__ void put_queue_entry(uint8_t* rows, uint32_t at, uint
   else rows[at] = (uint8_t)v;
 }
 
-template <typename L, int kQueueOrder, bool kBusy>
+template <typename L, int kQueueOrder, bool kBusy, bool kFix>
 __global__ void __launch_bounds__(kBlock)
 simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                 double* __restrict__ t_done, void* __restrict__ queue_order, int entry_bytes,
@@ -209,7 +209,7 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     FastOut fo;
     fo.queue_order = (uint8_t*)out.queue_order;
     fo.slots = tv.slots;
-    FastResult r = simulate_fast<L, kQueueOrder, kBusy>(s, fs, scf, lds, fo);
+    FastResult r = simulate_fast<L, kQueueOrder, kBusy, kFix>(s, fs, scf, lds, fo);
     if (r.ok) {
       t_done[i] = r.t_done;
       if (busy) {
@@ -315,7 +315,7 @@ __device__ __noinline__ void sweep_generic_evaluation(const Scenario& s, double 
                                                       const SimOut& out) {
   double load[kMaxDims];
 #pragma unroll
-  for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? 0.0 : inf64();
+  for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? s.fix[k] + s.fix[k] : inf64();
   for (uint32_t c = 0; c < s.C; ++c) {
     uint32_t code = schedule_chunk(s, chunk, themis_on, rel, th, load);
     size_t at = (size_t)c * w.stride + e;
@@ -328,7 +328,7 @@ __device__ __noinline__ void sweep_generic_evaluation(const Scenario& s, double 
       out);
 }
 
-template <typename L>
+template <typename L, bool kFix>
 __global__ void __launch_bounds__(kBlock)
 sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
              unsigned policy_mask, int n_pol, double* __restrict__ t_done, Workspace w,
@@ -366,7 +366,7 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     FastOut fo;
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;
-    FastResult r = simulate_fast<L, kNoQueueOrder, false>(s, fs, scf, lds, fo);
+    FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, fs, scf, lds, fo);
     if (r.ok) { t_done[e] = r.t_done; return; }
   }
   if (!have_ws) { t_done[e] = nan64(); return; }
@@ -378,6 +378,39 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
   out.entry_bytes = 1;
   out.slots = b.max_chunks;
   sweep_generic_evaluation(s, chunk, themis_on, rel, th, scf, e, w, out);
+}
+
+// ---------------------------------------------------------------------------
+// themis_metrics_batch: average bandwidth utilisation (Sec. 3) and Ideal
+// (Table 3) per scenario.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+metrics_kernel(themis_batch_t b, const double* __restrict__ t_done,
+               const double* __restrict__ transfer, double* __restrict__ utilization,
+               double* __restrict__ ideal) {
+  uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= b.n) return;
+  const int D = b.ndims[i];
+  double u = nan64(), id = nan64();
+  if (D >= 1 && D <= kMaxDims) {
+    double num = 0.0, den = 0.0;
+    for (int k = 0; k < D; ++k) {
+      const double bw = b.bw[(size_t)k * b.n + i];
+      num = num + transfer[(size_t)k * b.n + i] * bw;
+      den = den + bw;
+    }
+    double total = 0.0;
+    if (b.n_coll) {
+      const uint32_t Q = b.n_coll[i] <= b.max_coll ? b.n_coll[i] : b.max_coll;
+      for (uint32_t q = 0; q < Q; ++q) total = total + b.coll_size[(size_t)q * b.n + i];
+    } else {
+      total = b.size_bytes[i];
+    }
+    u = num / (t_done[i] * den);
+    id = total / den;
+  }
+  if (utilization) utilization[i] = u;
+  if (ideal) ideal[i] = id;
 }
 
 // ---------------------------------------------------------------------------
@@ -411,30 +444,28 @@ static int launch_status() {
 using SimKernel = void (*)(themis_batch_t, const uint8_t*, double*, void*, int, double*, Workspace,
                            bool);
 
+template <typename L, int kMode>
+static SimKernel pick_flags(bool busy, bool fix) {
+  return busy ? (fix ? simulate_kernel<L, kMode, true, true> : simulate_kernel<L, kMode, true, false>)
+              : (fix ? simulate_kernel<L, kMode, false, true> : simulate_kernel<L, kMode, false, false>);
+}
+
 template <typename L>
-static SimKernel pick_mode(int mode, bool busy) {
+static SimKernel pick_mode(int mode, bool busy, bool fix) {
   constexpr bool small = L::kCap == 64u;
   switch (mode) {
-    case kNoQueueOrder:
-      return busy ? simulate_kernel<L, kNoQueueOrder, true> : simulate_kernel<L, kNoQueueOrder, false>;
-    case kBytes:
-      return busy ? simulate_kernel<L, kBytes, true> : simulate_kernel<L, kBytes, false>;
-    case kWords:
-      if (!small) return nullptr;
-      return busy ? simulate_kernel<L, small ? kWords : kBytes, true>
-                  : simulate_kernel<L, small ? kWords : kBytes, false>;
-    case kShorts:
-      if (small) return nullptr;
-      return busy ? simulate_kernel<L, small ? kBytes : kShorts, true>
-                  : simulate_kernel<L, small ? kBytes : kShorts, false>;
+    case kNoQueueOrder: return pick_flags<L, kNoQueueOrder>(busy, fix);
+    case kBytes: return pick_flags<L, kBytes>(busy, fix);
+    case kWords: return small ? pick_flags<L, small ? kWords : kBytes>(busy, fix) : nullptr;
+    case kShorts: return small ? nullptr : pick_flags<L, small ? kBytes : kShorts>(busy, fix);
   }
   return nullptr;
 }
 
-static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy) {
-  if (cap == 64u) return pick_mode<Layout64>(mode, busy);
-  if (cap == 128u) return pick_mode<LayoutWide<128>>(mode, busy);
-  return pick_mode<LayoutWide<512>>(mode, busy);
+static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy, bool fix) {
+  if (cap == 64u) return pick_mode<Layout64>(mode, busy, fix);
+  if (cap == 128u) return pick_mode<LayoutWide<128>>(mode, busy, fix);
+  return pick_mode<LayoutWide<512>>(mode, busy, fix);
 }
 
 // The generic area comes first in the workspace, rounded up so that the trace
@@ -451,7 +482,7 @@ using namespace themis;
 
 extern "C" {
 
-int themis_version(void) { return 100; }
+int themis_version(void) { return 101; }
 
 const char* themis_status_string(int status) {
   switch (status) {
@@ -516,7 +547,8 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                        busy, w, have_ws, trace_area, tl);
     return launch_status();
   }
-  SimKernel kernel = pick_simulate_kernel(cap, cap == 64u ? mode64 : modew, busy != nullptr);
+  SimKernel kernel = pick_simulate_kernel(cap, cap == 64u ? mode64 : modew, busy != nullptr,
+                                          batch->fixed_delay != nullptr);
   if (!kernel) return THEMIS_ERR_DEVICE;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
@@ -541,11 +573,25 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
                        workspace_bytes_given >= workspace_bytes(evals, batch->max_chunks);
   Workspace w = carve_workspace(workspace, evals, batch->max_chunks);
   const uint32_t cap = batch->max_chunks > 128u ? 512u : batch->max_chunks > 64u ? 128u : 64u;
-  auto kernel = cap == 64u ? sweep_kernel<Layout64>
-              : cap == 128u ? sweep_kernel<LayoutWide<128>> : sweep_kernel<LayoutWide<512>>;
+  const bool fix = batch->fixed_delay != nullptr;
+  auto kernel = cap == 64u ? (fix ? sweep_kernel<Layout64, true> : sweep_kernel<Layout64, false>)
+              : cap == 128u ? (fix ? sweep_kernel<LayoutWide<128>, true> : sweep_kernel<LayoutWide<128>, false>)
+                            : (fix ? sweep_kernel<LayoutWide<512>, true> : sweep_kernel<LayoutWide<512>, false>);
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                      n_pol, t_done, w, have_ws);
+  return launch_status();
+}
+
+int themis_metrics_batch(const themis_batch_t* batch, const double* t_done, const double* transfer,
+                         double* utilization, double* ideal, void* stream) {
+  if (!batch) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (batch->n == 0) return THEMIS_OK;
+  if (!batch->ndims || !batch->bw || !t_done || !transfer) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (batch->n_coll ? !batch->coll_size : !batch->size_bytes) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (batch->n > (uint64_t)0x7fffffff * 256u) return THEMIS_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(metrics_kernel, dim3((unsigned)((batch->n + 255) / 256)), dim3(256), 0,
+                     (hipStream_t)stream, *batch, t_done, transfer, utilization, ideal);
   return launch_status();
 }
 

@@ -45,6 +45,8 @@ struct Scenario {
   uint32_t C;      // chunks per collective
   uint32_t P[kMaxDims];
   double coef[kMaxDims];  // seconds per resident byte: ((P-1)/P)/bw  (Sec. 4.5)
+  double fix[kMaxDims];   // fixed delay per stage on the dimension (A_K of Sec. 4.5), 0 if none
+  bool has_fix;           // the batch carries fixed delays
   bool valid;
 };
 
@@ -54,13 +56,16 @@ __device__ __forceinline__ Scenario load_scenario(const themis_batch_t& b, uint6
   s.D = b.ndims[i];
   s.C = b.chunks[i];
   s.valid = (s.D >= 1 && s.D <= kMaxDims) && (s.C >= 1u && s.C <= b.max_chunks);
+  s.has_fix = b.fixed_delay != nullptr;
 #pragma unroll
   for (int k = 0; k < kMaxDims; ++k) {
     uint32_t p = b.npus[(size_t)k * b.n + i];
     double bw = b.bw[(size_t)k * b.n + i];
     bool used = k < s.D;
-    if (used && !(p >= 2u && finite_positive(bw))) s.valid = false;
-    if (!used || !s.valid) { p = 2u; bw = 1.0; }
+    double fx = (s.has_fix && used) ? b.fixed_delay[(size_t)k * b.n + i] : 0.0;
+    if (used && !(p >= 2u && finite_positive(bw) && fx >= 0.0 && fx < inf64())) s.valid = false;
+    if (!used || !s.valid) { p = 2u; bw = 1.0; fx = 0.0; }
+    s.fix[k] = fx;
     s.P[k] = p;
     double pd = (double)p;
     s.coef[k] = ((double)(p - 1u) / pd) / bw;

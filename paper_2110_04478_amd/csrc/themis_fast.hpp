@@ -171,7 +171,7 @@ __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario&
   for (int k = 0; k < kMaxDims; ++k) {
     e[k] = (fs.epack >> (8 * k)) & 0xffu;
     coef[k] = (k < D) ? s.coef[k] : 0.0;   // unused dimensions: zero time, load stays +inf
-    load[k] = (k < D) ? 0.0 : inf64();
+    load[k] = (k < D) ? s.fix[k] + s.fix[k] : inf64();  // tracker starts at A_K
   }
   const uint32_t field_mask = (1u << (2 * D)) - 1u;
   for (uint32_t c = 0; c < s.C; ++c) {
@@ -268,7 +268,10 @@ __device__ __forceinline__ double min_f64(double a, double b) {
 enum QueueOrderMode { kNoQueueOrder = 0, kBytes = 1, kWords = 2, kShorts = 3 };
 
 // Chunk dwords must already be initialised with L::init_chunk().
-template <typename L, int kQueueOrder, bool kBusy>
+// kFix: the batch carries fixed per-stage delays (a compile-time switch: even a
+// wave-uniform run-time branch around the four-way selection cost 4 % on
+// batches without delays).
+template <typename L, int kQueueOrder, bool kBusy, bool kFix>
 __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const FastScenario& fs,
                                                     bool scf, const LaneLds& lds,
                                                     const FastOut& out) {
@@ -334,8 +337,9 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
       // k; the All-Gather reuses it (mask still contains k then)
       const uint32_t ek = (fs.epack >> (8u * k)) & 0xffu;
       const uint32_t E = esum(fs.epack, mask) - (phase ? ek : 0u);
-      const double t = scale_down(fs.chunk, E) *
-                       sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+      double t = scale_down(fs.chunk, E) *
+                 sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+      if (kFix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
       const double f = now + t;
       stalled |= !(f > now);
       const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;

@@ -138,6 +138,7 @@ __device__ void simulate_generic(const Scenario& s, uint32_t Q, bool scf, const 
             }
           }
           double t = x * s.coef[k];
+          if (s.has_fix) t = s.fix[k] + t;
           finish[k] = now + t;
           busy[k] = busy[k] + t;
           serving[k] = (int)g;

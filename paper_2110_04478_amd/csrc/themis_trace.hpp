@@ -222,7 +222,8 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       const uint32_t mask = w & 15u, phase = (w >> 4) & 1u;
       const uint32_t ek = (epack >> (8u * k)) & 0xffu;
       const uint32_t E = esum(epack, mask) - (phase ? ek : 0u);
-      const double t = scale_down(rg.CH(h / C), E) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+      double t = scale_down(rg.CH(h / C), E) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+      if (s.has_fix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
       const double fin = now + t;
       stalled |= !(fin > now);
       uint32_t pos = 0;

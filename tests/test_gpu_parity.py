@@ -303,3 +303,55 @@ def test_full_size_config3_sampled_and_invariants(gpu, oracle):
     assert_close("t_done", t[sel].cpu().numpy(), o_t)
     assert_close("loads", loads[:, sel].cpu().numpy(), o_loads)
     assert_close("busy", busy[:, sel].cpu().numpy(), o_busy)
+
+
+def _with_fixed_delay(b, seed):
+    rng = np.random.default_rng(seed)
+    b.fixed_delay = np.ascontiguousarray(
+        rng.uniform(0, 2e-5, (4, b.n)) * (rng.uniform(0, 1, (4, b.n)) < 0.7))
+    return b
+
+
+def test_fixed_delay_per_stage(gpu, oracle):
+    """Fixed delay A_K (Sec. 4.5): tracker start and stage times, on every path
+    (LDS layouts, generic, trace, sweep)."""
+    import torch
+    W = w()
+    check_batch(gpu, oracle, W.table2())
+    check_batch(gpu, oracle, W.table2(intra=W.INTRA_FIFO, chunks=512))
+    check_batch(gpu, oracle, _with_fixed_delay(W.mixed(900, seed=51), 1))
+    check_batch(gpu, oracle, _with_fixed_delay(W.mixed(300, seed=52, pow2=False), 2))
+    check_batch(gpu, oracle, _with_fixed_delay(W.mixed(120, seed=53, max_chunks=200), 3))
+    check_batch(gpu, oracle, _with_fixed_delay(W.config5(n=70, n_coll=7), 4))
+    b = _with_fixed_delay(W.mixed(400, seed=54), 5)
+    b.fixed_delay[1, 17] = -1.0          # invalid delay -> NaN scenario (if D > 1)
+    b.ndims[17] = 3
+    t = check_batch(gpu, oracle, b)
+    assert np.isnan(t[17])
+    thr = np.array([0.0, 1 / 16])
+    want = oracle.sweep(b, thr, 7, threads=8)
+    d = gpu.to_device(b)
+    ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(d.n * 2 * 3, d.max_chunks))
+    got = gpu.themis_sweep(d, torch.from_numpy(thr).cuda(), 7, workspace=ws)
+    torch.cuda.synchronize()
+    assert_close("sweep with fixed delay", got.cpu().numpy(), want)
+
+
+def test_metrics_match_oracle(gpu, oracle):
+    import torch
+    W = w()
+    for b in (W.config3(n=5000), W.mixed(777, seed=61, pow2=False), W.config5(n=66, n_coll=5)):
+        d = gpu.to_device(b)
+        orders, loads = gpu.themis_plan_batch(d)
+        ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(
+            d.n, d.max_chunks, d.max_coll if d.n_coll is not None else 0))
+        t, _, busy = gpu.themis_simulate_batch(d, orders, workspace=ws, want_queue_order=False)
+        util, ideal = gpu.themis_metrics_batch(d, t, busy)
+        torch.cuda.synchronize()
+        o_util, o_ideal = oracle.metrics_batch(b, t.cpu().numpy(), busy.cpu().numpy())
+        assert_close("utilization", util.cpu().numpy(), o_util)
+        assert_close("ideal", ideal.cpu().numpy(), o_ideal)
+        u = util.cpu().numpy()
+        assert np.all((u > 0) & (u <= 1 + 1e-12))
+        # T >= Ideal (equality up to rounding for one dimension of two NPUs)
+        assert np.all(t.cpu().numpy() >= ideal.cpu().numpy() * (1 - 1e-12))
