@@ -177,6 +177,16 @@ def main():
                       % (m, cores, cpu_s),
             "parity_on_sample": {"orders_equal": same_orders, "t_done_max_rel_err": rel},
         }
+        # the same oracle on one core, on a 1/16 sub-sample
+        m1 = max(1, m // 16)
+        one = host.take(slice(0, m1))
+        c1 = time.perf_counter()
+        o1, _ = themis_oracle.plan_batch(one, threads=1)
+        themis_oracle.simulate_batch(one, o1, want_queue_order=qo is not None, threads=1)
+        one_s = time.perf_counter() - c1
+        result["cpu_baseline_single_core"] = {
+            "value": m1 / one_s, "unit": "scenarios/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d scenarios, %.1f s" % (m1, one_s)}
     print(json.dumps(result))
 
 
