@@ -30,6 +30,8 @@
 enum { TO_INTER_BASELINE = 0, TO_INTER_THEMIS = 1 };
 enum { TO_INTRA_FIFO = 0, TO_INTRA_SCF = 1 };
 enum { TO_THR_ABS = 0, TO_THR_REL = 1 };
+/* CollectiveType of Alg. 1 */
+enum { TO_ALL_REDUCE = 0, TO_REDUCE_SCATTER = 1, TO_ALL_GATHER = 2 };
 
 /* ------------------------------------------------------------------------ */
 /* Latency model (Sec. 4.5: latency of chunk i on dim K is n_K^i * B_K, with
@@ -102,11 +104,12 @@ static uint8_t encode_order(int ndims, const int *dims)
  * Returns 1 on success, 0 if the inputs are invalid (nothing written).       */
 /* ------------------------------------------------------------------------ */
 int to_plan(int ndims, const uint32_t *npus, const double *bw,
-            const double *fixed_delay, double size_bytes, uint32_t C,
+            const double *fixed_delay, int ctype, double size_bytes, uint32_t C,
             int inter_policy, int threshold_mode, double threshold,
             uint8_t *orders, double *loads, double *stage_time)
 {
   if (!to_network_valid(ndims, npus, bw)) return 0;
+  if (ctype < TO_ALL_REDUCE || ctype > TO_ALL_GATHER) return 0;
   if (!to_fixed_delay_valid(ndims, fixed_delay)) return 0;
   if (!finite_positive(size_bytes) || C < 1u) return 0;
   if (!(threshold >= 0.0)) return 0; /* also rejects NaN */
@@ -123,7 +126,9 @@ int to_plan(int ndims, const uint32_t *npus, const double *bw,
    * delay once for its Reduce-Scatter and once for its All-Gather. */
   double load[TO_MAX_DIMS] = {0.0, 0.0, 0.0, 0.0};
   if (fixed_delay)
-    for (int k = 0; k < ndims; ++k) load[k] = fixed_delay[k] + fixed_delay[k];
+    for (int k = 0; k < ndims; ++k)
+      load[k] = (ctype == TO_ALL_REDUCE) ? fixed_delay[k] + fixed_delay[k]
+                                         : fixed_delay[k];
 
   for (uint32_t i = 0; i < C; ++i) {
     /* Scheduler.Schedule: current loads, their min and max (line 18-19). */
@@ -133,9 +138,18 @@ int to_plan(int ndims, const uint32_t *npus, const double *bw,
       if (load[k] < lo) { lo = load[k]; kmin = k; }
       if (load[k] > hi) hi = load[k];
     }
+    /* Threshold relative to "an RS/AG of a whole chunk on the least-loaded
+     * dimension" (Sec. 5.3): an All-Gather stage that starts from `chunk`
+     * bytes moves (P-1) * chunk of them. */
     double thr = threshold;
-    if (threshold_mode == TO_THR_REL) thr = threshold * (chunk * coef[kmin]);
+    if (threshold_mode == TO_THR_REL)
+      thr = (ctype == TO_ALL_GATHER)
+                ? threshold * ((chunk * (double)npus[kmin]) * coef[kmin])
+                : threshold * (chunk * coef[kmin]);
 
+    /* ascending order first (the Reduce-Scatter schedule, Alg. 1 line 23); an
+     * All-Gather takes it in reverse (line 25: descending loads, and
+     * dimD..dim1 as its baseline, Sec. 2.3) */
     int order[TO_MAX_DIMS];
     for (int k = 0; k < ndims; ++k) order[k] = k; /* baseline: dim1..dimD */
     if (inter_policy != TO_INTER_BASELINE && !((hi - lo) < thr)) {
@@ -152,16 +166,31 @@ int to_plan(int ndims, const uint32_t *npus, const double *bw,
       }
     }
 
+    if (ctype == TO_ALL_GATHER) {
+      for (int a = 0, b = ndims - 1; a < b; ++a, --b) {
+        int tmp = order[a]; order[a] = order[b]; order[b] = tmp;
+      }
+    }
+
     /* Latency Model + tracker update (lines 28-30).  The chunk shrinks by
-     * P_k after its Reduce-Scatter on dimension k (Sec. 2.1); its All-Gather
-     * on k later moves the same bytes, so the dimension is charged twice. */
+     * P_k after its Reduce-Scatter on dimension k (Sec. 2.1); in an All-Reduce
+     * its All-Gather on k later moves the same bytes, so the dimension is
+     * charged twice.  A stand-alone All-Gather grows the chunk by P_k per
+     * stage and moves (P_k-1)/P_k of the grown size. */
     double x = chunk;
     for (int j = 0; j < ndims; ++j) {
       int k = order[j];
-      double t = x * coef[k];
+      double t;
+      if (ctype == TO_ALL_GATHER) {
+        x = x * (double)npus[k];
+        t = x * coef[k];
+        load[k] = load[k] + t;
+      } else {
+        t = x * coef[k];
+        load[k] = load[k] + ((ctype == TO_ALL_REDUCE) ? (t + t) : t);
+        x = x / (double)npus[k];
+      }
       if (stage_time) stage_time[(size_t)i * TO_MAX_DIMS + k] = t;
-      load[k] = load[k] + (t + t);
-      x = x / (double)npus[k];
     }
     orders[i] = encode_order(ndims, order);
   }
@@ -200,6 +229,13 @@ static int stage_dim(const to_chunk *c, int ndims)
                             : c->order[2 * ndims - 1 - c->stage];
 }
 
+/* stages of one chunk: an All-Reduce runs D Reduce-Scatter and D All-Gather
+ * stages, the stand-alone collectives only their own D (Sec. 2.3 footnote) */
+static int stage_count(int ctype, int ndims)
+{
+  return (ctype == TO_ALL_REDUCE) ? 2 * ndims : ndims;
+}
+
 /* Does chunk a (id ga) go before chunk b (id gb) in one dimension's queue? */
 static int goes_first(int intra_policy, const to_chunk *a, uint32_t ga,
                       const to_chunk *b, uint32_t gb)
@@ -214,7 +250,7 @@ static int goes_first(int intra_policy, const to_chunk *a, uint32_t ga,
 }
 
 int to_simulate(int ndims, const uint32_t *npus, const double *bw,
-                const double *fixed_delay, uint32_t n_coll, const double *coll_size,
+                const double *fixed_delay, int ctype, uint32_t n_coll, const double *coll_size,
                 const double *release, uint32_t C, int intra_policy,
                 const uint8_t *orders, double *t_done, double *coll_done,
                 uint32_t *queue_order, double *busy)
@@ -222,6 +258,8 @@ int to_simulate(int ndims, const uint32_t *npus, const double *bw,
   if (!to_network_valid(ndims, npus, bw)) return 0;
   if (!to_fixed_delay_valid(ndims, fixed_delay)) return 0;
   if (n_coll < 1u || C < 1u) return 0;
+  if (ctype < TO_ALL_REDUCE || ctype > TO_ALL_GATHER) return 0;
+  const int last = stage_count(ctype, ndims);
   for (uint32_t q = 0; q < n_coll; ++q) {
     if (!finite_positive(coll_size[q])) return 0;
     if (release && !(isfinite(release[q]) && release[q] >= 0.0)) return 0;
@@ -247,8 +285,13 @@ int to_simulate(int ndims, const uint32_t *npus, const double *bw,
       double x = chunk;
       for (int j = 0; j < ndims; ++j) {
         int k = c->order[j];
-        c->t[k] = x * coef[k];
-        x = x / (double)npus[k];
+        if (ctype == TO_ALL_GATHER) {
+          x = x * (double)npus[k];
+          c->t[k] = x * coef[k];
+        } else {
+          c->t[k] = x * coef[k];
+          x = x / (double)npus[k];
+        }
       }
     }
   }
@@ -269,7 +312,7 @@ int to_simulate(int ndims, const uint32_t *npus, const double *bw,
       int best = -1;
       for (uint32_t g = 0; g < G; ++g) {
         const to_chunk *c = &ch[g];
-        if (c->stage >= 2 * ndims || c->running) continue;
+        if (c->stage >= last || c->running) continue;
         if (stage_dim(c, ndims) != k) continue;
         if (c->arrival > now) continue; /* not released yet */
         if (best < 0 || goes_first(intra_policy, c, g, &ch[best], (uint32_t)best))
@@ -284,7 +327,7 @@ int to_simulate(int ndims, const uint32_t *npus, const double *bw,
       finish[k] = now + service;
       busy_acc[k] = busy_acc[k] + service;
       if (queue_order) {
-        uint32_t phase = (c->stage >= ndims) ? 1u : 0u;
+        uint32_t phase = (ctype == TO_ALL_GATHER || c->stage >= ndims) ? 1u : 0u;
         queue_order[(size_t)k * 2u * G + executed[k]] = ((uint32_t)best << 1) | phase;
       }
       executed[k]++;
@@ -296,7 +339,7 @@ int to_simulate(int ndims, const uint32_t *npus, const double *bw,
       if (serving[k] >= 0 && finish[k] < next) next = finish[k];
     for (uint32_t g = 0; g < G; ++g) {
       const to_chunk *c = &ch[g];
-      if (c->stage < 2 * ndims && !c->running && c->arrival > now &&
+      if (c->stage < last && !c->running && c->arrival > now &&
           c->arrival < next)
         next = c->arrival;
     }
@@ -308,13 +351,15 @@ int to_simulate(int ndims, const uint32_t *npus, const double *bw,
       if (serving[k] < 0 || finish[k] != now) continue;
       uint32_t g = (uint32_t)serving[k];
       to_chunk *c = &ch[g];
-      if (c->stage < ndims) c->size = c->size / (double)npus[k]; /* RS */
-      else                  c->size = c->size * (double)npus[k]; /* AG */
+      if (ctype != TO_ALL_GATHER && c->stage < ndims)
+        c->size = c->size / (double)npus[k]; /* Reduce-Scatter stage */
+      else
+        c->size = c->size * (double)npus[k]; /* All-Gather stage */
       c->stage++;
       c->running = 0;
       c->arrival = now;
       serving[k] = -1;
-      if (c->stage == 2 * ndims) {
+      if (c->stage == last) {
         last_done = now;
         if (coll_done) coll_done[g / C] = now;
       }
@@ -358,8 +403,9 @@ void to_plan_batch(uint64_t n, uint64_t begin, uint64_t end,
                    const double *bw, const double *size_bytes,
                    const uint32_t *chunks, const uint8_t *inter_policy,
                    const double *threshold, const double *fixed_delay,
-                   uint32_t max_coll, const uint32_t *n_coll,
-                   const double *coll_size, uint8_t *orders, double *loads)
+                   const uint8_t *collective_type, uint32_t max_coll,
+                   const uint32_t *n_coll, const double *coll_size,
+                   uint8_t *orders, double *loads)
 {
   uint32_t mc = (n_coll && max_coll > 0u) ? max_coll : 1u;
   size_t slots = (size_t)max_chunks * mc;
@@ -375,8 +421,9 @@ void to_plan_batch(uint64_t n, uint64_t begin, uint64_t end,
     int ok = (C >= 1u && C <= max_chunks && Q >= 1u && Q <= mc);
     for (uint32_t q = 0; ok && q < Q; ++q) {
       double S = n_coll ? coll_size[(size_t)q * n + i] : size_bytes[i];
-      ok = to_plan((int)ndims[i], p, b, fixed, S, C, (int)inter_policy[i],
-                   threshold_mode, threshold[i],
+      ok = to_plan((int)ndims[i], p, b, fixed,
+                   collective_type ? (int)collective_type[i] : TO_ALL_REDUCE,
+                   S, C, (int)inter_policy[i], threshold_mode, threshold[i],
                    row + (size_t)q * max_chunks, ld, NULL);
     }
     if (!ok) {
@@ -395,7 +442,8 @@ void to_simulate_batch(uint64_t n, uint64_t begin, uint64_t end,
                        const uint32_t *npus, const double *bw,
                        const double *size_bytes, const uint32_t *chunks,
                        const uint8_t *intra_policy, const double *fixed_delay,
-                       uint32_t max_coll, const uint32_t *n_coll,
+                       const uint8_t *collective_type, uint32_t max_coll,
+                       const uint32_t *n_coll,
                        const double *coll_size, const double *release_time,
                        const uint8_t *orders,
                        double *t_done, uint16_t *queue_order, double *busy)
@@ -425,8 +473,9 @@ void to_simulate_batch(uint64_t n, uint64_t begin, uint64_t end,
         memcpy(od + (size_t)q * C,
                orders + (size_t)i * slots + (size_t)q * max_chunks, C);
       }
-      ok = to_simulate(D, p, b, fixed, Q, cs, rl, C, (int)intra_policy[i], od,
-                       &T, NULL, qo, bz);
+      ok = to_simulate(D, p, b, fixed,
+                       collective_type ? (int)collective_type[i] : TO_ALL_REDUCE,
+                       Q, cs, rl, C, (int)intra_policy[i], od, &T, NULL, qo, bz);
     }
     if (!ok) {
       T = NAN;
@@ -440,8 +489,11 @@ void to_simulate_batch(uint64_t n, uint64_t begin, uint64_t end,
       memset(row, 0xFF, sizeof(uint16_t) * TO_MAX_DIMS * 2u * slots);
       if (ok) {
         uint32_t G = Q * C;
+        /* an All-Reduce runs two operations per chunk and dimension, the
+         * stand-alone collectives one */
+        uint32_t per_dim = (collective_type && collective_type[i] != TO_ALL_REDUCE) ? G : 2u * G;
         for (int k = 0; k < D; ++k)
-          for (uint32_t e = 0; e < 2u * G; ++e)
+          for (uint32_t e = 0; e < per_dim; ++e)
             row[(size_t)k * 2u * slots + e] = (uint16_t)qo[(size_t)k * 2u * G + e];
       }
     }
@@ -479,12 +531,12 @@ void to_sweep(uint64_t n, uint64_t begin, uint64_t end, uint32_t max_chunks,
         double T = NAN;
         int ok = (C >= 1u && C <= max_chunks);
         if (ok)
-          ok = to_plan((int)ndims[i], p, b, fixed, size_bytes[i], C, inter,
-                       threshold_mode, th, od, ld, NULL);
+          ok = to_plan((int)ndims[i], p, b, fixed, TO_ALL_REDUCE, size_bytes[i],
+                       C, inter, threshold_mode, th, od, ld, NULL);
         if (ok) {
           double S = size_bytes[i];
-          ok = to_simulate((int)ndims[i], p, b, fixed, 1u, &S, NULL, C, intra,
-                           od, &T, NULL, NULL, NULL);
+          ok = to_simulate((int)ndims[i], p, b, fixed, TO_ALL_REDUCE, 1u, &S, NULL,
+                           C, intra, od, &T, NULL, NULL, NULL);
         }
         if (!ok) T = NAN;
         t_done[((size_t)i * n_thr + a) * n_pol + col] = T;

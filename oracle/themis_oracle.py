@@ -28,21 +28,21 @@ def lib():
     if _lib is None:
         L = C.CDLL(_build.build())
         L.to_plan.restype = C.c_int
-        L.to_plan.argtypes = [C.c_int, _u32p, _f64p, _f64p, C.c_double, C.c_uint32,
+        L.to_plan.argtypes = [C.c_int, _u32p, _f64p, _f64p, C.c_int, C.c_double, C.c_uint32,
                               C.c_int, C.c_int, C.c_double, _u8p, _f64p, _f64p]
         L.to_simulate.restype = C.c_int
-        L.to_simulate.argtypes = [C.c_int, _u32p, _f64p, _f64p, C.c_uint32, _f64p,
+        L.to_simulate.argtypes = [C.c_int, _u32p, _f64p, _f64p, C.c_int, C.c_uint32, _f64p,
                                   _f64p, C.c_uint32, C.c_int, _u8p, _f64p,
                                   _f64p, _u32p, _f64p]
         L.to_plan_batch.restype = None
         L.to_plan_batch.argtypes = [
             C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, C.c_int, _u8p,
-            _u32p, _f64p, _f64p, _u32p, _u8p, _f64p, _f64p, C.c_uint32, _u32p,
+            _u32p, _f64p, _f64p, _u32p, _u8p, _f64p, _f64p, _u8p, C.c_uint32, _u32p,
             _f64p, _u8p, _f64p]
         L.to_simulate_batch.restype = None
         L.to_simulate_batch.argtypes = [
             C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, _u8p, _u32p,
-            _f64p, _f64p, _u32p, _u8p, _f64p, C.c_uint32, _u32p, _f64p, _f64p,
+            _f64p, _f64p, _u32p, _u8p, _f64p, _u8p, C.c_uint32, _u32p, _f64p, _f64p,
             _u8p, _f64p, _u16p, _f64p]
         L.to_sweep.restype = None
         L.to_sweep.argtypes = [
@@ -102,8 +102,11 @@ def _fixed4(fixed_delay, D):
     return f
 
 
+ALL_REDUCE, REDUCE_SCATTER, ALL_GATHER = 0, 1, 2
+
+
 def plan(npus, bw, size_bytes, chunks, inter_policy=1, threshold_mode=0,
-         threshold=0.0, fixed_delay=None):
+         threshold=0.0, fixed_delay=None, ctype=ALL_REDUCE):
     """Alg. 1 for one collective.  Returns (orders u8[C], loads f64[4],
     stage_time f64[C,4]) or None if the inputs are invalid."""
     D = len(npus)
@@ -113,7 +116,7 @@ def plan(npus, bw, size_bytes, chunks, inter_policy=1, threshold_mode=0,
     loads = np.zeros(4)
     st = np.zeros((chunks, 4))
     fx = _fixed4(fixed_delay, D)
-    ok = lib().to_plan(D, _p(P, _u32p), _p(B, _f64p), _p(fx, _f64p), float(size_bytes),
+    ok = lib().to_plan(D, _p(P, _u32p), _p(B, _f64p), _p(fx, _f64p), int(ctype), float(size_bytes),
                        int(chunks), int(inter_policy), int(threshold_mode),
                        float(threshold), _p(orders, _u8p), _p(loads, _f64p),
                        _p(st, _f64p))
@@ -121,7 +124,7 @@ def plan(npus, bw, size_bytes, chunks, inter_policy=1, threshold_mode=0,
 
 
 def simulate(npus, bw, coll_sizes, chunks, intra_policy, orders, release=None,
-             fixed_delay=None):
+             fixed_delay=None, ctype=ALL_REDUCE):
     """Queue simulation of one scenario (one or several collectives).
     Returns dict(t_done, coll_done, queue_order[D][2G], busy[4]) or None."""
     D = len(npus)
@@ -138,7 +141,7 @@ def simulate(npus, bw, coll_sizes, chunks, intra_policy, orders, release=None,
     qo = np.zeros((4, 2 * G), np.uint32)
     busy = np.zeros(4)
     fx = _fixed4(fixed_delay, D)
-    ok = lib().to_simulate(D, _p(P, _u32p), _p(B, _f64p), _p(fx, _f64p), Q, _p(cs, _f64p),
+    ok = lib().to_simulate(D, _p(P, _u32p), _p(B, _f64p), _p(fx, _f64p), int(ctype), Q, _p(cs, _f64p),
                            _p(rl, _f64p), int(chunks), int(intra_policy),
                            _p(od, _u8p), C.byref(t), _p(cd, _f64p),
                            _p(qo, _u32p), _p(busy, _f64p))
@@ -151,6 +154,11 @@ def simulate(npus, bw, coll_sizes, chunks, intra_policy, orders, release=None,
 def _fixed(b):
     f = getattr(b, "fixed_delay", None)
     return None if f is None else _arr(f, np.float64)
+
+
+def _ctype(b):
+    c = getattr(b, "collective_type", None)
+    return None if c is None else _arr(c, np.uint8)
 
 
 def _trace(b):
@@ -173,13 +181,14 @@ def plan_batch(b, threads=1):
              inter=_arr(b.inter_policy, np.uint8),
              thr=_arr(b.threshold, np.float64))
     fx = _fixed(b)
+    ct = _ctype(b)
 
     def run(lo, hi):
         lib().to_plan_batch(
             b.n, lo, hi, b.max_chunks, b.threshold_mode, _p(a["ndims"], _u8p),
             _p(a["npus"], _u32p), _p(a["bw"], _f64p), _p(a["size"], _f64p),
             _p(a["chunks"], _u32p), _p(a["inter"], _u8p), _p(a["thr"], _f64p),
-            _p(fx, _f64p), mc, _p(ncoll, _u32p), _p(csize, _f64p),
+            _p(fx, _f64p), _p(ct, _u8p), mc, _p(ncoll, _u32p), _p(csize, _f64p),
             _p(orders, _u8p), _p(loads, _f64p))
     _fan_out(run, b.n, threads)
     return orders, loads
@@ -199,12 +208,13 @@ def simulate_batch(b, orders, want_queue_order=True, threads=1):
              chunks=_arr(b.chunks, np.uint32),
              intra=_arr(b.intra_policy, np.uint8))
     fx = _fixed(b)
+    ct = _ctype(b)
 
     def run(lo, hi):
         lib().to_simulate_batch(
             b.n, lo, hi, b.max_chunks, _p(a["ndims"], _u8p),
             _p(a["npus"], _u32p), _p(a["bw"], _f64p), _p(a["size"], _f64p),
-            _p(a["chunks"], _u32p), _p(a["intra"], _u8p), _p(fx, _f64p), mc,
+            _p(a["chunks"], _u32p), _p(a["intra"], _u8p), _p(fx, _f64p), _p(ct, _u8p), mc,
             _p(ncoll, _u32p), _p(csize, _f64p), _p(rel, _f64p), _p(od, _u8p),
             _p(t, _f64p), _p(qo, _u16p), _p(busy, _f64p))
     _fan_out(run, b.n, threads)

@@ -28,8 +28,21 @@ def exact_stage_times(npus, bw, chunk, dims):
     return out, x
 
 
+def exact_all_gather_times(npus, bw, chunk, dims):
+    """Exact (time, size-before) of the D stages of a stand-alone All-Gather:
+    a stage on k grows the resident size by P_k and moves (P_k-1)/P_k of the
+    grown size (Sec. 2.1, 4.5)."""
+    y = Fraction(chunk)
+    out = []
+    for k in dims:
+        P = Fraction(int(npus[k]))
+        out.append(((P - 1) / P * (y * P) / Fraction(bw[k]), y))
+        y = y * P
+    return out
+
+
 def rebuild_and_check(npus, bw, coll_sizes, C, intra_policy, orders,
-                      queue_order, release=None, fixed_delay=None):
+                      queue_order, release=None, fixed_delay=None, ctype=0):
     """Returns (T, busy[D]) as Fractions after asserting the schedule is a
     valid execution under the policy.  queue_order[k] lists (g<<1|phase)."""
     D = len(npus)
@@ -41,23 +54,34 @@ def rebuild_and_check(npus, bw, coll_sizes, C, intra_policy, orders,
         q = g // C
         dims = order_dims(int(orders[g]), D)
         assert sorted(dims) == list(range(D))
+        if ctype == 2:  # stand-alone All-Gather: D stages, phase bit 1
+            ag = exact_all_gather_times(npus, bw, Fraction(coll_sizes[q]) / C, dims)
+            if fixed_delay is not None:
+                ag = [(t + Fraction(fixed_delay[k]), y) for (t, y), k in zip(ag, dims)]
+            stages.append([(dims[j], 1, ag[j][0], ag[j][1]) for j in range(D)])
+            continue
         rs, xD = exact_stage_times(npus, bw, Fraction(coll_sizes[q]) / C, dims)
         if fixed_delay is not None:  # A_K of Sec. 4.5: a fixed delay per stage on that dimension
             rs = [(t + Fraction(fixed_delay[k]), x) for (t, x), k in zip(rs, dims)]
         st = [(dims[j], 0, rs[j][0], rs[j][1]) for j in range(D)]
-        y = xD
-        for j in reversed(range(D)):
-            st.append((dims[j], 1, rs[j][0], y))
-            y = y * int(npus[dims[j]])
+        if ctype == 0:  # All-Reduce: the All-Gather stages follow in reverse order
+            y = xD
+            for j in reversed(range(D)):
+                st.append((dims[j], 1, rs[j][0], y))
+                y = y * int(npus[dims[j]])
         stages.append(st)
 
     rel = [Fraction(0) if release is None else Fraction(release[g // C])
            for g in range(G)]
     # position of every (g, stage index) in its dimension's list
+    per_chunk = 2 if ctype == 0 else 1
+    nops = per_chunk * G
+    queue_order = [list(row[:nops]) for row in queue_order]
     for k in range(D):
         ops = [int(e) for e in queue_order[k]]
-        assert len(ops) == 2 * G, "each dimension executes exactly 2 ops per chunk"
-        assert sorted(ops) == list(range(2 * G)), "every (chunk, phase) once"
+        want = (list(range(2 * G)) if ctype == 0 else
+                [2 * g + (1 if ctype == 2 else 0) for g in range(G)])
+        assert sorted(ops) == want, "every (chunk, phase) exactly once per dimension"
 
     # iterative longest-path evaluation over the two precedence chains
     stage_idx = {}
@@ -72,7 +96,7 @@ def rebuild_and_check(npus, bw, coll_sizes, C, intra_policy, orders,
     while progressed:
         progressed = False
         for k in range(D):
-            while ptr[k] < 2 * G:
+            while ptr[k] < nops:
                 e = int(queue_order[k][ptr[k]])
                 g, ph = e >> 1, e & 1
                 s = stage_idx[(k, g, ph)]
@@ -86,7 +110,7 @@ def rebuild_and_check(npus, bw, coll_sizes, C, intra_policy, orders,
                 ptr[k] += 1
                 done_ops += 1
                 progressed = True
-    assert done_ops == 2 * D * G, "executed order lists are not a consistent schedule"
+    assert done_ops == D * nops, "executed order lists are not a consistent schedule"
 
     # policy conformance, operation by operation
     for k in range(D):
@@ -117,6 +141,6 @@ def rebuild_and_check(npus, bw, coll_sizes, C, intra_policy, orders,
             prev_end = end[(g, s)]
 
     T = max(end.values())
-    busy = [sum((stages[g][s][2] for g in range(G) for s in range(2 * D)
-                 if stages[g][s][0] == k), Fraction(0)) for k in range(D)]
+    busy = [sum((st[2] for g in range(G) for st in stages[g] if st[0] == k), Fraction(0))
+            for k in range(D)]
     return T, busy

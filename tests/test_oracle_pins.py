@@ -495,3 +495,92 @@ def test_utilization_and_ideal(oracle):
     assert util[0] == pytest.approx(20.0 / 24.0, rel=1e-13)
     assert ideal[0] == pytest.approx(256 * MB / (1.5 * B0), rel=1e-15)
     assert t[0] >= ideal[0]
+
+
+# ---------------------------------------------------------------- stand-alone RS / AG
+RS, AG = 1, 2
+
+
+@pytest.mark.parametrize("P,B,S,C", [(8, 100e9, 2.0 ** 30, 64), (3, 77e9, 123456789.0, 5),
+                                     (2, 400e9, 3e8, 7)])
+def test_one_dimensional_reduce_scatter_and_all_gather(oracle, P, B, S, C):
+    """Sec. 2.1: on P NPUs a Reduce-Scatter sends (P-1)/P of the resident data
+    and leaves 1/P of it; an All-Gather that starts from S bytes per NPU ends
+    with P*S and sends (P-1)*S.  An All-Reduce of S is the one followed by the
+    other on S/P."""
+    od, ld, _ = oracle.plan([P], [B], S, C, 1, ctype=RS)
+    rs = oracle.simulate([P], [B], [S], C, 0, od, ctype=RS)
+    assert rs["t_done"] == pytest.approx((P - 1) / P * S / B, rel=1e-13)
+    assert ld[0] == pytest.approx((P - 1) / P * S / B, rel=1e-13)
+    assert sorted(rs["queue_order"][0][:C].tolist()) == [2 * g for g in range(C)]
+    od, ld, _ = oracle.plan([P], [B], S / P, C, 1, ctype=AG)
+    ag = oracle.simulate([P], [B], [S / P], C, 0, od, ctype=AG)
+    assert ag["t_done"] == pytest.approx((P - 1) * (S / P) / B, rel=1e-13)
+    assert sorted(ag["queue_order"][0][:C].tolist()) == [2 * g + 1 for g in range(C)]
+    od, _, _ = oracle.plan([P], [B], S, C, 1)
+    ar = oracle.simulate([P], [B], [S], C, 0, od)
+    assert ar["t_done"] == pytest.approx(rs["t_done"] + ag["t_done"], rel=1e-13)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_single_chunk_all_reduce_is_rs_then_ag(oracle, seed):
+    """With one chunk nothing overlaps: the baseline All-Reduce (RS dim1..dimD,
+    AG dimD..dim1, Sec. 2.3) takes the Reduce-Scatter of S plus the All-Gather
+    of what is left, S / (P_1*...*P_D), each with its own baseline order."""
+    rng = np.random.default_rng(2000 + seed)
+    D = int(rng.integers(1, 5))
+    P, bw = _rand_net(rng, D, dyadic=True)
+    S = float(2 ** int(rng.integers(24, 30)))
+    prod = int(np.prod(P))
+    od_ar = oracle.plan(P, bw, S, 1, 0)[0]
+    od_rs = oracle.plan(P, bw, S, 1, 0, ctype=RS)[0]
+    od_ag = oracle.plan(P, bw, S / prod, 1, 0, ctype=AG)[0]
+    assert order_dims(int(od_rs[0]), D) == list(range(D))
+    assert order_dims(int(od_ag[0]), D) == list(range(D))[::-1]
+    t_ar = oracle.simulate(P, bw, [S], 1, 0, od_ar)["t_done"]
+    t_rs = oracle.simulate(P, bw, [S], 1, 0, od_rs, ctype=RS)["t_done"]
+    t_ag = oracle.simulate(P, bw, [S / prod], 1, 0, od_ag, ctype=AG)["t_done"]
+    assert Fraction(t_ar) == Fraction(t_rs) + Fraction(t_ag)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_stand_alone_collectives_plan_and_queue_rules(oracle, seed):
+    """Alg. 1 for CT = Reduce-Scatter (ascending loads) and All-Gather
+    (descending loads, ties to the higher dimension so that equal loads give
+    dimD..dim1) replayed with exact rationals, and the simulation checked by
+    the independent schedule checker."""
+    rng = np.random.default_rng(2100 + seed)
+    ctype = RS if seed % 2 else AG
+    D = int(rng.integers(1, 5))
+    P, bw = _rand_net(rng, D, dyadic=True)
+    C = int(rng.integers(1, 12))
+    S = float(C * 2 ** int(rng.integers(18, 24)))
+    f = Fraction(int(rng.integers(0, 4)), 16)
+    fx = [float(rng.integers(0, 5)) * 2.0 ** -14 for _ in range(D)] if seed % 3 == 0 else None
+    orders, loads, _ = oracle.plan(P, bw, S, C, 1, 1, float(f), fixed_delay=fx, ctype=ctype)
+    coef = [Fraction(P[k] - 1, P[k]) / Fraction(bw[k]) for k in range(D)]
+    load = [Fraction(fx[k]) if fx else Fraction(0) for k in range(D)]
+    chunk = Fraction(S) / C
+    for i in range(C):
+        lo = min(load)
+        kmin = load.index(lo)
+        whole = chunk * P[kmin] * coef[kmin] if ctype == AG else chunk * coef[kmin]
+        asc = (list(range(D)) if max(load) - lo < f * whole
+               else sorted(range(D), key=lambda k: (load[k], k)))
+        want = asc[::-1] if ctype == AG else asc
+        assert order_dims(int(orders[i]), D) == want
+        x = chunk
+        for k in want:
+            if ctype == AG:
+                x *= P[k]
+                load[k] += x * coef[k]
+            else:
+                load[k] += x * coef[k]
+                x /= P[k]
+    assert [Fraction(v) for v in loads[:D]] == load
+    for intra in (0, 1):
+        r = oracle.simulate(P, bw, [S], C, intra, orders, fixed_delay=fx, ctype=ctype)
+        T, busy = rebuild_and_check(P, bw, [S], C, intra, orders, r["queue_order"],
+                                    fixed_delay=fx, ctype=ctype)
+        assert Fraction(r["t_done"]) == T
+        assert [Fraction(v) for v in r["busy"][:D]] == busy
