@@ -80,6 +80,9 @@ enum { THEMIS_INTRA_FIFO = 0, THEMIS_INTRA_SCF = 1 };
  *        (Sec. 5.3) is f = 1/16. */
 enum { THEMIS_THR_ABS = 0, THEMIS_THR_REL = 1 };
 
+/* CollectiveType of Alg. 1. */
+enum { THEMIS_COLL_ALL_REDUCE = 0, THEMIS_COLL_REDUCE_SCATTER = 1, THEMIS_COLL_ALL_GATHER = 2 };
+
 /* Bits of themis_sweep's policy_mask, evaluated in ascending bit order. */
 enum {
   THEMIS_SWEEP_BASELINE = 1u,    /* baseline order + FIFO   */
@@ -122,6 +125,17 @@ typedef struct themis_batch {
    * stage of each kind per dimension), and every stage on k takes
    * fixed_delay[k] + bytes * per-byte latency in the simulation. */
   const double *fixed_delay;  /* [4][n] >= 0 and finite, or NULL               */
+  /* Optional CollectiveType of Alg. 1 per scenario; NULL = All-Reduce.
+   * A stand-alone Reduce-Scatter runs only the D Reduce-Scatter stages
+   * (tracker += t, started at fixed_delay[k]); a stand-alone All-Gather of
+   * size_bytes per NPU runs D stages, each of which multiplies the resident
+   * size by P_k and takes (size * P_k) * coef[k]; its order is the reverse of
+   * the ascending sort (descending loads, ties to the higher dimension, so
+   * equal loads give dimD..dim1, its baseline order), its relative Threshold
+   * is threshold * ((chunk * P_kmin) * coef[kmin]), and its queue entries
+   * carry phase 1.  Each dimension then executes `chunks` operations, not
+   * 2 * chunks.  themis_sweep evaluates All-Reduce only. */
+  const uint8_t *collective_type; /* [n] THEMIS_COLL_*, or NULL               */
 } themis_batch_t;
 
 /* Library version as major*10000 + minor*100 + patch. */

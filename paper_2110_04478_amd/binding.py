@@ -29,7 +29,7 @@ class _Batch(C.Structure):
         ("ndims", _vp), ("npus", _vp), ("bw", _vp), ("size_bytes", _vp), ("chunks", _vp),
         ("inter_policy", _vp), ("intra_policy", _vp), ("threshold", _vp),
         ("max_coll", C.c_uint32), ("n_coll", _vp), ("coll_size", _vp), ("release_time", _vp),
-        ("fixed_delay", _vp),
+        ("fixed_delay", _vp), ("collective_type", _vp),
     ]
 
 
@@ -104,6 +104,7 @@ class DeviceBatch:
     coll_size: Optional[torch.Tensor] = None
     release_time: Optional[torch.Tensor] = None
     fixed_delay: Optional[torch.Tensor] = None
+    collective_type: Optional[torch.Tensor] = None
 
     @property
     def slots(self) -> int:
@@ -118,7 +119,8 @@ class DeviceBatch:
                       _ptr(self.npus), _ptr(self.bw), _ptr(self.size_bytes), _ptr(self.chunks),
                       _ptr(self.inter_policy), _ptr(self.intra_policy), _ptr(self.threshold),
                       self.max_coll, _ptr(self.n_coll), _ptr(self.coll_size),
-                      _ptr(self.release_time), _ptr(self.fixed_delay))
+                      _ptr(self.release_time), _ptr(self.fixed_delay),
+                      _ptr(self.collective_type))
 
 
 def to_device(b, device="cuda:0") -> DeviceBatch:
@@ -138,7 +140,8 @@ def to_device(b, device="cuda:0") -> DeviceBatch:
         threshold=up(b.threshold, torch.float64), max_coll=int(b.max_coll),
         n_coll=up(b.n_coll, torch.uint32), coll_size=up(b.coll_size, torch.float64),
         release_time=up(b.release_time, torch.float64),
-        fixed_delay=up(getattr(b, "fixed_delay", None), torch.float64))
+        fixed_delay=up(getattr(b, "fixed_delay", None), torch.float64),
+        collective_type=up(getattr(b, "collective_type", None), torch.uint8))
 
 
 def themis_version() -> int:

@@ -98,7 +98,7 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
           }
         } else {
 #pragma unroll
-          for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? s.fix[k] + s.fix[k] : inf64();
+          for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? tracker_start(s, k) : inf64();
           for (uint32_t c = 0; c < s.C; ++c)
             r[c] = (uint8_t)schedule_chunk(s, chunk, themis_on, rel, thr, load);
           filled = s.C;
@@ -194,7 +194,7 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
           if (c4 + j < s.C) {
             uint32_t code = (v >> (8u * j)) & 0xffu;
             codes_ok = codes_ok && order_code_ok(code, s.D);
-            L::init_chunk(lds, c4 + j, code);
+            L::init_chunk(lds, c4 + j, stored_code(s, fs, code), fs.state0);
           }
         }
       }
@@ -202,7 +202,7 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       for (uint32_t c = 0; c < s.C; ++c) {
         uint32_t code = row[c];
         codes_ok = codes_ok && order_code_ok(code, s.D);
-        L::init_chunk(lds, c, code);
+        L::init_chunk(lds, c, stored_code(s, fs, code), fs.state0);
       }
     }
     if (!codes_ok) { write_invalid(out); return; }
@@ -260,6 +260,8 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
   const uint8_t* row = orders + (size_t)i * tv.slots;
   bool fast = trace_area != nullptr && tl.bytes != 0u && Q <= tl.Q;
   uint32_t epack = 0;
+  FastScenario fs0;
+  fs0.state0 = 0u; fs0.rs_only = false; fs0.gather = false;
   if (fast) {
     TraceRegion rg;
     rg.base = trace_area + (size_t)i * tl.bytes;
@@ -267,12 +269,11 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     // every collective must be in the range where halvings are exact, and
     // released at t = 0
     for (uint32_t q = 0; q < Q; ++q) {
-      FastScenario fs;
       const double chunk = collective_size(b, tv, i, q) / (double)s.C;
-      fast = fast && fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs) &&
+      fast = fast && fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs0) &&
              collective_release(b, tv, i, q) == 0.0;
-      epack = fs.epack;
-      rg.CH(q) = chunk;
+      epack = fs0.epack;
+      rg.CH(q) = fs0.base;  // resident size at mask 0
     }
     bool codes_ok = true;
     if (fast) {
@@ -280,14 +281,14 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
         for (uint32_t c = 0; c < s.C; ++c) {
           const uint32_t code = row[(size_t)q * b.max_chunks + c];
           codes_ok = codes_ok && order_code_ok(code, s.D);
-          rg.W(q * s.C + c) = trace_word(code);
+          rg.W(q * s.C + c) = trace_word(stored_code(s, fs0, code), fs0.state0);
         }
       if (!codes_ok) { write_invalid(out); return; }
       LaneLds lds;
       lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
       double T, z[kMaxDims];
       uint32_t ex[kMaxDims];
-      if (simulate_trace_fast(s, Q, epack, scf, rg, lds, out, busy != nullptr, T, z, ex)) {
+      if (simulate_trace_fast(s, Q, epack, fs0.state0, fs0.rs_only, scf, rg, lds, out, T, z, ex)) {
         t_done[i] = T;
         if (busy) {
 #pragma unroll
@@ -315,7 +316,7 @@ __device__ __noinline__ void sweep_generic_evaluation(const Scenario& s, double 
                                                       const SimOut& out) {
   double load[kMaxDims];
 #pragma unroll
-  for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? s.fix[k] + s.fix[k] : inf64();
+  for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? tracker_start(s, k) : inf64();
   for (uint32_t c = 0; c < s.C; ++c) {
     uint32_t code = schedule_chunk(s, chunk, themis_on, rel, th, load);
     size_t at = (size_t)c * w.stride + e;
@@ -349,6 +350,7 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
   const bool scf = bit == 2;
 
   Scenario s = load_scenario(b, i);
+  s.ctype = THEMIS_COLL_ALL_REDUCE;  // sweeps evaluate All-Reduce only
   const bool rel = b.threshold_mode == THEMIS_THR_REL;
   const double th = thr_per_scenario ? thr[(size_t)a * b.n + i] : thr[a];
   const double S = b.size_bytes[i];
@@ -362,7 +364,7 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
     double load[kMaxDims];
     plan_fast(s, fs, themis_on, rel, th, load,
-              [&](uint32_t c, uint32_t code) { L::init_chunk(lds, c, code); });
+              [&](uint32_t c, uint32_t code) { L::init_chunk(lds, c, code, 0u); });
     FastOut fo;
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;

@@ -47,6 +47,7 @@ struct Scenario {
   double coef[kMaxDims];  // seconds per resident byte: ((P-1)/P)/bw  (Sec. 4.5)
   double fix[kMaxDims];   // fixed delay per stage on the dimension (A_K of Sec. 4.5), 0 if none
   bool has_fix;           // the batch carries fixed delays
+  int ctype;              // THEMIS_COLL_*
   bool valid;
 };
 
@@ -57,6 +58,8 @@ __device__ __forceinline__ Scenario load_scenario(const themis_batch_t& b, uint6
   s.C = b.chunks[i];
   s.valid = (s.D >= 1 && s.D <= kMaxDims) && (s.C >= 1u && s.C <= b.max_chunks);
   s.has_fix = b.fixed_delay != nullptr;
+  s.ctype = b.collective_type ? (int)b.collective_type[i] : THEMIS_COLL_ALL_REDUCE;
+  if (s.ctype > THEMIS_COLL_ALL_GATHER) { s.valid = false; s.ctype = THEMIS_COLL_ALL_REDUCE; }
 #pragma unroll
   for (int k = 0; k < kMaxDims; ++k) {
     uint32_t p = b.npus[(size_t)k * b.n + i];
@@ -91,6 +94,21 @@ __device__ __forceinline__ bool order_code_ok(uint32_t code, int D) {
   return ok;
 }
 
+// Order code with its D fields reversed.
+__device__ __forceinline__ uint32_t reverse_code(uint32_t code, int D) {
+  uint32_t r = 0;
+#pragma unroll
+  for (int j = 0; j < kMaxDims; ++j)
+    if (j < D) r |= ((code >> (2 * j)) & 3u) << (2 * (D - 1 - j));
+  return r;
+}
+
+// Tracker contents before the first chunk: the fixed delay A_K of the
+// collective type (Sec. 4.5), i.e. one stage per dimension, two for All-Reduce.
+__device__ __forceinline__ double tracker_start(const Scenario& s, int k) {
+  return s.ctype == THEMIS_COLL_ALL_REDUCE ? s.fix[k] + s.fix[k] : s.fix[k];
+}
+
 // One step of Alg. 1's Scheduler.Schedule for the chunk that comes next, given
 // the Dim Load Tracker contents load[0..3] (unused dimensions hold +inf on
 // entry and are left untouched).  Returns the order code and adds the chunk's
@@ -112,10 +130,13 @@ __device__ __forceinline__ uint32_t schedule_chunk(const Scenario& s, double chu
       if (load[k] > hi) hi = load[k];
     }
   }
+  const bool gather = s.ctype == THEMIS_COLL_ALL_GATHER;
   double t = thr;
   if (rel) {
     double cmin = sel4(kmin, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
-    t = thr * (chunk * cmin);
+    double whole = chunk;
+    if (gather) whole = chunk * (double)sel4(kmin, s.P[0], s.P[1], s.P[2], s.P[3]);
+    t = thr * (whole * cmin);
   }
   uint32_t code = 0xE4u;  // identity 0,1,2,3
   if (themis && !((hi - lo) < t)) {
@@ -136,21 +157,24 @@ __device__ __forceinline__ uint32_t schedule_chunk(const Scenario& s, double chu
     for (int k = 0; k < kMaxDims; ++k) code |= (uint32_t)k << (2 * rank[k]);
   }
   code &= (1u << (2 * D)) - 1u;
+  if (gather) code = reverse_code(code, D);  // descending loads, dimD..dim1 when tied
 
   // latency model + tracker update along the chosen order
+  const bool twice = s.ctype == THEMIS_COLL_ALL_REDUCE;  // RS now and AG later on the same bytes
   double x = chunk;
 #pragma unroll
   for (int j = 0; j < kMaxDims; ++j) {
     if (j < D) {
       int k = (code >> (2 * j)) & 3;
       double ck = sel4(k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
-      uint32_t pk = sel4(k, s.P[0], s.P[1], s.P[2], s.P[3]);
+      double pk = (double)sel4(k, s.P[0], s.P[1], s.P[2], s.P[3]);
+      if (gather) x = x * pk;
       double tj = x * ck;
-      double add = tj + tj;
+      double add = twice ? tj + tj : tj;
 #pragma unroll
       for (int kk = 0; kk < kMaxDims; ++kk)
         if (kk == k) load[kk] = load[kk] + add;
-      x = x / (double)pk;
+      if (!gather) x = x / pk;
     }
   }
   return code;

@@ -59,13 +59,14 @@ struct Layout64 {
   static constexpr uint32_t kEnd = 0xffu;
   using Link = uint8_t;               // width of a chunk id in LDS
   using Ids = Pack4<uint32_t, 8>;     // chunk id / operation count per dimension
-  static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code) {
-    *(uint32_t*)l.dword(c) = (code << 16) | (kEnd << 8);  // mask 0, Reduce-Scatter phase
+  static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
+                                                    uint32_t state0) {
+    *(uint32_t*)l.dword(c) = (code << 16) | (kEnd << 8) | state0;
   }
   static __device__ __forceinline__ uint32_t code(uint32_t w) { return (w >> 16) & 0xffu; }
   static __device__ __forceinline__ uint32_t next(uint32_t w) { return (w >> 8) & 0xffu; }
-  static __device__ __forceinline__ uint32_t first_dim(const LaneLds& l, uint32_t c) {
-    return l.dword(c)[2] & 3u;
+  static __device__ __forceinline__ uint32_t code_of(const LaneLds& l, uint32_t c) {
+    return l.dword(c)[2];
   }
   // new state of chunk c (whole dword w known), end of its list
   static __device__ __forceinline__ void store_state(uint8_t* cp, uint32_t, uint32_t state) {
@@ -89,13 +90,14 @@ struct LayoutWide {
   static constexpr uint32_t kEnd = 0xffffu;
   using Link = uint16_t;
   using Ids = Pack4<uint64_t, 16>;
-  static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code) {
-    *(uint32_t*)l.dword(c) = (code << 8) | (kEnd << 16);
+  static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
+                                                    uint32_t state0) {
+    *(uint32_t*)l.dword(c) = (code << 8) | (kEnd << 16) | state0;
   }
   static __device__ __forceinline__ uint32_t code(uint32_t w) { return (w >> 8) & 0xffu; }
   static __device__ __forceinline__ uint32_t next(uint32_t w) { return w >> 16; }
-  static __device__ __forceinline__ uint32_t first_dim(const LaneLds& l, uint32_t c) {
-    return l.dword(c)[1] & 3u;
+  static __device__ __forceinline__ uint32_t code_of(const LaneLds& l, uint32_t c) {
+    return l.dword(c)[1];
   }
   static __device__ __forceinline__ void store_state(uint8_t* cp, uint32_t w, uint32_t state) {
     *(uint32_t*)cp = state | (w & 0xff00u) | (kEnd << 16);
@@ -112,13 +114,47 @@ struct LayoutWide {
 };
 
 // Per-evaluation constants of the fast path.
+//
+// Collective types share one machine.  A chunk's state is (mask of dimensions
+// it is currently reduced on, phase); a Reduce-Scatter stage on k sets bit k,
+// an All-Gather stage clears it, and the resident size is base * 2^-E(mask).
+//   All-Reduce     : starts at (0, RS), base = chunk, ends when an AG stage
+//                    empties the mask.
+//   Reduce-Scatter : the same, but ends when the mask is full.
+//   All-Gather     : starts at (full, AG) with base = chunk * 2^Etot, so the
+//                    resident size starts at chunk and doubles back up; the
+//                    AG half walks a code from its last field to its first,
+//                    so the chunk words hold the order code reversed.
 struct FastScenario {
   uint32_t epack;   // e_k = log2 P_k in byte k (0 for unused dimensions)
   uint32_t etot;    // sum of e_k
   double chunk;     // bytes per chunk (normal binary64, exponent > etot)
+  double base;      // resident size at mask 0: chunk, or chunk * 2^etot for All-Gather
+  uint32_t state0;  // initial mask | phase << 4
+  bool rs_only;     // stand-alone Reduce-Scatter
+  bool gather;      // stand-alone All-Gather
 };
 
 __device__ __forceinline__ bool is_pow2(uint32_t p) { return (p & (p - 1u)) == 0u; }
+
+// x * 2^e for a normal x whose exponent stays in range.
+__device__ __forceinline__ double scale_up(double x, uint32_t e) {
+  int hi = __double2hiint(x) + (int)(e << 20);
+  return __hiloint2double(hi, __double2loint(x));
+}
+
+// x * 2^-e for a normal x whose exponent stays in range (checked above).
+__device__ __forceinline__ double scale_down(double x, uint32_t e) {
+  int hi = __double2hiint(x) - (int)(e << 20);
+  return __hiloint2double(hi, __double2loint(x));
+}
+
+// Sum of e_k over the dimensions in mask.
+__device__ __forceinline__ uint32_t esum(uint32_t epack, uint32_t mask) {
+  uint32_t spread = (mask * 0x00204081u) & 0x01010101u;  // bit k -> byte k
+  uint32_t sel = (spread * 0xffu) & epack;
+  return __builtin_amdgcn_sad_u8(sel, 0u, 0u);            // add the four bytes
+}
 
 // Can this scenario take the fast path?  Fills fs when it can.
 __device__ __forceinline__ bool fast_eligible(const Scenario& s, double chunk, uint32_t cap,
@@ -134,26 +170,23 @@ __device__ __forceinline__ bool fast_eligible(const Scenario& s, double chunk, u
       et += e;
     }
   }
-  // every halving must stay a normal number: biased exponent - etot >= 1
+  // every halving (doubling, for an All-Gather) must stay a normal number
   uint32_t ex = (uint32_t)((__double_as_longlong(chunk) >> 52) & 0x7ff);
-  ok = ok && ex < 0x7ffu && ex > et;
+  fs.gather = s.ctype == THEMIS_COLL_ALL_GATHER;
+  fs.rs_only = s.ctype == THEMIS_COLL_REDUCE_SCATTER;
+  ok = ok && ex < 0x7ffu && (fs.gather ? ex + et < 0x7ffu : ex > et);
   fs.epack = ep;
   fs.etot = et;
   fs.chunk = chunk;
+  fs.base = fs.gather ? scale_up(chunk, ok ? et : 0u) : chunk;
+  fs.state0 = fs.gather ? (((1u << s.D) - 1u) | 16u) : 0u;
   return ok;
 }
 
-// x * 2^-e for a normal x whose exponent stays in range (checked above).
-__device__ __forceinline__ double scale_down(double x, uint32_t e) {
-  int hi = __double2hiint(x) - (int)(e << 20);
-  return __hiloint2double(hi, __double2loint(x));
-}
-
-// Sum of e_k over the dimensions in mask.
-__device__ __forceinline__ uint32_t esum(uint32_t epack, uint32_t mask) {
-  uint32_t spread = (mask * 0x00204081u) & 0x01010101u;  // bit k -> byte k
-  uint32_t sel = (spread * 0xffu) & epack;
-  return __builtin_amdgcn_sad_u8(sel, 0u, 0u);            // add the four bytes
+// The order code as the chunk words hold it (see FastScenario).
+__device__ __forceinline__ uint32_t stored_code(const Scenario& s, const FastScenario& fs,
+                                                uint32_t code) {
+  return fs.gather ? reverse_code(code, s.D) : code;
 }
 
 // ---------------------------------------------------------------------------
@@ -171,21 +204,26 @@ __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario&
   for (int k = 0; k < kMaxDims; ++k) {
     e[k] = (fs.epack >> (8 * k)) & 0xffu;
     coef[k] = (k < D) ? s.coef[k] : 0.0;   // unused dimensions: zero time, load stays +inf
-    load[k] = (k < D) ? s.fix[k] + s.fix[k] : inf64();  // tracker starts at A_K
+    load[k] = (k < D) ? tracker_start(s, k) : inf64();  // tracker starts at A_K
   }
   const uint32_t field_mask = (1u << (2 * D)) - 1u;
   for (uint32_t c = 0; c < s.C; ++c) {
     // least / most loaded dimension, ties to the lower index
     double lo = load[0], hi = load[0], cmin = coef[0];
+    uint32_t emin = e[0];
 #pragma unroll
     for (int k = 1; k < kMaxDims; ++k) {
       bool used = k < D;
       bool less = used && load[k] < lo;
       lo = less ? load[k] : lo;
       cmin = less ? coef[k] : cmin;
+      emin = less ? e[k] : emin;
       hi = (used && load[k] > hi) ? load[k] : hi;
     }
-    double t = rel ? thr * (fs.chunk * cmin) : thr;
+    // a whole-chunk stage on the least-loaded dimension: an All-Gather moves
+    // the grown size chunk * P
+    const double whole = fs.gather ? scale_up(fs.chunk, emin) : fs.chunk;
+    double t = rel ? thr * (whole * cmin) : thr;
     bool sort = themis && !((hi - lo) < t);
     // after[a][b] (a < b): does a come after b in the chosen order?
     // stable ascending sort: only when a's load is strictly larger.
@@ -206,14 +244,33 @@ __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario&
     uint32_t E1 = (b01 ? e[0] : 0u) + (b21 ? e[2] : 0u) + (b31 ? e[3] : 0u);
     uint32_t E2 = (b02 ? e[0] : 0u) + (b12 ? e[1] : 0u) + (b32 ? e[3] : 0u);
     uint32_t E3 = (b03 ? e[0] : 0u) + (b13 ? e[1] : 0u) + (b23 ? e[2] : 0u);
-    double t0 = scale_down(fs.chunk, E0) * coef[0];
-    double t1 = scale_down(fs.chunk, E1) * coef[1];
-    double t2 = scale_down(fs.chunk, E2) * coef[2];
-    double t3 = scale_down(fs.chunk, E3) * coef[3];
-    load[0] = load[0] + (t0 + t0);
-    load[1] = load[1] + (t1 + t1);
-    load[2] = load[2] + (t2 + t2);
-    load[3] = load[3] + (t3 + t3);
+    double t0, t1, t2, t3;
+    if (fs.gather) {
+      // the All-Gather visits the dimensions in the reverse order: the ones
+      // after k in the ascending order are gathered before it, and its stage
+      // moves the size grown by P_k as well:  E(after k) + e_k = etot - E(before k)
+      code = reverse_code(code, D);
+      t0 = scale_up(fs.chunk, fs.etot - E0) * coef[0];
+      t1 = scale_up(fs.chunk, fs.etot - E1) * coef[1];
+      t2 = scale_up(fs.chunk, fs.etot - E2) * coef[2];
+      t3 = scale_up(fs.chunk, fs.etot - E3) * coef[3];
+    } else {
+      t0 = scale_down(fs.chunk, E0) * coef[0];
+      t1 = scale_down(fs.chunk, E1) * coef[1];
+      t2 = scale_down(fs.chunk, E2) * coef[2];
+      t3 = scale_down(fs.chunk, E3) * coef[3];
+    }
+    if (s.ctype == THEMIS_COLL_ALL_REDUCE) {
+      load[0] = load[0] + (t0 + t0);
+      load[1] = load[1] + (t1 + t1);
+      load[2] = load[2] + (t2 + t2);
+      load[3] = load[3] + (t3 + t3);
+    } else {
+      load[0] = load[0] + t0;
+      load[1] = load[1] + t1;
+      load[2] = load[2] + t2;
+      load[3] = load[3] + t3;
+    }
     emit(c, code);
   }
 }
@@ -307,9 +364,15 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
     work |= 1u << (q >> 4);
   };
 
-  // a6: every chunk waits at the dimension of its first stage, resident size
-  // = chunk (mask 0, the lowest class), in chunk-id order
-  for (uint32_t c = 0; c < C; ++c) push(16u * L::first_dim(lds, c), c);
+  // a6: every chunk waits at the dimension of its first stage, in chunk-id
+  // order, in the class of the initial mask
+  {
+    const uint32_t mask0 = fs.state0 & 15u, phase0 = fs.state0 >> 4;
+    const uint32_t pos0 = 2u * ((uint32_t)__builtin_popcount(mask0) - phase0);
+    const uint32_t cls0 = (uint32_t)(ranktab >> (4u * mask0)) & 15u;
+    for (uint32_t c = 0; c < C; ++c)
+      push(16u * ((L::code_of(lds, c) >> pos0) & 3u) + cls0, c);
+  }
 
   double now = 0.0;
   const uint32_t max_steps = 2u * D * C + 8u;
@@ -337,7 +400,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
       // k; the All-Gather reuses it (mask still contains k then)
       const uint32_t ek = (fs.epack >> (8u * k)) & 0xffu;
       const uint32_t E = esum(fs.epack, mask) - (phase ? ek : 0u);
-      double t = scale_down(fs.chunk, E) *
+      double t = scale_down(fs.base, E) *
                  sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
       if (kFix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
       const double f = now + t;
@@ -397,7 +460,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
       uint32_t phase = (w >> 4) & 1u;
       // a Reduce-Scatter sets the dimension's bit, an All-Gather clears it
       const uint32_t mask = (w & 15u) ^ (1u << k);
-      const bool finished = phase != 0u && mask == 0u;
+      const bool finished = (phase != 0u && mask == 0u) || (fs.rs_only && mask == full);
       phase |= (mask == full) ? 1u : 0u;  // last Reduce-Scatter: All-Gather starts on the same dim
       if (!finished) {
         // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]

@@ -70,7 +70,11 @@ __device__ void simulate_generic(const Scenario& s, uint32_t Q, bool scf, const 
   const int D = s.D;
   const uint32_t C = s.C;
   const uint32_t G = Q * C;
-  const int last_stage = 2 * D;
+  const bool all_reduce = s.ctype == THEMIS_COLL_ALL_REDUCE;
+  const bool gather = s.ctype == THEMIS_COLL_ALL_GATHER;
+  // an All-Reduce runs D Reduce-Scatter and D All-Gather stages (the latter in
+  // reverse order), the stand-alone collectives only their own D
+  const int last_stage = all_reduce ? 2 * D : D;
 
   int serving[kMaxDims] = {-1, -1, -1, -1};
   double finish[kMaxDims] = {0.0, 0.0, 0.0, 0.0};
@@ -98,7 +102,7 @@ __device__ void simulate_generic(const Scenario& s, uint32_t Q, bool scf, const 
         int stage = (int)(m & 15u);
         if (stage >= last_stage || (m & kMetaRunning)) continue;
         uint32_t code = (m >> 8) & 0xFFu;
-        int pos = stage < D ? stage : last_stage - 1 - stage;
+        int pos = stage < D ? stage : 2 * D - 1 - stage;
         int k = (int)((code >> (2 * pos)) & 3u);
         if (sel4(k, serving[0], serving[1], serving[2], serving[3]) >= 0) continue;
         double arr = w.arrival[at];
@@ -127,10 +131,12 @@ __device__ void simulate_generic(const Scenario& s, uint32_t Q, bool scf, const 
           // the current size; the All-Gather reuses the same product, so the
           // Reduce-Scatter size is replayed from the chunk size.
           double x;
-          if (stage < D) {
+          if (gather) {
+            x = w.size[at] * (double)s.P[k];  // a stand-alone All-Gather moves the grown size
+          } else if (stage < D) {
             x = w.size[at];
           } else {
-            int pos = last_stage - 1 - stage;
+            int pos = 2 * D - 1 - stage;
             x = chunk_of(g / C);
             for (int j = 0; j < pos; ++j) {
               int kj = (int)((code >> (2 * j)) & 3u);
@@ -143,7 +149,8 @@ __device__ void simulate_generic(const Scenario& s, uint32_t Q, bool scf, const 
           busy[k] = busy[k] + t;
           serving[k] = (int)g;
           w.meta[at] = m | kMetaRunning;
-          if (out.queue_order) put_entry(out, k, executed[k], (g << 1) | (stage >= D ? 1u : 0u));
+          if (out.queue_order)
+            put_entry(out, k, executed[k], (g << 1) | ((gather || stage >= D) ? 1u : 0u));
           executed[k]++;
         }
       }
@@ -171,7 +178,7 @@ __device__ void simulate_generic(const Scenario& s, uint32_t Q, bool scf, const 
         int stage = (int)(m & 15u);
         double sz = w.size[at];
         double pk = (double)s.P[k];
-        sz = (stage < D) ? sz / pk : sz * pk;
+        sz = (!gather && stage < D) ? sz / pk : sz * pk;
         w.size[at] = sz;
         w.arrival[at] = now;
         w.meta[at] = (m & ~(15u | kMetaRunning)) | (uint32_t)(stage + 1);

@@ -81,7 +81,9 @@ struct TraceRegion {
 
 // Chunk dword: bits 0-3 reduced-dims mask, bit 4 phase, bits 8-15 order code,
 // bits 16-31 next chunk in its list (kNoChunk = last).
-__device__ __forceinline__ uint32_t trace_word(uint32_t code) { return (code << 8) | (kNoChunk << 16); }
+__device__ __forceinline__ uint32_t trace_word(uint32_t code, uint32_t state0) {
+  return state0 | (code << 8) | (kNoChunk << 16);
+}
 
 // Ranks of all resident sizes: a merge of the 2^D sorted lists
 // { chunk_q * 2^-E(mask) : q in ascending chunk order }, one list per mask.
@@ -135,12 +137,14 @@ __device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, 
 
 constexpr uint32_t kTraceLdsWords = 48;  // per lane, for trace_build_ranks
 
-// Runs the simulation of one trace.  The region must hold CH[q] (chunk bytes
-// of every collective) and W[g] = trace_word(code) for g = q*C + i.
+// Runs the simulation of one trace.  The region must hold CH[q] (resident
+// bytes at mask 0 of a chunk of collective q) and W[g] = trace_word(stored
+// code, state0) for g = q*C + i; state0 / rs_only as in FastScenario.
 // Returns false if time failed to advance somewhere (generic path decides).
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
-                                           bool scf, const TraceRegion& rg, const LaneLds& lds,
-                                           const SimOut& out, bool want_busy, double& t_done,
+                                           uint32_t state0, bool rs_only, bool scf,
+                                           const TraceRegion& rg, const LaneLds& lds,
+                                           const SimOut& out, double& t_done,
                                            double (&busy)[kMaxDims],
                                            uint32_t (&executed_out)[kMaxDims]) {
   const uint32_t D = (uint32_t)s.D;
@@ -204,8 +208,13 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     return h;
   };
 
-  // a6: every chunk waits at the dimension of its first stage (mask 0)
-  for (uint32_t g = 0; g < G; ++g) push((rg.W(g) >> 8) & 3u, rank_of(g, 0u), g);
+  // a6: every chunk waits at the dimension of its first stage (initial mask)
+  {
+    const uint32_t mask0 = state0 & 15u, phase0 = state0 >> 4;
+    const uint32_t pos0 = 2u * ((uint32_t)__builtin_popcount(mask0) - phase0);
+    for (uint32_t g = 0; g < G; ++g)
+      push((rg.W(g) >> (8u + pos0)) & 3u, rank_of(g, mask0), g);
+  }
 
   double now = 0.0;
   const uint64_t max_steps = (uint64_t)2u * D * G + 8u;
@@ -262,7 +271,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       const uint32_t code = (w >> 8) & 0xffu;
       uint32_t phase = (w >> 4) & 1u;
       const uint32_t mask = (w & 15u) ^ (1u << k);
-      const bool finished = phase != 0u && mask == 0u;
+      const bool finished = (phase != 0u && mask == 0u) || (rs_only && mask == full);
       phase |= (mask == full) ? 1u : 0u;
       if (!finished) {
         const uint32_t p = (uint32_t)__builtin_popcount(mask) - phase;
@@ -276,7 +285,6 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   t_done = now;
 #pragma unroll
   for (uint32_t kk = 0; kk < 4u; ++kk) { busy[kk] = z[kk]; executed_out[kk] = executed[kk]; }
-  (void)want_busy;
   return !stalled;
 }
 

@@ -23,6 +23,7 @@ INTER_BASELINE, INTER_THEMIS = 0, 1
 INTRA_FIFO, INTRA_SCF = 0, 1
 THR_ABS, THR_REL = 0, 1
 SWEEP_BASELINE, SWEEP_THEMIS_FIFO, SWEEP_THEMIS_SCF = 1, 2, 4
+COLL_ALL_REDUCE, COLL_REDUCE_SCATTER, COLL_ALL_GATHER = 0, 1, 2
 
 SEED_BASE = 0x211004478
 MIB = float(2 ** 20)
@@ -48,6 +49,7 @@ class ScenarioBatch:
     coll_size: Optional[np.ndarray] = None     # f64 [max_coll, n]
     release_time: Optional[np.ndarray] = None  # f64 [max_coll, n]
     fixed_delay: Optional[np.ndarray] = None   # f64 [4, n] seconds per stage, or None
+    collective_type: Optional[np.ndarray] = None  # u8 [n] COLL_*, or None (All-Reduce)
 
     @property
     def slots(self) -> int:
@@ -72,7 +74,9 @@ class ScenarioBatch:
             max_coll=self.max_coll,
             n_coll=None if self.n_coll is None else self.n_coll[idx].copy(),
             coll_size=opt(self.coll_size), release_time=opt(self.release_time),
-            fixed_delay=opt(self.fixed_delay))
+            fixed_delay=opt(self.fixed_delay),
+            collective_type=(None if self.collective_type is None
+                             else self.collective_type[idx].copy()))
 
 
 def make_batch(ndims, npus, bw, size_bytes, chunks, inter_policy, intra_policy,

@@ -355,3 +355,26 @@ def test_metrics_match_oracle(gpu, oracle):
         assert np.all((u > 0) & (u <= 1 + 1e-12))
         # T >= Ideal (equality up to rounding for one dimension of two NPUs)
         assert np.all(t.cpu().numpy() >= ideal.cpu().numpy() * (1 - 1e-12))
+
+
+def _with_collective_types(b, seed):
+    b.collective_type = np.random.default_rng(seed).integers(0, 3, b.n).astype(np.uint8)
+    return b
+
+
+def test_stand_alone_reduce_scatter_and_all_gather(gpu, oracle):
+    """Alg. 1's CollectiveType per scenario, on every path."""
+    W = w()
+    check_batch(gpu, oracle, _with_collective_types(W.mixed(1000, seed=71), 1))
+    check_batch(gpu, oracle, _with_collective_types(W.mixed(1000, seed=72, thr_mode=0), 2))
+    check_batch(gpu, oracle, _with_collective_types(W.mixed(400, seed=73, pow2=False), 3))
+    check_batch(gpu, oracle, _with_collective_types(W.mixed(150, seed=74, max_chunks=300), 4))
+    check_batch(gpu, oracle, _with_collective_types(_with_fixed_delay(W.mixed(500, seed=75), 6), 5))
+    check_batch(gpu, oracle, _with_collective_types(W.config5(n=90, n_coll=8), 7))
+    b = _with_collective_types(W.config3(n=3000), 8)
+    check_batch(gpu, oracle, b)
+    b = W.mixed(128, seed=76)
+    b.collective_type = np.full(b.n, 1, np.uint8)
+    b.collective_type[5] = 3               # not a collective type -> invalid scenario
+    t = check_batch(gpu, oracle, b)
+    assert np.isnan(t[5]) and np.isfinite(t[4])
