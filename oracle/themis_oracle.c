@@ -592,3 +592,99 @@ void to_metrics_batch(uint64_t n, uint64_t begin, uint64_t end,
     to_metrics(D, b, total, t_done[i], tr, &utilization[i], &ideal[i]);
   }
 }
+
+/* ------------------------------------------------------------------------ */
+/* Exhaustive search (Sec. 4.1, observation 2): every chunk may take any of
+ * the D! dimension orders, so a collective has (D!)^C schedules once the
+ * All-Gather order of an All-Reduce is tied to the reverse of its
+ * Reduce-Scatter order.  For tiny C all of them are simulated; the best
+ * completion time and the first assignment that reaches it are returned.
+ *
+ * Assignment number a gives chunk c the permutation with lexicographic index
+ * (a / (D!)^c) mod D! of (0, 1, .., D-1).
+ * Returns 1 on success; 0 if the inputs are invalid or (D!)^C > max_assign. */
+/* ------------------------------------------------------------------------ */
+static void nth_permutation(int ndims, uint32_t idx, int *dims)
+{
+  int pool[TO_MAX_DIMS] = {0, 1, 2, 3};
+  uint32_t fact = 1;
+  for (int j = 2; j < ndims; ++j) fact *= (uint32_t)j; /* (D-1)! */
+  for (int j = 0; j < ndims; ++j) {
+    uint32_t pick = idx / fact;
+    idx %= fact;
+    dims[j] = pool[pick];
+    for (int m = (int)pick; m < ndims - 1 - j; ++m) pool[m] = pool[m + 1];
+    if (ndims - 1 - j > 0) fact /= (uint32_t)(ndims - 1 - j);
+  }
+}
+
+int to_search(int ndims, const uint32_t *npus, const double *bw,
+              const double *fixed_delay, int ctype, double size_bytes,
+              uint32_t C, int intra_policy, uint64_t max_assign, double *best_t,
+              uint8_t *best_orders, uint64_t *n_assign)
+{
+  if (!to_network_valid(ndims, npus, bw) || C < 1u) return 0;
+  uint64_t F = 1;
+  for (int j = 2; j <= ndims; ++j) F *= (uint64_t)j;
+  uint64_t total = 1;
+  for (uint32_t c = 0; c < C; ++c) {
+    if (total > max_assign / F) return 0; /* too many schedules */
+    total *= F;
+  }
+  uint8_t *od = (uint8_t *)malloc(C);
+  double best = INFINITY;
+  int any = 0;
+  for (uint64_t a = 0; a < total; ++a) {
+    uint64_t rest = a;
+    for (uint32_t c = 0; c < C; ++c) {
+      int dims[TO_MAX_DIMS];
+      nth_permutation(ndims, (uint32_t)(rest % F), dims);
+      rest /= F;
+      od[c] = encode_order(ndims, dims);
+    }
+    double T;
+    if (!to_simulate(ndims, npus, bw, fixed_delay, ctype, 1u, &size_bytes, NULL,
+                     C, intra_policy, od, &T, NULL, NULL, NULL)) {
+      free(od);
+      return 0;
+    }
+    if (!any || T < best) { /* strict: the first best assignment wins */
+      best = T;
+      any = 1;
+      memcpy(best_orders, od, C);
+    }
+  }
+  free(od);
+  *best_t = best;
+  if (n_assign) *n_assign = total;
+  return 1;
+}
+
+/* best_t [n], best_orders [n][max_chunks] (0xFF padded / on failure) */
+void to_search_batch(uint64_t n, uint64_t begin, uint64_t end,
+                     uint32_t max_chunks, const uint8_t *ndims,
+                     const uint32_t *npus, const double *bw,
+                     const double *size_bytes, const uint32_t *chunks,
+                     const uint8_t *intra_policy, const double *fixed_delay,
+                     const uint8_t *collective_type, uint64_t max_assign,
+                     double *best_t, uint8_t *best_orders)
+{
+  for (uint64_t i = begin; i < end; ++i) {
+    uint32_t p[TO_MAX_DIMS];
+    double b[TO_MAX_DIMS], fx[TO_MAX_DIMS];
+    gather_network(n, i, npus, bw, p, b);
+    const double *fixed = gather_fixed(n, i, fixed_delay, fx);
+    uint8_t *row = best_orders + (size_t)i * max_chunks;
+    memset(row, 0xFF, max_chunks);
+    uint32_t C = chunks[i];
+    double T = NAN;
+    int ok = (C >= 1u && C <= max_chunks);
+    if (ok)
+      ok = to_search((int)ndims[i], p, b, fixed,
+                     collective_type ? (int)collective_type[i] : TO_ALL_REDUCE,
+                     size_bytes[i], C, (int)intra_policy[i], max_assign, &T, row,
+                     NULL);
+    if (!ok) { T = NAN; memset(row, 0xFF, max_chunks); }
+    best_t[i] = T;
+  }
+}

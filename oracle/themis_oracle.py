@@ -53,6 +53,10 @@ def lib():
         L.to_metrics_batch.argtypes = [
             C.c_uint64, C.c_uint64, C.c_uint64, _u8p, _f64p, _f64p, C.c_uint32,
             _u32p, _f64p, _f64p, _f64p, _f64p, _f64p]
+        L.to_search_batch.restype = None
+        L.to_search_batch.argtypes = [
+            C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, _u8p, _u32p, _f64p,
+            _f64p, _u32p, _u8p, _f64p, _u8p, C.c_uint64, _f64p, _u8p]
         L.to_latency_coef.restype = None
         L.to_latency_coef.argtypes = [C.c_int, _u32p, _f64p, _f64p]
         _lib = L
@@ -257,3 +261,22 @@ def metrics_batch(b, t_done, transfer, threads=1):
                                _p(util, _f64p), _p(ideal, _f64p))
     _fan_out(run, b.n, threads)
     return util, ideal
+
+
+def search_batch(b, max_assignments, threads=1):
+    """Exhaustive search over per-chunk orders -> (best_t f64[n], best_orders u8[n, max_chunks])."""
+    best_t = np.empty(b.n)
+    best_orders = np.empty((b.n, b.max_chunks), np.uint8)
+    a = dict(ndims=_arr(b.ndims, np.uint8), npus=_arr(b.npus, np.uint32),
+             bw=_arr(b.bw, np.float64), size=_arr(b.size_bytes, np.float64),
+             chunks=_arr(b.chunks, np.uint32), intra=_arr(b.intra_policy, np.uint8))
+    fx, ct = _fixed(b), _ctype(b)
+
+    def run(lo, hi):
+        lib().to_search_batch(
+            b.n, lo, hi, b.max_chunks, _p(a["ndims"], _u8p), _p(a["npus"], _u32p),
+            _p(a["bw"], _f64p), _p(a["size"], _f64p), _p(a["chunks"], _u32p),
+            _p(a["intra"], _u8p), _p(fx, _f64p), _p(ct, _u8p), int(max_assignments),
+            _p(best_t, _f64p), _p(best_orders, _u8p))
+    _fan_out(run, b.n, threads)
+    return best_t, best_orders

@@ -584,3 +584,50 @@ def test_stand_alone_collectives_plan_and_queue_rules(oracle, seed):
                                     fixed_delay=fx, ctype=ctype)
         assert Fraction(r["t_done"]) == T
         assert [Fraction(v) for v in r["busy"][:D]] == busy
+
+
+# ---------------------------------------------------------------- exhaustive search
+def test_exhaustive_search_against_python_enumeration(oracle):
+    """The search must return the minimum over all (D!)^C assignments
+    (Sec. 4.1) and the first assignment that reaches it; re-enumerated here
+    with itertools, every schedule's time taken from the independent checker."""
+    from paper_2110_04478_amd import workloads as W
+    rng = np.random.default_rng(77)
+    cases = [(2, 4), (3, 3), (2, 6), (4, 2), (1, 5)]
+    for D, C in cases:
+        P, bw = _rand_net(rng, D, dyadic=True)
+        S = float(C * 2 ** 22)
+        for intra in (0, 1):
+            b = W.make_batch([D], [P], [bw], S, C, 1, intra, 0.0)
+            best_t, best_orders = oracle.search_batch(b, math.factorial(D) ** C)
+            perms = [code_of(p) for p in itertools.permutations(range(D))]  # lexicographic
+            best, arg = None, None
+            # chunk 0 is the least significant digit of the assignment number
+            for rev in itertools.product(perms, repeat=C):
+                od = np.array(rev[::-1], dtype=np.uint8)
+                r = oracle.simulate(P, bw, [S], C, intra, od)
+                T, _ = rebuild_and_check(P, bw, [S], C, intra, od, r["queue_order"])
+                if best is None or T < best:
+                    best, arg = T, od
+            assert Fraction(best_t[0]) == best
+            assert best_orders[0, :C].tolist() == arg.tolist()
+            themis = oracle.plan(P, bw, S, C, 1)[0]
+            assert best_t[0] <= oracle.simulate(P, bw, [S], C, intra, themis)["t_done"]
+    # too many schedules for the given bound -> no answer
+    b = W.make_batch([3], [[4, 4, 4]], [[1e9, 1e9, 1e9]], 2.0 ** 24, 4, 1, 0, 0.0)
+    t, od = oracle.search_batch(b, 6 ** 4 - 1)
+    assert np.isnan(t[0]) and (od == 0xFF).all()
+
+
+def test_worked_example_optimum(oracle):
+    """4x4 worked example, 4 chunks: over all 2^4 assignments the best
+    schedule takes 8 units for both policies -- greedy Themis is optimal here,
+    and so is the baseline (derived; the paper's timing figure is not
+    available as text)."""
+    from paper_2110_04478_amd import workloads as W
+    B0 = 100e9
+    unit = 64 * MB * 0.75 / B0
+    for intra in (0, 1):
+        b = W.make_batch([2], [[4, 4]], [[B0, B0 / 2]], 256 * MB, 4, 1, intra, 0.0)
+        t, od = oracle.search_batch(b, 16)
+        assert t[0] / unit == pytest.approx(8.0, rel=1e-13)
