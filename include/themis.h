@@ -261,6 +261,33 @@ int themis_metrics_batch(const themis_batch_t *batch, const double *t_done,
                          const double *transfer, double *utilization,
                          double *ideal, void *stream);
 
+/*
+ * themis_search_batch -- exhaustive search over per-chunk dimension orders
+ * for tiny chunk counts (Sec. 4.1, observation 2: a collective of C chunks has
+ * (D!)^C schedules once an All-Reduce's All-Gather order is tied to the
+ * reverse of its Reduce-Scatter order), to measure how far the greedy
+ * scheduler is from the best schedule.
+ *
+ * Assignment number a (0 <= a < (D!)^C) gives chunk c the permutation of
+ * (0, 1, .., D-1) with lexicographic index (a / (D!)^c) mod D!.  Every
+ * assignment is simulated with the scenario's intra_policy (and fixed_delay /
+ * collective_type, if given); inter_policy and threshold are ignored.
+ *
+ *   max_assignments : upper bound on (D!)^C over the batch; a scenario with
+ *                     more schedules than this comes back as NaN / all-ones.
+ *   best_t      : [n] smallest completion time.
+ *   best_orders : [n][max_chunks] order codes of the first assignment (lowest
+ *                 a) that reaches it; slots >= chunks[i] are 0xFF.  May be NULL.
+ *   workspace   : themis_search_workspace_bytes(n, max_assignments) bytes
+ *                 (one time per scenario and assignment), required.
+ * Covers single collectives (n_coll == NULL) of at most 64 chunks with
+ * power-of-two NPU counts; other scenarios come back as NaN / all-ones.
+ */
+size_t themis_search_workspace_bytes(uint64_t n, uint64_t max_assignments);
+int themis_search_batch(const themis_batch_t *batch, uint64_t max_assignments,
+                        double *best_t, uint8_t *best_orders, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,11 @@ def lib():
                                             C.c_size_t, _vp]
         L.themis_metrics_batch.restype = C.c_int
         L.themis_metrics_batch.argtypes = [C.POINTER(_Batch), _vp, _vp, _vp, _vp, _vp]
+        L.themis_search_workspace_bytes.restype = C.c_size_t
+        L.themis_search_workspace_bytes.argtypes = [C.c_uint64, C.c_uint64]
+        L.themis_search_batch.restype = C.c_int
+        L.themis_search_batch.argtypes = [C.POINTER(_Batch), C.c_uint64, _vp, _vp, _vp,
+                                          C.c_size_t, _vp]
         L.themis_sweep.restype = C.c_int
         L.themis_sweep.argtypes = [C.POINTER(_Batch), C.c_int, _vp, C.c_int, C.c_uint, _vp,
                                    _vp, C.c_size_t, _vp]
@@ -219,6 +224,24 @@ def themis_metrics_batch(b: DeviceBatch, t_done: torch.Tensor, transfer: torch.T
     _check(lib().themis_metrics_batch(C.byref(s), _ptr(t_done), _ptr(transfer), _ptr(utilization),
                                       _ptr(ideal), _stream()))
     return utilization, ideal
+
+
+def themis_search_workspace_bytes(n: int, max_assignments: int) -> int:
+    return lib().themis_search_workspace_bytes(n, max_assignments)
+
+
+def themis_search_batch(b: DeviceBatch, max_assignments: int,
+                        workspace: Optional[torch.Tensor] = None):
+    """Exhaustive search over per-chunk orders -> (best_t f64[n], best_orders u8[n, max_chunks])."""
+    best_t = torch.empty(b.n, dtype=torch.float64, device=b.device)
+    best_orders = torch.empty((b.n, b.max_chunks), dtype=torch.uint8, device=b.device)
+    if workspace is None:
+        workspace = alloc_workspace(themis_search_workspace_bytes(b.n, max_assignments), b.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    s = b.c_struct()
+    _check(lib().themis_search_batch(C.byref(s), max_assignments, _ptr(best_t), _ptr(best_orders),
+                                     _ptr(workspace), ws_bytes, _stream()))
+    return best_t, best_orders
 
 
 def alloc_workspace(nbytes: int, device="cuda:0") -> Optional[torch.Tensor]:

@@ -383,6 +383,120 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
 }
 
 // ---------------------------------------------------------------------------
+// themis_search_batch: every assignment of dimension orders to chunks.
+// ---------------------------------------------------------------------------
+// Order code of the permutation of (0..D-1) with lexicographic index idx.
+__device__ __forceinline__ uint32_t nth_permutation_code(uint32_t D, uint32_t idx) {
+  uint32_t pool = 0x3210u;  // remaining dimensions, one nibble each, ascending
+  uint32_t code = 0;
+  uint32_t fact = D >= 4u ? 6u : D == 3u ? 2u : 1u;  // (D-1)!
+  for (uint32_t j = 0; j < D; ++j) {
+    const uint32_t pick = idx / fact;
+    idx -= pick * fact;
+    code |= ((pool >> (4u * pick)) & 3u) << (2u * j);
+    pool = (pool & ((1u << (4u * pick)) - 1u)) | ((pool >> (4u * (pick + 1u))) << (4u * pick));
+    const uint32_t left = D - 1u - j;
+    if (left > 1u) fact /= left;
+  }
+  return code;
+}
+
+__device__ __forceinline__ uint32_t factorial_u32(uint32_t D) {
+  return D >= 4u ? 24u : D == 3u ? 6u : D == 2u ? 2u : 1u;
+}
+
+// (D!)^C if it does not exceed bound, else 0.
+__device__ __forceinline__ uint64_t assignment_count(uint32_t D, uint32_t C, uint64_t bound) {
+  const uint64_t F = factorial_u32(D);
+  uint64_t total = 1;
+  for (uint32_t c = 0; c < C; ++c) {
+    if (total > bound / F) return 0;
+    total *= F;
+  }
+  return total;
+}
+
+// One lane per (scenario, assignment): times[i * max_assign + a].  Slots past
+// a scenario's own count hold +inf; NaN marks a scenario that cannot be searched.
+template <bool kFix>
+__global__ void __launch_bounds__(kBlock)
+search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ times) {
+  __shared__ uint32_t lds_block[Layout64::kLaneWords * kBlock];
+  const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= b.n * max_assign) return;
+  const uint64_t i = e / max_assign;
+  const uint64_t a = e - i * max_assign;
+  Scenario s = load_scenario(b, i);
+  const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
+  const double S = b.size_bytes[i];
+  FastScenario fs;
+  const bool ok = s.valid && finite_positive(S) &&
+                  fast_eligible(s, S / (double)s.C, Layout64::kCap, fs);
+  const uint64_t count = ok ? assignment_count((uint32_t)s.D, s.C, max_assign) : 0;
+  if (count == 0) { times[e] = nan64(); return; }
+  if (a >= count) { times[e] = inf64(); return; }
+  LaneLds lds;
+  lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+  const uint32_t F = factorial_u32((uint32_t)s.D);
+  uint64_t rest = a;
+  for (uint32_t c = 0; c < s.C; ++c) {
+    const uint64_t q = rest / F;
+    const uint32_t digit = (uint32_t)(rest - q * F);
+    rest = q;
+    Layout64::init_chunk(lds, c, stored_code(s, fs, nth_permutation_code((uint32_t)s.D, digit)),
+                         fs.state0);
+  }
+  FastOut fo;
+  fo.queue_order = nullptr;
+  fo.slots = b.max_chunks;
+  FastResult r = simulate_fast<Layout64, kNoQueueOrder, false, kFix>(s, fs, scf, lds, fo);
+  times[e] = r.ok ? r.t_done : nan64();
+}
+
+// One wavefront per scenario: smallest time and the lowest assignment number
+// that reaches it.
+__global__ void __launch_bounds__(kBlock)
+search_reduce_kernel(themis_batch_t b, uint64_t max_assign, const double* __restrict__ times,
+                     double* __restrict__ best_t, uint8_t* __restrict__ best_orders) {
+  const uint64_t i = blockIdx.x;
+  const double* row = times + i * max_assign;
+  double best = inf64();
+  uint64_t arg = ~0ull;
+  bool bad = false;
+  for (uint64_t a = threadIdx.x; a < max_assign; a += kBlock) {
+    const double t = row[a];
+    bad |= !(t == t);
+    if (t < best) { best = t; arg = a; }  // ascending a per lane: the first minimum stays
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    const double ob = __shfl_down(best, off);
+    const uint64_t oa = ((uint64_t)__shfl_down((uint32_t)(arg >> 32), off) << 32) |
+                        __shfl_down((uint32_t)arg, off);
+    const int obad = __shfl_down((int)bad, off);
+    bad |= obad != 0;
+    if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+  }
+  if (threadIdx.x != 0) return;
+  const uint32_t D = b.ndims[i], C = b.chunks[i];
+  const bool ok = !bad && arg != ~0ull && D >= 1u && D <= (uint32_t)kMaxDims && C <= b.max_chunks;
+  best_t[i] = ok ? best : nan64();
+  if (best_orders) {
+    uint8_t* out = best_orders + i * b.max_chunks;
+    const uint32_t F = factorial_u32(D);
+    uint64_t rest = arg;
+    for (uint32_t c = 0; c < b.max_chunks; ++c) {
+      uint32_t code = 0xFFu;
+      if (ok && c < C) {
+        const uint64_t q = rest / F;
+        code = nth_permutation_code(D, (uint32_t)(rest - q * F));
+        rest = q;
+      }
+      out[c] = (uint8_t)code;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // themis_metrics_batch: average bandwidth utilisation (Sec. 3) and Ideal
 // (Table 3) per scenario.
 // ---------------------------------------------------------------------------
@@ -484,7 +598,7 @@ using namespace themis;
 
 extern "C" {
 
-int themis_version(void) { return 101; }
+int themis_version(void) { return 102; }
 
 const char* themis_status_string(int status) {
   switch (status) {
@@ -582,6 +696,34 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                      n_pol, t_done, w, have_ws);
+  return launch_status();
+}
+
+size_t themis_search_workspace_bytes(uint64_t n, uint64_t max_assignments) {
+  return (size_t)n * max_assignments * sizeof(double);
+}
+
+int themis_search_batch(const themis_batch_t* batch, uint64_t max_assignments, double* best_t,
+                        uint8_t* best_orders, void* workspace, size_t workspace_bytes_given,
+                        void* stream) {
+  int st = check_batch(batch, true, false);
+  if (st != THEMIS_OK) return st;
+  if (batch->n_coll) return THEMIS_ERR_UNSUPPORTED;  // single collectives only
+  if (max_assignments < 1u) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (batch->n == 0) return THEMIS_OK;
+  if (!best_t) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (max_assignments > ((uint64_t)1 << 40) / batch->n) return THEMIS_ERR_UNSUPPORTED;
+  const uint64_t evals = batch->n * max_assignments;
+  if (evals > (uint64_t)0x7fffffff * kBlock || batch->n > 0x7fffffffull) return THEMIS_ERR_UNSUPPORTED;
+  if (!workspace || ((uintptr_t)workspace & 7u) ||
+      workspace_bytes_given < themis_search_workspace_bytes(batch->n, max_assignments))
+    return THEMIS_ERR_WORKSPACE;
+  double* times = (double*)workspace;
+  auto eval = batch->fixed_delay ? search_eval_kernel<true> : search_eval_kernel<false>;
+  hipLaunchKernelGGL(eval, dim3(blocks_for(evals)), dim3(kBlock), 0, (hipStream_t)stream, *batch,
+                     max_assignments, times);
+  hipLaunchKernelGGL(search_reduce_kernel, dim3((unsigned)batch->n), dim3(kBlock), 0,
+                     (hipStream_t)stream, *batch, max_assignments, times, best_t, best_orders);
   return launch_status();
 }
 

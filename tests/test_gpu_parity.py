@@ -378,3 +378,34 @@ def test_stand_alone_reduce_scatter_and_all_gather(gpu, oracle):
     b.collective_type[5] = 3               # not a collective type -> invalid scenario
     t = check_batch(gpu, oracle, b)
     assert np.isnan(t[5]) and np.isfinite(t[4])
+
+
+def test_exhaustive_search_matches_oracle(gpu, oracle):
+    """themis_search_batch: all (D!)^C assignments per scenario, best time and
+    the first assignment that reaches it."""
+    import torch
+    W = w()
+    rng = np.random.default_rng(8)
+    n = 150
+    D = rng.integers(1, 5, n)
+    C = np.array([int(rng.integers(1, {1: 9, 2: 9, 3: 5, 4: 4}[int(d)])) for d in D])
+    D[3], C[3] = 4, 8                     # 24^8 schedules: over the bound
+    P = [[int(2 ** rng.integers(1, 5)) for _ in range(d)] for d in D]
+    bw = [[float(rng.uniform(25e9, 400e9)) for _ in range(d)] for d in D]
+    b = W.make_batch(D, P, bw, np.floor(rng.uniform(2 ** 20, 2 ** 30, n)), C, 1,
+                     rng.integers(0, 2, n), 0.0, max_chunks=8)
+    b.collective_type = rng.integers(0, 3, n).astype(np.uint8)
+    bound = 24 ** 3
+    want_t, want_od = oracle.search_batch(b, bound, threads=8)
+    d = gpu.to_device(b)
+    got_t, got_od = gpu.themis_search_batch(d, bound)
+    torch.cuda.synchronize()
+    assert np.isnan(want_t[3])
+    assert_close("best_t", got_t.cpu().numpy(), want_t)
+    assert np.array_equal(got_od.cpu().numpy(), want_od)
+    # the greedy plan can never beat the exhaustive optimum
+    orders, _ = gpu.themis_plan_batch(d)
+    t, _, _ = gpu.themis_simulate_batch(d, orders, want_queue_order=False)
+    torch.cuda.synchronize()
+    ok = ~np.isnan(want_t)
+    assert np.all(t.cpu().numpy()[ok] >= want_t[ok])
