@@ -688,3 +688,43 @@ void to_search_batch(uint64_t n, uint64_t begin, uint64_t end,
     best_t[i] = T;
   }
 }
+
+/* ------------------------------------------------------------------------ */
+/* Bandwidth provisioning of a dimension pair (Sec. 6.3, with the balance
+ * condition of Sec. 3.3): for K < L the baseline schedule keeps both
+ * dimensions equally busy when BW(dimK) = P_K * P_{K+1} * .. * P_{L-1} * BW(dimL).
+ *   0  just enough      BW(dimK) == that product
+ *   1  over-provisioned BW(dimK) <  it (dimL has bandwidth the baseline wastes)
+ *   2  under-provisioned BW(dimK) > it
+ * The product is accumulated left to right in double precision. */
+/* ------------------------------------------------------------------------ */
+int to_provision_class(int K, int L, const uint32_t *npus, const double *bw)
+{
+  double shrink = 1.0;
+  for (int j = K; j < L; ++j) shrink = shrink * (double)npus[j];
+  double balanced = shrink * bw[L];
+  if (bw[K] < balanced) return 1;
+  if (bw[K] > balanced) return 2;
+  return 0;
+}
+
+/* classes [6][n], pairs in the order (1,2) (1,3) (1,4) (2,3) (2,4) (3,4) of
+ * the paper's 1-based dimension names; 0xFF for pairs outside the network or
+ * an invalid network. */
+void to_classify_batch(uint64_t n, uint64_t begin, uint64_t end,
+                       const uint8_t *ndims, const uint32_t *npus,
+                       const double *bw, uint8_t *classes)
+{
+  for (uint64_t i = begin; i < end; ++i) {
+    uint32_t P[TO_MAX_DIMS];
+    double B[TO_MAX_DIMS];
+    gather_network(n, i, npus, bw, P, B);
+    int D = (int)ndims[i];
+    int ok = to_network_valid(D, P, B);
+    int pair = 0;
+    for (int K = 0; K < TO_MAX_DIMS; ++K)
+      for (int L = K + 1; L < TO_MAX_DIMS; ++L, ++pair)
+        classes[(size_t)pair * n + i] =
+            (ok && L < D) ? (uint8_t)to_provision_class(K, L, P, B) : 0xFF;
+  }
+}

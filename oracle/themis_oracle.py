@@ -57,6 +57,8 @@ def lib():
         L.to_search_batch.argtypes = [
             C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, _u8p, _u32p, _f64p,
             _f64p, _u32p, _u8p, _f64p, _u8p, C.c_uint64, _f64p, _u8p]
+        L.to_classify_batch.restype = None
+        L.to_classify_batch.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, _u8p, _u32p, _f64p, _u8p]
         L.to_latency_coef.restype = None
         L.to_latency_coef.argtypes = [C.c_int, _u32p, _f64p, _f64p]
         _lib = L
@@ -280,3 +282,15 @@ def search_batch(b, max_assignments, threads=1):
             _p(best_t, _f64p), _p(best_orders, _u8p))
     _fan_out(run, b.n, threads)
     return best_t, best_orders
+
+
+JUST_ENOUGH, OVER_PROVISIONED, UNDER_PROVISIONED = 0, 1, 2
+PAIRS = ((0, 1), (0, 2), (0, 3), (1, 2), (1, 3), (2, 3))
+
+
+def classify_batch(b):
+    """Bandwidth provisioning class of every dimension pair (Sec. 6.3) -> u8[6, n]."""
+    out = np.empty((6, b.n), np.uint8)
+    nd, P, bw = _arr(b.ndims, np.uint8), _arr(b.npus, np.uint32), _arr(b.bw, np.float64)
+    lib().to_classify_batch(b.n, 0, b.n, _p(nd, _u8p), _p(P, _u32p), _p(bw, _f64p), _p(out, _u8p))
+    return out
