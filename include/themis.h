@@ -288,6 +288,28 @@ int themis_search_batch(const themis_batch_t *batch, uint64_t max_assignments,
                         double *best_t, uint8_t *best_orders, void *workspace,
                         size_t workspace_bytes, void *stream);
 
+/*
+ * themis_classify_batch -- bandwidth provisioning class of every dimension
+ * pair of each scenario's network (Sec. 6.3, balance condition of Sec. 3.3).
+ * For K < L the baseline keeps dimK and dimL equally busy when
+ * BW(dimK) = P_K * P_{K+1} * .. * P_{L-1} * BW(dimL) (product accumulated left
+ * to right in double precision); dimL is over-provisioned when BW(dimK) is
+ * below that (the case Themis recovers) and under-provisioned when above (the
+ * design points the paper advises against).
+ *
+ *   classes : [6][n] device bytes, THEMIS_BW_* per pair, pairs in the order
+ *             (1,2) (1,3) (1,4) (2,3) (2,4) (3,4) of the paper's 1-based
+ *             dimension names; 0xFF for pairs outside the network and for
+ *             scenarios whose ndims / npus / bw are invalid.
+ * Only ndims, npus and bw of the batch are read.
+ */
+enum {
+  THEMIS_BW_JUST_ENOUGH = 0,
+  THEMIS_BW_OVER_PROVISIONED = 1,
+  THEMIS_BW_UNDER_PROVISIONED = 2
+};
+int themis_classify_batch(const themis_batch_t *batch, uint8_t *classes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

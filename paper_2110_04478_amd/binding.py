@@ -64,6 +64,8 @@ def lib():
         L.themis_search_batch.restype = C.c_int
         L.themis_search_batch.argtypes = [C.POINTER(_Batch), C.c_uint64, _vp, _vp, _vp,
                                           C.c_size_t, _vp]
+        L.themis_classify_batch.restype = C.c_int
+        L.themis_classify_batch.argtypes = [C.POINTER(_Batch), _vp, _vp]
         L.themis_sweep.restype = C.c_int
         L.themis_sweep.argtypes = [C.POINTER(_Batch), C.c_int, _vp, C.c_int, C.c_uint, _vp,
                                    _vp, C.c_size_t, _vp]
@@ -134,6 +136,8 @@ def to_device(b, device="cuda:0") -> DeviceBatch:
         if a is None:
             return None
         a = np.ascontiguousarray(a)
+        if not a.flags.writeable:  # broadcast views: torch wants a writable source
+            a = a.copy()
         if dt == torch.uint32:  # torch cannot build uint32 from numpy directly everywhere
             return torch.from_numpy(a.view(np.int32)).to(device).view(torch.uint32)
         return torch.from_numpy(a).to(device)
@@ -242,6 +246,14 @@ def themis_search_batch(b: DeviceBatch, max_assignments: int,
     _check(lib().themis_search_batch(C.byref(s), max_assignments, _ptr(best_t), _ptr(best_orders),
                                      _ptr(workspace), ws_bytes, _stream()))
     return best_t, best_orders
+
+
+def themis_classify_batch(b: DeviceBatch) -> torch.Tensor:
+    """Bandwidth provisioning class of every dimension pair -> u8[6, n]."""
+    classes = torch.empty((6, b.n), dtype=torch.uint8, device=b.device)
+    s = b.c_struct()
+    _check(lib().themis_classify_batch(C.byref(s), _ptr(classes), _stream()))
+    return classes
 
 
 def alloc_workspace(nbytes: int, device="cuda:0") -> Optional[torch.Tensor]:

@@ -530,6 +530,41 @@ metrics_kernel(themis_batch_t b, const double* __restrict__ t_done,
 }
 
 // ---------------------------------------------------------------------------
+// themis_classify_batch: bandwidth provisioning class of each dimension pair
+// (Sec. 6.3).  classes [6][n].
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+classify_kernel(themis_batch_t b, uint8_t* __restrict__ classes) {
+  const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= b.n) return;
+  const int D = b.ndims[i];
+  bool ok = D >= 1 && D <= kMaxDims;
+  double P[kMaxDims], B[kMaxDims];
+#pragma unroll
+  for (int k = 0; k < kMaxDims; ++k) {
+    const uint32_t p = b.npus[(size_t)k * b.n + i];
+    P[k] = (double)p;
+    B[k] = b.bw[(size_t)k * b.n + i];
+    if (k < D && !(p >= 2u && finite_positive(B[k]))) ok = false;
+  }
+  int pair = 0;
+#pragma unroll
+  for (int K = 0; K < kMaxDims; ++K) {
+    double shrink = 1.0;  // factor by which a chunk shrinks between dimK and dimL
+#pragma unroll
+    for (int L = K + 1; L < kMaxDims; ++L, ++pair) {
+      shrink = shrink * P[L - 1];
+      const double balanced = shrink * B[L];
+      uint32_t c = B[K] < balanced ? THEMIS_BW_OVER_PROVISIONED
+                 : B[K] > balanced ? THEMIS_BW_UNDER_PROVISIONED
+                                   : THEMIS_BW_JUST_ENOUGH;
+      if (!ok || L >= D) c = 0xFFu;
+      classes[(size_t)pair * b.n + i] = (uint8_t)c;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 constexpr uint32_t kMaxSlots = 32767u;  // 16-bit queue entries, all-ones reserved
@@ -598,7 +633,7 @@ using namespace themis;
 
 extern "C" {
 
-int themis_version(void) { return 102; }
+int themis_version(void) { return 103; }
 
 const char* themis_status_string(int status) {
   switch (status) {
@@ -736,6 +771,16 @@ int themis_metrics_batch(const themis_batch_t* batch, const double* t_done, cons
   if (batch->n > (uint64_t)0x7fffffff * 256u) return THEMIS_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(metrics_kernel, dim3((unsigned)((batch->n + 255) / 256)), dim3(256), 0,
                      (hipStream_t)stream, *batch, t_done, transfer, utilization, ideal);
+  return launch_status();
+}
+
+int themis_classify_batch(const themis_batch_t* batch, uint8_t* classes, void* stream) {
+  if (!batch) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (batch->n == 0) return THEMIS_OK;
+  if (!batch->ndims || !batch->npus || !batch->bw || !classes) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (batch->n > (uint64_t)0x7fffffff * 256u) return THEMIS_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(classify_kernel, dim3((unsigned)((batch->n + 255) / 256)), dim3(256), 0,
+                     (hipStream_t)stream, *batch, classes);
   return launch_status();
 }
 

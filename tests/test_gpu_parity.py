@@ -409,3 +409,33 @@ def test_exhaustive_search_matches_oracle(gpu, oracle):
     torch.cuda.synchronize()
     ok = ~np.isnan(want_t)
     assert np.all(t.cpu().numpy()[ok] >= want_t[ok])
+
+
+def test_provisioning_classes_match_oracle(gpu, oracle):
+    """themis_classify_batch on balanced ladders tilted by powers of two (all
+    three classes, exact ties included), arbitrary networks and invalid ones."""
+    import torch
+    W = w()
+    rng = np.random.default_rng(64)
+    n = 5000
+    D = rng.integers(1, 5, n)
+    P, bw = [], []
+    for i in range(n):
+        p = [int(rng.integers(2, 65)) for _ in range(D[i])]
+        if i % 2:
+            top, b_i, shrink = float(2 ** rng.integers(30, 40)), [], 1.0
+            for k in range(D[i]):
+                b_i.append(top / shrink * float(2.0 ** rng.integers(-1, 2)))
+                shrink *= p[k]
+        else:
+            b_i = [float(rng.uniform(1e9, 1e12)) for _ in range(D[i])]
+        P.append(p); bw.append(b_i)
+    P[7][0] = 1                            # invalid NPU count
+    bw[9][D[9] - 1] = float("inf")         # invalid bandwidth
+    b = W.make_batch(D, P, bw, 1e9, 4, 1, 0, 0.0)
+    want = oracle.classify_batch(b)
+    got = gpu.themis_classify_batch(gpu.to_device(b))
+    torch.cuda.synchronize()
+    assert (want[:, 7] == 0xFF).all() and (want[:, 9] == 0xFF).all()
+    assert set(np.unique(want).tolist()) == {0, 1, 2, 0xFF}
+    assert np.array_equal(got.cpu().numpy(), want)
