@@ -603,7 +603,7 @@ static SimKernel pick_flags(bool busy, bool fix) {
 
 template <typename L>
 static SimKernel pick_mode(int mode, bool busy, bool fix) {
-  constexpr bool small = L::kCap == 64u;
+  constexpr bool small = sizeof(typename L::Link) == 1;  // 8-bit chunk ids
   switch (mode) {
     case kNoQueueOrder: return pick_flags<L, kNoQueueOrder>(busy, fix);
     case kBytes: return pick_flags<L, kBytes>(busy, fix);

@@ -16,7 +16,7 @@
 // (arrival time, chunk id) order because lists are appended in time order and
 // simultaneous completions are appended in chunk-id order.  A 64-bit bitmap
 // (16 bits per dimension) marks the non-empty lists, so "smallest chunk
-// first" is a find-highest-bit and a list pop: O(1) per chunk-stage event
+// first" is a find-lowest-bit and a list pop: O(1) per chunk-stage event
 // instead of a scan over all chunks.
 //
 // LDS layout: every lane owns kLaneWords dwords, stored transposed
@@ -39,12 +39,35 @@ template <typename Word, int kBits>
 struct Pack4 {
   Word v = 0;
   static constexpr Word kMask = (Word(1) << kBits) - 1;
+  static constexpr int kFieldBits = kBits;
   __device__ __forceinline__ uint32_t get(uint32_t k) const { return (uint32_t)((v >> (kBits * k)) & kMask); }
   __device__ __forceinline__ void set(uint32_t k, uint32_t x) {
     v = (v & ~(kMask << (kBits * k))) | (Word(x) << (kBits * k));
   }
   __device__ __forceinline__ void inc(uint32_t k) { v += Word(1) << (kBits * k); }
+  __device__ __forceinline__ uint32_t sum() const { return get(0) + get(1) + get(2) + get(3); }
 };
+
+// All-ones in every field whose bit of `keep` is clear.
+__device__ __forceinline__ uint32_t blank_fields(const Pack4<uint32_t, 8>&, uint32_t keep) {
+  // byte selector 0x0d gives 0xff, 0x0c gives 0x00
+  const uint32_t spread = (keep * 0x00204081u) & 0x01010101u;
+  return __builtin_amdgcn_perm(0u, 0u, 0x0d0d0d0du - spread);
+}
+__device__ __forceinline__ uint64_t blank_fields(const Pack4<uint64_t, 16>&, uint32_t keep) {
+  const uint32_t lo = (((keep & 3u) * 0x8001u) & 0x00010001u) * 0xffffu;
+  const uint32_t hi = (((keep >> 2) * 0x8001u) & 0x00010001u) * 0xffffu;
+  return ~(((uint64_t)hi << 32) | lo);
+}
+// Smallest of the four fields.
+__device__ __forceinline__ uint32_t min_field(uint32_t v) {
+  const uint32_t a = min(v & 0xffu, (v >> 8) & 0xffu), b = min((v >> 16) & 0xffu, v >> 24);
+  return min(a, b);
+}
+__device__ __forceinline__ uint32_t min_field(uint64_t v) {
+  const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+  return min(min(lo & 0xffffu, lo >> 16), min(hi & 0xffffu, hi >> 16));
+}
 
 // Per-lane LDS layout for up to 64 chunks (80 dwords, 20 KiB per wavefront):
 //   dword c (0..63), one per chunk c AND per list q = 16*dim + class:
@@ -152,8 +175,7 @@ __device__ __forceinline__ double scale_down(double x, uint32_t e) {
 // Sum of e_k over the dimensions in mask.
 __device__ __forceinline__ uint32_t esum(uint32_t epack, uint32_t mask) {
   uint32_t spread = (mask * 0x00204081u) & 0x01010101u;  // bit k -> byte k
-  uint32_t sel = (spread * 0xffu) & epack;
-  return __builtin_amdgcn_sad_u8(sel, 0u, 0u);            // add the four bytes
+  return __builtin_amdgcn_udot4(spread, epack, 0u, false);  // sum of byte products
 }
 
 // Can this scenario take the fast path?  Fills fs when it can.
@@ -291,7 +313,8 @@ struct FastResult {
 };
 
 // Class (rank of the resident size) of every mask, 4 bits each: the number of
-// masks with a strictly smaller E, i.e. a strictly larger resident size.
+// masks with a strictly larger E, i.e. a strictly smaller resident size, so
+// that the lowest non-empty class of a dimension holds its smallest chunks.
 __device__ __forceinline__ uint64_t build_rank_table(uint32_t epack, bool scf) {
   if (!scf) return 0ull;
   uint32_t E[16];
@@ -302,7 +325,7 @@ __device__ __forceinline__ uint64_t build_rank_table(uint32_t epack, bool scf) {
   for (uint32_t m = 0; m < 16; ++m) {
     uint32_t r = 0;
 #pragma unroll
-    for (uint32_t o = 0; o < 16; ++o) r += (E[o] < E[m]) ? 1u : 0u;
+    for (uint32_t o = 0; o < 16; ++o) r += (E[o] > E[m]) ? 1u : 0u;
     tab |= (uint64_t)r << (4 * m);
   }
   return tab;
@@ -341,12 +364,11 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
 
   double f0 = kInf, f1 = kInf, f2 = kInf, f3 = kInf;  // finish time, +inf = idle
   double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
-  typename L::Ids serving;   // chunk id per dimension
+  typename L::Ids serving;   // per dimension: chunk id << 2 | dimension
   typename L::Ids executed;  // operations started per dimension
   uint64_t nonempty = 0;  // bit q = 16*dim + class: list q holds chunks
   uint32_t work = 0;      // bit k: some list of dimension k holds chunks
   uint32_t idle = full;   // bit k: dimension k serves nothing
-  bool stalled = false;   // a stage did not advance time: generic path decides
   uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0;  // kWords: last four queue entries per dimension
   const uint32_t row_len = 2u * out.slots;
 
@@ -380,8 +402,9 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
     // a7: every idle dimension with waiting chunks starts its first one
     for (uint32_t need = idle & work; need != 0u; need = idle & work) {
       const uint32_t k = (uint32_t)__builtin_ctz(need);
-      const uint32_t field = (uint32_t)(nonempty >> (16u * k)) & 0xffffu;
-      const uint32_t cls = 31u - (uint32_t)__clz((int)field);  // smallest resident size
+      // lists of dimension k and above; work bit k says that one of k's is non-empty
+      const uint32_t field = (uint32_t)(nonempty >> (16u * k));
+      const uint32_t cls = (uint32_t)__builtin_ctz(field);  // smallest resident size
       const uint32_t q = 16u * k + cls;
       Link* hp = L::head_ptr(lds, q);
       const uint32_t h = *hp;
@@ -389,29 +412,29 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
       const uint32_t nx = L::next(w);
       *hp = (Link)nx;  // harmless when the list is now empty
       const bool emptied = nx == L::kEnd;
-      nonempty &= ~(emptied ? (1ull << q) : 0ull);
-      const bool no_work = (field & ~((emptied ? 1u : 0u) << cls)) == 0u;
+      nonempty ^= (uint64_t)(emptied ? 1u : 0u) << q;  // the bit was set
+      const bool no_work = ((field ^ ((emptied ? 1u : 0u) << cls)) & 0xffffu) == 0u;
       work &= ~((no_work ? 1u : 0u) << k);
-      idle &= ~(1u << k);
+      const uint32_t kbit = 1u << k;
+      idle &= ~kbit;
 
-      const uint32_t mask = w & 15u;
       const uint32_t phase = (w >> 4) & 1u;
       // bytes moved on k = resident size before the chunk's Reduce-Scatter on
-      // k; the All-Gather reuses it (mask still contains k then)
-      const uint32_t ek = (fs.epack >> (8u * k)) & 0xffu;
-      const uint32_t E = esum(fs.epack, mask) - (phase ? ek : 0u);
+      // k, i.e. with every reduced dimension but k itself taken off; the
+      // All-Gather reuses it (its mask still contains k)
+      const uint32_t E = esum(fs.epack, w & 15u & ~kbit);
       double t = scale_down(fs.base, E) *
                  sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
       if (kFix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
       const double f = now + t;
-      stalled |= !(f > now);
       const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
       f0 = k0 ? f : f0; f1 = k1 ? f : f1; f2 = k2 ? f : f2; f3 = k3 ? f : f3;
       if (kBusy) {
-        z0 = k0 ? z0 + t : z0; z1 = k1 ? z1 + t : z1;
-        z2 = k2 ? z2 + t : z2; z3 = k3 ? z3 + t : z3;
+        // z_j + t * [k == j]: one rounding of the exact sum, the same as z_j + t
+        z0 = __builtin_fma(t, k0 ? 1.0 : 0.0, z0); z1 = __builtin_fma(t, k1 ? 1.0 : 0.0, z1);
+        z2 = __builtin_fma(t, k2 ? 1.0 : 0.0, z2); z3 = __builtin_fma(t, k3 ? 1.0 : 0.0, z3);
       }
-      serving.set(k, h);
+      serving.set(k, (h << 2) | k);
       if (kQueueOrder != kNoQueueOrder) {
         const uint32_t pos = executed.get(k);
         const uint32_t entry = (h << 1) | phase;
@@ -426,7 +449,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
           const uint32_t a = __builtin_amdgcn_alignbit(entry, sel4((int)k, a0, a1, a2, a3), 8u);
           a0 = k0 ? a : a0; a1 = k1 ? a : a1; a2 = k2 ? a : a2; a3 = k3 ? a : a3;
           if ((pos & 3u) == 3u && pos < row_len)
-            *(uint32_t*)(out.queue_order + k * row_len + (pos & ~3u)) = a;
+            *(uint32_t*)(out.queue_order + __umul24(k, row_len) + (pos & ~3u)) = a;
         }
       }
       executed.inc(k);
@@ -441,19 +464,15 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
     f0 = d0 ? kInf : f0; f1 = d1 ? kInf : f1; f2 = d2 ? kInf : f2; f3 = d3 ? kInf : f3;
     idle |= done;
     // deliver all completions of this instant, lowest chunk id first, so that
-    // equal arrival times are appended in chunk-id order
+    // equal arrival times are appended in chunk-id order: the smallest
+    // (id << 2 | dimension) field among the dimensions that completed
+    auto keys = serving.v | blank_fields(serving, done);
     do {
-      uint32_t k = (uint32_t)__builtin_ctz(done);
-      if (done & (done - 1u)) {
-        uint32_t best = 0xffffffffu;
-#pragma unroll
-        for (uint32_t kk = 0; kk < (uint32_t)kMaxDims; ++kk) {
-          uint32_t id = serving.get(kk);
-          if ((done >> kk & 1u) && id < best) { best = id; k = kk; }
-        }
-      }
+      const uint32_t key = min_field(keys);
+      const uint32_t k = key & 3u;
+      const uint32_t c = key >> 2;
+      keys |= decltype(keys)(L::Ids::kMask) << (L::Ids::kFieldBits * k);
       done &= ~(1u << k);
-      const uint32_t c = serving.get(k);
       uint8_t* cp = lds.dword(c);
       const uint32_t w = *(const uint32_t*)cp;
       const uint32_t code = L::code(w);
@@ -489,7 +508,20 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
   }
 
   FastResult res;
-  res.ok = !stalled;
+  // The answer stands when every stage ran and completed and no stage was too
+  // short to move the clock: each stage lasts at least t_min, the smallest
+  // product over the dimensions, so `t_done + t_min / 4 > t_done` (t_min is
+  // then at least two units in the last place of every earlier instant)
+  // shows that each finish time was strictly after its start.  Anything else
+  // (overflow to infinity, NaN, a vanishing stage) is left to the generic path.
+  double t_min = kInf;
+#pragma unroll
+  for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) {
+    const uint32_t ek = (fs.epack >> (8u * k)) & 0xffu;
+    if (k < D) t_min = min_f64(t_min, scale_down(fs.base, fs.etot - ek) * s.coef[k]);
+  }
+  const uint32_t stages = (fs.rs_only || fs.gather) ? D : 2u * D;
+  res.ok = executed.sum() == stages * C && idle == full && (now + 0.25 * t_min > now);
   res.t_done = now;
   res.busy[0] = z0; res.busy[1] = z1; res.busy[2] = z2; res.busy[3] = z3;
 #pragma unroll
