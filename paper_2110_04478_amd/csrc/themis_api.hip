@@ -118,10 +118,12 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
 // themis_simulate_batch (hot-path steps a6-a9): LDS fast path, with the
 // generic workspace path for the scenarios it does not cover.
 // ---------------------------------------------------------------------------
-__device__ __noinline__ void simulate_generic_scenario(const themis_batch_t& b, const TraceView& tv,
-                                                       const Scenario& s, uint32_t Q, uint64_t i,
+// (Structures by value: a reference would make the caller keep its own copy,
+// kernel arguments included, in scratch memory for the whole kernel.)
+__device__ __noinline__ void simulate_generic_scenario(const themis_batch_t b, const TraceView tv,
+                                                       const Scenario s, uint32_t Q, uint64_t i,
                                                        const uint8_t* row, bool scf,
-                                                       const Workspace& w, const SimOut& out) {
+                                                       const Workspace w, const SimOut out) {
   bool ok = true;
   bool has_release = false;
   // a6: every chunk waits at the dimension of its first stage
@@ -310,10 +312,10 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 // themis_sweep (hot-path step a10): one lane per scenario x threshold x
 // scheduler; the plan goes straight into LDS and only the time leaves.
 // ---------------------------------------------------------------------------
-__device__ __noinline__ void sweep_generic_evaluation(const Scenario& s, double chunk,
+__device__ __noinline__ void sweep_generic_evaluation(const Scenario s, double chunk,
                                                       bool themis_on, bool rel, double th,
-                                                      bool scf, uint64_t e, const Workspace& w,
-                                                      const SimOut& out) {
+                                                      bool scf, uint64_t e, const Workspace w,
+                                                      const SimOut out) {
   double load[kMaxDims];
 #pragma unroll
   for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? tracker_start(s, k) : inf64();
