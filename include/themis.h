@@ -221,6 +221,8 @@ int themis_plan_batch(const themis_batch_t *batch, uint8_t *orders,
  *   queue_order : NULL, or [n][4][2*slots] entries (see above).
  *   busy        : NULL, or [4][n] seconds each dimension spent serving.
  *   workspace, workspace_bytes : see themis_workspace_bytes().
+ * A scenario whose stage times or clock overflow binary64 (bandwidths or
+ * sizes hundreds of orders of magnitude apart) comes back like an invalid one.
  */
 int themis_simulate_batch(const themis_batch_t *batch, const uint8_t *orders,
                           double *t_done, void *queue_order, double *busy,

@@ -366,9 +366,16 @@ int to_simulate(int ndims, const uint32_t *npus, const double *bw,
     }
   }
 
+  free(ch);
+  /* A stage time or a clock value that overflowed binary64 leaves the model:
+   * such a scenario is reported like an invalid one.  Every clock value is at
+   * most the completion time and every stage time at most its dimension's
+   * busy time, so these sums being finite covers all of them. */
+  if (!isfinite(last_done)) return 0;
+  for (int k = 0; k < ndims; ++k)
+    if (!isfinite(busy_acc[k])) return 0;
   *t_done = last_done;
   if (busy) for (int k = 0; k < TO_MAX_DIMS; ++k) busy[k] = busy_acc[k];
-  free(ch);
   return 1;
 }
 

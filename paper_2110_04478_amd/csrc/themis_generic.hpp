@@ -188,6 +188,13 @@ __device__ void simulate_generic(const Scenario& s, uint32_t Q, bool scf, const 
     }
   }
 
+  // a stage time or clock value that overflowed leaves the model: reported
+  // like an invalid scenario (these sums bound every one of them)
+  bool finite = last_done < inf64();
+#pragma unroll
+  for (int k = 0; k < kMaxDims; ++k) finite = finite && busy[k] < inf64();
+  if (!finite) { write_invalid(out); return; }
+
   if (out.t_done) *out.t_done = last_done;
   if (out.busy)
     for (int k = 0; k < kMaxDims; ++k) out.busy[(size_t)k * out.busy_stride] = busy[k];

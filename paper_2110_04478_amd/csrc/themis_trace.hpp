@@ -234,7 +234,8 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       double t = scale_down(rg.CH(h / C), E) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
       if (s.has_fix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
       const double fin = now + t;
-      stalled |= !(fin > now);
+      // a stage that does not move the clock, or overflows it: generic path decides
+      stalled |= !(fin > now && fin < kInf);
       uint32_t pos = 0;
 #pragma unroll
       for (uint32_t kk = 0; kk < 4u; ++kk) {

@@ -34,7 +34,8 @@ def assert_close(name, got, want):
     nan_g, nan_w = np.isnan(got), np.isnan(want)
     assert np.array_equal(nan_g, nan_w), f"{name}: NaN pattern differs"
     g, x = got[~nan_g], want[~nan_w]
-    err = np.abs(g - x) / np.maximum(np.abs(x), np.finfo(np.float64).tiny)
+    with np.errstate(invalid="ignore"):   # equal infinities
+        err = np.abs(g - x) / np.maximum(np.abs(x), np.finfo(np.float64).tiny)
     err[(g == x)] = 0.0
     assert err.size == 0 or err.max() <= REL_TOL, (
         f"{name}: max rel err {err.max():.3e} at {int(err.argmax())}, "
@@ -439,3 +440,19 @@ def test_provisioning_classes_match_oracle(gpu, oracle):
     assert (want[:, 7] == 0xFF).all() and (want[:, 9] == 0xFF).all()
     assert set(np.unique(want).tolist()) == {0, 1, 2, 0xFF}
     assert np.array_equal(got.cpu().numpy(), want)
+
+
+def test_extreme_magnitudes_fall_back_to_the_generic_path(gpu, oracle):
+    """Power-of-two networks whose stage times differ by hundreds of orders of
+    magnitude: some stages are too short to move the clock, some times
+    overflow.  The LDS path must notice and hand these scenarios to the generic
+    path, lane by lane, next to ordinary scenarios in the same wavefront."""
+    W = w()
+    P = [[4, 4], [4, 4], [2, 8, 4], [4, 4], [4, 4], [4, 8], [2, 2, 2, 2]]
+    bw = [[1e3, 1e300], [1e300, 1e3], [1e9, 1e290, 1e-5], [1e-300, 1e9], [1e9, 1e-300],
+          [200e9, 50e9], [1e11, 1e-200, 1e200, 1e11]]
+    reps = 20
+    b = W.make_batch([len(p) for p in P] * reps, P * reps, bw * reps, 2.0 ** 30,
+                     [8, 5, 8, 3, 8, 8, 6] * reps, 1, [1, 0, 1, 1, 0, 1, 1] * reps, 0.0,
+                     max_chunks=8)
+    check_batch(gpu, oracle, b)

@@ -703,3 +703,24 @@ def test_provisioning_class_rejects_invalid_networks(oracle):
     b = W.make_batch([2, 2, 0], [[4, 1], [4, 4], [4, 4]], [[1e9, 1e9], [1e9, -1.0], [1e9, 1e9]],
                      1e6, 4, 1, 0, 0.0)
     assert (oracle.classify_batch(b) == 0xFF).all()
+
+
+def test_overflowing_times_are_reported_as_invalid(oracle):
+    """A stage time beyond binary64 (bandwidth 1e-300 B/s) has no place in the
+    model: NaN / all-ones, like an invalid scenario.  A stage too short to move
+    the clock is legal and still obeys the 1-D closed form on its own
+    dimension."""
+    from paper_2110_04478_amd import workloads as W
+    b = W.make_batch([2, 2, 1], [[4, 4], [4, 4], [4]], [[1e-300, 1e9], [1e3, 1e300], [1e-300]],
+                     2.0 ** 30, 8, 1, 1, 0.0, max_chunks=8)
+    od, _ = oracle.plan_batch(b)
+    t, q, busy = oracle.simulate_batch(b, od)
+    assert np.isnan(t[0]) and np.isnan(busy[:, 0]).all() and (q[0] == 0xFFFF).all()
+    assert np.isnan(t[2])
+    assert np.isfinite(t[1]) and (q[1][:2, :16] != 0xFFFF).all()
+    # Themis sends every chunk but the first through the (free) dim2 first, so
+    # dim1 serves one full chunk and seven quarter chunks, twice each; dim2's
+    # 1e-291 s stages vanish next to that
+    assert od[1].tolist() == [code_of([0, 1])] + [code_of([1, 0])] * 7
+    assert busy[0, 1] == pytest.approx(2 * 0.75 * 2.0 ** 27 * (1 + 7 / 4) / 1e3, rel=1e-12)
+    assert t[1] == pytest.approx(busy[0, 1], rel=1e-9)
