@@ -420,10 +420,10 @@ __device__ __forceinline__ uint64_t assignment_count(uint32_t D, uint32_t C, uin
 
 // One lane per (scenario, assignment): times[i * max_assign + a].  Slots past
 // a scenario's own count hold +inf; NaN marks a scenario that cannot be searched.
-template <bool kFix>
+template <typename L, bool kFix>
 __global__ void __launch_bounds__(kBlock)
 search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ times) {
-  __shared__ uint32_t lds_block[Layout64::kLaneWords * kBlock];
+  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (e >= b.n * max_assign) return;
   const uint64_t i = e / max_assign;
@@ -433,7 +433,7 @@ search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ t
   const double S = b.size_bytes[i];
   FastScenario fs;
   const bool ok = s.valid && finite_positive(S) &&
-                  fast_eligible(s, S / (double)s.C, Layout64::kCap, fs);
+                  fast_eligible(s, S / (double)s.C, L::kCap, fs);
   const uint64_t count = ok ? assignment_count((uint32_t)s.D, s.C, max_assign) : 0;
   if (count == 0) { times[e] = nan64(); return; }
   if (a >= count) { times[e] = inf64(); return; }
@@ -445,13 +445,13 @@ search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ t
     const uint64_t q = rest / F;
     const uint32_t digit = (uint32_t)(rest - q * F);
     rest = q;
-    Layout64::init_chunk(lds, c, stored_code(s, fs, nth_permutation_code((uint32_t)s.D, digit)),
+    L::init_chunk(lds, c, stored_code(s, fs, nth_permutation_code((uint32_t)s.D, digit)),
                          fs.state0);
   }
   FastOut fo;
   fo.queue_order = nullptr;
   fo.slots = b.max_chunks;
-  FastResult r = simulate_fast<Layout64, kNoQueueOrder, false, kFix>(s, fs, scf, lds, fo);
+  FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, fs, scf, lds, fo);
   times[e] = r.ok ? r.t_done : nan64();
 }
 
@@ -616,6 +616,7 @@ static SimKernel pick_mode(int mode, bool busy, bool fix) {
 }
 
 static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy, bool fix) {
+  if (cap == 16u) return pick_mode<Layout16>(mode, busy, fix);
   if (cap == 64u) return pick_mode<Layout64>(mode, busy, fix);
   if (cap == 128u) return pick_mode<LayoutWide<128>>(mode, busy, fix);
   return pick_mode<LayoutWide<512>>(mode, busy, fix);
@@ -688,7 +689,8 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                      ((uintptr_t)queue_order & 3u) == 0u;
   const int mode64 = !queue_order ? kNoQueueOrder : (words ? kWords : kBytes);
   const int modew = !queue_order ? kNoQueueOrder : (entry_bytes == 2 ? kShorts : kBytes);
-  const uint32_t cap = (tv.on || batch->max_chunks > 128u) ? 512u : batch->max_chunks > 64u ? 128u : 64u;
+  const uint32_t cap = (tv.on || batch->max_chunks > 128u) ? 512u
+                     : batch->max_chunks > 64u ? 128u : batch->max_chunks > 16u ? 64u : 16u;
   if (tv.on) {
     const TraceLayout tl = trace_layout(batch->max_chunks, batch->max_coll);
     const size_t generic = generic_area_bytes(batch->n, tv.slots);
@@ -700,7 +702,7 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                        busy, w, have_ws, trace_area, tl);
     return launch_status();
   }
-  SimKernel kernel = pick_simulate_kernel(cap, cap == 64u ? mode64 : modew, busy != nullptr,
+  SimKernel kernel = pick_simulate_kernel(cap, cap <= 64u ? mode64 : modew, busy != nullptr,
                                           batch->fixed_delay != nullptr);
   if (!kernel) return THEMIS_ERR_DEVICE;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
@@ -725,9 +727,11 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   const bool have_ws = workspace != nullptr &&
                        workspace_bytes_given >= workspace_bytes(evals, batch->max_chunks);
   Workspace w = carve_workspace(workspace, evals, batch->max_chunks);
-  const uint32_t cap = batch->max_chunks > 128u ? 512u : batch->max_chunks > 64u ? 128u : 64u;
+  const uint32_t cap = batch->max_chunks > 128u ? 512u
+                     : batch->max_chunks > 64u ? 128u : batch->max_chunks > 16u ? 64u : 16u;
   const bool fix = batch->fixed_delay != nullptr;
-  auto kernel = cap == 64u ? (fix ? sweep_kernel<Layout64, true> : sweep_kernel<Layout64, false>)
+  auto kernel = cap == 16u ? (fix ? sweep_kernel<Layout16, true> : sweep_kernel<Layout16, false>)
+              : cap == 64u ? (fix ? sweep_kernel<Layout64, true> : sweep_kernel<Layout64, false>)
               : cap == 128u ? (fix ? sweep_kernel<LayoutWide<128>, true> : sweep_kernel<LayoutWide<128>, false>)
                             : (fix ? sweep_kernel<LayoutWide<512>, true> : sweep_kernel<LayoutWide<512>, false>);
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
@@ -756,7 +760,10 @@ int themis_search_batch(const themis_batch_t* batch, uint64_t max_assignments, d
       workspace_bytes_given < themis_search_workspace_bytes(batch->n, max_assignments))
     return THEMIS_ERR_WORKSPACE;
   double* times = (double*)workspace;
-  auto eval = batch->fixed_delay ? search_eval_kernel<true> : search_eval_kernel<false>;
+  const bool fix = batch->fixed_delay != nullptr;
+  auto eval = batch->max_chunks <= 16u
+      ? (fix ? search_eval_kernel<Layout16, true> : search_eval_kernel<Layout16, false>)
+      : (fix ? search_eval_kernel<Layout64, true> : search_eval_kernel<Layout64, false>);
   hipLaunchKernelGGL(eval, dim3(blocks_for(evals)), dim3(kBlock), 0, (hipStream_t)stream, *batch,
                      max_assignments, times);
   hipLaunchKernelGGL(search_reduce_kernel, dim3((unsigned)batch->n), dim3(kBlock), 0,

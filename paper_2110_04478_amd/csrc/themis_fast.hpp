@@ -69,16 +69,24 @@ __device__ __forceinline__ uint32_t min_field(uint64_t v) {
   return min(min(lo & 0xffffu, lo >> 16), min(hi & 0xffffu, hi >> 16));
 }
 
-// Per-lane LDS layout for up to 64 chunks (80 dwords, 20 KiB per wavefront):
+// Per-lane LDS layouts with 8-bit chunk ids (kChunks <= 64).
+//
+// Layout64 (80 dwords, 20 KiB per wavefront, 8 wavefronts per CU):
 //   dword c (0..63), one per chunk c AND per list q = 16*dim + class:
 //     byte 0  chunk c: reduced-dims mask | phase << 4
 //     byte 1  chunk c: next chunk in its list (0xFF = last)
 //     byte 2  chunk c: order code
 //     byte 3  list q: head chunk
 //   dwords 64..79  u8 tail[64]: last chunk of list q
-struct Layout64 {
-  static constexpr uint32_t kCap = 64;
-  static constexpr uint32_t kLaneWords = 80;
+// LayoutByte<16> (48 dwords, 12 KiB per wavefront, 13 wavefronts per CU; the
+// kernel runs faster the more wavefronts share a SIMD): 16 chunk dwords with
+// byte 3 unused, then u8 head[64] and u8 tail[64].
+template <uint32_t kChunks>
+struct LayoutByte {
+  static constexpr uint32_t kCap = kChunks;
+  static constexpr bool kHeadInChunkWord = kChunks == 64;
+  static constexpr uint32_t kTailBase = kHeadInChunkWord ? kChunks : kChunks + 16;
+  static constexpr uint32_t kLaneWords = kTailBase + 16;
   static constexpr uint32_t kEnd = 0xffu;
   using Link = uint8_t;               // width of a chunk id in LDS
   using Ids = Pack4<uint32_t, 8>;     // chunk id / operation count per dimension
@@ -96,11 +104,16 @@ struct Layout64 {
     *(uint16_t*)cp = (uint16_t)(state | (kEnd << 8));
   }
   static __device__ __forceinline__ Link* next_ptr(const LaneLds& l, uint32_t c) { return l.dword(c) + 1; }
-  static __device__ __forceinline__ Link* head_ptr(const LaneLds& l, uint32_t q) { return l.dword(q) + 3; }
+  static __device__ __forceinline__ Link* head_ptr(const LaneLds& l, uint32_t q) {
+    if (kHeadInChunkWord) return l.dword(q) + 3;
+    return l.base + ((kChunks + (q >> 2)) << 8) + (q & 3u);
+  }
   static __device__ __forceinline__ Link* tail_ptr(const LaneLds& l, uint32_t q) {
-    return l.base + ((64u + (q >> 2)) << 8) + (q & 3u);
+    return l.base + ((kTailBase + (q >> 2)) << 8) + (q & 3u);
   }
 };
+using Layout64 = LayoutByte<64>;
+using Layout16 = LayoutByte<16>;
 
 // Layout for up to kChunks <= 512 chunks (kChunks + 64 dwords per lane):
 //   dword c: byte 0 mask | phase << 4, byte 1 order code, bytes 2-3 next

@@ -101,6 +101,23 @@ def test_ragged_mixed_batches(gpu, oracle, n, thr_mode):
     check_batch(gpu, oracle, w().mixed(n, seed=1234 + n, thr_mode=thr_mode))
 
 
+@pytest.mark.parametrize("max_chunks", [1, 7, 16, 17])
+def test_small_chunk_counts(gpu, oracle, max_chunks):
+    """C up to 16 runs on the 48-dword LDS layout (13 wavefronts per CU); 17 is
+    the first size back on the 64-chunk layout; odd row lengths store queue
+    entries bytewise."""
+    b = w().mixed(900, seed=40 + max_chunks, max_chunks=max_chunks)
+    check_batch(gpu, oracle, b)
+    import torch
+    thr = torch.tensor([0.0, 1 / 16, 1.0], dtype=torch.float64, device="cuda")
+    want = oracle.sweep(b, thr.cpu().numpy(), 7, threads=8)
+    d = gpu.to_device(b)
+    ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(d.n * 3 * 3, d.max_chunks))
+    got = gpu.themis_sweep(d, thr, 7, workspace=ws)
+    torch.cuda.synchronize()
+    assert_close("sweep", got.cpu().numpy(), want)
+
+
 def test_non_power_of_two_npus(gpu, oracle):
     check_batch(gpu, oracle, w().mixed(700, seed=77, pow2=False))
 
