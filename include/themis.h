@@ -65,7 +65,7 @@ typedef enum themis_status {
   THEMIS_ERR_INVALID_ARGUMENT = -1, /* NULL pointer, bad size or enum      */
   THEMIS_ERR_UNSUPPORTED = -2,      /* a valid request this build lacks    */
   THEMIS_ERR_DEVICE = -3,           /* a HIP call failed (launch, device)  */
-  THEMIS_ERR_WORKSPACE = -4         /* workspace missing or too small      */
+  THEMIS_ERR_WORKSPACE = -4         /* workspace missing, small, misaligned */
 } themis_status_t;
 
 /* Inter-dimension scheduler of a scenario (paper Table 3). */

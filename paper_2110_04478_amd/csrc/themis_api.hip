@@ -677,6 +677,7 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   if (st != THEMIS_OK) return st;
   if (batch->n == 0) return THEMIS_OK;
   if (!orders || !t_done) return THEMIS_ERR_INVALID_ARGUMENT;
+  if ((uintptr_t)workspace & 15u) return THEMIS_ERR_WORKSPACE;
   const TraceView tv = trace_view(*batch);
   const bool have_ws =
       workspace != nullptr && workspace_bytes_given >= workspace_bytes(batch->n, tv.slots);
@@ -721,6 +722,7 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
     return THEMIS_ERR_INVALID_ARGUMENT;
   if (batch->n == 0) return THEMIS_OK;
   if (!t_done) return THEMIS_ERR_INVALID_ARGUMENT;
+  if ((uintptr_t)workspace & 15u) return THEMIS_ERR_WORKSPACE;
   int n_pol = __builtin_popcount(policy_mask & 7u);
   uint64_t evals = batch->n * (uint64_t)n_thr * (uint64_t)n_pol;
   if (evals > (uint64_t)0x7fffffff * kBlock) return THEMIS_ERR_UNSUPPORTED;

@@ -61,3 +61,20 @@ def test_argument_errors_are_reported_without_a_device():
     b.n = 0
     assert L.themis_plan_batch(ctypes.byref(b), None, None, None) == 0    # empty batch: no-op
     assert L.themis_sweep(ctypes.byref(b), 0, None, 0, 7, None, None, 0, None) == -1
+
+
+def test_misaligned_workspace_is_rejected_on_the_host():
+    """The workspace must be 16-byte aligned; the check comes before any HIP
+    call (the pointers below are never dereferenced on the host)."""
+    from paper_2110_04478_amd import binding
+    L = binding.lib()
+    b = binding._Batch()
+    b.n, b.max_chunks, b.threshold_mode = 4, 64, 0
+    fake = 0x10000
+    for f in ("ndims", "npus", "bw", "size_bytes", "chunks", "inter_policy", "intra_policy",
+              "threshold"):
+        setattr(b, f, fake)
+    assert L.themis_simulate_batch(ctypes.byref(b), fake, fake, None, None, fake + 8, 1 << 20,
+                                   None) == -4
+    assert L.themis_sweep(ctypes.byref(b), 1, fake, 0, 7, fake, fake + 4, 1 << 20, None) == -4
+    assert L.themis_search_batch(ctypes.byref(b), 16, fake, None, fake + 4, 1 << 20, None) == -4
