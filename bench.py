@@ -7,6 +7,11 @@ themis_simulate_batch (queue simulation) with every output requested (order
 codes, final loads, completion times, per-dimension queue orders, busy times).
 The workload is the 1,048,576-scenario 4-D configuration (P = (2,8,8,64),
 C = 64, Themis + SCF, relative threshold).  Prints ONE JSON line.
+
+--workload config4 / config5 time the two heavier configurations instead (the
+512-chunk threshold sweep through themis_sweep, the 200-collective traces
+through themis_plan_batch + themis_simulate_batch); they exist to profile the
+wide-layout and trace kernels and print the same kind of line.
 """
 import argparse
 import json
@@ -42,6 +47,90 @@ PROFILED = {
 }
 
 
+def other_workload(args, np, torch, binding, workloads):
+    """config4: one step = themis_sweep over 8 thresholds x {FIFO, SCF} of 65,536 scenarios
+    with C = 512.  config5: one step = plan + simulate of 16,384 traces of 200 collectives."""
+    dev = "cuda:0"
+    if args.workload == "config4":
+        n = args.scenarios if args.scenarios != 1 << 20 else 65536
+        host = workloads.config4(n=n)
+        D, C, Q = 4, 512, 1
+        d = binding.to_device(host, dev)
+        thr = torch.from_numpy(workloads.CONFIG4_THRESHOLDS).to(dev)
+        mask = workloads.SWEEP_THEMIS_FIFO | workloads.SWEEP_THEMIS_SCF
+        evals = n * len(workloads.CONFIG4_THRESHOLDS) * 2
+        out = torch.empty((n, len(workloads.CONFIG4_THRESHOLDS), 2), dtype=torch.float64, device=dev)
+
+        def step():
+            binding.themis_sweep(d, thr, mask, t_done=out)
+        name = ("config4: %d scenarios x 8 thresholds x {FIFO,SCF}, 4-D P_k=2^U{1..6}, C=512, "
+                "themis_sweep" % n)
+        kernel = "sweep"
+    else:
+        n = args.scenarios if args.scenarios != 1 << 20 else 16384
+        host = workloads.config5(n=n)
+        D, C, Q = 3, 64, host.max_coll
+        d = binding.to_device(host, dev)
+        evals = n
+        orders = torch.empty((n, d.slots), dtype=torch.uint8, device=dev)
+        loads = torch.empty((4, n), dtype=torch.float64, device=dev)
+        out = torch.empty(n, dtype=torch.float64, device=dev)
+        busy = torch.empty((4, n), dtype=torch.float64, device=dev)
+        ws = binding.alloc_workspace(binding.themis_workspace_bytes(n, d.max_chunks, d.max_coll))
+
+        def step():
+            binding.themis_plan_batch(d, orders, loads)
+            binding.themis_simulate_batch(d, orders, out, None, busy, ws, want_queue_order=False)
+        name = ("config5: %d traces of %d All-Reduces, 3-D P=(8,16,32), C=64, Themis+SCF, "
+                "plan + simulate (times and busy)" % (n, Q))
+        kernel = "simulate_trace"
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = wall * 1e3 / args.steps
+    events = evals * 2 * D * C * Q
+    lane_ops = evals * Q * algorithmic_lane_ops(D, C)["simulate"]
+    achieved = lane_ops / (ev0.elapsed_time(ev1) * 1e-3 / args.steps)
+    result = {
+        "metric": "scenarios_per_sec", "value": n / (ms * 1e-3), "unit": "scenarios/s",
+        "evaluations_per_sec": evals / (ms * 1e-3), "events_per_sec": events / (ms * 1e-3),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic", "config": {"workload": name},
+        "nan_results": int(torch.isnan(out).sum().item()),
+        "roofline": {"bound": "alu", "kernel": kernel, "achieved": achieved / 1e12,
+                     "peak": PEAK_LANE_OPS_PER_S / 1e12, "unit": "Tlane-op/s",
+                     "frac": achieved / PEAK_LANE_OPS_PER_S, "traffic": None},
+    }
+    if args.cpu_sample > 0:
+        from oracle import themis_oracle
+        m = min(n, 256 if args.workload == "config4" else 48)
+        sample = host.take(slice(0, m))
+        cores = min(os.cpu_count() or 1, 16)
+        c0 = time.perf_counter()
+        if args.workload == "config4":
+            o = themis_oracle.sweep(sample, workloads.CONFIG4_THRESHOLDS, mask, threads=cores)
+            g = out[:m].cpu().numpy()
+        else:
+            oo, _ = themis_oracle.plan_batch(sample, threads=cores)
+            o, _, _ = themis_oracle.simulate_batch(sample, oo, want_queue_order=False, threads=cores)
+            g = out[:m].cpu().numpy()
+        cpu_s = time.perf_counter() - c0
+        result["cpu_baseline"] = {
+            "value": m / cpu_s, "unit": "scenarios/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d scenarios, %d threads, %.1f s" % (m, cores, cpu_s),
+            "parity_on_sample": {"t_done_max_rel_err": float(np.max(np.abs(g - o) / o))}}
+    return result
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,6 +142,7 @@ def main():
                     help="scenarios the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-queue-order", action="store_true",
                     help="do not request the per-dimension queue orders")
+    ap.add_argument("--workload", choices=("config3", "config4", "config5"), default="config3")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB MiB "
                          "(known traffic, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
@@ -75,6 +165,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": src.numel(), "copy_probe_bytes_written": dst.numel()}))
+        return
+    if args.workload != "config3":
+        print(json.dumps(other_workload(args, np, torch, binding, workloads)))
         return
     n = args.scenarios
     host = workloads.config3(n=n)
