@@ -603,22 +603,32 @@ static SimKernel pick_flags(bool busy, bool fix) {
               : (fix ? simulate_kernel<L, kMode, false, true> : simulate_kernel<L, kMode, false, false>);
 }
 
+// Queue-entry store modes a layout is built with: four-at-a-time dword stores
+// need 8-bit entries (at most 127 slots), 16-bit entries start at 128 slots.
 template <typename L>
 static SimKernel pick_mode(int mode, bool busy, bool fix) {
-  constexpr bool small = sizeof(typename L::Link) == 1;  // 8-bit chunk ids
+  constexpr bool words = L::kCap <= 128u, shorts = L::kCap >= 128u;
   switch (mode) {
     case kNoQueueOrder: return pick_flags<L, kNoQueueOrder>(busy, fix);
-    case kBytes: return pick_flags<L, kBytes>(busy, fix);
-    case kWords: return small ? pick_flags<L, small ? kWords : kBytes>(busy, fix) : nullptr;
-    case kShorts: return small ? nullptr : pick_flags<L, small ? kBytes : kShorts>(busy, fix);
+    case kBytes: return words ? pick_flags<L, words ? kBytes : kNoQueueOrder>(busy, fix) : nullptr;
+    case kWords: return words ? pick_flags<L, words ? kWords : kBytes>(busy, fix) : nullptr;
+    case kShorts: return shorts ? pick_flags<L, shorts ? kShorts : kBytes>(busy, fix) : nullptr;
   }
   return nullptr;
+}
+
+// Smallest LDS layout that holds max_chunks chunks per evaluation (the less
+// LDS a wavefront takes, the more of them share a CU).
+static uint32_t layout_capacity(uint32_t max_chunks) {
+  return max_chunks > 256u ? 512u : max_chunks > 128u ? 256u : max_chunks > 64u ? 128u
+       : max_chunks > 16u ? 64u : 16u;
 }
 
 static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy, bool fix) {
   if (cap == 16u) return pick_mode<Layout16>(mode, busy, fix);
   if (cap == 64u) return pick_mode<Layout64>(mode, busy, fix);
-  if (cap == 128u) return pick_mode<LayoutWide<128>>(mode, busy, fix);
+  if (cap == 128u) return pick_mode<Layout128>(mode, busy, fix);
+  if (cap == 256u) return pick_mode<LayoutWide<256>>(mode, busy, fix);
   return pick_mode<LayoutWide<512>>(mode, busy, fix);
 }
 
@@ -684,14 +694,13 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   Workspace w = carve_workspace(workspace, batch->n, tv.slots);
   const int entry_bytes =
       themis_queue_entry_bytes(batch->max_chunks, tv.on ? batch->max_coll : 0u);
-  // 8-bit entries of the 64-chunk layout are stored four at a time when the
-  // rows (2*slots bytes each) start on 4-byte boundaries
-  const bool words = entry_bytes == 1 && (tv.slots & 1u) == 0u &&
+  const uint32_t cap = tv.on ? 512u : layout_capacity(batch->max_chunks);
+  // 8-bit entries are stored four at a time by the layouts with 8-bit chunk
+  // ids when the rows (2*slots bytes each) start on 4-byte boundaries
+  const bool words = entry_bytes == 1 && cap <= 128u && (tv.slots & 1u) == 0u &&
                      ((uintptr_t)queue_order & 3u) == 0u;
-  const int mode64 = !queue_order ? kNoQueueOrder : (words ? kWords : kBytes);
-  const int modew = !queue_order ? kNoQueueOrder : (entry_bytes == 2 ? kShorts : kBytes);
-  const uint32_t cap = (tv.on || batch->max_chunks > 128u) ? 512u
-                     : batch->max_chunks > 64u ? 128u : batch->max_chunks > 16u ? 64u : 16u;
+  const int mode = !queue_order ? kNoQueueOrder
+                 : entry_bytes == 2 ? kShorts : (words ? kWords : kBytes);
   if (tv.on) {
     const TraceLayout tl = trace_layout(batch->max_chunks, batch->max_coll);
     const size_t generic = generic_area_bytes(batch->n, tv.slots);
@@ -703,7 +712,7 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                        busy, w, have_ws, trace_area, tl);
     return launch_status();
   }
-  SimKernel kernel = pick_simulate_kernel(cap, cap <= 64u ? mode64 : modew, busy != nullptr,
+  SimKernel kernel = pick_simulate_kernel(cap, mode, busy != nullptr,
                                           batch->fixed_delay != nullptr);
   if (!kernel) return THEMIS_ERR_DEVICE;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
@@ -729,12 +738,12 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   const bool have_ws = workspace != nullptr &&
                        workspace_bytes_given >= workspace_bytes(evals, batch->max_chunks);
   Workspace w = carve_workspace(workspace, evals, batch->max_chunks);
-  const uint32_t cap = batch->max_chunks > 128u ? 512u
-                     : batch->max_chunks > 64u ? 128u : batch->max_chunks > 16u ? 64u : 16u;
+  const uint32_t cap = layout_capacity(batch->max_chunks);
   const bool fix = batch->fixed_delay != nullptr;
   auto kernel = cap == 16u ? (fix ? sweep_kernel<Layout16, true> : sweep_kernel<Layout16, false>)
               : cap == 64u ? (fix ? sweep_kernel<Layout64, true> : sweep_kernel<Layout64, false>)
-              : cap == 128u ? (fix ? sweep_kernel<LayoutWide<128>, true> : sweep_kernel<LayoutWide<128>, false>)
+              : cap == 128u ? (fix ? sweep_kernel<Layout128, true> : sweep_kernel<Layout128, false>)
+              : cap == 256u ? (fix ? sweep_kernel<LayoutWide<256>, true> : sweep_kernel<LayoutWide<256>, false>)
                             : (fix ? sweep_kernel<LayoutWide<512>, true> : sweep_kernel<LayoutWide<512>, false>);
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,

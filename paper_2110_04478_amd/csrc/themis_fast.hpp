@@ -24,6 +24,8 @@
 // always hit 64 different banks, whatever per-lane index they use.
 #pragma once
 
+#include <type_traits>
+
 #include "themis_device.hpp"
 
 namespace themis {
@@ -69,7 +71,7 @@ __device__ __forceinline__ uint32_t min_field(uint64_t v) {
   return min(min(lo & 0xffffu, lo >> 16), min(hi & 0xffffu, hi >> 16));
 }
 
-// Per-lane LDS layouts with 8-bit chunk ids (kChunks <= 64).
+// Per-lane LDS layouts with 8-bit chunk ids (kChunks <= 128; 0xFF ends a list).
 //
 // Layout64 (80 dwords, 20 KiB per wavefront, 8 wavefronts per CU):
 //   dword c (0..63), one per chunk c AND per list q = 16*dim + class:
@@ -78,18 +80,22 @@ __device__ __forceinline__ uint32_t min_field(uint64_t v) {
 //     byte 2  chunk c: order code
 //     byte 3  list q: head chunk
 //   dwords 64..79  u8 tail[64]: last chunk of list q
+// LayoutByte<128> (144 dwords, 4 wavefronts per CU): the same with 128 chunk
+// dwords, of which the first 64 carry the list heads.
 // LayoutByte<16> (48 dwords, 12 KiB per wavefront, 13 wavefronts per CU; the
 // kernel runs faster the more wavefronts share a SIMD): 16 chunk dwords with
 // byte 3 unused, then u8 head[64] and u8 tail[64].
 template <uint32_t kChunks>
 struct LayoutByte {
   static constexpr uint32_t kCap = kChunks;
-  static constexpr bool kHeadInChunkWord = kChunks == 64;
+  static_assert(kChunks <= 128, "chunk ids and the list end mark share 8 bits");
+  static constexpr bool kHeadInChunkWord = kChunks >= 64;
   static constexpr uint32_t kTailBase = kHeadInChunkWord ? kChunks : kChunks + 16;
   static constexpr uint32_t kLaneWords = kTailBase + 16;
   static constexpr uint32_t kEnd = 0xffu;
   using Link = uint8_t;               // width of a chunk id in LDS
-  using Ids = Pack4<uint32_t, 8>;     // chunk id / operation count per dimension
+  // per dimension: chunk id << 2 | dimension, and the operation count (up to 2 * kChunks)
+  using Ids = typename std::conditional<(kChunks <= 64), Pack4<uint32_t, 8>, Pack4<uint64_t, 16>>::type;
   static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
                                                     uint32_t state0) {
     *(uint32_t*)l.dword(c) = (code << 16) | (kEnd << 8) | state0;
@@ -114,6 +120,7 @@ struct LayoutByte {
 };
 using Layout64 = LayoutByte<64>;
 using Layout16 = LayoutByte<16>;
+using Layout128 = LayoutByte<128>;
 
 // Layout for up to kChunks <= 512 chunks (kChunks + 64 dwords per lane):
 //   dword c: byte 0 mask | phase << 4, byte 1 order code, bytes 2-3 next

@@ -131,6 +131,9 @@ def test_large_chunk_counts(gpu, oracle):
     check_batch(gpu, oracle, w().mixed(200, seed=7, max_chunks=128))
     check_batch(gpu, oracle, w().mixed(200, seed=8, max_chunks=127))
     check_batch(gpu, oracle, w().mixed(200, seed=9, max_chunks=63))
+    check_batch(gpu, oracle, w().mixed(130, seed=10, max_chunks=256))   # 320-dword layout
+    check_batch(gpu, oracle, w().mixed(130, seed=11, max_chunks=129))
+    check_batch(gpu, oracle, w().mixed(100, seed=12, max_chunks=257))   # first size on the 576-dword one
 
 
 def test_empty_batch(gpu):
