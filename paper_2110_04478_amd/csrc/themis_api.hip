@@ -51,6 +51,16 @@ __device__ __forceinline__ bool threshold_ok(double thr, bool rel) {
   return thr >= 0.0 && (!rel || thr < inf64());
 }
 
+// A completion time of this bit pattern (a NaN no computation produces) marks
+// an evaluation that the LDS kernel leaves to the generic kernel launched
+// right behind it.  Keeping the generic path out of the LDS kernels keeps its
+// registers and scratch memory out of their budgets.
+constexpr uint64_t kLeftToGeneric = 0x7ff8a5a55a5a0001ull;
+__device__ __forceinline__ double left_to_generic() { return __longlong_as_double((long long)kLeftToGeneric); }
+__device__ __forceinline__ bool is_left_to_generic(double t) {
+  return (uint64_t)__double_as_longlong(t) == kLeftToGeneric;
+}
+
 // ---------------------------------------------------------------------------
 // themis_plan_batch: Alg. 1 per scenario (hot-path steps a1-a5).
 // ---------------------------------------------------------------------------
@@ -118,12 +128,10 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
 // themis_simulate_batch (hot-path steps a6-a9): LDS fast path, with the
 // generic workspace path for the scenarios it does not cover.
 // ---------------------------------------------------------------------------
-// (Structures by value: a reference would make the caller keep its own copy,
-// kernel arguments included, in scratch memory for the whole kernel.)
-__device__ __noinline__ void simulate_generic_scenario(const themis_batch_t b, const TraceView tv,
-                                                       const Scenario s, uint32_t Q, uint64_t i,
-                                                       const uint8_t* row, bool scf,
-                                                       const Workspace w, const SimOut out) {
+__device__ __forceinline__ void simulate_generic_scenario(const themis_batch_t& b, const TraceView& tv,
+                                                          const Scenario& s, uint32_t Q, uint64_t i,
+                                                          const uint8_t* row, bool scf,
+                                                          const Workspace& w, const SimOut& out) {
   bool ok = true;
   bool has_release = false;
   // a6: every chunk waits at the dimension of its first stage
@@ -154,10 +162,10 @@ __device__ __forceinline__ void put_queue_entry(uint8_t* rows, uint32_t at, uint
 }
 
 template <typename L, int kQueueOrder, bool kBusy, bool kFix>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
 simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                 double* __restrict__ t_done, void* __restrict__ queue_order, int entry_bytes,
-                double* __restrict__ busy, Workspace w, bool have_ws) {
+                double* __restrict__ busy, bool have_ws) {
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= b.n) return;
@@ -227,7 +235,31 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     }
   }
   if (!have_ws) { write_invalid(out); return; }
-  simulate_generic_scenario(b, tv, s, Q, i, row, scf, w, out);
+  t_done[i] = left_to_generic();
+}
+
+// Second kernel of themis_simulate_batch: the scenarios the LDS kernel marked.
+__global__ void __launch_bounds__(kBlock)
+simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
+                        double* __restrict__ t_done, void* __restrict__ queue_order,
+                        int entry_bytes, double* __restrict__ busy, Workspace w) {
+  uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= b.n || !is_left_to_generic(t_done[i])) return;
+  const TraceView tv = trace_view(b);
+  Scenario s = load_scenario(b, i);
+  const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
+  uint32_t Q;
+  collectives_ok(b, tv, i, Q);  // marked scenarios passed this check already
+  SimOut out;
+  out.t_done = t_done + i;
+  out.busy = busy ? busy + i : nullptr;
+  out.busy_stride = b.n;
+  out.entry_bytes = entry_bytes;
+  out.slots = tv.slots;
+  out.queue_order = queue_order
+      ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
+      : nullptr;
+  simulate_generic_scenario(b, tv, s, Q, i, orders + (size_t)i * tv.slots, scf, w, out);
 }
 
 // ---------------------------------------------------------------------------
@@ -312,10 +344,10 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 // themis_sweep (hot-path step a10): one lane per scenario x threshold x
 // scheduler; the plan goes straight into LDS and only the time leaves.
 // ---------------------------------------------------------------------------
-__device__ __noinline__ void sweep_generic_evaluation(const Scenario s, double chunk,
-                                                      bool themis_on, bool rel, double th,
-                                                      bool scf, uint64_t e, const Workspace w,
-                                                      const SimOut out) {
+__device__ __forceinline__ void sweep_generic_evaluation(const Scenario& s, double chunk,
+                                                         bool themis_on, bool rel, double th,
+                                                         bool scf, uint64_t e, const Workspace& w,
+                                                         const SimOut& out) {
   double load[kMaxDims];
 #pragma unroll
   for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? tracker_start(s, k) : inf64();
@@ -331,32 +363,47 @@ __device__ __noinline__ void sweep_generic_evaluation(const Scenario s, double c
       out);
 }
 
-template <typename L, bool kFix>
-__global__ void __launch_bounds__(kBlock)
-sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
-             unsigned policy_mask, int n_pol, double* __restrict__ t_done, Workspace w,
-             bool have_ws) {
-  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
-  uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
-  if (e >= total) return;
-  uint64_t i = e / ((uint64_t)n_thr * n_pol);
-  uint32_t rem = (uint32_t)(e - i * (uint64_t)n_thr * n_pol);
-  int a = (int)(rem / (uint32_t)n_pol);
-  int col = (int)(rem - (uint32_t)a * (uint32_t)n_pol);
+// What one lane of a sweep evaluates.
+struct SweepItem {
+  uint64_t i;      // scenario
+  double th;       // threshold
+  bool themis_on;  // Themis or baseline order
+  bool scf;        // Smallest-Chunk-First or FIFO
+};
+
+__device__ __forceinline__ SweepItem sweep_item(const themis_batch_t& b, uint64_t e, int n_thr,
+                                                const double* thr, int thr_per_scenario,
+                                                unsigned policy_mask, int n_pol) {
+  SweepItem it;
+  it.i = e / ((uint64_t)n_thr * n_pol);
+  const uint32_t rem = (uint32_t)(e - it.i * (uint64_t)n_thr * n_pol);
+  const int a = (int)(rem / (uint32_t)n_pol);
+  const int col = (int)(rem - (uint32_t)a * (uint32_t)n_pol);
   // col-th set bit of the mask selects the scheduler
   int bit = 0;
   for (int seen = 0; bit < 3; ++bit)
     if (policy_mask & (1u << bit)) { if (seen == col) break; ++seen; }
-  const bool themis_on = bit != 0;
-  const bool scf = bit == 2;
+  it.themis_on = bit != 0;
+  it.scf = bit == 2;
+  it.th = thr_per_scenario ? thr[(size_t)a * b.n + it.i] : thr[a];
+  return it;
+}
 
-  Scenario s = load_scenario(b, i);
+template <typename L, bool kFix>
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
+sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
+             unsigned policy_mask, int n_pol, double* __restrict__ t_done, bool have_ws) {
+  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
+  uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
+  if (e >= total) return;
+  const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
+
+  Scenario s = load_scenario(b, it.i);
   s.ctype = THEMIS_COLL_ALL_REDUCE;  // sweeps evaluate All-Reduce only
   const bool rel = b.threshold_mode == THEMIS_THR_REL;
-  const double th = thr_per_scenario ? thr[(size_t)a * b.n + i] : thr[a];
-  const double S = b.size_bytes[i];
-  bool ok = s.valid && finite_positive(S) && threshold_ok(th, rel);
+  const double S = b.size_bytes[it.i];
+  bool ok = s.valid && finite_positive(S) && threshold_ok(it.th, rel);
   if (!ok) { t_done[e] = nan64(); return; }
 
   const double chunk = S / (double)s.C;
@@ -365,15 +412,28 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     LaneLds lds;
     lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
     double load[kMaxDims];
-    plan_fast(s, fs, themis_on, rel, th, load,
+    plan_fast(s, fs, it.themis_on, rel, it.th, load,
               [&](uint32_t c, uint32_t code) { L::init_chunk(lds, c, code, 0u); });
     FastOut fo;
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;
-    FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, fs, scf, lds, fo);
+    FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, fs, it.scf, lds, fo);
     if (r.ok) { t_done[e] = r.t_done; return; }
   }
-  if (!have_ws) { t_done[e] = nan64(); return; }
+  t_done[e] = have_ws ? left_to_generic() : nan64();
+}
+
+// Second kernel of themis_sweep: the evaluations the LDS kernel marked.
+__global__ void __launch_bounds__(kBlock)
+sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
+                     int thr_per_scenario, unsigned policy_mask, int n_pol,
+                     double* __restrict__ t_done, Workspace w) {
+  uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
+  if (e >= total || !is_left_to_generic(t_done[e])) return;
+  const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
+  Scenario s = load_scenario(b, it.i);
+  s.ctype = THEMIS_COLL_ALL_REDUCE;
   SimOut out;
   out.t_done = t_done + e;
   out.busy = nullptr;
@@ -381,7 +441,8 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
   out.queue_order = nullptr;
   out.entry_bytes = 1;
   out.slots = b.max_chunks;
-  sweep_generic_evaluation(s, chunk, themis_on, rel, th, scf, e, w, out);
+  sweep_generic_evaluation(s, b.size_bytes[it.i] / (double)s.C, it.themis_on,
+                           b.threshold_mode == THEMIS_THR_REL, it.th, it.scf, e, w, out);
 }
 
 // ---------------------------------------------------------------------------
@@ -421,7 +482,7 @@ __device__ __forceinline__ uint64_t assignment_count(uint32_t D, uint32_t C, uin
 // One lane per (scenario, assignment): times[i * max_assign + a].  Slots past
 // a scenario's own count hold +inf; NaN marks a scenario that cannot be searched.
 template <typename L, bool kFix>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
 search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ times) {
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -594,8 +655,7 @@ static int launch_status() {
   return hipGetLastError() == hipSuccess ? THEMIS_OK : THEMIS_ERR_DEVICE;
 }
 
-using SimKernel = void (*)(themis_batch_t, const uint8_t*, double*, void*, int, double*, Workspace,
-                           bool);
+using SimKernel = void (*)(themis_batch_t, const uint8_t*, double*, void*, int, double*, bool);
 
 template <typename L, int kMode>
 static SimKernel pick_flags(bool busy, bool fix) {
@@ -717,7 +777,12 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   if (!kernel) return THEMIS_ERR_DEVICE;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
-                     w, have_ws);
+                     have_ws);
+  // scenarios outside the LDS path (marked in t_done) are redone from the workspace
+  if (have_ws)
+    hipLaunchKernelGGL(simulate_generic_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
+                       busy, w);
   return launch_status();
 }
 
@@ -747,7 +812,11 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
                             : (fix ? sweep_kernel<LayoutWide<512>, true> : sweep_kernel<LayoutWide<512>, false>);
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                     n_pol, t_done, w, have_ws);
+                     n_pol, t_done, have_ws);
+  if (have_ws)
+    hipLaunchKernelGGL(sweep_generic_kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
+                       n_pol, t_done, w);
   return launch_status();
 }
 

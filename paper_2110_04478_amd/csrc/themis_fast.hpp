@@ -92,6 +92,9 @@ struct LayoutByte {
   static constexpr bool kHeadInChunkWord = kChunks >= 64;
   static constexpr uint32_t kTailBase = kHeadInChunkWord ? kChunks : kChunks + 16;
   static constexpr uint32_t kLaneWords = kTailBase + 16;
+  // wavefronts per SIMD that the LDS block allows (160 KiB per CU, 4 SIMDs,
+  // rounded up): the kernels ask for a register budget that does not cap it lower
+  static constexpr uint32_t kWavesPerSimd = (160u * 1024u / (kLaneWords * 256u) + 3u) / 4u;
   static constexpr uint32_t kEnd = 0xffu;
   using Link = uint8_t;               // width of a chunk id in LDS
   // per dimension: chunk id << 2 | dimension, and the operation count (up to 2 * kChunks)
@@ -130,6 +133,7 @@ template <uint32_t kChunks>
 struct LayoutWide {
   static constexpr uint32_t kCap = kChunks;
   static constexpr uint32_t kLaneWords = kChunks + 64;
+  static constexpr uint32_t kWavesPerSimd = 1;
   static constexpr uint32_t kEnd = 0xffffu;
   using Link = uint16_t;
   using Ids = Pack4<uint64_t, 16>;
