@@ -476,3 +476,56 @@ def test_extreme_magnitudes_fall_back_to_the_generic_path(gpu, oracle):
                      [8, 5, 8, 3, 8, 8, 6] * reps, 1, [1, 0, 1, 1, 0, 1, 1] * reps, 0.0,
                      max_chunks=8)
     check_batch(gpu, oracle, b)
+
+
+def test_entry_points_replay_inside_a_hip_graph(gpu, oracle):
+    """The C ABI allocates nothing and only launches kernels on the caller's
+    stream, so plan + simulate + sweep can be captured into a HIP graph once and
+    replayed; every replay (with eager work and synchronisations in between)
+    must reproduce the eager, oracle-checked result bit for bit."""
+    import torch
+    b = w().mixed(3000, seed=77)           # includes scenarios that go to the generic kernel
+    d = gpu.to_device(b)
+    n = d.n
+    orders = torch.empty((n, d.slots), dtype=torch.uint8, device="cuda")
+    loads = torch.empty((4, n), dtype=torch.float64, device="cuda")
+    t_done = torch.empty(n, dtype=torch.float64, device="cuda")
+    busy = torch.empty((4, n), dtype=torch.float64, device="cuda")
+    qo = torch.empty((n, 4, 2 * d.slots), dtype=torch.uint8, device="cuda")
+    thr = torch.tensor([0.0, 0.25], dtype=torch.float64, device="cuda")
+    sw = torch.empty((n, 2, 3), dtype=torch.float64, device="cuda")
+    ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(n * 6, d.max_chunks))
+
+    def run():
+        gpu.themis_plan_batch(d, orders, loads)
+        gpu.themis_simulate_batch(d, orders, t_done, qo, busy, ws)
+        gpu.themis_sweep(d, thr, 7, t_done=sw, workspace=ws)
+
+    run()
+    torch.cuda.synchronize()
+    want = [x.clone() for x in (orders, loads, t_done, busy, qo, sw)]
+    o_orders, _ = oracle.plan_batch(b, threads=8)
+    o_t, _, _ = oracle.simulate_batch(b, o_orders, want_queue_order=False, threads=8)
+    assert np.array_equal(want[0].cpu().numpy(), o_orders)
+    assert_close("eager t_done", want[2].cpu().numpy(), o_t)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        run()                               # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for x in (orders, loads, t_done, busy, qo, sw):
+            x.fill_(7 if x.dtype == torch.uint8 else -1.0)   # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, ref in zip(("orders", "loads", "t_done", "busy", "queue_order", "sweep"),
+                                  (orders, loads, t_done, busy, qo, sw), want):
+            same = torch.equal(got, ref) if got.dtype == torch.uint8 else bool(
+                ((got == ref) | (torch.isnan(got) & torch.isnan(ref))).all())
+            assert same, f"replay {rep}: {name} differs from the eager run"
