@@ -266,12 +266,13 @@ simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 // themis_simulate_batch for traces (several collectives sharing the queues):
 // the ranked-list path of themis_trace.hpp, else the generic path.
 // ---------------------------------------------------------------------------
+template <bool kLdsBitmaps>
 __global__ void __launch_bounds__(kBlock)
 simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                       double* __restrict__ t_done, void* __restrict__ queue_order,
                       int entry_bytes, double* __restrict__ busy, Workspace w, bool have_ws,
                       uint8_t* __restrict__ trace_area, TraceLayout tl) {
-  __shared__ uint32_t lds_block[kTraceLdsWords * kBlock];
+  __shared__ uint32_t lds_block[(kLdsBitmaps ? kTraceLdsWordsBitmaps : kTraceLdsWords) * kBlock];
   uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= b.n) return;
   const TraceView tv = trace_view(b);
@@ -322,7 +323,7 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
       double T, z[kMaxDims];
       uint32_t ex[kMaxDims];
-      if (simulate_trace_fast(s, Q, epack, fs0.state0, fs0.rs_only, scf, rg, lds, out, T, z, ex)) {
+      if (simulate_trace_fast<kLdsBitmaps>(s, Q, epack, fs0.state0, fs0.rs_only, scf, rg, lds, out, T, z, ex)) {
         t_done[i] = T;
         if (busy) {
 #pragma unroll
@@ -651,6 +652,15 @@ static int check_batch(const themis_batch_t* b, bool need_intra, bool need_inter
   return THEMIS_OK;
 }
 
+// Compute units of the current device (0 if the query fails: callers then take
+// the variant that suits large grids).
+static unsigned compute_units() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  return cus > 0 ? (unsigned)cus : 0u;
+}
+
 static int launch_status() {
   return hipGetLastError() == hipSuccess ? THEMIS_OK : THEMIS_ERR_DEVICE;
 }
@@ -767,7 +777,10 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
     const bool have_trace = workspace != nullptr && tl.bytes != 0u &&
                             workspace_bytes_given >= generic + (size_t)batch->n * tl.bytes;
     uint8_t* trace_area = have_trace ? (uint8_t*)workspace + generic : nullptr;
-    hipLaunchKernelGGL(simulate_trace_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+    // few wavefronts (no more than CUs): the bitmap leaves move into the LDS nothing else would use
+    auto trace_kernel = blocks_for(batch->n) <= compute_units() ? simulate_trace_kernel<true>
+                                                                 : simulate_trace_kernel<false>;
+    hipLaunchKernelGGL(trace_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
                        busy, w, have_ws, trace_area, tl);
     return launch_status();

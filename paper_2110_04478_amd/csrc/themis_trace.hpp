@@ -135,12 +135,21 @@ __device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, 
   return rank + 1u;
 }
 
-constexpr uint32_t kTraceLdsWords = 48;  // per lane, for trace_build_ranks
+// Per-lane LDS of the trace path: 48 dwords for trace_build_ranks, reused
+// afterwards for the summary words (dwords 0-15) and, in the large variant,
+// followed by the bitmap leaves of all four dimensions.  The large variant
+// (132 KiB per wavefront, one wavefront per CU) is for batches of no more
+// wavefronts than CUs, where nothing else could have used the LDS anyway.
+constexpr uint32_t kTraceLdsWords = 48;
+constexpr uint32_t kTraceLdsWordsBitmaps = 16 + 4 * kTraceLeafWords;
 
 // Runs the simulation of one trace.  The region must hold CH[q] (resident
 // bytes at mask 0 of a chunk of collective q) and W[g] = trace_word(stored
 // code, state0) for g = q*C + i; state0 / rs_only as in FastScenario.
 // Returns false if time failed to advance somewhere (generic path decides).
+// kLdsBitmaps: the bitmap leaves live in LDS (kTraceLdsWordsBitmaps dwords per
+// lane) instead of the region; the summary words always do.
+template <bool kLdsBitmaps>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
                                            uint32_t state0, bool rs_only, bool scf,
                                            const TraceRegion& rg, const LaneLds& lds,
@@ -154,14 +163,29 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   const double kInf = inf64();
 
   if (scf) trace_build_ranks(rg, Q, D, epack, lds);
+  // non-empty bitmaps: one summary word per 32 leaves, one leaf bit per rank
+  auto SUM = [&](uint32_t k, uint32_t sw) -> uint32_t& {
+    return *(uint32_t*)lds.dword((k & 3u) * kTraceSumWords + (sw & (kTraceSumWords - 1u)));
+  };
+  auto BM = [&](uint32_t k, uint32_t leaf) -> uint32_t& {
+    if (kLdsBitmaps)
+      return *(uint32_t*)lds.dword(16u + (k & 3u) * kTraceLeafWords + (leaf & (kTraceLeafWords - 1u)));
+    return rg.BM(k, leaf);
+  };
   for (uint32_t k = 0; k < 4u; ++k) {
-    for (uint32_t l = 0; l < kTraceLeafWords; ++l) rg.BM(k, l) = 0u;
-    for (uint32_t l = 0; l < kTraceSumWords; ++l) rg.SUM(k, l) = 0u;
+    for (uint32_t l = 0; l < kTraceLeafWords; ++l) BM(k, l) = 0u;
+    for (uint32_t l = 0; l < kTraceSumWords; ++l) SUM(k, l) = 0u;
   }
 
   double f[kMaxDims] = {kInf, kInf, kInf, kInf};
   double z[kMaxDims] = {0.0, 0.0, 0.0, 0.0};
   uint32_t serving[kMaxDims] = {0u, 0u, 0u, 0u};
+  // what the completion of the chunk a dimension serves will do, worked out at
+  // dispatch so that the completion itself reads nothing but its target list:
+  // the chunk's next word, its next dimension (4 = finished) and size rank there
+  uint32_t next_word[kMaxDims] = {0u, 0u, 0u, 0u};
+  uint32_t next_dim[kMaxDims] = {4u, 4u, 4u, 4u};
+  uint32_t next_rank[kMaxDims] = {0u, 0u, 0u, 0u};
   uint32_t executed[kMaxDims] = {0u, 0u, 0u, 0u};
   uint32_t waiting[kMaxDims] = {0u, 0u, 0u, 0u};
   bool stalled = false;
@@ -171,37 +195,39 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   };
   auto push = [&](uint32_t k, uint32_t r, uint32_t g) {
     const uint32_t leaf = r >> 5, bit = 1u << (r & 31u);
-    const uint32_t lw = rg.BM(k, leaf);
+    const uint32_t lw = BM(k, leaf);
     if (lw & bit) {
       const uint32_t ht = rg.HT(k, r);
       const uint32_t tl = ht >> 16;
-      rg.W(tl) = (rg.W(tl) & 0xffffu) | (g << 16);
+      ((uint16_t*)&rg.W(tl))[1] = (uint16_t)g;  // the old tail's next field
       rg.HT(k, r) = (ht & 0xffffu) | (g << 16);
     } else {
       rg.HT(k, r) = g | (g << 16);
-      rg.BM(k, leaf) = lw | bit;
-      rg.SUM(k, leaf >> 5) |= 1u << (leaf & 31u);
+      BM(k, leaf) = lw | bit;
+      SUM(k, leaf >> 5) |= 1u << (leaf & 31u);
     }
 #pragma unroll
     for (uint32_t kk = 0; kk < 4u; ++kk) waiting[kk] += (kk == k) ? 1u : 0u;
   };
-  // first chunk of the lowest non-empty rank (smallest resident size)
-  auto pop = [&](uint32_t k) -> uint32_t {
+  // first chunk of the lowest non-empty rank (smallest resident size); w
+  // receives its chunk word
+  auto pop = [&](uint32_t k, uint32_t& w) -> uint32_t {
     uint32_t leaf = 0;
     for (uint32_t sw = 0; sw < kTraceSumWords; ++sw) {
-      const uint32_t v = rg.SUM(k, sw);
+      const uint32_t v = SUM(k, sw);
       if (v) { leaf = sw * 32u + (uint32_t)__builtin_ctz(v); break; }
     }
-    const uint32_t lw = rg.BM(k, leaf);
+    const uint32_t lw = BM(k, leaf);
     const uint32_t r = leaf * 32u + (lw ? (uint32_t)__builtin_ctz(lw) : 0u);
     const uint32_t ht = rg.HT(k, r);
     const uint32_t h = ht & 0xffffu, tl = ht >> 16;
+    w = rg.W(h);
     if (h == tl) {
       const uint32_t nlw = lw & ~(1u << (r & 31u));
-      rg.BM(k, leaf) = nlw;
-      if (!nlw) rg.SUM(k, leaf >> 5) &= ~(1u << (leaf & 31u));
+      BM(k, leaf) = nlw;
+      if (!nlw) SUM(k, leaf >> 5) &= ~(1u << (leaf & 31u));
     } else {
-      rg.HT(k, r) = (rg.W(h) >> 16) | (tl << 16);
+      rg.HT(k, r) = (w >> 16) | (tl << 16);
     }
 #pragma unroll
     for (uint32_t kk = 0; kk < 4u; ++kk) waiting[kk] -= (kk == k) ? 1u : 0u;
@@ -226,8 +252,8 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       for (uint32_t kk = 0; kk < 4u; ++kk) need |= (f[kk] == kInf && waiting[kk] != 0u) ? (1u << kk) : 0u;
       if (!need) break;
       const uint32_t k = (uint32_t)__builtin_ctz(need);
-      const uint32_t h = pop(k);
-      const uint32_t w = rg.W(h);
+      uint32_t w;
+      const uint32_t h = pop(k, w);
       const uint32_t mask = w & 15u, phase = (w >> 4) & 1u;
       const uint32_t ek = (epack >> (8u * k)) & 0xffu;
       const uint32_t E = esum(epack, mask) - (phase ? ek : 0u);
@@ -236,6 +262,17 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       const double fin = now + t;
       // a stage that does not move the clock, or overflows it: generic path decides
       stalled |= !(fin > now && fin < kInf);
+      // the chunk's state after this stage: a Reduce-Scatter sets the
+      // dimension's bit, an All-Gather clears it
+      const uint32_t code = (w >> 8) & 0xffu;
+      const uint32_t mask2 = mask ^ (1u << k);
+      const bool finished = (phase != 0u && mask2 == 0u) || (rs_only && mask2 == full);
+      const uint32_t phase2 = phase | ((mask2 == full) ? 1u : 0u);  // last RS: AG starts on the same dim
+      // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
+      const uint32_t p = (uint32_t)__builtin_popcount(mask2) - phase2;
+      const uint32_t kn = finished ? 4u : (code >> ((2u * p) & 31u)) & 3u;
+      const uint32_t rk = finished ? 0u : rank_of(h, mask2);
+      const uint32_t nw = mask2 | (phase2 << 4) | (code << 8) | (kNoChunk << 16);
       uint32_t pos = 0;
 #pragma unroll
       for (uint32_t kk = 0; kk < 4u; ++kk) {
@@ -243,6 +280,9 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
           f[kk] = fin;
           z[kk] = z[kk] + t;
           serving[kk] = h;
+          next_word[kk] = nw;
+          next_dim[kk] = kn;
+          next_rank[kk] = rk;
           pos = executed[kk];
           executed[kk] = pos + 1u;
         }
@@ -268,17 +308,13 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
         if ((done >> kk & 1u) && serving[kk] < best) { best = serving[kk]; k = kk; }
       done &= ~(1u << k);
       const uint32_t g = best;
-      const uint32_t w = rg.W(g);
-      const uint32_t code = (w >> 8) & 0xffu;
-      uint32_t phase = (w >> 4) & 1u;
-      const uint32_t mask = (w & 15u) ^ (1u << k);
-      const bool finished = (phase != 0u && mask == 0u) || (rs_only && mask == full);
-      phase |= (mask == full) ? 1u : 0u;
-      if (!finished) {
-        const uint32_t p = (uint32_t)__builtin_popcount(mask) - phase;
-        const uint32_t kn = (code >> ((2u * p) & 31u)) & 3u;
-        rg.W(g) = mask | (phase << 4) | (code << 8) | (kNoChunk << 16);
-        push(kn, rank_of(g, mask), g);
+      uint32_t nw = 0, kn = 4u, rk = 0;
+#pragma unroll
+      for (uint32_t kk = 0; kk < 4u; ++kk)
+        if (kk == k) { nw = next_word[kk]; kn = next_dim[kk]; rk = next_rank[kk]; }
+      if (kn < 4u) {
+        rg.W(g) = nw;
+        push(kn, rk, g);
       }
     } while (done);
   }

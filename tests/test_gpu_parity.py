@@ -229,6 +229,9 @@ def test_traces_ranked_list_path(gpu, oracle):
     # non-power-of-two NPU counts in a trace stay on the generic path
     b = _add_trace(w().mixed(100, seed=43, max_chunks=8, pow2=False), rng, 5, pow2_sizes=False)
     check_batch(gpu, oracle, b)
+    # more wavefronts than CUs: the variant that keeps its bitmaps in the workspace
+    b = _add_trace(w().mixed(256 * 64 + 700, seed=44, max_chunks=5), rng, 3, pow2_sizes=True)
+    check_batch(gpu, oracle, b, threads=16)
 
 
 def test_trace_with_generic_only_workspace(gpu, oracle):
