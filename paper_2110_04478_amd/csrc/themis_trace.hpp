@@ -30,7 +30,7 @@ struct TraceLayout {
   uint32_t G;   // chunk slots (max_chunks * max_coll)
   uint32_t Q;   // collectives the region is sized for
   uint32_t R;   // ranks per dimension = Q * 16
-  uint32_t off_ht, off_bm, off_sum, off_sr, off_ch, off_sq;
+  uint32_t off_ht, off_bm, off_sr, off_ch, off_sq;
   uint32_t bytes;  // multiple of 16; 0 if the batch cannot use this path
 };
 
@@ -42,8 +42,7 @@ __host__ __device__ inline TraceLayout trace_layout(uint32_t max_chunks, uint32_
   if (max_coll == 0u || max_coll > kTraceMaxColl) { t.bytes = 0; return t; }
   uint32_t o = t.G * 4u;                   // W: one dword per chunk
   t.off_ht = o;  o += 4u * t.R * 4u;       // head | tail << 16 per (dimension, rank)
-  t.off_bm = o;  o += 4u * kTraceLeafWords * 4u;
-  t.off_sum = o; o += 4u * kTraceSumWords * 4u;
+  t.off_bm = o;  o += 4u * kTraceLeafWords * 4u;   // bitmap leaves (when they are not in LDS)
   t.off_ch = (o + 7u) & ~7u; o = t.off_ch + t.Q * 8u;   // chunk bytes per collective
   t.off_sr = o;  o += t.R * 2u;            // size rank per (collective, mask)
   t.off_sq = o;  o += t.Q * 2u;            // collectives sorted by chunk size
@@ -64,9 +63,6 @@ struct TraceRegion {
   }
   __device__ __forceinline__ uint32_t& BM(uint32_t k, uint32_t leaf) const {
     return ((uint32_t*)(base + t.off_bm))[(k & 3u) * kTraceLeafWords + (leaf & (kTraceLeafWords - 1u))];
-  }
-  __device__ __forceinline__ uint32_t& SUM(uint32_t k, uint32_t sw) const {
-    return ((uint32_t*)(base + t.off_sum))[(k & 3u) * kTraceSumWords + (sw & (kTraceSumWords - 1u))];
   }
   __device__ __forceinline__ double& CH(uint32_t q) const {
     return ((double*)(base + t.off_ch))[q < t.Q ? q : t.Q - 1u];
