@@ -154,8 +154,10 @@ def main():
     import numpy as np
     import torch
     from paper_2110_04478_amd import binding, workloads
+    from paper_2110_04478_amd.csrc.build import ensure_built
 
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    ensure_built()          # compiles only when no library is in the tree
     torch.cuda.set_device(0)
     if args.copy_probe:
         src = torch.full((args.copy_probe << 20,), 7, dtype=torch.uint8, device="cuda:0")

@@ -38,5 +38,11 @@ def build(force: bool = True, extra=()) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only if no library is there at all (tests, smoke and bench call
+    this; the binding itself never builds and fails loudly instead)."""
+    return LIB if os.path.exists(LIB) else build(force=True)
+
+
 if __name__ == "__main__":
     print(build(force=True, extra=sys.argv[1:]))

@@ -4,7 +4,16 @@ import ctypes
 import os
 import re
 
+import pytest
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built_library():
+    """hipcc cross-compiles without a GPU; compiles only when no library is in the tree."""
+    from paper_2110_04478_amd.csrc.build import ensure_built
+    ensure_built()
 
 
 def declared_functions():
