@@ -429,6 +429,14 @@ def test_exhaustive_search_matches_oracle(gpu, oracle):
     assert np.isnan(want_t[3])
     assert_close("best_t", got_t.cpu().numpy(), want_t)
     assert np.array_equal(got_od.cpu().numpy(), want_od)
+    # the same search with fixed per-stage delays, rows wide enough for the 64-chunk layout
+    b2 = W.make_batch(D, P, bw, b.size_bytes, C, 1, b.intra_policy, 0.0, max_chunks=20)
+    b2.fixed_delay = np.ascontiguousarray(rng.uniform(0, 5e-6, (4, n)))
+    w2_t, w2_od = oracle.search_batch(b2, bound, threads=8)
+    g2_t, g2_od = gpu.themis_search_batch(gpu.to_device(b2), bound)
+    torch.cuda.synchronize()
+    assert_close("best_t (fixed delay)", g2_t.cpu().numpy(), w2_t)
+    assert np.array_equal(g2_od.cpu().numpy(), w2_od)
     # the greedy plan can never beat the exhaustive optimum
     orders, _ = gpu.themis_plan_batch(d)
     t, _, _ = gpu.themis_simulate_batch(d, orders, want_queue_order=False)
