@@ -231,6 +231,13 @@ def test_traces_ranked_list_path(gpu, oracle):
     # non-power-of-two NPU counts in a trace stay on the generic path
     b = _add_trace(w().mixed(100, seed=43, max_chunks=8, pow2=False), rng, 5, pow2_sizes=False)
     check_batch(gpu, oracle, b)
+    # the largest trace the ranked lists take (256 collectives) and one beyond it (generic path)
+    b = _add_trace(w().mixed(40, seed=45, max_chunks=4), rng, 256, pow2_sizes=False)
+    b.n_coll[:20] = 256
+    check_batch(gpu, oracle, b, threads=16)
+    b = _add_trace(w().mixed(12, seed=46, max_chunks=3), rng, 300, pow2_sizes=True)
+    b.n_coll[:6] = 300
+    check_batch(gpu, oracle, b, threads=16)
     # more wavefronts than CUs: the variant that keeps its bitmaps in the workspace
     b = _add_trace(w().mixed(256 * 64 + 700, seed=44, max_chunks=5), rng, 3, pow2_sizes=True)
     check_batch(gpu, oracle, b, threads=16)
