@@ -703,9 +703,9 @@ static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy, bool fi
 }
 
 // The generic area comes first in the workspace, rounded up so that the trace
-// regions behind it stay 16-byte aligned.
+// regions behind it keep the workspace's alignment up to 64 bytes.
 static size_t generic_area_bytes(uint64_t evals, uint64_t slots) {
-  return (workspace_bytes(evals, slots) + 15u) & ~(size_t)15u;
+  return (workspace_bytes(evals, slots) + 63u) & ~(size_t)63u;
 }
 
 static unsigned blocks_for(uint64_t items) { return (unsigned)((items + kBlock - 1) / kBlock); }

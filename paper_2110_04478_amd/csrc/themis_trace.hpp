@@ -24,13 +24,14 @@ constexpr uint32_t kTraceMaxColl = 256;   // ranks <= 4096: 128 bitmap leaves, 4
 constexpr uint32_t kTraceLeafWords = kTraceMaxColl * 16 / 32;
 constexpr uint32_t kTraceSumWords = 4;
 constexpr uint32_t kNoChunk = 0xffffu;
+constexpr uint32_t kTraceCollBytes = 64;
 
 // Byte offsets inside one scenario's region of the workspace.
 struct TraceLayout {
   uint32_t G;   // chunk slots (max_chunks * max_coll)
   uint32_t Q;   // collectives the region is sized for
   uint32_t R;   // ranks per dimension = Q * 16
-  uint32_t off_ht, off_bm, off_sr, off_ch, off_sq;
+  uint32_t off_ht, off_bm, off_col, off_sq;
   uint32_t bytes;  // multiple of 16; 0 if the batch cannot use this path
 };
 
@@ -43,10 +44,11 @@ __host__ __device__ inline TraceLayout trace_layout(uint32_t max_chunks, uint32_
   uint32_t o = t.G * 4u;                   // W: one dword per chunk
   t.off_ht = o;  o += 4u * t.R * 4u;       // head | tail << 16 per (dimension, rank)
   t.off_bm = o;  o += 4u * kTraceLeafWords * 4u;   // bitmap leaves (when they are not in LDS)
-  t.off_ch = (o + 7u) & ~7u; o = t.off_ch + t.Q * 8u;   // chunk bytes per collective
-  t.off_sr = o;  o += t.R * 2u;            // size rank per (collective, mask)
+  // one 64-byte record per collective: chunk bytes (f64) and the size rank of
+  // each of the 16 masks (u16) -- a dispatch needs both, and gets them from one line
+  t.off_col = (o + 63u) & ~63u; o = t.off_col + t.Q * kTraceCollBytes;
   t.off_sq = o;  o += t.Q * 2u;            // collectives sorted by chunk size
-  t.bytes = (o + 15u) & ~15u;
+  t.bytes = (o + 63u) & ~63u;
   return t;
 }
 
@@ -65,10 +67,10 @@ struct TraceRegion {
     return ((uint32_t*)(base + t.off_bm))[(k & 3u) * kTraceLeafWords + (leaf & (kTraceLeafWords - 1u))];
   }
   __device__ __forceinline__ double& CH(uint32_t q) const {
-    return ((double*)(base + t.off_ch))[q < t.Q ? q : t.Q - 1u];
+    return *(double*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes);
   }
   __device__ __forceinline__ uint16_t& SR(uint32_t q, uint32_t mask) const {
-    return ((uint16_t*)(base + t.off_sr))[(q < t.Q ? q : t.Q - 1u) * 16u + (mask & 15u)];
+    return ((uint16_t*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes + 8u))[mask & 15u];
   }
   __device__ __forceinline__ uint16_t& SQ(uint32_t j) const {
     return ((uint16_t*)(base + t.off_sq))[j < t.Q ? j : t.Q - 1u];
