@@ -149,7 +149,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build evaluates one GPU's share on one GPU; "
-                 "run with --gpus 1 (scenarios are independent, see DESIGN.md on sharding)")
+                 "run with --gpus 1 (scenarios are independent: a batch shards by scenario range)")
 
     import numpy as np
     import torch
