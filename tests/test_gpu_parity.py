@@ -549,3 +549,37 @@ def test_entry_points_replay_inside_a_hip_graph(gpu, oracle):
             same = torch.equal(got, ref) if got.dtype == torch.uint8 else bool(
                 ((got == ref) | (torch.isnan(got) & torch.isnan(ref))).all())
             assert same, f"replay {rep}: {name} differs from the eager run"
+
+
+@pytest.mark.parametrize("max_chunks,pow2,thr_mode", [(2, True, 0), (64, True, 1), (64, False, 0),
+                                                      (100, True, 1)])
+def test_special_values(gpu, oracle, max_chunks, pow2, thr_mode):
+    """Thresholds 0 / denormal / huge / infinite / negative / NaN, sizes of one
+    byte, 2^60 bytes, 1e-300 bytes (halvings leave the normal range), zero and
+    infinity, bandwidths 60 orders of magnitude apart: valid ones must match
+    the oracle, invalid ones come back as NaN / all-ones on both sides."""
+    n = 1200
+    rng = np.random.default_rng(900 + max_chunks)
+    b = w().mixed(n, seed=901 + max_chunks, max_chunks=max_chunks, pow2=pow2, thr_mode=thr_mode)
+    sel = rng.random(n)
+    thr = b.threshold.copy()
+    thr[sel < 0.1] = np.inf if thr_mode == 0 else 1e300
+    thr[(sel >= 0.1) & (sel < 0.2)] = 5e-324
+    thr[(sel >= 0.2) & (sel < 0.25)] = -1.0
+    thr[(sel >= 0.25) & (sel < 0.28)] = np.nan
+    b.threshold = thr
+    sel = rng.random(n)
+    S = b.size_bytes.copy()
+    S[sel < 0.1] = 1.0
+    S[(sel >= 0.1) & (sel < 0.2)] = 2.0 ** 60
+    S[(sel >= 0.2) & (sel < 0.25)] = 1e-300
+    S[(sel >= 0.25) & (sel < 0.27)] = 0.0
+    S[(sel >= 0.27) & (sel < 0.29)] = np.inf
+    b.size_bytes = S
+    sel = rng.random((4, n))
+    bw = b.bw.copy()
+    bw[sel < 0.03] = 1e-30
+    bw[(sel >= 0.03) & (sel < 0.06)] = 1e30
+    b.bw = np.ascontiguousarray(bw)
+    t = check_batch(gpu, oracle, b, threads=16)
+    assert 0 < int(np.isnan(t).sum()) < n
