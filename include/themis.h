@@ -164,10 +164,12 @@ int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
  *   - single collectives with power-of-two NPU counts and sizes whose
  *     halvings stay in the normal binary64 range run entirely in registers
  *     and LDS and need no workspace;
- *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace;
- *   - everything else (an NPU count that is not a power of two, extreme
- *     magnitudes, staggered release times) runs on a generic path with
- *     per-chunk state in the workspace.
+ *   - the other single collectives (an NPU count that is not a power of two,
+ *     extreme magnitudes) run on a generic path whose per-chunk state also
+ *     sits in LDS while max_chunks <= 64 (no workspace needed), and in the
+ *     workspace beyond;
+ *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace
+ *     (staggered release times: on the generic path, in the workspace too).
  * For themis_sweep pass n * n_thr * n_pol as n and max_coll = 0.
  * Passing a smaller or NULL workspace is allowed: every scenario that would
  * have needed it then comes back as NaN / all-ones, like an invalid one (the

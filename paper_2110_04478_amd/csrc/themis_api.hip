@@ -128,9 +128,11 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
 // themis_simulate_batch (hot-path steps a6-a9): LDS fast path, with the
 // generic workspace path for the scenarios it does not cover.
 // ---------------------------------------------------------------------------
+// i: scenario; col: its column of the workspace arrays.
+template <bool kEager>
 __device__ __forceinline__ void simulate_generic_scenario(const themis_batch_t& b, const TraceView& tv,
                                                           const Scenario& s, uint32_t Q, uint64_t i,
-                                                          const uint8_t* row, bool scf,
+                                                          uint64_t col, const uint8_t* row, bool scf,
                                                           const Workspace& w, const SimOut& out) {
   bool ok = true;
   bool has_release = false;
@@ -142,15 +144,15 @@ __device__ __forceinline__ void simulate_generic_scenario(const themis_batch_t& 
     for (uint32_t c = 0; c < s.C; ++c) {
       uint32_t code = row[(size_t)q * b.max_chunks + c];
       if (!order_code_ok(code, s.D)) ok = false;
-      size_t at = (size_t)(q * s.C + c) * w.stride + i;
+      size_t at = (size_t)(q * s.C + c) * w.stride + col;
       w.meta[at] = code << 8;
       w.size[at] = chunk;
       w.arrival[at] = rel;
     }
   }
   if (!ok) { write_invalid(out); return; }
-  simulate_generic(
-      s, Q, scf, w, i,
+  simulate_generic<kEager>(
+      s, Q, scf, w, col,
       [&](uint32_t q) { return collective_size(b, tv, i, q) / (double)s.C; },
       [&](uint32_t q) { return collective_release(b, tv, i, q); }, has_release, out);
 }
@@ -165,7 +167,7 @@ template <typename L, int kQueueOrder, bool kBusy, bool kFix>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
 simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                 double* __restrict__ t_done, void* __restrict__ queue_order, int entry_bytes,
-                double* __restrict__ busy, bool have_ws) {
+                double* __restrict__ busy, bool hand_over) {
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= b.n) return;
@@ -234,17 +236,28 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       return;
     }
   }
-  if (!have_ws) { write_invalid(out); return; }
+  // hand_over: a generic kernel follows (it has the memory it needs)
+  if (!hand_over) { write_invalid(out); return; }
   t_done[i] = left_to_generic();
 }
 
 // Second kernel of themis_simulate_batch: the scenarios the LDS kernel marked.
+// kLdsSlots > 0: the per-chunk arrays (20 bytes per chunk) live in LDS, laid
+// out like the workspace with the 64 lanes as columns; for batches of at most
+// kLdsSlots chunk slots per scenario, which then need no workspace at all.
+template <uint32_t kLdsSlots>
 __global__ void __launch_bounds__(kBlock)
 simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                         double* __restrict__ t_done, void* __restrict__ queue_order,
                         int entry_bytes, double* __restrict__ busy, Workspace w) {
+  __shared__ double lds_block[kLdsSlots ? (kLdsSlots * kBlock * 5u + 1u) / 2u : 1u];
   uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= b.n || !is_left_to_generic(t_done[i])) return;
+  uint64_t col = i;
+  if (kLdsSlots) {
+    w = carve_workspace(lds_block, kBlock, kLdsSlots);
+    col = threadIdx.x;
+  }
   const TraceView tv = trace_view(b);
   Scenario s = load_scenario(b, i);
   const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
@@ -259,7 +272,7 @@ simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
   out.queue_order = queue_order
       ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
       : nullptr;
-  simulate_generic_scenario(b, tv, s, Q, i, orders + (size_t)i * tv.slots, scf, w, out);
+  simulate_generic_scenario<(kLdsSlots > 0)>(b, tv, s, Q, i, col, orders + (size_t)i * tv.slots, scf, w, out);
 }
 
 // ---------------------------------------------------------------------------
@@ -338,13 +351,14 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     }
   }
   if (!have_ws) { write_invalid(out); return; }
-  simulate_generic_scenario(b, tv, s, Q, i, row, scf, w, out);
+  simulate_generic_scenario<false>(b, tv, s, Q, i, i, row, scf, w, out);
 }
 
 // ---------------------------------------------------------------------------
 // themis_sweep (hot-path step a10): one lane per scenario x threshold x
 // scheduler; the plan goes straight into LDS and only the time leaves.
 // ---------------------------------------------------------------------------
+template <bool kEager>
 __device__ __forceinline__ void sweep_generic_evaluation(const Scenario& s, double chunk,
                                                          bool themis_on, bool rel, double th,
                                                          bool scf, uint64_t e, const Workspace& w,
@@ -359,7 +373,7 @@ __device__ __forceinline__ void sweep_generic_evaluation(const Scenario& s, doub
     w.size[at] = chunk;
     w.arrival[at] = 0.0;
   }
-  simulate_generic(
+  simulate_generic<kEager>(
       s, 1u, scf, w, e, [&](uint32_t) { return chunk; }, [&](uint32_t) { return 0.0; }, false,
       out);
 }
@@ -393,7 +407,7 @@ __device__ __forceinline__ SweepItem sweep_item(const themis_batch_t& b, uint64_
 template <typename L, bool kFix>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
 sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
-             unsigned policy_mask, int n_pol, double* __restrict__ t_done, bool have_ws) {
+             unsigned policy_mask, int n_pol, double* __restrict__ t_done, bool hand_over) {
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
@@ -421,17 +435,25 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, fs, it.scf, lds, fo);
     if (r.ok) { t_done[e] = r.t_done; return; }
   }
-  t_done[e] = have_ws ? left_to_generic() : nan64();
+  t_done[e] = hand_over ? left_to_generic() : nan64();
 }
 
-// Second kernel of themis_sweep: the evaluations the LDS kernel marked.
+// Second kernel of themis_sweep: the evaluations the LDS kernel marked
+// (kLdsSlots as in simulate_generic_kernel).
+template <uint32_t kLdsSlots>
 __global__ void __launch_bounds__(kBlock)
 sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
                      int thr_per_scenario, unsigned policy_mask, int n_pol,
                      double* __restrict__ t_done, Workspace w) {
+  __shared__ double lds_block[kLdsSlots ? (kLdsSlots * kBlock * 5u + 1u) / 2u : 1u];
   uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
   if (e >= total || !is_left_to_generic(t_done[e])) return;
+  uint64_t col = e;
+  if (kLdsSlots) {
+    w = carve_workspace(lds_block, kBlock, kLdsSlots);
+    col = threadIdx.x;
+  }
   const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
   Scenario s = load_scenario(b, it.i);
   s.ctype = THEMIS_COLL_ALL_REDUCE;
@@ -442,8 +464,8 @@ sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr
   out.queue_order = nullptr;
   out.entry_bytes = 1;
   out.slots = b.max_chunks;
-  sweep_generic_evaluation(s, b.size_bytes[it.i] / (double)s.C, it.themis_on,
-                           b.threshold_mode == THEMIS_THR_REL, it.th, it.scf, e, w, out);
+  sweep_generic_evaluation<(kLdsSlots > 0)>(s, b.size_bytes[it.i] / (double)s.C, it.themis_on,
+                           b.threshold_mode == THEMIS_THR_REL, it.th, it.scf, col, w, out);
 }
 
 // ---------------------------------------------------------------------------
@@ -788,12 +810,16 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   SimKernel kernel = pick_simulate_kernel(cap, mode, busy != nullptr,
                                           batch->fixed_delay != nullptr);
   if (!kernel) return THEMIS_ERR_DEVICE;
+  // scenarios outside the LDS path (marked in t_done) are redone by the generic
+  // kernel: with its arrays in LDS up to 64 chunks, from the workspace beyond
+  auto generic = cap <= 16u ? simulate_generic_kernel<16> : cap <= 64u ? simulate_generic_kernel<64>
+                                                                       : simulate_generic_kernel<0>;
+  const bool hand_over = cap <= 64u || have_ws;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
-                     have_ws);
-  // scenarios outside the LDS path (marked in t_done) are redone from the workspace
-  if (have_ws)
-    hipLaunchKernelGGL(simulate_generic_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+                     hand_over);
+  if (hand_over)
+    hipLaunchKernelGGL(generic, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
                        busy, w);
   return launch_status();
@@ -823,11 +849,14 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
               : cap == 128u ? (fix ? sweep_kernel<Layout128, true> : sweep_kernel<Layout128, false>)
               : cap == 256u ? (fix ? sweep_kernel<LayoutWide<256>, true> : sweep_kernel<LayoutWide<256>, false>)
                             : (fix ? sweep_kernel<LayoutWide<512>, true> : sweep_kernel<LayoutWide<512>, false>);
+  auto generic = cap <= 16u ? sweep_generic_kernel<16> : cap <= 64u ? sweep_generic_kernel<64>
+                                                                    : sweep_generic_kernel<0>;
+  const bool hand_over = cap <= 64u || have_ws;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                     n_pol, t_done, have_ws);
-  if (have_ws)
-    hipLaunchKernelGGL(sweep_generic_kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
+                     n_pol, t_done, hand_over);
+  if (hand_over)
+    hipLaunchKernelGGL(generic, dim3(blocks_for(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                        n_pol, t_done, w);
   return launch_status();

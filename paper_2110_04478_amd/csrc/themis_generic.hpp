@@ -63,7 +63,11 @@ __device__ __forceinline__ void write_invalid(const SimOut& o) {
 // meta = code << 8 (stage 0), size = chunk bytes of its collective, arrival =
 // release time.  chunk_of(q) returns collective q's chunk size, release_of(q)
 // its release time; both are only consulted while replaying stage times.
-template <typename ChunkOf, typename ReleaseOf>
+// kEager: read a chunk's arrival time and size together with its meta word
+// instead of only once it is known to be a candidate -- no branches and
+// several chunks' loads in flight at once; for arrays in LDS, where the extra
+// reads cost next to nothing.
+template <bool kEager, typename ChunkOf, typename ReleaseOf>
 __device__ void simulate_generic(const Scenario& s, uint32_t Q, bool scf, const Workspace& w,
                                  uint64_t col, ChunkOf chunk_of, ReleaseOf release_of,
                                  bool has_release, const SimOut& out) {
@@ -96,25 +100,55 @@ __device__ void simulate_generic(const Scenario& s, uint32_t Q, bool scf, const 
       double bsize[kMaxDims] = {0.0, 0.0, 0.0, 0.0};
       double barr[kMaxDims] = {0.0, 0.0, 0.0, 0.0};
       uint32_t bmeta[kMaxDims] = {0u, 0u, 0u, 0u};
-      for (uint32_t g = 0; g < G; ++g) {
-        size_t at = (size_t)g * w.stride + col;
-        uint32_t m = w.meta[at];
-        int stage = (int)(m & 15u);
-        if (stage >= last_stage || (m & kMetaRunning)) continue;
-        uint32_t code = (m >> 8) & 0xFFu;
-        int pos = stage < D ? stage : 2 * D - 1 - stage;
-        int k = (int)((code >> (2 * pos)) & 3u);
-        if (sel4(k, serving[0], serving[1], serving[2], serving[3]) >= 0) continue;
-        double arr = w.arrival[at];
-        if (arr > now) continue;  // not released yet
-        double sz = scf ? w.size[at] : 0.0;
+      if (kEager) {
+        const uint32_t idle_dims = (serving[0] < 0 ? 1u : 0u) | (serving[1] < 0 ? 2u : 0u) |
+                                   (serving[2] < 0 ? 4u : 0u) | (serving[3] < 0 ? 8u : 0u);
+#pragma unroll 4
+        for (uint32_t g = 0; g < G; ++g) {
+          const size_t at = (size_t)g * w.stride + col;
+          const uint32_t m = w.meta[at];
+          const double arr = w.arrival[at];
+          const double sz = scf ? w.size[at] : 0.0;
+          const int stage = (int)(m & 15u);
+          const uint32_t code = (m >> 8) & 0xFFu;
+          const int pos = stage < D ? stage : 2 * D - 1 - stage;
+          const int k = (int)((code >> ((2 * pos) & 31)) & 3u);
+          // bitwise on purpose: selects, not branches
+          const bool cand = (stage < last_stage) & ((m & kMetaRunning) == 0u) &
+                            (((idle_dims >> k) & 1u) != 0u) & !(arr > now);
 #pragma unroll
-        for (int kk = 0; kk < kMaxDims; ++kk) {
-          if (kk == k) {
-            bool first = best[kk] < 0;
+          for (int kk = 0; kk < kMaxDims; ++kk) {
             // ascending g with strict '<' keeps the lowest chunk id on ties
-            bool better = (sz < bsize[kk]) || (sz == bsize[kk] && arr < barr[kk]);
-            if (first || better) { best[kk] = (int)g; bsize[kk] = sz; barr[kk] = arr; bmeta[kk] = m; }
+            const bool better = (best[kk] < 0) | (sz < bsize[kk]) |
+                                ((sz == bsize[kk]) & (arr < barr[kk]));
+            const bool upd = cand & (kk == k) & better;
+            best[kk] = upd ? (int)g : best[kk];
+            bsize[kk] = upd ? sz : bsize[kk];
+            barr[kk] = upd ? arr : barr[kk];
+            bmeta[kk] = upd ? m : bmeta[kk];
+          }
+        }
+      } else {
+        for (uint32_t g = 0; g < G; ++g) {
+          size_t at = (size_t)g * w.stride + col;
+          uint32_t m = w.meta[at];
+          int stage = (int)(m & 15u);
+          if (stage >= last_stage || (m & kMetaRunning)) continue;
+          uint32_t code = (m >> 8) & 0xFFu;
+          int pos = stage < D ? stage : 2 * D - 1 - stage;
+          int k = (int)((code >> (2 * pos)) & 3u);
+          if (sel4(k, serving[0], serving[1], serving[2], serving[3]) >= 0) continue;
+          double arr = w.arrival[at];
+          if (arr > now) continue;  // not released yet
+          double sz = scf ? w.size[at] : 0.0;
+#pragma unroll
+          for (int kk = 0; kk < kMaxDims; ++kk) {
+            if (kk == k) {
+              bool first = best[kk] < 0;
+              // ascending g with strict '<' keeps the lowest chunk id on ties
+              bool better = (sz < bsize[kk]) || (sz == bsize[kk] && arr < barr[kk]);
+              if (first || better) { best[kk] = (int)g; bsize[kk] = sz; barr[kk] = arr; bmeta[kk] = m; }
+            }
           }
         }
       }

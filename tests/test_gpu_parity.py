@@ -124,6 +124,41 @@ def test_non_power_of_two_npus(gpu, oracle):
     check_batch(gpu, oracle, w().mixed(700, seed=77, pow2=False))
 
 
+def test_workspace_is_only_needed_beyond_64_chunks(gpu, oracle):
+    """Up to 64 chunks the generic kernel keeps its per-chunk arrays in LDS: no
+    workspace, same results.  Beyond, scenarios off the LDS path come back as
+    NaN / all-ones when no workspace is passed, the others are unaffected."""
+    import torch
+    for mc in (9, 64):
+        b = w().mixed(500, seed=300 + mc, max_chunks=mc, pow2=False)
+        o_orders, _ = oracle.plan_batch(b, threads=8)
+        o_t, o_qo, o_busy = oracle.simulate_batch(b, o_orders, threads=8)
+        d = gpu.to_device(b)
+        orders, _ = gpu.themis_plan_batch(d)
+        t, qo, busy = gpu.themis_simulate_batch(d, orders)          # no workspace
+        thr = torch.tensor([0.0, 0.125], dtype=torch.float64, device="cuda")
+        sw = gpu.themis_sweep(d, thr, 6)                            # no workspace
+        torch.cuda.synchronize()
+        assert not np.isnan(o_t).any()
+        assert_close("t_done", t.cpu().numpy(), o_t)
+        assert np.array_equal(widen_queue(qo), o_qo)
+        assert_close("busy", busy.cpu().numpy(), o_busy)
+        assert_close("sweep", sw.cpu().numpy(), oracle.sweep(b, thr.cpu().numpy(), 6, threads=8))
+    b = w().mixed(400, seed=365, max_chunks=100, pow2=False)
+    pow2 = np.array([all((int(p) & (int(p) - 1)) == 0 for p in b.npus[:b.ndims[i], i])
+                     for i in range(b.n)])
+    o_orders, _ = oracle.plan_batch(b, threads=8)
+    o_t, _, _ = oracle.simulate_batch(b, o_orders, want_queue_order=False, threads=8)
+    d = gpu.to_device(b)
+    orders, _ = gpu.themis_plan_batch(d)
+    t, qo, _ = gpu.themis_simulate_batch(d, orders)
+    torch.cuda.synchronize()
+    t = t.cpu().numpy()
+    assert 0 < pow2.sum() < b.n
+    assert np.isnan(t[~pow2]).all() and (qo.cpu().numpy()[~pow2] == 0xFF).all()
+    assert_close("t_done of the LDS-path scenarios", t[pow2], o_t[pow2])
+
+
 def test_large_chunk_counts(gpu, oracle):
     """C up to 512: the wide LDS layouts, 8- and 16-bit queue entries, odd
     row lengths."""
