@@ -12,13 +12,17 @@
  * -ffp-contract=off; no blocking, no reordering, no cleverness: each function
  * walks the paper's steps in the paper's order.
  *
- * Pinning (tests/test_oracle_*.py): 1-D ring closed form 2(P-1)/P*S/B, the
- * stage-time ratios and chunk orders of the paper's 4x4 worked example, load
- * conservation, the balanced-bandwidth reduction to the baseline order, an
- * independent time-stepped simulator on integer service times, and brute
- * force over all per-chunk orders for tiny C.  The completion time that the
- * paper's timing figure would show for Themis on the worked example is
- * "parity unpinned": the figure is not available in text form.
+ * Pinning (tests/test_oracle_pins.py): 1-D ring closed forms (All-Reduce
+ * 2(P-1)/P*S/B, with fixed delays, stand-alone Reduce-Scatter / All-Gather),
+ * the stage-time ratios and chunk orders of the paper's 4x4 worked example,
+ * Alg. 1 replayed with exact rationals, load conservation, the
+ * balanced-bandwidth reduction to the baseline order, an independent
+ * exact-rational checker that rebuilds every start and end time from the
+ * reported per-dimension orders and verifies work conservation and FIFO / SCF
+ * conformance, brute force over all per-chunk orders for tiny C, hand values
+ * for the derived metrics and the provisioning classes.  The completion time
+ * that the paper's timing figure would show for Themis on the worked example
+ * is "parity unpinned": the figure is not available in text form.
  */
 #include <math.h>
 #include <stdint.h>
