@@ -251,28 +251,30 @@ simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                         double* __restrict__ t_done, void* __restrict__ queue_order,
                         int entry_bytes, double* __restrict__ busy, Workspace w) {
   __shared__ double lds_block[kLdsSlots ? (kLdsSlots * kBlock * 5u + 1u) / 2u : 1u];
-  uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= b.n || !is_left_to_generic(t_done[i])) return;
-  uint64_t col = i;
-  if (kLdsSlots) {
-    w = carve_workspace(lds_block, kBlock, kLdsSlots);
-    col = threadIdx.x;
-  }
+  if (kLdsSlots) w = carve_workspace(lds_block, kBlock, kLdsSlots);
   const TraceView tv = trace_view(b);
-  Scenario s = load_scenario(b, i);
-  const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
-  uint32_t Q;
-  collectives_ok(b, tv, i, Q);  // marked scenarios passed this check already
-  SimOut out;
-  out.t_done = t_done + i;
-  out.busy = busy ? busy + i : nullptr;
-  out.busy_stride = b.n;
-  out.entry_bytes = entry_bytes;
-  out.slots = tv.slots;
-  out.queue_order = queue_order
-      ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
-      : nullptr;
-  simulate_generic_scenario<(kLdsSlots > 0)>(b, tv, s, Q, i, col, orders + (size_t)i * tv.slots, scf, w, out);
+  // a few workgroups walk all groups of 64 scenarios: most groups have nothing marked
+  const uint64_t groups = (b.n + kBlock - 1) / kBlock;
+  for (uint64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const uint64_t i = grp * kBlock + threadIdx.x;
+    if (i >= b.n || !is_left_to_generic(t_done[i])) continue;
+    const uint64_t col = kLdsSlots ? threadIdx.x : i;
+    Scenario s = load_scenario(b, i);
+    const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
+    uint32_t Q;
+    collectives_ok(b, tv, i, Q);  // marked scenarios passed this check already
+    SimOut out;
+    out.t_done = t_done + i;
+    out.busy = busy ? busy + i : nullptr;
+    out.busy_stride = b.n;
+    out.entry_bytes = entry_bytes;
+    out.slots = tv.slots;
+    out.queue_order = queue_order
+        ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
+        : nullptr;
+    simulate_generic_scenario<(kLdsSlots > 0)>(b, tv, s, Q, i, col, orders + (size_t)i * tv.slots,
+                                               scf, w, out);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -446,26 +448,27 @@ sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr
                      int thr_per_scenario, unsigned policy_mask, int n_pol,
                      double* __restrict__ t_done, Workspace w) {
   __shared__ double lds_block[kLdsSlots ? (kLdsSlots * kBlock * 5u + 1u) / 2u : 1u];
-  uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
-  if (e >= total || !is_left_to_generic(t_done[e])) return;
-  uint64_t col = e;
-  if (kLdsSlots) {
-    w = carve_workspace(lds_block, kBlock, kLdsSlots);
-    col = threadIdx.x;
+  if (kLdsSlots) w = carve_workspace(lds_block, kBlock, kLdsSlots);
+  const uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
+  const uint64_t groups = (total + kBlock - 1) / kBlock;
+  for (uint64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const uint64_t e = grp * kBlock + threadIdx.x;
+    if (e >= total || !is_left_to_generic(t_done[e])) continue;
+    const uint64_t col = kLdsSlots ? threadIdx.x : e;
+    const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
+    Scenario s = load_scenario(b, it.i);
+    s.ctype = THEMIS_COLL_ALL_REDUCE;
+    SimOut out;
+    out.t_done = t_done + e;
+    out.busy = nullptr;
+    out.busy_stride = 0;
+    out.queue_order = nullptr;
+    out.entry_bytes = 1;
+    out.slots = b.max_chunks;
+    sweep_generic_evaluation<(kLdsSlots > 0)>(s, b.size_bytes[it.i] / (double)s.C, it.themis_on,
+                                              b.threshold_mode == THEMIS_THR_REL, it.th, it.scf,
+                                              col, w, out);
   }
-  const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
-  Scenario s = load_scenario(b, it.i);
-  s.ctype = THEMIS_COLL_ALL_REDUCE;
-  SimOut out;
-  out.t_done = t_done + e;
-  out.busy = nullptr;
-  out.busy_stride = 0;
-  out.queue_order = nullptr;
-  out.entry_bytes = 1;
-  out.slots = b.max_chunks;
-  sweep_generic_evaluation<(kLdsSlots > 0)>(s, b.size_bytes[it.i] / (double)s.C, it.themis_on,
-                           b.threshold_mode == THEMIS_THR_REL, it.th, it.scf, col, w, out);
 }
 
 // ---------------------------------------------------------------------------
@@ -732,6 +735,15 @@ static size_t generic_area_bytes(uint64_t evals, uint64_t slots) {
 
 static unsigned blocks_for(uint64_t items) { return (unsigned)((items + kBlock - 1) / kBlock); }
 
+// Grid of a follow-up kernel (its workgroups stride over the groups of 64
+// evaluations): enough to fill the device, no more.
+static unsigned follow_up_blocks(uint64_t items) {
+  const unsigned cus = compute_units();
+  const unsigned cap = 8u * (cus ? cus : 256u);
+  const unsigned all = blocks_for(items);
+  return all < cap ? all : cap;
+}
+
 }  // namespace themis
 
 using namespace themis;
@@ -819,7 +831,7 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                      (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
                      hand_over);
   if (hand_over)
-    hipLaunchKernelGGL(generic, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+    hipLaunchKernelGGL(generic, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
                        busy, w);
   return launch_status();
@@ -856,7 +868,7 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                      n_pol, t_done, hand_over);
   if (hand_over)
-    hipLaunchKernelGGL(generic, dim3(blocks_for(evals)), dim3(kBlock), 0,
+    hipLaunchKernelGGL(generic, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                        n_pol, t_done, w);
   return launch_status();
