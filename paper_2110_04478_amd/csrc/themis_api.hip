@@ -221,7 +221,7 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     FastOut fo;
     fo.queue_order = (uint8_t*)out.queue_order;
     fo.slots = tv.slots;
-    FastResult r = simulate_fast<L, kQueueOrder, kBusy, kFix>(s, fs, scf, lds, fo);
+    FastResult r = simulate_fast<L, kQueueOrder, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
     if (r.ok) {
       t_done[i] = r.t_done;
       if (busy) {
@@ -434,7 +434,7 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     FastOut fo;
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;
-    FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, fs, it.scf, lds, fo);
+    FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, it.scf), lds, fo);
     if (r.ok) { t_done[e] = r.t_done; return; }
   }
   t_done[e] = hand_over ? left_to_generic() : nan64();
@@ -538,7 +538,7 @@ search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ t
   FastOut fo;
   fo.queue_order = nullptr;
   fo.slots = b.max_chunks;
-  FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, fs, scf, lds, fo);
+  FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
   times[e] = r.ok ? r.t_done : nan64();
 }
 

@@ -371,19 +371,57 @@ __device__ __forceinline__ double min_f64(double a, double b) {
 // and needs rows that start on a 4-byte boundary (an even number of slots).
 enum QueueOrderMode { kNoQueueOrder = 0, kBytes = 1, kWords = 2, kShorts = 3 };
 
+// What the event loop needs to know about sizes and times, for scenarios with
+// power-of-two NPU counts: the resident size is base * 2^-E(mask), so a stage
+// time is one exponent adjustment and one multiply, and the size class of a
+// mask comes from a 16 x 4-bit table in a register pair.
+struct Pow2Model {
+  const Scenario& s;
+  const FastScenario& fs;
+  uint64_t ranktab;
+  __device__ __forceinline__ Pow2Model(const Scenario& s_, const FastScenario& fs_, bool scf)
+      : s(s_), fs(fs_), ranktab(build_rank_table(fs_.epack, scf)) {}
+  __device__ __forceinline__ uint32_t state0() const { return fs.state0; }
+  __device__ __forceinline__ bool rs_only() const { return fs.rs_only; }
+  __device__ __forceinline__ bool one_phase() const { return fs.rs_only || fs.gather; }
+  // bits of the chunk's state byte that a state change must carry over
+  __device__ __forceinline__ uint32_t keep(uint32_t) const { return 0u; }
+  // time of the stage chunk word w is waiting for, on dimension k (kbit = 1 << k):
+  // bytes moved on k = resident size before the chunk's Reduce-Scatter on k,
+  // i.e. with every reduced dimension but k itself taken off; the All-Gather
+  // reuses it (its mask still contains k)
+  __device__ __forceinline__ double stage_time(uint32_t k, uint32_t kbit, uint32_t w) const {
+    const uint32_t E = esum(fs.epack, w & 15u & ~kbit);
+    return scale_down(fs.base, E) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+  }
+  // size class of a chunk (word w) once its state is (mask, phase)
+  __device__ __forceinline__ uint32_t size_class(uint32_t, uint32_t mask, uint32_t) const {
+    return (uint32_t)(ranktab >> (4u * mask)) & 15u;
+  }
+  // a lower bound of every stage time
+  __device__ __forceinline__ double t_min(uint32_t D) const {
+    double m = inf64();
+#pragma unroll
+    for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) {
+      const uint32_t ek = (fs.epack >> (8u * k)) & 0xffu;
+      if (k < D) m = min_f64(m, scale_down(fs.base, fs.etot - ek) * s.coef[k]);
+    }
+    return m;
+  }
+};
+
 // Chunk dwords must already be initialised with L::init_chunk().
 // kFix: the batch carries fixed per-stage delays (a compile-time switch: even a
 // wave-uniform run-time branch around the four-way selection cost 4 % on
 // batches without delays).
-template <typename L, int kQueueOrder, bool kBusy, bool kFix>
-__device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const FastScenario& fs,
-                                                    bool scf, const LaneLds& lds,
-                                                    const FastOut& out) {
+// Model: Pow2Model or a type with the same members (sizes, times, classes).
+template <typename L, int kQueueOrder, bool kBusy, bool kFix, typename Model>
+__device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Model& model,
+                                                    const LaneLds& lds, const FastOut& out) {
   using Link = typename L::Link;
   const uint32_t D = (uint32_t)s.D;
   const uint32_t C = s.C;
   const uint32_t full = (1u << D) - 1u;
-  const uint64_t ranktab = build_rank_table(fs.epack, scf);
   const double kInf = inf64();
 
   double f0 = kInf, f1 = kInf, f2 = kInf, f3 = kInf;  // finish time, +inf = idle
@@ -413,11 +451,12 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
   // a6: every chunk waits at the dimension of its first stage, in chunk-id
   // order, in the class of the initial mask
   {
-    const uint32_t mask0 = fs.state0 & 15u, phase0 = fs.state0 >> 4;
+    const uint32_t mask0 = model.state0() & 15u, phase0 = (model.state0() >> 4) & 1u;
     const uint32_t pos0 = 2u * ((uint32_t)__builtin_popcount(mask0) - phase0);
-    const uint32_t cls0 = (uint32_t)(ranktab >> (4u * mask0)) & 15u;
-    for (uint32_t c = 0; c < C; ++c)
-      push(16u * ((L::code_of(lds, c) >> pos0) & 3u) + cls0, c);
+    for (uint32_t c = 0; c < C; ++c) {
+      const uint32_t w = *(const uint32_t*)lds.dword(c);
+      push(16u * ((L::code(w) >> pos0) & 3u) + model.size_class(w, mask0, phase0), c);
+    }
   }
 
   double now = 0.0;
@@ -443,12 +482,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
       idle &= ~kbit;
 
       const uint32_t phase = (w >> 4) & 1u;
-      // bytes moved on k = resident size before the chunk's Reduce-Scatter on
-      // k, i.e. with every reduced dimension but k itself taken off; the
-      // All-Gather reuses it (its mask still contains k)
-      const uint32_t E = esum(fs.epack, w & 15u & ~kbit);
-      double t = scale_down(fs.base, E) *
-                 sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+      double t = model.stage_time(k, kbit, w);
       if (kFix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
       const double f = now + t;
       const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
@@ -503,15 +537,14 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
       uint32_t phase = (w >> 4) & 1u;
       // a Reduce-Scatter sets the dimension's bit, an All-Gather clears it
       const uint32_t mask = (w & 15u) ^ (1u << k);
-      const bool finished = (phase != 0u && mask == 0u) || (fs.rs_only && mask == full);
+      const bool finished = (phase != 0u && mask == 0u) || (model.rs_only() && mask == full);
       phase |= (mask == full) ? 1u : 0u;  // last Reduce-Scatter: All-Gather starts on the same dim
       if (!finished) {
         // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
         const uint32_t pos = (uint32_t)__builtin_popcount(mask) - phase;
         const uint32_t kn = (code >> (2u * pos)) & 3u;
-        L::store_state(cp, w, mask | (phase << 4));
-        const uint32_t cls = (uint32_t)(ranktab >> (4u * mask)) & 15u;
-        push(16u * kn + cls, c);
+        L::store_state(cp, w, mask | (phase << 4) | model.keep(w));
+        push(16u * kn + model.size_class(w, mask, phase), c);
       }
     } while (done);
   }
@@ -538,13 +571,8 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Fas
   // then at least two units in the last place of every earlier instant)
   // shows that each finish time was strictly after its start.  Anything else
   // (overflow to infinity, NaN, a vanishing stage) is left to the generic path.
-  double t_min = kInf;
-#pragma unroll
-  for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) {
-    const uint32_t ek = (fs.epack >> (8u * k)) & 0xffu;
-    if (k < D) t_min = min_f64(t_min, scale_down(fs.base, fs.etot - ek) * s.coef[k]);
-  }
-  const uint32_t stages = (fs.rs_only || fs.gather) ? D : 2u * D;
+  const double t_min = model.t_min(D);
+  const uint32_t stages = model.one_phase() ? D : 2u * D;
   res.ok = executed.sum() == stages * C && idle == full && (now + 0.25 * t_min > now);
   res.t_done = now;
   res.busy[0] = z0; res.busy[1] = z1; res.busy[2] = z2; res.busy[3] = z3;
