@@ -165,9 +165,11 @@ int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
  *     halvings stay in the normal binary64 range run entirely in registers
  *     and LDS and need no workspace;
  *   - the other single collectives (an NPU count that is not a power of two,
- *     extreme magnitudes) run on a generic path whose per-chunk state also
- *     sits in LDS while max_chunks <= 64 (no workspace needed), and in the
- *     workspace beyond;
+ *     extreme magnitudes) need no workspace either while max_chunks <= 64
+ *     (an LDS path on per-order tables up to 8 distinct order codes per
+ *     scenario, else a slower generic path whose per-chunk state also sits in
+ *     LDS); beyond 64 chunks the generic path keeps that state in the
+ *     workspace;
  *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace
  *     (staggered release times: on the generic path, in the workspace too).
  * For themis_sweep pass n * n_thr * n_pol as n and max_coll = 0.

@@ -124,6 +124,35 @@ def test_non_power_of_two_npus(gpu, oracle):
     check_batch(gpu, oracle, w().mixed(700, seed=77, pow2=False))
 
 
+@pytest.mark.parametrize("ctype", [0, 1])
+def test_three_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle, ctype):
+    """NPU counts such as 3, 6, 12, 24, 72: resident sizes depend on the order
+    of the divisions.  With at most 8 distinct order codes per scenario (always
+    the case up to three dimensions) the LDS event loop runs on per-order-code
+    tables; sizes that divide evenly make many equal Smallest-Chunk-First keys."""
+    import torch
+    W = w()
+    n = 3000
+    rng = np.random.default_rng(31 + ctype)
+    b = W.config2(n=n)
+    b.npus = np.ascontiguousarray(rng.choice([3, 6, 12, 24, 72, 5, 8], (4, n)).astype(np.uint32))
+    b.ndims = rng.integers(1, 4, n).astype(np.uint8)
+    b.intra_policy = rng.integers(0, 2, n).astype(np.uint8)
+    b.size_bytes = np.where(rng.random(n) < 0.5, 2.0 ** rng.integers(24, 31, n) * 9.0, b.size_bytes)
+    b.bw = np.ascontiguousarray(np.where(rng.random((4, n)) < 0.5,
+                                         2.0 ** rng.integers(33, 37, (4, n)), b.bw))
+    b.chunks = rng.choice([1, 7, 32, 64], n).astype(np.uint32)
+    b.collective_type = np.full(n, ctype, np.uint8)
+    if ctype:
+        b.fixed_delay = np.ascontiguousarray(rng.uniform(0, 2e-6, (4, n)))
+    check_batch(gpu, oracle, b, threads=16)
+    thr = torch.tensor([0.0, 1 / 16], dtype=torch.float64, device="cuda")
+    if ctype == 0:
+        got = gpu.themis_sweep(gpu.to_device(b), thr, 7)
+        torch.cuda.synchronize()
+        assert_close("sweep", got.cpu().numpy(), oracle.sweep(b, thr.cpu().numpy(), 7, threads=16))
+
+
 def test_workspace_is_only_needed_beyond_64_chunks(gpu, oracle):
     """Up to 64 chunks the generic kernel keeps its per-chunk arrays in LDS: no
     workspace, same results.  Beyond, scenarios off the LDS path come back as
