@@ -71,6 +71,34 @@ __device__ __forceinline__ uint32_t min_field(uint64_t v) {
   return min(min(lo & 0xffffu, lo >> 16), min(hi & 0xffffu, hi >> 16));
 }
 
+// Which of a dimension's FIFO lists (one per size class) hold chunks: 16 classes
+// per dimension, all four dimensions in one register pair.  List q = 16*k + class.
+struct Classes16 {
+  static constexpr uint32_t kPerDim = 16;
+  uint64_t nonempty = 0;
+  __device__ __forceinline__ explicit Classes16(const LaneLds&) {}
+  // marks list q non-empty; returns whether it already was
+  __device__ __forceinline__ bool mark(uint32_t q) {
+    const uint64_t bit = 1ull << q;
+    const bool had = (nonempty & bit) != 0ull;
+    nonempty |= bit;
+    return had;
+  }
+  // lowest non-empty class of dimension k (the caller knows there is one);
+  // field: the lists of dimension k and above, for popped()
+  __device__ __forceinline__ uint32_t lowest(uint32_t k, uint32_t& field) const {
+    field = (uint32_t)(nonempty >> (16u * k));
+    return (uint32_t)__builtin_ctz(field);
+  }
+  // list q = 16*k + cls lost its head chunk and is empty now if `emptied`;
+  // returns whether no list of dimension k holds chunks any more
+  __device__ __forceinline__ bool popped(uint32_t, uint32_t cls, uint32_t q, uint32_t field,
+                                         bool emptied) {
+    nonempty ^= (uint64_t)(emptied ? 1u : 0u) << q;  // the bit was set
+    return ((field ^ ((emptied ? 1u : 0u) << cls)) & 0xffffu) == 0u;
+  }
+};
+
 // Per-lane LDS layouts with 8-bit chunk ids (kChunks <= 128; 0xFF ends a list).
 //
 // Layout64 (80 dwords, 20 KiB per wavefront, 8 wavefronts per CU):
@@ -97,6 +125,7 @@ struct LayoutByte {
   static constexpr uint32_t kWavesPerSimd = (160u * 1024u / (kLaneWords * 256u) + 3u) / 4u;
   static constexpr uint32_t kEnd = 0xffu;
   using Link = uint8_t;               // width of a chunk id in LDS
+  using Classes = Classes16;
   // per dimension: chunk id << 2 | dimension, and the operation count (up to 2 * kChunks)
   using Ids = typename std::conditional<(kChunks <= 64), Pack4<uint32_t, 8>, Pack4<uint64_t, 16>>::type;
   static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
@@ -136,6 +165,7 @@ struct LayoutWide {
   static constexpr uint32_t kWavesPerSimd = 1;
   static constexpr uint32_t kEnd = 0xffffu;
   using Link = uint16_t;
+  using Classes = Classes16;
   using Ids = Pack4<uint64_t, 16>;
   static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
                                                     uint32_t state0) {
@@ -428,7 +458,8 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
   double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
   typename L::Ids serving;   // per dimension: chunk id << 2 | dimension
   typename L::Ids executed;  // operations started per dimension
-  uint64_t nonempty = 0;  // bit q = 16*dim + class: list q holds chunks
+  typename L::Classes classes(lds);  // which list q = kPerDim*dim + class holds chunks
+  constexpr uint32_t kPerDim = L::Classes::kPerDim;
   uint32_t work = 0;      // bit k: some list of dimension k holds chunks
   uint32_t idle = full;   // bit k: dimension k serves nothing
   uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0;  // kWords: last four queue entries per dimension
@@ -437,15 +468,13 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
   // append chunk c to list q (branch-free: an empty list takes c as its head,
   // otherwise the old tail's next field does)
   auto push = [&](uint32_t q, uint32_t c) {
-    uint64_t bit = 1ull << q;
-    bool had = (nonempty & bit) != 0ull;
+    const bool had = classes.mark(q);
     Link* tp = L::tail_ptr(lds, q);
     uint32_t t = *tp;
     Link* dst = had ? L::next_ptr(lds, t) : L::head_ptr(lds, q);
     *dst = (Link)c;
     *tp = (Link)c;
-    nonempty |= bit;
-    work |= 1u << (q >> 4);
+    work |= 1u << (q / kPerDim);
   };
 
   // a6: every chunk waits at the dimension of its first stage, in chunk-id
@@ -455,7 +484,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
     const uint32_t pos0 = 2u * ((uint32_t)__builtin_popcount(mask0) - phase0);
     for (uint32_t c = 0; c < C; ++c) {
       const uint32_t w = *(const uint32_t*)lds.dword(c);
-      push(16u * ((L::code(w) >> pos0) & 3u) + model.size_class(w, mask0, phase0), c);
+      push(kPerDim * ((L::code(w) >> pos0) & 3u) + model.size_class(w, mask0, phase0), c);
     }
   }
 
@@ -465,18 +494,17 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
     // a7: every idle dimension with waiting chunks starts its first one
     for (uint32_t need = idle & work; need != 0u; need = idle & work) {
       const uint32_t k = (uint32_t)__builtin_ctz(need);
-      // lists of dimension k and above; work bit k says that one of k's is non-empty
-      const uint32_t field = (uint32_t)(nonempty >> (16u * k));
-      const uint32_t cls = (uint32_t)__builtin_ctz(field);  // smallest resident size
-      const uint32_t q = 16u * k + cls;
+      // work bit k says that one of k's lists is non-empty
+      uint32_t field;
+      const uint32_t cls = classes.lowest(k, field);  // smallest resident size
+      const uint32_t q = kPerDim * k + cls;
       Link* hp = L::head_ptr(lds, q);
       const uint32_t h = *hp;
       const uint32_t w = *(const uint32_t*)lds.dword(h);
       const uint32_t nx = L::next(w);
       *hp = (Link)nx;  // harmless when the list is now empty
       const bool emptied = nx == L::kEnd;
-      nonempty ^= (uint64_t)(emptied ? 1u : 0u) << q;  // the bit was set
-      const bool no_work = ((field ^ ((emptied ? 1u : 0u) << cls)) & 0xffffu) == 0u;
+      const bool no_work = classes.popped(k, cls, q, field, emptied);
       work &= ~((no_work ? 1u : 0u) << k);
       const uint32_t kbit = 1u << k;
       idle &= ~kbit;
@@ -544,7 +572,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
         const uint32_t pos = (uint32_t)__builtin_popcount(mask) - phase;
         const uint32_t kn = (code >> (2u * pos)) & 3u;
         L::store_state(cp, w, mask | (phase << 4) | model.keep(w));
-        push(16u * kn + model.size_class(w, mask, phase), c);
+        push(kPerDim * kn + model.size_class(w, mask, phase), c);
       }
     } while (done);
   }
