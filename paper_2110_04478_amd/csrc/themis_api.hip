@@ -278,23 +278,25 @@ simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
   }
 }
 
-// Kernel between the two: marked scenarios whose NPU counts are not powers of
-// two run the same LDS event loop on per-order-code tables (themis_table.hpp);
-// what it cannot take stays marked for the generic kernel.
-template <int kQueueOrder>
+// Kernels between the two: marked scenarios whose NPU counts are not powers of
+// two run the same LDS event loop on per-order-code tables (themis_table.hpp),
+// first the variant for at most 8 distinct order codes, then (kWide) the one
+// for any number of them; what they cannot take stays marked for the generic
+// kernel.
+template <int kQueueOrder, bool kWide>
 __global__ void __launch_bounds__(kBlock)
 simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                       double* __restrict__ t_done, void* __restrict__ queue_order,
                       double* __restrict__ busy) {
-  __shared__ uint32_t lds_block[LayoutTable::kLaneWords * kBlock];
+  using L = typename std::conditional<kWide, LayoutTableWide, LayoutTable>::type;
+  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   const uint64_t groups = (b.n + kBlock - 1) / kBlock;
   for (uint64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
     const uint64_t i = grp * kBlock + threadIdx.x;
     if (i >= b.n || !is_left_to_generic(t_done[i])) continue;
     Scenario s = load_scenario(b, i);
     const double S = b.size_bytes[i];
-    if (!s.valid || s.ctype == THEMIS_COLL_ALL_GATHER || s.C > LayoutTable::kCap ||
-        !finite_positive(S))
+    if (!s.valid || s.ctype == THEMIS_COLL_ALL_GATHER || s.C > L::kCap || !finite_positive(S))
       continue;
     const uint8_t* row = orders + (size_t)i * b.max_chunks;
     bool codes_ok = true;
@@ -302,17 +304,24 @@ simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     if (!codes_ok) continue;
     LaneLds lds;
     lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
-    TableModel model;
     const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
-    if (!table_setup(s, S / (double)s.C, scf, lds, [&](uint32_t c) { return (uint32_t)row[c]; },
-                     model))
-      continue;
+    const double chunk = S / (double)s.C;
+    auto code_at = [&](uint32_t c) { return (uint32_t)row[c]; };
     const uint32_t rows_bytes = (uint32_t)kMaxDims * 2u * b.max_chunks;
     FastOut fo;
     fo.queue_order = (kQueueOrder != kNoQueueOrder && queue_order)
         ? (uint8_t*)queue_order + (size_t)i * rows_bytes : nullptr;
     fo.slots = b.max_chunks;
-    const FastResult r = simulate_fast<LayoutTable, kQueueOrder, true, true>(s, model, lds, fo);
+    FastResult r;
+    if constexpr (kWide) {
+      DivModel model(s, lds, chunk, scf);
+      table_setup_wide(s, scf, lds, code_at, model);
+      r = simulate_fast<L, kQueueOrder, true, true>(s, model, lds, fo);
+    } else {
+      TableModel model;
+      if (!table_setup(s, chunk, scf, lds, code_at, model)) continue;
+      r = simulate_fast<L, kQueueOrder, true, true>(s, model, lds, fo);
+    }
     if (!r.ok) continue;
     t_done[i] = r.t_done;
     if (busy) {
@@ -523,11 +532,13 @@ sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr
 
 // The same for themis_sweep: Alg. 1 with real divisions straight into the
 // chunk words, then the table-driven event loop.
+template <bool kWide>
 __global__ void __launch_bounds__(kBlock)
 sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
                    int thr_per_scenario, unsigned policy_mask, int n_pol,
                    double* __restrict__ t_done) {
-  __shared__ uint32_t lds_block[LayoutTable::kLaneWords * kBlock];
+  using L = typename std::conditional<kWide, LayoutTableWide, LayoutTable>::type;
+  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   const uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
   const uint64_t groups = (total + kBlock - 1) / kBlock;
   for (uint64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
@@ -536,7 +547,7 @@ sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
     const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
     Scenario s = load_scenario(b, it.i);
     s.ctype = THEMIS_COLL_ALL_REDUCE;
-    if (s.C > LayoutTable::kCap) continue;
+    if (s.C > L::kCap) continue;
     const double chunk = b.size_bytes[it.i] / (double)s.C;
     const bool rel = b.threshold_mode == THEMIS_THR_REL;
     LaneLds lds;
@@ -544,15 +555,20 @@ sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
     double load[kMaxDims];
 #pragma unroll
     for (int k = 0; k < kMaxDims; ++k) load[k] = (k < s.D) ? tracker_start(s, k) : inf64();
-    TableModel model;
-    if (!table_setup(s, chunk, it.scf, lds,
-                     [&](uint32_t) { return schedule_chunk(s, chunk, it.themis_on, rel, it.th, load); },
-                     model))
-      continue;
+    auto code_at = [&](uint32_t) { return schedule_chunk(s, chunk, it.themis_on, rel, it.th, load); };
     FastOut fo;
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;
-    const FastResult r = simulate_fast<LayoutTable, kNoQueueOrder, false, true>(s, model, lds, fo);
+    FastResult r;
+    if constexpr (kWide) {
+      DivModel model(s, lds, chunk, it.scf);
+      table_setup_wide(s, it.scf, lds, code_at, model);
+      r = simulate_fast<L, kNoQueueOrder, false, true>(s, model, lds, fo);
+    } else {
+      TableModel model;
+      if (!table_setup(s, chunk, it.scf, lds, code_at, model)) continue;
+      r = simulate_fast<L, kNoQueueOrder, false, true>(s, model, lds, fo);
+    }
     if (r.ok) t_done[e] = r.t_done;
   }
 }
@@ -917,9 +933,15 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                      (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
                      hand_over);
   if (cap <= 64u) {
-    auto table = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder>
-               : mode == kWords ? simulate_table_kernel<kWords> : simulate_table_kernel<kBytes>;
+    auto table = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, false>
+               : mode == kWords ? simulate_table_kernel<kWords, false>
+                                : simulate_table_kernel<kBytes, false>;
+    auto wide = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, true>
+              : mode == kWords ? simulate_table_kernel<kWords, true>
+                               : simulate_table_kernel<kBytes, true>;
     hipLaunchKernelGGL(table, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy);
+    hipLaunchKernelGGL(wide, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, busy);
   }
   if (hand_over)
@@ -959,10 +981,14 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                      n_pol, t_done, hand_over);
-  if (cap <= 64u)
-    hipLaunchKernelGGL(sweep_table_kernel, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
+  if (cap <= 64u) {
+    hipLaunchKernelGGL(sweep_table_kernel<false>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                        n_pol, t_done);
+    hipLaunchKernelGGL(sweep_table_kernel<true>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
+                       n_pol, t_done);
+  }
   if (hand_over)
     hipLaunchKernelGGL(generic, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,

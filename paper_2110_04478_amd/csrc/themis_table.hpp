@@ -17,8 +17,14 @@
 // The slot of a chunk rides in the three spare bits of its state byte.
 //
 // Covered: single All-Reduce / Reduce-Scatter collectives of at most 64 chunks
-// with at most kSlots distinct order codes.  Everything else stays with the
-// generic path.
+// with at most kSlots distinct order codes (LayoutTable: every network of up
+// to three dimensions).  With more distinct codes (four dimensions: up to 24)
+// the sizes that can wait for one dimension no longer fit 16 classes; the
+// wide variant (LayoutTableWide, Classes64, DivModel) gives every dimension
+// 64 classes with its bitmap in LDS, keeps the slot in its own byte of the
+// chunk word, and pays for the larger list tables by redoing a stage time's
+// divisions at each dispatch instead of tabulating them.  Everything else
+// stays with the generic path.
 #pragma once
 
 #include "themis_fast.hpp"
@@ -159,6 +165,181 @@ __device__ inline bool table_setup(const Scenario& s, double chunk, bool scf, co
   model.scf = scf;
   model.tmin = tmin;
   return true;
+}
+
+// ---------------------------------------------------------------------------
+// Wide variant: up to 24 distinct order codes, 64 size classes per dimension.
+// ---------------------------------------------------------------------------
+// Per-lane LDS (248 dwords, 62 KiB per wavefront, 2 wavefronts per CU):
+//   dwords 0..63     chunk c: byte 0 mask | phase << 4, byte 1 next chunk,
+//                    byte 2 order code, byte 3 slot
+//   dwords 64..127   u8 head[256]: first chunk of list q = 64*dim + class
+//   dwords 128..191  u8 tail[256]
+//   dwords 192..199  non-empty bitmap, two dwords per dimension
+//   dwords 200..247  class[slot][stage] bytes, 24 slots x 8 stages
+// Before the event loop starts, the head and tail tables double as scratch
+// for the setup (slot codes, then the sizes being ranked).
+struct Classes64 {
+  static constexpr uint32_t kPerDim = 64;
+  static constexpr uint32_t kBase = 192;
+  LaneLds lds;
+  __device__ __forceinline__ explicit Classes64(const LaneLds& l) : lds(l) {
+    for (uint32_t d = 0; d < 8u; ++d) *(uint32_t*)lds.dword(kBase + d) = 0u;
+  }
+  __device__ __forceinline__ bool mark(uint32_t q) {
+    uint32_t* wp = (uint32_t*)lds.dword(kBase + (q >> 5));
+    const uint32_t v = *wp, bit = 1u << (q & 31u);
+    *wp = v | bit;
+    return (v & bit) != 0u;
+  }
+  __device__ __forceinline__ uint32_t lowest(uint32_t k, uint32_t& field) const {
+    const uint32_t lo = *(const uint32_t*)lds.dword(kBase + 2u * k);
+    const uint32_t hi = *(const uint32_t*)lds.dword(kBase + 2u * k + 1u);
+    field = 0u;
+    return lo ? (uint32_t)__builtin_ctz(lo) : 32u + (uint32_t)__builtin_ctz(hi | 0x80000000u);
+  }
+  __device__ __forceinline__ bool popped(uint32_t k, uint32_t, uint32_t q, uint32_t, bool emptied) {
+    uint32_t* wp = (uint32_t*)lds.dword(kBase + (q >> 5));
+    const uint32_t v = *wp ^ ((emptied ? 1u : 0u) << (q & 31u));  // the bit was set
+    *wp = v;
+    const uint32_t other = *(const uint32_t*)lds.dword(kBase + ((q >> 5) ^ 1u));
+    (void)k;
+    return (v | other) == 0u;
+  }
+};
+
+struct LayoutTableWide {
+  static constexpr uint32_t kCap = 64;
+  static constexpr uint32_t kSlots = 24;
+  static constexpr uint32_t kHeadBase = 64, kTailBase = 128, kClassBase = 200;
+  static constexpr uint32_t kLaneWords = kClassBase + kSlots * 8u / 4u;  // 248
+  static constexpr uint32_t kWavesPerSimd = 1;
+  static constexpr uint32_t kEnd = 0xffu;
+  using Link = uint8_t;
+  using Classes = Classes64;
+  using Ids = Pack4<uint32_t, 8>;
+  static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
+                                                    uint32_t slot) {
+    *(uint32_t*)l.dword(c) = (slot << 24) | (code << 16) | (kEnd << 8);
+  }
+  static __device__ __forceinline__ uint32_t code(uint32_t w) { return (w >> 16) & 0xffu; }
+  static __device__ __forceinline__ uint32_t next(uint32_t w) { return (w >> 8) & 0xffu; }
+  static __device__ __forceinline__ void store_state(uint8_t* cp, uint32_t, uint32_t state) {
+    *(uint16_t*)cp = (uint16_t)(state | (kEnd << 8));
+  }
+  static __device__ __forceinline__ Link* next_ptr(const LaneLds& l, uint32_t c) { return l.dword(c) + 1; }
+  static __device__ __forceinline__ Link* head_ptr(const LaneLds& l, uint32_t q) {
+    return l.base + ((kHeadBase + (q >> 2)) << 8) + (q & 3u);
+  }
+  static __device__ __forceinline__ Link* tail_ptr(const LaneLds& l, uint32_t q) {
+    return l.base + ((kTailBase + (q >> 2)) << 8) + (q & 3u);
+  }
+};
+
+// Model for the wide variant: classes from the table, stage times from the
+// chunk size by the order's own divisions.
+struct DivModel {
+  const Scenario& s;
+  LaneLds lds;
+  double chunk;
+  double tmin;
+  bool rs;
+  bool scf;
+  __device__ __forceinline__ DivModel(const Scenario& s_, const LaneLds& l, double chunk_, bool scf_)
+      : s(s_), lds(l), chunk(chunk_), tmin(inf64()),
+        rs(s_.ctype == THEMIS_COLL_REDUCE_SCATTER), scf(scf_) {}
+  __device__ __forceinline__ uint32_t state0() const { return 0u; }
+  __device__ __forceinline__ bool rs_only() const { return rs; }
+  __device__ __forceinline__ bool one_phase() const { return rs; }
+  __device__ __forceinline__ uint32_t keep(uint32_t) const { return 0u; }  // the slot has its own byte
+  // x * coef on the pos-th dimension of `code`, x divided step by step
+  __device__ __forceinline__ double time_at(uint32_t code, uint32_t pos) const {
+    double x = chunk;
+    for (uint32_t j = 0; j < pos; ++j) {
+      const uint32_t kj = (code >> (2u * j)) & 3u;
+      x = x / (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+    }
+    const uint32_t k = (code >> (2u * pos)) & 3u;
+    return x * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+  }
+  __device__ __forceinline__ double stage_time(uint32_t, uint32_t, uint32_t w) const {
+    const uint32_t pos = ((uint32_t)__builtin_popcount(w & 15u) - ((w >> 4) & 1u)) & 3u;
+    return time_at(LayoutTableWide::code(w), pos);
+  }
+  __device__ __forceinline__ uint32_t size_class(uint32_t w, uint32_t mask, uint32_t phase) const {
+    if (!scf) return 0u;
+    const uint32_t r = (uint32_t)__builtin_popcount(mask);
+    const uint32_t stage = (phase ? 2u * (uint32_t)s.D - r : r) & 7u;
+    const uint32_t slot = w >> 24;
+    const uint32_t idx = (slot < LayoutTableWide::kSlots ? slot : 0u) * 8u + stage;
+    return lds.dword(LayoutTableWide::kClassBase + (idx >> 2))[idx & 3u];
+  }
+  __device__ __forceinline__ double t_min(uint32_t) const { return tmin; }
+};
+
+// Setup of the wide variant; code_at as in table_setup().  Cannot fail: four
+// dimensions have 24 orders.
+template <typename CodeAt>
+__device__ inline void table_setup_wide(const Scenario& s, bool scf, const LaneLds& lds,
+                                        CodeAt code_at, DivModel& model) {
+  using LT = LayoutTableWide;
+  const uint32_t D = (uint32_t)s.D;
+  // scratch: slot codes as bytes from dword kHeadBase, sizes as doubles from dword kHeadBase + 8
+  auto slot_code = [&](uint32_t sl) -> uint8_t& { return lds.dword(LT::kHeadBase + (sl >> 2))[sl & 3u]; };
+  const uint32_t sizes = LT::kHeadBase + 8u;
+  uint32_t n = 0;
+  for (uint32_t c = 0; c < s.C; ++c) {
+    const uint32_t code = code_at(c);
+    uint32_t slot = n;
+    for (uint32_t j = 0; j < n; ++j)
+      if (slot_code(j) == code) slot = j;
+    if (slot == n) {
+      if (n < LT::kSlots) { slot_code(n) = (uint8_t)code; ++n; }
+      else slot = 0;  // unreachable for checked codes
+    }
+    LT::init_chunk(lds, c, code, slot);
+  }
+  double tmin = inf64();
+  for (uint32_t sl = 0; sl < n; ++sl)
+    for (uint32_t j = 0; j < D; ++j) tmin = min_f64(tmin, model.time_at(slot_code(sl), j));
+  model.tmin = tmin;
+  if (!scf) return;
+  for (uint32_t k = 0; k < D; ++k) {
+    for (uint32_t sl = 0; sl < n; ++sl) {
+      const uint32_t code = slot_code(sl);
+      double x = model.chunk, before_rs = 0.0, before_ag = 0.0;
+      for (uint32_t j = 0; j < D; ++j) {
+        const uint32_t kj = (code >> (2u * j)) & 3u;
+        if (kj == k) before_rs = x;
+        x = x / (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+      }
+      for (uint32_t j = D; j-- > 0u;) {
+        const uint32_t kj = (code >> (2u * j)) & 3u;
+        if (kj == k) before_ag = x;
+        x = x * (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+      }
+      lds_put_double(lds, sizes + 4u * sl, before_rs);
+      lds_put_double(lds, sizes + 4u * sl + 2u, before_ag);
+    }
+    const uint32_t entries = 2u * n;
+    for (uint32_t e = 0; e < entries; ++e) {
+      if (model.rs && (e & 1u)) continue;
+      const double v = lds_double(lds, sizes + 2u * e);
+      uint32_t smaller = 0;
+      for (uint32_t o = 0; o < entries; ++o) {
+        if (model.rs && (o & 1u)) continue;
+        smaller += lds_double(lds, sizes + 2u * o) < v ? 1u : 0u;
+      }
+      const uint32_t sl = e >> 1;
+      const uint32_t code = slot_code(sl);
+      uint32_t pos = 0;
+      for (uint32_t j = 0; j < D; ++j)
+        if (((code >> (2u * j)) & 3u) == k) pos = j;
+      const uint32_t stage = (e & 1u) ? 2u * D - 1u - pos : pos;
+      const uint32_t idx = sl * 8u + stage;
+      lds.dword(LT::kClassBase + (idx >> 2))[idx & 3u] = (uint8_t)smaller;
+    }
+  }
 }
 
 }  // namespace themis

@@ -153,6 +153,44 @@ def test_three_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle, ctype
         assert_close("sweep", got.cpu().numpy(), oracle.sweep(b, thr.cpu().numpy(), 7, threads=16))
 
 
+def test_four_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle):
+    """4-D networks with NPU counts like 3, 6, 10, 48, 72: Themis plans use well
+    over 8 distinct orders, random plans all 24 -- the variant with 64 size
+    classes per dimension.  Evenly dividing sizes give equal keys."""
+    import torch
+    W = w()
+    n = 1500
+    rng = np.random.default_rng(57)
+    b = W.config3(n=n)
+    b.npus = np.ascontiguousarray(rng.choice([3, 6, 10, 12, 48, 72, 5, 4], (4, n)).astype(np.uint32))
+    b.intra_policy = rng.integers(0, 2, n).astype(np.uint8)
+    b.size_bytes = np.where(rng.random(n) < 0.5, 2.0 ** rng.integers(24, 31, n) * 45.0, b.size_bytes)
+    b.bw = np.ascontiguousarray(np.where(rng.random((4, n)) < 0.5,
+                                         2.0 ** rng.integers(33, 37, (4, n)), b.bw))
+    b.chunks = rng.choice([5, 24, 63, 64], n).astype(np.uint32)
+    b.collective_type = rng.integers(0, 2, n).astype(np.uint8)
+    b.fixed_delay = np.ascontiguousarray(rng.uniform(0, 2e-6, (4, n)) * (rng.random((4, n)) < 0.5))
+    check_batch(gpu, oracle, b, threads=16)
+    # arbitrary (not planned) orders: all 24 permutations in one scenario
+    orders = np.full((n, b.max_chunks), 0xFF, np.uint8)
+    perms = [sum(int(k) << (2 * j) for j, k in enumerate(p))
+             for p in __import__("itertools").permutations(range(4))]
+    for i in range(n):
+        orders[i, :b.chunks[i]] = rng.choice(perms, int(b.chunks[i]))
+    o_t, o_qo, o_busy = oracle.simulate_batch(b, orders, threads=16)
+    d = gpu.to_device(b)
+    t, qo, busy = gpu.themis_simulate_batch(d, torch.from_numpy(orders).cuda())
+    torch.cuda.synchronize()
+    assert_close("t_done", t.cpu().numpy(), o_t)
+    assert np.array_equal(widen_queue(qo), o_qo)
+    assert_close("busy", busy.cpu().numpy(), o_busy)
+    b.collective_type = None
+    thr = torch.tensor([0.0, 1 / 16], dtype=torch.float64, device="cuda")
+    got = gpu.themis_sweep(gpu.to_device(b), thr, 7)
+    torch.cuda.synchronize()
+    assert_close("sweep", got.cpu().numpy(), oracle.sweep(b, thr.cpu().numpy(), 7, threads=16))
+
+
 def test_workspace_is_only_needed_beyond_64_chunks(gpu, oracle):
     """Up to 64 chunks the generic kernel keeps its per-chunk arrays in LDS: no
     workspace, same results.  Beyond, scenarios off the LDS path come back as
