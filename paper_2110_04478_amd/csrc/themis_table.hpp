@@ -326,10 +326,10 @@ __device__ inline void table_setup_wide(const Scenario& s, bool scf, const LaneL
       if (model.rs && (e & 1u)) continue;
       const double v = lds_double(lds, sizes + 2u * e);
       uint32_t smaller = 0;
-      for (uint32_t o = 0; o < entries; ++o) {
-        if (model.rs && (o & 1u)) continue;
+      const uint32_t step = model.rs ? 2u : 1u;  // a Reduce-Scatter only has the even entries
+#pragma unroll 4
+      for (uint32_t o = 0; o < entries; o += step)
         smaller += lds_double(lds, sizes + 2u * o) < v ? 1u : 0u;
-      }
       const uint32_t sl = e >> 1;
       const uint32_t code = slot_code(sl);
       uint32_t pos = 0;
