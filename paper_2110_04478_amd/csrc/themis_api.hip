@@ -1,6 +1,8 @@
 // C ABI of the library (see include/themis.h) and the kernels behind it.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "themis.h"
 #include "themis_device.hpp"
 #include "themis_fast.hpp"
@@ -60,6 +62,20 @@ constexpr uint64_t kLeftToGeneric = 0x7ff8a5a55a5a0001ull;
 __device__ __forceinline__ double left_to_generic() { return __longlong_as_double((long long)kLeftToGeneric); }
 __device__ __forceinline__ bool is_left_to_generic(double t) {
   return (uint64_t)__double_as_longlong(t) == kLeftToGeneric;
+}
+
+// Every call that may hand evaluations over carries a number of its own (host
+// counter, never 0); a kernel that marks one raises this word to its call's
+// number, and the follow-up kernels of a call return at once while the word is
+// below theirs -- then nothing of that call can be marked.  A larger number
+// left by another call only costs the scan for marks.
+__device__ unsigned long long g_marked_call = 0ull;
+__device__ __forceinline__ void mark_left_to_generic(double* slot, unsigned long long call) {
+  *slot = left_to_generic();
+  atomicMax(&g_marked_call, call);
+}
+__device__ __forceinline__ bool nothing_marked(unsigned long long call) {
+  return *(volatile unsigned long long*)&g_marked_call < call;
 }
 
 // ---------------------------------------------------------------------------
@@ -168,7 +184,7 @@ template <typename L, int kQueueOrder, bool kBusy, bool kFix>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
 simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                 double* __restrict__ t_done, void* __restrict__ queue_order, int entry_bytes,
-                double* __restrict__ busy, bool hand_over) {
+                double* __restrict__ busy, unsigned long long hand_over) {
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= b.n) return;
@@ -237,9 +253,9 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       return;
     }
   }
-  // hand_over: a generic kernel follows (it has the memory it needs)
+  // hand_over != 0: follow-up kernels come (this call's number), else nothing can take it
   if (!hand_over) { write_invalid(out); return; }
-  t_done[i] = left_to_generic();
+  mark_left_to_generic(t_done + i, hand_over);
 }
 
 // Second kernel of themis_simulate_batch: the scenarios the LDS kernel marked.
@@ -250,8 +266,10 @@ template <uint32_t kLdsSlots>
 __global__ void __launch_bounds__(kBlock)
 simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                         double* __restrict__ t_done, void* __restrict__ queue_order,
-                        int entry_bytes, double* __restrict__ busy, Workspace w) {
+                        int entry_bytes, double* __restrict__ busy, Workspace w,
+                        unsigned long long call) {
   __shared__ double lds_block[kLdsSlots ? (kLdsSlots * kBlock * 5u + 1u) / 2u : 1u];
+  if (nothing_marked(call)) return;
   if (kLdsSlots) w = carve_workspace(lds_block, kBlock, kLdsSlots);
   const TraceView tv = trace_view(b);
   // a few workgroups walk all groups of 64 scenarios: most groups have nothing marked
@@ -287,9 +305,10 @@ template <int kQueueOrder, bool kWide>
 __global__ void __launch_bounds__(kBlock)
 simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                       double* __restrict__ t_done, void* __restrict__ queue_order,
-                      double* __restrict__ busy) {
+                      double* __restrict__ busy, unsigned long long call) {
   using L = typename std::conditional<kWide, LayoutTableWide, LayoutTable>::type;
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
+  if (nothing_marked(call)) return;
   const uint64_t groups = (b.n + kBlock - 1) / kBlock;
   for (uint64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
     const uint64_t i = grp * kBlock + threadIdx.x;
@@ -468,7 +487,8 @@ __device__ __forceinline__ SweepItem sweep_item(const themis_batch_t& b, uint64_
 template <typename L, bool kFix>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
 sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
-             unsigned policy_mask, int n_pol, double* __restrict__ t_done, bool hand_over) {
+             unsigned policy_mask, int n_pol, double* __restrict__ t_done,
+             unsigned long long hand_over) {
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
@@ -496,7 +516,8 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, it.scf), lds, fo);
     if (r.ok) { t_done[e] = r.t_done; return; }
   }
-  t_done[e] = hand_over ? left_to_generic() : nan64();
+  if (hand_over) mark_left_to_generic(t_done + e, hand_over);
+  else t_done[e] = nan64();
 }
 
 // Second kernel of themis_sweep: the evaluations the LDS kernel marked
@@ -505,8 +526,9 @@ template <uint32_t kLdsSlots>
 __global__ void __launch_bounds__(kBlock)
 sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
                      int thr_per_scenario, unsigned policy_mask, int n_pol,
-                     double* __restrict__ t_done, Workspace w) {
+                     double* __restrict__ t_done, Workspace w, unsigned long long call) {
   __shared__ double lds_block[kLdsSlots ? (kLdsSlots * kBlock * 5u + 1u) / 2u : 1u];
+  if (nothing_marked(call)) return;
   if (kLdsSlots) w = carve_workspace(lds_block, kBlock, kLdsSlots);
   const uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
   const uint64_t groups = (total + kBlock - 1) / kBlock;
@@ -536,9 +558,10 @@ template <bool kWide>
 __global__ void __launch_bounds__(kBlock)
 sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
                    int thr_per_scenario, unsigned policy_mask, int n_pol,
-                   double* __restrict__ t_done) {
+                   double* __restrict__ t_done, unsigned long long call) {
   using L = typename std::conditional<kWide, LayoutTableWide, LayoutTable>::type;
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
+  if (nothing_marked(call)) return;
   const uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
   const uint64_t groups = (total + kBlock - 1) / kBlock;
   for (uint64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
@@ -788,11 +811,18 @@ static unsigned compute_units() {
   return cus > 0 ? (unsigned)cus : 0u;
 }
 
+// Number of a call whose kernels may hand evaluations over (see g_marked_call).
+static unsigned long long next_call_number() {
+  static std::atomic<unsigned long long> counter{0};
+  return ++counter;
+}
+
 static int launch_status() {
   return hipGetLastError() == hipSuccess ? THEMIS_OK : THEMIS_ERR_DEVICE;
 }
 
-using SimKernel = void (*)(themis_batch_t, const uint8_t*, double*, void*, int, double*, bool);
+using SimKernel = void (*)(themis_batch_t, const uint8_t*, double*, void*, int, double*,
+                           unsigned long long);
 
 template <typename L, int kMode>
 static SimKernel pick_flags(bool busy, bool fix) {
@@ -928,10 +958,11 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   // kernel: with its arrays in LDS up to 64 chunks, from the workspace beyond
   auto generic = cap <= 16u ? simulate_generic_kernel<16> : cap <= 64u ? simulate_generic_kernel<64>
                                                                        : simulate_generic_kernel<0>;
-  const bool hand_over = cap <= 64u || have_ws;
+  const unsigned long long call = (cap <= 64u || have_ws) ? next_call_number() : 0ull;
+  const bool hand_over = call != 0ull;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
-                     hand_over);
+                     call);
   if (cap <= 64u) {
     auto table = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, false>
                : mode == kWords ? simulate_table_kernel<kWords, false>
@@ -940,14 +971,14 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
               : mode == kWords ? simulate_table_kernel<kWords, true>
                                : simulate_table_kernel<kBytes, true>;
     hipLaunchKernelGGL(table, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy);
+                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
     hipLaunchKernelGGL(wide, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy);
+                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
   }
   if (hand_over)
     hipLaunchKernelGGL(generic, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
-                       busy, w);
+                       busy, w, call);
   return launch_status();
 }
 
@@ -977,22 +1008,23 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
                             : (fix ? sweep_kernel<LayoutWide<512>, true> : sweep_kernel<LayoutWide<512>, false>);
   auto generic = cap <= 16u ? sweep_generic_kernel<16> : cap <= 64u ? sweep_generic_kernel<64>
                                                                     : sweep_generic_kernel<0>;
-  const bool hand_over = cap <= 64u || have_ws;
+  const unsigned long long call = (cap <= 64u || have_ws) ? next_call_number() : 0ull;
+  const bool hand_over = call != 0ull;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                     n_pol, t_done, hand_over);
+                     n_pol, t_done, call);
   if (cap <= 64u) {
     hipLaunchKernelGGL(sweep_table_kernel<false>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                       n_pol, t_done);
+                       n_pol, t_done, call);
     hipLaunchKernelGGL(sweep_table_kernel<true>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                       n_pol, t_done);
+                       n_pol, t_done, call);
   }
   if (hand_over)
     hipLaunchKernelGGL(generic, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                       n_pol, t_done, w);
+                       n_pol, t_done, w, call);
   return launch_status();
 }
 
