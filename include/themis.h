@@ -166,10 +166,9 @@ int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
  *     and LDS and need no workspace;
  *   - the other single collectives (an NPU count that is not a power of two,
  *     extreme magnitudes) need no workspace either while max_chunks <= 64
- *     (LDS paths on per-order tables for All-Reduce and Reduce-Scatter, a
- *     slower generic path whose per-chunk state also sits in LDS for the
- *     rest); beyond 64 chunks the generic path keeps that state in the
- *     workspace;
+ *     (LDS paths on per-order tables; a slower generic path whose per-chunk
+ *     state also sits in LDS remains behind them); beyond 64 chunks the
+ *     generic path keeps that state in the workspace;
  *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace
  *     (staggered release times: on the generic path, in the workspace too).
  * For themis_sweep pass n * n_thr * n_pol as n and max_coll = 0.

@@ -315,8 +315,7 @@ simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     if (i >= b.n || !is_left_to_generic(t_done[i])) continue;
     Scenario s = load_scenario(b, i);
     const double S = b.size_bytes[i];
-    if (!s.valid || s.ctype == THEMIS_COLL_ALL_GATHER || s.C > L::kCap || !finite_positive(S))
-      continue;
+    if (!s.valid || s.C > L::kCap || !finite_positive(S)) continue;
     const uint8_t* row = orders + (size_t)i * b.max_chunks;
     bool codes_ok = true;
     for (uint32_t c = 0; c < s.C; ++c) codes_ok = codes_ok && order_code_ok(row[c], s.D);

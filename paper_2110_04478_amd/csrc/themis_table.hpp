@@ -16,7 +16,7 @@
 //                      the same dimension (two per slot, so at most 16)
 // The slot of a chunk rides in the three spare bits of its state byte.
 //
-// Covered: single All-Reduce / Reduce-Scatter collectives of at most 64 chunks
+// Covered: single collectives (All-Reduce, Reduce-Scatter, All-Gather) of at most 64 chunks
 // with at most kSlots distinct order codes (LayoutTable: every network of up
 // to three dimensions).  With more distinct codes (four dimensions: up to 24)
 // the sizes that can wait for one dimension no longer fit 16 classes; the
@@ -53,11 +53,12 @@ struct TableModel {
   LaneLds lds;
   uint32_t D;
   bool rs;      // stand-alone Reduce-Scatter
+  bool gather;  // stand-alone All-Gather (chunk words hold the order code reversed)
   bool scf;
   double tmin;  // smallest tabulated stage time
-  __device__ __forceinline__ uint32_t state0() const { return 0u; }
+  __device__ __forceinline__ uint32_t state0() const { return gather ? (((1u << D) - 1u) | 16u) : 0u; }
   __device__ __forceinline__ bool rs_only() const { return rs; }
-  __device__ __forceinline__ bool one_phase() const { return rs; }
+  __device__ __forceinline__ bool one_phase() const { return rs || gather; }
   __device__ __forceinline__ uint32_t keep(uint32_t w) const { return w & 0xe0u; }
   __device__ __forceinline__ double stage_time(uint32_t, uint32_t, uint32_t w) const {
     // RS: the next dimension of the order; AG: the last one still reduced
@@ -84,11 +85,14 @@ __device__ inline bool table_setup(const Scenario& s, double chunk, bool scf, co
                                    CodeAt code_at, TableModel& model) {
   const uint32_t D = (uint32_t)s.D;
   const bool rs = s.ctype == THEMIS_COLL_REDUCE_SCATTER;
+  const bool gather = s.ctype == THEMIS_COLL_ALL_GATHER;
+  const uint32_t state0 = gather ? (((1u << D) - 1u) | 16u) : 0u;
   uint64_t codes = 0;  // one byte per slot
   uint32_t n = 0;
   bool fits = true;
   for (uint32_t c = 0; c < s.C; ++c) {
-    const uint32_t code = code_at(c);
+    // a stand-alone All-Gather walks its code from the last field to the first
+    const uint32_t code = gather ? reverse_code(code_at(c), (int)D) : code_at(c);
     uint32_t slot = n;
 #pragma unroll
     for (uint32_t j = 0; j < LayoutTable::kSlots; ++j)
@@ -97,7 +101,7 @@ __device__ inline bool table_setup(const Scenario& s, double chunk, bool scf, co
       if (n == LayoutTable::kSlots) { fits = false; slot = 0; }
       else { codes |= (uint64_t)code << (8u * n); ++n; }
     }
-    LayoutTable::init_chunk(lds, c, code, slot << 5);
+    LayoutTable::init_chunk(lds, c, code, state0 | (slot << 5));
   }
   if (!fits) return false;
 
@@ -110,30 +114,27 @@ __device__ inline bool table_setup(const Scenario& s, double chunk, bool scf, co
       for (uint32_t sl = 0; sl < n; ++sl) {
         const uint32_t code = (uint32_t)(codes >> (8u * sl)) & 0xffu;
         double x = chunk, before_rs = 0.0, before_ag = 0.0;
-        uint32_t pos_k = 0;
-        for (uint32_t j = 0; j < D; ++j) {  // Reduce-Scatter stages shrink the resident size
+        for (uint32_t j = 0; j < D && !gather; ++j) {  // Reduce-Scatter stages shrink the resident size
           const uint32_t kj = (code >> (2u * j)) & 3u;
-          if (kj == k) { before_rs = x; pos_k = j; }
+          if (kj == k) before_rs = x;
           x = x / (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
         }
-        for (uint32_t j = D; j-- > 0u;) {   // All-Gather stages grow it back, last dimension first
+        for (uint32_t j = D; j-- > 0u;) {   // All-Gather stages grow it (back), last field first
           const uint32_t kj = (code >> (2u * j)) & 3u;
           if (kj == k) before_ag = x;
           x = x * (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
         }
-        (void)pos_k;
         lds_put_double(lds, LayoutTable::kTimeBase + 4u * sl, before_rs);
         lds_put_double(lds, LayoutTable::kTimeBase + 4u * sl + 2u, before_ag);
       }
       const uint32_t entries = 2u * n;  // entry 2*slot: RS, 2*slot+1: AG
-      for (uint32_t e = 0; e < entries; ++e) {
-        if (rs && (e & 1u)) continue;   // a stand-alone Reduce-Scatter has no All-Gather stages
+      // a stand-alone Reduce-Scatter has only the even entries, an All-Gather only the odd ones
+      const uint32_t first = gather ? 1u : 0u, step = (rs || gather) ? 2u : 1u;
+      for (uint32_t e = first; e < entries; e += step) {
         const double v = lds_double(lds, LayoutTable::kTimeBase + 2u * e);
         uint32_t smaller = 0;
-        for (uint32_t o = 0; o < entries; ++o) {
-          if (rs && (o & 1u)) continue;
+        for (uint32_t o = first; o < entries; o += step)
           smaller += lds_double(lds, LayoutTable::kTimeBase + 2u * o) < v ? 1u : 0u;
-        }
         const uint32_t sl = e >> 1;
         const uint32_t code = (uint32_t)(codes >> (8u * sl)) & 0xffu;
         uint32_t pos = 0;
@@ -151,6 +152,17 @@ __device__ inline bool table_setup(const Scenario& s, double chunk, bool scf, co
   for (uint32_t sl = 0; sl < n; ++sl) {
     const uint32_t code = (uint32_t)(codes >> (8u * sl)) & 0xffu;
     double x = chunk;
+    if (gather) {
+      // stages run from the code's last field to its first; each moves the grown size
+      for (uint32_t j = D; j-- > 0u;) {
+        const uint32_t kj = (code >> (2u * j)) & 3u;
+        x = x * (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+        const double t = x * sel4((int)kj, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+        lds_put_double(lds, LayoutTable::kTimeBase + 2u * (sl * 4u + j), t);
+        tmin = min_f64(tmin, t);
+      }
+      continue;
+    }
     for (uint32_t j = 0; j < D; ++j) {
       const uint32_t kj = (code >> (2u * j)) & 3u;
       const double t = x * sel4((int)kj, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
@@ -162,6 +174,7 @@ __device__ inline bool table_setup(const Scenario& s, double chunk, bool scf, co
   model.lds = lds;
   model.D = D;
   model.rs = rs;
+  model.gather = gather;
   model.scf = scf;
   model.tmin = tmin;
   return true;
@@ -219,8 +232,8 @@ struct LayoutTableWide {
   using Classes = Classes64;
   using Ids = Pack4<uint32_t, 8>;
   static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
-                                                    uint32_t slot) {
-    *(uint32_t*)l.dword(c) = (slot << 24) | (code << 16) | (kEnd << 8);
+                                                    uint32_t slot, uint32_t state0) {
+    *(uint32_t*)l.dword(c) = (slot << 24) | (code << 16) | (kEnd << 8) | state0;
   }
   static __device__ __forceinline__ uint32_t code(uint32_t w) { return (w >> 16) & 0xffu; }
   static __device__ __forceinline__ uint32_t next(uint32_t w) { return (w >> 8) & 0xffu; }
@@ -244,17 +257,30 @@ struct DivModel {
   double chunk;
   double tmin;
   bool rs;
+  bool gather;  // stand-alone All-Gather (chunk words hold the order code reversed)
   bool scf;
   __device__ __forceinline__ DivModel(const Scenario& s_, const LaneLds& l, double chunk_, bool scf_)
       : s(s_), lds(l), chunk(chunk_), tmin(inf64()),
-        rs(s_.ctype == THEMIS_COLL_REDUCE_SCATTER), scf(scf_) {}
-  __device__ __forceinline__ uint32_t state0() const { return 0u; }
+        rs(s_.ctype == THEMIS_COLL_REDUCE_SCATTER), gather(s_.ctype == THEMIS_COLL_ALL_GATHER),
+        scf(scf_) {}
+  __device__ __forceinline__ uint32_t state0() const {
+    return gather ? (((1u << s.D) - 1u) | 16u) : 0u;
+  }
   __device__ __forceinline__ bool rs_only() const { return rs; }
-  __device__ __forceinline__ bool one_phase() const { return rs; }
+  __device__ __forceinline__ bool one_phase() const { return rs || gather; }
   __device__ __forceinline__ uint32_t keep(uint32_t) const { return 0u; }  // the slot has its own byte
   // x * coef on the pos-th dimension of `code`, x divided step by step
+  // (All-Gather: x grown step by step from the code's last field down to pos)
   __device__ __forceinline__ double time_at(uint32_t code, uint32_t pos) const {
     double x = chunk;
+    if (gather) {
+      for (uint32_t j = (uint32_t)s.D; j-- > pos;) {
+        const uint32_t kj = (code >> (2u * j)) & 3u;
+        x = x * (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+      }
+      const uint32_t k = (code >> (2u * pos)) & 3u;
+      return x * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+    }
     for (uint32_t j = 0; j < pos; ++j) {
       const uint32_t kj = (code >> (2u * j)) & 3u;
       x = x / (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
@@ -289,7 +315,7 @@ __device__ inline void table_setup_wide(const Scenario& s, bool scf, const LaneL
   const uint32_t sizes = LT::kHeadBase + 8u;
   uint32_t n = 0;
   for (uint32_t c = 0; c < s.C; ++c) {
-    const uint32_t code = code_at(c);
+    const uint32_t code = model.gather ? reverse_code(code_at(c), (int)D) : code_at(c);
     uint32_t slot = n;
     for (uint32_t j = 0; j < n; ++j)
       if (slot_code(j) == code) slot = j;
@@ -297,7 +323,7 @@ __device__ inline void table_setup_wide(const Scenario& s, bool scf, const LaneL
       if (n < LT::kSlots) { slot_code(n) = (uint8_t)code; ++n; }
       else slot = 0;  // unreachable for checked codes
     }
-    LT::init_chunk(lds, c, code, slot);
+    LT::init_chunk(lds, c, code, slot, model.state0());
   }
   double tmin = inf64();
   for (uint32_t sl = 0; sl < n; ++sl)
@@ -308,7 +334,7 @@ __device__ inline void table_setup_wide(const Scenario& s, bool scf, const LaneL
     for (uint32_t sl = 0; sl < n; ++sl) {
       const uint32_t code = slot_code(sl);
       double x = model.chunk, before_rs = 0.0, before_ag = 0.0;
-      for (uint32_t j = 0; j < D; ++j) {
+      for (uint32_t j = 0; j < D && !model.gather; ++j) {
         const uint32_t kj = (code >> (2u * j)) & 3u;
         if (kj == k) before_rs = x;
         x = x / (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
@@ -322,13 +348,13 @@ __device__ inline void table_setup_wide(const Scenario& s, bool scf, const LaneL
       lds_put_double(lds, sizes + 4u * sl + 2u, before_ag);
     }
     const uint32_t entries = 2u * n;
-    for (uint32_t e = 0; e < entries; ++e) {
-      if (model.rs && (e & 1u)) continue;
+    // a stand-alone Reduce-Scatter has only the even entries, an All-Gather only the odd ones
+    const uint32_t first = model.gather ? 1u : 0u, step = model.one_phase() ? 2u : 1u;
+    for (uint32_t e = first; e < entries; e += step) {
       const double v = lds_double(lds, sizes + 2u * e);
       uint32_t smaller = 0;
-      const uint32_t step = model.rs ? 2u : 1u;  // a Reduce-Scatter only has the even entries
 #pragma unroll 4
-      for (uint32_t o = 0; o < entries; o += step)
+      for (uint32_t o = first; o < entries; o += step)
         smaller += lds_double(lds, sizes + 2u * o) < v ? 1u : 0u;
       const uint32_t sl = e >> 1;
       const uint32_t code = slot_code(sl);

@@ -124,7 +124,7 @@ def test_non_power_of_two_npus(gpu, oracle):
     check_batch(gpu, oracle, w().mixed(700, seed=77, pow2=False))
 
 
-@pytest.mark.parametrize("ctype", [0, 1])
+@pytest.mark.parametrize("ctype", [0, 1, 2])
 def test_three_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle, ctype):
     """NPU counts such as 3, 6, 12, 24, 72: resident sizes depend on the order
     of the divisions.  With at most 8 distinct order codes per scenario (always
@@ -168,7 +168,7 @@ def test_four_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle):
     b.bw = np.ascontiguousarray(np.where(rng.random((4, n)) < 0.5,
                                          2.0 ** rng.integers(33, 37, (4, n)), b.bw))
     b.chunks = rng.choice([5, 24, 63, 64], n).astype(np.uint32)
-    b.collective_type = rng.integers(0, 2, n).astype(np.uint8)
+    b.collective_type = rng.integers(0, 3, n).astype(np.uint8)
     b.fixed_delay = np.ascontiguousarray(rng.uniform(0, 2e-6, (4, n)) * (rng.random((4, n)) < 0.5))
     check_batch(gpu, oracle, b, threads=16)
     # arbitrary (not planned) orders: all 24 permutations in one scenario
