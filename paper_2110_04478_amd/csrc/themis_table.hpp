@@ -16,8 +16,8 @@
 //                      the same dimension (two per slot, so at most 16)
 // The slot of a chunk rides in the three spare bits of its state byte.
 //
-// Covered: single collectives (All-Reduce, Reduce-Scatter, All-Gather) of at most 64 chunks
-// with at most kSlots distinct order codes (LayoutTable: every network of up
+// Covered: single collectives (All-Reduce, Reduce-Scatter, All-Gather) of at
+// most 64 chunks with at most kSlots distinct order codes (LayoutTable: every network of up
 // to three dimensions).  With more distinct codes (four dimensions: up to 24)
 // the sizes that can wait for one dimension no longer fit 16 classes; the
 // wide variant (LayoutTableWide, Classes64, DivModel) gives every dimension
