@@ -17,8 +17,8 @@
 // The slot of a chunk rides in the three spare bits of its state byte.
 //
 // Covered: single collectives (All-Reduce, Reduce-Scatter, All-Gather) of at
-// most 64 chunks with at most kSlots distinct order codes (LayoutTable: every network of up
-// to three dimensions).  With more distinct codes (four dimensions: up to 24)
+// most 64 chunks with at most kSlots distinct order codes (LayoutTable: every
+// network of up to three dimensions).  With more distinct codes (four dimensions: up to 24)
 // the sizes that can wait for one dimension no longer fit 16 classes; the
 // wide variant (LayoutTableWide, Classes64, DivModel) gives every dimension
 // 64 classes with its bitmap in LDS, keeps the slot in its own byte of the
