@@ -18,13 +18,13 @@
 //
 // Covered: single collectives (All-Reduce, Reduce-Scatter, All-Gather) of at
 // most 64 chunks with at most kSlots distinct order codes (LayoutTable: every
-// network of up to three dimensions).  With more distinct codes (four dimensions: up to 24)
-// the sizes that can wait for one dimension no longer fit 16 classes; the
-// wide variant (LayoutTableWide, Classes64, DivModel) gives every dimension
-// 64 classes with its bitmap in LDS, keeps the slot in its own byte of the
-// chunk word, and pays for the larger list tables by redoing a stage time's
-// divisions at each dispatch instead of tabulating them.  Everything else
-// stays with the generic path.
+// network of up to three dimensions).  With more distinct codes (four
+// dimensions: up to 24) the sizes that can wait for one dimension no longer
+// fit 16 classes; the wide variant (LayoutTableWide, Classes64, DivModel)
+// gives every dimension 64 classes (one bitmap register pair each), keeps the slot in
+// its own byte of the chunk word, and pays for the larger list tables by
+// redoing a stage time's divisions at each dispatch instead of tabulating
+// them.  Everything else stays with the generic path.
 #pragma once
 
 #include "themis_fast.hpp"
@@ -183,49 +183,46 @@ __device__ inline bool table_setup(const Scenario& s, double chunk, bool scf, co
 // ---------------------------------------------------------------------------
 // Wide variant: up to 24 distinct order codes, 64 size classes per dimension.
 // ---------------------------------------------------------------------------
-// Per-lane LDS (248 dwords, 62 KiB per wavefront, 2 wavefronts per CU):
+// Per-lane LDS (240 dwords, 60 KiB per wavefront, 2 wavefronts per CU):
 //   dwords 0..63     chunk c: byte 0 mask | phase << 4, byte 1 next chunk,
 //                    byte 2 order code, byte 3 slot
 //   dwords 64..127   u8 head[256]: first chunk of list q = 64*dim + class
 //   dwords 128..191  u8 tail[256]
-//   dwords 192..199  non-empty bitmap, two dwords per dimension
-//   dwords 200..247  class[slot][stage] bytes, 24 slots x 8 stages
+//   dwords 192..239  class[slot][stage] bytes, 24 slots x 8 stages
 // Before the event loop starts, the head and tail tables double as scratch
 // for the setup (slot codes, then the sizes being ranked).
 struct Classes64 {
   static constexpr uint32_t kPerDim = 64;
-  static constexpr uint32_t kBase = 192;
-  LaneLds lds;
-  __device__ __forceinline__ explicit Classes64(const LaneLds& l) : lds(l) {
-    for (uint32_t d = 0; d < 8u; ++d) *(uint32_t*)lds.dword(kBase + d) = 0u;
+  // one 64-bit word per dimension, in registers: a four-way select by the
+  // dimension costs less than the LDS round trips of a bitmap kept there
+  uint64_t n0 = 0, n1 = 0, n2 = 0, n3 = 0;
+  __device__ __forceinline__ explicit Classes64(const LaneLds&) {}
+  __device__ __forceinline__ uint64_t of(uint32_t k) const { return sel4((int)k, n0, n1, n2, n3); }
+  __device__ __forceinline__ void put(uint32_t k, uint64_t v) {
+    n0 = k == 0u ? v : n0; n1 = k == 1u ? v : n1; n2 = k == 2u ? v : n2; n3 = k == 3u ? v : n3;
   }
   __device__ __forceinline__ bool mark(uint32_t q) {
-    uint32_t* wp = (uint32_t*)lds.dword(kBase + (q >> 5));
-    const uint32_t v = *wp, bit = 1u << (q & 31u);
-    *wp = v | bit;
-    return (v & bit) != 0u;
+    const uint32_t k = q >> 6;
+    const uint64_t v = of(k), bit = 1ull << (q & 63u);
+    put(k, v | bit);
+    return (v & bit) != 0ull;
   }
   __device__ __forceinline__ uint32_t lowest(uint32_t k, uint32_t& field) const {
-    const uint32_t lo = *(const uint32_t*)lds.dword(kBase + 2u * k);
-    const uint32_t hi = *(const uint32_t*)lds.dword(kBase + 2u * k + 1u);
     field = 0u;
-    return lo ? (uint32_t)__builtin_ctz(lo) : 32u + (uint32_t)__builtin_ctz(hi | 0x80000000u);
+    return (uint32_t)__builtin_ctzll(of(k) | (1ull << 63));
   }
-  __device__ __forceinline__ bool popped(uint32_t k, uint32_t, uint32_t q, uint32_t, bool emptied) {
-    uint32_t* wp = (uint32_t*)lds.dword(kBase + (q >> 5));
-    const uint32_t v = *wp ^ ((emptied ? 1u : 0u) << (q & 31u));  // the bit was set
-    *wp = v;
-    const uint32_t other = *(const uint32_t*)lds.dword(kBase + ((q >> 5) ^ 1u));
-    (void)k;
-    return (v | other) == 0u;
+  __device__ __forceinline__ bool popped(uint32_t k, uint32_t cls, uint32_t, uint32_t, bool emptied) {
+    const uint64_t v = of(k) ^ ((uint64_t)(emptied ? 1u : 0u) << cls);  // the bit was set
+    put(k, v);
+    return v == 0ull;
   }
 };
 
 struct LayoutTableWide {
   static constexpr uint32_t kCap = 64;
   static constexpr uint32_t kSlots = 24;
-  static constexpr uint32_t kHeadBase = 64, kTailBase = 128, kClassBase = 200;
-  static constexpr uint32_t kLaneWords = kClassBase + kSlots * 8u / 4u;  // 248
+  static constexpr uint32_t kHeadBase = 64, kTailBase = 128, kClassBase = 192;
+  static constexpr uint32_t kLaneWords = kClassBase + kSlots * 8u / 4u;  // 240
   static constexpr uint32_t kWavesPerSimd = 1;
   static constexpr uint32_t kEnd = 0xffu;
   using Link = uint8_t;
