@@ -7,6 +7,7 @@
 #include "themis_device.hpp"
 #include "themis_fast.hpp"
 #include "themis_generic.hpp"
+#include "themis_packed.hpp"
 #include "themis_table.hpp"
 #include "themis_trace.hpp"
 
@@ -174,6 +175,22 @@ __device__ __forceinline__ void simulate_generic_scenario(const themis_batch_t& 
       [&](uint32_t q) { return collective_release(b, tv, i, q); }, has_release, out);
 }
 
+// Chunk c's word / record in the lane's LDS block, whichever the layout keeps.
+template <typename L>
+__device__ __forceinline__ void init_chunk(const LaneLds& lds, uint32_t c, uint32_t code,
+                                           uint32_t state0, uint32_t D) {
+  if constexpr (L::kPacked) L::init_chunk(lds, c, code, state0, D);
+  else L::init_chunk(lds, c, code, state0);
+}
+
+// The power-of-two event loop that goes with the layout.
+template <typename L, int kQueueOrder, bool kBusy, bool kFix>
+__device__ __forceinline__ FastResult simulate_pow2(const Scenario& s, const Pow2Model& model,
+                                                    const LaneLds& lds, const FastOut& out) {
+  if constexpr (L::kPacked) return simulate_packed<L, kQueueOrder, kBusy, kFix>(s, model, lds, out);
+  else return simulate_fast<L, kQueueOrder, kBusy, kFix>(s, model, lds, out);
+}
+
 template <int kQueueOrder>
 __device__ __forceinline__ void put_queue_entry(uint8_t* rows, uint32_t at, uint32_t v) {
   if (kQueueOrder == kShorts) ((uint16_t*)rows)[at] = (uint16_t)v;
@@ -223,7 +240,7 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
           if (c4 + j < s.C) {
             uint32_t code = (v >> (8u * j)) & 0xffu;
             codes_ok = codes_ok && order_code_ok(code, s.D);
-            L::init_chunk(lds, c4 + j, stored_code(s, fs, code), fs.state0);
+            init_chunk<L>(lds, c4 + j, stored_code(s, fs, code), fs.state0, (uint32_t)s.D);
           }
         }
       }
@@ -231,14 +248,14 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       for (uint32_t c = 0; c < s.C; ++c) {
         uint32_t code = row[c];
         codes_ok = codes_ok && order_code_ok(code, s.D);
-        L::init_chunk(lds, c, stored_code(s, fs, code), fs.state0);
+        init_chunk<L>(lds, c, stored_code(s, fs, code), fs.state0, (uint32_t)s.D);
       }
     }
     if (!codes_ok) { write_invalid(out); return; }
     FastOut fo;
     fo.queue_order = (uint8_t*)out.queue_order;
     fo.slots = tv.slots;
-    FastResult r = simulate_fast<L, kQueueOrder, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
+    FastResult r = simulate_pow2<L, kQueueOrder, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
     if (r.ok) {
       t_done[i] = r.t_done;
       if (busy) {
@@ -508,11 +525,11 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
     double load[kMaxDims];
     plan_fast(s, fs, it.themis_on, rel, it.th, load,
-              [&](uint32_t c, uint32_t code) { L::init_chunk(lds, c, code, 0u); });
+              [&](uint32_t c, uint32_t code) { init_chunk<L>(lds, c, code, 0u, (uint32_t)s.D); });
     FastOut fo;
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;
-    FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, it.scf), lds, fo);
+    FastResult r = simulate_pow2<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, it.scf), lds, fo);
     if (r.ok) { t_done[e] = r.t_done; return; }
   }
   if (hand_over) mark_left_to_generic(t_done + e, hand_over);
@@ -855,7 +872,7 @@ static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy, bool fi
   if (cap == 64u) return pick_mode<Layout64>(mode, busy, fix);
   if (cap == 128u) return pick_mode<Layout128>(mode, busy, fix);
   if (cap == 256u) return pick_mode<LayoutWide<256>>(mode, busy, fix);
-  return pick_mode<LayoutWide<512>>(mode, busy, fix);
+  return pick_mode<LayoutPacked<512>>(mode, busy, fix);
 }
 
 // The generic area comes first in the workspace, rounded up so that the trace
@@ -1004,7 +1021,7 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
               : cap == 64u ? (fix ? sweep_kernel<Layout64, true> : sweep_kernel<Layout64, false>)
               : cap == 128u ? (fix ? sweep_kernel<Layout128, true> : sweep_kernel<Layout128, false>)
               : cap == 256u ? (fix ? sweep_kernel<LayoutWide<256>, true> : sweep_kernel<LayoutWide<256>, false>)
-                            : (fix ? sweep_kernel<LayoutWide<512>, true> : sweep_kernel<LayoutWide<512>, false>);
+                            : (fix ? sweep_kernel<LayoutPacked<512>, true> : sweep_kernel<LayoutPacked<512>, false>);
   auto generic = cap <= 16u ? sweep_generic_kernel<16> : cap <= 64u ? sweep_generic_kernel<64>
                                                                     : sweep_generic_kernel<0>;
   const unsigned long long call = (cap <= 64u || have_ws) ? next_call_number() : 0ull;

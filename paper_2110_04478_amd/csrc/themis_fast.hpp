@@ -115,6 +115,7 @@ struct Classes16 {
 // byte 3 unused, then u8 head[64] and u8 tail[64].
 template <uint32_t kChunks>
 struct LayoutByte {
+  static constexpr bool kPacked = false;  // 32-bit chunk words, simulate_fast
   static constexpr uint32_t kCap = kChunks;
   static_assert(kChunks <= 128, "chunk ids and the list end mark share 8 bits");
   static constexpr bool kHeadInChunkWord = kChunks >= 64;
@@ -160,6 +161,7 @@ using Layout128 = LayoutByte<128>;
 //   then u16 head[64] (32 dwords) and u16 tail[64] (32 dwords)
 template <uint32_t kChunks>
 struct LayoutWide {
+  static constexpr bool kPacked = false;
   static constexpr uint32_t kCap = kChunks;
   static constexpr uint32_t kLaneWords = kChunks + 64;
   static constexpr uint32_t kWavesPerSimd = 1;

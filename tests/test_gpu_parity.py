@@ -294,6 +294,31 @@ def test_arbitrary_orders_are_accepted_and_malformed_ones_rejected(gpu, oracle):
     assert_close("busy", busy.cpu().numpy(), o_busy)
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("max_chunks", [200, 257, 512])
+def test_arbitrary_orders_with_hundreds_of_chunks(gpu, oracle, max_chunks):
+    """Any permutation per chunk, all three collective types and both queue
+    policies on the LDS layouts for more than 128 chunks (16-bit queue
+    entries), where a chunk's state is derived from its order, not stored."""
+    import torch
+    b = _with_collective_types(w().mixed(140, seed=300 + max_chunks, max_chunks=max_chunks), 31)
+    b.chunks[:4] = [max_chunks, max_chunks - 1, 1, 2]
+    rng = np.random.default_rng(max_chunks)
+    orders = np.full((b.n, b.slots), 0xFF, np.uint8)
+    for i in range(b.n):
+        D = int(b.ndims[i])
+        perms = np.argsort(rng.random((int(b.chunks[i]), D)), axis=1)
+        orders[i, :perms.shape[0]] = (perms << (2 * np.arange(D))).sum(axis=1)
+    o_t, o_qo, o_busy = oracle.simulate_batch(b, orders, threads=8)
+    d = gpu.to_device(b)
+    t, qo, busy = gpu.themis_simulate_batch(d, torch.from_numpy(orders).cuda())
+    torch.cuda.synchronize()
+    assert np.isfinite(o_t).all()
+    assert_close("t_done", t.cpu().numpy(), o_t)
+    assert np.array_equal(widen_queue(qo), o_qo)
+    assert_close("busy", busy.cpu().numpy(), o_busy)
+
+
 def test_trace_of_collectives_sharing_queues(gpu, oracle):
     b = w().config5(n=96, n_coll=6)
     check_batch(gpu, oracle, b)
