@@ -871,7 +871,7 @@ static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy, bool fi
   if (cap == 16u) return pick_mode<Layout16>(mode, busy, fix);
   if (cap == 64u) return pick_mode<Layout64>(mode, busy, fix);
   if (cap == 128u) return pick_mode<Layout128>(mode, busy, fix);
-  if (cap == 256u) return pick_mode<LayoutWide<256>>(mode, busy, fix);
+  if (cap == 256u) return pick_mode<LayoutPacked<256>>(mode, busy, fix);
   return pick_mode<LayoutPacked<512>>(mode, busy, fix);
 }
 
@@ -1020,7 +1020,7 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   auto kernel = cap == 16u ? (fix ? sweep_kernel<Layout16, true> : sweep_kernel<Layout16, false>)
               : cap == 64u ? (fix ? sweep_kernel<Layout64, true> : sweep_kernel<Layout64, false>)
               : cap == 128u ? (fix ? sweep_kernel<Layout128, true> : sweep_kernel<Layout128, false>)
-              : cap == 256u ? (fix ? sweep_kernel<LayoutWide<256>, true> : sweep_kernel<LayoutWide<256>, false>)
+              : cap == 256u ? (fix ? sweep_kernel<LayoutPacked<256>, true> : sweep_kernel<LayoutPacked<256>, false>)
                             : (fix ? sweep_kernel<LayoutPacked<512>, true> : sweep_kernel<LayoutPacked<512>, false>);
   auto generic = cap <= 16u ? sweep_generic_kernel<16> : cap <= 64u ? sweep_generic_kernel<64>
                                                                     : sweep_generic_kernel<0>;

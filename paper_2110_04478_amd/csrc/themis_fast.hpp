@@ -155,43 +155,6 @@ using Layout64 = LayoutByte<64>;
 using Layout16 = LayoutByte<16>;
 using Layout128 = LayoutByte<128>;
 
-// Layout for up to kChunks <= 512 chunks (kChunks + 64 dwords per lane):
-//   dword c: byte 0 mask | phase << 4, byte 1 order code, bytes 2-3 next
-//            chunk (0xFFFF = last)
-//   then u16 head[64] (32 dwords) and u16 tail[64] (32 dwords)
-template <uint32_t kChunks>
-struct LayoutWide {
-  static constexpr bool kPacked = false;
-  static constexpr uint32_t kCap = kChunks;
-  static constexpr uint32_t kLaneWords = kChunks + 64;
-  static constexpr uint32_t kWavesPerSimd = 1;
-  static constexpr uint32_t kEnd = 0xffffu;
-  using Link = uint16_t;
-  using Classes = Classes16;
-  using Ids = Pack4<uint64_t, 16>;
-  static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
-                                                    uint32_t state0) {
-    *(uint32_t*)l.dword(c) = (code << 8) | (kEnd << 16) | state0;
-  }
-  static __device__ __forceinline__ uint32_t code(uint32_t w) { return (w >> 8) & 0xffu; }
-  static __device__ __forceinline__ uint32_t next(uint32_t w) { return w >> 16; }
-  static __device__ __forceinline__ uint32_t code_of(const LaneLds& l, uint32_t c) {
-    return l.dword(c)[1];
-  }
-  static __device__ __forceinline__ void store_state(uint8_t* cp, uint32_t w, uint32_t state) {
-    *(uint32_t*)cp = state | (w & 0xff00u) | (kEnd << 16);
-  }
-  static __device__ __forceinline__ Link* next_ptr(const LaneLds& l, uint32_t c) {
-    return (Link*)(l.dword(c) + 2);
-  }
-  static __device__ __forceinline__ Link* head_ptr(const LaneLds& l, uint32_t q) {
-    return (Link*)(l.base + ((kChunks + (q >> 1)) << 8) + 2u * (q & 1u));
-  }
-  static __device__ __forceinline__ Link* tail_ptr(const LaneLds& l, uint32_t q) {
-    return (Link*)(l.base + ((kChunks + 32u + (q >> 1)) << 8) + 2u * (q & 1u));
-  }
-};
-
 // Per-evaluation constants of the fast path.
 //
 // Collective types share one machine.  A chunk's state is (mask of dimensions
