@@ -465,6 +465,55 @@ def test_full_size_config3_sampled_and_invariants(gpu, oracle):
     assert_close("busy", busy[:, sel].cpu().numpy(), o_busy)
 
 
+def test_full_size_config4_sweep_sampled_and_invariants(gpu, oracle):
+    """The 512-chunk threshold sweep whole (65,536 scenarios x 8 thresholds x
+    {FIFO, SCF}) in the launch shape bench.py times with --workload config4:
+    sampled scenarios against the oracle, and T >= S / sum B (Table 3, Ideal)
+    for every evaluation."""
+    import torch
+    W = w()
+    b = W.config4()
+    thr = W.CONFIG4_THRESHOLDS
+    mask = W.SWEEP_THEMIS_FIFO | W.SWEEP_THEMIS_SCF
+    d = gpu.to_device(b)
+    got = gpu.themis_sweep(d, torch.from_numpy(thr).cuda(), mask)
+    torch.cuda.synchronize()
+    assert got.shape == (b.n, len(thr), 2)
+    assert bool(torch.isfinite(got).all())
+    ideal = d.size_bytes / d.bw.sum(dim=0)
+    assert bool((got >= ideal[:, None, None]).all())
+    idx = np.sort(np.random.default_rng(4478).choice(b.n, 48, replace=False))
+    want = oracle.sweep(b.take(idx), thr, mask, threads=8)
+    assert_close("sweep t_done", got[torch.from_numpy(idx).cuda()].cpu().numpy(), want)
+
+
+def test_full_size_config5_traces_sampled_and_invariants(gpu, oracle):
+    """The 16,384 traces of 200 collectives whole, in the launch shape bench.py
+    times with --workload config5 (times and busy times, no queue orders):
+    sampled scenarios against the oracle; T >= the busiest dimension's busy
+    time (Sec. 4.4) and T >= sum S / sum B for every scenario."""
+    import torch
+    W = w()
+    b = W.config5()
+    d = gpu.to_device(b)
+    orders, loads = gpu.themis_plan_batch(d)
+    ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(d.n, d.max_chunks, d.max_coll))
+    t, _, busy = gpu.themis_simulate_batch(d, orders, workspace=ws, want_queue_order=False)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(t).all())
+    assert bool((t >= busy.max(dim=0).values * (1 - 1e-12)).all())
+    ideal = d.coll_size.sum(dim=0) / d.bw[:3].sum(dim=0)
+    assert bool((t >= ideal).all())
+    idx = np.sort(np.random.default_rng(2110).choice(b.n, 24, replace=False))
+    sub = b.take(idx)
+    o_orders, _ = oracle.plan_batch(sub, threads=8)
+    o_t, _, o_busy = oracle.simulate_batch(sub, o_orders, want_queue_order=False, threads=8)
+    sel = torch.from_numpy(idx).cuda()
+    assert np.array_equal(orders[sel].cpu().numpy(), o_orders)
+    assert_close("t_done", t[sel].cpu().numpy(), o_t)
+    assert_close("busy", busy[:, sel].cpu().numpy(), o_busy)
+
+
 def _with_fixed_delay(b, seed):
     rng = np.random.default_rng(seed)
     b.fixed_delay = np.ascontiguousarray(
