@@ -31,7 +31,7 @@ struct TraceLayout {
   uint32_t G;   // chunk slots (max_chunks * max_coll)
   uint32_t Q;   // collectives the region is sized for
   uint32_t R;   // ranks per dimension = Q * 16
-  uint32_t off_ht, off_bm, off_col, off_sq;
+  uint32_t off_ht, off_bm, off_col, off_sz, off_sq, off_sq2;
   uint32_t bytes;  // multiple of 16; 0 if the batch cannot use this path
 };
 
@@ -44,10 +44,12 @@ __host__ __device__ inline TraceLayout trace_layout(uint32_t max_chunks, uint32_
   uint32_t o = t.G * 4u;                   // W: one dword per chunk
   t.off_ht = o;  o += 4u * t.R * 4u;       // head | tail << 16 per (dimension, rank)
   t.off_bm = o;  o += 4u * kTraceLeafWords * 4u;   // bitmap leaves (when they are not in LDS)
-  // one 64-byte record per collective: chunk bytes (f64) and the size rank of
-  // each of the 16 masks (u16) -- a dispatch needs both, and gets them from one line
+  // one 64-byte record per collective: the size rank of each of the 16 masks
+  // (u16, one 32-byte row) and the chunk bytes (f64)
   t.off_col = (o + 63u) & ~63u; o = t.off_col + t.Q * kTraceCollBytes;
-  t.off_sq = o;  o += t.Q * 2u;            // collectives sorted by chunk size
+  t.off_sz = o;  o += t.R * 8u;            // resident bytes of every size rank (f64)
+  t.off_sq = o;  o += ((t.Q + 1u) & ~1u) * 2u;   // collectives sorted by chunk size
+  t.off_sq2 = o; o += ((t.Q + 1u) & ~1u) * 2u;   // the merge sort's second buffer
   t.bytes = (o + 63u) & ~63u;
   return t;
 }
@@ -67,13 +69,24 @@ struct TraceRegion {
     return ((uint32_t*)(base + t.off_bm))[(k & 3u) * kTraceLeafWords + (leaf & (kTraceLeafWords - 1u))];
   }
   __device__ __forceinline__ double& CH(uint32_t q) const {
-    return *(double*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes);
+    return *(double*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes + 32u);
   }
   __device__ __forceinline__ uint16_t& SR(uint32_t q, uint32_t mask) const {
-    return ((uint16_t*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes + 8u))[mask & 15u];
+    return ((uint16_t*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes))[mask & 15u];
+  }
+  // the 16 ranks of collective q as eight dwords
+  __device__ __forceinline__ const uint4* SRrow(uint32_t q) const {
+    return (const uint4*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes);
+  }
+  __device__ __forceinline__ double& SZ(uint32_t r) const {
+    return ((double*)(base + t.off_sz))[r < t.R ? r : t.R - 1u];
   }
   __device__ __forceinline__ uint16_t& SQ(uint32_t j) const {
     return ((uint16_t*)(base + t.off_sq))[j < t.Q ? j : t.Q - 1u];
+  }
+  // buffer 0 is SQ, buffer 1 the merge sort's spare
+  __device__ __forceinline__ uint16_t& SQbuf(uint32_t which, uint32_t j) const {
+    return ((uint16_t*)(base + ((which & 1u) ? t.off_sq2 : t.off_sq)))[j < t.Q ? j : t.Q - 1u];
   }
 };
 
@@ -86,20 +99,38 @@ __device__ __forceinline__ uint32_t trace_word(uint32_t code, uint32_t state0) {
 // Ranks of all resident sizes: a merge of the 2^D sorted lists
 // { chunk_q * 2^-E(mask) : q in ascending chunk order }, one list per mask.
 // Returns the number of distinct ranks.  lds: 48 dwords of this lane.
+template <typename Lds>
 __device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, uint32_t D,
-                                             uint32_t epack, const LaneLds& lds) {
-  // collectives in ascending (chunk bytes, index) order: insertion sort
-  for (uint32_t a = 0; a < Q; ++a) {
-    const double key = rg.CH(a);
-    uint32_t j = a;
-    while (j > 0u) {
-      const uint32_t qp = rg.SQ(j - 1u);
-      if (!(rg.CH(qp) > key)) break;
-      rg.SQ(j) = (uint16_t)qp;
-      --j;
+                                             uint32_t epack, const Lds& lds) {
+  // collectives in ascending (chunk bytes, index) order: a bottom-up merge sort
+  // of their indices (every step is a round trip to memory, so the number of
+  // steps matters: Q log Q instead of the Q^2 / 4 of an insertion sort).  Runs
+  // of `width` sorted indices are merged from buffer `src` into the other one,
+  // the left run winning ties, so equal sizes stay in index order.
+  for (uint32_t a = 0; a < Q; ++a) rg.SQbuf(0u, a) = (uint16_t)a;
+  uint32_t src = 0u;
+  for (uint32_t width = 1u; width < Q; width *= 2u) {
+    for (uint32_t lo = 0u; lo < Q; lo += 2u * width) {
+      const uint32_t mid = min(lo + width, Q), hi = min(lo + 2u * width, Q);
+      uint32_t a = lo, b = mid;
+      uint32_t ia = rg.SQbuf(src, a), ib = b < hi ? (uint32_t)rg.SQbuf(src, b) : 0u;
+      double ka = rg.CH(ia), kb = b < hi ? rg.CH(ib) : inf64();
+      for (uint32_t o = lo; o < hi; ++o) {
+        const bool left = a < mid && (b >= hi || !(ka > kb));
+        rg.SQbuf(src ^ 1u, o) = (uint16_t)(left ? ia : ib);
+        if (left) {
+          ++a;
+          if (a < mid) { ia = rg.SQbuf(src, a); ka = rg.CH(ia); }
+        } else {
+          ++b;
+          if (b < hi) { ib = rg.SQbuf(src, b); kb = rg.CH(ib); }
+        }
+      }
     }
-    rg.SQ(j) = (uint16_t)a;
+    src ^= 1u;
   }
+  if (src != 0u)
+    for (uint32_t a = 0; a < Q; ++a) rg.SQbuf(0u, a) = rg.SQbuf(1u, a);
   // merge heads in LDS: value (dwords 2m, 2m+1) and position (dword 32 + m)
   const uint32_t nm = 1u << D;
   const double first = rg.CH(rg.SQ(0));
@@ -121,6 +152,7 @@ __device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, 
       if (v < vb) { vb = v; mb = m; }
     }
     if (out > 0u && vb > prev) ++rank;
+    if (out == 0u || vb > prev) rg.SZ(rank) = vb;
     prev = vb;
     const uint32_t p = *(const uint32_t*)lds.dword(32u + mb);
     rg.SR(rg.SQ(p), mb) = (uint16_t)rank;
@@ -147,10 +179,10 @@ constexpr uint32_t kTraceLdsWordsBitmaps = 16 + 4 * kTraceLeafWords;
 // Returns false if time failed to advance somewhere (generic path decides).
 // kLdsBitmaps: the bitmap leaves live in LDS (kTraceLdsWordsBitmaps dwords per
 // lane) instead of the region; the summary words always do.
-template <bool kLdsBitmaps>
+template <bool kLdsBitmaps, typename Lds>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
                                            uint32_t state0, bool rs_only, bool scf,
-                                           const TraceRegion& rg, const LaneLds& lds,
+                                           const TraceRegion& rg, const Lds& lds,
                                            const SimOut& out, double& t_done,
                                            double (&busy)[kMaxDims],
                                            uint32_t (&executed_out)[kMaxDims]) {
@@ -188,8 +220,12 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   uint32_t waiting[kMaxDims] = {0u, 0u, 0u, 0u};
   bool stalled = false;
 
+  // g / C for g < 2^23 (chunk ids stay below 2^16) without a division:
+  // ceil(2^32 / C) fits 32 bits from C = 2 on
+  const uint32_t c_inv = (uint32_t)((0x100000000ull + C - 1u) / C);
+  auto coll_of = [&](uint32_t g) -> uint32_t { return C == 1u ? g : __umulhi(g, c_inv); };
   auto rank_of = [&](uint32_t g, uint32_t mask) -> uint32_t {
-    return scf ? (uint32_t)rg.SR(g / C, mask) : 0u;
+    return scf ? (uint32_t)rg.SR(coll_of(g), mask) : 0u;
   };
   auto push = [&](uint32_t k, uint32_t r, uint32_t g) {
     const uint32_t leaf = r >> 5, bit = 1u << (r & 31u);
@@ -208,8 +244,11 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     for (uint32_t kk = 0; kk < 4u; ++kk) waiting[kk] += (kk == k) ? 1u : 0u;
   };
   // first chunk of the lowest non-empty rank (smallest resident size); w
-  // receives its chunk word
-  auto pop = [&](uint32_t k, uint32_t& w) -> uint32_t {
+  // receives its chunk word, size the resident bytes of a chunk of that rank
+  // and row the size ranks of the chunk's collective.  The loads that do not
+  // depend on each other are issued together: list head and size of the rank,
+  // then chunk word and rank row, two round trips to memory instead of three.
+  auto pop = [&](uint32_t k, uint32_t& w, double& size, uint4& row_lo, uint4& row_hi) -> uint32_t {
     uint32_t leaf = 0;
     for (uint32_t sw = 0; sw < kTraceSumWords; ++sw) {
       const uint32_t v = SUM(k, sw);
@@ -218,8 +257,17 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     const uint32_t lw = BM(k, leaf);
     const uint32_t r = leaf * 32u + (lw ? (uint32_t)__builtin_ctz(lw) : 0u);
     const uint32_t ht = rg.HT(k, r);
+    if (scf) size = rg.SZ(r);
     const uint32_t h = ht & 0xffffu, tl = ht >> 16;
     w = rg.W(h);
+    if (scf) {
+      const uint4* row = rg.SRrow(coll_of(h));
+      row_lo = row[0];
+      row_hi = row[1];
+    } else {
+      // one list per dimension: the size comes from the chunk's collective
+      size = scale_down(rg.CH(coll_of(h)), esum(epack, w & 15u));
+    }
     if (h == tl) {
       const uint32_t nlw = lw & ~(1u << (r & 31u));
       BM(k, leaf) = nlw;
@@ -251,11 +299,14 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       if (!need) break;
       const uint32_t k = (uint32_t)__builtin_ctz(need);
       uint32_t w;
-      const uint32_t h = pop(k, w);
+      double size;
+      uint4 row_lo = {0u, 0u, 0u, 0u}, row_hi = {0u, 0u, 0u, 0u};
+      const uint32_t h = pop(k, w, size, row_lo, row_hi);
       const uint32_t mask = w & 15u, phase = (w >> 4) & 1u;
       const uint32_t ek = (epack >> (8u * k)) & 0xffu;
-      const uint32_t E = esum(epack, mask) - (phase ? ek : 0u);
-      double t = scale_down(rg.CH(h / C), E) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+      // bytes moved on k: the resident size before the chunk's Reduce-Scatter
+      // on k, which an All-Gather on k finds 2^ek times smaller
+      double t = scale_up(size, phase ? ek : 0u) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
       if (s.has_fix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
       const double fin = now + t;
       // a stage that does not move the clock, or overflows it: generic path decides
@@ -269,7 +320,14 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
       const uint32_t p = (uint32_t)__builtin_popcount(mask2) - phase2;
       const uint32_t kn = finished ? 4u : (code >> ((2u * p) & 31u)) & 3u;
-      const uint32_t rk = finished ? 0u : rank_of(h, mask2);
+      uint32_t rk = 0u;
+      if (scf) {
+        const uint32_t pair = sel4((int)(mask2 >> 1), sel4((int)(mask2 >> 3), row_lo.x, row_hi.x, 0u, 0u),
+                                   sel4((int)(mask2 >> 3), row_lo.y, row_hi.y, 0u, 0u),
+                                   sel4((int)(mask2 >> 3), row_lo.z, row_hi.z, 0u, 0u),
+                                   sel4((int)(mask2 >> 3), row_lo.w, row_hi.w, 0u, 0u));
+        rk = (pair >> (16u * (mask2 & 1u))) & 0xffffu;
+      }
       const uint32_t nw = mask2 | (phase2 << 4) | (code << 8) | (kNoChunk << 16);
       uint32_t pos = 0;
 #pragma unroll
