@@ -375,16 +375,15 @@ simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 // themis_simulate_batch for traces (several collectives sharing the queues):
 // the ranked-list path of themis_trace.hpp, else the generic path.
 // ---------------------------------------------------------------------------
-template <bool kLdsBitmaps, uint32_t kLaneShift>
+template <bool kLdsBitmaps>
 __global__ void __launch_bounds__(kBlock)
 simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                       double* __restrict__ t_done, void* __restrict__ queue_order,
                       int entry_bytes, double* __restrict__ busy, Workspace w, bool have_ws,
                       uint8_t* __restrict__ trace_area, TraceLayout tl) {
-  constexpr uint32_t kLanes = 1u << (kLaneShift - 2u);  // scenarios per wavefront
-  __shared__ uint32_t lds_block[(kLdsBitmaps ? kTraceLdsWordsBitmaps : kTraceLdsWords) * kLanes];
-  uint64_t i = (uint64_t)blockIdx.x * kLanes + threadIdx.x;
-  if (threadIdx.x >= kLanes || i >= b.n) return;
+  __shared__ uint32_t lds_block[(kLdsBitmaps ? kTraceLdsWordsBitmaps : kTraceLdsWords) * kBlock];
+  uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= b.n) return;
   const TraceView tv = trace_view(b);
   Scenario s = load_scenario(b, i);
   const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
@@ -429,7 +428,7 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
           rg.W(q * s.C + c) = trace_word(stored_code(s, fs0, code), fs0.state0);
         }
       if (!codes_ok) { write_invalid(out); return; }
-      LaneLdsT<kLaneShift> lds;
+      LaneLds lds;
       lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
       double T, z[kMaxDims];
       uint32_t ex[kMaxDims];
@@ -961,14 +960,9 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                             workspace_bytes_given >= generic + (size_t)batch->n * tl.bytes;
     uint8_t* trace_area = have_trace ? (uint8_t*)workspace + generic : nullptr;
     // few wavefronts (no more than CUs): the bitmap leaves move into the LDS nothing else would use
-    unsigned lanes = 64;
-    if (const char* e = getenv("THEMIS_TRACE_LANES")) lanes = (unsigned)atoi(e);
-    auto trace_kernel = lanes == 64 ? (blocks_for(batch->n) <= compute_units() ? simulate_trace_kernel<true, 8>
-                                                                 : simulate_trace_kernel<false, 8>)
-                      : lanes == 32 ? simulate_trace_kernel<true, 7>
-                      : lanes == 16 ? simulate_trace_kernel<true, 6>
-                      : lanes == 8 ? simulate_trace_kernel<true, 5> : simulate_trace_kernel<true, 4>;
-    hipLaunchKernelGGL(trace_kernel, dim3((unsigned)((batch->n + lanes - 1) / lanes)), dim3(kBlock), 0,
+    auto trace_kernel = blocks_for(batch->n) <= compute_units() ? simulate_trace_kernel<true>
+                                                                 : simulate_trace_kernel<false>;
+    hipLaunchKernelGGL(trace_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
                        busy, w, have_ws, trace_area, tl);
     return launch_status();

@@ -30,15 +30,11 @@
 
 namespace themis {
 
-// One lane's share of a wavefront's LDS block: the block is dword-transposed
-// over the 2^(kLaneShift - 2) lanes that use it.
-template <uint32_t kLaneShift>
-struct LaneLdsT {
+struct LaneLds {
   uint8_t* base;  // LDS block of the wavefront + 4*lane
-  // byte address of dword d of this lane (2^kLaneShift bytes apart)
-  __device__ __forceinline__ uint8_t* dword(uint32_t d) const { return base + (d << kLaneShift); }
+  // byte address of dword d of this lane (transposed layout: 256 B apart)
+  __device__ __forceinline__ uint8_t* dword(uint32_t d) const { return base + (d << 8); }
 };
-using LaneLds = LaneLdsT<8>;  // all 64 lanes: 256 B apart
 
 // Four small per-dimension counters / ids packed in one register (pair).
 template <typename Word, int kBits>

@@ -99,9 +99,8 @@ __device__ __forceinline__ uint32_t trace_word(uint32_t code, uint32_t state0) {
 // Ranks of all resident sizes: a merge of the 2^D sorted lists
 // { chunk_q * 2^-E(mask) : q in ascending chunk order }, one list per mask.
 // Returns the number of distinct ranks.  lds: 48 dwords of this lane.
-template <typename Lds>
 __device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, uint32_t D,
-                                             uint32_t epack, const Lds& lds) {
+                                             uint32_t epack, const LaneLds& lds) {
   // collectives in ascending (chunk bytes, index) order: a bottom-up merge sort
   // of their indices (every step is a round trip to memory, so the number of
   // steps matters: Q log Q instead of the Q^2 / 4 of an insertion sort).  Runs
@@ -179,10 +178,10 @@ constexpr uint32_t kTraceLdsWordsBitmaps = 16 + 4 * kTraceLeafWords;
 // Returns false if time failed to advance somewhere (generic path decides).
 // kLdsBitmaps: the bitmap leaves live in LDS (kTraceLdsWordsBitmaps dwords per
 // lane) instead of the region; the summary words always do.
-template <bool kLdsBitmaps, typename Lds>
+template <bool kLdsBitmaps>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
                                            uint32_t state0, bool rs_only, bool scf,
-                                           const TraceRegion& rg, const Lds& lds,
+                                           const TraceRegion& rg, const LaneLds& lds,
                                            const SimOut& out, double& t_done,
                                            double (&busy)[kMaxDims],
                                            uint32_t (&executed_out)[kMaxDims]) {
