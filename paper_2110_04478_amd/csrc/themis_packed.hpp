@@ -74,7 +74,7 @@ struct PackedOrder {
 // Same contract as simulate_fast (records initialised with L::init_chunk(),
 // result.ok false leaves the evaluation to the generic path); power-of-two
 // model only.
-template <typename L, int kQueueOrder, bool kBusy, bool kFix>
+template <typename L, int kQueueOrder, bool kBusy, bool kFix, bool kOnePerPass = false>
 __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const Pow2Model& model,
                                                       const LaneLds& lds, const FastOut& out) {
   static_assert(kQueueOrder == kNoQueueOrder || kQueueOrder == kBytes || kQueueOrder == kShorts,
@@ -128,10 +128,11 @@ __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const P
   }
 
   double now = 0.0;
-  const uint32_t max_steps = 2u * D * C + 8u;
+  const uint32_t max_steps = 4u * D * C + 16u;
   for (uint32_t step = 0; step <= max_steps; ++step) {
     // a7: every idle dimension with waiting chunks starts its first one
-    for (uint32_t need = idle & work; need != 0u; need = idle & work) {
+    // (kOnePerPass as in simulate_fast)
+    for (uint32_t need = idle & work; need != 0u; need = kOnePerPass ? 0u : (idle & work)) {
       const uint32_t k = (uint32_t)__builtin_ctz(need);
       uint32_t field;
       const uint32_t cls = classes.lowest(k, field);  // smallest resident size
@@ -196,6 +197,7 @@ __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const P
       if (kQueueOrder != kNoQueueOrder) executed.inc(k);
       ++started;
     }
+    if (kOnePerPass && (idle & work) != 0u) continue;
 
     // a8: advance to the earliest completion
     const double next = min_f64(min_f64(f0, f1), min_f64(f2, f3));
