@@ -226,15 +226,20 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   auto rank_of = [&](uint32_t g, uint32_t mask) -> uint32_t {
     return scf ? (uint32_t)rg.SR(coll_of(g), mask) : 0u;
   };
-  auto push = [&](uint32_t k, uint32_t r, uint32_t g) {
+  // Memory operations of one wavefront retire in order, so waiting for a load
+  // also waits for every store issued before it: push and pop read first and
+  // store last (word: the chunk's new word, stored here for that reason).
+  auto push = [&](uint32_t k, uint32_t r, uint32_t g, bool has_word, uint32_t word) {
     const uint32_t leaf = r >> 5, bit = 1u << (r & 31u);
     const uint32_t lw = BM(k, leaf);
     if (lw & bit) {
       const uint32_t ht = rg.HT(k, r);
       const uint32_t tl = ht >> 16;
+      if (has_word) rg.W(g) = word;
       ((uint16_t*)&rg.W(tl))[1] = (uint16_t)g;  // the old tail's next field
       rg.HT(k, r) = (ht & 0xffffu) | (g << 16);
     } else {
+      if (has_word) rg.W(g) = word;
       rg.HT(k, r) = g | (g << 16);
       BM(k, leaf) = lw | bit;
       SUM(k, leaf >> 5) |= 1u << (leaf & 31u);
@@ -247,7 +252,10 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   // and row the size ranks of the chunk's collective.  The loads that do not
   // depend on each other are issued together: list head and size of the rank,
   // then chunk word and rank row, two round trips to memory instead of three.
-  auto pop = [&](uint32_t k, uint32_t& w, double& size, uint4& row_lo, uint4& row_hi) -> uint32_t {
+  // new_entry / at: the list's entry once its head is gone, for the caller to
+  // store (at = 4 * R: nothing to store, the list is empty now)
+  auto pop = [&](uint32_t k, uint32_t& w, double& size, uint4& row_lo, uint4& row_hi,
+                 uint32_t& new_entry, uint32_t& at) -> uint32_t {
     uint32_t leaf = 0;
     for (uint32_t sw = 0; sw < kTraceSumWords; ++sw) {
       const uint32_t v = SUM(k, sw);
@@ -267,12 +275,15 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       // one list per dimension: the size comes from the chunk's collective
       size = scale_down(rg.CH(coll_of(h)), esum(epack, w & 15u));
     }
+    at = 4u * rg.t.R;
+    new_entry = 0u;
     if (h == tl) {
       const uint32_t nlw = lw & ~(1u << (r & 31u));
       BM(k, leaf) = nlw;
       if (!nlw) SUM(k, leaf >> 5) &= ~(1u << (leaf & 31u));
     } else {
-      rg.HT(k, r) = (w >> 16) | (tl << 16);
+      new_entry = (w >> 16) | (tl << 16);
+      at = (k & 3u) * rg.t.R + (r < rg.t.R ? r : rg.t.R - 1u);  // clamped as in HT()
     }
 #pragma unroll
     for (uint32_t kk = 0; kk < 4u; ++kk) waiting[kk] -= (kk == k) ? 1u : 0u;
@@ -284,23 +295,30 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     const uint32_t mask0 = state0 & 15u, phase0 = state0 >> 4;
     const uint32_t pos0 = 2u * ((uint32_t)__builtin_popcount(mask0) - phase0);
     for (uint32_t g = 0; g < G; ++g)
-      push((rg.W(g) >> (8u + pos0)) & 3u, rank_of(g, mask0), g);
+      push((rg.W(g) >> (8u + pos0)) & 3u, rank_of(g, mask0), g, false, 0u);
   }
 
   double now = 0.0;
-  const uint64_t max_steps = (uint64_t)2u * D * G + 8u;
-  for (uint64_t step = 0; step <= max_steps; ++step) {
-    // a7: every idle dimension with waiting chunks starts its first one
-    for (;;) {
-      uint32_t need = 0;
+  // One pass starts at most one stage and, once no idle dimension has chunks
+  // waiting, advances the clock (as in simulate_fast: a lane with two stages to
+  // start at one instant takes two passes, the other lanes of the wavefront go
+  // on meanwhile).
+  auto idle_with_work = [&]() -> uint32_t {
+    uint32_t need = 0;
 #pragma unroll
-      for (uint32_t kk = 0; kk < 4u; ++kk) need |= (f[kk] == kInf && waiting[kk] != 0u) ? (1u << kk) : 0u;
-      if (!need) break;
+    for (uint32_t kk = 0; kk < 4u; ++kk) need |= (f[kk] == kInf && waiting[kk] != 0u) ? (1u << kk) : 0u;
+    return need;
+  };
+  const uint64_t max_steps = (uint64_t)4u * D * G + 16u;
+  for (uint64_t step = 0; step <= max_steps; ++step) {
+    // a7: an idle dimension with waiting chunks starts its first one
+    if (const uint32_t need = idle_with_work()) {
       const uint32_t k = (uint32_t)__builtin_ctz(need);
       uint32_t w;
       double size;
       uint4 row_lo = {0u, 0u, 0u, 0u}, row_hi = {0u, 0u, 0u, 0u};
-      const uint32_t h = pop(k, w, size, row_lo, row_hi);
+      uint32_t new_entry, entry_at;
+      const uint32_t h = pop(k, w, size, row_lo, row_hi, new_entry, entry_at);
       const uint32_t mask = w & 15u, phase = (w >> 4) & 1u;
       const uint32_t ek = (epack >> (8u * k)) & 0xffu;
       // bytes moved on k: the resident size before the chunk's Reduce-Scatter
@@ -343,8 +361,10 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
         }
       }
       if (out.queue_order && pos < 2u * out.slots) put_entry(out, (int)k, pos, (h << 1) | phase);
+      if (entry_at < 4u * rg.t.R) ((uint32_t*)(rg.base + rg.t.off_ht))[entry_at] = new_entry;
     }
     if (stalled) break;
+    if (idle_with_work() != 0u) continue;  // all stages of an instant start before the clock moves
 
     // a8: advance to the earliest completion
     const double next = min_f64(min_f64(f[0], f[1]), min_f64(f[2], f[3]));
@@ -367,10 +387,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
 #pragma unroll
       for (uint32_t kk = 0; kk < 4u; ++kk)
         if (kk == k) { nw = next_word[kk]; kn = next_dim[kk]; rk = next_rank[kk]; }
-      if (kn < 4u) {
-        rg.W(g) = nw;
-        push(kn, rk, g);
-      }
+      if (kn < 4u) push(kn, rk, g, true, nw);
     } while (done);
   }
 
