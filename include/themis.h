@@ -164,11 +164,14 @@ int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
  *   - single collectives with power-of-two NPU counts and sizes whose
  *     halvings stay in the normal binary64 range run entirely in registers
  *     and LDS and need no workspace;
- *   - the other single collectives (an NPU count that is not a power of two,
- *     extreme magnitudes) need no workspace either while max_chunks <= 64
- *     (LDS paths on per-order tables; a slower generic path whose per-chunk
- *     state also sits in LDS remains behind them); beyond 64 chunks the
- *     generic path keeps that state in the workspace;
+ *   - the other single collectives need no workspace either while
+ *     max_chunks <= 64 (NPU counts that are not powers of two: LDS paths on
+ *     per-order tables; a slower generic path whose per-chunk state also sits
+ *     in LDS remains behind them for the rest, e.g. extreme magnitudes);
+ *   - up to 128 chunks NPU counts that are not powers of two still run in
+ *     LDS without a workspace; beyond 64 chunks the generic path, which takes
+ *     what no LDS path can (beyond 128 chunks: every NPU count that is not a
+ *     power of two), keeps its per-chunk state in the workspace;
  *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace
  *     (staggered release times: on the generic path, in the workspace too).
  * For themis_sweep pass n * n_thr * n_pol as n and max_coll = 0.

@@ -308,6 +308,8 @@ simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     out.queue_order = queue_order
         ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
         : nullptr;
+    // beyond the LDS variant's chunk count the arrays need the caller's workspace
+    if (!kLdsSlots && !w.meta) { write_invalid(out); continue; }
     simulate_generic_scenario<(kLdsSlots > 0)>(b, tv, s, Q, i, col, orders + (size_t)i * tv.slots,
                                                scf, w, out);
   }
@@ -318,12 +320,22 @@ simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 // first the variant for at most 8 distinct order codes, then (kWide) the one
 // for any number of them; what they cannot take stays marked for the generic
 // kernel.
-template <int kQueueOrder, bool kWide>
+// kVariant: 0 tables for at most 8 order codes (64 chunks), 1 any number of
+// codes (64 chunks), 2 the same for up to 128 chunks.
+template <int kVariant>
+struct TableVariant {
+  using L = typename std::conditional<kVariant == 0, LayoutTable,
+            typename std::conditional<kVariant == 1, LayoutTableWide, LayoutTableWide128>::type>::type;
+};
+
+template <int kQueueOrder, int kVariant>
 __global__ void __launch_bounds__(kBlock)
 simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                       double* __restrict__ t_done, void* __restrict__ queue_order,
                       double* __restrict__ busy, unsigned long long call) {
-  using L = typename std::conditional<kWide, LayoutTableWide, LayoutTable>::type;
+  using L = typename TableVariant<kVariant>::L;
+  constexpr bool kWide = kVariant != 0;
+  constexpr uint32_t kEntryBytes = kQueueOrder == kShorts ? 2u : 1u;
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   if (nothing_marked(call)) return;
   const uint64_t groups = (b.n + kBlock - 1) / kBlock;
@@ -342,15 +354,15 @@ simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
     const double chunk = S / (double)s.C;
     auto code_at = [&](uint32_t c) { return (uint32_t)row[c]; };
-    const uint32_t rows_bytes = (uint32_t)kMaxDims * 2u * b.max_chunks;
+    const uint32_t rows_bytes = (uint32_t)kMaxDims * 2u * b.max_chunks * kEntryBytes;
     FastOut fo;
     fo.queue_order = (kQueueOrder != kNoQueueOrder && queue_order)
         ? (uint8_t*)queue_order + (size_t)i * rows_bytes : nullptr;
     fo.slots = b.max_chunks;
     FastResult r;
     if constexpr (kWide) {
-      DivModel model(s, lds, chunk, scf);
-      table_setup_wide(s, scf, lds, code_at, model);
+      DivModelT<L> model(s, lds, chunk, scf);
+      table_setup_wide<L>(s, scf, lds, code_at, model);
       r = simulate_fast<L, kQueueOrder, true, true>(s, model, lds, fo);
     } else {
       TableModel model;
@@ -366,7 +378,7 @@ simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     if (kQueueOrder != kNoQueueOrder && fo.queue_order) {
       for (int k = 0; k < kMaxDims; ++k)
         for (uint32_t e = r.executed[k]; e < 2u * b.max_chunks; ++e)
-          fo.queue_order[(uint32_t)k * 2u * b.max_chunks + e] = 0xFFu;
+          put_queue_entry<kQueueOrder>(fo.queue_order, (uint32_t)k * 2u * b.max_chunks + e, 0xFFFFu);
     }
   }
 }
@@ -564,6 +576,7 @@ sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr
     out.queue_order = nullptr;
     out.entry_bytes = 1;
     out.slots = b.max_chunks;
+    if (!kLdsSlots && !w.meta) { t_done[e] = nan64(); continue; }
     sweep_generic_evaluation<(kLdsSlots > 0)>(s, b.size_bytes[it.i] / (double)s.C, it.themis_on,
                                               b.threshold_mode == THEMIS_THR_REL, it.th, it.scf,
                                               col, w, out);
@@ -572,12 +585,13 @@ sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr
 
 // The same for themis_sweep: Alg. 1 with real divisions straight into the
 // chunk words, then the table-driven event loop.
-template <bool kWide>
+template <int kVariant>
 __global__ void __launch_bounds__(kBlock)
 sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
                    int thr_per_scenario, unsigned policy_mask, int n_pol,
                    double* __restrict__ t_done, unsigned long long call) {
-  using L = typename std::conditional<kWide, LayoutTableWide, LayoutTable>::type;
+  using L = typename TableVariant<kVariant>::L;
+  constexpr bool kWide = kVariant != 0;
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
   if (nothing_marked(call)) return;
   const uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
@@ -602,8 +616,8 @@ sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
     fo.slots = b.max_chunks;
     FastResult r;
     if constexpr (kWide) {
-      DivModel model(s, lds, chunk, it.scf);
-      table_setup_wide(s, it.scf, lds, code_at, model);
+      DivModelT<L> model(s, lds, chunk, it.scf);
+      table_setup_wide<L>(s, it.scf, lds, code_at, model);
       r = simulate_fast<L, kNoQueueOrder, false, true>(s, model, lds, fo);
     } else {
       TableModel model;
@@ -976,27 +990,36 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   // kernel: with its arrays in LDS up to 64 chunks, from the workspace beyond
   auto generic = cap <= 16u ? simulate_generic_kernel<16> : cap <= 64u ? simulate_generic_kernel<64>
                                                                        : simulate_generic_kernel<0>;
-  const unsigned long long call = (cap <= 64u || have_ws) ? next_call_number() : 0ull;
+  // up to 128 chunks follow-up kernels always come: the table kernels need no
+  // workspace, and the generic kernel without one only closes what they left
+  const unsigned long long call = (cap <= 128u || have_ws) ? next_call_number() : 0ull;
   const bool hand_over = call != 0ull;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
                      call);
   if (cap <= 64u) {
-    auto table = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, false>
-               : mode == kWords ? simulate_table_kernel<kWords, false>
-                                : simulate_table_kernel<kBytes, false>;
-    auto wide = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, true>
-              : mode == kWords ? simulate_table_kernel<kWords, true>
-                               : simulate_table_kernel<kBytes, true>;
+    auto table = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 0>
+               : mode == kWords ? simulate_table_kernel<kWords, 0>
+                                : simulate_table_kernel<kBytes, 0>;
+    auto wide = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 1>
+              : mode == kWords ? simulate_table_kernel<kWords, 1>
+                               : simulate_table_kernel<kBytes, 1>;
     hipLaunchKernelGGL(table, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
+    hipLaunchKernelGGL(wide, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
+  } else if (cap == 128u) {
+    auto wide = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 2>
+              : mode == kWords ? simulate_table_kernel<kWords, 2>
+              : mode == kShorts ? simulate_table_kernel<kShorts, 2>
+                                : simulate_table_kernel<kBytes, 2>;
     hipLaunchKernelGGL(wide, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
   }
   if (hand_over)
     hipLaunchKernelGGL(generic, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
-                       busy, w, call);
+                       busy, have_ws ? w : Workspace{}, call);
   return launch_status();
 }
 
@@ -1026,23 +1049,27 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
                             : (fix ? sweep_kernel<LayoutPacked<512>, true> : sweep_kernel<LayoutPacked<512>, false>);
   auto generic = cap <= 16u ? sweep_generic_kernel<16> : cap <= 64u ? sweep_generic_kernel<64>
                                                                     : sweep_generic_kernel<0>;
-  const unsigned long long call = (cap <= 64u || have_ws) ? next_call_number() : 0ull;
+  const unsigned long long call = (cap <= 128u || have_ws) ? next_call_number() : 0ull;
   const bool hand_over = call != 0ull;
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                      n_pol, t_done, call);
   if (cap <= 64u) {
-    hipLaunchKernelGGL(sweep_table_kernel<false>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
+    hipLaunchKernelGGL(sweep_table_kernel<0>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                        n_pol, t_done, call);
-    hipLaunchKernelGGL(sweep_table_kernel<true>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
+    hipLaunchKernelGGL(sweep_table_kernel<1>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
+                       n_pol, t_done, call);
+  } else if (cap == 128u) {
+    hipLaunchKernelGGL(sweep_table_kernel<2>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                        n_pol, t_done, call);
   }
   if (hand_over)
     hipLaunchKernelGGL(generic, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                       n_pol, t_done, w, call);
+                       n_pol, t_done, have_ws ? w : Workspace{}, call);
   return launch_status();
 }
 

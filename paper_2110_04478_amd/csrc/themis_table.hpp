@@ -20,11 +20,12 @@
 // most 64 chunks with at most kSlots distinct order codes (LayoutTable: every
 // network of up to three dimensions).  With more distinct codes (four
 // dimensions: up to 24) the sizes that can wait for one dimension no longer
-// fit 16 classes; the wide variant (LayoutTableWide, Classes64, DivModel)
-// gives every dimension 64 classes (one bitmap register pair each), keeps the slot in
-// its own byte of the chunk word, and pays for the larger list tables by
+// fit 16 classes; the wide variant (LayoutTableWideT, Classes64, DivModelT)
+// gives every dimension 64 classes (one bitmap register pair each), keeps the
+// slot in its own byte of the chunk word, pays for the larger list tables by
 // redoing a stage time's divisions at each dispatch instead of tabulating
-// them.  Everything else stays with the generic path.
+// them, and also comes with 128 chunk words.  Everything else stays with the
+// generic path.
 #pragma once
 
 #include "themis_fast.hpp"
@@ -218,16 +219,20 @@ struct Classes64 {
   }
 };
 
-struct LayoutTableWide {
-  static constexpr uint32_t kCap = 64;
+template <uint32_t kChunks>
+struct LayoutTableWideT {
+  static constexpr bool kPacked = false;
+  static constexpr uint32_t kCap = kChunks;
+  static_assert(kChunks == 64 || kChunks == 128, "8-bit links; ids as in LayoutByte");
   static constexpr uint32_t kSlots = 24;
-  static constexpr uint32_t kHeadBase = 64, kTailBase = 128, kClassBase = 192;
-  static constexpr uint32_t kLaneWords = kClassBase + kSlots * 8u / 4u;  // 240
+  // kChunks chunk dwords, then u8 head[256], u8 tail[256], u8 class[kSlots][8]
+  static constexpr uint32_t kHeadBase = kChunks, kTailBase = kChunks + 64, kClassBase = kChunks + 128;
+  static constexpr uint32_t kLaneWords = kClassBase + kSlots * 8u / 4u;  // 240 / 304
   static constexpr uint32_t kWavesPerSimd = 1;
   static constexpr uint32_t kEnd = 0xffu;
   using Link = uint8_t;
   using Classes = Classes64;
-  using Ids = Pack4<uint32_t, 8>;
+  using Ids = typename std::conditional<(kChunks <= 64), Pack4<uint32_t, 8>, Pack4<uint64_t, 16>>::type;
   static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
                                                     uint32_t slot, uint32_t state0) {
     *(uint32_t*)l.dword(c) = (slot << 24) | (code << 16) | (kEnd << 8) | state0;
@@ -245,10 +250,13 @@ struct LayoutTableWide {
     return l.base + ((kTailBase + (q >> 2)) << 8) + (q & 3u);
   }
 };
+using LayoutTableWide = LayoutTableWideT<64>;      // 240 dwords, two wavefronts per CU
+using LayoutTableWide128 = LayoutTableWideT<128>;  // 304 dwords, two wavefronts per CU
 
 // Model for the wide variant: classes from the table, stage times from the
 // chunk size by the order's own divisions.
-struct DivModel {
+template <typename LT>
+struct DivModelT {
   const Scenario& s;
   LaneLds lds;
   double chunk;
@@ -256,7 +264,7 @@ struct DivModel {
   bool rs;
   bool gather;  // stand-alone All-Gather (chunk words hold the order code reversed)
   bool scf;
-  __device__ __forceinline__ DivModel(const Scenario& s_, const LaneLds& l, double chunk_, bool scf_)
+  __device__ __forceinline__ DivModelT(const Scenario& s_, const LaneLds& l, double chunk_, bool scf_)
       : s(s_), lds(l), chunk(chunk_), tmin(inf64()),
         rs(s_.ctype == THEMIS_COLL_REDUCE_SCATTER), gather(s_.ctype == THEMIS_COLL_ALL_GATHER),
         scf(scf_) {}
@@ -287,25 +295,24 @@ struct DivModel {
   }
   __device__ __forceinline__ double stage_time(uint32_t, uint32_t, uint32_t w) const {
     const uint32_t pos = ((uint32_t)__builtin_popcount(w & 15u) - ((w >> 4) & 1u)) & 3u;
-    return time_at(LayoutTableWide::code(w), pos);
+    return time_at(LT::code(w), pos);
   }
   __device__ __forceinline__ uint32_t size_class(uint32_t w, uint32_t mask, uint32_t phase) const {
     if (!scf) return 0u;
     const uint32_t r = (uint32_t)__builtin_popcount(mask);
     const uint32_t stage = (phase ? 2u * (uint32_t)s.D - r : r) & 7u;
     const uint32_t slot = w >> 24;
-    const uint32_t idx = (slot < LayoutTableWide::kSlots ? slot : 0u) * 8u + stage;
-    return lds.dword(LayoutTableWide::kClassBase + (idx >> 2))[idx & 3u];
+    const uint32_t idx = (slot < LT::kSlots ? slot : 0u) * 8u + stage;
+    return lds.dword(LT::kClassBase + (idx >> 2))[idx & 3u];
   }
   __device__ __forceinline__ double t_min(uint32_t) const { return tmin; }
 };
 
 // Setup of the wide variant; code_at as in table_setup().  Cannot fail: four
 // dimensions have 24 orders.
-template <typename CodeAt>
+template <typename LT, typename CodeAt>
 __device__ inline void table_setup_wide(const Scenario& s, bool scf, const LaneLds& lds,
-                                        CodeAt code_at, DivModel& model) {
-  using LT = LayoutTableWide;
+                                        CodeAt code_at, DivModelT<LT>& model) {
   const uint32_t D = (uint32_t)s.D;
   // scratch: slot codes as bytes from dword kHeadBase, sizes as doubles from dword kHeadBase + 8
   auto slot_code = [&](uint32_t sl) -> uint8_t& { return lds.dword(LT::kHeadBase + (sl >> 2))[sl & 3u]; };

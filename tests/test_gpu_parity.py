@@ -53,23 +53,23 @@ def widen_queue(q):
     return q.astype(np.uint16)
 
 
-def run_gpu(gpu, batch, queue=True):
+def run_gpu(gpu, batch, queue=True, workspace=True):
     import torch
     d = gpu.to_device(batch)
     orders, loads = gpu.themis_plan_batch(d)
     ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(
-        d.n, d.max_chunks, d.max_coll if d.n_coll is not None else 0))
+        d.n, d.max_chunks, d.max_coll if d.n_coll is not None else 0)) if workspace else None
     t, qo, busy = gpu.themis_simulate_batch(d, orders, workspace=ws, want_queue_order=queue)
     torch.cuda.synchronize()
     return (orders.cpu().numpy(), loads.cpu().numpy(), t.cpu().numpy(),
             widen_queue(qo) if queue else None, busy.cpu().numpy())
 
 
-def check_batch(gpu, oracle, batch, queue=True, threads=8):
+def check_batch(gpu, oracle, batch, queue=True, threads=8, workspace=True):
     o_orders, o_loads = oracle.plan_batch(batch, threads=threads)
     o_t, o_qo, o_busy = oracle.simulate_batch(batch, o_orders, want_queue_order=queue,
                                               threads=threads)
-    g_orders, g_loads, g_t, g_qo, g_busy = run_gpu(gpu, batch, queue)
+    g_orders, g_loads, g_t, g_qo, g_busy = run_gpu(gpu, batch, queue, workspace)
     bad = np.nonzero((g_orders != o_orders).any(axis=1))[0]
     assert bad.size == 0, f"order codes differ in {bad.size} scenarios, first {bad[:5]}"
     assert_close("loads", g_loads, o_loads)
@@ -153,24 +153,28 @@ def test_three_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle, ctype
         assert_close("sweep", got.cpu().numpy(), oracle.sweep(b, thr.cpu().numpy(), 7, threads=16))
 
 
-def test_four_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle):
+@pytest.mark.parametrize("max_chunks", [64, 100, 128])
+def test_four_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle, max_chunks):
     """4-D networks with NPU counts like 3, 6, 10, 48, 72: Themis plans use well
     over 8 distinct orders, random plans all 24 -- the variant with 64 size
-    classes per dimension.  Evenly dividing sizes give equal keys."""
+    classes per dimension (up to 128 chunks; 8- and 16-bit queue entries).
+    Evenly dividing sizes give equal keys.  No workspace is passed: nothing
+    may be left to the generic scan."""
     import torch
     W = w()
-    n = 1500
-    rng = np.random.default_rng(57)
+    n = 1500 if max_chunks == 64 else 600
+    rng = np.random.default_rng(57 + max_chunks)
     b = W.config3(n=n)
+    b.max_chunks = max_chunks
     b.npus = np.ascontiguousarray(rng.choice([3, 6, 10, 12, 48, 72, 5, 4], (4, n)).astype(np.uint32))
     b.intra_policy = rng.integers(0, 2, n).astype(np.uint8)
     b.size_bytes = np.where(rng.random(n) < 0.5, 2.0 ** rng.integers(24, 31, n) * 45.0, b.size_bytes)
     b.bw = np.ascontiguousarray(np.where(rng.random((4, n)) < 0.5,
                                          2.0 ** rng.integers(33, 37, (4, n)), b.bw))
-    b.chunks = rng.choice([5, 24, 63, 64], n).astype(np.uint32)
+    b.chunks = rng.choice([5, 24, max_chunks - 1, max_chunks], n).astype(np.uint32)
     b.collective_type = rng.integers(0, 3, n).astype(np.uint8)
     b.fixed_delay = np.ascontiguousarray(rng.uniform(0, 2e-6, (4, n)) * (rng.random((4, n)) < 0.5))
-    check_batch(gpu, oracle, b, threads=16)
+    check_batch(gpu, oracle, b, threads=16, workspace=False)
     # arbitrary (not planned) orders: all 24 permutations in one scenario
     orders = np.full((n, b.max_chunks), 0xFF, np.uint8)
     perms = [sum(int(k) << (2 * j) for j, k in enumerate(p))
@@ -191,12 +195,14 @@ def test_four_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle):
     assert_close("sweep", got.cpu().numpy(), oracle.sweep(b, thr.cpu().numpy(), 7, threads=16))
 
 
-def test_workspace_is_only_needed_beyond_64_chunks(gpu, oracle):
-    """Up to 64 chunks the generic kernel keeps its per-chunk arrays in LDS: no
-    workspace, same results.  Beyond, scenarios off the LDS path come back as
-    NaN / all-ones when no workspace is passed, the others are unaffected."""
+def test_workspace_is_only_needed_beyond_128_chunks(gpu, oracle):
+    """Up to 64 chunks the generic kernel keeps its per-chunk arrays in LDS, up
+    to 128 the LDS kernels for arbitrary NPU counts take what the power-of-two
+    kernel leaves: no workspace, same results.  Beyond, scenarios off the LDS
+    paths come back as NaN / all-ones when no workspace is passed, the others
+    are unaffected."""
     import torch
-    for mc in (9, 64):
+    for mc in (9, 64, 100, 128):
         b = w().mixed(500, seed=300 + mc, max_chunks=mc, pow2=False)
         o_orders, _ = oracle.plan_batch(b, threads=8)
         o_t, o_qo, o_busy = oracle.simulate_batch(b, o_orders, threads=8)
@@ -211,7 +217,7 @@ def test_workspace_is_only_needed_beyond_64_chunks(gpu, oracle):
         assert np.array_equal(widen_queue(qo), o_qo)
         assert_close("busy", busy.cpu().numpy(), o_busy)
         assert_close("sweep", sw.cpu().numpy(), oracle.sweep(b, thr.cpu().numpy(), 6, threads=8))
-    b = w().mixed(400, seed=365, max_chunks=100, pow2=False)
+    b = w().mixed(400, seed=365, max_chunks=200, pow2=False)
     pow2 = np.array([all((int(p) & (int(p) - 1)) == 0 for p in b.npus[:b.ndims[i], i])
                      for i in range(b.n)])
     o_orders, _ = oracle.plan_batch(b, threads=8)
@@ -222,7 +228,7 @@ def test_workspace_is_only_needed_beyond_64_chunks(gpu, oracle):
     torch.cuda.synchronize()
     t = t.cpu().numpy()
     assert 0 < pow2.sum() < b.n
-    assert np.isnan(t[~pow2]).all() and (qo.cpu().numpy()[~pow2] == 0xFF).all()
+    assert np.isnan(t[~pow2]).all() and (qo.cpu().numpy()[~pow2] == 0xFFFF).all()
     assert_close("t_done of the LDS-path scenarios", t[pow2], o_t[pow2])
 
 
