@@ -172,8 +172,7 @@ int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
  *     LDS without a workspace; beyond 64 chunks the generic path, which takes
  *     what no LDS path can (beyond 128 chunks: every NPU count that is not a
  *     power of two), keeps its per-chunk state in the workspace;
- *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace
- *     (staggered release times: on the generic path, in the workspace too).
+ *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace.
  * For themis_sweep pass n * n_thr * n_pol as n and max_coll = 0.
  * Passing a smaller or NULL workspace is allowed: every scenario that would
  * have needed it then comes back as NaN / all-ones, like an invalid one (the

@@ -387,7 +387,7 @@ simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 // themis_simulate_batch for traces (several collectives sharing the queues):
 // the ranked-list path of themis_trace.hpp, else the generic path.
 // ---------------------------------------------------------------------------
-template <bool kLdsBitmaps>
+template <bool kLdsBitmaps, bool kReleases>
 __global__ void __launch_bounds__(kBlock)
 simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                       double* __restrict__ t_done, void* __restrict__ queue_order,
@@ -422,14 +422,18 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     TraceRegion rg;
     rg.base = trace_area + (size_t)i * tl.bytes;
     rg.t = tl;
-    // every collective must be in the range where halvings are exact, and
-    // released at t = 0
+    // every collective must be in the range where halvings are exact
+    bool has_release = false;
     for (uint32_t q = 0; q < Q; ++q) {
       const double chunk = collective_size(b, tv, i, q) / (double)s.C;
-      fast = fast && fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs0) &&
-             collective_release(b, tv, i, q) == 0.0;
+      fast = fast && fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs0);
       epack = fs0.epack;
       rg.CH(q) = fs0.base;  // resident size at mask 0
+      if (kReleases) {
+        const double release = collective_release(b, tv, i, q);
+        rg.REL(q) = release;
+        has_release = has_release || release > 0.0;
+      }
     }
     bool codes_ok = true;
     if (fast) {
@@ -444,7 +448,8 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
       double T, z[kMaxDims];
       uint32_t ex[kMaxDims];
-      if (simulate_trace_fast<kLdsBitmaps>(s, Q, epack, fs0.state0, fs0.rs_only, scf, rg, lds, out, T, z, ex)) {
+      if (simulate_trace_fast<kLdsBitmaps, kReleases>(s, Q, epack, fs0.state0, fs0.rs_only, scf,
+                                                      has_release, rg, lds, out, T, z, ex)) {
         t_done[i] = T;
         if (busy) {
 #pragma unroll
@@ -976,8 +981,10 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                             workspace_bytes_given >= generic + (size_t)batch->n * tl.bytes;
     uint8_t* trace_area = have_trace ? (uint8_t*)workspace + generic : nullptr;
     // few wavefronts (no more than CUs): the bitmap leaves move into the LDS nothing else would use
-    auto trace_kernel = blocks_for(batch->n) <= compute_units() ? simulate_trace_kernel<true>
-                                                                 : simulate_trace_kernel<false>;
+    const bool lds_bitmaps = blocks_for(batch->n) <= compute_units();
+    const bool releases = batch->release_time != nullptr;
+    auto trace_kernel = lds_bitmaps ? (releases ? simulate_trace_kernel<true, true> : simulate_trace_kernel<true, false>)
+                                    : (releases ? simulate_trace_kernel<false, true> : simulate_trace_kernel<false, false>);
     hipLaunchKernelGGL(trace_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
                        busy, w, have_ws, trace_area, tl);

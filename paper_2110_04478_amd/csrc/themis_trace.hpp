@@ -12,8 +12,10 @@
 // chunk-stage event then costs a bounded number of memory operations instead
 // of a scan over all waiting chunks.
 //
-// Covered: power-of-two NPU counts, up to kTraceMaxColl collectives, all
-// released at t = 0.  Everything else stays on the generic path.
+// Covered: power-of-two NPU counts, up to kTraceMaxColl collectives, any
+// release times (a release that falls on the very instant of a completion is
+// left to the generic path, which orders the arrivals of both kinds by chunk
+// id).  Everything else stays on the generic path.
 #pragma once
 
 #include "themis_fast.hpp"
@@ -31,7 +33,7 @@ struct TraceLayout {
   uint32_t G;   // chunk slots (max_chunks * max_coll)
   uint32_t Q;   // collectives the region is sized for
   uint32_t R;   // ranks per dimension = Q * 16
-  uint32_t off_ht, off_bm, off_col, off_sz, off_sq, off_sq2;
+  uint32_t off_ht, off_bm, off_col, off_sz, off_sq, off_sq2, off_rq;
   uint32_t bytes;  // multiple of 16; 0 if the batch cannot use this path
 };
 
@@ -45,11 +47,12 @@ __host__ __device__ inline TraceLayout trace_layout(uint32_t max_chunks, uint32_
   t.off_ht = o;  o += 4u * t.R * 4u;       // head | tail << 16 per (dimension, rank)
   t.off_bm = o;  o += 4u * kTraceLeafWords * 4u;   // bitmap leaves (when they are not in LDS)
   // one 64-byte record per collective: the size rank of each of the 16 masks
-  // (u16, one 32-byte row) and the chunk bytes (f64)
+  // (u16, one 32-byte row), the chunk bytes and the release time (f64 each)
   t.off_col = (o + 63u) & ~63u; o = t.off_col + t.Q * kTraceCollBytes;
   t.off_sz = o;  o += t.R * 8u;            // resident bytes of every size rank (f64)
   t.off_sq = o;  o += ((t.Q + 1u) & ~1u) * 2u;   // collectives sorted by chunk size
   t.off_sq2 = o; o += ((t.Q + 1u) & ~1u) * 2u;   // the merge sort's second buffer
+  t.off_rq = o;  o += ((t.Q + 1u) & ~1u) * 2u;   // collectives sorted by release time
   t.bytes = (o + 63u) & ~63u;
   return t;
 }
@@ -84,9 +87,13 @@ struct TraceRegion {
   __device__ __forceinline__ uint16_t& SQ(uint32_t j) const {
     return ((uint16_t*)(base + t.off_sq))[j < t.Q ? j : t.Q - 1u];
   }
-  // buffer 0 is SQ, buffer 1 the merge sort's spare
+  // buffer 0 is SQ, buffer 1 the merge sort's spare, buffer 2 the release order
   __device__ __forceinline__ uint16_t& SQbuf(uint32_t which, uint32_t j) const {
-    return ((uint16_t*)(base + ((which & 1u) ? t.off_sq2 : t.off_sq)))[j < t.Q ? j : t.Q - 1u];
+    const uint32_t off = which == 0u ? t.off_sq : which == 1u ? t.off_sq2 : t.off_rq;
+    return ((uint16_t*)(base + off))[j < t.Q ? j : t.Q - 1u];
+  }
+  __device__ __forceinline__ double& REL(uint32_t q) const {
+    return *(double*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes + 40u);
   }
 };
 
@@ -96,40 +103,47 @@ __device__ __forceinline__ uint32_t trace_word(uint32_t code, uint32_t state0) {
   return state0 | (code << 8) | (kNoChunk << 16);
 }
 
-// Ranks of all resident sizes: a merge of the 2^D sorted lists
-// { chunk_q * 2^-E(mask) : q in ascending chunk order }, one list per mask.
-// Returns the number of distinct ranks.  lds: 48 dwords of this lane.
-__device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, uint32_t D,
-                                             uint32_t epack, const LaneLds& lds) {
-  // collectives in ascending (chunk bytes, index) order: a bottom-up merge sort
-  // of their indices (every step is a round trip to memory, so the number of
-  // steps matters: Q log Q instead of the Q^2 / 4 of an insertion sort).  Runs
-  // of `width` sorted indices are merged from buffer `src` into the other one,
-  // the left run winning ties, so equal sizes stay in index order.
-  for (uint32_t a = 0; a < Q; ++a) rg.SQbuf(0u, a) = (uint16_t)a;
-  uint32_t src = 0u;
+// Collective indices in ascending (key, index) order into buffer `dst` (0 or
+// 2; buffer 1 is the spare): a bottom-up merge sort (every step is a round
+// trip to memory, so the number of steps matters: Q log Q instead of the
+// Q^2 / 4 of an insertion sort).  Runs of `width` sorted indices are merged
+// from one buffer into the other, the left run winning ties, so equal keys
+// stay in index order.
+template <typename KeyOf>
+__device__ inline void trace_sort_collectives(const TraceRegion& rg, uint32_t Q, uint32_t dst,
+                                              KeyOf key_of) {
+  for (uint32_t a = 0; a < Q; ++a) rg.SQbuf(dst, a) = (uint16_t)a;
+  uint32_t src = dst, other = 1u;
   for (uint32_t width = 1u; width < Q; width *= 2u) {
     for (uint32_t lo = 0u; lo < Q; lo += 2u * width) {
       const uint32_t mid = min(lo + width, Q), hi = min(lo + 2u * width, Q);
       uint32_t a = lo, b = mid;
       uint32_t ia = rg.SQbuf(src, a), ib = b < hi ? (uint32_t)rg.SQbuf(src, b) : 0u;
-      double ka = rg.CH(ia), kb = b < hi ? rg.CH(ib) : inf64();
+      double ka = key_of(ia), kb = b < hi ? key_of(ib) : inf64();
       for (uint32_t o = lo; o < hi; ++o) {
         const bool left = a < mid && (b >= hi || !(ka > kb));
-        rg.SQbuf(src ^ 1u, o) = (uint16_t)(left ? ia : ib);
+        rg.SQbuf(other, o) = (uint16_t)(left ? ia : ib);
         if (left) {
           ++a;
-          if (a < mid) { ia = rg.SQbuf(src, a); ka = rg.CH(ia); }
+          if (a < mid) { ia = rg.SQbuf(src, a); ka = key_of(ia); }
         } else {
           ++b;
-          if (b < hi) { ib = rg.SQbuf(src, b); kb = rg.CH(ib); }
+          if (b < hi) { ib = rg.SQbuf(src, b); kb = key_of(ib); }
         }
       }
     }
-    src ^= 1u;
+    const uint32_t t = src; src = other; other = t;
   }
-  if (src != 0u)
-    for (uint32_t a = 0; a < Q; ++a) rg.SQbuf(0u, a) = rg.SQbuf(1u, a);
+  if (src != dst)
+    for (uint32_t a = 0; a < Q; ++a) rg.SQbuf(dst, a) = rg.SQbuf(src, a);
+}
+
+// Ranks of all resident sizes: a merge of the 2^D sorted lists
+// { chunk_q * 2^-E(mask) : q in ascending chunk order }, one list per mask.
+// Returns the number of distinct ranks.  lds: 48 dwords of this lane.
+__device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, uint32_t D,
+                                             uint32_t epack, const LaneLds& lds) {
+  trace_sort_collectives(rg, Q, 0u, [&](uint32_t q) { return (double)rg.CH(q); });
   // merge heads in LDS: value (dwords 2m, 2m+1) and position (dword 32 + m)
   const uint32_t nm = 1u << D;
   const double first = rg.CH(rg.SQ(0));
@@ -173,14 +187,19 @@ constexpr uint32_t kTraceLdsWords = 48;
 constexpr uint32_t kTraceLdsWordsBitmaps = 16 + 4 * kTraceLeafWords;
 
 // Runs the simulation of one trace.  The region must hold CH[q] (resident
-// bytes at mask 0 of a chunk of collective q) and W[g] = trace_word(stored
-// code, state0) for g = q*C + i; state0 / rs_only as in FastScenario.
+// bytes at mask 0 of a chunk of collective q), REL[q] (its release time; read
+// only if has_release) and W[g] = trace_word(stored code, state0) for
+// g = q*C + i; state0 / rs_only as in FastScenario.
 // Returns false if time failed to advance somewhere (generic path decides).
+// kReleases: the batch carries release times (has_release: this scenario has
+// one that is not zero); without them the loop is compiled without the step
+// that looks for the next release.
 // kLdsBitmaps: the bitmap leaves live in LDS (kTraceLdsWordsBitmaps dwords per
 // lane) instead of the region; the summary words always do.
-template <bool kLdsBitmaps>
+template <bool kLdsBitmaps, bool kReleases>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
                                            uint32_t state0, bool rs_only, bool scf,
+                                           bool has_release,
                                            const TraceRegion& rg, const LaneLds& lds,
                                            const SimOut& out, double& t_done,
                                            double (&busy)[kMaxDims],
@@ -290,15 +309,38 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     return h;
   };
 
-  // a6: every chunk waits at the dimension of its first stage (initial mask)
-  {
+  // a6: the chunks of a collective join the queues of their first dimensions
+  // (initial mask) when it is released, collectives in (release time, index)
+  // order, chunks in id order
+  if (kReleases && has_release)
+    trace_sort_collectives(rg, Q, 2u, [&](uint32_t q) { return (double)rg.REL(q); });
+  uint32_t rel_next = 0;   // position in that order of the next collective to release
+  double rel_time = 0.0;   // its release time, +inf when all are out
+  double now = 0.0;
+  auto release_due = [&]() {
+    const uint32_t mask0 = state0 & 15u, phase0 = state0 >> 4;
+    const uint32_t pos0 = 2u * ((uint32_t)__builtin_popcount(mask0) - phase0);
+    while (rel_time <= now) {
+      const uint32_t q = has_release ? (uint32_t)rg.SQbuf(2u, rel_next) : rel_next;
+      for (uint32_t c = 0; c < C; ++c) {
+        const uint32_t g = q * C + c;
+        push((rg.W(g) >> (8u + pos0)) & 3u, rank_of(g, mask0), g, false, 0u);
+      }
+      ++rel_next;
+      rel_time = rel_next >= Q ? kInf : has_release ? (double)rg.REL(rg.SQbuf(2u, rel_next)) : 0.0;
+    }
+  };
+  if (kReleases) {
+    if (has_release) rel_time = Q ? (double)rg.REL(rg.SQbuf(2u, 0u)) : kInf;
+    if (Q == 0u) rel_time = kInf;
+    release_due();
+  } else {
     const uint32_t mask0 = state0 & 15u, phase0 = state0 >> 4;
     const uint32_t pos0 = 2u * ((uint32_t)__builtin_popcount(mask0) - phase0);
     for (uint32_t g = 0; g < G; ++g)
       push((rg.W(g) >> (8u + pos0)) & 3u, rank_of(g, mask0), g, false, 0u);
   }
 
-  double now = 0.0;
   // One pass starts at most one stage and, once no idle dimension has chunks
   // waiting, advances the clock (as in simulate_fast: a lane with two stages to
   // start at one instant takes two passes, the other lanes of the wavefront go
@@ -309,7 +351,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     for (uint32_t kk = 0; kk < 4u; ++kk) need |= (f[kk] == kInf && waiting[kk] != 0u) ? (1u << kk) : 0u;
     return need;
   };
-  const uint64_t max_steps = (uint64_t)4u * D * G + 16u;
+  const uint64_t max_steps = (uint64_t)4u * D * G + Q + 16u;
   for (uint64_t step = 0; step <= max_steps; ++step) {
     // a7: an idle dimension with waiting chunks starts its first one
     if (const uint32_t need = idle_with_work()) {
@@ -366,9 +408,20 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     if (stalled) break;
     if (idle_with_work() != 0u) continue;  // all stages of an instant start before the clock moves
 
-    // a8: advance to the earliest completion
+    // a8: advance to the earliest completion, or to the next release if that
+    // comes first
     const double next = min_f64(min_f64(f[0], f[1]), min_f64(f[2], f[3]));
-    if (!(next < kInf)) break;
+    if (!kReleases) {
+      if (!(next < kInf)) break;
+    } else if (rel_time <= next) {
+      if (!(rel_time < kInf)) break;  // nothing running, nothing left to release
+      // chunks arriving at one instant from a release and from a completion
+      // would have to be merged by id: the generic path does that
+      if (rel_time == next) { stalled = true; break; }
+      now = rel_time;
+      release_due();
+      continue;
+    }
     now = next;
     uint32_t done = 0;
 #pragma unroll

@@ -376,6 +376,42 @@ def test_traces_ranked_list_path(gpu, oracle):
     check_batch(gpu, oracle, b, threads=16)
 
 
+def test_traces_with_staggered_releases(gpu, oracle):
+    """Collectives released at different times (gradients of a back-propagation
+    pass) on the ranked-list path: releases before, between and after the
+    completions, several collectives per release instant, idle gaps, and a
+    release that falls exactly on a completion (arrivals of both kinds at one
+    instant are ordered by chunk id)."""
+    rng = np.random.default_rng(77)
+    # release instants on a coarse grid: many collectives share one
+    b = _add_trace(w().mixed(300, seed=81, max_chunks=10), rng, 12, pow2_sizes=True)
+    b.release_time = np.ascontiguousarray(rng.integers(0, 5, b.coll_size.shape) * 2e-4)
+    check_batch(gpu, oracle, b)
+    # continuous release times, long gaps (the queues drain in between), all three collective types
+    b = _with_collective_types(_add_trace(w().mixed(300, seed=82, max_chunks=8), rng, 25, pow2_sizes=False), 83)
+    b.release_time = np.ascontiguousarray(rng.uniform(0, 1, b.coll_size.shape) ** 4 * 5e-2)
+    check_batch(gpu, oracle, b)
+    # nothing released at t = 0, fixed delays
+    b = _with_fixed_delay(w().config5(n=70, n_coll=9), 84)
+    b.release_time = np.ascontiguousarray(rng.uniform(1e-5, 3e-3, b.coll_size.shape))
+    b.intra_policy[::3] = 0
+    check_batch(gpu, oracle, b)
+    # exact coincidence: one dimension of two NPUs at 2^30 B/s, chunks of 2^20 bytes:
+    # every stage takes 2^-11 s, and the second collective is released at 3 * 2^-11 s
+    b = _add_trace(w().mixed(64, seed=85, max_chunks=4), rng, 3, pow2_sizes=True)
+    b.release_time = np.zeros_like(b.coll_size)
+    for i in range(0, 64, 2):
+        b.ndims[i] = 1
+        b.npus[0, i] = 2
+        b.bw[0, i] = 2.0 ** 30
+        b.chunks[i] = 4
+        b.n_coll[i] = 3
+        b.coll_size[:, i] = 4 * 2.0 ** 20
+        b.release_time[:, i] = [0.0, 3 * 2.0 ** -11, 5 * 2.0 ** -11]
+    t = check_batch(gpu, oracle, b)
+    assert np.isfinite(t).all()
+
+
 def test_trace_with_generic_only_workspace(gpu, oracle):
     """A workspace that only covers the generic area still gives exact results."""
     import torch
