@@ -225,17 +225,19 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     for (uint32_t l = 0; l < kTraceSumWords; ++l) SUM(k, l) = 0u;
   }
 
-  double f[kMaxDims] = {kInf, kInf, kInf, kInf};
-  double z[kMaxDims] = {0.0, 0.0, 0.0, 0.0};
-  uint32_t serving[kMaxDims] = {0u, 0u, 0u, 0u};
-  // what the completion of the chunk a dimension serves will do, worked out at
-  // dispatch so that the completion itself reads nothing but its target list:
-  // the chunk's next word, its next dimension (4 = finished) and size rank there
-  uint32_t next_word[kMaxDims] = {0u, 0u, 0u, 0u};
-  uint32_t next_dim[kMaxDims] = {4u, 4u, 4u, 4u};
-  uint32_t next_rank[kMaxDims] = {0u, 0u, 0u, 0u};
-  uint32_t executed[kMaxDims] = {0u, 0u, 0u, 0u};
-  uint32_t waiting[kMaxDims] = {0u, 0u, 0u, 0u};
+  double f0 = kInf, f1 = kInf, f2 = kInf, f3 = kInf;  // finish time, +inf = idle
+  double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
+  // Per dimension, the chunk it serves (sv: chunk << 2 | dimension) and what
+  // that chunk's completion will do, worked out at dispatch so that the
+  // completion itself reads nothing but its target list (nx: the chunk's next
+  // word without its link in bits 0-15, the next dimension in bits 16-18
+  // (4 = finished) and the size rank there from bit 19)
+  uint32_t sv0 = 0u, sv1 = 0u, sv2 = 0u, sv3 = 0u;
+  uint32_t nx0 = 0u, nx1 = 0u, nx2 = 0u, nx3 = 0u;
+  uint32_t e0 = 0u, e1 = 0u, e2 = 0u, e3 = 0u;  // operations started per dimension
+  // tops: bit 4 * k + sw says that summary word sw of dimension k is not zero;
+  // work: bit k says that dimension k has chunks waiting; idle: serves nothing
+  uint32_t tops = 0u, work = 0u, idle = 15u;
   bool stalled = false;
 
   // g / C for g < 2^23 (chunk ids stay below 2^16) without a division:
@@ -263,8 +265,8 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       BM(k, leaf) = lw | bit;
       SUM(k, leaf >> 5) |= 1u << (leaf & 31u);
     }
-#pragma unroll
-    for (uint32_t kk = 0; kk < 4u; ++kk) waiting[kk] += (kk == k) ? 1u : 0u;
+    tops |= 1u << (4u * (k & 3u) + ((leaf >> 5) & 3u));
+    work |= 1u << (k & 3u);
   };
   // first chunk of the lowest non-empty rank (smallest resident size); w
   // receives its chunk word, size the resident bytes of a chunk of that rank
@@ -275,11 +277,10 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   // store (at = 4 * R: nothing to store, the list is empty now)
   auto pop = [&](uint32_t k, uint32_t& w, double& size, uint4& row_lo, uint4& row_hi,
                  uint32_t& new_entry, uint32_t& at) -> uint32_t {
-    uint32_t leaf = 0;
-    for (uint32_t sw = 0; sw < kTraceSumWords; ++sw) {
-      const uint32_t v = SUM(k, sw);
-      if (v) { leaf = sw * 32u + (uint32_t)__builtin_ctz(v); break; }
-    }
+    // work bit k is set: one of k's summary words is not zero
+    const uint32_t sw = (uint32_t)__builtin_ctz(((tops >> (4u * k)) & 15u) | 16u) & 3u;
+    const uint32_t sumw = SUM(k, sw);
+    const uint32_t leaf = sw * 32u + (sumw ? (uint32_t)__builtin_ctz(sumw) : 0u);
     const uint32_t lw = BM(k, leaf);
     const uint32_t r = leaf * 32u + (lw ? (uint32_t)__builtin_ctz(lw) : 0u);
     const uint32_t ht = rg.HT(k, r);
@@ -299,13 +300,18 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     if (h == tl) {
       const uint32_t nlw = lw & ~(1u << (r & 31u));
       BM(k, leaf) = nlw;
-      if (!nlw) SUM(k, leaf >> 5) &= ~(1u << (leaf & 31u));
+      if (!nlw) {
+        const uint32_t rest = sumw & ~(1u << (leaf & 31u));
+        SUM(k, sw) = rest;
+        if (!rest) {
+          tops &= ~(1u << (4u * k + sw));
+          if (((tops >> (4u * k)) & 15u) == 0u) work &= ~(1u << k);
+        }
+      }
     } else {
       new_entry = (w >> 16) | (tl << 16);
       at = (k & 3u) * rg.t.R + (r < rg.t.R ? r : rg.t.R - 1u);  // clamped as in HT()
     }
-#pragma unroll
-    for (uint32_t kk = 0; kk < 4u; ++kk) waiting[kk] -= (kk == k) ? 1u : 0u;
     return h;
   };
 
@@ -345,16 +351,10 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   // waiting, advances the clock (as in simulate_fast: a lane with two stages to
   // start at one instant takes two passes, the other lanes of the wavefront go
   // on meanwhile).
-  auto idle_with_work = [&]() -> uint32_t {
-    uint32_t need = 0;
-#pragma unroll
-    for (uint32_t kk = 0; kk < 4u; ++kk) need |= (f[kk] == kInf && waiting[kk] != 0u) ? (1u << kk) : 0u;
-    return need;
-  };
   const uint64_t max_steps = (uint64_t)4u * D * G + Q + 16u;
   for (uint64_t step = 0; step <= max_steps; ++step) {
     // a7: an idle dimension with waiting chunks starts its first one
-    if (const uint32_t need = idle_with_work()) {
+    if (const uint32_t need = idle & work) {
       const uint32_t k = (uint32_t)__builtin_ctz(need);
       uint32_t w;
       double size;
@@ -387,30 +387,27 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
                                    sel4((int)(mask2 >> 3), row_lo.w, row_hi.w, 0u, 0u));
         rk = (pair >> (16u * (mask2 & 1u))) & 0xffffu;
       }
-      const uint32_t nw = mask2 | (phase2 << 4) | (code << 8) | (kNoChunk << 16);
-      uint32_t pos = 0;
-#pragma unroll
-      for (uint32_t kk = 0; kk < 4u; ++kk) {
-        if (kk == k) {
-          f[kk] = fin;
-          z[kk] = z[kk] + t;
-          serving[kk] = h;
-          next_word[kk] = nw;
-          next_dim[kk] = kn;
-          next_rank[kk] = rk;
-          pos = executed[kk];
-          executed[kk] = pos + 1u;
-        }
-      }
+      const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
+      f0 = k0 ? fin : f0; f1 = k1 ? fin : f1; f2 = k2 ? fin : f2; f3 = k3 ? fin : f3;
+      // z_j + t * [k == j]: one rounding of the exact sum, the same as z_j + t
+      z0 = __builtin_fma(t, k0 ? 1.0 : 0.0, z0); z1 = __builtin_fma(t, k1 ? 1.0 : 0.0, z1);
+      z2 = __builtin_fma(t, k2 ? 1.0 : 0.0, z2); z3 = __builtin_fma(t, k3 ? 1.0 : 0.0, z3);
+      const uint32_t sv = (h << 2) | k;
+      const uint32_t nx = mask2 | (phase2 << 4) | (code << 8) | (kn << 16) | (rk << 19);
+      sv0 = k0 ? sv : sv0; sv1 = k1 ? sv : sv1; sv2 = k2 ? sv : sv2; sv3 = k3 ? sv : sv3;
+      nx0 = k0 ? nx : nx0; nx1 = k1 ? nx : nx1; nx2 = k2 ? nx : nx2; nx3 = k3 ? nx : nx3;
+      idle &= ~(1u << k);
+      const uint32_t pos = sel4((int)k, e0, e1, e2, e3);
+      e0 += k0 ? 1u : 0u; e1 += k1 ? 1u : 0u; e2 += k2 ? 1u : 0u; e3 += k3 ? 1u : 0u;
       if (out.queue_order && pos < 2u * out.slots) put_entry(out, (int)k, pos, (h << 1) | phase);
       if (entry_at < 4u * rg.t.R) ((uint32_t*)(rg.base + rg.t.off_ht))[entry_at] = new_entry;
     }
     if (stalled) break;
-    if (idle_with_work() != 0u) continue;  // all stages of an instant start before the clock moves
+    if ((idle & work) != 0u) continue;  // all stages of an instant start before the clock moves
 
     // a8: advance to the earliest completion, or to the next release if that
     // comes first
-    const double next = min_f64(min_f64(f[0], f[1]), min_f64(f[2], f[3]));
+    const double next = min_f64(min_f64(f0, f1), min_f64(f2, f3));
     if (!kReleases) {
       if (!(next < kInf)) break;
     } else if (rel_time <= next) {
@@ -423,30 +420,31 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       continue;
     }
     now = next;
-    uint32_t done = 0;
-#pragma unroll
-    for (uint32_t kk = 0; kk < 4u; ++kk) {
-      if (f[kk] == now) { done |= 1u << kk; f[kk] = kInf; }
-    }
-    // deliver all completions of this instant, lowest chunk id first
-    do {
-      uint32_t k = 0, best = 0xffffffffu;
-#pragma unroll
-      for (uint32_t kk = 0; kk < 4u; ++kk)
-        if ((done >> kk & 1u) && serving[kk] < best) { best = serving[kk]; k = kk; }
+    const bool d0 = f0 == now, d1 = f1 == now, d2 = f2 == now, d3 = f3 == now;
+    uint32_t done = (d0 ? 1u : 0u) | (d1 ? 2u : 0u) | (d2 ? 4u : 0u) | (d3 ? 8u : 0u);
+    f0 = d0 ? kInf : f0; f1 = d1 ? kInf : f1; f2 = d2 ? kInf : f2; f3 = d3 ? kInf : f3;
+    idle |= done;
+    // deliver all completions of this instant, lowest chunk id first: the
+    // smallest chunk << 2 | dimension among the dimensions that completed
+    uint32_t g0 = d0 ? sv0 : ~0u, g1 = d1 ? sv1 : ~0u, g2 = d2 ? sv2 : ~0u, g3 = d3 ? sv3 : ~0u;
+    for (;;) {
+      const uint32_t key = min(min(g0, g1), min(g2, g3));
+      const uint32_t k = key & 3u;
+      const uint32_t nx = sel4((int)k, nx0, nx1, nx2, nx3);
+      const uint32_t kn = (nx >> 16) & 7u;
+      if (kn < 4u) push(kn, nx >> 19, key >> 2, true, (nx & 0xffffu) | (kNoChunk << 16));
       done &= ~(1u << k);
-      const uint32_t g = best;
-      uint32_t nw = 0, kn = 4u, rk = 0;
-#pragma unroll
-      for (uint32_t kk = 0; kk < 4u; ++kk)
-        if (kk == k) { nw = next_word[kk]; kn = next_dim[kk]; rk = next_rank[kk]; }
-      if (kn < 4u) push(kn, rk, g, true, nw);
-    } while (done);
+      if (done == 0u) break;
+      g0 = g0 == key ? ~0u : g0; g1 = g1 == key ? ~0u : g1;
+      g2 = g2 == key ? ~0u : g2; g3 = g3 == key ? ~0u : g3;
+    }
   }
 
   t_done = now;
 #pragma unroll
-  for (uint32_t kk = 0; kk < 4u; ++kk) { busy[kk] = z[kk]; executed_out[kk] = executed[kk]; }
+  for (uint32_t kk = 0; kk < 4u; ++kk) { busy[kk] = 0.0; executed_out[kk] = 0u; }
+  busy[0] = z0; busy[1] = z1; busy[2] = z2; busy[3] = z3;
+  executed_out[0] = e0; executed_out[1] = e1; executed_out[2] = e2; executed_out[3] = e3;
   return !stalled;
 }
 
