@@ -387,7 +387,9 @@ simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 // themis_simulate_batch for traces (several collectives sharing the queues):
 // the ranked-list path of themis_trace.hpp, else the generic path.
 // ---------------------------------------------------------------------------
-template <bool kLdsBitmaps, bool kReleases>
+// kExtras: the batch carries release times or fixed delays (one switch for
+// both keeps the number of variants down).
+template <bool kLdsBitmaps, bool kExtras>
 __global__ void __launch_bounds__(kBlock)
 simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
                       double* __restrict__ t_done, void* __restrict__ queue_order,
@@ -429,7 +431,7 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       fast = fast && fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs0);
       epack = fs0.epack;
       rg.CH(q) = fs0.base;  // resident size at mask 0
-      if (kReleases) {
+      if (kExtras) {
         const double release = collective_release(b, tv, i, q);
         rg.REL(q) = release;
         has_release = has_release || release > 0.0;
@@ -448,7 +450,7 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
       double T, z[kMaxDims];
       uint32_t ex[kMaxDims];
-      if (simulate_trace_fast<kLdsBitmaps, kReleases>(s, Q, epack, fs0.state0, fs0.rs_only, scf,
+      if (simulate_trace_fast<kLdsBitmaps, kExtras, kExtras>(s, Q, epack, fs0.state0, fs0.rs_only, scf,
                                                       has_release, rg, lds, out, T, z, ex)) {
         t_done[i] = T;
         if (busy) {
@@ -982,9 +984,9 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
     uint8_t* trace_area = have_trace ? (uint8_t*)workspace + generic : nullptr;
     // few wavefronts (no more than CUs): the bitmap leaves move into the LDS nothing else would use
     const bool lds_bitmaps = blocks_for(batch->n) <= compute_units();
-    const bool releases = batch->release_time != nullptr;
-    auto trace_kernel = lds_bitmaps ? (releases ? simulate_trace_kernel<true, true> : simulate_trace_kernel<true, false>)
-                                    : (releases ? simulate_trace_kernel<false, true> : simulate_trace_kernel<false, false>);
+    const bool extras = batch->release_time != nullptr || batch->fixed_delay != nullptr;
+    auto trace_kernel = lds_bitmaps ? (extras ? simulate_trace_kernel<true, true> : simulate_trace_kernel<true, false>)
+                                    : (extras ? simulate_trace_kernel<false, true> : simulate_trace_kernel<false, false>);
     hipLaunchKernelGGL(trace_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
                        busy, w, have_ws, trace_area, tl);

@@ -193,10 +193,10 @@ constexpr uint32_t kTraceLdsWordsBitmaps = 16 + 4 * kTraceLeafWords;
 // Returns false if time failed to advance somewhere (generic path decides).
 // kReleases: the batch carries release times (has_release: this scenario has
 // one that is not zero); without them the loop is compiled without the step
-// that looks for the next release.
+// that looks for the next release.  kFix: the batch carries fixed delays.
 // kLdsBitmaps: the bitmap leaves live in LDS (kTraceLdsWordsBitmaps dwords per
 // lane) instead of the region; the summary words always do.
-template <bool kLdsBitmaps, bool kReleases>
+template <bool kLdsBitmaps, bool kReleases, bool kFix>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
                                            uint32_t state0, bool rs_only, bool scf,
                                            bool has_release,
@@ -366,7 +366,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       // bytes moved on k: the resident size before the chunk's Reduce-Scatter
       // on k, which an All-Gather on k finds 2^ek times smaller
       double t = scale_up(size, phase ? ek : 0u) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
-      if (s.has_fix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
+      if (kFix && s.has_fix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
       const double fin = now + t;
       // a stage that does not move the clock, or overflows it: generic path decides
       stalled |= !(fin > now && fin < kInf);

@@ -262,7 +262,7 @@ def config5(n: int = 16384, seed: int = SEED_BASE + 5, first: int = 0,
         intra_policy=_const(n, INTRA_SCF, np.uint8),
         threshold=_const(n, 1 / 16, np.float64),
         max_coll=n_coll, n_coll=_const(n, n_coll, np.uint32),
-        coll_size=sizes, release_time=np.zeros((n_coll, n)))
+        coll_size=sizes, release_time=None)
 
 
 def mixed(n: int, seed: int = SEED_BASE + 99, max_chunks: int = 64,
