@@ -63,37 +63,37 @@ struct TraceRegion {
   uint8_t* base;
   TraceLayout t;
   __device__ __forceinline__ uint32_t& W(uint32_t g) const {
-    return ((uint32_t*)base)[g < t.G ? g : t.G - 1u];
+    return ((uint32_t*)base)[min(g, t.G - 1u)];
   }
   __device__ __forceinline__ uint32_t& HT(uint32_t k, uint32_t r) const {
-    return ((uint32_t*)(base + t.off_ht))[(k & 3u) * t.R + (r < t.R ? r : t.R - 1u)];
+    return ((uint32_t*)(base + t.off_ht))[(k & 3u) * t.R + min(r, t.R - 1u)];
   }
   __device__ __forceinline__ uint32_t& BM(uint32_t k, uint32_t leaf) const {
     return ((uint32_t*)(base + t.off_bm))[(k & 3u) * kTraceLeafWords + (leaf & (kTraceLeafWords - 1u))];
   }
   __device__ __forceinline__ double& CH(uint32_t q) const {
-    return *(double*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes + 32u);
+    return *(double*)(base + t.off_col + min(q, t.Q - 1u) * kTraceCollBytes + 32u);
   }
   __device__ __forceinline__ uint16_t& SR(uint32_t q, uint32_t mask) const {
-    return ((uint16_t*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes))[mask & 15u];
+    return ((uint16_t*)(base + t.off_col + min(q, t.Q - 1u) * kTraceCollBytes))[mask & 15u];
   }
   // the 16 ranks of collective q as eight dwords
   __device__ __forceinline__ const uint4* SRrow(uint32_t q) const {
-    return (const uint4*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes);
+    return (const uint4*)(base + t.off_col + min(q, t.Q - 1u) * kTraceCollBytes);
   }
   __device__ __forceinline__ double& SZ(uint32_t r) const {
-    return ((double*)(base + t.off_sz))[r < t.R ? r : t.R - 1u];
+    return ((double*)(base + t.off_sz))[min(r, t.R - 1u)];
   }
   __device__ __forceinline__ uint16_t& SQ(uint32_t j) const {
-    return ((uint16_t*)(base + t.off_sq))[j < t.Q ? j : t.Q - 1u];
+    return ((uint16_t*)(base + t.off_sq))[min(j, t.Q - 1u)];
   }
   // buffer 0 is SQ, buffer 1 the merge sort's spare, buffer 2 the release order
   __device__ __forceinline__ uint16_t& SQbuf(uint32_t which, uint32_t j) const {
     const uint32_t off = which == 0u ? t.off_sq : which == 1u ? t.off_sq2 : t.off_rq;
-    return ((uint16_t*)(base + off))[j < t.Q ? j : t.Q - 1u];
+    return ((uint16_t*)(base + off))[min(j, t.Q - 1u)];
   }
   __device__ __forceinline__ double& REL(uint32_t q) const {
-    return *(double*)(base + t.off_col + (q < t.Q ? q : t.Q - 1u) * kTraceCollBytes + 40u);
+    return *(double*)(base + t.off_col + min(q, t.Q - 1u) * kTraceCollBytes + 40u);
   }
 };
 
@@ -280,9 +280,9 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     // work bit k is set: one of k's summary words is not zero
     const uint32_t sw = (uint32_t)__builtin_ctz(((tops >> (4u * k)) & 15u) | 16u) & 3u;
     const uint32_t sumw = SUM(k, sw);
-    const uint32_t leaf = sw * 32u + (sumw ? (uint32_t)__builtin_ctz(sumw) : 0u);
+    const uint32_t leaf = sw * 32u + ((uint32_t)__builtin_ctz(sumw | 0x80000000u));
     const uint32_t lw = BM(k, leaf);
-    const uint32_t r = leaf * 32u + (lw ? (uint32_t)__builtin_ctz(lw) : 0u);
+    const uint32_t r = leaf * 32u + ((uint32_t)__builtin_ctz(lw | 0x80000000u));
     const uint32_t ht = rg.HT(k, r);
     if (scf) size = rg.SZ(r);
     const uint32_t h = ht & 0xffffu, tl = ht >> 16;
@@ -310,7 +310,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       }
     } else {
       new_entry = (w >> 16) | (tl << 16);
-      at = (k & 3u) * rg.t.R + (r < rg.t.R ? r : rg.t.R - 1u);  // clamped as in HT()
+      at = (k & 3u) * rg.t.R + min(r, rg.t.R - 1u);  // clamped as in HT()
     }
     return h;
   };
