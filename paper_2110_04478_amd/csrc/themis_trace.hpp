@@ -240,10 +240,12 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   uint32_t tops = 0u, work = 0u, idle = 15u;
   bool stalled = false;
 
-  // g / C for g < 2^23 (chunk ids stay below 2^16) without a division:
-  // ceil(2^32 / C) fits 32 bits from C = 2 on
-  const uint32_t c_inv = (uint32_t)((0x100000000ull + C - 1u) / C);
-  auto coll_of = [&](uint32_t g) -> uint32_t { return C == 1u ? g : __umulhi(g, c_inv); };
+  // g / C for g < 2^23 (chunk ids stay below 2^16) without a division or a
+  // branch: the high half of g * ceil(2^32 / C), which fits 32 bits from C = 2
+  // on; for C = 1 the multiplier is 0 and g itself is added
+  const uint32_t c_inv = C == 1u ? 0u : (uint32_t)((0x100000000ull + C - 1u) / C);
+  const uint32_t c_one = C == 1u ? ~0u : 0u;
+  auto coll_of = [&](uint32_t g) -> uint32_t { return __umulhi(g, c_inv) + (g & c_one); };
   auto rank_of = [&](uint32_t g, uint32_t mask) -> uint32_t {
     return scf ? (uint32_t)rg.SR(coll_of(g), mask) : 0u;
   };
@@ -283,18 +285,17 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     const uint32_t leaf = sw * 32u + ((uint32_t)__builtin_ctz(sumw | 0x80000000u));
     const uint32_t lw = BM(k, leaf);
     const uint32_t r = leaf * 32u + ((uint32_t)__builtin_ctz(lw | 0x80000000u));
+    // (the size and rank tables are read whatever the policy: a load nobody
+    // uses costs less here than a branch around it)
     const uint32_t ht = rg.HT(k, r);
-    if (scf) size = rg.SZ(r);
+    size = rg.SZ(r);
     const uint32_t h = ht & 0xffffu, tl = ht >> 16;
     w = rg.W(h);
-    if (scf) {
-      const uint4* row = rg.SRrow(coll_of(h));
-      row_lo = row[0];
-      row_hi = row[1];
-    } else {
-      // one list per dimension: the size comes from the chunk's collective
-      size = scale_down(rg.CH(coll_of(h)), esum(epack, w & 15u));
-    }
+    const uint4* row = rg.SRrow(coll_of(h));
+    row_lo = row[0];
+    row_hi = row[1];
+    // FIFO, one list per dimension: the size comes from the chunk's collective
+    if (!scf) size = scale_down(rg.CH(coll_of(h)), esum(epack, w & 15u));
     at = 4u * rg.t.R;
     new_entry = 0u;
     if (h == tl) {
@@ -379,14 +380,10 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
       const uint32_t p = (uint32_t)__builtin_popcount(mask2) - phase2;
       const uint32_t kn = finished ? 4u : (code >> ((2u * p) & 31u)) & 3u;
-      uint32_t rk = 0u;
-      if (scf) {
-        const uint32_t pair = sel4((int)(mask2 >> 1), sel4((int)(mask2 >> 3), row_lo.x, row_hi.x, 0u, 0u),
-                                   sel4((int)(mask2 >> 3), row_lo.y, row_hi.y, 0u, 0u),
-                                   sel4((int)(mask2 >> 3), row_lo.z, row_hi.z, 0u, 0u),
-                                   sel4((int)(mask2 >> 3), row_lo.w, row_hi.w, 0u, 0u));
-        rk = (pair >> (16u * (mask2 & 1u))) & 0xffffu;
-      }
+      const bool upper = (mask2 & 8u) != 0u;
+      const uint32_t pair = sel4((int)(mask2 >> 1), upper ? row_hi.x : row_lo.x, upper ? row_hi.y : row_lo.y,
+                                 upper ? row_hi.z : row_lo.z, upper ? row_hi.w : row_lo.w);
+      const uint32_t rk = scf ? (pair >> (16u * (mask2 & 1u))) & 0xffffu : 0u;
       const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
       f0 = k0 ? fin : f0; f1 = k1 ? fin : f1; f2 = k2 ? fin : f2; f3 = k3 ? fin : f3;
       // z_j + t * [k == j]: one rounding of the exact sum, the same as z_j + t
