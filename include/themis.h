@@ -164,14 +164,13 @@ int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
  *   - single collectives with power-of-two NPU counts and sizes whose
  *     halvings stay in the normal binary64 range run entirely in registers
  *     and LDS and need no workspace;
- *   - the other single collectives need no workspace either while
- *     max_chunks <= 64 (NPU counts that are not powers of two: LDS paths on
- *     per-order tables; a slower generic path whose per-chunk state also sits
- *     in LDS remains behind them for the rest, e.g. extreme magnitudes);
- *   - up to 128 chunks NPU counts that are not powers of two still run in
- *     LDS without a workspace; beyond 64 chunks the generic path, which takes
- *     what no LDS path can (beyond 128 chunks: every NPU count that is not a
- *     power of two), keeps its per-chunk state in the workspace;
+ *   - single collectives with NPU counts that are not powers of two run in
+ *     LDS as well, on per-order tables, at every chunk count, and need no
+ *     workspace either;
+ *   - what no LDS path takes (e.g. stage times too short to move the clock,
+ *     times that leave the binary64 range on the way) goes to a slower generic
+ *     path, whose per-chunk state sits in LDS up to 64 chunks and in the
+ *     workspace beyond;
  *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace.
  * For themis_sweep pass n * n_thr * n_pol as n and max_coll = 0.
  * Passing a smaller or NULL workspace is allowed: every scenario that would

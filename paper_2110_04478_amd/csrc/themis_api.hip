@@ -321,11 +321,15 @@ simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 // for any number of them; what they cannot take stays marked for the generic
 // kernel.
 // kVariant: 0 tables for at most 8 order codes (64 chunks), 1 any number of
-// codes (64 chunks), 2 the same for up to 128 chunks.
+// codes (64 chunks), 2 the same for up to 128 chunks, 3 and 4 16-bit chunk
+// records for up to 256 and 512 chunks.
 template <int kVariant>
 struct TableVariant {
   using L = typename std::conditional<kVariant == 0, LayoutTable,
-            typename std::conditional<kVariant == 1, LayoutTableWide, LayoutTableWide128>::type>::type;
+            typename std::conditional<kVariant == 1, LayoutTableWide,
+            typename std::conditional<kVariant == 2, LayoutTableWide128,
+            typename std::conditional<kVariant == 3, LayoutTablePacked<256>,
+                                      LayoutTablePacked<512>>::type>::type>::type>::type;
 };
 
 template <int kQueueOrder, int kVariant>
@@ -360,7 +364,11 @@ simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
         ? (uint8_t*)queue_order + (size_t)i * rows_bytes : nullptr;
     fo.slots = b.max_chunks;
     FastResult r;
-    if constexpr (kWide) {
+    if constexpr (kVariant >= 3) {
+      DivModelT<LayoutTableWide> model(s, lds, chunk, scf);
+      table_setup_packed<L>(s, scf, lds, code_at, model);
+      r = simulate_table_packed<L, kQueueOrder, true>(s, model, lds, fo);
+    } else if constexpr (kWide) {
       DivModelT<L> model(s, lds, chunk, scf);
       table_setup_wide<L>(s, scf, lds, code_at, model);
       r = simulate_fast<L, kQueueOrder, true, true>(s, model, lds, fo);
@@ -622,7 +630,11 @@ sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;
     FastResult r;
-    if constexpr (kWide) {
+    if constexpr (kVariant >= 3) {
+      DivModelT<LayoutTableWide> model(s, lds, chunk, it.scf);
+      table_setup_packed<L>(s, it.scf, lds, code_at, model);
+      r = simulate_table_packed<L, kNoQueueOrder, false>(s, model, lds, fo);
+    } else if constexpr (kWide) {
       DivModelT<L> model(s, lds, chunk, it.scf);
       table_setup_wide<L>(s, it.scf, lds, code_at, model);
       r = simulate_fast<L, kNoQueueOrder, false, true>(s, model, lds, fo);
@@ -999,10 +1011,9 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
   // kernel: with its arrays in LDS up to 64 chunks, from the workspace beyond
   auto generic = cap <= 16u ? simulate_generic_kernel<16> : cap <= 64u ? simulate_generic_kernel<64>
                                                                        : simulate_generic_kernel<0>;
-  // up to 128 chunks follow-up kernels always come: the table kernels need no
-  // workspace, and the generic kernel without one only closes what they left
-  const unsigned long long call = (cap <= 128u || have_ws) ? next_call_number() : 0ull;
-  const bool hand_over = call != 0ull;
+  // follow-up kernels always come: the table kernels need no workspace, and
+  // beyond 64 chunks the generic kernel without one only closes what they left
+  const unsigned long long call = next_call_number();
   hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
                      call);
@@ -1024,11 +1035,17 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                                 : simulate_table_kernel<kBytes, 2>;
     hipLaunchKernelGGL(wide, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
+  } else {
+    auto packed = cap == 256u ? (mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 3>
+                                                       : simulate_table_kernel<kShorts, 3>)
+                              : (mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 4>
+                                                       : simulate_table_kernel<kShorts, 4>);
+    hipLaunchKernelGGL(packed, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
   }
-  if (hand_over)
-    hipLaunchKernelGGL(generic, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
-                       busy, have_ws ? w : Workspace{}, call);
+  hipLaunchKernelGGL(generic, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
+                     (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
+                     busy, have_ws ? w : Workspace{}, call);
   return launch_status();
 }
 
@@ -1058,8 +1075,7 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
                             : (fix ? sweep_kernel<LayoutPacked<512>, true> : sweep_kernel<LayoutPacked<512>, false>);
   auto generic = cap <= 16u ? sweep_generic_kernel<16> : cap <= 64u ? sweep_generic_kernel<64>
                                                                     : sweep_generic_kernel<0>;
-  const unsigned long long call = (cap <= 128u || have_ws) ? next_call_number() : 0ull;
-  const bool hand_over = call != 0ull;
+  const unsigned long long call = next_call_number();
   hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                      n_pol, t_done, call);
@@ -1074,11 +1090,15 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
     hipLaunchKernelGGL(sweep_table_kernel<2>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                        n_pol, t_done, call);
-  }
-  if (hand_over)
-    hipLaunchKernelGGL(generic, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
+  } else {
+    hipLaunchKernelGGL(cap == 256u ? sweep_table_kernel<3> : sweep_table_kernel<4>,
+                       dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
                        (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                       n_pol, t_done, have_ws ? w : Workspace{}, call);
+                       n_pol, t_done, call);
+  }
+  hipLaunchKernelGGL(generic, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
+                     (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
+                     n_pol, t_done, have_ws ? w : Workspace{}, call);
   return launch_status();
 }
 

@@ -372,4 +372,257 @@ __device__ inline void table_setup_wide(const Scenario& s, bool scf, const LaneL
   }
 }
 
+// ---------------------------------------------------------------------------
+// More than 128 chunks with NPU counts that are not powers of two: 16-bit
+// chunk records as in themis_packed.hpp, with the chunk's slot where that
+// file keeps the order (a slot stands for one order code, kept in a small
+// table), 64 classes per dimension as in the wide variant, and a stage time's
+// divisions redone at each dispatch.
+//   record: bits 0-8 next chunk of its list (its own id: the last one),
+//           bit 9 phase, bits 10-14 slot
+// Lane block: u16 record[kChunks], u16 head[256], u16 tail[256] (a tail entry
+// carries the upper bits of the tail chunk's record), u8 class[kSlots][8],
+// u8 code[kSlots].  One wavefront per CU.
+// ---------------------------------------------------------------------------
+template <uint32_t kChunks>
+struct LayoutTablePacked {
+  static constexpr uint32_t kCap = kChunks;
+  static_assert(kChunks <= 512 && kChunks % 2 == 0, "9-bit chunk ids, two records per dword");
+  static constexpr uint32_t kSlots = 24;
+  static constexpr uint32_t kHeadBase = kChunks / 2, kTailBase = kHeadBase + 128;
+  static constexpr uint32_t kClassBase = kTailBase + 128, kCodeBase = kClassBase + kSlots * 8u / 4u;
+  static constexpr uint32_t kLaneWords = kCodeBase + kSlots / 4u;  // 438 / 566
+  static constexpr uint32_t kIdMask = 0x1ffu;
+  using Ids = Pack4<uint64_t, 16>;
+  static __device__ __forceinline__ uint16_t* half(const LaneLds& l, uint32_t base, uint32_t i) {
+    return (uint16_t*)(l.base + ((base + (i >> 1)) << 8) + 2u * (i & 1u));
+  }
+  static __device__ __forceinline__ uint16_t* record(const LaneLds& l, uint32_t c) { return half(l, 0u, c); }
+  static __device__ __forceinline__ uint16_t* head(const LaneLds& l, uint32_t q) { return half(l, kHeadBase, q); }
+  static __device__ __forceinline__ uint16_t* tail(const LaneLds& l, uint32_t q) { return half(l, kTailBase, q); }
+  static __device__ __forceinline__ uint8_t* slot_code(const LaneLds& l, uint32_t sl) {
+    const uint32_t i = sl < kSlots ? sl : 0u;
+    return l.dword(kCodeBase + (i >> 2)) + (i & 3u);
+  }
+  static __device__ __forceinline__ uint8_t* size_class(const LaneLds& l, uint32_t sl, uint32_t stage) {
+    const uint32_t i = (sl < kSlots ? sl : 0u) * 8u + (stage & 7u);
+    return l.dword(kClassBase + (i >> 2)) + (i & 3u);
+  }
+};
+
+// Slots, records and class table for simulate_table_packed(); code_at as in
+// table_setup().  model: a DivModelT (its chunk-word members are not used).
+template <typename L, typename Model, typename CodeAt>
+__device__ inline void table_setup_packed(const Scenario& s, bool scf, const LaneLds& lds,
+                                          CodeAt code_at, Model& model) {
+  const uint32_t D = (uint32_t)s.D;
+  const uint32_t phase0 = (model.state0() >> 4) & 1u;
+  const uint32_t sizes = L::kHeadBase;  // scratch: two doubles per slot
+  uint32_t n = 0;
+  for (uint32_t c = 0; c < s.C; ++c) {
+    const uint32_t code = model.gather ? reverse_code(code_at(c), (int)D) : code_at(c);
+    uint32_t slot = n;
+    for (uint32_t j = 0; j < n; ++j)
+      if (*L::slot_code(lds, j) == code) slot = j;
+    if (slot == n) {
+      if (n < L::kSlots) { *L::slot_code(lds, n) = (uint8_t)code; ++n; }
+      else slot = 0;  // unreachable for checked codes
+    }
+    *L::record(lds, c) = (uint16_t)(c | (phase0 << 9) | (slot << 10));
+  }
+  double tmin = inf64();
+  for (uint32_t sl = 0; sl < n; ++sl)
+    for (uint32_t j = 0; j < D; ++j) tmin = min_f64(tmin, model.time_at(*L::slot_code(lds, sl), j));
+  model.tmin = tmin;
+  if (!scf) return;
+  for (uint32_t k = 0; k < D; ++k) {
+    for (uint32_t sl = 0; sl < n; ++sl) {
+      const uint32_t code = *L::slot_code(lds, sl);
+      double x = model.chunk, before_rs = 0.0, before_ag = 0.0;
+      for (uint32_t j = 0; j < D && !model.gather; ++j) {
+        const uint32_t kj = (code >> (2u * j)) & 3u;
+        if (kj == k) before_rs = x;
+        x = x / (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+      }
+      for (uint32_t j = D; j-- > 0u;) {
+        const uint32_t kj = (code >> (2u * j)) & 3u;
+        if (kj == k) before_ag = x;
+        x = x * (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+      }
+      lds_put_double(lds, sizes + 4u * sl, before_rs);
+      lds_put_double(lds, sizes + 4u * sl + 2u, before_ag);
+    }
+    const uint32_t entries = 2u * n;
+    // a stand-alone Reduce-Scatter has only the even entries, an All-Gather only the odd ones
+    const uint32_t first = model.gather ? 1u : 0u, step = model.one_phase() ? 2u : 1u;
+    for (uint32_t e = first; e < entries; e += step) {
+      const double v = lds_double(lds, sizes + 2u * e);
+      uint32_t smaller = 0;
+#pragma unroll 4
+      for (uint32_t o = first; o < entries; o += step)
+        smaller += lds_double(lds, sizes + 2u * o) < v ? 1u : 0u;
+      const uint32_t sl = e >> 1;
+      const uint32_t code = *L::slot_code(lds, sl);
+      uint32_t pos = 0;
+      for (uint32_t j = 0; j < D; ++j)
+        if (((code >> (2u * j)) & 3u) == k) pos = j;
+      *L::size_class(lds, sl, (e & 1u) ? 2u * D - 1u - pos : pos) = (uint8_t)smaller;
+    }
+  }
+}
+
+// The event loop of simulate_packed() on slots: same contract as
+// simulate_fast (result.ok false leaves the evaluation to the generic path).
+// A chunk in the Reduce-Scatter phase at position pos of its order waits for
+// stage pos, in the All-Gather phase for stage 2 D - 1 - pos.
+template <typename L, int kQueueOrder, bool kBusy, typename Model>
+__device__ __forceinline__ FastResult simulate_table_packed(const Scenario& s, const Model& model,
+                                                            const LaneLds& lds, const FastOut& out) {
+  static_assert(kQueueOrder == kNoQueueOrder || kQueueOrder == kBytes || kQueueOrder == kShorts,
+                "entries are stored one by one");
+  const uint32_t D = (uint32_t)s.D;
+  const uint32_t C = s.C;
+  const uint32_t full = (1u << D) - 1u;
+  const double kInf = inf64();
+  const bool rs_only = model.rs_only();
+  const bool scf = model.scf;
+
+  double f0 = kInf, f1 = kInf, f2 = kInf, f3 = kInf;  // finish time, +inf = idle
+  double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
+  // per dimension, the stage it serves and what its completion does: bits 0-7
+  // list to join, 8-13 upper record bits then, 14 chunk is done, 15-16 the
+  // dimension, 17-25 the chunk
+  uint32_t v0 = 0, v1 = 0, v2 = 0, v3 = 0;
+  typename L::Ids executed;  // operations started per dimension (kept when queue orders are written)
+  uint32_t started = 0;      // operations started in all
+  Classes64 classes(lds);
+  uint32_t work = 0;      // bit k: some list of dimension k holds chunks
+  uint32_t idle = full;   // bit k: dimension k serves nothing
+  const uint32_t row_len = 2u * out.slots;
+
+  // chunk c (upper record bits `up`: phase | slot << 1) becomes the last of list q = 64 * dim + class
+  auto push = [&](uint32_t q, uint32_t c, uint32_t up) {
+    const bool had = classes.mark(q);
+    uint16_t* tp = L::tail(lds, q);
+    const uint32_t t = *tp;
+    const uint32_t rec = c | (up << 9);
+    *L::record(lds, c) = (uint16_t)rec;  // own id: end of list
+    uint16_t* dst = had ? L::record(lds, t & L::kIdMask) : L::head(lds, q);
+    *dst = (uint16_t)(had ? ((t & ~L::kIdMask) | c) : c);
+    *tp = (uint16_t)rec;
+    work |= 1u << (q >> 6);
+  };
+  auto class_of = [&](uint32_t slot, uint32_t stage) -> uint32_t {
+    return scf ? (uint32_t)*L::size_class(lds, slot, stage) : 0u;
+  };
+
+  // a6: every chunk waits at the dimension of its first stage, in chunk-id order
+  {
+    const uint32_t phase0 = (model.state0() >> 4) & 1u;
+    const uint32_t pos0 = phase0 ? D - 1u : 0u, stage0 = phase0 ? D : 0u;
+    for (uint32_t c = 0; c < C; ++c) {
+      const uint32_t up = (uint32_t)*L::record(lds, c) >> 9;
+      const uint32_t code = *L::slot_code(lds, up >> 1);
+      push(64u * ((code >> (2u * pos0)) & 3u) + class_of(up >> 1, stage0), c, up);
+    }
+  }
+
+  double now = 0.0;
+  const uint32_t max_steps = 4u * D * C + 16u;
+  for (uint32_t step = 0; step <= max_steps; ++step) {
+    // a7: an idle dimension with waiting chunks starts its first one
+    if (const uint32_t need = idle & work) {
+      const uint32_t k = (uint32_t)__builtin_ctz(need);
+      uint32_t field;
+      const uint32_t cls = classes.lowest(k, field);  // smallest resident size
+      const uint32_t q = 64u * k + cls;
+      uint16_t* hp = L::head(lds, q);
+      const uint32_t h = *hp;
+      const uint32_t w = *L::record(lds, h);
+      const uint32_t nx = w & L::kIdMask;
+      *hp = (uint16_t)nx;  // harmless when the list is now empty
+      const bool no_work = classes.popped(k, cls, q, field, nx == h);
+      work &= ~((no_work ? 1u : 0u) << k);
+      idle &= ~(1u << k);
+
+      const uint32_t phase = (w >> 9) & 1u;
+      const bool ag = phase != 0u;
+      const uint32_t slot = (w >> 10) & 31u;
+      const uint32_t code = *L::slot_code(lds, slot);
+      const uint32_t o0 = code & 3u, o1 = (code >> 2) & 3u, o2 = (code >> 4) & 3u, o3 = code >> 6;
+      const bool p0 = k == o0, p1 = k == o1, p2 = k == o2;
+      const uint32_t pos = p0 ? 0u : p1 ? 1u : p2 ? 2u : 3u;
+      // the All-Gather on k reuses the time of the chunk's Reduce-Scatter on k
+      double t = model.time_at(code, pos);
+      t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
+      const double f = now + t;
+      const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
+      f0 = k0 ? f : f0; f1 = k1 ? f : f1; f2 = k2 ? f : f2; f3 = k3 ? f : f3;
+      if (kBusy) {
+        z0 = __builtin_fma(t, k0 ? 1.0 : 0.0, z0); z1 = __builtin_fma(t, k1 ? 1.0 : 0.0, z1);
+        z2 = __builtin_fma(t, k2 ? 1.0 : 0.0, z2); z3 = __builtin_fma(t, k3 ? 1.0 : 0.0, z3);
+      }
+      // what the completion will do: a Reduce-Scatter goes on to the next
+      // dimension of the order, the last one turns into the All-Gather on the
+      // same dimension; an All-Gather goes back to the previous one
+      {
+        const bool last_rs = !ag && pos + 1u == D;
+        const bool finished = ag ? p0 : (last_rs && rs_only);
+        const uint32_t prev = p1 ? o0 : p2 ? o1 : o2;
+        const uint32_t succ = p0 ? o1 : p1 ? o2 : o3;
+        const uint32_t kn = last_rs ? k : ag ? prev : succ;
+        const uint32_t stage = last_rs ? D : ag ? 2u * D - pos : pos + 1u;
+        const uint32_t up = (w >> 9) | (last_rs ? 1u : 0u);
+        const uint32_t qn = 64u * kn + class_of(slot, stage);
+        const uint32_t v = qn | (up << 8) | (finished ? 0x4000u : 0u) | (k << 15) | (h << 17);
+        v0 = k0 ? v : v0; v1 = k1 ? v : v1; v2 = k2 ? v : v2; v3 = k3 ? v : v3;
+      }
+      if (kQueueOrder != kNoQueueOrder) {
+        const uint32_t at = executed.get(k);
+        const uint32_t entry = (h << 1) | phase;
+        // at < row_len always holds for a consistent plan; it keeps the store in bounds
+        if (kQueueOrder == kBytes) {
+          if (at < row_len) out.queue_order[k * row_len + at] = (uint8_t)entry;
+        } else {
+          if (at < row_len) ((uint16_t*)out.queue_order)[k * row_len + at] = (uint16_t)entry;
+        }
+        executed.inc(k);
+      }
+      ++started;
+    }
+    if ((idle & work) != 0u) continue;  // all stages of an instant start before the clock moves
+
+    // a8: advance to the earliest completion
+    const double next = min_f64(min_f64(f0, f1), min_f64(f2, f3));
+    if (!(next < kInf)) break;  // nothing running: every chunk is done
+    now = next;
+    const bool d0 = f0 == now, d1 = f1 == now, d2 = f2 == now, d3 = f3 == now;
+    uint32_t done = (d0 ? 1u : 0u) | (d1 ? 2u : 0u) | (d2 ? 4u : 0u) | (d3 ? 8u : 0u);
+    f0 = d0 ? kInf : f0; f1 = d1 ? kInf : f1; f2 = d2 ? kInf : f2; f3 = d3 ? kInf : f3;
+    idle |= done;
+    // deliver all completions of this instant, lowest chunk id first
+    uint32_t g0 = d0 ? v0 : ~0u, g1 = d1 ? v1 : ~0u, g2 = d2 ? v2 : ~0u, g3 = d3 ? v3 : ~0u;
+    for (;;) {
+      const uint32_t g = min(min(g0, g1), min(g2, g3));
+      if ((g & 0x4000u) == 0u) push(g & 255u, g >> 17, (g >> 8) & 63u);
+      done &= ~(1u << ((g >> 15) & 3u));
+      if (done == 0u) break;
+      g0 = g0 == g ? ~0u : g0; g1 = g1 == g ? ~0u : g1;
+      g2 = g2 == g ? ~0u : g2; g3 = g3 == g ? ~0u : g3;
+    }
+  }
+
+  FastResult res;
+  // as in simulate_fast: every stage ran and completed, and none was too short
+  // to move the clock
+  const double t_min = model.t_min(D);
+  const uint32_t stages = model.one_phase() ? D : 2u * D;
+  res.ok = started == stages * C && idle == full && (now + 0.25 * t_min > now);
+  res.t_done = now;
+  res.busy[0] = z0; res.busy[1] = z1; res.busy[2] = z2; res.busy[3] = z3;
+#pragma unroll
+  for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) res.executed[k] = executed.get(k);
+  return res;
+}
+
 }  // namespace themis

@@ -195,15 +195,15 @@ def test_four_dimensional_networks_with_arbitrary_npu_counts(gpu, oracle, max_ch
     assert_close("sweep", got.cpu().numpy(), oracle.sweep(b, thr.cpu().numpy(), 7, threads=16))
 
 
-def test_workspace_is_only_needed_beyond_128_chunks(gpu, oracle):
-    """Up to 64 chunks the generic kernel keeps its per-chunk arrays in LDS, up
-    to 128 the LDS kernels for arbitrary NPU counts take what the power-of-two
-    kernel leaves: no workspace, same results.  Beyond, scenarios off the LDS
-    paths come back as NaN / all-ones when no workspace is passed, the others
-    are unaffected."""
+def test_single_collectives_run_without_a_workspace(gpu, oracle):
+    """Single collectives of any chunk count run in LDS without a workspace,
+    whatever the NPU counts (up to 64 chunks even the generic scan keeps its
+    per-chunk arrays in LDS).  Only what no LDS path takes beyond 64 chunks
+    (here: stage times too short to move the clock) needs the workspace and
+    comes back as NaN / all-ones without it, next to unaffected scenarios."""
     import torch
-    for mc in (9, 64, 100, 128):
-        b = w().mixed(500, seed=300 + mc, max_chunks=mc, pow2=False)
+    for mc in (9, 64, 100, 128, 200, 300, 512):
+        b = w().mixed(500 if mc <= 128 else 150, seed=300 + mc, max_chunks=mc, pow2=False)
         o_orders, _ = oracle.plan_batch(b, threads=8)
         o_t, o_qo, o_busy = oracle.simulate_batch(b, o_orders, threads=8)
         d = gpu.to_device(b)
@@ -217,19 +217,24 @@ def test_workspace_is_only_needed_beyond_128_chunks(gpu, oracle):
         assert np.array_equal(widen_queue(qo), o_qo)
         assert_close("busy", busy.cpu().numpy(), o_busy)
         assert_close("sweep", sw.cpu().numpy(), oracle.sweep(b, thr.cpu().numpy(), 6, threads=8))
-    b = w().mixed(400, seed=365, max_chunks=200, pow2=False)
-    pow2 = np.array([all((int(p) & (int(p) - 1)) == 0 for p in b.npus[:b.ndims[i], i])
-                     for i in range(b.n)])
+    W = w()
+    P = [[4, 4], [4, 4], [4, 8]]
+    bw = [[1e3, 1e300], [1e300, 1e3], [200e9, 50e9]]
+    reps = 10
+    b = W.make_batch([2, 2, 2] * reps, P * reps, bw * reps, 2.0 ** 30, [100, 70, 90] * reps, 1,
+                     [1, 0, 1] * reps, 0.0, max_chunks=100)
     o_orders, _ = oracle.plan_batch(b, threads=8)
     o_t, _, _ = oracle.simulate_batch(b, o_orders, want_queue_order=False, threads=8)
+    ordinary = np.arange(b.n) % 3 == 2
     d = gpu.to_device(b)
     orders, _ = gpu.themis_plan_batch(d)
-    t, qo, _ = gpu.themis_simulate_batch(d, orders)
+    t, qo, _ = gpu.themis_simulate_batch(d, orders)                 # no workspace
     torch.cuda.synchronize()
     t = t.cpu().numpy()
-    assert 0 < pow2.sum() < b.n
-    assert np.isnan(t[~pow2]).all() and (qo.cpu().numpy()[~pow2] == 0xFFFF).all()
-    assert_close("t_done of the LDS-path scenarios", t[pow2], o_t[pow2])
+    assert np.isfinite(o_t).all()
+    assert np.isnan(t[~ordinary]).all() and (qo.cpu().numpy()[~ordinary] == 0xFF).all()
+    assert_close("t_done of the LDS-path scenarios", t[ordinary], o_t[ordinary])
+    check_batch(gpu, oracle, b)                                     # with a workspace
 
 
 def test_large_chunk_counts(gpu, oracle):
