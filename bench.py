@@ -134,8 +134,8 @@ def other_workload(args, np, torch, binding, workloads):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--scenarios", type=int, default=1 << 20,
                     help="batch size (default: the 1M-scenario configuration)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 20,
