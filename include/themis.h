@@ -251,6 +251,27 @@ int themis_sweep(const themis_batch_t *batch, int n_thr, const double *thr,
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * themis_sweep_best -- what a parameter study reports per scenario and
+ * scheduler: the threshold that gives the smallest completion time (Sec. 5.3
+ * fixes one Threshold for all experiments; this finds the best one per
+ * scenario) and the speed-up over the baseline schedule (Sec. 6.1).
+ *
+ *   t_done       : [n][n_thr][n_pol] device doubles as written by themis_sweep.
+ *   baseline_col : column p of the baseline scheduler (0 when policy_mask
+ *                  contained THEMIS_SWEEP_BASELINE), or -1 for no speed-up.
+ *   best_t       : [n][n_pol] min over a of t_done[i][a][p]; NaN entries are
+ *                  skipped, NaN if all n_thr entries are.
+ *   best_thr     : [n][n_pol] lowest a that reaches it, 0xFFFFFFFF if none.
+ *                  May be NULL.
+ *   speedup      : [n][n_pol] t_done[i][0][baseline_col] / best_t[i][p] (the
+ *                  baseline ignores the threshold, so a = 0 stands for all).
+ *                  May be NULL; not written when baseline_col < 0.
+ */
+int themis_sweep_best(uint64_t n, int n_thr, int n_pol, const double *t_done,
+                      int baseline_col, double *best_t, uint32_t *best_thr,
+                      double *speedup, void *stream);
+
+/*
  * themis_metrics_batch -- the derived quantities of the paper's evaluation.
  *
  *   utilization[i] = sum_k transfer[k][i] * bw[k][i] / (t_done[i] * sum_k bw[k][i])

@@ -20,7 +20,8 @@
  * exact-rational checker that rebuilds every start and end time from the
  * reported per-dimension orders and verifies work conservation and FIFO / SCF
  * conformance, brute force over all per-chunk orders for tiny C, hand values
- * for the derived metrics and the provisioning classes.  The completion time
+ * for the derived metrics and the provisioning classes, hand values and the
+ * library minimum / argmin for the best threshold of a sweep.  The completion time
  * that the paper's timing figure would show for Themis on the worked example
  * is "parity unpinned": the figure is not available in text form.
  */
@@ -737,5 +738,37 @@ void to_classify_batch(uint64_t n, uint64_t begin, uint64_t end,
       for (int L = K + 1; L < TO_MAX_DIMS; ++L, ++pair)
         classes[(size_t)pair * n + i] =
             (ok && L < D) ? (uint8_t)to_provision_class(K, L, P, B) : 0xFF;
+  }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Best threshold of a sweep (Sec. 5.3 fixes one Threshold for all
+ * experiments; a parameter study asks which one is best per scenario) and the
+ * speed-up over the baseline schedule (Sec. 6.1).
+ * t_done [n][n_thr][n_pol]; per scenario i and scheduler column p:
+ *   best_t   = the smallest t_done[i][a][p] over a that is not NaN (NaN if
+ *              there is none), best_thr = the lowest a that reaches it
+ *              (0xFFFFFFFF if there is none),
+ *   speedup  = t_done[i][0][baseline_col] / best_t   (baseline_col >= 0).  */
+/* ------------------------------------------------------------------------ */
+void to_sweep_best(uint64_t n, uint32_t n_thr, uint32_t n_pol,
+                   const double *t_done, int baseline_col, double *best_t,
+                   uint32_t *best_thr, double *speedup)
+{
+  for (uint64_t i = 0; i < n; ++i) {
+    for (uint32_t p = 0; p < n_pol; ++p) {
+      double best = NAN;
+      uint32_t at = 0xFFFFFFFFu;
+      for (uint32_t a = 0; a < n_thr; ++a) {
+        double t = t_done[((size_t)i * n_thr + a) * n_pol + p];
+        if (isnan(t)) continue;
+        if (at == 0xFFFFFFFFu || t < best) { best = t; at = a; }
+      }
+      best_t[(size_t)i * n_pol + p] = best;
+      if (best_thr) best_thr[(size_t)i * n_pol + p] = at;
+      if (speedup && baseline_col >= 0)
+        speedup[(size_t)i * n_pol + p] =
+            t_done[(size_t)i * n_thr * n_pol + (uint32_t)baseline_col] / best;
+    }
   }
 }

@@ -59,6 +59,8 @@ def lib():
             _f64p, _u32p, _u8p, _f64p, _u8p, C.c_uint64, _f64p, _u8p]
         L.to_classify_batch.restype = None
         L.to_classify_batch.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, _u8p, _u32p, _f64p, _u8p]
+        L.to_sweep_best.restype = None
+        L.to_sweep_best.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, _f64p, C.c_int, _f64p, _u32p, _f64p]
         L.to_latency_coef.restype = None
         L.to_latency_coef.argtypes = [C.c_int, _u32p, _f64p, _f64p]
         _lib = L
@@ -294,3 +296,17 @@ def classify_batch(b):
     nd, P, bw = _arr(b.ndims, np.uint8), _arr(b.npus, np.uint32), _arr(b.bw, np.float64)
     lib().to_classify_batch(b.n, 0, b.n, _p(nd, _u8p), _p(P, _u32p), _p(bw, _f64p), _p(out, _u8p))
     return out
+
+
+def sweep_best(t_done, baseline_col=-1):
+    """Best threshold per scenario and scheduler of a sweep result [n, n_thr, n_pol]
+    (Sec. 5.3, Sec. 6.1) -> (best_t f64[n, n_pol], best_thr u32[n, n_pol],
+    speedup f64[n, n_pol] or None)."""
+    t = _arr(t_done, np.float64)
+    n, n_thr, n_pol = t.shape
+    best_t = np.empty((n, n_pol), np.float64)
+    best_thr = np.empty((n, n_pol), np.uint32)
+    speedup = np.empty((n, n_pol), np.float64) if baseline_col >= 0 else None
+    lib().to_sweep_best(n, n_thr, n_pol, _p(t, _f64p), baseline_col, _p(best_t, _f64p),
+                        _p(best_thr, _u32p), _p(speedup, _f64p) if speedup is not None else None)
+    return best_t, best_thr, speedup

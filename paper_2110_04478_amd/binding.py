@@ -66,6 +66,8 @@ def lib():
                                           C.c_size_t, _vp]
         L.themis_classify_batch.restype = C.c_int
         L.themis_classify_batch.argtypes = [C.POINTER(_Batch), _vp, _vp]
+        L.themis_sweep_best.restype = C.c_int
+        L.themis_sweep_best.argtypes = [C.c_uint64, C.c_int, C.c_int, _vp, C.c_int, _vp, _vp, _vp, _vp]
         L.themis_sweep.restype = C.c_int
         L.themis_sweep.argtypes = [C.POINTER(_Batch), C.c_int, _vp, C.c_int, C.c_uint, _vp,
                                    _vp, C.c_size_t, _vp]
@@ -254,6 +256,20 @@ def themis_classify_batch(b: DeviceBatch) -> torch.Tensor:
     s = b.c_struct()
     _check(lib().themis_classify_batch(C.byref(s), _ptr(classes), _stream()))
     return classes
+
+
+def themis_sweep_best(t_done: torch.Tensor, baseline_col: int = -1):
+    """Best threshold per scenario and scheduler of a sweep result f64[n, n_thr, n_pol]
+    -> (best_t f64[n, n_pol], best_thr u32[n, n_pol], speedup f64[n, n_pol] or None)."""
+    n, n_thr, n_pol = t_done.shape
+    assert t_done.dtype == torch.float64 and t_done.is_contiguous()
+    best_t = torch.empty((n, n_pol), dtype=torch.float64, device=t_done.device)
+    best_thr = torch.empty((n, n_pol), dtype=torch.uint32, device=t_done.device)
+    speedup = (torch.empty((n, n_pol), dtype=torch.float64, device=t_done.device)
+               if baseline_col >= 0 else None)
+    _check(lib().themis_sweep_best(n, n_thr, n_pol, _ptr(t_done), baseline_col, _ptr(best_t),
+                                   _ptr(best_thr), _ptr(speedup), _stream()))
+    return best_t, best_thr, speedup
 
 
 def alloc_workspace(nbytes: int, device="cuda:0") -> Optional[torch.Tensor]:

@@ -648,6 +648,32 @@ sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
 }
 
 // ---------------------------------------------------------------------------
+// themis_sweep_best: per scenario and scheduler the best threshold of a sweep
+// and the speed-up over the baseline (Sec. 5.3, Sec. 6.1).  One lane per
+// (scenario, scheduler).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+sweep_best_kernel(uint64_t n, uint32_t n_thr, uint32_t n_pol, const double* __restrict__ t_done,
+                  int baseline_col, double* __restrict__ best_t, uint32_t* __restrict__ best_thr,
+                  double* __restrict__ speedup) {
+  const uint64_t e = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= n * n_pol) return;
+  const uint64_t i = e / n_pol;
+  const uint32_t p = (uint32_t)(e - i * n_pol);
+  const double* row = t_done + i * n_thr * n_pol;
+  double best = nan64();
+  uint32_t at = 0xffffffffu;
+  for (uint32_t a = 0; a < n_thr; ++a) {
+    const double t = row[(size_t)a * n_pol + p];
+    // the first value that is not NaN, then every strictly smaller one
+    if (t == t && (at == 0xffffffffu || t < best)) { best = t; at = a; }
+  }
+  best_t[e] = best;
+  if (best_thr) best_thr[e] = at;
+  if (speedup && baseline_col >= 0) speedup[e] = row[baseline_col] / best;
+}
+
+// ---------------------------------------------------------------------------
 // themis_search_batch: every assignment of dimension orders to chunks.
 // ---------------------------------------------------------------------------
 // Order code of the permutation of (0..D-1) with lexicographic index idx.
@@ -1152,6 +1178,19 @@ int themis_classify_batch(const themis_batch_t* batch, uint8_t* classes, void* s
   if (batch->n > (uint64_t)0x7fffffff * 256u) return THEMIS_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(classify_kernel, dim3((unsigned)((batch->n + 255) / 256)), dim3(256), 0,
                      (hipStream_t)stream, *batch, classes);
+  return launch_status();
+}
+
+int themis_sweep_best(uint64_t n, int n_thr, int n_pol, const double* t_done, int baseline_col,
+                      double* best_t, uint32_t* best_thr, double* speedup, void* stream) {
+  if (n_thr < 1 || n_pol < 1 || n_pol > 3 || baseline_col >= n_pol) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (n == 0) return THEMIS_OK;
+  if (!t_done || !best_t) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (n > (uint64_t)0x7fffffff * 64u) return THEMIS_ERR_UNSUPPORTED;
+  const uint64_t items = n * (uint64_t)n_pol;
+  hipLaunchKernelGGL(sweep_best_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
+                     (hipStream_t)stream, n, (uint32_t)n_thr, (uint32_t)n_pol, t_done, baseline_col,
+                     best_t, best_thr, speedup);
   return launch_status();
 }
 

@@ -457,6 +457,44 @@ def test_sweep_matches_oracle(gpu, oracle):
     assert_close("sweep t_done (per-scenario thr)", got.cpu().numpy(), want)
 
 
+def test_sweep_best_matches_oracle(gpu, oracle):
+    """Best threshold per scenario and scheduler and speed-up over the baseline
+    (Sec. 5.3, Sec. 6.1), on a real sweep (with invalid scenarios: NaN rows)
+    and on values with ties, NaN entries and all-NaN columns."""
+    import torch
+    W = w()
+    b = W.mixed(1500, seed=91)
+    b.bw[0, 7] = float("nan")
+    b.chunks[9] = 0
+    thr = np.array([0.0, 1 / 64, 1 / 16, 1 / 4, 1.0])
+    d = gpu.to_device(b)
+    for mask, col in ((7, 0), (6, -1), (3, 0), (4, -1)):
+        t = gpu.themis_sweep(d, torch.from_numpy(thr).cuda(), mask)
+        best_t, best_thr, speedup = gpu.themis_sweep_best(t, col)
+        torch.cuda.synchronize()
+        o_t, o_thr, o_s = oracle.sweep_best(t.cpu().numpy(), col)
+        assert_close("best_t", best_t.cpu().numpy(), o_t)
+        assert np.array_equal(best_thr.cpu().numpy(), o_thr)
+        if col >= 0:
+            assert_close("speedup", speedup.cpu().numpy(), o_s)
+        else:
+            assert speedup is None
+        assert np.isnan(o_t[7]).all() and (o_thr[9] == 0xFFFFFFFF).all()
+    rng = np.random.default_rng(5)
+    t = rng.integers(1, 6, (4000, 7, 3)).astype(np.float64)      # many ties
+    t[rng.random(t.shape) < 0.3] = np.nan
+    t[::17, :, 1] = np.nan
+    best_t, best_thr, speedup = gpu.themis_sweep_best(torch.from_numpy(t).cuda(), 0)
+    torch.cuda.synchronize()
+    o_t, o_thr, o_s = oracle.sweep_best(t, 0)
+    assert_close("best_t", best_t.cpu().numpy(), o_t)
+    assert np.array_equal(best_thr.cpu().numpy(), o_thr)
+    assert_close("speedup", speedup.cpu().numpy(), o_s)
+    # an empty batch is fine
+    e = gpu.themis_sweep_best(torch.empty((0, 3, 2), dtype=torch.float64, device="cuda"), 0)
+    assert e[0].shape == (0, 2)
+
+
 def test_determinism_and_permutation_invariance(gpu):
     """The same scenario gives the same bits wherever it sits in the batch
     (the consistency requirement of Sec. 4.6: every NPU must derive exactly

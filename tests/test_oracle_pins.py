@@ -724,3 +724,39 @@ def test_overflowing_times_are_reported_as_invalid(oracle):
     assert od[1].tolist() == [code_of([0, 1])] + [code_of([1, 0])] * 7
     assert busy[0, 1] == pytest.approx(2 * 0.75 * 2.0 ** 27 * (1 + 7 / 4) / 1e3, rel=1e-12)
     assert t[1] == pytest.approx(busy[0, 1], rel=1e-9)
+
+
+def test_sweep_best_hand_values(oracle):
+    """Best threshold and speed-up (Sec. 5.3, Sec. 6.1) on values worked out by
+    hand: the lowest index among equal minima, NaN entries skipped, an all-NaN
+    column, and the speed-up taken against the baseline column at a = 0."""
+    nan = float("nan")
+    #            a=0            a=1            a=2          (columns: baseline, Themis+FIFO, Themis+SCF)
+    t = np.array([[[8.0, 7.0, 6.0], [8.0, 5.0, 6.0], [8.0, 5.0, 4.0]],
+                  [[2.0, nan, nan], [2.0, 1.0, nan], [2.0, 0.5, nan]],
+                  [[3.0, 3.0, 9.0], [3.0, 3.0, 9.0], [3.0, 3.0, 1.5]]])
+    best_t, best_thr, speedup = oracle.sweep_best(t, baseline_col=0)
+    assert best_t[0].tolist() == [8.0, 5.0, 4.0] and best_thr[0].tolist() == [0, 1, 2]
+    assert speedup[0].tolist() == [1.0, 1.6, 2.0]
+    assert best_t[1, :2].tolist() == [2.0, 0.5] and np.isnan(best_t[1, 2])
+    assert best_thr[1].tolist() == [0, 2, 0xFFFFFFFF]
+    assert speedup[1, :2].tolist() == [1.0, 4.0] and np.isnan(speedup[1, 2])
+    assert best_thr[2].tolist() == [0, 0, 2] and speedup[2].tolist() == [1.0, 1.0, 2.0]
+    # no baseline column: no speed-up
+    assert oracle.sweep_best(t)[2] is None
+
+
+def test_sweep_best_is_the_library_minimum(oracle):
+    """Against numpy's minimum / argmin on a real sweep of the oracle: the best
+    time is the minimum over the threshold axis, the index the first position
+    of it, and no threshold beats the best one."""
+    from paper_2110_04478_amd import workloads as W
+    b = W.mixed(300, seed=11, max_chunks=24)
+    thr = np.array([0.0, 1 / 64, 1 / 16, 1 / 4, 1.0])
+    t = oracle.sweep(b, thr, 7, threads=4)
+    best_t, best_thr, speedup = oracle.sweep_best(t, baseline_col=0)
+    assert np.array_equal(best_t, t.min(axis=1))
+    assert np.array_equal(best_thr, t.argmin(axis=1).astype(np.uint32))
+    assert np.array_equal(speedup, t[:, 0, 0][:, None] / t.min(axis=1))
+    assert (speedup[:, 0] == 1.0).all()          # the baseline against itself
+    assert (t >= best_t[:, None, :]).all()
