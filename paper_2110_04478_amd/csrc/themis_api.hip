@@ -82,11 +82,19 @@ __device__ __forceinline__ bool nothing_marked(unsigned long long call) {
 // ---------------------------------------------------------------------------
 // themis_plan_batch: Alg. 1 per scenario (hot-path steps a1-a5).
 // ---------------------------------------------------------------------------
+// kPerCollective: one lane per (scenario, collective) instead of one per
+// scenario -- the tracker starts afresh for every collective (Alg. 1 line 2),
+// so the collectives of a trace are planned independently, and a batch of a
+// few thousand traces has too few scenarios to fill the GPU.
+template <bool kPerCollective>
 __global__ void __launch_bounds__(kBlock)
 plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__ loads) {
-  uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= b.n) return;
   const TraceView tv = trace_view(b);
+  const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  const uint64_t i = kPerCollective ? e / tv.mc : e;
+  if (i >= b.n) return;
+  const uint32_t q_first = kPerCollective ? (uint32_t)(e - i * tv.mc) : 0u;
+  const uint32_t q_end = kPerCollective ? q_first + 1u : tv.mc;
   Scenario s = load_scenario(b, i);
   const bool rel = b.threshold_mode == THEMIS_THR_REL;
   const double thr = b.threshold[i];
@@ -97,11 +105,11 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
   uint8_t* row = orders + (size_t)i * tv.slots;
   double load[kMaxDims] = {0.0, 0.0, 0.0, 0.0};
   if (!ok) {
-    for (uint32_t c = 0; c < tv.slots; ++c) row[c] = 0xFFu;
+    for (uint32_t c = q_first * b.max_chunks; c < q_end * b.max_chunks; ++c) row[c] = 0xFFu;
   } else {
     // rows are written four codes at a time when they are 4-byte aligned
     const bool words = (b.max_chunks & 3u) == 0u;
-    for (uint32_t q = 0; q < tv.mc; ++q) {
+    for (uint32_t q = q_first; q < q_end; ++q) {
       uint8_t* r = row + (size_t)q * b.max_chunks;
       uint32_t filled = 0;
       if (q < Q) {
@@ -135,7 +143,8 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
       for (uint32_t c = filled; c < b.max_chunks; ++c) r[c] = 0xFFu;
     }
   }
-  if (loads) {
+  // the tracker of the scenario's last collective (an invalid scenario: NaN)
+  if (loads && (!kPerCollective || q_first == (ok ? Q - 1u : 0u))) {
 #pragma unroll
     for (int k = 0; k < kMaxDims; ++k)
       loads[(size_t)k * b.n + i] = ok ? ((k < s.D) ? load[k] : 0.0) : nan64();
@@ -988,8 +997,14 @@ int themis_plan_batch(const themis_batch_t* batch, uint8_t* orders, double* load
   if (st != THEMIS_OK) return st;
   if (batch->n == 0) return THEMIS_OK;
   if (!orders) return THEMIS_ERR_INVALID_ARGUMENT;
-  hipLaunchKernelGGL(plan_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
-                     (hipStream_t)stream, *batch, orders, loads);
+  const TraceView tv = trace_view(*batch);
+  if (batch->n * (uint64_t)tv.mc > (uint64_t)0x7fffffff * kBlock) return THEMIS_ERR_UNSUPPORTED;
+  if (tv.mc > 1u)
+    hipLaunchKernelGGL(plan_kernel<true>, dim3(blocks_for(batch->n * tv.mc)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, orders, loads);
+  else
+    hipLaunchKernelGGL(plan_kernel<false>, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
+                       (hipStream_t)stream, *batch, orders, loads);
   return launch_status();
 }
 
