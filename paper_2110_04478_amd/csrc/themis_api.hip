@@ -196,7 +196,7 @@ __device__ __forceinline__ void init_chunk(const LaneLds& lds, uint32_t c, uint3
 template <typename L, int kQueueOrder, bool kBusy, bool kFix, bool kOnePerPass = true>
 __device__ __forceinline__ FastResult simulate_pow2(const Scenario& s, const Pow2Model& model,
                                                     const LaneLds& lds, const FastOut& out) {
-  if constexpr (L::kPacked) return simulate_packed<L, kQueueOrder, kBusy, kFix, true>(s, model, lds, out);
+  if constexpr (L::kPacked) return simulate_packed<L, kQueueOrder, kBusy, kFix>(s, model, lds, out);
   else return simulate_fast<L, kQueueOrder, kBusy, kFix, Pow2Model, kOnePerPass>(s, model, lds, out);
 }
 

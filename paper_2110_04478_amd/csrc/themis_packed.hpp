@@ -74,7 +74,7 @@ struct PackedOrder {
 // Same contract as simulate_fast (records initialised with L::init_chunk(),
 // result.ok false leaves the evaluation to the generic path); power-of-two
 // model only.
-template <typename L, int kQueueOrder, bool kBusy, bool kFix, bool kOnePerPass = false>
+template <typename L, int kQueueOrder, bool kBusy, bool kFix>
 __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const Pow2Model& model,
                                                       const LaneLds& lds, const FastOut& out) {
   static_assert(kQueueOrder == kNoQueueOrder || kQueueOrder == kBytes || kQueueOrder == kShorts,
@@ -130,9 +130,9 @@ __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const P
   double now = 0.0;
   const uint32_t max_steps = 4u * D * C + 16u;
   for (uint32_t step = 0; step <= max_steps; ++step) {
-    // a7: every idle dimension with waiting chunks starts its first one
-    // (kOnePerPass as in simulate_fast)
-    for (uint32_t need = idle & work; need != 0u; need = kOnePerPass ? 0u : (idle & work)) {
+    // a7: an idle dimension with waiting chunks starts its first one (one stage
+    // per pass, as in simulate_fast: here it pays for every output set)
+    if (const uint32_t need = idle & work) {
       const uint32_t k = (uint32_t)__builtin_ctz(need);
       uint32_t field;
       const uint32_t cls = classes.lowest(k, field);  // smallest resident size
@@ -197,7 +197,7 @@ __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const P
       if (kQueueOrder != kNoQueueOrder) executed.inc(k);
       ++started;
     }
-    if (kOnePerPass && (idle & work) != 0u) continue;
+    if ((idle & work) != 0u) continue;  // all stages of an instant start before the clock moves
 
     // a8: advance to the earliest completion
     const double next = min_f64(min_f64(f0, f1), min_f64(f2, f3));
