@@ -131,6 +131,82 @@ def other_workload(args, np, torch, binding, workloads):
     return result
 
 
+def extras_workload(args, np, torch, binding, workloads):
+    """The entry points beyond plan / simulate / sweep on the 4-D bench networks, each timed
+    on its own with HIP events on the stream the kernels run on: per-stage fixed delays,
+    stand-alone Reduce-Scatter / All-Gather, the derived metrics, the provisioning classes,
+    the exhaustive search over per-chunk orders and the best threshold of a sweep."""
+    dev = "cuda:0"
+    n = args.scenarios
+    rng = np.random.default_rng(workloads.SEED_BASE)
+    rows = {}
+
+    def timed(name, units, fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(args.steps):
+            fn()
+        ev1.record()
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1) / args.steps
+        rows[name] = {"ms": ms, "per_sec": units / (ms * 1e-3)}
+
+    base = workloads.config3(n=n)
+    events = n * 512.0
+    # fixed delays per stage (Sec. 4.4): tracker start and stage times
+    host = workloads.config3(n=n)
+    host.fixed_delay = np.ascontiguousarray(rng.uniform(0, 2e-6, (4, n)))
+    d = binding.to_device(host, dev)
+    orders, loads = binding.themis_plan_batch(d)
+    qo = torch.empty((n, 4, 2 * d.slots), dtype=torch.uint8, device=dev)
+    t = torch.empty(n, dtype=torch.float64, device=dev)
+    busy = torch.empty((4, n), dtype=torch.float64, device=dev)
+    timed("fixed_delay: plan", n, lambda: binding.themis_plan_batch(d, orders, loads))
+    timed("fixed_delay: simulate, all outputs (events/s)", events,
+          lambda: binding.themis_simulate_batch(d, orders, t, qo, busy))
+    # stand-alone collectives (Alg. 1's CollectiveType): a third each of All-Reduce, RS, AG
+    host = workloads.config3(n=n)
+    host.collective_type = rng.integers(0, 3, n).astype(np.uint8)
+    d2 = binding.to_device(host, dev)
+    ev2 = float(((host.collective_type == 0) + 1).sum()) * 4 * 64
+    timed("collective types: plan", n, lambda: binding.themis_plan_batch(d2, orders, loads))
+    timed("collective types: simulate, all outputs (events/s)", ev2,
+          lambda: binding.themis_simulate_batch(d2, orders, t, qo, busy))
+    # derived metrics and provisioning classes
+    d0 = binding.to_device(base, dev)
+    binding.themis_plan_batch(d0, orders, loads)
+    binding.themis_simulate_batch(d0, orders, t, qo, busy)
+    timed("metrics (utilisation, Ideal)", n, lambda: binding.themis_metrics_batch(d0, t, busy))
+    timed("provisioning classes", n, lambda: binding.themis_classify_batch(d0))
+    # exhaustive search: 3-D, 4 chunks -> 6^4 = 1,296 schedules per scenario
+    ns = max(1, n // 64)
+    small = workloads.config2(n=ns)
+    small.chunks[:] = 4
+    small.max_chunks = 4
+    ds = binding.to_device(small, dev)
+    timed("search: %d scenarios x 1,296 schedules (schedules/s)" % ns, ns * 1296.0,
+          lambda: binding.themis_search_batch(ds, 1296))
+    # best threshold of a sweep
+    thr = torch.from_numpy(workloads.CONFIG4_THRESHOLDS).to(dev)
+    sweep = binding.themis_sweep(d0, thr, 7)
+    timed("sweep: 8 thresholds x 3 schedulers (evaluations/s)", n * 24.0,
+          lambda: binding.themis_sweep(d0, thr, 7, t_done=sweep))
+    timed("sweep_best", n, lambda: binding.themis_sweep_best(sweep, 0))
+    best_t, best_thr, speedup = binding.themis_sweep_best(sweep, 0)
+    torch.cuda.synchronize()
+    sp = speedup.cpu().numpy()
+    return {"metric": "extras", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "dtype": "f64", "data": "synthetic",
+            "config": {"workload": "extras: %d scenarios of the 4-D bench networks" % n},
+            "rows": rows,
+            "speedup_over_baseline_best_threshold": {
+                "themis_fifo_mean": float(np.mean(sp[:, 1])), "themis_scf_mean": float(np.mean(sp[:, 2])),
+                "themis_scf_max": float(np.max(sp[:, 2]))}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -142,7 +218,7 @@ def main():
                     help="scenarios the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-queue-order", action="store_true",
                     help="do not request the per-dimension queue orders")
-    ap.add_argument("--workload", choices=("config3", "config4", "config5"), default="config3")
+    ap.add_argument("--workload", choices=("config3", "config4", "config5", "extras"), default="config3")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB MiB "
                          "(known traffic, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
@@ -167,6 +243,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": src.numel(), "copy_probe_bytes_written": dst.numel()}))
+        return
+    if args.workload == "extras":
+        print(json.dumps(extras_workload(args, np, torch, binding, workloads)))
         return
     if args.workload != "config3":
         print(json.dumps(other_workload(args, np, torch, binding, workloads)))
