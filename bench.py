@@ -42,8 +42,8 @@ def algorithmic_lane_ops(D, C):
 # file on the default workload); not measured live.  Only attached to the JSON
 # line when the run uses that workload.
 PROFILED = {
-    "traffic_bytes_per_launch": 4.58e9,   # FETCH_SIZE x2.0 + WRITE_SIZE x1.0, simulate kernel
-    "valu_issue_frac": 0.772,             # SQ_ACTIVE_INST_VALU / (256 CUs x busy cycles)
+    "traffic_bytes_per_launch": 1.78e9,   # FETCH_SIZE x2.0 + WRITE_SIZE x1.0, simulate kernel
+    "valu_issue_frac": 0.760,             # SQ_ACTIVE_INST_VALU / (256 CUs x busy cycles)
 }
 
 

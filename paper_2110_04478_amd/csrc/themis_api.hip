@@ -220,6 +220,22 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
   uint32_t Q;
   bool ok = collectives_ok(b, tv, i, Q) && s.valid;
 
+  // Queue orders of a wavefront whose 64 scenarios all exist are staged
+  // transposed inside the wavefront's own block of the output (see FastOut)
+  // and put in place once the wavefront is through: a lane appends a dword to
+  // each of its four rows every few events, and with the rows in place the
+  // partly written lines of all resident wavefronts do not fit the L2, so they
+  // went to memory several times over.
+  // dwords per row that the last step holds in registers (a row has up to kCap / 2)
+  constexpr uint32_t kStagedWords = L::kCap / 2u < 32u ? L::kCap / 2u : 32u;
+  const uint32_t rows_bytes = (uint32_t)kMaxDims * 2u * tv.slots * (uint32_t)entry_bytes;
+  const bool staged = kQueueOrder == kWords && queue_order != nullptr &&
+                      (tv.slots >> 1) <= kStagedWords &&
+                      (uint64_t)(blockIdx.x + 1u) * kBlock <= b.n;  // the same for all lanes
+  enum { kRowsStaged = 1, kRowsAllOnes = 2, kRowsNotMine = 3 };
+  uint32_t rows = kRowsNotMine;
+  uint32_t executed[kMaxDims] = {0u, 0u, 0u, 0u};
+
   SimOut out;
   out.t_done = t_done + i;
   out.busy = busy ? busy + i : nullptr;
@@ -227,61 +243,132 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
   out.entry_bytes = entry_bytes;
   out.slots = tv.slots;
   out.queue_order = (kQueueOrder != kNoQueueOrder && queue_order)
-      ? (void*)((uint8_t*)queue_order + (size_t)i * kMaxDims * 2u * tv.slots * entry_bytes)
-      : nullptr;
-  if (!ok) { write_invalid(out); return; }
+      ? (void*)((uint8_t*)queue_order + (size_t)i * rows_bytes) : nullptr;
+  // an invalid scenario: NaN / all-ones (its rows at the end, if rows are staged in the block)
+  auto invalid = [&]() {
+    SimOut o = out;
+    if (staged) o.queue_order = nullptr;
+    write_invalid(o);
+    rows = kRowsAllOnes;
+  };
 
-  const uint8_t* row = orders + (size_t)i * tv.slots;
-  FastScenario fs;
-  bool fast = !tv.on &&
-              fast_eligible(s, collective_size(b, tv, i, 0) / (double)s.C, L::kCap, fs);
-  if (fast) {
-    LaneLds lds;
-    lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
-    // order codes -> chunk words (mask 0, Reduce-Scatter phase)
-    bool codes_ok = true;
-    if ((tv.slots & 3u) == 0u) {
-      const uint32_t* row4 = (const uint32_t*)row;
-      for (uint32_t c4 = 0; c4 < s.C; c4 += 4u) {
-        uint32_t v = row4[c4 >> 2];
+  do {
+    if (!ok) { invalid(); break; }
+    const uint8_t* row = orders + (size_t)i * tv.slots;
+    FastScenario fs;
+    bool fast = !tv.on &&
+                fast_eligible(s, collective_size(b, tv, i, 0) / (double)s.C, L::kCap, fs);
+    if (fast) {
+      LaneLds lds;
+      lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+      // order codes -> chunk words (mask 0, Reduce-Scatter phase)
+      bool codes_ok = true;
+      if ((tv.slots & 3u) == 0u) {
+        const uint32_t* row4 = (const uint32_t*)row;
+        for (uint32_t c4 = 0; c4 < s.C; c4 += 4u) {
+          uint32_t v = row4[c4 >> 2];
 #pragma unroll
-        for (uint32_t j = 0; j < 4u; ++j) {
-          if (c4 + j < s.C) {
-            uint32_t code = (v >> (8u * j)) & 0xffu;
-            codes_ok = codes_ok && order_code_ok(code, s.D);
-            init_chunk<L>(lds, c4 + j, stored_code(s, fs, code), fs.state0, (uint32_t)s.D);
+          for (uint32_t j = 0; j < 4u; ++j) {
+            if (c4 + j < s.C) {
+              uint32_t code = (v >> (8u * j)) & 0xffu;
+              codes_ok = codes_ok && order_code_ok(code, s.D);
+              init_chunk<L>(lds, c4 + j, stored_code(s, fs, code), fs.state0, (uint32_t)s.D);
+            }
           }
         }
+      } else {
+        for (uint32_t c = 0; c < s.C; ++c) {
+          uint32_t code = row[c];
+          codes_ok = codes_ok && order_code_ok(code, s.D);
+          init_chunk<L>(lds, c, stored_code(s, fs, code), fs.state0, (uint32_t)s.D);
+        }
       }
-    } else {
-      for (uint32_t c = 0; c < s.C; ++c) {
-        uint32_t code = row[c];
-        codes_ok = codes_ok && order_code_ok(code, s.D);
-        init_chunk<L>(lds, c, stored_code(s, fs, code), fs.state0, (uint32_t)s.D);
+      if (!codes_ok) { invalid(); break; }
+      FastOut fo;
+      fo.queue_order = (uint8_t*)out.queue_order;
+      fo.slots = tv.slots;
+      if (staged) {
+        fo.queue_order = (uint8_t*)queue_order + (size_t)blockIdx.x * kBlock * rows_bytes + 4u * threadIdx.x;
+        fo.word_stride = 4u * kBlock;
+      }
+      FastResult r = simulate_pow2<L, kQueueOrder, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
+      if (r.ok) {
+        t_done[i] = r.t_done;
+        if (busy) {
+#pragma unroll
+          for (int k = 0; k < kMaxDims; ++k) busy[(size_t)k * b.n + i] = r.busy[k];
+        }
+        if (staged) {
+          rows = kRowsStaged;
+#pragma unroll
+          for (int k = 0; k < kMaxDims; ++k) executed[k] = r.executed[k];
+        } else if (kQueueOrder != kNoQueueOrder && out.queue_order) {
+          for (int k = 0; k < kMaxDims; ++k)
+            for (uint32_t e = r.executed[k]; e < 2u * tv.slots; ++e)
+              put_queue_entry<kQueueOrder>(fo.queue_order, (uint32_t)k * 2u * tv.slots + e, 0xFFFFu);
+        }
+        break;
       }
     }
-    if (!codes_ok) { write_invalid(out); return; }
-    FastOut fo;
-    fo.queue_order = (uint8_t*)out.queue_order;
-    fo.slots = tv.slots;
-    FastResult r = simulate_pow2<L, kQueueOrder, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
-    if (r.ok) {
-      t_done[i] = r.t_done;
-      if (busy) {
+    // hand_over != 0: follow-up kernels come (this call's number) and write
+    // everything of this scenario, else nothing can take it
+    if (!hand_over) { invalid(); break; }
+    mark_left_to_generic(t_done + i, hand_over);
+  } while (false);
+
+  if constexpr (kQueueOrder == kWords) {
+    if (staged) {
+      // every lane fetches its own rows from the staging order (64 lanes read
+      // 256 contiguous bytes per dword), waits until the whole wavefront has
+      // all of them in registers, and writes them where they belong, with
+      // all-ones from the first unused entry on
+      const uint32_t wpr = tv.slots >> 1;  // dwords per row
+      const uint32_t* from =
+          (const uint32_t*)((uint8_t*)queue_order + (size_t)blockIdx.x * kBlock * rows_bytes) + threadIdx.x;
+      uint32_t q[kMaxDims][kStagedWords];
 #pragma unroll
-        for (int k = 0; k < kMaxDims; ++k) busy[(size_t)k * b.n + i] = r.busy[k];
+      for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k)
+#pragma unroll
+        for (uint32_t w = 0; w < kStagedWords; ++w)
+          q[k][w] = (w < wpr && rows == kRowsStaged) ? from[(size_t)(k * wpr + w) * kBlock] : 0xffffffffu;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (rows != kRowsNotMine) {
+        uint32_t* to = (uint32_t*)((uint8_t*)queue_order + (size_t)i * rows_bytes);
+        // four dwords per store where the rows allow it: a quarter of the
+        // memory transactions of this step
+        const bool quads = (wpr & 3u) == 0u && ((uintptr_t)queue_order & 15u) == 0u;
+        // rows without an unused entry (every dimension ran all 2 * slots
+        // operations: an All-Reduce of `slots` chunks on four dimensions) need no marks
+        bool full_rows = rows == kRowsStaged;
+#pragma unroll
+        for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) full_rows = full_rows && executed[k] == 2u * tv.slots;
+        const bool marks = __builtin_amdgcn_ballot_w64(!full_rows) != 0ull;  // the same for all lanes
+#pragma unroll
+        for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k)
+#pragma unroll
+          for (uint32_t w4 = 0; w4 < kStagedWords; w4 += 4u) {
+            uint32_t v[4];
+#pragma unroll
+            for (uint32_t j = 0; j < 4u; ++j) {
+              const uint32_t w = w4 + j;
+              v[j] = w < kStagedWords ? q[k][w] : 0xffffffffu;
+              if (marks) {
+                // entries of this dword that are in use, 0..4; all-ones above them
+                const int left = min(max((int)executed[k] - (int)(4u * w), 0), 4);
+                v[j] |= (uint32_t)(0xffffffffull << (8 * left));
+              }
+            }
+            if (quads) {
+              if (w4 < wpr) *(uint4*)(to + k * wpr + w4) = make_uint4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+              for (uint32_t j = 0; j < 4u; ++j)
+                if (w4 + j < wpr) to[k * wpr + w4 + j] = v[j];
+            }
+          }
       }
-      if (kQueueOrder != kNoQueueOrder && out.queue_order) {
-        for (int k = 0; k < kMaxDims; ++k)
-          for (uint32_t e = r.executed[k]; e < 2u * tv.slots; ++e)
-            put_queue_entry<kQueueOrder>(fo.queue_order, (uint32_t)k * 2u * tv.slots + e, 0xFFFFu);
-      }
-      return;
     }
   }
-  // hand_over != 0: follow-up kernels come (this call's number), else nothing can take it
-  if (!hand_over) { write_invalid(out); return; }
-  mark_left_to_generic(t_done + i, hand_over);
 }
 
 // Second kernel of themis_simulate_batch: the scenarios the LDS kernel marked.

@@ -322,6 +322,13 @@ __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario&
 struct FastOut {
   uint8_t* queue_order;  // this evaluation's [4][2*slots] entries, or null
   uint32_t slots;
+  // kWords only: bytes from one dword of the evaluation's rows to the next.
+  // 4: the rows lie as the caller sees them.  256: they are staged transposed
+  // inside the wavefront's block of the output (dword w of lane L at
+  // (w * 64 + L) * 4 from queue_order - 4 * L), so that the dwords the lanes
+  // of a wavefront store at about the same time share cache lines; whoever
+  // asks for that puts the rows in place afterwards.
+  uint32_t word_stride = 4;
 };
 
 struct FastResult {
@@ -509,7 +516,8 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
           const uint32_t a = __builtin_amdgcn_alignbit(entry, sel4((int)k, a0, a1, a2, a3), 8u);
           a0 = k0 ? a : a0; a1 = k1 ? a : a1; a2 = k2 ? a : a2; a3 = k3 ? a : a3;
           if ((pos & 3u) == 3u && pos < row_len)
-            *(uint32_t*)(out.queue_order + __umul24(k, row_len) + (pos & ~3u)) = a;
+            *(uint32_t*)(out.queue_order +
+                         __umul24(__umul24(k, out.slots >> 1) + (pos >> 2), out.word_stride)) = a;
         }
       }
       executed.inc(k);
@@ -554,17 +562,16 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
   }
 
   if (kQueueOrder == kWords) {
-    // entries that did not fill a whole dword yet
+    // entries that did not fill a whole dword yet, with unused-entry marks
+    // (all-ones) behind them
     const uint32_t acc[kMaxDims] = {a0, a1, a2, a3};
 #pragma unroll
     for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) {
       const uint32_t n = executed.get(k);
       const uint32_t rem = n & 3u;
-      for (uint32_t j = 0; j < rem; ++j) {
-        const uint32_t pos = n - rem + j;
-        if (pos < row_len)
-          out.queue_order[k * row_len + pos] = (uint8_t)(acc[k] >> (8u * (4u - rem + j)));
-      }
+      if (rem != 0u && n < row_len)
+        *(uint32_t*)(out.queue_order + __umul24(__umul24(k, out.slots >> 1) + (n >> 2), out.word_stride)) =
+            (acc[k] >> (8u * (4u - rem))) | (0xffffffffu << (8u * rem));
     }
   }
 
