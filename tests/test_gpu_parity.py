@@ -103,6 +103,37 @@ def test_ragged_mixed_batches(gpu, oracle, n, thr_mode):
     check_batch(gpu, oracle, w().mixed(n, seed=1234 + n, thr_mode=thr_mode))
 
 
+@pytest.mark.parametrize("max_chunks", [8, 22, 64, 126])
+@pytest.mark.parametrize("offset", [0, 1, 4, 8])
+def test_queue_orders_at_any_address(gpu, oracle, max_chunks, offset):
+    """The queue-order array may start at any byte: rows of whole wavefronts are
+    put in place sixteen bytes at a time only where the address and the row
+    length allow it, four or one at a time otherwise. 64 * 9 + 11 scenarios:
+    whole wavefronts and a ragged last one; NPU counts that are not powers of
+    two leave some scenarios of a wavefront to the second kernel."""
+    import torch
+    b = w().mixed(64 * 9 + 11, seed=77 + max_chunks, max_chunks=max_chunks, pow2=False)
+    keep = np.arange(b.n) % 3 == 0          # two of three scenarios get powers of two
+    b.npus = np.where(keep[None, :], b.npus,
+                      1 << np.floor(np.log2(b.npus)).astype(np.int64)).astype(np.uint32)
+    _with_collective_types(b, 5)
+    o_orders, _ = oracle.plan_batch(b, threads=8)
+    o_t, o_qo, _ = oracle.simulate_batch(b, o_orders, threads=8)
+    d = gpu.to_device(b)
+    orders, _ = gpu.themis_plan_batch(d)
+    assert gpu.themis_queue_entry_bytes(max_chunks) == 1
+    row = 4 * 2 * d.slots
+    raw = torch.full((b.n * row + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    qo = raw[offset:offset + b.n * row].view(b.n, 4, 2 * d.slots)
+    ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(d.n, d.max_chunks))
+    t, _, _ = gpu.themis_simulate_batch(d, orders, queue_order=qo, workspace=ws)
+    torch.cuda.synchronize()
+    assert_close("t_done", t.cpu().numpy(), o_t)
+    assert np.array_equal(widen_queue(qo), o_qo)
+    host = raw.cpu().numpy()   # nothing outside the array was touched
+    assert (host[:offset] == 0x5A).all() and (host[offset + b.n * row:] == 0x5A).all()
+
+
 @pytest.mark.parametrize("max_chunks", [1, 7, 16, 17])
 def test_small_chunk_counts(gpu, oracle, max_chunks):
     """C up to 16 runs on the 48-dword LDS layout (13 wavefronts per CU); 17 is
