@@ -222,7 +222,11 @@ int themis_plan_batch(const themis_batch_t *batch, uint8_t *orders,
  *                 codes, e.g. themis_plan_batch's output; any permutation
  *                 code is accepted, a malformed one invalidates the scenario.
  *   t_done      : [n] completion time of the last stage.
- *   queue_order : NULL, or [n][4][2*slots] entries (see above).
+ *   queue_order : NULL, or [n][4][2*slots] entries (see above).  The array
+ *                 also serves as staging while the call runs (rows are put in
+ *                 place at the end), so it holds the result only once the
+ *                 call's work on the stream is complete, like every output,
+ *                 and it must not overlap any other argument.
  *   busy        : NULL, or [4][n] seconds each dimension spent serving.
  *   workspace, workspace_bytes : see themis_workspace_bytes().
  * A scenario whose stage times or clock overflow binary64 (bandwidths or

@@ -221,11 +221,11 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
   bool ok = collectives_ok(b, tv, i, Q) && s.valid;
 
   // Queue orders of a wavefront whose 64 scenarios all exist are staged
-  // transposed inside the wavefront's own block of the output (see FastOut)
-  // and put in place once the wavefront is through: a lane appends a dword to
-  // each of its four rows every few events, and with the rows in place the
+  // transposed inside the wavefront's own block of the output (kStagedBytes)
+  // and put in place once the wavefront is through: a lane appends an entry to
+  // one of its four rows at every event, and with the rows in place the
   // partly written lines of all resident wavefronts do not fit the L2, so they
-  // went to memory several times over.
+  // go to memory several times over.
   // dwords per row that the last step holds in registers (a row has up to kCap / 2)
   constexpr uint32_t kStagedWords = L::kCap / 2u < 32u ? L::kCap / 2u : 32u;
   const uint32_t rows_bytes = (uint32_t)kMaxDims * 2u * tv.slots * (uint32_t)entry_bytes;
@@ -287,11 +287,15 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       FastOut fo;
       fo.queue_order = (uint8_t*)out.queue_order;
       fo.slots = tv.slots;
-      if (staged) {
+      if (staged)
         fo.queue_order = (uint8_t*)queue_order + (size_t)blockIdx.x * kBlock * rows_bytes + 4u * threadIdx.x;
-        fo.word_stride = 4u * kBlock;
+      FastResult r;
+      if constexpr (kQueueOrder == kWords && !L::kPacked) {
+        r = staged ? simulate_pow2<L, kStagedBytes, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo)
+                   : simulate_pow2<L, kWords, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
+      } else {
+        r = simulate_pow2<L, kQueueOrder, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
       }
-      FastResult r = simulate_pow2<L, kQueueOrder, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
       if (r.ok) {
         t_done[i] = r.t_done;
         if (busy) {

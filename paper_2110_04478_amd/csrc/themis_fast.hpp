@@ -320,15 +320,10 @@ __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario&
 // Queue simulation.
 // ---------------------------------------------------------------------------
 struct FastOut {
-  uint8_t* queue_order;  // this evaluation's [4][2*slots] entries, or null
+  // kStagedBytes: the lane's first byte inside its wavefront's staging block,
+  // else this evaluation's [4][2*slots] entries; or null
+  uint8_t* queue_order;
   uint32_t slots;
-  // kWords only: bytes from one dword of the evaluation's rows to the next.
-  // 4: the rows lie as the caller sees them.  256: they are staged transposed
-  // inside the wavefront's block of the output (dword w of lane L at
-  // (w * 64 + L) * 4 from queue_order - 4 * L), so that the dwords the lanes
-  // of a wavefront store at about the same time share cache lines; whoever
-  // asks for that puts the rows in place afterwards.
-  uint32_t word_stride = 4;
 };
 
 struct FastResult {
@@ -365,13 +360,19 @@ __device__ __forceinline__ double min_f64(double a, double b) {
   return r;
 }
 
-// How the per-dimension queue orders leave the kernel.  Every lane appends
-// entries to its own four rows, so stores never coalesce across lanes.
-// kBytes / kShorts store each 8- / 16-bit entry as it is produced; kWords
-// (8-bit entries) collects four entries per dimension in a register and
-// stores them as one aligned dword (a quarter of the memory transactions),
-// and needs rows that start on a 4-byte boundary (an even number of slots).
-enum QueueOrderMode { kNoQueueOrder = 0, kBytes = 1, kWords = 2, kShorts = 3 };
+// How the per-dimension queue orders leave the kernel.
+// kBytes / kShorts store each 8- / 16-bit entry into the lane's own rows as
+// it is produced.  kWords (8-bit entries) collects four entries per dimension
+// in a register and stores them as one aligned dword (a quarter of the memory
+// transactions); it needs rows that start on a 4-byte boundary (an even number
+// of slots).  Either way every lane appends to its own four rows, so the
+// stores of a wavefront never share a cache line.  kStagedBytes (8-bit
+// entries, whole wavefronts) stores each entry into a staging order inside
+// the wavefront's own block of the output: dword w of lane L's rows (four
+// entries) at byte (w * 64 + L) * 4, so that the entries the 64 lanes store at
+// about the same time share cache lines; whoever asks for it puts the rows in
+// place afterwards.
+enum QueueOrderMode { kNoQueueOrder = 0, kBytes = 1, kWords = 2, kShorts = 3, kStagedBytes = 4 };
 
 // What the event loop needs to know about sizes and times, for scenarios with
 // power-of-two NPU counts: the resident size is base * 2^-E(mask), so a stage
@@ -510,14 +511,17 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
           if (pos < row_len) out.queue_order[k * row_len + pos] = (uint8_t)entry;
         } else if (kQueueOrder == kShorts) {
           if (pos < row_len) ((uint16_t*)out.queue_order)[k * row_len + pos] = (uint16_t)entry;
+        } else if (kQueueOrder == kStagedBytes) {
+          // byte pos & 3 of dword pos >> 2 of row k; consecutive dwords of a lane lie 256 bytes apart
+          if (pos < row_len)
+            out.queue_order[((__umul24(k, out.slots >> 1) + (pos >> 2)) << 8) | (pos & 3u)] = (uint8_t)entry;
         } else {
           // shift the entry in from the top: after four entries the register
           // holds them in memory (little-endian) order
           const uint32_t a = __builtin_amdgcn_alignbit(entry, sel4((int)k, a0, a1, a2, a3), 8u);
           a0 = k0 ? a : a0; a1 = k1 ? a : a1; a2 = k2 ? a : a2; a3 = k3 ? a : a3;
           if ((pos & 3u) == 3u && pos < row_len)
-            *(uint32_t*)(out.queue_order +
-                         __umul24(__umul24(k, out.slots >> 1) + (pos >> 2), out.word_stride)) = a;
+            ((uint32_t*)out.queue_order)[__umul24(k, out.slots >> 1) + (pos >> 2)] = a;
         }
       }
       executed.inc(k);
@@ -570,7 +574,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
       const uint32_t n = executed.get(k);
       const uint32_t rem = n & 3u;
       if (rem != 0u && n < row_len)
-        *(uint32_t*)(out.queue_order + __umul24(__umul24(k, out.slots >> 1) + (n >> 2), out.word_stride)) =
+        ((uint32_t*)out.queue_order)[__umul24(k, out.slots >> 1) + (n >> 2)] =
             (acc[k] >> (8u * (4u - rem))) | (0xffffffffu << (8u * rem));
     }
   }
