@@ -330,6 +330,8 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       // all of them in registers, and writes them where they belong, with
       // all-ones from the first unused entry on
       const uint32_t wpr = tv.slots >> 1;  // dwords per row
+      // the entries a lane fetches were stored by other lanes of its wavefront
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
       const uint32_t* from =
           (const uint32_t*)((uint8_t*)queue_order + (size_t)blockIdx.x * kBlock * rows_bytes) + threadIdx.x;
       uint32_t q[kMaxDims][kStagedWords];
