@@ -290,11 +290,14 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       FastOut fo;
       fo.queue_order = (uint8_t*)out.queue_order;
       fo.slots = tv.slots;
-      if (staged)
-        fo.queue_order = (uint8_t*)queue_order + (size_t)blockIdx.x * kBlock * rows_bytes + 4u * threadIdx.x;
+      // staged: the same address for all lanes plus a 32-bit offset
+      FastOut so;
+      so.queue_order = (uint8_t*)queue_order + (size_t)blockIdx.x * kBlock * rows_bytes;
+      so.slots = tv.slots;
+      so.lane_offset = 4u * threadIdx.x;
       FastResult r;
       if constexpr (kQueueOrder == kWords && !L::kPacked) {
-        r = staged ? simulate_pow2<L, kStagedBytes, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo)
+        r = staged ? simulate_pow2<L, kStagedBytes, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, so)
                    : simulate_pow2<L, kWords, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
       } else {
         r = simulate_pow2<L, kQueueOrder, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, fo);

@@ -193,7 +193,7 @@ __device__ __forceinline__ double scale_down(double x, uint32_t e) {
 
 // Sum of e_k over the dimensions in mask.
 __device__ __forceinline__ uint32_t esum(uint32_t epack, uint32_t mask) {
-  uint32_t spread = (mask * 0x00204081u) & 0x01010101u;  // bit k -> byte k
+  uint32_t spread = __umul24(mask, 0x00204081u) & 0x01010101u;  // bit k -> byte k (mask < 16)
   return __builtin_amdgcn_udot4(spread, epack, 0u, false);  // sum of byte products
 }
 
@@ -324,6 +324,7 @@ struct FastOut {
   // else this evaluation's [4][2*slots] entries; or null
   uint8_t* queue_order;
   uint32_t slots;
+  uint32_t lane_offset = 0;  // kStagedBytes: added to every offset from queue_order
 };
 
 struct FastResult {
@@ -352,8 +353,8 @@ __device__ __forceinline__ uint64_t build_rank_table(uint32_t epack, bool scf) {
   return tab;
 }
 
-// min of two non-NaN doubles in one instruction (fmin() would first
-// canonicalise both operands).
+// Minimum of two doubles in one instruction (fmin() would first canonicalise
+// both operands); of a quiet NaN and a number it returns the number.
 __device__ __forceinline__ double min_f64(double a, double b) {
   double r;
   asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
@@ -428,7 +429,14 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
   const uint32_t full = (1u << D) - 1u;
   const double kInf = inf64();
 
-  double f0 = kInf, f1 = kInf, f2 = kInf, f3 = kInf;  // finish time, +inf = idle
+  // finish time; a NaN = idle (the minimum instruction skips a quiet NaN
+  // operand, and putting one in the upper half of the register pair is all it
+  // takes to mark a dimension idle)
+  const double kIdle = nan64();
+  double f0 = kIdle, f1 = kIdle, f2 = kIdle, f3 = kIdle;
+  auto idle_if = [](bool d, double f) {
+    return __hiloint2double(d ? 0x7ff80000 : __double2hiint(f), __double2loint(f));
+  };
   double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
   typename L::Ids serving;   // per dimension: chunk id << 2 | dimension
   typename L::Ids executed;  // operations started per dimension
@@ -513,8 +521,10 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
           if (pos < row_len) ((uint16_t*)out.queue_order)[k * row_len + pos] = (uint16_t)entry;
         } else if (kQueueOrder == kStagedBytes) {
           // byte pos & 3 of dword pos >> 2 of row k; consecutive dwords of a lane lie 256 bytes apart
-          if (pos < row_len)
-            out.queue_order[((__umul24(k, out.slots >> 1) + (pos >> 2)) << 8) | (pos & 3u)] = (uint8_t)entry;
+          const uint32_t at = min(pos, row_len - 1u);  // pos < row_len for a consistent plan
+          uint32_t word;  // k * dwords per row + at / 4 (a full-rate multiply-add)
+          asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(word) : "v"(k), "v"(out.slots >> 1), "v"(at >> 2));
+          out.queue_order[((word << 8) | (at & 3u)) + out.lane_offset] = (uint8_t)entry;
         } else {
           // shift the entry in from the top: after four entries the register
           // holds them in memory (little-endian) order
@@ -531,11 +541,11 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
 
     // a8: advance to the earliest completion
     const double next = min_f64(min_f64(f0, f1), min_f64(f2, f3));
-    if (!(next < kInf)) break;  // nothing running: every chunk is done
+    if (!(next < kInf)) break;  // NaN: nothing running, every chunk is done (+inf: overflow)
     now = next;
     const bool d0 = f0 == now, d1 = f1 == now, d2 = f2 == now, d3 = f3 == now;
     uint32_t done = (d0 ? 1u : 0u) | (d1 ? 2u : 0u) | (d2 ? 4u : 0u) | (d3 ? 8u : 0u);
-    f0 = d0 ? kInf : f0; f1 = d1 ? kInf : f1; f2 = d2 ? kInf : f2; f3 = d3 ? kInf : f3;
+    f0 = idle_if(d0, f0); f1 = idle_if(d1, f1); f2 = idle_if(d2, f2); f3 = idle_if(d3, f3);
     idle |= done;
     // deliver all completions of this instant, lowest chunk id first, so that
     // equal arrival times are appended in chunk-id order: the smallest
