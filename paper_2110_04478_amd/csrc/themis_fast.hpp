@@ -361,6 +361,89 @@ __device__ __forceinline__ double min_f64(double a, double b) {
   return r;
 }
 
+// Dimension k (0..3, differing from lane to lane) starts a stage at `now`:
+//   t = [fix_k +] x * coef_k   (start_stage_scaled)   or   t given (start_stage)
+//   f_k = now + t   and, with kBusy,   z_k = z_k + t.
+// Registers cannot be indexed by a lane's own k, and as selects this takes two
+// per double and dimension (choosing coef_k, storing f_k, adding to z_k); here
+// the lanes with k == j are made the active ones in turn, j = 0..3, and do
+// their arithmetic on dimension j's registers directly.  The operations and
+// their order are those of the plain code, so the results are bit-identical.
+#define THEMIS_LANES_OF(J) "v_cmpx_eq_u32_e32 vcc, " #J ", %[k]\n\t"
+#define THEMIS_ALL_LANES "s_mov_b64 exec, %[act]\n\t"
+#define THEMIS_FOUR(BODY) "s_mov_b64 %[act], exec\n\t" BODY(0) BODY(1) BODY(2) BODY(3)
+
+#define THEMIS_GIVEN(J) \
+  THEMIS_LANES_OF(J) "v_add_f64 %[f" #J "], %[now], %[t]\n\t" THEMIS_ALL_LANES
+#define THEMIS_GIVEN_BUSY(J) \
+  THEMIS_LANES_OF(J) "v_add_f64 %[f" #J "], %[now], %[t]\n\t" \
+  "v_add_f64 %[z" #J "], %[z" #J "], %[t]\n\t" THEMIS_ALL_LANES
+#define THEMIS_SCALED(J) \
+  THEMIS_LANES_OF(J) "v_mul_f64 %[t], %[x], %[c" #J "]\n\t" \
+  "v_add_f64 %[f" #J "], %[now], %[t]\n\t" THEMIS_ALL_LANES
+#define THEMIS_SCALED_BUSY(J) \
+  THEMIS_LANES_OF(J) "v_mul_f64 %[t], %[x], %[c" #J "]\n\t" \
+  "v_add_f64 %[f" #J "], %[now], %[t]\n\t" \
+  "v_add_f64 %[z" #J "], %[z" #J "], %[t]\n\t" THEMIS_ALL_LANES
+#define THEMIS_SCALED_FIX(J) \
+  THEMIS_LANES_OF(J) "v_mul_f64 %[t], %[x], %[c" #J "]\n\t" \
+  "v_add_f64 %[t], %[a" #J "], %[t]\n\t" \
+  "v_add_f64 %[f" #J "], %[now], %[t]\n\t" THEMIS_ALL_LANES
+#define THEMIS_SCALED_FIX_BUSY(J) \
+  THEMIS_LANES_OF(J) "v_mul_f64 %[t], %[x], %[c" #J "]\n\t" \
+  "v_add_f64 %[t], %[a" #J "], %[t]\n\t" \
+  "v_add_f64 %[f" #J "], %[now], %[t]\n\t" \
+  "v_add_f64 %[z" #J "], %[z" #J "], %[t]\n\t" THEMIS_ALL_LANES
+
+#define THEMIS_F_OPERANDS [f0] "+v"(f0), [f1] "+v"(f1), [f2] "+v"(f2), [f3] "+v"(f3)
+#define THEMIS_Z_OPERANDS [z0] "+v"(z0), [z1] "+v"(z1), [z2] "+v"(z2), [z3] "+v"(z3)
+#define THEMIS_C_OPERANDS [c0] "v"(c[0]), [c1] "v"(c[1]), [c2] "v"(c[2]), [c3] "v"(c[3])
+#define THEMIS_A_OPERANDS [a0] "v"(a[0]), [a1] "v"(a[1]), [a2] "v"(a[2]), [a3] "v"(a[3])
+
+template <bool kBusy>
+__device__ __forceinline__ void start_stage(uint32_t k, double now, double t, double& f0, double& f1,
+                                            double& f2, double& f3, double& z0, double& z1,
+                                            double& z2, double& z3) {
+  uint64_t act;  // the lanes that are here
+  if (kBusy) {
+    asm(THEMIS_FOUR(THEMIS_GIVEN_BUSY)
+        : [act] "=&s"(act), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS
+        : [k] "v"(k), [now] "v"(now), [t] "v"(t) : "vcc");
+  } else {
+    asm(THEMIS_FOUR(THEMIS_GIVEN)
+        : [act] "=&s"(act), THEMIS_F_OPERANDS
+        : [k] "v"(k), [now] "v"(now), [t] "v"(t) : "vcc");
+  }
+}
+
+// c[]: per-byte latencies (coef), a[]: fixed delays per stage (used with kFix).
+template <bool kBusy, bool kFix>
+__device__ __forceinline__ void start_stage_scaled(uint32_t k, double now, double x,
+                                                   const double (&c)[kMaxDims],
+                                                   const double (&a)[kMaxDims], double& f0,
+                                                   double& f1, double& f2, double& f3, double& z0,
+                                                   double& z1, double& z2, double& z3) {
+  uint64_t act;
+  double t;
+  if (kBusy && kFix) {
+    asm(THEMIS_FOUR(THEMIS_SCALED_FIX_BUSY)
+        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS
+        : [k] "v"(k), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS, THEMIS_A_OPERANDS : "vcc");
+  } else if (kBusy) {
+    asm(THEMIS_FOUR(THEMIS_SCALED_BUSY)
+        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS
+        : [k] "v"(k), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
+  } else if (kFix) {
+    asm(THEMIS_FOUR(THEMIS_SCALED_FIX)
+        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS
+        : [k] "v"(k), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS, THEMIS_A_OPERANDS : "vcc");
+  } else {
+    asm(THEMIS_FOUR(THEMIS_SCALED)
+        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS
+        : [k] "v"(k), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
+  }
+}
+
 // How the per-dimension queue orders leave the kernel.
 // kBytes / kShorts store each 8- / 16-bit entry into the lane's own rows as
 // it is produced.  kWords (8-bit entries) collects four entries per dimension
@@ -394,9 +477,12 @@ struct Pow2Model {
   // bytes moved on k = resident size before the chunk's Reduce-Scatter on k,
   // i.e. with every reduced dimension but k itself taken off; the All-Gather
   // reuses it (its mask still contains k)
+  static constexpr bool kScaledProduct = true;  // stage time = stage_bytes() * coef[k]
+  __device__ __forceinline__ double stage_bytes(uint32_t kbit, uint32_t w) const {
+    return scale_down(fs.base, esum(fs.epack, w & 15u & ~kbit));
+  }
   __device__ __forceinline__ double stage_time(uint32_t k, uint32_t kbit, uint32_t w) const {
-    const uint32_t E = esum(fs.epack, w & 15u & ~kbit);
-    return scale_down(fs.base, E) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
+    return stage_bytes(kbit, w) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
   }
   // size class of a chunk (word w) once its state is (mask, phase)
   __device__ __forceinline__ uint32_t size_class(uint32_t, uint32_t mask, uint32_t) const {
@@ -500,16 +586,16 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
       idle &= ~kbit;
 
       const uint32_t phase = (w >> 4) & 1u;
-      double t = model.stage_time(k, kbit, w);
-      if (kFix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
-      const double f = now + t;
-      const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
-      f0 = k0 ? f : f0; f1 = k1 ? f : f1; f2 = k2 ? f : f2; f3 = k3 ? f : f3;
-      if (kBusy) {
-        // z_j + t * [k == j]: one rounding of the exact sum, the same as z_j + t
-        z0 = __builtin_fma(t, k0 ? 1.0 : 0.0, z0); z1 = __builtin_fma(t, k1 ? 1.0 : 0.0, z1);
-        z2 = __builtin_fma(t, k2 ? 1.0 : 0.0, z2); z3 = __builtin_fma(t, k3 ? 1.0 : 0.0, z3);
+      if constexpr (Model::kScaledProduct) {
+        // t = bytes * coef_k, picked per lane inside
+        start_stage_scaled<kBusy, kFix>(k, now, model.stage_bytes(kbit, w), s.coef, s.fix,
+                                        f0, f1, f2, f3, z0, z1, z2, z3);
+      } else {
+        double t = model.stage_time(k, kbit, w);
+        if (kFix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
+        start_stage<kBusy>(k, now, t, f0, f1, f2, f3, z0, z1, z2, z3);
       }
+      const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
       serving.set(k, (h << 2) | k);
       if (kQueueOrder != kNoQueueOrder) {
         const uint32_t pos = executed.get(k);
@@ -523,7 +609,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
           // byte pos & 3 of dword pos >> 2 of row k; consecutive dwords of a lane lie 256 bytes apart
           const uint32_t at = min(pos, row_len - 1u);  // pos < row_len for a consistent plan
           uint32_t word;  // k * dwords per row + at / 4 (a full-rate multiply-add)
-          asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(word) : "v"(k), "v"(out.slots >> 1), "v"(at >> 2));
+          asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(word) : "v"(k), "s"(out.slots >> 1), "v"(at >> 2));
           out.queue_order[((word << 8) | (at & 3u)) + out.lane_offset] = (uint8_t)entry;
         } else {
           // shift the entry in from the top: after four entries the register

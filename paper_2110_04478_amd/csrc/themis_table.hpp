@@ -61,6 +61,7 @@ struct TableModel {
   __device__ __forceinline__ bool rs_only() const { return rs; }
   __device__ __forceinline__ bool one_phase() const { return rs || gather; }
   __device__ __forceinline__ uint32_t keep(uint32_t w) const { return w & 0xe0u; }
+  static constexpr bool kScaledProduct = false;  // stage times come from stage_time()
   __device__ __forceinline__ double stage_time(uint32_t, uint32_t, uint32_t w) const {
     // RS: the next dimension of the order; AG: the last one still reduced
     const uint32_t pos = (uint32_t)__builtin_popcount(w & 15u) - ((w >> 4) & 1u);
@@ -293,6 +294,7 @@ struct DivModelT {
     const uint32_t k = (code >> (2u * pos)) & 3u;
     return x * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
   }
+  static constexpr bool kScaledProduct = false;  // stage times come from stage_time()
   __device__ __forceinline__ double stage_time(uint32_t, uint32_t, uint32_t w) const {
     const uint32_t pos = ((uint32_t)__builtin_popcount(w & 15u) - ((w >> 4) & 1u)) & 3u;
     return time_at(LT::code(w), pos);
