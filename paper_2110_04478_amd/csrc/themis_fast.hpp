@@ -372,76 +372,100 @@ __device__ __forceinline__ double min_f64(double a, double b) {
 #define THEMIS_LANES_OF(J) "v_cmpx_eq_u32_e32 vcc, " #J ", %[k]\n\t"
 #define THEMIS_ALL_LANES "s_mov_b64 exec, %[act]\n\t"
 #define THEMIS_FOUR(BODY) "s_mov_b64 %[act], exec\n\t" BODY(0) BODY(1) BODY(2) BODY(3)
+#define THEMIS_MUL(J) "v_mul_f64 %[t], %[x], %[c" #J "]\n\t"
+#define THEMIS_FIX(J) "v_add_f64 %[t], %[a" #J "], %[t]\n\t"
+#define THEMIS_END(J) "v_add_f64 %[f" #J "], %[now], %[t]\n\t"
+#define THEMIS_BUSY(J) "v_add_f64 %[z" #J "], %[z" #J "], %[t]\n\t"
+#define THEMIS_SERVE(J) "v_mov_b32_e32 %[s" #J "], %[val]\n\t"
 
-#define THEMIS_GIVEN(J) \
-  THEMIS_LANES_OF(J) "v_add_f64 %[f" #J "], %[now], %[t]\n\t" THEMIS_ALL_LANES
+#define THEMIS_GIVEN(J) THEMIS_LANES_OF(J) THEMIS_END(J) THEMIS_SERVE(J) THEMIS_ALL_LANES
 #define THEMIS_GIVEN_BUSY(J) \
-  THEMIS_LANES_OF(J) "v_add_f64 %[f" #J "], %[now], %[t]\n\t" \
-  "v_add_f64 %[z" #J "], %[z" #J "], %[t]\n\t" THEMIS_ALL_LANES
+  THEMIS_LANES_OF(J) THEMIS_END(J) THEMIS_BUSY(J) THEMIS_SERVE(J) THEMIS_ALL_LANES
 #define THEMIS_SCALED(J) \
-  THEMIS_LANES_OF(J) "v_mul_f64 %[t], %[x], %[c" #J "]\n\t" \
-  "v_add_f64 %[f" #J "], %[now], %[t]\n\t" THEMIS_ALL_LANES
+  THEMIS_LANES_OF(J) THEMIS_MUL(J) THEMIS_END(J) THEMIS_SERVE(J) THEMIS_ALL_LANES
 #define THEMIS_SCALED_BUSY(J) \
-  THEMIS_LANES_OF(J) "v_mul_f64 %[t], %[x], %[c" #J "]\n\t" \
-  "v_add_f64 %[f" #J "], %[now], %[t]\n\t" \
-  "v_add_f64 %[z" #J "], %[z" #J "], %[t]\n\t" THEMIS_ALL_LANES
+  THEMIS_LANES_OF(J) THEMIS_MUL(J) THEMIS_END(J) THEMIS_BUSY(J) THEMIS_SERVE(J) THEMIS_ALL_LANES
 #define THEMIS_SCALED_FIX(J) \
-  THEMIS_LANES_OF(J) "v_mul_f64 %[t], %[x], %[c" #J "]\n\t" \
-  "v_add_f64 %[t], %[a" #J "], %[t]\n\t" \
-  "v_add_f64 %[f" #J "], %[now], %[t]\n\t" THEMIS_ALL_LANES
-#define THEMIS_SCALED_FIX_BUSY(J) \
-  THEMIS_LANES_OF(J) "v_mul_f64 %[t], %[x], %[c" #J "]\n\t" \
-  "v_add_f64 %[t], %[a" #J "], %[t]\n\t" \
-  "v_add_f64 %[f" #J "], %[now], %[t]\n\t" \
-  "v_add_f64 %[z" #J "], %[z" #J "], %[t]\n\t" THEMIS_ALL_LANES
+  THEMIS_LANES_OF(J) THEMIS_MUL(J) THEMIS_FIX(J) THEMIS_END(J) THEMIS_SERVE(J) THEMIS_ALL_LANES
+#define THEMIS_SCALED_FIX_BUSY(J)                                                        \
+  THEMIS_LANES_OF(J) THEMIS_MUL(J) THEMIS_FIX(J) THEMIS_END(J) THEMIS_BUSY(J) THEMIS_SERVE(J) \
+  THEMIS_ALL_LANES
 
-#define THEMIS_F_OPERANDS [f0] "+v"(f0), [f1] "+v"(f1), [f2] "+v"(f2), [f3] "+v"(f3)
-#define THEMIS_Z_OPERANDS [z0] "+v"(z0), [z1] "+v"(z1), [z2] "+v"(z2), [z3] "+v"(z3)
+#define THEMIS_F_OPERANDS [f0] "+v"(d.f0), [f1] "+v"(d.f1), [f2] "+v"(d.f2), [f3] "+v"(d.f3)
+#define THEMIS_Z_OPERANDS [z0] "+v"(d.z0), [z1] "+v"(d.z1), [z2] "+v"(d.z2), [z3] "+v"(d.z3)
+#define THEMIS_S_OPERANDS [s0] "+v"(d.s0), [s1] "+v"(d.s1), [s2] "+v"(d.s2), [s3] "+v"(d.s3)
 #define THEMIS_C_OPERANDS [c0] "v"(c[0]), [c1] "v"(c[1]), [c2] "v"(c[2]), [c3] "v"(c[3])
 #define THEMIS_A_OPERANDS [a0] "v"(a[0]), [a1] "v"(a[1]), [a2] "v"(a[2]), [a3] "v"(a[3])
 
+// What the event loop keeps per dimension, one register (pair) each.
+struct DimState {
+  double f0, f1, f2, f3;    // finish time of the running stage, a quiet NaN when idle
+  double z0, z1, z2, z3;    // busy time
+  uint32_t s0, s1, s2, s3;  // the running stage: chunk id << 2 | dimension
+};
+
 template <bool kBusy>
-__device__ __forceinline__ void start_stage(uint32_t k, double now, double t, double& f0, double& f1,
-                                            double& f2, double& f3, double& z0, double& z1,
-                                            double& z2, double& z3) {
+__device__ __forceinline__ void start_stage(uint32_t k, uint32_t val, double now, double t,
+                                            DimState& d) {
   uint64_t act;  // the lanes that are here
   if (kBusy) {
     asm(THEMIS_FOUR(THEMIS_GIVEN_BUSY)
-        : [act] "=&s"(act), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS
-        : [k] "v"(k), [now] "v"(now), [t] "v"(t) : "vcc");
+        : [act] "=&s"(act), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [t] "v"(t) : "vcc");
   } else {
     asm(THEMIS_FOUR(THEMIS_GIVEN)
-        : [act] "=&s"(act), THEMIS_F_OPERANDS
-        : [k] "v"(k), [now] "v"(now), [t] "v"(t) : "vcc");
+        : [act] "=&s"(act), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [t] "v"(t) : "vcc");
   }
 }
 
 // c[]: per-byte latencies (coef), a[]: fixed delays per stage (used with kFix).
 template <bool kBusy, bool kFix>
-__device__ __forceinline__ void start_stage_scaled(uint32_t k, double now, double x,
+__device__ __forceinline__ void start_stage_scaled(uint32_t k, uint32_t val, double now, double x,
                                                    const double (&c)[kMaxDims],
-                                                   const double (&a)[kMaxDims], double& f0,
-                                                   double& f1, double& f2, double& f3, double& z0,
-                                                   double& z1, double& z2, double& z3) {
+                                                   const double (&a)[kMaxDims], DimState& d) {
   uint64_t act;
   double t;
   if (kBusy && kFix) {
     asm(THEMIS_FOUR(THEMIS_SCALED_FIX_BUSY)
-        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS
-        : [k] "v"(k), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS, THEMIS_A_OPERANDS : "vcc");
+        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
+          THEMIS_A_OPERANDS : "vcc");
   } else if (kBusy) {
     asm(THEMIS_FOUR(THEMIS_SCALED_BUSY)
-        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS
-        : [k] "v"(k), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
+        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
   } else if (kFix) {
     asm(THEMIS_FOUR(THEMIS_SCALED_FIX)
-        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS
-        : [k] "v"(k), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS, THEMIS_A_OPERANDS : "vcc");
+        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
+          THEMIS_A_OPERANDS : "vcc");
   } else {
     asm(THEMIS_FOUR(THEMIS_SCALED)
-        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS
-        : [k] "v"(k), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
+        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
   }
+}
+
+// The clock has moved to `now`: every dimension whose stage ends now becomes
+// idle.  Returns the bits of those dimensions and, in `first`, the smallest
+// chunk id << 2 | dimension among their stages (all-ones if there is none).
+#define THEMIS_ENDS_NOW(J, BIT)                          \
+  "v_cmpx_eq_f64_e32 vcc, %[now], %[f" #J "]\n\t"       \
+  "v_mov_b64_e32 %[f" #J "], %[nan]\n\t"                \
+  "v_min_u32_e32 %[first], %[first], %[s" #J "]\n\t"    \
+  "v_or_b32_e32 %[done], " #BIT ", %[done]\n\t" THEMIS_ALL_LANES
+__device__ __forceinline__ uint32_t stages_ending(double now, DimState& d, uint32_t& first) {
+  uint64_t act;
+  uint32_t done = 0u;
+  first = ~0u;
+  asm("s_mov_b64 %[act], exec\n\t"
+      THEMIS_ENDS_NOW(0, 1) THEMIS_ENDS_NOW(1, 2) THEMIS_ENDS_NOW(2, 4) THEMIS_ENDS_NOW(3, 8)
+      : [act] "=&s"(act), [done] "+v"(done), [first] "+v"(first), THEMIS_F_OPERANDS
+      : [now] "v"(now), [nan] "v"(nan64()), [s0] "v"(d.s0), [s1] "v"(d.s1), [s2] "v"(d.s2),
+        [s3] "v"(d.s3)
+      : "vcc");
+  return done;
 }
 
 // How the per-dimension queue orders leave the kernel.
@@ -515,16 +539,12 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
   const uint32_t full = (1u << D) - 1u;
   const double kInf = inf64();
 
-  // finish time; a NaN = idle (the minimum instruction skips a quiet NaN
-  // operand, and putting one in the upper half of the register pair is all it
-  // takes to mark a dimension idle)
-  const double kIdle = nan64();
-  double f0 = kIdle, f1 = kIdle, f2 = kIdle, f3 = kIdle;
-  auto idle_if = [](bool d, double f) {
-    return __hiloint2double(d ? 0x7ff80000 : __double2hiint(f), __double2loint(f));
-  };
-  double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
-  typename L::Ids serving;   // per dimension: chunk id << 2 | dimension
+  // an idle dimension's finish time is a quiet NaN: the minimum instruction
+  // skips it, and no comparison with the clock holds
+  DimState d;
+  d.f0 = d.f1 = d.f2 = d.f3 = nan64();
+  d.z0 = d.z1 = d.z2 = d.z3 = 0.0;
+  d.s0 = d.s1 = d.s2 = d.s3 = 0u;
   typename L::Ids executed;  // operations started per dimension
   typename L::Classes classes(lds);  // which list q = kPerDim*dim + class holds chunks
   constexpr uint32_t kPerDim = L::Classes::kPerDim;
@@ -588,15 +608,14 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
       const uint32_t phase = (w >> 4) & 1u;
       if constexpr (Model::kScaledProduct) {
         // t = bytes * coef_k, picked per lane inside
-        start_stage_scaled<kBusy, kFix>(k, now, model.stage_bytes(kbit, w), s.coef, s.fix,
-                                        f0, f1, f2, f3, z0, z1, z2, z3);
+        start_stage_scaled<kBusy, kFix>(k, (h << 2) | k, now, model.stage_bytes(kbit, w), s.coef,
+                                        s.fix, d);
       } else {
         double t = model.stage_time(k, kbit, w);
         if (kFix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
-        start_stage<kBusy>(k, now, t, f0, f1, f2, f3, z0, z1, z2, z3);
+        start_stage<kBusy>(k, (h << 2) | k, now, t, d);
       }
       const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
-      serving.set(k, (h << 2) | k);
       if (kQueueOrder != kNoQueueOrder) {
         const uint32_t pos = executed.get(k);
         const uint32_t entry = (h << 1) | phase;
@@ -626,22 +645,17 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
     if (kOnePerPass && (idle & work) != 0u) continue;
 
     // a8: advance to the earliest completion
-    const double next = min_f64(min_f64(f0, f1), min_f64(f2, f3));
+    const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));
     if (!(next < kInf)) break;  // NaN: nothing running, every chunk is done (+inf: overflow)
     now = next;
-    const bool d0 = f0 == now, d1 = f1 == now, d2 = f2 == now, d3 = f3 == now;
-    uint32_t done = (d0 ? 1u : 0u) | (d1 ? 2u : 0u) | (d2 ? 4u : 0u) | (d3 ? 8u : 0u);
-    f0 = idle_if(d0, f0); f1 = idle_if(d1, f1); f2 = idle_if(d2, f2); f3 = idle_if(d3, f3);
-    idle |= done;
     // deliver all completions of this instant, lowest chunk id first, so that
-    // equal arrival times are appended in chunk-id order: the smallest
-    // (id << 2 | dimension) field among the dimensions that completed
-    auto keys = serving.v | blank_fields(serving, done);
-    do {
-      const uint32_t key = min_field(keys);
+    // equal arrival times are appended in chunk-id order
+    uint32_t key;
+    uint32_t done = stages_ending(now, d, key);
+    idle |= done;
+    for (;;) {
       const uint32_t k = key & 3u;
       const uint32_t c = key >> 2;
-      keys |= decltype(keys)(L::Ids::kMask) << (L::Ids::kFieldBits * k);
       done &= ~(1u << k);
       uint8_t* cp = lds.dword(c);
       const uint32_t w = *(const uint32_t*)cp;
@@ -658,7 +672,11 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
         L::store_state(cp, w, mask | (phase << 4) | model.keep(w));
         push(kPerDim * kn + model.size_class(w, mask, phase), c);
       }
-    } while (done);
+      if (done == 0u) break;
+      // one more stage ends at this very instant (rare): the smallest one left
+      key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
+                min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
+    }
   }
 
   if (kQueueOrder == kWords) {
@@ -686,7 +704,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
   const uint32_t stages = model.one_phase() ? D : 2u * D;
   res.ok = executed.sum() == stages * C && idle == full && (now + 0.25 * t_min > now);
   res.t_done = now;
-  res.busy[0] = z0; res.busy[1] = z1; res.busy[2] = z2; res.busy[3] = z3;
+  res.busy[0] = d.z0; res.busy[1] = d.z1; res.busy[2] = d.z2; res.busy[3] = d.z3;
 #pragma unroll
   for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) res.executed[k] = executed.get(k);
   return res;
