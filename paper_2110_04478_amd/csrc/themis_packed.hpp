@@ -87,14 +87,14 @@ __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const P
   const uint64_t ranktab = model.ranktab;
   const bool rs_only = model.rs_only();
 
-  double f0 = kInf, f1 = kInf, f2 = kInf, f3 = kInf;  // finish time, +inf = idle
-  double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
-  // per dimension, the stage it serves and what its completion does:
+  // per dimension (DimState::s0..s3), the stage it serves and what its
+  // completion does:
   //   bits 0-5 list to join, 6-11 upper record bits then, 12 chunk is done,
   //   13-14 the dimension, 15-23 the chunk
-  // (one register each: with one or two wavefronts per CU every instruction
-  // counts, and four selects are fewer than a 64-bit field insertion)
-  uint32_t v0 = 0, v1 = 0, v2 = 0, v3 = 0;
+  DimState d;
+  d.f0 = d.f1 = d.f2 = d.f3 = nan64();
+  d.z0 = d.z1 = d.z2 = d.z3 = 0.0;
+  d.s0 = d.s1 = d.s2 = d.s3 = 0u;
   typename L::Ids executed;  // operations started per dimension (kept when queue orders are written)
   uint32_t started = 0;      // operations started in all
   Classes16 classes(lds);
@@ -155,18 +155,6 @@ __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const P
       const bool p0 = k == ord.o0, p1 = k == ord.o1, p2 = k == ord.o2;
       const uint32_t before = p0 ? 0u : p1 ? (1u << ord.o0) : p2 ? ord.first_two
                                                                  : (ord.first_two | (1u << ord.o2));
-      // bytes moved on k = resident size before the chunk's Reduce-Scatter on
-      // k; the All-Gather on k reuses that time
-      double t = scale_down(model.fs.base, esum(epack, before)) *
-                 sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
-      if (kFix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
-      const double f = now + t;
-      const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
-      f0 = k0 ? f : f0; f1 = k1 ? f : f1; f2 = k2 ? f : f2; f3 = k3 ? f : f3;
-      if (kBusy) {
-        z0 = __builtin_fma(t, k0 ? 1.0 : 0.0, z0); z1 = __builtin_fma(t, k1 ? 1.0 : 0.0, z1);
-        z2 = __builtin_fma(t, k2 ? 1.0 : 0.0, z2); z3 = __builtin_fma(t, k3 ? 1.0 : 0.0, z3);
-      }
       // what the completion of this stage will do: a Reduce-Scatter adds k to
       // the reduced dimensions and goes on to the next one of the order, the
       // last one turns into the All-Gather on the same dimension; an
@@ -182,7 +170,10 @@ __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const P
         const uint32_t up = (w >> 9) | (last_rs ? 1u : 0u);
         const uint32_t qn = 16u * kn + ((uint32_t)(ranktab >> (4u * mask)) & 15u);
         const uint32_t v = qn | (up << 6) | (finished ? 0x1000u : 0u) | (k << 13) | (h << 15);
-        v0 = k0 ? v : v0; v1 = k1 ? v : v1; v2 = k2 ? v : v2; v3 = k3 ? v : v3;
+        // bytes moved on k = resident size before the chunk's Reduce-Scatter on
+        // k; the All-Gather on k reuses that time
+        start_stage_scaled<kBusy, kFix>(k, v, now, scale_down(model.fs.base, esum(epack, before)),
+                                        s.coef, s.fix, d);
       }
       if (kQueueOrder != kNoQueueOrder) {
         const uint32_t at = executed.get(k);
@@ -200,23 +191,21 @@ __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const P
     if ((idle & work) != 0u) continue;  // all stages of an instant start before the clock moves
 
     // a8: advance to the earliest completion
-    const double next = min_f64(min_f64(f0, f1), min_f64(f2, f3));
-    if (!(next < kInf)) break;  // nothing running: every chunk is done
+    const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));
+    if (!(next < kInf)) break;  // NaN: nothing running, every chunk is done (+inf: overflow)
     now = next;
-    const bool d0 = f0 == now, d1 = f1 == now, d2 = f2 == now, d3 = f3 == now;
-    uint32_t done = (d0 ? 1u : 0u) | (d1 ? 2u : 0u) | (d2 ? 4u : 0u) | (d3 ? 8u : 0u);
-    f0 = d0 ? kInf : f0; f1 = d1 ? kInf : f1; f2 = d2 ? kInf : f2; f3 = d3 ? kInf : f3;
-    idle |= done;
     // deliver all completions of this instant, lowest chunk id first, so that
     // equal arrival times are appended in chunk-id order
-    uint32_t g0 = d0 ? v0 : ~0u, g1 = d1 ? v1 : ~0u, g2 = d2 ? v2 : ~0u, g3 = d3 ? v3 : ~0u;
+    uint32_t g;
+    uint32_t done = stages_ending(now, d, g);
+    idle |= done;
     for (;;) {
-      const uint32_t g = min(min(g0, g1), min(g2, g3));
       if ((g & 0x1000u) == 0u) push(g & 63u, g >> 15, (g >> 6) & 63u);
       done &= ~(1u << ((g >> 13) & 3u));
       if (done == 0u) break;
-      g0 = g0 == g ? ~0u : g0; g1 = g1 == g ? ~0u : g1;
-      g2 = g2 == g ? ~0u : g2; g3 = g3 == g ? ~0u : g3;
+      // one more stage ends at this very instant (rare): the smallest one left
+      g = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
+              min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
     }
   }
 
@@ -227,7 +216,7 @@ __device__ __forceinline__ FastResult simulate_packed(const Scenario& s, const P
   const uint32_t stages = model.one_phase() ? D : 2u * D;
   res.ok = started == stages * C && idle == full && (now + 0.25 * t_min > now);
   res.t_done = now;
-  res.busy[0] = z0; res.busy[1] = z1; res.busy[2] = z2; res.busy[3] = z3;
+  res.busy[0] = d.z0; res.busy[1] = d.z1; res.busy[2] = d.z2; res.busy[3] = d.z3;
 #pragma unroll
   for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) res.executed[k] = executed.get(k);
   return res;
