@@ -43,7 +43,7 @@ def algorithmic_lane_ops(D, C):
 # line when the run uses that workload.
 PROFILED = {
     "traffic_bytes_per_launch": 1.78e9,   # FETCH_SIZE x2.0 + WRITE_SIZE x1.0, simulate kernel
-    "valu_issue_frac": 0.723,             # SQ_ACTIVE_INST_VALU / (256 CUs x busy cycles)
+    "valu_issue_frac": 0.672,             # SQ_ACTIVE_INST_VALU / (256 CUs x busy cycles)
 }
 
 
