@@ -193,11 +193,11 @@ __device__ __forceinline__ void init_chunk(const LaneLds& lds, uint32_t c, uint3
 }
 
 // The power-of-two event loop that goes with the layout.
-template <typename L, int kQueueOrder, bool kBusy, bool kFix, bool kOnePerPass = true>
+template <typename L, int kQueueOrder, bool kBusy, bool kFix>
 __device__ __forceinline__ FastResult simulate_pow2(const Scenario& s, const Pow2Model& model,
                                                     const LaneLds& lds, const FastOut& out) {
   if constexpr (L::kPacked) return simulate_packed<L, kQueueOrder, kBusy, kFix>(s, model, lds, out);
-  else return simulate_fast<L, kQueueOrder, kBusy, kFix, Pow2Model, kOnePerPass>(s, model, lds, out);
+  else return simulate_fast<L, kQueueOrder, kBusy, kFix, Pow2Model>(s, model, lds, out);
 }
 
 template <int kQueueOrder>
@@ -664,9 +664,9 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     FastOut fo;
     fo.queue_order = nullptr;
     fo.slots = b.max_chunks;
-    // times only: passes are short, and up to 16 chunks too few for the rounds to pay
-    FastResult r = simulate_pow2<L, kNoQueueOrder, false, kFix, (L::kCap <= 16u)>(
-        s, Pow2Model(s, fs, it.scf), lds, fo);
+    // times only
+    FastResult r =
+        simulate_pow2<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, it.scf), lds, fo);
     if (r.ok) { t_done[e] = r.t_done; return; }
   }
   if (hand_over) mark_left_to_generic(t_done + e, hand_over);

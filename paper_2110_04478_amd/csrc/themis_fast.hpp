@@ -529,8 +529,7 @@ struct Pow2Model {
 // wave-uniform run-time branch around the four-way selection cost 4 % on
 // batches without delays).
 // Model: Pow2Model or a type with the same members (sizes, times, classes).
-// kOnePerPass: see the event loop.
-template <typename L, int kQueueOrder, bool kBusy, bool kFix, typename Model, bool kOnePerPass = true>
+template <typename L, int kQueueOrder, bool kBusy, bool kFix, typename Model>
 __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Model& model,
                                                     const LaneLds& lds, const FastOut& out) {
   using Link = typename L::Link;
@@ -577,18 +576,15 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
   }
 
   double now = 0.0;
-  // kOnePerPass: one pass starts at most one stage and, once no idle dimension
-  // has chunks waiting, advances the clock to the next completion.  A lane that
-  // has to start two stages at one instant takes two passes for it; the other
-  // lanes of the wavefront go on with their own events meanwhile instead of
-  // waiting.  Otherwise a pass starts every stage of the instant (as many
-  // rounds as the lane with the most stages to start needs) before the clock
-  // moves: fewer passes, which pays when a pass is short (no outputs but the
-  // time) and many lanes start two stages.
+  // One pass starts at most one stage and, once no idle dimension has chunks
+  // waiting, advances the clock to the next completion.  A lane that has to
+  // start two stages at one instant takes two passes for it; the other lanes of
+  // the wavefront go on with their own events meanwhile instead of waiting
+  // through a second round of starts.
   const uint32_t max_steps = 4u * D * C + 16u;
   for (uint32_t step = 0; step <= max_steps; ++step) {
     // a7: an idle dimension with waiting chunks starts its first one
-    for (uint32_t need = idle & work; need != 0u; need = kOnePerPass ? 0u : (idle & work)) {
+    if (const uint32_t need = idle & work) {
       const uint32_t k = (uint32_t)__builtin_ctz(need);
       // work bit k says that one of k's lists is non-empty
       uint32_t field;
@@ -642,7 +638,7 @@ __device__ __forceinline__ FastResult simulate_fast(const Scenario& s, const Mod
       executed.inc(k);
     }
     // all stages of an instant start before the clock moves
-    if (kOnePerPass && (idle & work) != 0u) continue;
+    if ((idle & work) != 0u) continue;
 
     // a8: advance to the earliest completion
     const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));
