@@ -566,7 +566,7 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
       double T, z[kMaxDims];
       uint32_t ex[kMaxDims];
-      if (simulate_trace_fast<kLdsBitmaps, kExtras, kExtras>(s, Q, epack, fs0.state0, fs0.rs_only, scf,
+      if (simulate_trace_fast<kLdsBitmaps, kExtras, kExtras, kExtras>(s, Q, epack, fs0.state0, fs0.rs_only, scf,
                                                       has_release, rg, lds, out, T, z, ex)) {
         t_done[i] = T;
         if (busy) {
@@ -1136,7 +1136,8 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
     uint8_t* trace_area = have_trace ? (uint8_t*)workspace + generic : nullptr;
     // few wavefronts (no more than CUs): the bitmap leaves move into the LDS nothing else would use
     const bool lds_bitmaps = blocks_for(batch->n) <= compute_units();
-    const bool extras = batch->release_time != nullptr || batch->fixed_delay != nullptr;
+    const bool extras = batch->release_time != nullptr || batch->fixed_delay != nullptr ||
+                        queue_order != nullptr;
     auto trace_kernel = lds_bitmaps ? (extras ? simulate_trace_kernel<true, true> : simulate_trace_kernel<true, false>)
                                     : (extras ? simulate_trace_kernel<false, true> : simulate_trace_kernel<false, false>);
     hipLaunchKernelGGL(trace_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,

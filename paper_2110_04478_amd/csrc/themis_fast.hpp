@@ -455,7 +455,8 @@ __device__ __forceinline__ void start_stage_scaled(uint32_t k, uint32_t val, dou
   "v_mov_b64_e32 %[f" #J "], %[nan]\n\t"                \
   "v_min_u32_e32 %[first], %[first], %[s" #J "]\n\t"    \
   "v_or_b32_e32 %[done], " #BIT ", %[done]\n\t" THEMIS_ALL_LANES
-__device__ __forceinline__ uint32_t stages_ending(double now, DimState& d, uint32_t& first) {
+template <typename Dims>
+__device__ __forceinline__ uint32_t stages_ending(double now, Dims& d, uint32_t& first) {
   uint64_t act;
   uint32_t done = 0u;
   first = ~0u;

@@ -196,7 +196,58 @@ constexpr uint32_t kTraceLdsWordsBitmaps = 16 + 4 * kTraceLeafWords;
 // that looks for the next release.  kFix: the batch carries fixed delays.
 // kLdsBitmaps: the bitmap leaves live in LDS (kTraceLdsWordsBitmaps dwords per
 // lane) instead of the region; the summary words always do.
-template <bool kLdsBitmaps, bool kReleases, bool kFix>
+// What the trace loop keeps per dimension, one register (pair) each.
+struct TraceDims {
+  double f0, f1, f2, f3;    // finish time of the running stage, a quiet NaN when idle
+  double z0, z1, z2, z3;    // busy time
+  uint32_t s0, s1, s2, s3;  // the running stage: chunk << 2 | dimension
+  uint32_t n0, n1, n2, n3;  // what its completion will do (see simulate_trace_fast)
+  uint32_t e0, e1, e2, e3;  // operations started (kept when queue orders are written)
+};
+
+// Dimension k of each lane starts a stage at `now` on x bytes: the lanes with
+// k == j take their turn as the active ones, j = 0..3 (see start_stage_scaled):
+//   t = [a_j +] x * c_j;  f_j = now + t;  z_j += t;  s_j = sv;  n_j = nx;
+//   kQueue: pos = e_j, e_j += 1.
+// Returns t; pos is left alone without kQueue.
+#define THEMIS_TRACE_NEXT(J) "v_mov_b32_e32 %[n" #J "], %[nx]\n\t"
+#define THEMIS_TRACE_COUNT(J) \
+  "v_mov_b32_e32 %[pos], %[e" #J "]\n\t" "v_add_u32_e32 %[e" #J "], 1, %[e" #J "]\n\t"
+#define THEMIS_TRACE_PLAIN(J)                                                             \
+  THEMIS_LANES_OF(J) THEMIS_MUL(J) THEMIS_END(J) THEMIS_BUSY(J) THEMIS_SERVE(J) THEMIS_TRACE_NEXT(J) \
+  THEMIS_ALL_LANES
+#define THEMIS_TRACE_FULL(J)                                                           \
+  THEMIS_LANES_OF(J) THEMIS_MUL(J) THEMIS_FIX(J) THEMIS_END(J) THEMIS_BUSY(J) THEMIS_SERVE(J) \
+  THEMIS_TRACE_NEXT(J) THEMIS_TRACE_COUNT(J) THEMIS_ALL_LANES
+#define THEMIS_N_OPERANDS [n0] "+v"(d.n0), [n1] "+v"(d.n1), [n2] "+v"(d.n2), [n3] "+v"(d.n3)
+#define THEMIS_E_OPERANDS [e0] "+v"(d.e0), [e1] "+v"(d.e1), [e2] "+v"(d.e2), [e3] "+v"(d.e3)
+
+template <bool kFixAndQueue>
+__device__ __forceinline__ double start_stage_trace(uint32_t k, uint32_t val, uint32_t nx,
+                                                    double now, double x,
+                                                    const double (&c)[kMaxDims],
+                                                    const double (&a)[kMaxDims], TraceDims& d,
+                                                    uint32_t& pos) {
+  uint64_t act;
+  double t;
+  if (kFixAndQueue) {
+    asm(THEMIS_FOUR(THEMIS_TRACE_FULL)
+        : [act] "=&s"(act), [t] "=&v"(t), [pos] "+v"(pos), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS,
+          THEMIS_S_OPERANDS, THEMIS_N_OPERANDS, THEMIS_E_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [nx] "v"(nx), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
+          THEMIS_A_OPERANDS
+        : "vcc");
+  } else {
+    asm(THEMIS_FOUR(THEMIS_TRACE_PLAIN)
+        : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS, THEMIS_S_OPERANDS,
+          THEMIS_N_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [nx] "v"(nx), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS
+        : "vcc");
+  }
+  return t;
+}
+
+template <bool kLdsBitmaps, bool kReleases, bool kFix, bool kQueue>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
                                            uint32_t state0, bool rs_only, bool scf,
                                            bool has_release,
@@ -225,16 +276,19 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     for (uint32_t l = 0; l < kTraceSumWords; ++l) SUM(k, l) = 0u;
   }
 
-  double f0 = kInf, f1 = kInf, f2 = kInf, f3 = kInf;  // finish time, +inf = idle
-  double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;      // busy time
-  // Per dimension, the chunk it serves (sv: chunk << 2 | dimension) and what
-  // that chunk's completion will do, worked out at dispatch so that the
-  // completion itself reads nothing but its target list (nx: the chunk's next
-  // word without its link in bits 0-15, the next dimension in bits 16-18
-  // (4 = finished) and the size rank there from bit 19)
-  uint32_t sv0 = 0u, sv1 = 0u, sv2 = 0u, sv3 = 0u;
-  uint32_t nx0 = 0u, nx1 = 0u, nx2 = 0u, nx3 = 0u;
-  uint32_t e0 = 0u, e1 = 0u, e2 = 0u, e3 = 0u;  // operations started per dimension
+  // Per dimension (TraceDims): finish and busy time, the chunk it serves
+  // (s: chunk << 2 | dimension) and what that chunk's completion will do,
+  // worked out at dispatch so that the completion itself reads nothing but its
+  // target list (n: the chunk's next word without its link in bits 0-15, the
+  // next dimension in bits 16-18 (4 = finished) and the size rank there from
+  // bit 19)
+  static_assert(kQueue == kFix, "the two per-dimension extras come together");
+  TraceDims d;
+  d.f0 = d.f1 = d.f2 = d.f3 = nan64();
+  d.z0 = d.z1 = d.z2 = d.z3 = 0.0;
+  d.s0 = d.s1 = d.s2 = d.s3 = 0u;
+  d.n0 = d.n1 = d.n2 = d.n3 = 0u;
+  d.e0 = d.e1 = d.e2 = d.e3 = 0u;
   // tops: bit 4 * k + sw says that summary word sw of dimension k is not zero;
   // work: bit k says that dimension k has chunks waiting; idle: serves nothing
   uint32_t tops = 0u, work = 0u, idle = 15u;
@@ -364,13 +418,6 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       const uint32_t h = pop(k, w, size, row_lo, row_hi, new_entry, entry_at);
       const uint32_t mask = w & 15u, phase = (w >> 4) & 1u;
       const uint32_t ek = (epack >> (8u * k)) & 0xffu;
-      // bytes moved on k: the resident size before the chunk's Reduce-Scatter
-      // on k, which an All-Gather on k finds 2^ek times smaller
-      double t = scale_up(size, phase ? ek : 0u) * sel4((int)k, s.coef[0], s.coef[1], s.coef[2], s.coef[3]);
-      if (kFix && s.has_fix) t = sel4((int)k, s.fix[0], s.fix[1], s.fix[2], s.fix[3]) + t;
-      const double fin = now + t;
-      // a stage that does not move the clock, or overflows it: generic path decides
-      stalled |= !(fin > now && fin < kInf);
       // the chunk's state after this stage: a Reduce-Scatter sets the
       // dimension's bit, an All-Gather clears it
       const uint32_t code = (w >> 8) & 0xffu;
@@ -384,19 +431,18 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       const uint32_t pair = sel4((int)(mask2 >> 1), upper ? row_hi.x : row_lo.x, upper ? row_hi.y : row_lo.y,
                                  upper ? row_hi.z : row_lo.z, upper ? row_hi.w : row_lo.w);
       const uint32_t rk = scf ? (pair >> (16u * (mask2 & 1u))) & 0xffffu : 0u;
-      const bool k0 = k == 0u, k1 = k == 1u, k2 = k == 2u, k3 = k == 3u;
-      f0 = k0 ? fin : f0; f1 = k1 ? fin : f1; f2 = k2 ? fin : f2; f3 = k3 ? fin : f3;
-      // z_j + t * [k == j]: one rounding of the exact sum, the same as z_j + t
-      z0 = __builtin_fma(t, k0 ? 1.0 : 0.0, z0); z1 = __builtin_fma(t, k1 ? 1.0 : 0.0, z1);
-      z2 = __builtin_fma(t, k2 ? 1.0 : 0.0, z2); z3 = __builtin_fma(t, k3 ? 1.0 : 0.0, z3);
       const uint32_t sv = (h << 2) | k;
       const uint32_t nx = mask2 | (phase2 << 4) | (code << 8) | (kn << 16) | (rk << 19);
-      sv0 = k0 ? sv : sv0; sv1 = k1 ? sv : sv1; sv2 = k2 ? sv : sv2; sv3 = k3 ? sv : sv3;
-      nx0 = k0 ? nx : nx0; nx1 = k1 ? nx : nx1; nx2 = k2 ? nx : nx2; nx3 = k3 ? nx : nx3;
+      uint32_t pos = 0u;
+      // bytes moved on k: the resident size before the chunk's Reduce-Scatter
+      // on k, which an All-Gather on k finds 2^ek times smaller
+      const double t = start_stage_trace<kQueue>(k, sv, nx, now, scale_up(size, phase ? ek : 0u),
+                                                 s.coef, s.fix, d, pos);
+      const double fin = now + t;
+      // a stage that does not move the clock, or overflows it: generic path decides
+      stalled |= !(fin > now && fin < kInf);
       idle &= ~(1u << k);
-      const uint32_t pos = sel4((int)k, e0, e1, e2, e3);
-      e0 += k0 ? 1u : 0u; e1 += k1 ? 1u : 0u; e2 += k2 ? 1u : 0u; e3 += k3 ? 1u : 0u;
-      if (out.queue_order && pos < 2u * out.slots) put_entry(out, (int)k, pos, (h << 1) | phase);
+      if (kQueue && out.queue_order && pos < 2u * out.slots) put_entry(out, (int)k, pos, (h << 1) | phase);
       if (entry_at < 4u * rg.t.R) ((uint32_t*)(rg.base + rg.t.off_ht))[entry_at] = new_entry;
     }
     if (stalled) break;
@@ -404,10 +450,10 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
 
     // a8: advance to the earliest completion, or to the next release if that
     // comes first
-    const double next = min_f64(min_f64(f0, f1), min_f64(f2, f3));
+    const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));  // NaN: nothing runs
     if (!kReleases) {
       if (!(next < kInf)) break;
-    } else if (rel_time <= next) {
+    } else if (!(next < rel_time)) {
       if (!(rel_time < kInf)) break;  // nothing running, nothing left to release
       // chunks arriving at one instant from a release and from a completion
       // would have to be merged by id: the generic path does that
@@ -417,31 +463,29 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       continue;
     }
     now = next;
-    const bool d0 = f0 == now, d1 = f1 == now, d2 = f2 == now, d3 = f3 == now;
-    uint32_t done = (d0 ? 1u : 0u) | (d1 ? 2u : 0u) | (d2 ? 4u : 0u) | (d3 ? 8u : 0u);
-    f0 = d0 ? kInf : f0; f1 = d1 ? kInf : f1; f2 = d2 ? kInf : f2; f3 = d3 ? kInf : f3;
-    idle |= done;
     // deliver all completions of this instant, lowest chunk id first: the
     // smallest chunk << 2 | dimension among the dimensions that completed
-    uint32_t g0 = d0 ? sv0 : ~0u, g1 = d1 ? sv1 : ~0u, g2 = d2 ? sv2 : ~0u, g3 = d3 ? sv3 : ~0u;
+    uint32_t key;
+    uint32_t done = stages_ending(now, d, key);
+    idle |= done;
     for (;;) {
-      const uint32_t key = min(min(g0, g1), min(g2, g3));
       const uint32_t k = key & 3u;
-      const uint32_t nx = sel4((int)k, nx0, nx1, nx2, nx3);
+      const uint32_t nx = sel4((int)k, d.n0, d.n1, d.n2, d.n3);
       const uint32_t kn = (nx >> 16) & 7u;
       if (kn < 4u) push(kn, nx >> 19, key >> 2, true, (nx & 0xffffu) | (kNoChunk << 16));
       done &= ~(1u << k);
       if (done == 0u) break;
-      g0 = g0 == key ? ~0u : g0; g1 = g1 == key ? ~0u : g1;
-      g2 = g2 == key ? ~0u : g2; g3 = g3 == key ? ~0u : g3;
+      // one more stage ends at this very instant (rare): the smallest one left
+      key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
+                min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
     }
   }
 
   t_done = now;
 #pragma unroll
   for (uint32_t kk = 0; kk < 4u; ++kk) { busy[kk] = 0.0; executed_out[kk] = 0u; }
-  busy[0] = z0; busy[1] = z1; busy[2] = z2; busy[3] = z3;
-  executed_out[0] = e0; executed_out[1] = e1; executed_out[2] = e2; executed_out[3] = e3;
+  busy[0] = d.z0; busy[1] = d.z1; busy[2] = d.z2; busy[3] = d.z3;
+  executed_out[0] = d.e0; executed_out[1] = d.e1; executed_out[2] = d.e2; executed_out[3] = d.e3;
   return !stalled;
 }
 
