@@ -36,40 +36,16 @@ struct LaneLds {
   __device__ __forceinline__ uint8_t* dword(uint32_t d) const { return base + (d << 8); }
 };
 
-// Four small per-dimension counters / ids packed in one register (pair).
+// Four small per-dimension counters packed in one register (pair).
 template <typename Word, int kBits>
 struct Pack4 {
   Word v = 0;
   static constexpr Word kMask = (Word(1) << kBits) - 1;
   static constexpr int kFieldBits = kBits;
   __device__ __forceinline__ uint32_t get(uint32_t k) const { return (uint32_t)((v >> (kBits * k)) & kMask); }
-  __device__ __forceinline__ void set(uint32_t k, uint32_t x) {
-    v = (v & ~(kMask << (kBits * k))) | (Word(x) << (kBits * k));
-  }
   __device__ __forceinline__ void inc(uint32_t k) { v += Word(1) << (kBits * k); }
   __device__ __forceinline__ uint32_t sum() const { return get(0) + get(1) + get(2) + get(3); }
 };
-
-// All-ones in every field whose bit of `keep` is clear.
-__device__ __forceinline__ uint32_t blank_fields(const Pack4<uint32_t, 8>&, uint32_t keep) {
-  // byte selector 0x0d gives 0xff, 0x0c gives 0x00
-  const uint32_t spread = (keep * 0x00204081u) & 0x01010101u;
-  return __builtin_amdgcn_perm(0u, 0u, 0x0d0d0d0du - spread);
-}
-__device__ __forceinline__ uint64_t blank_fields(const Pack4<uint64_t, 16>&, uint32_t keep) {
-  const uint32_t lo = (((keep & 3u) * 0x8001u) & 0x00010001u) * 0xffffu;
-  const uint32_t hi = (((keep >> 2) * 0x8001u) & 0x00010001u) * 0xffffu;
-  return ~(((uint64_t)hi << 32) | lo);
-}
-// Smallest of the four fields.
-__device__ __forceinline__ uint32_t min_field(uint32_t v) {
-  const uint32_t a = min(v & 0xffu, (v >> 8) & 0xffu), b = min((v >> 16) & 0xffu, v >> 24);
-  return min(a, b);
-}
-__device__ __forceinline__ uint32_t min_field(uint64_t v) {
-  const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-  return min(min(lo & 0xffffu, lo >> 16), min(hi & 0xffffu, hi >> 16));
-}
 
 // Which of a dimension's FIFO lists (one per size class) hold chunks: 16 classes
 // per dimension, all four dimensions in one register pair.  List q = 16*k + class.
