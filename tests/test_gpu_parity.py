@@ -412,6 +412,20 @@ def test_traces_ranked_list_path(gpu, oracle):
     check_batch(gpu, oracle, b, threads=16)
 
 
+def test_traces_without_queue_orders(gpu, oracle):
+    """Traces with neither release times, fixed delays nor queue orders asked
+    for run a kernel compiled without those steps: times and busy times against
+    the oracle, with the bitmaps in LDS and (more wavefronts than CUs) in the
+    workspace."""
+    rng = np.random.default_rng(6)
+    b = _add_trace(w().mixed(300, seed=51, max_chunks=12), rng, 9, pow2_sizes=True)
+    check_batch(gpu, oracle, _with_collective_types(b, 4), queue=False)
+    b = _add_trace(w().mixed(150, seed=52, max_chunks=64), rng, 6, pow2_sizes=False)
+    check_batch(gpu, oracle, b, queue=False)
+    b = _add_trace(w().mixed(256 * 64 + 300, seed=53, max_chunks=5), rng, 3, pow2_sizes=True)
+    check_batch(gpu, oracle, b, queue=False, threads=16)
+
+
 def test_traces_with_staggered_releases(gpu, oracle):
     """Collectives released at different times (gradients of a back-propagation
     pass) on the ranked-list path: releases before, between and after the
