@@ -38,6 +38,48 @@ def build(force: bool = True, extra=()) -> str:
     return LIB
 
 
+def exec_hazards(asm_text: str):
+    """The event loops switch the active lanes inside inline-assembly blocks
+    (v_cmpx ... s_mov exec), into which the compiler's hazard recogniser does
+    not look.  On this target an instruction that reads other lanes (DPP,
+    v_readlane, v_readfirstlane, v_writelane, v_permlane) needs up to five wait
+    states after a vector instruction that wrote exec.  Returns the blocks
+    after whose last v_cmpx fewer instructions than that come before such an
+    instruction, as (instructions inside the block after it, the window)."""
+    import re
+    lines = asm_text.split("\n")
+    found, blocks, i = [], 0, 0
+    while i < len(lines):
+        if "ASMSTART" in lines[i]:
+            j = i
+            while "ASMEND" not in lines[j]:
+                j += 1
+            block = [l.strip() for l in lines[i + 1:j] if l.strip() and not l.strip().startswith(";")]
+            if any(l.startswith("v_cmpx") for l in block):
+                blocks += 1
+                last = max(k for k, l in enumerate(block) if l.startswith("v_cmpx"))
+                inside = len(block) - last - 1
+                follow, k = [], j + 1
+                while len(follow) < 5 and k < len(lines):
+                    l = lines[k].strip()
+                    k += 1
+                    if l and l[0] not in ";." and not l.endswith(":"):
+                        follow.append(l)
+                window = follow[:max(0, 5 - inside)]
+                if any(re.search(r"dpp|readlane|readfirstlane|writelane|permlane", l) for l in window):
+                    found.append((inside, window))
+            i = j
+        i += 1
+    return blocks, found
+
+
+def device_assembly() -> str:
+    """The device code of the library as assembly text (same flags as build())."""
+    flags = [f for f in FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [HIPCC, *flags, "-S", "--cuda-device-only", "-o", "-", *SOURCES]
+    return subprocess.run(cmd, check=True, capture_output=True, text=True).stdout
+
+
 def ensure_built() -> str:
     """Build only if no library is there at all (tests, smoke and bench call
     this; the binding itself never builds and fails loudly instead)."""

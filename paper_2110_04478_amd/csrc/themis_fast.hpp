@@ -345,6 +345,11 @@ __device__ __forceinline__ double min_f64(double a, double b) {
 // the lanes with k == j are made the active ones in turn, j = 0..3, and do
 // their arithmetic on dimension j's registers directly.  The operations and
 // their order are those of the plain code, so the results are bit-identical.
+// The compiler does not look into these blocks: an instruction that reads
+// other lanes (DPP, v_readlane, ...) must not follow the last v_cmpx within
+// five wait states; build.py's exec_hazards() checks the compiled code for
+// that (a no-op at the end of the blocks would rule it out, but two of them
+// per pass cost 2.6 % of the kernel's time).
 #define THEMIS_LANES_OF(J) "v_cmpx_eq_u32_e32 vcc, " #J ", %[k]\n\t"
 #define THEMIS_ALL_LANES "s_mov_b64 exec, %[act]\n\t"
 #define THEMIS_FOUR(BODY) "s_mov_b64 %[act], exec\n\t" BODY(0) BODY(1) BODY(2) BODY(3)

@@ -87,3 +87,16 @@ def test_misaligned_workspace_is_rejected_on_the_host():
                                    None) == -4
     assert L.themis_sweep(ctypes.byref(b), 1, fake, 0, 7, fake, fake + 4, 1 << 20, None) == -4
     assert L.themis_search_batch(ctypes.byref(b), 16, fake, None, fake + 4, 1 << 20, None) == -4
+
+
+def test_no_lane_crossing_instruction_right_after_an_exec_switch():
+    """The inline-assembly blocks that make each dimension's lanes the active
+    ones in turn are opaque to the compiler's hazard recogniser: no instruction
+    that reads other lanes may follow the last exec write within the wait
+    states the target asks for (checked on the compiled device code)."""
+    from paper_2110_04478_amd.csrc import build
+    if not os.path.exists(build.HIPCC):
+        pytest.skip("no hipcc here")
+    blocks, found = build.exec_hazards(build.device_assembly())
+    assert blocks > 0          # the blocks are there (else this test checks nothing)
+    assert not found, found
