@@ -21,7 +21,13 @@
  * reported per-dimension orders and verifies work conservation and FIFO / SCF
  * conformance, brute force over all per-chunk orders for tiny C, hand values
  * for the derived metrics and the provisioning classes, hand values and the
- * library minimum / argmin for the best threshold of a sweep.  The completion time
+ * library minimum / argmin for the best threshold of a sweep.  The batch drivers
+ * (tests/test_oracle_batch_pins.py): hand-derived times for every column of a
+ * sweep and for shared and per-scenario thresholds, each column rebuilt by the
+ * schedule checker under its own policy, ragged traces with rows longer than
+ * the chunk count replayed with rationals and checked operation by operation,
+ * the 1-D sum of closed forms over a trace, hand values for the trace totals
+ * of the metrics, per-scenario delays and collective types.  The completion time
  * that the paper's timing figure would show for Themis on the worked example
  * is "parity unpinned": the figure is not available in text form.
  */
