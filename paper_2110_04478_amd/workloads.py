@@ -295,6 +295,43 @@ def mixed(n: int, seed: int = SEED_BASE + 99, max_chunks: int = 64,
         threshold=thr)
 
 
+def dyadic_ties(n: int, seed: int = SEED_BASE + 77, max_chunks: int = 64,
+                tilt: bool = True) -> ScenarioBatch:
+    """Networks on which many stages end at the very same binary64 instant:
+    power-of-two NPU counts, bandwidths 2^a * (P-1)/P (so every per-byte latency
+    is a power of two), chunks of 2^m bytes.  The exponents follow the paper's
+    just-enough ladder (Sec. 3.3 / 6.3: BW(dim1) = P1 * BW(dim2) = ..., which
+    makes the baseline's stage times equal on all dimensions), optionally
+    tilted by a factor of two per dimension.  All stage times are then powers
+    of two and every clock value an exact sum of them, so completions on
+    different dimensions coincide again and again.  D in 1..4, both schedulers
+    and queue policies, relative thresholds 0, 1/16 or 1/4 (which also make the
+    threshold test of Alg. 1 hit exact equality)."""
+    i = np.arange(n, dtype=np.uint64)
+    D = (1 + np.minimum((_u01(seed, i, 0) * 5).astype(np.int64), 3)).astype(np.uint8)  # 4 twice as often
+    P = np.full((MAX_DIMS, n), 2, dtype=np.uint32)
+    B = np.ones((MAX_DIMS, n))
+    a = 33.0 + np.floor(_u01(seed, i, 13) * 3)        # log2 of dim1's scaled bandwidth
+    for k in range(4):
+        e = 1 + np.minimum((_u01(seed, i, 1 + k) * 3).astype(np.int64), 2)   # P in {2, 4, 8}
+        P[k] = (1 << e).astype(np.uint32)
+        t = np.floor(_u01(seed, i, 5 + k) * 3) - 1 if tilt else 0.0
+        p = P[k].astype(np.float64)
+        B[k] = 2.0 ** (a + (t if k else 0.0)) * ((p - 1.0) / p)
+        a = a - e                                      # the next rung of the ladder
+    C = (1 + np.minimum((_u01(seed, i, 10) * max_chunks).astype(np.int64),
+                        max_chunks - 1)).astype(np.uint32)
+    C[_u01(seed, i, 14) < 0.4] = max_chunks            # many at the layout's capacity
+    S = C.astype(np.float64) * 2.0 ** (20 + np.floor(_u01(seed, i, 9) * 5))
+    inter = (_u01(seed, i, 11) < 0.8).astype(np.uint8)
+    intra = (_u01(seed, i, 12) < 0.5).astype(np.uint8)
+    thr = np.choose((_u01(seed, i, 15) * 3).astype(np.int64), [0.0, 1 / 16, 1 / 4])
+    return ScenarioBatch(
+        n=n, max_chunks=max_chunks, threshold_mode=THR_REL, ndims=D, npus=P,
+        bw=B, size_bytes=S, chunks=C, inter_policy=inter, intra_policy=intra,
+        threshold=thr)
+
+
 # --------------------------------------------------------------------------
 # the six 1024-NPU platforms of the paper's Table 2
 # --------------------------------------------------------------------------
