@@ -238,6 +238,30 @@ int themis_simulate_batch(const themis_batch_t *batch, const uint8_t *orders,
                           void *stream);
 
 /*
+ * themis_simulate_batch_noalloc -- themis_simulate_batch for callers that
+ * cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and kernels; the scratch that themis_simulate_batch takes
+ * from the caller's workspace sits in a device array of
+ * THEMIS_STATIC_SCRATCH_BYTES that the library itself holds on every GPU it is
+ * loaded on, for the life of the process.  The call allocates and frees
+ * nothing.
+ *   - A batch that would need more (themis_workspace_bytes(n, max_chunks,
+ *     max_coll) for traces, and for single collectives of more than 64 chunk
+ *     slots; nothing otherwise) is refused with THEMIS_ERR_WORKSPACE before
+ *     anything is launched.
+ *   - All calls on one GPU share that GPU's array: two such calls must not be
+ *     in flight at once on one GPU (different streams or threads), or they race.
+ *     Contents left by an earlier call are never read.
+ *   - The first call on a device asks the runtime for the array's address
+ *     (no stream work); make one call per device before capturing a graph.
+ */
+#define THEMIS_STATIC_SCRATCH_BYTES (32u << 20)
+int themis_simulate_batch_noalloc(const themis_batch_t *batch, const uint8_t *orders,
+                                  double *t_done, void *queue_order, double *busy,
+                                  void *stream);
+
+/*
  * themis_sweep -- fused plan + simulate for every scenario x threshold x
  * scheduler of policy_mask (the parameter studies of Sec. 6.1), keeping only
  * completion times.  inter_policy / intra_policy / threshold of the batch are

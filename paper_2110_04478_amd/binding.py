@@ -57,6 +57,8 @@ def lib():
         L.themis_simulate_batch.restype = C.c_int
         L.themis_simulate_batch.argtypes = [C.POINTER(_Batch), _vp, _vp, _vp, _vp, _vp,
                                             C.c_size_t, _vp]
+        L.themis_simulate_batch_noalloc.restype = C.c_int
+        L.themis_simulate_batch_noalloc.argtypes = [C.POINTER(_Batch), _vp, _vp, _vp, _vp, _vp]
         L.themis_metrics_batch.restype = C.c_int
         L.themis_metrics_batch.argtypes = [C.POINTER(_Batch), _vp, _vp, _vp, _vp, _vp]
         L.themis_search_workspace_bytes.restype = C.c_size_t
@@ -200,6 +202,20 @@ def themis_simulate_batch(b: DeviceBatch, orders: torch.Tensor,
     s = b.c_struct()
     _check(lib().themis_simulate_batch(C.byref(s), _ptr(orders), _ptr(t_done), _ptr(queue_order),
                                        _ptr(busy), _ptr(workspace), ws_bytes, _stream()))
+    return t_done, queue_order, busy
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def themis_simulate_batch_noalloc(b: DeviceBatch, orders: torch.Tensor, t_done: torch.Tensor,
+                                  queue_order: Optional[torch.Tensor],
+                                  busy: Optional[torch.Tensor]):
+    """themis_simulate_batch on the library's own scratch: every buffer is the
+    caller's, nothing is allocated here or in the library."""
+    s = b.c_struct()
+    _check(lib().themis_simulate_batch_noalloc(C.byref(s), _ptr(orders), _ptr(t_done),
+                                               _ptr(queue_order), _ptr(busy), _stream()))
     return t_done, queue_order, busy
 
 

@@ -11,6 +11,12 @@
 #include "themis_table.hpp"
 #include "themis_trace.hpp"
 
+// Scratch of themis_simulate_batch_noalloc: device memory the library itself
+// brings along, one copy per GPU that loads the code object.  Host code never
+// uses this name as an address; it asks the runtime for the array's device
+// address once per device (scratch_of_current_device()).
+static __device__ __align__(256) unsigned char scratch[THEMIS_STATIC_SCRATCH_BYTES];
+
 namespace themis {
 
 struct TraceView {
@@ -1075,7 +1081,7 @@ const char* themis_status_string(int status) {
     case THEMIS_ERR_INVALID_ARGUMENT: return "invalid argument";
     case THEMIS_ERR_UNSUPPORTED: return "unsupported request";
     case THEMIS_ERR_DEVICE: return "HIP device error";
-    case THEMIS_ERR_WORKSPACE: return "workspace missing or too small";
+    case THEMIS_ERR_WORKSPACE: return "workspace missing, too small or misaligned, or the request exceeds the built-in scratch";
     default: return "unknown status";
   }
 }
@@ -1107,9 +1113,9 @@ int themis_plan_batch(const themis_batch_t* batch, uint8_t* orders, double* load
   return launch_status();
 }
 
-int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, double* t_done,
-                          void* queue_order, double* busy, void* workspace,
-                          size_t workspace_bytes_given, void* stream) {
+static int simulate_batch_impl(const themis_batch_t* batch, const uint8_t* orders, double* t_done,
+                               void* queue_order, double* busy, void* workspace,
+                               size_t workspace_bytes_given, void* stream) {
   int st = check_batch(batch, true, false);
   if (st != THEMIS_OK) return st;
   if (batch->n == 0) return THEMIS_OK;
@@ -1188,6 +1194,49 @@ int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, do
                      (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
                      busy, have_ws ? w : Workspace{}, call);
   return launch_status();
+}
+
+int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, double* t_done,
+                          void* queue_order, double* busy, void* workspace,
+                          size_t workspace_bytes_given, void* stream) {
+  return simulate_batch_impl(batch, orders, t_done, queue_order, busy, workspace,
+                             workspace_bytes_given, stream);
+}
+
+// Device address of `scratch` on the current device, asked for once per device
+// and kept: every GPU holds its own copy of the array at its own address.
+static int scratch_of_current_device(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> known[kMaxDevices];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return THEMIS_ERR_DEVICE;
+  void* p = known[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return THEMIS_ERR_DEVICE;
+    known[dev].store(p, std::memory_order_release);  // two first calls at once store the same address
+  }
+  *out = p;
+  return THEMIS_OK;
+}
+
+int themis_simulate_batch_noalloc(const themis_batch_t* batch, const uint8_t* orders,
+                                  double* t_done, void* queue_order, double* busy, void* stream) {
+  int st = check_batch(batch, true, false);
+  if (st != THEMIS_OK) return st;
+  if (batch->n == 0) return THEMIS_OK;
+  // what themis_simulate_batch would ask a caller for: traces keep their queues
+  // there, single collectives only what the generic path needs beyond 64 chunks
+  const bool trace = batch->n_coll != nullptr;
+  const size_t need = (trace || batch->max_chunks > 64u)
+      ? themis_workspace_bytes(batch->n, batch->max_chunks, trace ? batch->max_coll : 0u) : 0u;
+  if (need > (size_t)THEMIS_STATIC_SCRATCH_BYTES) return THEMIS_ERR_WORKSPACE;
+  void* ws = nullptr;
+  st = scratch_of_current_device(&ws);
+  if (st != THEMIS_OK) return st;
+  // nothing in the scratch has to start at zero: the kernels initialise every
+  // word they read (chunk state, list heads behind a set bitmap bit, bitmaps)
+  return simulate_batch_impl(batch, orders, t_done, queue_order, busy, ws,
+                             (size_t)THEMIS_STATIC_SCRATCH_BYTES, stream);
 }
 
 int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int thr_per_scenario,
