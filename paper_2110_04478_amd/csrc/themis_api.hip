@@ -8,6 +8,7 @@
 #include "themis_fast.hpp"
 #include "themis_generic.hpp"
 #include "themis_packed.hpp"
+#include "themis_ring.hpp"
 #include "themis_table.hpp"
 #include "themis_trace.hpp"
 
@@ -190,6 +191,20 @@ __device__ __forceinline__ void simulate_generic_scenario(const themis_batch_t& 
       [&](uint32_t q) { return collective_release(b, tv, i, q); }, has_release, out);
 }
 
+// This lane's view of its wavefront's LDS block.
+template <typename L>
+__device__ __forceinline__ LaneLds lane_lds(uint32_t* lds_block) {
+  LaneLds lds;
+  if constexpr (IsRing<L>::value) {
+    lds.base = (uint8_t*)lds_block + L::lane_term_rec(threadIdx.x);
+    lds.aux = (uint8_t*)lds_block + L::lane_term_tail(threadIdx.x);
+  } else {
+    lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+    lds.aux = nullptr;
+  }
+  return lds;
+}
+
 // Chunk c's word / record in the lane's LDS block, whichever the layout keeps.
 template <typename L>
 __device__ __forceinline__ void init_chunk(const LaneLds& lds, uint32_t c, uint32_t code,
@@ -202,8 +217,15 @@ __device__ __forceinline__ void init_chunk(const LaneLds& lds, uint32_t c, uint3
 template <typename L, int kQueueOrder, bool kBusy, bool kFix>
 __device__ __forceinline__ FastResult simulate_pow2(const Scenario& s, const Pow2Model& model,
                                                     const LaneLds& lds, const FastOut& out) {
-  if constexpr (L::kPacked) return simulate_packed<L, kQueueOrder, kBusy, kFix>(s, model, lds, out);
-  else return simulate_fast<L, kQueueOrder, kBusy, kFix, Pow2Model>(s, model, lds, out);
+  if constexpr (IsRing<L>::value) {
+    // entries leave one by one: collected dwords become single bytes
+    constexpr int kMode = kQueueOrder == kWords ? (int)kBytes : kQueueOrder;
+    return simulate_ring<kMode, kBusy, kFix>(s, model, lds, out);
+  } else if constexpr (L::kPacked) {
+    return simulate_packed<L, kQueueOrder, kBusy, kFix>(s, model, lds, out);
+  } else {
+    return simulate_fast<L, kQueueOrder, kBusy, kFix, Pow2Model>(s, model, lds, out);
+  }
 }
 
 template <int kQueueOrder>
@@ -268,8 +290,7 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     bool fast = !tv.on &&
                 fast_eligible(s, collective_size(b, tv, i, 0) / (double)s.C, L::kCap, fs);
     if (fast) {
-      LaneLds lds;
-      lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+      const LaneLds lds = lane_lds<L>(lds_block);
       // order codes -> chunk words (mask 0, Reduce-Scatter phase)
       bool codes_ok = true;
       if ((tv.slots & 3u) == 0u) {
@@ -662,8 +683,7 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
   const double chunk = S / (double)s.C;
   FastScenario fs;
   if (fast_eligible(s, chunk, L::kCap, fs)) {
-    LaneLds lds;
-    lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+    const LaneLds lds = lane_lds<L>(lds_block);
     double load[kMaxDims];
     plan_fast(s, fs, it.themis_on, rel, it.th, load,
               [&](uint32_t c, uint32_t code) { init_chunk<L>(lds, c, code, 0u, (uint32_t)s.D); });
@@ -840,8 +860,7 @@ search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ t
   const uint64_t count = ok ? assignment_count((uint32_t)s.D, s.C, max_assign) : 0;
   if (count == 0) { times[e] = nan64(); return; }
   if (a >= count) { times[e] = inf64(); return; }
-  LaneLds lds;
-  lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+  const LaneLds lds = lane_lds<L>(lds_block);
   const uint32_t F = factorial_u32((uint32_t)s.D);
   uint64_t rest = a;
   for (uint32_t c = 0; c < s.C; ++c) {
@@ -854,7 +873,7 @@ search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ t
   FastOut fo;
   fo.queue_order = nullptr;
   fo.slots = b.max_chunks;
-  FastResult r = simulate_fast<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
+  FastResult r = simulate_pow2<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
   times[e] = r.ok ? r.t_done : nan64();
 }
 
@@ -1044,7 +1063,7 @@ static uint32_t layout_capacity(uint32_t max_chunks) {
 
 static SimKernel pick_simulate_kernel(uint32_t cap, int mode, bool busy, bool fix) {
   if (cap == 16u) return pick_mode<Layout16>(mode, busy, fix);
-  if (cap == 64u) return pick_mode<Layout64>(mode, busy, fix);
+  if (cap == 64u) return pick_mode<LayoutRing>(mode, busy, fix);
   if (cap == 128u) return pick_mode<Layout128>(mode, busy, fix);
   if (cap == 256u) return pick_mode<LayoutPacked<256>>(mode, busy, fix);
   return pick_mode<LayoutPacked<512>>(mode, busy, fix);
@@ -1259,7 +1278,7 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   const uint32_t cap = layout_capacity(batch->max_chunks);
   const bool fix = batch->fixed_delay != nullptr;
   auto kernel = cap == 16u ? (fix ? sweep_kernel<Layout16, true> : sweep_kernel<Layout16, false>)
-              : cap == 64u ? (fix ? sweep_kernel<Layout64, true> : sweep_kernel<Layout64, false>)
+              : cap == 64u ? (fix ? sweep_kernel<LayoutRing, true> : sweep_kernel<LayoutRing, false>)
               : cap == 128u ? (fix ? sweep_kernel<Layout128, true> : sweep_kernel<Layout128, false>)
               : cap == 256u ? (fix ? sweep_kernel<LayoutPacked<256>, true> : sweep_kernel<LayoutPacked<256>, false>)
                             : (fix ? sweep_kernel<LayoutPacked<512>, true> : sweep_kernel<LayoutPacked<512>, false>);
@@ -1315,7 +1334,7 @@ int themis_search_batch(const themis_batch_t* batch, uint64_t max_assignments, d
   const bool fix = batch->fixed_delay != nullptr;
   auto eval = batch->max_chunks <= 16u
       ? (fix ? search_eval_kernel<Layout16, true> : search_eval_kernel<Layout16, false>)
-      : (fix ? search_eval_kernel<Layout64, true> : search_eval_kernel<Layout64, false>);
+      : (fix ? search_eval_kernel<LayoutRing, true> : search_eval_kernel<LayoutRing, false>);
   hipLaunchKernelGGL(eval, dim3(blocks_for(evals)), dim3(kBlock), 0, (hipStream_t)stream, *batch,
                      max_assignments, times);
   hipLaunchKernelGGL(search_reduce_kernel, dim3((unsigned)batch->n), dim3(kBlock), 0,

@@ -32,6 +32,7 @@ namespace themis {
 
 struct LaneLds {
   uint8_t* base;  // LDS block of the wavefront + 4*lane
+  uint8_t* aux;   // layouts with a second region (LayoutRing: the list tails)
   // byte address of dword d of this lane (transposed layout: 256 B apart)
   __device__ __forceinline__ uint8_t* dword(uint32_t d) const { return base + (d << 8); }
 };

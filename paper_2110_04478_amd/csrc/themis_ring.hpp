@@ -1,0 +1,344 @@
+// Event loop of the power-of-two fast path for up to 64 chunks on a per-lane
+// LDS block small enough for twelve wavefronts per CU (three per SIMD).
+//
+// The loop of simulate_fast issues far fewer vector instructions than its
+// SIMDs could take: with the two wavefronts per SIMD that its 80 dwords per
+// lane allow, each wavefront spends a third of its time waiting for LDS reads
+// and the other one cannot fill all of it.  A third wavefront per SIMD gains
+// more than any instruction saved (wavefront counts that are not a multiple
+// of four per CU gain nothing), so the block is cut to 48 dwords per lane:
+//
+//   16-bit record per chunk   bits 0-3   reduced-dims mask
+//                             bits 4-9   first three fields of the order code
+//                                        (the fourth is what is left: the XOR
+//                                        of the three, for four dimensions)
+//                             bits 10-15 next chunk of its list
+//   8-bit tail per list       last chunk of list q = 16 * dimension + class
+//
+// The queue structure is the one of simulate_fast (paper Sec. 4.3: per
+// dimension one FIFO list per resident-size class, appended in (arrival time,
+// chunk id) order), but the lists are circular -- the tail's record points to
+// the head -- so that one byte per list is enough.  The phase is not stored:
+// a chunk waiting for dimension k is in its All-Gather phase exactly when k
+// is among its reduced dimensions.
+//
+// Sub-dword elements normally cost address arithmetic (element -> dword and
+// position inside it); here two (records) or four (tails) lanes share a dword
+// instead: record c of lane L sits at byte c * 128 + (L & 31) * 4 + (L >> 5) * 2
+// and tail q at q * 64 + (L & 15) * 4 + (L >> 4) behind the records, so every
+// address is one shift-and-add.  Lanes that share a dword touch different
+// bytes of it and hit the same bank with the same dword address, which the LDS
+// serves without a conflict.
+//
+// What the completion of a stage will do (the list the chunk joins, its new
+// record bits, whether it is finished) is worked out when the stage starts,
+// from the record that has just been read, and kept in the dimension's
+// register together with the chunk id; the completion itself then reads
+// nothing but the tail of the list it appends to.
+#pragma once
+
+#include "themis_fast.hpp"
+
+namespace themis {
+
+struct LayoutRing {
+  static constexpr bool kPacked = false;
+  static constexpr bool kRing = true;
+  static constexpr uint32_t kCap = 64;
+  static constexpr uint32_t kRecBytes = kCap * 128u;   // 64 records x 64 lanes x 2 bytes
+  static constexpr uint32_t kTailBytes = 64u * 64u;    // 64 lists x 64 lanes
+  // 53 dwords per lane (13,568 bytes per wavefront) keep it at exactly twelve
+  // wavefronts per CU; the block itself needs 48
+  static constexpr uint32_t kLaneWords = 53;
+  static_assert(kLaneWords * 256u >= kRecBytes + kTailBytes, "block holds records and tails");
+  static constexpr uint32_t kWavesPerSimd = 3;
+  using Ids = Pack4<uint32_t, 8>;
+  static __device__ __forceinline__ uint32_t lane_term_rec(uint32_t lane) {
+    return (lane & 31u) * 4u + (lane >> 5) * 2u;
+  }
+  static __device__ __forceinline__ uint32_t lane_term_tail(uint32_t lane) {
+    return kRecBytes + (lane & 15u) * 4u + (lane >> 4);
+  }
+  // l.base: block + lane_term_rec, l.aux: block + lane_term_tail
+  static __device__ __forceinline__ uint16_t* rec(const LaneLds& l, uint32_t c) {
+    return (uint16_t*)(l.base + (c << 7));
+  }
+  static __device__ __forceinline__ uint8_t* tail(const LaneLds& l, uint32_t q) {
+    return l.aux + (q << 6);
+  }
+  // state0: initial mask | phase << 4 as in FastScenario (the phase is implied)
+  static __device__ __forceinline__ void init_chunk(const LaneLds& l, uint32_t c, uint32_t code,
+                                                    uint32_t state0) {
+    *rec(l, c) = (uint16_t)((state0 & 15u) | ((code & 63u) << 4) | (c << 10));
+  }
+};
+
+template <typename L, typename = void>
+struct IsRing { static constexpr bool value = false; };
+template <typename L>
+struct IsRing<L, typename std::enable_if<L::kRing>::type> { static constexpr bool value = true; };
+
+// Lowest set bit, all-ones for zero (the builtin is undefined there).
+__device__ __forceinline__ uint32_t ffbl_or_ones(uint32_t v) {
+  uint32_t r;
+  asm("v_ffbl_b32 %0, %1" : "=v"(r) : "v"(v));
+  return r;
+}
+
+// (a & mask) | (b & ~mask) in one instruction.
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "v"(mask), "v"(a), "v"(b));
+  return r;
+}
+
+// All four fields of an order code from its first three: for four dimensions
+// the fourth is the dimension left over, the XOR of the other three; for
+// fewer the field is never looked at.
+__device__ __forceinline__ uint32_t whole_code(uint32_t code6) {
+  return code6 | (((code6 ^ (code6 >> 2) ^ (code6 >> 4)) & 3u) << 6);
+}
+
+// What the ring loop keeps per dimension beside DimState: nothing; its s0..s3
+// hold the running stage as
+//   bits 0-5   list the chunk joins when the stage completes
+//   bit  6     the chunk is finished then
+//   bits 7-16  low ten bits of its record then (mask, order fields)
+//   bits 17-18 the dimension
+//   bits 19-24 the chunk
+// so the smallest value among the stages that end at an instant is the one of
+// the lowest chunk id.
+//
+// The lanes of dimension J take their turn as the active ones (see
+// start_stage_scaled): the stage time, the finish time, the busy time, the
+// stage's description, and the dimension's sixteen bits taken out of the mask
+// of idle dimensions.  At least five instructions follow the last v_cmpx
+// inside every block, so no instruction that reads other lanes can come within
+// the wait states an exec write by a vector instruction asks for.
+#define THEMIS_RING_BUSY_0(J, IE, KEEP)
+#define THEMIS_RING_FIX_0(J)
+#define THEMIS_RING_BUSY_1(J, IE, KEEP) THEMIS_BUSY(J)
+#define THEMIS_RING_FIX_1(J) THEMIS_FIX(J)
+#define THEMIS_RING_START(J, IE, KEEP, BUSY, FIX)                               \
+  THEMIS_LANES_OF(J) THEMIS_MUL(J) THEMIS_RING_FIX_##FIX(J) THEMIS_END(J)      \
+  THEMIS_RING_BUSY_##BUSY(J, IE, KEEP) THEMIS_SERVE(J)                          \
+  "v_and_b32_e32 %[" #IE "], " #KEEP ", %[" #IE "]\n\t" THEMIS_ALL_LANES
+#define THEMIS_RING_STARTS(BUSY, FIX)                                               \
+  "s_mov_b64 %[act], exec\n\t"                                                      \
+  THEMIS_RING_START(0, iel, 0xffff0000, BUSY, FIX) THEMIS_RING_START(1, iel, 0xffff, BUSY, FIX) \
+  THEMIS_RING_START(2, ieh, 0xffff0000, BUSY, FIX) THEMIS_RING_START(3, ieh, 0xffff, BUSY, FIX)
+
+template <bool kBusy, bool kFix>
+__device__ __forceinline__ void ring_start_stage(uint32_t k, uint32_t val, double now, double x,
+                                                 const double (&c)[kMaxDims],
+                                                 const double (&a)[kMaxDims], DimState& d,
+                                                 uint32_t& ie_lo, uint32_t& ie_hi) {
+  uint64_t act;
+  double t;
+  if (kBusy && kFix) {
+    asm volatile(THEMIS_RING_STARTS(1, 1)
+        : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
+          THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
+          THEMIS_A_OPERANDS : "vcc");
+  } else if (kBusy) {
+    asm volatile(THEMIS_RING_STARTS(1, 0)
+        : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
+          THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
+  } else if (kFix) {
+    asm volatile(THEMIS_RING_STARTS(0, 1)
+        : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
+          THEMIS_S_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
+          THEMIS_A_OPERANDS : "vcc");
+  } else {
+    asm volatile(THEMIS_RING_STARTS(0, 0)
+        : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
+          THEMIS_S_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
+  }
+}
+
+// The clock has moved to `now`: every dimension whose stage ends now becomes
+// idle (quiet NaN as its finish time, its sixteen bits back in the mask of
+// idle dimensions).  Returns the bits of those dimensions and, in `first`,
+// the smallest stage description among them (all-ones if there is none).
+#define THEMIS_RING_ENDS(J, BIT, IE, FIELD)                 \
+  "v_cmpx_eq_f64_e32 vcc, %[now], %[f" #J "]\n\t"          \
+  "v_mov_b64_e32 %[f" #J "], %[nan]\n\t"                   \
+  "v_min_u32_e32 %[first], %[first], %[s" #J "]\n\t"       \
+  "v_or_b32_e32 %[done], " #BIT ", %[done]\n\t"            \
+  "v_or_b32_e32 %[" #IE "], " #FIELD ", %[" #IE "]\n\t" THEMIS_ALL_LANES
+__device__ __forceinline__ uint32_t ring_stages_ending(double now, DimState& d, uint32_t& first,
+                                                       uint32_t& ie_lo, uint32_t& ie_hi) {
+  uint64_t act;
+  uint32_t done = 0u;
+  first = ~0u;
+  asm volatile("s_mov_b64 %[act], exec\n\t"
+      THEMIS_RING_ENDS(0, 1, iel, 0xffff) THEMIS_RING_ENDS(1, 2, iel, 0xffff0000)
+      THEMIS_RING_ENDS(2, 4, ieh, 0xffff) THEMIS_RING_ENDS(3, 8, ieh, 0xffff0000)
+      : [act] "=&s"(act), [done] "+v"(done), [first] "+v"(first), [iel] "+v"(ie_lo),
+        [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS
+      : [now] "v"(now), [nan] "v"(nan64()), [s0] "v"(d.s0), [s1] "v"(d.s1), [s2] "v"(d.s2),
+        [s3] "v"(d.s3)
+      : "vcc");
+  return done;
+}
+
+constexpr uint32_t kRingFinished = 64u;
+
+// Same contract as simulate_fast: records initialised with
+// LayoutRing::init_chunk(), result.ok false leaves the evaluation to the
+// generic path; power-of-two model only.  Queue orders leave as single
+// entries (kBytes into the lane's own rows, kStagedBytes into the wavefront's
+// staging block).  Nothing in the block has to be cleared beforehand.
+template <int kQueueOrder, bool kBusy, bool kFix>
+__device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow2Model& model,
+                                                    const LaneLds& lds, const FastOut& out) {
+  static_assert(kQueueOrder == kNoQueueOrder || kQueueOrder == kBytes || kQueueOrder == kStagedBytes,
+                "entries are stored one by one");
+  using L = LayoutRing;
+  const uint32_t D = (uint32_t)s.D;
+  const uint32_t C = s.C;
+  const uint32_t full = (1u << D) - 1u;
+  const double kInf = inf64();
+  const uint32_t epack = model.fs.epack;
+  const uint64_t ranktab = model.ranktab;
+  const bool rs_only = model.rs_only();
+
+  DimState d;
+  d.f0 = d.f1 = d.f2 = d.f3 = nan64();
+  d.z0 = d.z1 = d.z2 = d.z3 = 0.0;
+  d.s0 = d.s1 = d.s2 = d.s3 = 0u;
+  uint64_t nonempty = 0;              // bit q: list q holds chunks
+  uint32_t ie_lo = ~0u, ie_hi = ~0u;  // the sixteen bits of every idle dimension
+  typename L::Ids executed;           // operations started per dimension (kept with queue orders)
+  uint32_t started = 0;               // operations started in all
+  const uint32_t row_len = 2u * out.slots;
+
+  // chunk c, whose record is to carry low10 (mask, order fields), becomes the
+  // last of list q.  Branch-free: an empty list makes c its own successor (the
+  // second store then repeats the first), otherwise c takes over the old
+  // tail's link to the head and the old tail points to c.
+  auto push = [&](uint32_t q, uint32_t c, uint32_t low10) {
+    const uint64_t bit = 1ull << q;
+    const bool had = (nonempty & bit) != 0ull;
+    uint8_t* tp = L::tail(lds, q);
+    const uint32_t t = *tp & 63u;  // an empty list's tail is whatever the byte holds
+    uint16_t* rt_p = L::rec(lds, t);
+    const uint32_t rt = *rt_p;
+    uint16_t* rc_p = L::rec(lds, c);
+    const uint32_t recc = low10 | ((had ? (rt >> 10) : c) << 10);
+    *rc_p = (uint16_t)recc;
+    uint16_t* dst = had ? rt_p : rc_p;
+    *dst = (uint16_t)(had ? ((rt & 0x3ffu) | (c << 10)) : recc);
+    *tp = (uint8_t)c;
+    nonempty |= bit;
+  };
+
+  // a6: every chunk waits at the dimension of its first stage, in chunk-id
+  // order, in the class of the initial mask
+  {
+    const uint32_t mask0 = model.state0() & 15u, phase0 = (model.state0() >> 4) & 1u;
+    const uint32_t pos0 = 2u * ((uint32_t)__builtin_popcount(mask0) - phase0);
+    const uint32_t cls0 = (uint32_t)(ranktab >> (4u * mask0)) & 15u;
+    for (uint32_t c = 0; c < C; ++c) {
+      const uint32_t low10 = (uint32_t)*L::rec(lds, c) & 0x3ffu;
+      push(16u * ((whole_code(low10 >> 4) >> pos0) & 3u) + cls0, c, low10);
+    }
+  }
+
+  double now = 0.0;
+  // One pass starts at most one stage and, once no idle dimension has chunks
+  // waiting, advances the clock to the next completion (as in simulate_fast).
+  const uint32_t max_steps = 4u * D * C + 16u;
+  for (uint32_t step = 0; step <= max_steps; ++step) {
+    // a7: the lowest idle dimension with chunks waiting starts the first chunk
+    // of its lowest class -- the lowest set bit among the lists of idle dimensions
+    const uint32_t q = min(ffbl_or_ones((uint32_t)nonempty & ie_lo),
+                           ffbl_or_ones((uint32_t)(nonempty >> 32) & ie_hi) | 32u);
+    if (q < 64u) {
+      const uint32_t k = q >> 4;
+      uint8_t* tp = L::tail(lds, q);
+      const uint32_t t = *tp & 63u;
+      uint16_t* rt_p = L::rec(lds, t);
+      const uint32_t rt = *rt_p;
+      const uint32_t h = rt >> 10;                    // the head follows the tail
+      const uint32_t rh = *L::rec(lds, h);
+      // the tail now points to the head's successor (h == t: the list is empty
+      // and the record is written afresh when the chunk joins a list again)
+      *rt_p = (uint16_t)bfi(0x3ffu, rt, rh);
+      nonempty ^= (uint64_t)(h == t ? 1u : 0u) << q;
+      const uint32_t kbit = 1u << k;
+      const uint32_t mask = rh & 15u;
+      const uint32_t phase = (mask >> k) & 1u;        // waiting for k while reduced on k: All-Gather
+      // what the completion of this stage will do: a Reduce-Scatter sets the
+      // dimension's bit, an All-Gather clears it; the last Reduce-Scatter is
+      // followed by the All-Gather on the same dimension
+      const uint32_t mask2 = mask ^ kbit;
+      const bool is_full = mask2 == full;
+      const bool finished = phase != 0u ? mask2 == 0u : (rs_only && is_full);
+      const uint32_t phase2 = is_full ? 1u : phase;
+      // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
+      const uint32_t pos2 = 2u * ((uint32_t)__builtin_popcount(mask2) - phase2);
+      const uint32_t kn = (whole_code((rh >> 4) & 63u) >> (pos2 & 31u)) & 3u;  // (finished: not used)
+      const uint32_t cls2 = (uint32_t)(ranktab >> (4u * mask2)) & 15u;
+      const uint32_t val = (16u * kn + cls2) | (finished ? kRingFinished : 0u) |
+                           (((rh & 0x3ffu) ^ kbit) << 7) | (k << 17) | (h << 19);
+      // bytes moved on k = resident size before the chunk's Reduce-Scatter on
+      // k, i.e. with every reduced dimension but k itself taken off
+      ring_start_stage<kBusy, kFix>(k, val, now, scale_down(model.fs.base, esum(epack, mask & ~kbit)),
+                                    s.coef, s.fix, d, ie_lo, ie_hi);
+      if (kQueueOrder != kNoQueueOrder) {
+        const uint32_t pos = executed.get(k);
+        const uint32_t entry = (h << 1) | phase;
+        // pos < row_len always holds for a consistent plan; it keeps the store in bounds
+        if (kQueueOrder == kBytes) {
+          if (pos < row_len) out.queue_order[k * row_len + pos] = (uint8_t)entry;
+        } else {
+          // byte pos & 3 of dword pos >> 2 of row k; consecutive dwords of a lane lie 256 bytes apart
+          const uint32_t at = min(pos, row_len - 1u);
+          uint32_t word;  // k * dwords per row + at / 4 (a full-rate multiply-add)
+          asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(word) : "v"(k), "s"(out.slots >> 1), "v"(at >> 2));
+          out.queue_order[((word << 8) | (at & 3u)) + out.lane_offset] = (uint8_t)entry;
+        }
+        executed.inc(k);
+      }
+      ++started;
+    }
+    // all stages of an instant start before the clock moves
+    if ((((uint32_t)nonempty & ie_lo) | ((uint32_t)(nonempty >> 32) & ie_hi)) != 0u) continue;
+
+    // a8: advance to the earliest completion
+    const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));
+    if (!(next < kInf)) break;  // NaN: nothing running, every chunk is done (+inf: overflow)
+    now = next;
+    // deliver all completions of this instant, lowest chunk id first, so that
+    // equal arrival times are appended in chunk-id order
+    uint32_t key;
+    uint32_t done = ring_stages_ending(now, d, key, ie_lo, ie_hi);
+    for (;;) {
+      if ((key & kRingFinished) == 0u) push(key & 63u, key >> 19, (key >> 7) & 0x3ffu);
+      if ((done & (done - 1u)) == 0u) break;  // that was the last one, usually the only one
+      // one more stage ends at this very instant: the smallest one left
+      done &= ~(1u << ((key >> 17) & 3u));
+      key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
+                min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
+    }
+  }
+
+  FastResult res;
+  // as in simulate_fast: every stage ran and completed, and none was too short
+  // to move the clock
+  const double t_min = model.t_min(D);
+  const uint32_t stages = model.one_phase() ? D : 2u * D;
+  res.ok = started == stages * C && (ie_lo & ie_hi) == ~0u && (now + 0.25 * t_min > now);
+  res.t_done = now;
+  res.busy[0] = d.z0; res.busy[1] = d.z1; res.busy[2] = d.z2; res.busy[3] = d.z3;
+#pragma unroll
+  for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) res.executed[k] = executed.get(k);
+  return res;
+}
+
+}  // namespace themis
