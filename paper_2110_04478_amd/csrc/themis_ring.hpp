@@ -99,15 +99,14 @@ __device__ __forceinline__ uint32_t whole_code(uint32_t code6) {
   return code6 | (((code6 ^ (code6 >> 2) ^ (code6 >> 4)) & 3u) << 6);
 }
 
-// What the ring loop keeps per dimension beside DimState: nothing; its s0..s3
-// hold the running stage as
+// The ring loop's s0..s3 (DimState) hold the running stage as
 //   bits 0-5   list the chunk joins when the stage completes
 //   bit  6     the chunk is finished then
 //   bits 7-16  low ten bits of its record then (mask, order fields)
-//   bits 17-18 the dimension
-//   bits 19-24 the chunk
+//   bits 17-22 the chunk
 // so the smallest value among the stages that end at an instant is the one of
-// the lowest chunk id.
+// the lowest chunk id, and bits 7-22 are the record's bits and the chunk's link
+// to itself as push() takes them.
 //
 // The lanes of dimension J take their turn as the active ones (see
 // start_stage_scaled): the stage time, the finish time, the busy time, the
@@ -188,11 +187,36 @@ __device__ __forceinline__ uint32_t ring_stages_ending(double now, DimState& d, 
 
 constexpr uint32_t kRingFinished = 64u;
 
+// Position of the next stage in a chunk's order once its reduced dimensions
+// are mask2: the number of reduced dimensions, less one in the All-Gather
+// phase (phase: the stage that ends is an All-Gather; mask2 == full: it is the
+// last Reduce-Scatter, and the All-Gather starts on the same dimension).  The
+// two cases exclude each other, so both go into one subtract-with-borrow.
+__device__ __forceinline__ uint32_t ring_next_position(uint32_t mask2, uint32_t full, uint32_t phase) {
+  uint32_t pos;
+  asm("v_bcnt_u32_b32 %0, %1, 0\n\t"
+      "v_cmp_eq_u32_e32 vcc, %1, %2\n\t"
+      "v_subb_co_u32_e32 %0, vcc, %0, %3, vcc"
+      : "=&v"(pos) : "v"(mask2), "v"(full), "v"(phase) : "vcc");
+  return pos;
+}
+
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0x96" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // Same contract as simulate_fast: records initialised with
 // LayoutRing::init_chunk(), result.ok false leaves the evaluation to the
 // generic path; power-of-two model only.  Queue orders leave as single
 // entries (kBytes into the lane's own rows, kStagedBytes into the wavefront's
 // staging block).  Nothing in the block has to be cleared beforehand.
+//
+// The wavefront leaves the loop as a whole: a lane that is through (no list
+// holds a chunk, no stage runs) finds nothing to start and nothing to complete
+// in the passes its neighbours still need, so it needs no exit of its own and
+// the loop carries no mask of lanes that have left.
 template <int kQueueOrder, bool kBusy, bool kFix>
 __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow2Model& model,
                                                     const LaneLds& lds, const FastOut& out) {
@@ -205,36 +229,44 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
   const double kInf = inf64();
   const uint32_t epack = model.fs.epack;
   const uint64_t ranktab = model.ranktab;
-  const bool rs_only = model.rs_only();
+  // a chunk is finished when its mask comes back to zero (the last All-Gather
+  // of an All-Reduce or an All-Gather; a Reduce-Scatter never leaves zero), a
+  // stand-alone Reduce-Scatter when it is full
+  const uint32_t fin_mask = model.rs_only() ? full : 0u;
 
   DimState d;
   d.f0 = d.f1 = d.f2 = d.f3 = nan64();
   d.z0 = d.z1 = d.z2 = d.z3 = 0.0;
   d.s0 = d.s1 = d.s2 = d.s3 = 0u;
-  uint64_t nonempty = 0;              // bit q: list q holds chunks
+  uint32_t ne_lo = 0u, ne_hi = 0u;    // bit q of the pair: list q holds chunks
   uint32_t ie_lo = ~0u, ie_hi = ~0u;  // the sixteen bits of every idle dimension
   typename L::Ids executed;           // operations started per dimension (kept with queue orders)
   uint32_t started = 0;               // operations started in all
   const uint32_t row_len = 2u * out.slots;
 
-  // chunk c, whose record is to carry low10 (mask, order fields), becomes the
-  // last of list q.  Branch-free: an empty list makes c its own successor (the
-  // second store then repeats the first), otherwise c takes over the old
-  // tail's link to the head and the old tail points to c.
-  auto push = [&](uint32_t q, uint32_t c, uint32_t low10) {
-    const uint64_t bit = 1ull << q;
-    const bool had = (nonempty & bit) != 0ull;
-    uint8_t* tp = L::tail(lds, q);
+  // chunk c = w >> 10, whose record is to carry w & 0x3ff (mask, order
+  // fields), becomes the last of list q (only the low six bits of q count).
+  // Branch-free: an empty list makes c its own successor (the second store
+  // then repeats the first), otherwise c takes over the old tail's link to the
+  // head and the old tail points to c.
+  auto push = [&](uint32_t q, uint32_t w) {
+    const uint64_t bit = 1ull << (q & 63u);
+    const uint32_t b_lo = (uint32_t)bit, b_hi = (uint32_t)(bit >> 32);
+    const bool had = ((ne_lo & b_lo) | (ne_hi & b_hi)) != 0u;
+    uint8_t* tp = L::tail(lds, q & 63u);
     const uint32_t t = *tp & 63u;  // an empty list's tail is whatever the byte holds
     uint16_t* rt_p = L::rec(lds, t);
     const uint32_t rt = *rt_p;
+    const uint32_t c = w >> 10;
     uint16_t* rc_p = L::rec(lds, c);
-    const uint32_t recc = low10 | ((had ? (rt >> 10) : c) << 10);
+    const uint32_t c10 = w & 0xfc00u;
+    const uint32_t recc = bfi(0x3ffu, w, had ? rt : c10);   // low ten bits of w, link of the old tail or to itself
     *rc_p = (uint16_t)recc;
     uint16_t* dst = had ? rt_p : rc_p;
-    *dst = (uint16_t)(had ? ((rt & 0x3ffu) | (c << 10)) : recc);
+    *dst = (uint16_t)(had ? bfi(0x3ffu, rt, c10) : recc);
     *tp = (uint8_t)c;
-    nonempty |= bit;
+    ne_lo |= b_lo;
+    ne_hi |= b_hi;
   };
 
   // a6: every chunk waits at the dimension of its first stage, in chunk-id
@@ -245,19 +277,21 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
     const uint32_t cls0 = (uint32_t)(ranktab >> (4u * mask0)) & 15u;
     for (uint32_t c = 0; c < C; ++c) {
       const uint32_t low10 = (uint32_t)*L::rec(lds, c) & 0x3ffu;
-      push(16u * ((whole_code(low10 >> 4) >> pos0) & 3u) + cls0, c, low10);
+      push(16u * ((whole_code(low10 >> 4) >> pos0) & 3u) + cls0, low10 | (c << 10));
     }
   }
 
   double now = 0.0;
   // One pass starts at most one stage and, once no idle dimension has chunks
   // waiting, advances the clock to the next completion (as in simulate_fast).
-  const uint32_t max_steps = 4u * D * C + 16u;
-  for (uint32_t step = 0; step <= max_steps; ++step) {
+  // Every pass of a lane that is not through starts or completes a stage, so
+  // 4 * D * C passes and a few always suffice; the bound is the same for all
+  // lanes (it only has to end the loop whatever the records hold).
+  constexpr uint32_t kMaxSteps = 4u * (uint32_t)kMaxDims * L::kCap + 16u;
+  for (uint32_t step = 0; step < kMaxSteps; ++step) {
     // a7: the lowest idle dimension with chunks waiting starts the first chunk
     // of its lowest class -- the lowest set bit among the lists of idle dimensions
-    const uint32_t q = min(ffbl_or_ones((uint32_t)nonempty & ie_lo),
-                           ffbl_or_ones((uint32_t)(nonempty >> 32) & ie_hi) | 32u);
+    const uint32_t q = min(ffbl_or_ones(ne_lo & ie_lo), ffbl_or_ones(ne_hi & ie_hi) | 32u);
     if (q < 64u) {
       const uint32_t k = q >> 4;
       uint8_t* tp = L::tail(lds, q);
@@ -269,7 +303,12 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
       // the tail now points to the head's successor (h == t: the list is empty
       // and the record is written afresh when the chunk joins a list again)
       *rt_p = (uint16_t)bfi(0x3ffu, rt, rh);
-      nonempty ^= (uint64_t)(h == t ? 1u : 0u) << q;
+      {
+        const uint32_t gone = (uint32_t)((int32_t)((h ^ t) - 1u) >> 31);  // all-ones if h == t
+        const uint64_t bit = 1ull << q;
+        ne_lo ^= (uint32_t)bit & gone;
+        ne_hi ^= (uint32_t)(bit >> 32) & gone;
+      }
       const uint32_t kbit = 1u << k;
       const uint32_t mask = rh & 15u;
       const uint32_t phase = (mask >> k) & 1u;        // waiting for k while reduced on k: All-Gather
@@ -277,28 +316,29 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
       // dimension's bit, an All-Gather clears it; the last Reduce-Scatter is
       // followed by the All-Gather on the same dimension
       const uint32_t mask2 = mask ^ kbit;
-      const bool is_full = mask2 == full;
-      const bool finished = phase != 0u ? mask2 == 0u : (rs_only && is_full);
-      const uint32_t phase2 = is_full ? 1u : phase;
       // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
-      const uint32_t pos2 = 2u * ((uint32_t)__builtin_popcount(mask2) - phase2);
-      const uint32_t kn = (whole_code((rh >> 4) & 63u) >> (pos2 & 31u)) & 3u;  // (finished: not used)
+      const uint32_t pos = ring_next_position(mask2, full, phase);
+      const uint32_t c6 = (rh >> 4) & 63u;
+      const uint32_t code = (xor3(c6, c6 >> 2, c6 >> 4) << 6) | c6;   // bits 6-7: the fourth field
+      const uint32_t kn = (code >> ((pos + pos) & 31u)) & 3u;         // (finished: not used)
       const uint32_t cls2 = (uint32_t)(ranktab >> (4u * mask2)) & 15u;
-      const uint32_t val = (16u * kn + cls2) | (finished ? kRingFinished : 0u) |
-                           (((rh & 0x3ffu) ^ kbit) << 7) | (k << 17) | (h << 19);
+      const uint32_t q2 = (16u * kn + cls2) | (mask2 == fin_mask ? kRingFinished : 0u);
+      // the chunk and its record's low bits then (the stage flips k's bit), above the list
+      const uint32_t val = (bfi(0x3ffu, rh ^ kbit, rt) << 7) | q2;
       // bytes moved on k = resident size before the chunk's Reduce-Scatter on
       // k, i.e. with every reduced dimension but k itself taken off
-      ring_start_stage<kBusy, kFix>(k, val, now, scale_down(model.fs.base, esum(epack, mask & ~kbit)),
+      // (mask & mask2 is mask without k, whichever way the stage flips it)
+      ring_start_stage<kBusy, kFix>(k, val, now, scale_down(model.fs.base, esum(epack, mask & mask2)),
                                     s.coef, s.fix, d, ie_lo, ie_hi);
       if (kQueueOrder != kNoQueueOrder) {
-        const uint32_t pos = executed.get(k);
-        const uint32_t entry = (h << 1) | phase;
-        // pos < row_len always holds for a consistent plan; it keeps the store in bounds
+        const uint32_t pos_k = executed.get(k);
+        const uint32_t entry = (h + h) | phase;
+        // pos_k < row_len always holds for a consistent plan; it keeps the store in bounds
         if (kQueueOrder == kBytes) {
-          if (pos < row_len) out.queue_order[k * row_len + pos] = (uint8_t)entry;
+          if (pos_k < row_len) out.queue_order[k * row_len + pos_k] = (uint8_t)entry;
         } else {
           // byte pos & 3 of dword pos >> 2 of row k; consecutive dwords of a lane lie 256 bytes apart
-          const uint32_t at = min(pos, row_len - 1u);
+          const uint32_t at = min(pos_k, row_len - 1u);
           uint32_t word;  // k * dwords per row + at / 4 (a full-rate multiply-add)
           asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(word) : "v"(k), "s"(out.slots >> 1), "v"(at >> 2));
           out.queue_order[((word << 8) | (at & 3u)) + out.lane_offset] = (uint8_t)entry;
@@ -307,25 +347,29 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
       }
       ++started;
     }
-    // all stages of an instant start before the clock moves
-    if ((((uint32_t)nonempty & ie_lo) | ((uint32_t)(nonempty >> 32) & ie_hi)) != 0u) continue;
-
-    // a8: advance to the earliest completion
+    // all stages of an instant start before the clock moves; then the clock
+    // advances to the earliest completion (NaN: nothing runs; +inf: overflow)
+    const bool more = ((ne_lo & ie_lo) | (ne_hi & ie_hi)) != 0u;
     const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));
-    if (!(next < kInf)) break;  // NaN: nothing running, every chunk is done (+inf: overflow)
-    now = next;
-    // deliver all completions of this instant, lowest chunk id first, so that
-    // equal arrival times are appended in chunk-id order
-    uint32_t key;
-    uint32_t done = ring_stages_ending(now, d, key, ie_lo, ie_hi);
-    for (;;) {
-      if ((key & kRingFinished) == 0u) push(key & 63u, key >> 19, (key >> 7) & 0x3ffu);
-      if ((done & (done - 1u)) == 0u) break;  // that was the last one, usually the only one
-      // one more stage ends at this very instant: the smallest one left
-      done &= ~(1u << ((key >> 17) & 3u));
-      key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
-                min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
+    const bool running = next < kInf;
+    if (!more && running) {
+      now = next;
+      // a8: deliver all completions of this instant, lowest chunk id first, so
+      // that equal arrival times are appended in chunk-id order
+      uint32_t key;
+      uint32_t done = ring_stages_ending(now, d, key, ie_lo, ie_hi);
+      if ((key & kRingFinished) == 0u) push(key, key >> 7);
+      // more stages end at this very instant (rare): the smallest one left, again and again
+      while ((done & (done - 1u)) != 0u) {
+        done &= ~((key == d.s0 ? 1u : 0u) | (key == d.s1 ? 2u : 0u) | (key == d.s2 ? 4u : 0u) |
+                  (key == d.s3 ? 8u : 0u));
+        key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
+                  min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
+        if ((key & kRingFinished) == 0u) push(key, key >> 7);
+      }
     }
+    // through: nothing waits, nothing runs -- for every lane of the wavefront
+    if (__builtin_amdgcn_ballot_w64(more || running) == 0ull) break;
   }
 
   FastResult res;
@@ -333,7 +377,8 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
   // to move the clock
   const double t_min = model.t_min(D);
   const uint32_t stages = model.one_phase() ? D : 2u * D;
-  res.ok = started == stages * C && (ie_lo & ie_hi) == ~0u && (now + 0.25 * t_min > now);
+  res.ok = started == stages * C && (ie_lo & ie_hi) == ~0u && (ne_lo | ne_hi) == 0u &&
+           (now + 0.25 * t_min > now);
   res.t_done = now;
   res.busy[0] = d.z0; res.busy[1] = d.z1; res.busy[2] = d.z2; res.busy[3] = d.z3;
 #pragma unroll
