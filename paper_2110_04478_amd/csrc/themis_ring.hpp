@@ -47,9 +47,13 @@ struct LayoutRing {
   static constexpr uint32_t kCap = 64;
   static constexpr uint32_t kRecBytes = kCap * 128u;   // 64 records x 64 lanes x 2 bytes
   static constexpr uint32_t kTailBytes = 64u * 64u;    // 64 lists x 64 lanes
-  // 53 dwords per lane (13,568 bytes per wavefront) keep it at exactly twelve
-  // wavefronts per CU; the block itself needs 48
-  static constexpr uint32_t kLaneWords = 53;
+  // The block itself needs 48 dwords per lane.  50 (12,800 bytes per
+  // wavefront) is what measures best: twelve wavefronts per CU, three on every
+  // SIMD.  With 48 or 49 a thirteenth wavefront fits, and kernels whose
+  // registers allow a fourth wavefront on a SIMD then run 9 % slower (wavefront
+  // counts per CU that are not a multiple of four never paid here); from 51 on
+  // every kernel runs 7 % slower, as if only eleven were resident.
+  static constexpr uint32_t kLaneWords = 50;
   static_assert(kLaneWords * 256u >= kRecBytes + kTailBytes, "block holds records and tails");
   static constexpr uint32_t kWavesPerSimd = 3;
   using Ids = Pack4<uint32_t, 8>;
