@@ -54,7 +54,8 @@ struct LayoutRing {
   // counts per CU that are not a multiple of four never paid here); from 51 on
   // every kernel runs 7 % slower, as if only eleven were resident.
   static constexpr uint32_t kLaneWords = 50;
-  static_assert(kLaneWords * 256u >= kRecBytes + kTailBytes, "block holds records and tails");
+  static constexpr uint32_t kTableBytes = 24u * 8u * 2u;  // the wavefront's stage table (ring_loop)
+  static_assert(kLaneWords * 256u >= kRecBytes + kTailBytes + kTableBytes, "block holds records, tails and table");
   static constexpr uint32_t kWavesPerSimd = 3;
   using Ids = Pack4<uint32_t, 8>;
   static __device__ __forceinline__ uint32_t lane_term_rec(uint32_t lane) {
@@ -211,6 +212,56 @@ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
   return r;
 }
 
+// Lexicographic rank (0..23) of an order code whose D fields are a
+// permutation of 0..D-1, read as a permutation of all four dimensions (the
+// unused fields take their own index).
+__device__ __forceinline__ uint32_t ring_order_rank(uint32_t code, uint32_t D) {
+  const uint32_t c8 = code | (0xe4u & ~((1u << (2u * D)) - 1u));
+  const uint32_t o0 = c8 & 3u, o1 = (c8 >> 2) & 3u, o2 = (c8 >> 4) & 3u, o3 = (c8 >> 6) & 3u;
+  const uint32_t r1 = o1 - (o1 > o0 ? 1u : 0u);
+  return 6u * o0 + 2u * r1 + (o2 > o3 ? 1u : 0u);
+}
+
+// The four-field order code of rank r (inverse of ring_order_rank).
+__device__ __forceinline__ uint32_t ring_order_of_rank(uint32_t r) {
+  uint32_t pool = 0x3210u, code = 0u, fact = 6u;
+#pragma unroll
+  for (uint32_t j = 0; j < 4u; ++j) {
+    const uint32_t pick = r / fact;
+    r -= pick * fact;
+    code |= ((pool >> (4u * pick)) & 3u) << (2u * j);
+    pool = (pool & ((1u << (4u * pick)) - 1u)) | ((pool >> (4u * (pick + 1u))) << (4u * pick));
+    if (j < 2u) fact /= (3u - j);
+  }
+  return code;
+}
+
+// Entry (order of rank r, `behind` stages done) of the wavefront's stage table
+// (see ring_loop): the chunk's states are walked from the initial one, with the
+// transitions the loop without a table takes one at a time.
+__device__ inline uint32_t ring_table_entry(uint32_t r, uint32_t behind, uint32_t state0,
+                                            uint32_t full, uint32_t fin_mask, uint32_t epack,
+                                            uint64_t ranktab) {
+  const uint32_t code = ring_order_of_rank(r);
+  uint32_t mask = state0 & 15u, phase = (state0 >> 4) & 1u;
+  for (uint32_t i = 0; i <= behind; ++i) {
+    const uint32_t pos = ((uint32_t)__builtin_popcount(mask) - phase) & 3u;
+    const uint32_t k = (code >> (2u * pos)) & 3u;
+    const uint32_t mask2 = (mask ^ (1u << k)) & 15u;
+    const uint32_t phase2 = phase | (mask2 == full ? 1u : 0u);
+    if (i == behind) {
+      const uint32_t pos2 = ((uint32_t)__builtin_popcount(mask2) - phase2) & 3u;
+      const uint32_t kn = (code >> (2u * pos2)) & 3u;
+      const uint32_t cls2 = (uint32_t)(ranktab >> (4u * mask2)) & 15u;
+      return (16u * kn + cls2) | (mask2 == fin_mask ? kRingFinished : 0u) | (phase << 8) |
+             ((esum(epack, mask & mask2) & 127u) << 9);
+    }
+    mask = mask2;
+    phase = phase2;
+  }
+  return 0u;
+}
+
 // Same contract as simulate_fast: records initialised with
 // LayoutRing::init_chunk(), result.ok false leaves the evaluation to the
 // generic path; power-of-two model only.  Queue orders leave as single
@@ -221,9 +272,25 @@ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
 // holds a chunk, no stage runs) finds nothing to start and nothing to complete
 // in the passes its neighbours still need, so it needs no exit of its own and
 // the loop carries no mask of lanes that have left.
-template <int kQueueOrder, bool kBusy, bool kFix>
-__device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow2Model& model,
-                                                    const LaneLds& lds, const FastOut& out) {
+//
+// kTable: every lane of the wavefront evaluates the same network under the
+// same policy (the usual parameter study: one topology, many bandwidths, sizes
+// and thresholds), so what a stage does depends only on the chunk's order and
+// on how many stages it has behind it.  The wavefront then shares one table in
+// LDS, entry (order, stage):
+//   bits 0-5   list the chunk joins when the stage completes
+//   bit  6     the chunk is finished then
+//   bit  8     the stage is an All-Gather
+//   bits 9-15  sum of log2 P over the dimensions the chunk is reduced on,
+//              the stage's own dimension left out (its resident-size exponent)
+// and a chunk's record carries bits 0-2 the number of stages behind it and
+// bits 3-7 its order as the lexicographic rank of the four-field code, in
+// place of mask and order fields.  One table read replaces the arithmetic that
+// derives all of that from mask and code at every stage start.
+template <bool kTable, int kQueueOrder, bool kBusy, bool kFix>
+__device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Model& model,
+                                                const LaneLds& lds, const FastOut& out,
+                                                const uint8_t* table) {
   static_assert(kQueueOrder == kNoQueueOrder || kQueueOrder == kBytes || kQueueOrder == kStagedBytes,
                 "entries are stored one by one");
   using L = LayoutRing;
@@ -281,7 +348,10 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
     const uint32_t cls0 = (uint32_t)(ranktab >> (4u * mask0)) & 15u;
     for (uint32_t c = 0; c < C; ++c) {
       const uint32_t low10 = (uint32_t)*L::rec(lds, c) & 0x3ffu;
-      push(16u * ((whole_code(low10 >> 4) >> pos0) & 3u) + cls0, low10 | (c << 10));
+      const uint32_t code = whole_code(low10 >> 4);
+      // kTable: no stage behind it, the order by its rank
+      push(16u * ((code >> pos0) & 3u) + cls0,
+           (kTable ? ring_order_rank(code, D) << 3 : low10) | (c << 10));
     }
   }
 
@@ -313,27 +383,38 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
         ne_lo ^= (uint32_t)bit & gone;
         ne_hi ^= (uint32_t)(bit >> 32) & gone;
       }
-      const uint32_t kbit = 1u << k;
-      const uint32_t mask = rh & 15u;
-      const uint32_t phase = (mask >> k) & 1u;        // waiting for k while reduced on k: All-Gather
-      // what the completion of this stage will do: a Reduce-Scatter sets the
-      // dimension's bit, an All-Gather clears it; the last Reduce-Scatter is
-      // followed by the All-Gather on the same dimension
-      const uint32_t mask2 = mask ^ kbit;
-      // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
-      const uint32_t pos = ring_next_position(mask2, full, phase);
-      const uint32_t c6 = (rh >> 4) & 63u;
-      const uint32_t code = (xor3(c6, c6 >> 2, c6 >> 4) << 6) | c6;   // bits 6-7: the fourth field
-      const uint32_t kn = (code >> ((pos + pos) & 31u)) & 3u;         // (finished: not used)
-      const uint32_t cls2 = (uint32_t)(ranktab >> (4u * mask2)) & 15u;
-      const uint32_t q2 = (16u * kn + cls2) | (mask2 == fin_mask ? kRingFinished : 0u);
-      // the chunk and its record's low bits then (the stage flips k's bit), above the list
-      const uint32_t val = (bfi(0x3ffu, rh ^ kbit, rt) << 7) | q2;
+      uint32_t phase, val;
+      double bytes;
+      if (kTable) {
+        const uint32_t e = *(const uint16_t*)(table + 2u * (rh & 0xffu));
+        phase = (e >> 8) & 1u;
+        // the chunk and its record's low bits then (one more stage behind it), above the list
+        val = (bfi(0x3ffu, rh + 1u, rt) << 7) | (e & 0x7fu);
+        bytes = __hiloint2double(__double2hiint(model.fs.base) - (int)((e << 11) & 0x07f00000u),
+                                 __double2loint(model.fs.base));
+      } else {
+        const uint32_t kbit = 1u << k;
+        const uint32_t mask = rh & 15u;
+        phase = (mask >> k) & 1u;        // waiting for k while reduced on k: All-Gather
+        // what the completion of this stage will do: a Reduce-Scatter sets the
+        // dimension's bit, an All-Gather clears it; the last Reduce-Scatter is
+        // followed by the All-Gather on the same dimension
+        const uint32_t mask2 = mask ^ kbit;
+        // next stage: RS -> order[#reduced], AG -> order[#reduced - 1]
+        const uint32_t pos = ring_next_position(mask2, full, phase);
+        const uint32_t c6 = (rh >> 4) & 63u;
+        const uint32_t code = (xor3(c6, c6 >> 2, c6 >> 4) << 6) | c6;   // bits 6-7: the fourth field
+        const uint32_t kn = (code >> ((pos + pos) & 31u)) & 3u;         // (finished: not used)
+        const uint32_t cls2 = (uint32_t)(ranktab >> (4u * mask2)) & 15u;
+        const uint32_t q2 = (16u * kn + cls2) | (mask2 == fin_mask ? kRingFinished : 0u);
+        // the chunk and its record's low bits then (the stage flips k's bit), above the list
+        val = (bfi(0x3ffu, rh ^ kbit, rt) << 7) | q2;
+        // (mask & mask2 is mask without k, whichever way the stage flips it)
+        bytes = scale_down(model.fs.base, esum(epack, mask & mask2));
+      }
       // bytes moved on k = resident size before the chunk's Reduce-Scatter on
       // k, i.e. with every reduced dimension but k itself taken off
-      // (mask & mask2 is mask without k, whichever way the stage flips it)
-      ring_start_stage<kBusy, kFix>(k, val, now, scale_down(model.fs.base, esum(epack, mask & mask2)),
-                                    s.coef, s.fix, d, ie_lo, ie_hi);
+      ring_start_stage<kBusy, kFix>(k, val, now, bytes, s.coef, s.fix, d, ie_lo, ie_hi);
       if (kQueueOrder != kNoQueueOrder) {
         const uint32_t pos_k = executed.get(k);
         const uint32_t entry = (h + h) | phase;
@@ -388,6 +469,41 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
 #pragma unroll
   for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) res.executed[k] = executed.get(k);
   return res;
+}
+
+constexpr uint32_t kRingTableEntries = 24u * 8u;
+
+template <int kQueueOrder, bool kBusy, bool kFix>
+__device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow2Model& model,
+                                                    const LaneLds& lds, const FastOut& out) {
+  using L = LayoutRing;
+  // Do the lanes that are here (others may have left with an invalid scenario)
+  // all evaluate the same network, collective type and queue policy?
+  const uint32_t D = (uint32_t)s.D;
+  const uint32_t full = (1u << D) - 1u;
+  const uint32_t fin_mask = model.rs_only() ? full : 0u;
+  const uint32_t sig[5] = {model.fs.epack, D | (model.state0() << 8) | (fin_mask << 16),
+                           (uint32_t)model.ranktab, (uint32_t)(model.ranktab >> 32), 0u};
+  bool same = true;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) same = same && sig[j] == (uint32_t)__builtin_amdgcn_readfirstlane((int)sig[j]);
+  const uint64_t here = __builtin_amdgcn_ballot_w64(true);
+  if (__builtin_amdgcn_ballot_w64(!same) != 0ull)
+    return ring_loop<false, kQueueOrder, kBusy, kFix>(s, model, lds, out, nullptr);
+  // the table sits behind the records and tails of the wavefront's block; the
+  // lanes that are here fill it together
+  uint8_t* table = lds.aux - L::lane_term_tail(threadIdx.x) + L::kRecBytes + L::kTailBytes;
+  const uint32_t lanes = (uint32_t)__builtin_popcountll(here);
+  const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(here >> 32),
+                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)here, 0u));
+  for (uint32_t i = rank; i < kRingTableEntries; i += lanes)
+    ((uint16_t*)table)[i] = (uint16_t)ring_table_entry(i >> 3, i & 7u, model.state0(), full, fin_mask,
+                                                       model.fs.epack, model.ranktab);
+  // the stores of a wavefront reach the LDS in program order; the fence keeps
+  // the compiler from moving the loop's reads above them
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  return ring_loop<true, kQueueOrder, kBusy, kFix>(s, model, lds, out, table);
 }
 
 }  // namespace themis
