@@ -668,9 +668,13 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
              unsigned policy_mask, int n_pol, double* __restrict__ t_done,
              unsigned long long hand_over) {
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
-  uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
-  if (e >= total) return;
+  // A wavefront takes 64 consecutive scenarios under one threshold and one
+  // scheduler: its lanes read consecutive inputs, and on a batch that keeps to
+  // one network they all take the same path through the event loop.
+  const uint32_t per = (uint32_t)n_thr * (uint32_t)n_pol;   // evaluations per scenario
+  const uint64_t i = (uint64_t)(blockIdx.x / per) * kBlock + threadIdx.x;
+  if (i >= b.n) return;
+  const uint64_t e = i * per + blockIdx.x % per;
   const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
 
   Scenario s = load_scenario(b, it.i);
@@ -1271,7 +1275,9 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   if ((uintptr_t)workspace & 15u) return THEMIS_ERR_WORKSPACE;
   int n_pol = __builtin_popcount(policy_mask & 7u);
   uint64_t evals = batch->n * (uint64_t)n_thr * (uint64_t)n_pol;
-  if (evals > (uint64_t)0x7fffffff * kBlock) return THEMIS_ERR_UNSUPPORTED;
+  if (evals > (uint64_t)0x7fffffff * kBlock ||
+      (uint64_t)blocks_for(batch->n) * (uint64_t)(n_thr * n_pol) > 0x7fffffffull)
+    return THEMIS_ERR_UNSUPPORTED;
   const bool have_ws = workspace != nullptr &&
                        workspace_bytes_given >= workspace_bytes(evals, batch->max_chunks);
   Workspace w = carve_workspace(workspace, evals, batch->max_chunks);
@@ -1285,7 +1291,7 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   auto generic = cap <= 16u ? sweep_generic_kernel<16> : cap <= 64u ? sweep_generic_kernel<64>
                                                                     : sweep_generic_kernel<0>;
   const unsigned long long call = next_call_number();
-  hipLaunchKernelGGL(kernel, dim3(blocks_for(evals)), dim3(kBlock), 0,
+  hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n) * (unsigned)(n_thr * n_pol)), dim3(kBlock), 0,
                      (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
                      n_pol, t_done, call);
   if (cap <= 64u) {

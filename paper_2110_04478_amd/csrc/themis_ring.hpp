@@ -126,11 +126,15 @@ __device__ __forceinline__ uint32_t whole_code(uint32_t code6) {
 #define THEMIS_RING_START(J, IE, KEEP, BUSY, FIX)                               \
   THEMIS_LANES_OF(J) THEMIS_MUL(J) THEMIS_RING_FIX_##FIX(J) THEMIS_END(J)      \
   THEMIS_RING_BUSY_##BUSY(J, IE, KEEP) THEMIS_SERVE(J)                          \
-  "v_and_b32_e32 %[" #IE "], " #KEEP ", %[" #IE "]\n\t" THEMIS_ALL_LANES
+  "v_and_b32_e32 %[" #IE "], %[" #KEEP "], %[" #IE "]\n\t" THEMIS_ALL_LANES
 #define THEMIS_RING_STARTS(BUSY, FIX)                                               \
   "s_mov_b64 %[act], exec\n\t"                                                      \
-  THEMIS_RING_START(0, iel, 0xffff0000, BUSY, FIX) THEMIS_RING_START(1, iel, 0xffff, BUSY, FIX) \
-  THEMIS_RING_START(2, ieh, 0xffff0000, BUSY, FIX) THEMIS_RING_START(3, ieh, 0xffff, BUSY, FIX)
+  THEMIS_RING_START(0, iel, upper, BUSY, FIX) THEMIS_RING_START(1, iel, lower, BUSY, FIX) \
+  THEMIS_RING_START(2, ieh, upper, BUSY, FIX) THEMIS_RING_START(3, ieh, lower, BUSY, FIX)
+
+// the two halves of a register, from scalar registers (a literal would make
+// the instruction twice as long)
+#define THEMIS_RING_HALVES [upper] "s"(0xffff0000u), [lower] "s"(0x0000ffffu)
 
 template <bool kBusy, bool kFix>
 __device__ __forceinline__ void ring_start_stage(uint32_t k, uint32_t val, double now, double x,
@@ -143,24 +147,26 @@ __device__ __forceinline__ void ring_start_stage(uint32_t k, uint32_t val, doubl
     asm volatile(THEMIS_RING_STARTS(1, 1)
         : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
           THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
-        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
-          THEMIS_A_OPERANDS : "vcc");
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_RING_HALVES,
+          THEMIS_C_OPERANDS, THEMIS_A_OPERANDS : "vcc");
   } else if (kBusy) {
     asm volatile(THEMIS_RING_STARTS(1, 0)
         : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
           THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
-        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_RING_HALVES,
+          THEMIS_C_OPERANDS : "vcc");
   } else if (kFix) {
     asm volatile(THEMIS_RING_STARTS(0, 1)
         : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
           THEMIS_S_OPERANDS
-        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
-          THEMIS_A_OPERANDS : "vcc");
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_RING_HALVES,
+          THEMIS_C_OPERANDS, THEMIS_A_OPERANDS : "vcc");
   } else {
     asm volatile(THEMIS_RING_STARTS(0, 0)
         : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
           THEMIS_S_OPERANDS
-        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
+        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_RING_HALVES,
+          THEMIS_C_OPERANDS : "vcc");
   }
 }
 
@@ -173,19 +179,19 @@ __device__ __forceinline__ void ring_start_stage(uint32_t k, uint32_t val, doubl
   "v_mov_b64_e32 %[f" #J "], %[nan]\n\t"                   \
   "v_min_u32_e32 %[first], %[first], %[s" #J "]\n\t"       \
   "v_or_b32_e32 %[done], " #BIT ", %[done]\n\t"            \
-  "v_or_b32_e32 %[" #IE "], " #FIELD ", %[" #IE "]\n\t" THEMIS_ALL_LANES
+  "v_or_b32_e32 %[" #IE "], %[" #FIELD "], %[" #IE "]\n\t" THEMIS_ALL_LANES
 __device__ __forceinline__ uint32_t ring_stages_ending(double now, DimState& d, uint32_t& first,
                                                        uint32_t& ie_lo, uint32_t& ie_hi) {
   uint64_t act;
   uint32_t done = 0u;
   first = ~0u;
   asm volatile("s_mov_b64 %[act], exec\n\t"
-      THEMIS_RING_ENDS(0, 1, iel, 0xffff) THEMIS_RING_ENDS(1, 2, iel, 0xffff0000)
-      THEMIS_RING_ENDS(2, 4, ieh, 0xffff) THEMIS_RING_ENDS(3, 8, ieh, 0xffff0000)
+      THEMIS_RING_ENDS(0, 1, iel, lower) THEMIS_RING_ENDS(1, 2, iel, upper)
+      THEMIS_RING_ENDS(2, 4, ieh, lower) THEMIS_RING_ENDS(3, 8, ieh, upper)
       : [act] "=&s"(act), [done] "+v"(done), [first] "+v"(first), [iel] "+v"(ie_lo),
         [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS
       : [now] "v"(now), [nan] "v"(nan64()), [s0] "v"(d.s0), [s1] "v"(d.s1), [s2] "v"(d.s2),
-        [s3] "v"(d.s3)
+        [s3] "v"(d.s3), THEMIS_RING_HALVES
       : "vcc");
   return done;
 }
@@ -312,7 +318,7 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
   uint32_t ne_lo = 0u, ne_hi = 0u;    // bit q of the pair: list q holds chunks
   uint32_t ie_lo = ~0u, ie_hi = ~0u;  // the sixteen bits of every idle dimension
   typename L::Ids executed;           // operations started per dimension (kept with queue orders)
-  uint32_t started = 0;               // operations started in all
+  uint32_t started = 0;               // operations started in all (counted without queue orders)
   const uint32_t row_len = 2u * out.slots;
 
   // chunk c = w >> 10, whose record is to carry w & 0x3ff (mask, order
@@ -429,8 +435,9 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
           out.queue_order[((word << 8) | (at & 3u)) + out.lane_offset] = (uint8_t)entry;
         }
         executed.inc(k);
+      } else {
+        ++started;
       }
-      ++started;
     }
     // all stages of an instant start before the clock moves; then the clock
     // advances to the earliest completion (NaN: nothing runs; +inf: overflow)
@@ -462,6 +469,7 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
   // to move the clock
   const double t_min = model.t_min(D);
   const uint32_t stages = model.one_phase() ? D : 2u * D;
+  if (kQueueOrder != kNoQueueOrder) started = executed.sum();
   res.ok = started == stages * C && (ie_lo & ie_hi) == ~0u && (ne_lo | ne_hi) == 0u &&
            (now + 0.25 * t_min > now);
   res.t_done = now;

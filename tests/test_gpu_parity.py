@@ -889,3 +889,62 @@ def test_special_values(gpu, oracle, max_chunks, pow2, thr_mode):
     b.bw = np.ascontiguousarray(bw)
     t = check_batch(gpu, oracle, b, threads=16)
     assert 0 < int(np.isnan(t).sum()) < n
+
+
+@pytest.mark.parametrize("ctype", [0, 1, 2])
+def test_wavefronts_that_share_one_network(gpu, oracle, ctype):
+    """Parameter studies put one topology into every lane of a wavefront, only
+    bandwidths, sizes, chunk counts and thresholds differ: such wavefronts take
+    what a stage does from an (order, stage) table the wavefront builds once.
+    Every dimension count, both queue policies, each collective type, planned
+    and arbitrary orders (all D! permutations inside a scenario), fixed delays,
+    a ragged last wavefront, an invalid scenario inside a wavefront, and a
+    batch whose wavefronts differ from each other (one table per wavefront)."""
+    import torch
+    W = w()
+    rng = np.random.default_rng(600 + ctype)
+    nets = [(1, [8]), (2, [4, 16]), (3, [2, 8, 4]), (4, [2, 8, 8, 64]), (4, [16, 2, 4, 4]), (3, [64, 2, 2])]
+    parts = []
+    for D, P in nets:
+        for intra in (0, 1):
+            n = 64 * 2 + (17 if (D, intra) == (4, 1) else 0)
+            b = W.config3(n=n, seed=W.SEED_BASE + 100 * D + intra)
+            b.ndims[:] = D
+            b.npus[:, :] = 2
+            for k in range(D):
+                b.npus[k, :] = P[k]
+            b.intra_policy[:] = intra
+            b.chunks = rng.integers(1, 65, n).astype(np.uint32)
+            b.chunks[:3] = [64, 1, 63]
+            parts.append(b)
+    cat = lambda f: np.concatenate([getattr(p, f) for p in parts], axis=-1)
+    n = sum(p.n for p in parts)
+    b = W.ScenarioBatch(n=n, max_chunks=64, threshold_mode=W.THR_REL, ndims=cat("ndims"),
+                        npus=np.ascontiguousarray(cat("npus")), bw=np.ascontiguousarray(cat("bw")),
+                        size_bytes=cat("size_bytes"), chunks=cat("chunks"),
+                        inter_policy=cat("inter_policy"), intra_policy=cat("intra_policy"),
+                        threshold=cat("threshold"))
+    b.collective_type = np.full(n, ctype, np.uint8)
+    b.bw[0, 70] = float("nan")            # an invalid scenario in the second wavefront
+    t = check_batch(gpu, oracle, b)
+    assert np.isnan(t[70]) and int(np.isnan(t).sum()) == 1
+    check_batch(gpu, oracle, _with_fixed_delay(b, 7))
+    # arbitrary orders
+    orders = np.full((n, 64), 0xFF, np.uint8)
+    for i in range(n):
+        D = int(b.ndims[i])
+        perms = np.argsort(rng.random((int(b.chunks[i]), D)), axis=1)
+        orders[i, :perms.shape[0]] = (perms << (2 * np.arange(D))).sum(axis=1)
+    o_t, o_qo, o_busy = oracle.simulate_batch(b, orders, threads=8)
+    d = gpu.to_device(b)
+    t, qo, busy = gpu.themis_simulate_batch(d, torch.from_numpy(orders).cuda())
+    torch.cuda.synchronize()
+    assert_close("t_done", t.cpu().numpy(), o_t)
+    assert np.array_equal(widen_queue(qo), o_qo)
+    assert_close("busy", busy.cpu().numpy(), o_busy)
+    if ctype == 0:      # the fused sweep on the same wavefronts (times only)
+        b.fixed_delay = None
+        thr = np.array([0.0, 1 / 16])
+        got = gpu.themis_sweep(gpu.to_device(b), torch.from_numpy(thr).cuda(), 7)
+        torch.cuda.synchronize()
+        assert_close("sweep", got.cpu().numpy(), oracle.sweep(b, thr, 7, threads=8))
