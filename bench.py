@@ -23,10 +23,25 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 compute units x 4 SIMDs, 2.4 GHz; a wave64 vector instruction
-# occupies its SIMD's issue port for 4 cycles (16 lanes per cycle).
-PEAK_WAVE_INSTR_PER_S = 256 * 4 * 2.4e9 / 4
-PEAK_LANE_OPS_PER_S = PEAK_WAVE_INSTR_PER_S * 64
+def device_peak(torch):
+    """Vector issue peak of the device the run is on: compute units x 4 SIMDs x
+    clock / 4 cycles per wave64 instruction, x 64 lanes.  Both figures come from
+    the device properties (MI355X: 256 CUs, 2.4 GHz -> 39.3 Tlane-op/s, which is
+    also the published 78.6 TFLOP/s of fp64 vector FMA)."""
+    p = torch.cuda.get_device_properties(0)
+    cus = int(p.multi_processor_count)
+    khz = getattr(p, "clock_rate", None)
+    if not khz:                       # older builds: ask the runtime
+        import ctypes
+        hip = ctypes.CDLL("libamdhip64.so")
+        v = ctypes.c_int(0)
+        rc = hip.hipDeviceGetAttribute(ctypes.byref(v), 5, 0)   # hipDeviceAttributeClockRate, kHz
+        khz = v.value
+        if rc != 0 or not 1e5 < khz < 1e7:
+            sys.exit("bench.py: the runtime reports no usable clock rate (%d, status %d)" % (khz, rc))
+    hz = float(khz) * 1e3
+    return {"compute_units": cus, "clock_mhz_nominal": hz / 1e6,
+            "wave_instr_per_s": cus * 4 * hz / 4, "lane_ops_per_s": cus * 4 * hz / 4 * 64}
 
 
 def algorithmic_lane_ops(D, C):
@@ -38,13 +53,32 @@ def algorithmic_lane_ops(D, C):
     return {"plan": 45 * C, "simulate": 2 * D * C * C}
 
 
-# Copied from profiles/simulate_kernel_config3.md (rocprofv3 --pmc runs of this
-# file on the default workload); not measured live.  Only attached to the JSON
-# line when the run uses that workload.
-PROFILED = {
-    "traffic_bytes_per_launch": 1.78e9,   # FETCH_SIZE x2.0 + WRITE_SIZE x1.0, simulate kernel
-    "valu_issue_frac": 0.672,             # SQ_ACTIVE_INST_VALU / (256 CUs x busy cycles)
-}
+def profiled_figures(name):
+    """Counter figures of an earlier rocprofv3 run of this file, kept as
+    `key: value` lines between the markers of profiles/<name>.md together with
+    the commit they were taken on.  None if the summary is not there."""
+    path = os.path.join(ROOT, "profiles", name + ".md")
+    if not os.path.exists(path):
+        return None
+    out, inside = {}, False
+    for line in open(path):
+        line = line.strip()
+        if line.startswith("<!-- figures"):
+            inside = True
+        elif line.startswith("<!-- end figures"):
+            inside = False
+        elif inside and ":" in line:
+            k, v = line.split(":", 1)
+            try:
+                out[k.strip()] = float(v)
+            except ValueError:
+                out[k.strip()] = v.strip()
+    return out or None
+
+
+def median(xs):
+    xs = sorted(xs)
+    return float(xs[len(xs) // 2]) if len(xs) % 2 else float(0.5 * (xs[len(xs) // 2 - 1] + xs[len(xs) // 2]))
 
 
 def other_workload(args, np, torch, binding, workloads):
@@ -87,28 +121,34 @@ def other_workload(args, np, torch, binding, workloads):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
     t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
+    for e in evs:
+        e[0].record()
         step()
-    ev1.record()
+        e[1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms = wall * 1e3 / args.steps
+    kernel_ms = median([e[0].elapsed_time(e[1]) for e in evs])
     events = evals * 2 * D * C * Q
+    peak = device_peak(torch)
+    PEAK_LANE_OPS_PER_S = peak["lane_ops_per_s"]
     lane_ops = evals * Q * algorithmic_lane_ops(D, C)["simulate"]
-    achieved = lane_ops / (ev0.elapsed_time(ev1) * 1e-3 / args.steps)
+    achieved = lane_ops / (kernel_ms * 1e-3)
     result = {
         "metric": "scenarios_per_sec", "value": n / (ms * 1e-3), "unit": "scenarios/s",
         "evaluations_per_sec": evals / (ms * 1e-3), "events_per_sec": events / (ms * 1e-3),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "kernel_ms": {kernel: kernel_ms, "statistic": "median of the per-step HIP-event times"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
         "data": "synthetic", "config": {"workload": name},
         "nan_results": int(torch.isnan(out).sum().item()),
         "roofline": {"bound": "alu", "kernel": kernel, "achieved": achieved / 1e12,
                      "peak": PEAK_LANE_OPS_PER_S / 1e12, "unit": "Tlane-op/s",
-                     "frac": achieved / PEAK_LANE_OPS_PER_S, "traffic": None},
+                     "frac": achieved / PEAK_LANE_OPS_PER_S, "traffic": None,
+                     "traffic_source": None, "compute_units": peak["compute_units"],
+                     "clock_mhz_nominal": peak["clock_mhz_nominal"]},
     }
     if args.cpu_sample > 0:
         from oracle import themis_oracle
@@ -253,7 +293,11 @@ def main():
     n = args.scenarios
     host = workloads.config3(n=n)
     D, C = 4, 64
+    torch.cuda.synchronize()
+    h0 = time.perf_counter()
     d = binding.to_device(host, "cuda:0")
+    torch.cuda.synchronize()
+    h2d_ms = (time.perf_counter() - h0) * 1e3     # pageable host arrays, once; not part of any step
 
     # outputs and scratch are allocated once, outside the timed region
     orders = torch.empty((n, d.slots), dtype=torch.uint8, device="cuda:0")
@@ -287,11 +331,14 @@ def main():
         step(events[k])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    plan_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    sim_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    plan_ms = median([e[0].elapsed_time(e[1]) for e in events])
+    sim_ms = median([e[1].elapsed_time(e[2]) for e in events])
+    step_ms = median([e[0].elapsed_time(e[2]) for e in events])
     ms_per_step = wall * 1e3 / args.steps
 
+    peak = device_peak(torch)
     default_workload = n == (1 << 20) and qo is not None
+    prof = profiled_figures("simulate_kernel_config3") if default_workload else None
     ops = algorithmic_lane_ops(D, C)
     achieved = ops["simulate"] * n / (sim_ms * 1e-3)
     result = {
@@ -301,7 +348,9 @@ def main():
         "events_per_sec": n * 2 * D * C / (ms_per_step * 1e-3),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "kernel_ms": {"plan": plan_ms, "simulate": sim_ms},
+        "kernel_ms": {"plan": plan_ms, "simulate": sim_ms, "step": step_ms,
+                      "statistic": "median of the per-step HIP-event times"},
+        "h2d_ms_once": h2d_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": "config3: %d scenarios, 4-D P=(2,8,8,64), C=64, "
@@ -310,32 +359,45 @@ def main():
                    "chunk_stage_events_per_scenario": 2 * D * C},
         "roofline": {
             "bound": "alu", "kernel": "simulate",
-            "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS_PER_S / 1e12,
-            "unit": "Tlane-op/s", "frac": achieved / PEAK_LANE_OPS_PER_S,
-            "traffic": PROFILED["traffic_bytes_per_launch"] if default_workload else None,
+            "achieved": achieved / 1e12, "peak": peak["lane_ops_per_s"] / 1e12,
+            "unit": "Tlane-op/s", "frac": achieved / peak["lane_ops_per_s"],
             "algorithmic_lane_ops_per_scenario": ops["simulate"],
-            "valu_issue_frac_rocprof": PROFILED["valu_issue_frac"] if default_workload else None,
+            "compute_units": peak["compute_units"], "clock_mhz_nominal": peak["clock_mhz_nominal"],
+            # what follows was not measured in this run: counters of an earlier
+            # rocprofv3 run of this file, with the commit they were taken on
+            "traffic": prof.get("traffic_bytes_per_launch") if prof else None,
+            "traffic_source": ("profiles/simulate_kernel_config3.md @ %s" % prof.get("commit", "?"))
+                              if prof else None,
+            "profiled": prof,
         },
     }
 
     # the fused sweep entry point on the same batch (times only), for reference
     thr = torch.full((1,), 1.0 / 16.0, dtype=torch.float64, device="cuda:0")
     sw_out = torch.empty((n, 1, 1), dtype=torch.float64, device="cuda:0")
-    binding.themis_sweep(d, thr, workloads.SWEEP_THEMIS_SCF, t_done=sw_out)
-    torch.cuda.synchronize()
-    s0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(3):
         binding.themis_sweep(d, thr, workloads.SWEEP_THEMIS_SCF, t_done=sw_out)
     torch.cuda.synchronize()
-    sweep_ms = (time.perf_counter() - s0) * 1e3 / args.steps
-    result["sweep_times_only"] = {"ms": sweep_ms, "evaluations_per_sec": n / (sweep_ms * 1e-3),
-                                  "events_per_sec": n * 2 * D * C / (sweep_ms * 1e-3)}
+    sw_ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    for e in sw_ev:
+        e[0].record()
+        binding.themis_sweep(d, thr, workloads.SWEEP_THEMIS_SCF, t_done=sw_out)
+        e[1].record()
+    torch.cuda.synchronize()
+    sweep_ms = median([e[0].elapsed_time(e[1]) for e in sw_ev])
+    sw_ops = (ops["plan"] + ops["simulate"]) * n / (sweep_ms * 1e-3)
+    result["sweep_times_only"] = {
+        "ms": sweep_ms, "evaluations_per_sec": n / (sweep_ms * 1e-3),
+        "events_per_sec": n * 2 * D * C / (sweep_ms * 1e-3),
+        "roofline": {"bound": "alu", "kernel": "sweep", "achieved": sw_ops / 1e12,
+                     "peak": peak["lane_ops_per_s"] / 1e12, "unit": "Tlane-op/s",
+                     "frac": sw_ops / peak["lane_ops_per_s"], "traffic": None, "traffic_source": None}}
 
     if args.cpu_sample > 0:
         from oracle import themis_oracle
         m = min(args.cpu_sample, n)
         sample = host.take(slice(0, m))
-        cores = min(os.cpu_count() or 1, 16)
+        cores = min(os.cpu_count() or 1, 16, m)
         c0 = time.perf_counter()
         o_orders, _ = themis_oracle.plan_batch(sample, threads=cores)
         o_t, _, _ = themis_oracle.simulate_batch(sample, o_orders, want_queue_order=qo is not None,

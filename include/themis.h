@@ -16,8 +16,19 @@
  * ---------------------------------------
  *  - Every pointer inside themis_batch_t and every array argument is a DEVICE
  *    pointer (HBM of the current HIP device), caller-owned.  The library never
- *    allocates or frees memory, keeps no global mutable state and is
- *    re-entrant.  Outputs are fully overwritten.
+ *    allocates or frees memory.  Outputs are fully overwritten.
+ *  - State the library keeps, and why concurrent calls (other threads, other
+ *    streams) and replays of a captured HIP graph are safe with it:
+ *      a process-wide host counter that gives every simulate / sweep call a
+ *      number, and one 64-bit word per GPU that a kernel raises (atomic
+ *      maximum) to its call's number when it leaves an evaluation to the
+ *      call's follow-up kernels.  A follow-up kernel skips its scan for such
+ *      evaluations only while the word is below its own call's number; a
+ *      larger number left by another call, or by the original run of a
+ *      replayed graph, only costs that scan, and a smaller one can never hide
+ *      a mark of this call.  Results never depend on either.
+ *      themis_simulate_batch_noalloc additionally uses a scratch array that
+ *      the library holds on every GPU (see there).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue kernels on that stream and return; they do not
  *    synchronise.

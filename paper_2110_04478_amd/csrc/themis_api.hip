@@ -2,6 +2,8 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <tuple>
+#include <utility>
 
 #include "themis.h"
 #include "themis_device.hpp"
@@ -1031,9 +1033,30 @@ static unsigned long long next_call_number() {
   return ++counter;
 }
 
-static int launch_status() {
-  return hipGetLastError() == hipSuccess ? THEMIS_OK : THEMIS_ERR_DEVICE;
-}
+// Launches through hipLaunchKernel and keeps the first error that a launch of
+// this call returns: the process-wide "last error" may hold what an unrelated
+// earlier call of the host program left there, and reading it would take that
+// away from its owner.
+struct Launcher {
+  hipStream_t stream;
+  hipError_t first = hipSuccess;
+  explicit Launcher(void* s) : stream((hipStream_t)s) {}
+  template <typename... P, typename... A>
+  void operator()(void (*kernel)(P...), unsigned blocks, unsigned threads, A&&... a) {
+    std::tuple<P...> params(std::forward<A>(a)...);  // converted to the kernel's own parameter types
+    void* ptrs[sizeof...(P)];
+    fill(ptrs, params, std::index_sequence_for<P...>{});
+    const hipError_t e = hipLaunchKernel((const void*)kernel, dim3(blocks), dim3(threads), ptrs, 0, stream);
+    if (first == hipSuccess) first = e;
+  }
+  int status() const { return first == hipSuccess ? THEMIS_OK : THEMIS_ERR_DEVICE; }
+
+ private:
+  template <typename T, size_t... I>
+  static void fill(void** ptrs, T& params, std::index_sequence<I...>) {
+    ((ptrs[I] = (void*)&std::get<I>(params)), ...);
+  }
+};
 
 using SimKernel = void (*)(themis_batch_t, const uint8_t*, double*, void*, int, double*,
                            unsigned long long);
@@ -1127,13 +1150,12 @@ int themis_plan_batch(const themis_batch_t* batch, uint8_t* orders, double* load
   if (!orders) return THEMIS_ERR_INVALID_ARGUMENT;
   const TraceView tv = trace_view(*batch);
   if (batch->n * (uint64_t)tv.mc > (uint64_t)0x7fffffff * kBlock) return THEMIS_ERR_UNSUPPORTED;
+  Launcher go(stream);
   if (tv.mc > 1u)
-    hipLaunchKernelGGL(plan_kernel<true>, dim3(blocks_for(batch->n * tv.mc)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, loads);
+    go(plan_kernel<true>, blocks_for(batch->n * tv.mc), kBlock, *batch, orders, loads);
   else
-    hipLaunchKernelGGL(plan_kernel<false>, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, loads);
-  return launch_status();
+    go(plan_kernel<false>, blocks_for(batch->n), kBlock, *batch, orders, loads);
+  return go.status();
 }
 
 static int simulate_batch_impl(const themis_batch_t* batch, const uint8_t* orders, double* t_done,
@@ -1151,6 +1173,7 @@ static int simulate_batch_impl(const themis_batch_t* batch, const uint8_t* order
   const int entry_bytes =
       themis_queue_entry_bytes(batch->max_chunks, tv.on ? batch->max_coll : 0u);
   const uint32_t cap = tv.on ? 512u : layout_capacity(batch->max_chunks);
+  Launcher go(stream);
   // 8-bit entries are stored four at a time by the layouts with 8-bit chunk
   // ids when the rows (2*slots bytes each) start on 4-byte boundaries
   const bool words = entry_bytes == 1 && cap <= 128u && (tv.slots & 1u) == 0u &&
@@ -1169,10 +1192,9 @@ static int simulate_batch_impl(const themis_batch_t* batch, const uint8_t* order
                         queue_order != nullptr;
     auto trace_kernel = lds_bitmaps ? (extras ? simulate_trace_kernel<true, true> : simulate_trace_kernel<true, false>)
                                     : (extras ? simulate_trace_kernel<false, true> : simulate_trace_kernel<false, false>);
-    hipLaunchKernelGGL(trace_kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
-                       busy, w, have_ws, trace_area, tl);
-    return launch_status();
+    go(trace_kernel, blocks_for(batch->n), kBlock, *batch, orders, t_done, queue_order,
+       entry_bytes, busy, w, have_ws, trace_area, tl);
+    return go.status();
   }
   SimKernel kernel = pick_simulate_kernel(cap, mode, busy != nullptr,
                                           batch->fixed_delay != nullptr);
@@ -1184,9 +1206,8 @@ static int simulate_batch_impl(const themis_batch_t* batch, const uint8_t* order
   // follow-up kernels always come: the table kernels need no workspace, and
   // beyond 64 chunks the generic kernel without one only closes what they left
   const unsigned long long call = next_call_number();
-  hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n)), dim3(kBlock), 0,
-                     (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes, busy,
-                     call);
+  go(kernel, blocks_for(batch->n), kBlock, *batch, orders, t_done, queue_order, entry_bytes, busy,
+     call);
   if (cap <= 64u) {
     auto table = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 0>
                : mode == kWords ? simulate_table_kernel<kWords, 0>
@@ -1194,29 +1215,24 @@ static int simulate_batch_impl(const themis_batch_t* batch, const uint8_t* order
     auto wide = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 1>
               : mode == kWords ? simulate_table_kernel<kWords, 1>
                                : simulate_table_kernel<kBytes, 1>;
-    hipLaunchKernelGGL(table, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
-    hipLaunchKernelGGL(wide, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
+    go(table, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, busy, call);
+    go(wide, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, busy, call);
   } else if (cap == 128u) {
     auto wide = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 2>
               : mode == kWords ? simulate_table_kernel<kWords, 2>
               : mode == kShorts ? simulate_table_kernel<kShorts, 2>
                                 : simulate_table_kernel<kBytes, 2>;
-    hipLaunchKernelGGL(wide, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
+    go(wide, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, busy, call);
   } else {
     auto packed = cap == 256u ? (mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 3>
                                                        : simulate_table_kernel<kShorts, 3>)
                               : (mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 4>
                                                        : simulate_table_kernel<kShorts, 4>);
-    hipLaunchKernelGGL(packed, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, orders, t_done, queue_order, busy, call);
+    go(packed, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, busy, call);
   }
-  hipLaunchKernelGGL(generic, dim3(follow_up_blocks(batch->n)), dim3(kBlock), 0,
-                     (hipStream_t)stream, *batch, orders, t_done, queue_order, entry_bytes,
-                     busy, have_ws ? w : Workspace{}, call);
-  return launch_status();
+  go(generic, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, entry_bytes,
+     busy, have_ws ? w : Workspace{}, call);
+  return go.status();
 }
 
 int themis_simulate_batch(const themis_batch_t* batch, const uint8_t* orders, double* t_done,
@@ -1291,30 +1307,24 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   auto generic = cap <= 16u ? sweep_generic_kernel<16> : cap <= 64u ? sweep_generic_kernel<64>
                                                                     : sweep_generic_kernel<0>;
   const unsigned long long call = next_call_number();
-  hipLaunchKernelGGL(kernel, dim3(blocks_for(batch->n) * (unsigned)(n_thr * n_pol)), dim3(kBlock), 0,
-                     (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                     n_pol, t_done, call);
+  Launcher go(stream);
+  go(kernel, blocks_for(batch->n) * (unsigned)(n_thr * n_pol), kBlock, *batch, n_thr, thr,
+     thr_per_scenario, policy_mask, n_pol, t_done, call);
   if (cap <= 64u) {
-    hipLaunchKernelGGL(sweep_table_kernel<0>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                       n_pol, t_done, call);
-    hipLaunchKernelGGL(sweep_table_kernel<1>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                       n_pol, t_done, call);
+    go(sweep_table_kernel<0>, follow_up_blocks(evals), kBlock, *batch, n_thr, thr,
+       thr_per_scenario, policy_mask, n_pol, t_done, call);
+    go(sweep_table_kernel<1>, follow_up_blocks(evals), kBlock, *batch, n_thr, thr,
+       thr_per_scenario, policy_mask, n_pol, t_done, call);
   } else if (cap == 128u) {
-    hipLaunchKernelGGL(sweep_table_kernel<2>, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                       n_pol, t_done, call);
+    go(sweep_table_kernel<2>, follow_up_blocks(evals), kBlock, *batch, n_thr, thr,
+       thr_per_scenario, policy_mask, n_pol, t_done, call);
   } else {
-    hipLaunchKernelGGL(cap == 256u ? sweep_table_kernel<3> : sweep_table_kernel<4>,
-                       dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
-                       (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                       n_pol, t_done, call);
+    go(cap == 256u ? sweep_table_kernel<3> : sweep_table_kernel<4>, follow_up_blocks(evals),
+       kBlock, *batch, n_thr, thr, thr_per_scenario, policy_mask, n_pol, t_done, call);
   }
-  hipLaunchKernelGGL(generic, dim3(follow_up_blocks(evals)), dim3(kBlock), 0,
-                     (hipStream_t)stream, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-                     n_pol, t_done, have_ws ? w : Workspace{}, call);
-  return launch_status();
+  go(generic, follow_up_blocks(evals), kBlock, *batch, n_thr, thr, thr_per_scenario, policy_mask,
+     n_pol, t_done, have_ws ? w : Workspace{}, call);
+  return go.status();
 }
 
 size_t themis_search_workspace_bytes(uint64_t n, uint64_t max_assignments) {
@@ -1338,14 +1348,14 @@ int themis_search_batch(const themis_batch_t* batch, uint64_t max_assignments, d
     return THEMIS_ERR_WORKSPACE;
   double* times = (double*)workspace;
   const bool fix = batch->fixed_delay != nullptr;
+  Launcher go(stream);
   auto eval = batch->max_chunks <= 16u
       ? (fix ? search_eval_kernel<Layout16, true> : search_eval_kernel<Layout16, false>)
       : (fix ? search_eval_kernel<LayoutRing, true> : search_eval_kernel<LayoutRing, false>);
-  hipLaunchKernelGGL(eval, dim3(blocks_for(evals)), dim3(kBlock), 0, (hipStream_t)stream, *batch,
-                     max_assignments, times);
-  hipLaunchKernelGGL(search_reduce_kernel, dim3((unsigned)batch->n), dim3(kBlock), 0,
-                     (hipStream_t)stream, *batch, max_assignments, times, best_t, best_orders);
-  return launch_status();
+  go(eval, blocks_for(evals), kBlock, *batch, max_assignments, times);
+  go(search_reduce_kernel, (unsigned)batch->n, kBlock, *batch, max_assignments, times, best_t,
+     best_orders);
+  return go.status();
 }
 
 int themis_metrics_batch(const themis_batch_t* batch, const double* t_done, const double* transfer,
@@ -1355,9 +1365,10 @@ int themis_metrics_batch(const themis_batch_t* batch, const double* t_done, cons
   if (!batch->ndims || !batch->bw || !t_done || !transfer) return THEMIS_ERR_INVALID_ARGUMENT;
   if (batch->n_coll ? !batch->coll_size : !batch->size_bytes) return THEMIS_ERR_INVALID_ARGUMENT;
   if (batch->n > (uint64_t)0x7fffffff * 256u) return THEMIS_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(metrics_kernel, dim3((unsigned)((batch->n + 255) / 256)), dim3(256), 0,
-                     (hipStream_t)stream, *batch, t_done, transfer, utilization, ideal);
-  return launch_status();
+  Launcher go(stream);
+  go(metrics_kernel, (unsigned)((batch->n + 255) / 256), 256, *batch, t_done, transfer,
+     utilization, ideal);
+  return go.status();
 }
 
 int themis_classify_batch(const themis_batch_t* batch, uint8_t* classes, void* stream) {
@@ -1365,9 +1376,9 @@ int themis_classify_batch(const themis_batch_t* batch, uint8_t* classes, void* s
   if (batch->n == 0) return THEMIS_OK;
   if (!batch->ndims || !batch->npus || !batch->bw || !classes) return THEMIS_ERR_INVALID_ARGUMENT;
   if (batch->n > (uint64_t)0x7fffffff * 256u) return THEMIS_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(classify_kernel, dim3((unsigned)((batch->n + 255) / 256)), dim3(256), 0,
-                     (hipStream_t)stream, *batch, classes);
-  return launch_status();
+  Launcher go(stream);
+  go(classify_kernel, (unsigned)((batch->n + 255) / 256), 256, *batch, classes);
+  return go.status();
 }
 
 int themis_sweep_best(uint64_t n, int n_thr, int n_pol, const double* t_done, int baseline_col,
@@ -1377,10 +1388,10 @@ int themis_sweep_best(uint64_t n, int n_thr, int n_pol, const double* t_done, in
   if (!t_done || !best_t) return THEMIS_ERR_INVALID_ARGUMENT;
   if (n > (uint64_t)0x7fffffff * 64u) return THEMIS_ERR_UNSUPPORTED;
   const uint64_t items = n * (uint64_t)n_pol;
-  hipLaunchKernelGGL(sweep_best_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
-                     (hipStream_t)stream, n, (uint32_t)n_thr, (uint32_t)n_pol, t_done, baseline_col,
-                     best_t, best_thr, speedup);
-  return launch_status();
+  Launcher go(stream);
+  go(sweep_best_kernel, (unsigned)((items + 255) / 256), 256, n, (uint32_t)n_thr, (uint32_t)n_pol,
+     t_done, baseline_col, best_t, best_thr, speedup);
+  return go.status();
 }
 
 }  // extern "C"

@@ -348,9 +348,10 @@ __device__ __forceinline__ double min_f64(double a, double b) {
 // their order are those of the plain code, so the results are bit-identical.
 // The compiler does not look into these blocks: an instruction that reads
 // other lanes (DPP, v_readlane, ...) must not follow the last v_cmpx within
-// five wait states; build.py's exec_hazards() checks the compiled code for
-// that (a no-op at the end of the blocks would rule it out, but two of them
-// per pass cost 2.6 % of the kernel's time).
+// five wait states.  Every block therefore ends with at least five wait
+// states of its own behind its last v_cmpx (the shorter variants are padded
+// with a no-op), and is volatile so that it stays whole; build.py's
+// exec_hazards() checks the compiled code on top of that.
 #define THEMIS_LANES_OF(J) "v_cmpx_eq_u32_e32 vcc, " #J ", %[k]\n\t"
 #define THEMIS_ALL_LANES "s_mov_b64 exec, %[act]\n\t"
 #define THEMIS_FOUR(BODY) "s_mov_b64 %[act], exec\n\t" BODY(0) BODY(1) BODY(2) BODY(3)
@@ -361,6 +362,8 @@ __device__ __forceinline__ double min_f64(double a, double b) {
 #define THEMIS_SERVE(J) "v_mov_b32_e32 %[s" #J "], %[val]\n\t"
 
 #define THEMIS_GIVEN(J) THEMIS_LANES_OF(J) THEMIS_END(J) THEMIS_SERVE(J) THEMIS_ALL_LANES
+#define THEMIS_PAD1 "s_nop 0\n\t"
+#define THEMIS_PAD2 "s_nop 1\n\t"
 #define THEMIS_GIVEN_BUSY(J) \
   THEMIS_LANES_OF(J) THEMIS_END(J) THEMIS_BUSY(J) THEMIS_SERVE(J) THEMIS_ALL_LANES
 #define THEMIS_SCALED(J) \
@@ -391,11 +394,11 @@ __device__ __forceinline__ void start_stage(uint32_t k, uint32_t val, double now
                                             DimState& d) {
   uint64_t act;  // the lanes that are here
   if (kBusy) {
-    asm(THEMIS_FOUR(THEMIS_GIVEN_BUSY)
+    asm volatile(THEMIS_FOUR(THEMIS_GIVEN_BUSY) THEMIS_PAD1
         : [act] "=&s"(act), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
         : [k] "v"(k), [val] "v"(val), [now] "v"(now), [t] "v"(t) : "vcc");
   } else {
-    asm(THEMIS_FOUR(THEMIS_GIVEN)
+    asm volatile(THEMIS_FOUR(THEMIS_GIVEN) THEMIS_PAD2
         : [act] "=&s"(act), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS
         : [k] "v"(k), [val] "v"(val), [now] "v"(now), [t] "v"(t) : "vcc");
   }
@@ -409,21 +412,21 @@ __device__ __forceinline__ void start_stage_scaled(uint32_t k, uint32_t val, dou
   uint64_t act;
   double t;
   if (kBusy && kFix) {
-    asm(THEMIS_FOUR(THEMIS_SCALED_FIX_BUSY)
+    asm volatile(THEMIS_FOUR(THEMIS_SCALED_FIX_BUSY)
         : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
         : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
           THEMIS_A_OPERANDS : "vcc");
   } else if (kBusy) {
-    asm(THEMIS_FOUR(THEMIS_SCALED_BUSY)
+    asm volatile(THEMIS_FOUR(THEMIS_SCALED_BUSY)
         : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
         : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
   } else if (kFix) {
-    asm(THEMIS_FOUR(THEMIS_SCALED_FIX)
+    asm volatile(THEMIS_FOUR(THEMIS_SCALED_FIX)
         : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS
         : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
           THEMIS_A_OPERANDS : "vcc");
   } else {
-    asm(THEMIS_FOUR(THEMIS_SCALED)
+    asm volatile(THEMIS_FOUR(THEMIS_SCALED) THEMIS_PAD1
         : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_S_OPERANDS
         : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS : "vcc");
   }
@@ -442,8 +445,8 @@ __device__ __forceinline__ uint32_t stages_ending(double now, Dims& d, uint32_t&
   uint64_t act;
   uint32_t done = 0u;
   first = ~0u;
-  asm("s_mov_b64 %[act], exec\n\t"
-      THEMIS_ENDS_NOW(0, 1) THEMIS_ENDS_NOW(1, 2) THEMIS_ENDS_NOW(2, 4) THEMIS_ENDS_NOW(3, 8)
+  asm volatile("s_mov_b64 %[act], exec\n\t"
+      THEMIS_ENDS_NOW(0, 1) THEMIS_ENDS_NOW(1, 2) THEMIS_ENDS_NOW(2, 4) THEMIS_ENDS_NOW(3, 8) THEMIS_PAD1
       : [act] "=&s"(act), [done] "+v"(done), [first] "+v"(first), THEMIS_F_OPERANDS
       : [now] "v"(now), [nan] "v"(nan64()), [s0] "v"(d.s0), [s1] "v"(d.s1), [s2] "v"(d.s2),
         [s3] "v"(d.s3)

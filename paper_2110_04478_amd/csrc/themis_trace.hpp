@@ -231,14 +231,14 @@ __device__ __forceinline__ double start_stage_trace(uint32_t k, uint32_t val, ui
   uint64_t act;
   double t;
   if (kFixAndQueue) {
-    asm(THEMIS_FOUR(THEMIS_TRACE_FULL)
+    asm volatile(THEMIS_FOUR(THEMIS_TRACE_FULL)
         : [act] "=&s"(act), [t] "=&v"(t), [pos] "+v"(pos), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS,
           THEMIS_S_OPERANDS, THEMIS_N_OPERANDS, THEMIS_E_OPERANDS
         : [k] "v"(k), [val] "v"(val), [nx] "v"(nx), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
           THEMIS_A_OPERANDS
         : "vcc");
   } else {
-    asm(THEMIS_FOUR(THEMIS_TRACE_PLAIN)
+    asm volatile(THEMIS_FOUR(THEMIS_TRACE_PLAIN)
         : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS, THEMIS_S_OPERANDS,
           THEMIS_N_OPERANDS
         : [k] "v"(k), [val] "v"(val), [nx] "v"(nx), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS

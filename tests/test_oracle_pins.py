@@ -70,8 +70,9 @@ def test_worked_example_stage_ratios(oracle):
     unit = st[0][0]                       # 64 MB Reduce-Scatter on dim1
     stages = [st[0][0], st[0][1], st[0][1], st[0][0]]  # RS d1, RS d2, AG d2, AG d1
     assert [s / unit for s in stages] == ratios
-    # "64MB RS (or 16MB AG) takes 1 unit": the AG that ends with 64 MB resident
-    # starts from 16 MB and costs the same as the 64 MB RS -- checked through
+    # Sec. 3.3 sets the unit of time as a Reduce-Scatter of 64 MB on dim1 and
+    # gives the All-Gather that starts from 16 MB the same unit: the AG that
+    # ends with 64 MB resident costs what the 64 MB RS does -- checked through
     # the simulator, whose dim1 must be busy exactly 8 units for 4 chunks
     r = oracle.simulate([4, 4], [B0, B0 / 2], [256 * MB], 4, 0, orders)
     assert r["busy"][0] / unit == 8.0 and r["busy"][1] / unit == 4.0
