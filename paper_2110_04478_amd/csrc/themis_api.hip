@@ -323,7 +323,8 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       FastOut so;
       so.queue_order = (uint8_t*)queue_order + (size_t)blockIdx.x * kBlock * rows_bytes;
       so.slots = tv.slots;
-      so.lane_offset = 4u * threadIdx.x;
+      so.lane_offset = IsRing<L>::value ? threadIdx.x : 4u * threadIdx.x;
+      so.staging_bytes = (uint32_t)kBlock * rows_bytes;
       FastResult r;
       if constexpr (kQueueOrder == kWords && !L::kPacked) {
         r = staged ? simulate_pow2<L, kStagedBytes, kBusy, kFix>(s, Pow2Model(s, fs, scf), lds, so)
@@ -367,12 +368,53 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       const uint32_t* from =
           (const uint32_t*)((uint8_t*)queue_order + (size_t)blockIdx.x * kBlock * rows_bytes) + threadIdx.x;
       uint32_t q[kMaxDims][kStagedWords];
+      if constexpr (IsRing<L>::value) {
+        // the ring loop stages single bytes, entry j of a row at byte 64 * j +
+        // lane: the four lanes of a quad fetch the dwords of entries 4w .. 4w+3
+        // (one each, the quad's four bytes of that entry) and exchange them, a
+        // 4 x 4 byte transpose inside the quad
+        const uint32_t sub = threadIdx.x & 3u;
+        const uint32_t* from4 = (const uint32_t*)((uint8_t*)queue_order +
+                                                  (size_t)blockIdx.x * kBlock * rows_bytes) +
+                                sub * 16u + (threadIdx.x >> 2);
+        // byte `sub` of the first operand's dword into byte 0, of the second's into byte 1
+        const uint32_t pick = sub * 0x0101u + 0x0400u;
 #pragma unroll
-      for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k)
+        for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k)
 #pragma unroll
-        for (uint32_t w = 0; w < kStagedWords; ++w)
-          q[k][w] = (w < wpr && rows == kRowsStaged) ? from[(size_t)(k * wpr + w) * kBlock] : 0xffffffffu;
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          for (uint32_t w = 0; w < kStagedWords; ++w)
+            q[k][w] = w < wpr ? from4[(size_t)(k * wpr + w) * kBlock] : 0xffffffffu;
+        // (the wait states a lane-crossing read asks for after a change of exec)
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 4" ::: "memory");
+#pragma unroll
+        for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k)
+#pragma unroll
+          for (uint32_t w = 0; w < kStagedWords; ++w) {
+            // lane a of the quad holds entry 4w + a: everybody takes byte `sub`
+            // of all four.  One block per dword, three temporaries: left to the
+            // compiler, the 128 dwords and its temporaries no longer fit the
+            // registers of three wavefronts per SIMD.
+            uint32_t t0, t1, t2;
+            asm volatile(
+                "v_mov_b32_dpp %[t0], %[q] quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                "v_mov_b32_dpp %[t1], %[q] quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                "v_mov_b32_dpp %[t2], %[q] quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                "v_perm_b32 %[t0], %[t1], %[t0], %[pick]\n\t"
+                "v_mov_b32_dpp %[t1], %[q] quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                "v_perm_b32 %[t1], %[t1], %[t2], %[pick]\n\t"
+                "v_perm_b32 %[q], %[t1], %[t0], %[join]"
+                : [q] "+v"(q[k][w]), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2)
+                : [pick] "v"(pick), [join] "s"(0x05040100u));
+            if (rows != kRowsStaged) q[k][w] = 0xffffffffu;
+          }
+      } else {
+#pragma unroll
+        for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k)
+#pragma unroll
+          for (uint32_t w = 0; w < kStagedWords; ++w)
+            q[k][w] = (w < wpr && rows == kRowsStaged) ? from[(size_t)(k * wpr + w) * kBlock] : 0xffffffffu;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
       if (rows != kRowsNotMine) {
         uint32_t* to = (uint32_t*)((uint8_t*)queue_order + (size_t)i * rows_bytes);
         // four dwords per store where the rows allow it: a quarter of the

@@ -302,6 +302,7 @@ struct FastOut {
   uint8_t* queue_order;
   uint32_t slots;
   uint32_t lane_offset = 0;  // kStagedBytes: added to every offset from queue_order
+  uint32_t staging_bytes = 0;  // kStagedBytes: size of the staging block
 };
 
 struct FastResult {

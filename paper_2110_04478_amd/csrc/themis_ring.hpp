@@ -119,55 +119,79 @@ __device__ __forceinline__ uint32_t whole_code(uint32_t code6) {
 // of idle dimensions.  At least five instructions follow the last v_cmpx
 // inside every block, so no instruction that reads other lanes can come within
 // the wait states an exec write by a vector instruction asks for.
-#define THEMIS_RING_BUSY_0(J, IE, KEEP)
+// With kStaged the dimension also hands out the place of its next queue-order
+// entry (w: byte offset inside the wavefront's staging block) and moves on by
+// one entry, 64 bytes.
+#define THEMIS_RING_BUSY_0(J)
 #define THEMIS_RING_FIX_0(J)
-#define THEMIS_RING_BUSY_1(J, IE, KEEP) THEMIS_BUSY(J)
+#define THEMIS_RING_PLACE_0(J)
+#define THEMIS_RING_BUSY_1(J) THEMIS_BUSY(J)
 #define THEMIS_RING_FIX_1(J) THEMIS_FIX(J)
-#define THEMIS_RING_START(J, IE, KEEP, BUSY, FIX)                               \
+#define THEMIS_RING_PLACE_1(J) \
+  "v_mov_b32_e32 %[at], %[w" #J "]\n\t" "v_add_u32_e32 %[w" #J "], 64, %[w" #J "]\n\t"
+#define THEMIS_RING_START(J, IE, KEEP, BUSY, FIX, PLACE)                        \
   THEMIS_LANES_OF(J) THEMIS_MUL(J) THEMIS_RING_FIX_##FIX(J) THEMIS_END(J)      \
-  THEMIS_RING_BUSY_##BUSY(J, IE, KEEP) THEMIS_SERVE(J)                          \
+  THEMIS_RING_BUSY_##BUSY(J) THEMIS_SERVE(J) THEMIS_RING_PLACE_##PLACE(J)       \
   "v_and_b32_e32 %[" #IE "], %[" #KEEP "], %[" #IE "]\n\t" THEMIS_ALL_LANES
-#define THEMIS_RING_STARTS(BUSY, FIX)                                               \
+#define THEMIS_RING_STARTS(BUSY, FIX, PLACE)                                        \
   "s_mov_b64 %[act], exec\n\t"                                                      \
-  THEMIS_RING_START(0, iel, upper, BUSY, FIX) THEMIS_RING_START(1, iel, lower, BUSY, FIX) \
-  THEMIS_RING_START(2, ieh, upper, BUSY, FIX) THEMIS_RING_START(3, ieh, lower, BUSY, FIX)
+  THEMIS_RING_START(0, iel, upper, BUSY, FIX, PLACE) THEMIS_RING_START(1, iel, lower, BUSY, FIX, PLACE) \
+  THEMIS_RING_START(2, ieh, upper, BUSY, FIX, PLACE) THEMIS_RING_START(3, ieh, lower, BUSY, FIX, PLACE)
 
 // the two halves of a register, from scalar registers (a literal would make
 // the instruction twice as long)
 #define THEMIS_RING_HALVES [upper] "s"(0xffff0000u), [lower] "s"(0x0000ffffu)
 
-template <bool kBusy, bool kFix>
-__device__ __forceinline__ void ring_start_stage(uint32_t k, uint32_t val, double now, double x,
-                                                 const double (&c)[kMaxDims],
-                                                 const double (&a)[kMaxDims], DimState& d,
-                                                 uint32_t& ie_lo, uint32_t& ie_hi) {
+// Place of the next queue-order entry of every dimension in the staging block.
+struct RingPlaces { uint32_t w0, w1, w2, w3; };
+#define THEMIS_W_OPERANDS [w0] "+v"(w.w0), [w1] "+v"(w.w1), [w2] "+v"(w.w2), [w3] "+v"(w.w3)
+
+// Returns the place of this stage's queue-order entry (kStaged, else 0).
+template <bool kBusy, bool kFix, bool kStaged>
+__device__ __forceinline__ uint32_t ring_start_stage(uint32_t k, uint32_t val, double now, double x,
+                                                     const double (&c)[kMaxDims],
+                                                     const double (&a)[kMaxDims], DimState& d,
+                                                     uint32_t& ie_lo, uint32_t& ie_hi, RingPlaces& w) {
   uint64_t act;
   double t;
-  if (kBusy && kFix) {
-    asm volatile(THEMIS_RING_STARTS(1, 1)
-        : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
-          THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
-        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_RING_HALVES,
-          THEMIS_C_OPERANDS, THEMIS_A_OPERANDS : "vcc");
+  uint32_t at = 0u;
+#define THEMIS_RING_OUT [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), \
+                        THEMIS_F_OPERANDS, THEMIS_S_OPERANDS
+#define THEMIS_RING_IN [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_RING_HALVES, \
+                       THEMIS_C_OPERANDS
+  if (kStaged) {
+    if (kBusy && kFix) {
+      asm volatile(THEMIS_RING_STARTS(1, 1, 1)
+          : THEMIS_RING_OUT, THEMIS_Z_OPERANDS, [at] "+v"(at), THEMIS_W_OPERANDS
+          : THEMIS_RING_IN, THEMIS_A_OPERANDS : "vcc");
+    } else if (kBusy) {
+      asm volatile(THEMIS_RING_STARTS(1, 0, 1)
+          : THEMIS_RING_OUT, THEMIS_Z_OPERANDS, [at] "+v"(at), THEMIS_W_OPERANDS
+          : THEMIS_RING_IN : "vcc");
+    } else if (kFix) {
+      asm volatile(THEMIS_RING_STARTS(0, 1, 1)
+          : THEMIS_RING_OUT, [at] "+v"(at), THEMIS_W_OPERANDS
+          : THEMIS_RING_IN, THEMIS_A_OPERANDS : "vcc");
+    } else {
+      asm volatile(THEMIS_RING_STARTS(0, 0, 1)
+          : THEMIS_RING_OUT, [at] "+v"(at), THEMIS_W_OPERANDS
+          : THEMIS_RING_IN : "vcc");
+    }
+  } else if (kBusy && kFix) {
+    asm volatile(THEMIS_RING_STARTS(1, 1, 0)
+        : THEMIS_RING_OUT, THEMIS_Z_OPERANDS : THEMIS_RING_IN, THEMIS_A_OPERANDS : "vcc");
   } else if (kBusy) {
-    asm volatile(THEMIS_RING_STARTS(1, 0)
-        : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
-          THEMIS_S_OPERANDS, THEMIS_Z_OPERANDS
-        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_RING_HALVES,
-          THEMIS_C_OPERANDS : "vcc");
+    asm volatile(THEMIS_RING_STARTS(1, 0, 0)
+        : THEMIS_RING_OUT, THEMIS_Z_OPERANDS : THEMIS_RING_IN : "vcc");
   } else if (kFix) {
-    asm volatile(THEMIS_RING_STARTS(0, 1)
-        : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
-          THEMIS_S_OPERANDS
-        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_RING_HALVES,
-          THEMIS_C_OPERANDS, THEMIS_A_OPERANDS : "vcc");
+    asm volatile(THEMIS_RING_STARTS(0, 1, 0)
+        : THEMIS_RING_OUT : THEMIS_RING_IN, THEMIS_A_OPERANDS : "vcc");
   } else {
-    asm volatile(THEMIS_RING_STARTS(0, 0)
-        : [act] "=&s"(act), [t] "=&v"(t), [iel] "+v"(ie_lo), [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS,
-          THEMIS_S_OPERANDS
-        : [k] "v"(k), [val] "v"(val), [now] "v"(now), [x] "v"(x), THEMIS_RING_HALVES,
-          THEMIS_C_OPERANDS : "vcc");
+    asm volatile(THEMIS_RING_STARTS(0, 0, 0) : THEMIS_RING_OUT : THEMIS_RING_IN : "vcc");
   }
+#undef THEMIS_RING_OUT
+#undef THEMIS_RING_IN
+  return at;
 }
 
 // The clock has moved to `now`: every dimension whose stage ends now becomes
@@ -259,8 +283,8 @@ __device__ inline uint32_t ring_table_entry(uint32_t r, uint32_t behind, uint32_
       const uint32_t pos2 = ((uint32_t)__builtin_popcount(mask2) - phase2) & 3u;
       const uint32_t kn = (code >> (2u * pos2)) & 3u;
       const uint32_t cls2 = (uint32_t)(ranktab >> (4u * mask2)) & 15u;
-      return (16u * kn + cls2) | (mask2 == fin_mask ? kRingFinished : 0u) | (phase << 8) |
-             ((esum(epack, mask & mask2) & 127u) << 9);
+      return (16u * kn + cls2) | (mask2 == fin_mask ? kRingFinished : 0u) | (phase << 9) |
+             ((esum(epack, mask & mask2) & 63u) << 10);
     }
     mask = mask2;
     phase = phase2;
@@ -271,8 +295,14 @@ __device__ inline uint32_t ring_table_entry(uint32_t r, uint32_t behind, uint32_
 // Same contract as simulate_fast: records initialised with
 // LayoutRing::init_chunk(), result.ok false leaves the evaluation to the
 // generic path; power-of-two model only.  Queue orders leave as single
-// entries (kBytes into the lane's own rows, kStagedBytes into the wavefront's
-// staging block).  Nothing in the block has to be cleared beforehand.
+// entries: kBytes into the lane's own rows; kStagedBytes into the wavefront's
+// staging block, entry j of dimension k of lane L at byte (k * 2 * slots + j) *
+// 64 + L, so that the place of a dimension's next entry is one register that
+// moves on by 64 (kept per dimension, advanced in the dimension's turn) and the
+// entries the lanes store at about the same time share cache lines.  The
+// stores go through a buffer descriptor of the block's size: whatever the
+// records hold, nothing is written outside the block.  Nothing in the LDS
+// block has to be cleared beforehand.
 //
 // The wavefront leaves the loop as a whole: a lane that is through (no list
 // holds a chunk, no stage runs) finds nothing to start and nothing to complete
@@ -286,9 +316,10 @@ __device__ inline uint32_t ring_table_entry(uint32_t r, uint32_t behind, uint32_
 // LDS, entry (order, stage):
 //   bits 0-5   list the chunk joins when the stage completes
 //   bit  6     the chunk is finished then
-//   bit  8     the stage is an All-Gather
-//   bits 9-15  sum of log2 P over the dimensions the chunk is reduced on,
-//              the stage's own dimension left out (its resident-size exponent)
+//   bit  9     the stage is an All-Gather
+//   bits 10-15 sum of log2 P over the dimensions the chunk is reduced on,
+//              the stage's own dimension left out (its resident-size exponent;
+//              networks of more than 2^63 NPUs go without a table)
 // and a chunk's record carries bits 0-2 the number of stages behind it and
 // bits 3-7 its order as the lexicographic rank of the four-field code, in
 // place of mask and order fields.  One table read replaces the arithmetic that
@@ -317,9 +348,17 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
   d.s0 = d.s1 = d.s2 = d.s3 = 0u;
   uint32_t ne_lo = 0u, ne_hi = 0u;    // bit q of the pair: list q holds chunks
   uint32_t ie_lo = ~0u, ie_hi = ~0u;  // the sixteen bits of every idle dimension
-  typename L::Ids executed;           // operations started per dimension (kept with queue orders)
+  typename L::Ids executed;           // operations started per dimension (kBytes)
   uint32_t started = 0;               // operations started in all (counted without queue orders)
   const uint32_t row_len = 2u * out.slots;
+  constexpr bool kStaged = kQueueOrder == kStagedBytes;
+  RingPlaces place;                   // kStaged: where each dimension's next entry goes
+  place.w0 = out.lane_offset;
+  place.w1 = out.lane_offset + 64u * row_len;
+  place.w2 = out.lane_offset + 128u * row_len;
+  place.w3 = out.lane_offset + 192u * row_len;
+  __amdgpu_buffer_rsrc_t staging = __builtin_amdgcn_make_buffer_rsrc(
+      kStaged ? out.queue_order : nullptr, 0, kStaged ? out.staging_bytes : 0u, 0x00020000);
 
   // chunk c = w >> 10, whose record is to carry w & 0x3ff (mask, order
   // fields), becomes the last of list q (only the low six bits of q count).
@@ -389,19 +428,21 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
         ne_lo ^= (uint32_t)bit & gone;
         ne_hi ^= (uint32_t)(bit >> 32) & gone;
       }
-      uint32_t phase, val;
+      uint32_t entry, val;   // entry: chunk << 1 | All-Gather
       double bytes;
       if (kTable) {
         const uint32_t e = *(const uint16_t*)(table + 2u * (rh & 0xffu));
-        phase = (e >> 8) & 1u;
+        // the head's id from the tail's link, the phase from the bit below it
+        entry = bfi(0xfc00u, rt, e) >> 9;
         // the chunk and its record's low bits then (one more stage behind it), above the list
         val = (bfi(0x3ffu, rh + 1u, rt) << 7) | (e & 0x7fu);
-        bytes = __hiloint2double(__double2hiint(model.fs.base) - (int)((e << 11) & 0x07f00000u),
+        bytes = __hiloint2double(__double2hiint(model.fs.base) - (int)((e << 10) & 0x03f00000u),
                                  __double2loint(model.fs.base));
       } else {
         const uint32_t kbit = 1u << k;
         const uint32_t mask = rh & 15u;
-        phase = (mask >> k) & 1u;        // waiting for k while reduced on k: All-Gather
+        const uint32_t phase = (mask >> k) & 1u;  // waiting for k while reduced on k: All-Gather
+        entry = (h + h) | phase;
         // what the completion of this stage will do: a Reduce-Scatter sets the
         // dimension's bit, an All-Gather clears it; the last Reduce-Scatter is
         // followed by the All-Gather on the same dimension
@@ -420,20 +461,14 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
       }
       // bytes moved on k = resident size before the chunk's Reduce-Scatter on
       // k, i.e. with every reduced dimension but k itself taken off
-      ring_start_stage<kBusy, kFix>(k, val, now, bytes, s.coef, s.fix, d, ie_lo, ie_hi);
-      if (kQueueOrder != kNoQueueOrder) {
+      const uint32_t at = ring_start_stage<kBusy, kFix, kStaged>(k, val, now, bytes, s.coef, s.fix, d,
+                                                                 ie_lo, ie_hi, place);
+      if (kStaged) {
+        __builtin_amdgcn_raw_buffer_store_b8((uint8_t)entry, staging, (int)at, 0, 0);
+      } else if (kQueueOrder == kBytes) {
         const uint32_t pos_k = executed.get(k);
-        const uint32_t entry = (h + h) | phase;
         // pos_k < row_len always holds for a consistent plan; it keeps the store in bounds
-        if (kQueueOrder == kBytes) {
-          if (pos_k < row_len) out.queue_order[k * row_len + pos_k] = (uint8_t)entry;
-        } else {
-          // byte pos & 3 of dword pos >> 2 of row k; consecutive dwords of a lane lie 256 bytes apart
-          const uint32_t at = min(pos_k, row_len - 1u);
-          uint32_t word;  // k * dwords per row + at / 4 (a full-rate multiply-add)
-          asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(word) : "v"(k), "s"(out.slots >> 1), "v"(at >> 2));
-          out.queue_order[((word << 8) | (at & 3u)) + out.lane_offset] = (uint8_t)entry;
-        }
+        if (pos_k < row_len) out.queue_order[k * row_len + pos_k] = (uint8_t)entry;
         executed.inc(k);
       } else {
         ++started;
@@ -469,13 +504,25 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
   // to move the clock
   const double t_min = model.t_min(D);
   const uint32_t stages = model.one_phase() ? D : 2u * D;
-  if (kQueueOrder != kNoQueueOrder) started = executed.sum();
+  if (kStaged) {
+    // a dimension's place has moved on by 64 bytes per operation
+    const uint32_t n0 = (place.w0 - out.lane_offset) >> 6;
+    const uint32_t n1 = (place.w1 - out.lane_offset) >> 6, n2 = (place.w2 - out.lane_offset) >> 6;
+    const uint32_t n3 = (place.w3 - out.lane_offset) >> 6;
+    res.executed[0] = n0; res.executed[1] = n1 - row_len;
+    res.executed[2] = n2 - 2u * row_len; res.executed[3] = n3 - 3u * row_len;
+    started = n0 + n1 + n2 + n3 - 6u * row_len;
+  } else if (kQueueOrder != kNoQueueOrder) {
+    started = executed.sum();
+  }
   res.ok = started == stages * C && (ie_lo & ie_hi) == ~0u && (ne_lo | ne_hi) == 0u &&
            (now + 0.25 * t_min > now);
   res.t_done = now;
   res.busy[0] = d.z0; res.busy[1] = d.z1; res.busy[2] = d.z2; res.busy[3] = d.z3;
+  if (!kStaged) {
 #pragma unroll
-  for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) res.executed[k] = executed.get(k);
+    for (uint32_t k = 0; k < (uint32_t)kMaxDims; ++k) res.executed[k] = executed.get(k);
+  }
   return res;
 }
 
@@ -496,7 +543,8 @@ __device__ __forceinline__ FastResult simulate_ring(const Scenario& s, const Pow
 #pragma unroll
   for (int j = 0; j < 4; ++j) same = same && sig[j] == (uint32_t)__builtin_amdgcn_readfirstlane((int)sig[j]);
   const uint64_t here = __builtin_amdgcn_ballot_w64(true);
-  if (__builtin_amdgcn_ballot_w64(!same) != 0ull)
+  // (the table's exponent field has six bits)
+  if (__builtin_amdgcn_ballot_w64(!same || model.fs.etot > 63u) != 0ull)
     return ring_loop<false, kQueueOrder, kBusy, kFix>(s, model, lds, out, nullptr);
   // the table sits behind the records and tails of the wavefront's block; the
   // lanes that are here fill it together
