@@ -111,7 +111,9 @@ __device__ __forceinline__ uint32_t whole_code(uint32_t code6) {
 //   bits 17-22 the chunk
 // so the smallest value among the stages that end at an instant is the one of
 // the lowest chunk id, and bits 7-22 are the record's bits and the chunk's link
-// to itself as push() takes them.
+// to itself as push() takes them.  With the wavefront's stage table (see
+// ring_loop) the record's bits are a byte and the description is put together
+// from whole bytes: bits 8-15 the record's low byte, bits 18-23 the chunk.
 //
 // The lanes of dimension J take their turn as the active ones (see
 // start_stage_scaled): the stage time, the finish time, the busy time, the
@@ -365,6 +367,7 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
   // Branch-free: an empty list makes c its own successor (the second store
   // then repeats the first), otherwise c takes over the old tail's link to the
   // head and the old tail points to c.
+  constexpr uint32_t kValShift = kTable ? 8u : 7u;  // a stage's description >> kValShift is push()'s w
   auto push = [&](uint32_t q, uint32_t w) {
     const uint64_t bit = 1ull << (q & 63u);
     const uint32_t b_lo = (uint32_t)bit, b_hi = (uint32_t)(bit >> 32);
@@ -411,6 +414,7 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
     // a7: the lowest idle dimension with chunks waiting starts the first chunk
     // of its lowest class -- the lowest set bit among the lists of idle dimensions
     const uint32_t q = min(ffbl_or_ones(ne_lo & ie_lo), ffbl_or_ones(ne_hi & ie_hi) | 32u);
+    uint32_t pending = 0u;  // lists of idle dimensions that still hold chunks (q == 64: none do)
     if (q < 64u) {
       const uint32_t k = q >> 4;
       uint8_t* tp = L::tail(lds, q);
@@ -422,20 +426,17 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
       // the tail now points to the head's successor (h == t: the list is empty
       // and the record is written afresh when the chunk joins a list again)
       *rt_p = (uint16_t)bfi(0x3ffu, rt, rh);
-      {
-        const uint32_t gone = (uint32_t)((int32_t)((h ^ t) - 1u) >> 31);  // all-ones if h == t
-        const uint64_t bit = 1ull << q;
-        ne_lo ^= (uint32_t)bit & gone;
-        ne_hi ^= (uint32_t)(bit >> 32) & gone;
-      }
+      const uint64_t gone = (uint64_t)(((h ^ t) - 1u) >> 31) << q;  // the list's bit if h == t
       uint32_t entry, val;   // entry: chunk << 1 | All-Gather
       double bytes;
       if (kTable) {
         const uint32_t e = *(const uint16_t*)(table + 2u * (rh & 0xffu));
-        // the head's id from the tail's link, the phase from the bit below it
-        entry = bfi(0xfc00u, rt, e) >> 9;
-        // the chunk and its record's low bits then (one more stage behind it), above the list
-        val = (bfi(0x3ffu, rh + 1u, rt) << 7) | (e & 0x7fu);
+        // the head's id from the tail's link, above the entry's low ten bits
+        const uint32_t he = bfi(0xfc00u, rt, e);
+        entry = he >> 9;  // the phase is the bit below the id
+        // byte 0: list and finished bit, byte 1: the record's low byte then (one
+        // more stage behind it), byte 2: the chunk << 2 (and the phase below it)
+        val = __builtin_amdgcn_perm(rh + 1u, he, 0x0c010400u);
         bytes = __hiloint2double(__double2hiint(model.fs.base) - (int)((e << 10) & 0x03f00000u),
                                  __double2loint(model.fs.base));
       } else {
@@ -473,30 +474,39 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
       } else {
         ++started;
       }
+      // k is no longer among the idle dimensions, so whether its list has just
+      // emptied does not matter here: the bit is taken out afterwards
+      pending = (ne_lo & ie_lo) | (ne_hi & ie_hi);
+      ne_lo ^= (uint32_t)gone;
+      ne_hi ^= (uint32_t)(gone >> 32);
     }
     // all stages of an instant start before the clock moves; then the clock
     // advances to the earliest completion (NaN: nothing runs; +inf: overflow)
-    const bool more = ((ne_lo & ie_lo) | (ne_hi & ie_hi)) != 0u;
+    // Both conditions as lane masks in scalar registers (of the lanes that are
+    // here: a comparison writes zero for the others): the branch and the
+    // wavefront's exit are then scalar work.
     const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));
-    const bool running = next < kInf;
-    if (!more && running) {
+    uint64_t more, running;
+    asm volatile("v_cmp_ne_u32_e64 %0, 0, %1" : "=s"(more) : "v"(pending));
+    asm volatile("v_cmp_lt_f64_e64 %0, %1, %2" : "=s"(running) : "v"(next), "s"(kInf));
+    if (__builtin_amdgcn_inverse_ballot_w64(running & ~more)) {
       now = next;
       // a8: deliver all completions of this instant, lowest chunk id first, so
       // that equal arrival times are appended in chunk-id order
       uint32_t key;
       uint32_t done = ring_stages_ending(now, d, key, ie_lo, ie_hi);
-      if ((key & kRingFinished) == 0u) push(key, key >> 7);
+      if ((key & kRingFinished) == 0u) push(key, key >> kValShift);
       // more stages end at this very instant (rare): the smallest one left, again and again
       while ((done & (done - 1u)) != 0u) {
         done &= ~((key == d.s0 ? 1u : 0u) | (key == d.s1 ? 2u : 0u) | (key == d.s2 ? 4u : 0u) |
                   (key == d.s3 ? 8u : 0u));
         key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
                   min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
-        if ((key & kRingFinished) == 0u) push(key, key >> 7);
+        if ((key & kRingFinished) == 0u) push(key, key >> kValShift);
       }
     }
     // through: nothing waits, nothing runs -- for every lane of the wavefront
-    if (__builtin_amdgcn_ballot_w64(more || running) == 0ull) break;
+    if ((more | running) == 0ull) break;
   }
 
   FastResult res;
