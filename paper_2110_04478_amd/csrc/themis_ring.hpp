@@ -198,13 +198,14 @@ __device__ __forceinline__ uint32_t ring_start_stage(uint32_t k, uint32_t val, d
 
 // The clock has moved to `now`: every dimension whose stage ends now becomes
 // idle (quiet NaN as its finish time, its sixteen bits back in the mask of
-// idle dimensions).  Returns the bits of those dimensions and, in `first`,
-// the smallest stage description among them (all-ones if there is none).
+// idle dimensions).  Returns the bits of those dimensions plus sixteen times
+// their number (32 and more: several at once) and, in `first`, the smallest
+// stage description among them (all-ones if there is none).
 #define THEMIS_RING_ENDS(J, BIT, IE, FIELD)                 \
   "v_cmpx_eq_f64_e32 vcc, %[now], %[f" #J "]\n\t"          \
   "v_mov_b64_e32 %[f" #J "], %[nan]\n\t"                   \
   "v_min_u32_e32 %[first], %[first], %[s" #J "]\n\t"       \
-  "v_or_b32_e32 %[done], " #BIT ", %[done]\n\t"            \
+  "v_add_u32_e32 %[done], " #BIT ", %[done]\n\t"           \
   "v_or_b32_e32 %[" #IE "], %[" #FIELD "], %[" #IE "]\n\t" THEMIS_ALL_LANES
 __device__ __forceinline__ uint32_t ring_stages_ending(double now, DimState& d, uint32_t& first,
                                                        uint32_t& ie_lo, uint32_t& ie_hi) {
@@ -212,8 +213,8 @@ __device__ __forceinline__ uint32_t ring_stages_ending(double now, DimState& d, 
   uint32_t done = 0u;
   first = ~0u;
   asm volatile("s_mov_b64 %[act], exec\n\t"
-      THEMIS_RING_ENDS(0, 1, iel, lower) THEMIS_RING_ENDS(1, 2, iel, upper)
-      THEMIS_RING_ENDS(2, 4, ieh, lower) THEMIS_RING_ENDS(3, 8, ieh, upper)
+      THEMIS_RING_ENDS(0, 17, iel, lower) THEMIS_RING_ENDS(1, 18, iel, upper)
+      THEMIS_RING_ENDS(2, 20, ieh, lower) THEMIS_RING_ENDS(3, 24, ieh, upper)
       : [act] "=&s"(act), [done] "+v"(done), [first] "+v"(first), [iel] "+v"(ie_lo),
         [ieh] "+v"(ie_hi), THEMIS_F_OPERANDS
       : [now] "v"(now), [nan] "v"(nan64()), [s0] "v"(d.s0), [s1] "v"(d.s1), [s2] "v"(d.s2),
@@ -364,25 +365,23 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
 
   // chunk c = w >> 10, whose record is to carry w & 0x3ff (mask, order
   // fields), becomes the last of list q (only the low six bits of q count).
-  // Branch-free: an empty list makes c its own successor (the second store
-  // then repeats the first), otherwise c takes over the old tail's link to the
-  // head and the old tail points to c.
+  // Branch-free: c takes over the old tail's link to the head, then the old
+  // tail is made to point to c.  For an empty list c stands in as its own old
+  // tail: the second store then writes c's record again, with c's own bits and
+  // the link to itself.
   constexpr uint32_t kValShift = kTable ? 8u : 7u;  // a stage's description >> kValShift is push()'s w
   auto push = [&](uint32_t q, uint32_t w) {
     const uint64_t bit = 1ull << (q & 63u);
     const uint32_t b_lo = (uint32_t)bit, b_hi = (uint32_t)(bit >> 32);
     const bool had = ((ne_lo & b_lo) | (ne_hi & b_hi)) != 0u;
     uint8_t* tp = L::tail(lds, q & 63u);
-    const uint32_t t = *tp & 63u;  // an empty list's tail is whatever the byte holds
+    const uint32_t c = w >> 10;
+    const uint32_t last = *tp & 63u;     // (an empty list's tail byte is whatever it last held)
+    const uint32_t t = had ? last : c;
     uint16_t* rt_p = L::rec(lds, t);
     const uint32_t rt = *rt_p;
-    const uint32_t c = w >> 10;
-    uint16_t* rc_p = L::rec(lds, c);
-    const uint32_t c10 = w & 0xfc00u;
-    const uint32_t recc = bfi(0x3ffu, w, had ? rt : c10);   // low ten bits of w, link of the old tail or to itself
-    *rc_p = (uint16_t)recc;
-    uint16_t* dst = had ? rt_p : rc_p;
-    *dst = (uint16_t)(had ? bfi(0x3ffu, rt, c10) : recc);
+    *L::rec(lds, c) = (uint16_t)bfi(0x3ffu, w, rt);   // low ten bits of w, the old tail's link
+    *rt_p = (uint16_t)bfi(0x3ffu, had ? rt : w, w);   // the old tail's own bits, link to c
     *tp = (uint8_t)c;
     ne_lo |= b_lo;
     ne_hi |= b_hi;
@@ -497,7 +496,8 @@ __device__ __forceinline__ FastResult ring_loop(const Scenario& s, const Pow2Mod
       uint32_t done = ring_stages_ending(now, d, key, ie_lo, ie_hi);
       if ((key & kRingFinished) == 0u) push(key, key >> kValShift);
       // more stages end at this very instant (rare): the smallest one left, again and again
-      while ((done & (done - 1u)) != 0u) {
+      while (done >= 32u) {
+        done -= 16u;
         done &= ~((key == d.s0 ? 1u : 0u) | (key == d.s1 ? 2u : 0u) | (key == d.s2 ? 4u : 0u) |
                   (key == d.s3 ? 8u : 0u));
         key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
