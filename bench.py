@@ -171,6 +171,47 @@ def other_workload(args, np, torch, binding, workloads):
     return result
 
 
+def small_workload(args, np, torch, binding, workloads):
+    """Latency of the small cases, end to end (plan + simulate with every output): the single
+    2-D scenario of the smallest configuration and the first 64 scenarios of the bench batch
+    (one wavefront).  Per call: median over the timed steps of the HIP-event time around the
+    two entry points, and the host's wall time per step with one synchronisation at the end."""
+    dev = "cuda:0"
+    rows = {}
+    for name, host in (("config1: 1 scenario, 2-D P=(4,8), C=64", workloads.config1()),
+                       ("64 scenarios of config3 (one wavefront)", workloads.config3(n=64))):
+        n = host.n
+        d = binding.to_device(host, dev)
+        orders = torch.empty((n, d.slots), dtype=torch.uint8, device=dev)
+        loads = torch.empty((4, n), dtype=torch.float64, device=dev)
+        t = torch.empty(n, dtype=torch.float64, device=dev)
+        busy = torch.empty((4, n), dtype=torch.float64, device=dev)
+        qo = torch.empty((n, 4, 2 * d.slots), dtype=torch.uint8, device=dev)
+
+        def step():
+            binding.themis_plan_batch(d, orders, loads)
+            binding.themis_simulate_batch(d, orders, t, qo, busy)
+        for _ in range(max(args.warmup, 3)):
+            step()
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for e in evs:
+            e[0].record()
+            step()
+            e[1].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        rows[name] = {"us_per_call_events_median": 1e3 * median([e[0].elapsed_time(e[1]) for e in evs]),
+                      "us_per_call_wall": 1e6 * wall / args.steps,
+                      "kernel_launches_per_call": "plan 1 + simulate 2",
+                      "t_done_first": float(t[0].item())}
+    return {"metric": "small_batch_latency", "unit": "us", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "dtype": "f64", "data": "synthetic", "higher_is_better": False,
+            "config": {"workload": "small: config1 and one wavefront of config3, plan + simulate, all outputs"},
+            "rows": rows}
+
+
 def extras_workload(args, np, torch, binding, workloads):
     """The entry points beyond plan / simulate / sweep on the 4-D bench networks, each timed
     on its own with HIP events on the stream the kernels run on: per-stage fixed delays,
@@ -258,7 +299,7 @@ def main():
                     help="scenarios the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-queue-order", action="store_true",
                     help="do not request the per-dimension queue orders")
-    ap.add_argument("--workload", choices=("config3", "config4", "config5", "extras"), default="config3")
+    ap.add_argument("--workload", choices=("config3", "config4", "config5", "extras", "small"), default="config3")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB MiB "
                          "(known traffic, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
@@ -283,6 +324,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": src.numel(), "copy_probe_bytes_written": dst.numel()}))
+        return
+    if args.workload == "small":
+        print(json.dumps(small_workload(args, np, torch, binding, workloads)))
         return
     if args.workload == "extras":
         print(json.dumps(extras_workload(args, np, torch, binding, workloads)))

@@ -458,14 +458,16 @@ simulate_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
 // kLdsSlots > 0: the per-chunk arrays (20 bytes per chunk) live in LDS, laid
 // out like the workspace with the 64 lanes as columns; for batches of at most
 // kLdsSlots chunk slots per scenario, which then need no workspace at all.
+// LDS a generic pass needs for kLdsSlots chunk slots per lane, in bytes.
+constexpr size_t generic_lds_bytes(uint32_t lds_slots) {
+  return lds_slots ? (size_t)((lds_slots * kBlock * 5u + 1u) / 2u) * sizeof(double) : 0u;
+}
+
 template <uint32_t kLdsSlots>
-__global__ void __launch_bounds__(kBlock)
-simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
-                        double* __restrict__ t_done, void* __restrict__ queue_order,
-                        int entry_bytes, double* __restrict__ busy, Workspace w,
-                        unsigned long long call) {
-  __shared__ double lds_block[kLdsSlots ? (kLdsSlots * kBlock * 5u + 1u) / 2u : 1u];
-  if (nothing_marked(call)) return;
+__device__ __forceinline__ void simulate_generic_pass(
+    const themis_batch_t& b, const uint8_t* __restrict__ orders, double* __restrict__ t_done,
+    void* __restrict__ queue_order, int entry_bytes, double* __restrict__ busy, Workspace w,
+    void* lds_block) {
   if (kLdsSlots) w = carve_workspace(lds_block, kBlock, kLdsSlots);
   const TraceView tv = trace_view(b);
   // a few workgroups walk all groups of 64 scenarios: most groups have nothing marked
@@ -494,6 +496,17 @@ simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
   }
 }
 
+template <uint32_t kLdsSlots>
+__global__ void __launch_bounds__(kBlock)
+simulate_generic_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
+                        double* __restrict__ t_done, void* __restrict__ queue_order,
+                        int entry_bytes, double* __restrict__ busy, Workspace w,
+                        unsigned long long call) {
+  __shared__ double lds_block[kLdsSlots ? generic_lds_bytes(kLdsSlots) / sizeof(double) : 1u];
+  if (nothing_marked(call)) return;
+  simulate_generic_pass<kLdsSlots>(b, orders, t_done, queue_order, entry_bytes, busy, w, lds_block);
+}
+
 // Kernels between the two: marked scenarios whose NPU counts are not powers of
 // two run the same LDS event loop on per-order-code tables (themis_table.hpp),
 // first the variant for at most 8 distinct order codes, then (kWide) the one
@@ -512,15 +525,12 @@ struct TableVariant {
 };
 
 template <int kQueueOrder, int kVariant>
-__global__ void __launch_bounds__(kBlock)
-simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
-                      double* __restrict__ t_done, void* __restrict__ queue_order,
-                      double* __restrict__ busy, unsigned long long call) {
+__device__ __forceinline__ void simulate_table_pass(
+    const themis_batch_t& b, const uint8_t* __restrict__ orders, double* __restrict__ t_done,
+    void* __restrict__ queue_order, double* __restrict__ busy, void* lds_block) {
   using L = typename TableVariant<kVariant>::L;
   constexpr bool kWide = kVariant != 0;
   constexpr uint32_t kEntryBytes = kQueueOrder == kShorts ? 2u : 1u;
-  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
-  if (nothing_marked(call)) return;
   const uint64_t groups = (b.n + kBlock - 1) / kBlock;
   for (uint64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
     const uint64_t i = grp * kBlock + threadIdx.x;
@@ -567,6 +577,42 @@ simulate_table_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
         for (uint32_t e = r.executed[k]; e < 2u * b.max_chunks; ++e)
           put_queue_entry<kQueueOrder>(fo.queue_order, (uint32_t)k * 2u * b.max_chunks + e, 0xFFFFu);
     }
+  }
+}
+
+constexpr size_t max_bytes(size_t a, size_t b) { return a > b ? a : b; }
+template <int kVariant>
+constexpr size_t table_lds_bytes() {
+  if constexpr (kVariant < 0) return 0u;
+  else return (size_t)TableVariant<kVariant>::L::kLaneWords * kBlock * sizeof(uint32_t);
+}
+constexpr uint32_t kNoGeneric = 0xffffffffu;
+
+// Everything that follows the LDS kernel of themis_simulate_batch, in one
+// launch: the table passes kTableA and kTableB (-1: none) and the generic pass
+// (kGeneric: its chunk slots in LDS, 0: arrays in the workspace, kNoGeneric:
+// none).  A workgroup walks the same groups of 64 scenarios in every pass, so
+// what one pass leaves marked is seen by the next without any ordering between
+// workgroups; the passes share one LDS block of the largest size among them.
+template <int kQueueOrder, int kTableA, int kTableB, uint32_t kGeneric>
+__global__ void __launch_bounds__(kBlock)
+simulate_follow_up_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
+                          double* __restrict__ t_done, void* __restrict__ queue_order,
+                          int entry_bytes, double* __restrict__ busy, Workspace w,
+                          unsigned long long call) {
+  constexpr size_t kBytes_ = max_bytes(max_bytes(table_lds_bytes<kTableA>(), table_lds_bytes<kTableB>()),
+                                       kGeneric == kNoGeneric ? 0u : generic_lds_bytes(kGeneric));
+  __shared__ double lds_block[kBytes_ ? (kBytes_ + 7u) / 8u : 1u];
+  if (nothing_marked(call)) return;
+  if constexpr (kTableA >= 0)
+    simulate_table_pass<kQueueOrder, kTableA>(b, orders, t_done, queue_order, busy, lds_block);
+  if constexpr (kTableB >= 0) {
+    __syncthreads();
+    simulate_table_pass<kQueueOrder, kTableB>(b, orders, t_done, queue_order, busy, lds_block);
+  }
+  if constexpr (kGeneric != kNoGeneric) {
+    __syncthreads();
+    simulate_generic_pass<kGeneric>(b, orders, t_done, queue_order, entry_bytes, busy, w, lds_block);
   }
 }
 
@@ -747,15 +793,12 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
   else t_done[e] = nan64();
 }
 
-// Second kernel of themis_sweep: the evaluations the LDS kernel marked
-// (kLdsSlots as in simulate_generic_kernel).
+// The generic pass of themis_sweep: the evaluations still marked (kLdsSlots
+// as in simulate_generic_pass).
 template <uint32_t kLdsSlots>
-__global__ void __launch_bounds__(kBlock)
-sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
-                     int thr_per_scenario, unsigned policy_mask, int n_pol,
-                     double* __restrict__ t_done, Workspace w, unsigned long long call) {
-  __shared__ double lds_block[kLdsSlots ? (kLdsSlots * kBlock * 5u + 1u) / 2u : 1u];
-  if (nothing_marked(call)) return;
+__device__ __forceinline__ void sweep_generic_pass(
+    const themis_batch_t& b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
+    unsigned policy_mask, int n_pol, double* __restrict__ t_done, Workspace w, void* lds_block) {
   if (kLdsSlots) w = carve_workspace(lds_block, kBlock, kLdsSlots);
   const uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
   const uint64_t groups = (total + kBlock - 1) / kBlock;
@@ -780,17 +823,25 @@ sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr
   }
 }
 
+template <uint32_t kLdsSlots>
+__global__ void __launch_bounds__(kBlock)
+sweep_generic_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
+                     int thr_per_scenario, unsigned policy_mask, int n_pol,
+                     double* __restrict__ t_done, Workspace w, unsigned long long call) {
+  __shared__ double lds_block[kLdsSlots ? generic_lds_bytes(kLdsSlots) / sizeof(double) : 1u];
+  if (nothing_marked(call)) return;
+  sweep_generic_pass<kLdsSlots>(b, n_thr, thr, thr_per_scenario, policy_mask, n_pol, t_done, w,
+                                lds_block);
+}
+
 // The same for themis_sweep: Alg. 1 with real divisions straight into the
 // chunk words, then the table-driven event loop.
 template <int kVariant>
-__global__ void __launch_bounds__(kBlock)
-sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
-                   int thr_per_scenario, unsigned policy_mask, int n_pol,
-                   double* __restrict__ t_done, unsigned long long call) {
+__device__ __forceinline__ void sweep_table_pass(
+    const themis_batch_t& b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
+    unsigned policy_mask, int n_pol, double* __restrict__ t_done, void* lds_block) {
   using L = typename TableVariant<kVariant>::L;
   constexpr bool kWide = kVariant != 0;
-  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
-  if (nothing_marked(call)) return;
   const uint64_t total = b.n * (uint64_t)n_thr * (uint64_t)n_pol;
   const uint64_t groups = (total + kBlock - 1) / kBlock;
   for (uint64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
@@ -826,6 +877,30 @@ sweep_table_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
       r = simulate_fast<L, kNoQueueOrder, false, true>(s, model, lds, fo);
     }
     if (r.ok) t_done[e] = r.t_done;
+  }
+}
+
+// Everything that follows the LDS kernel of themis_sweep, in one launch (see
+// simulate_follow_up_kernel).
+template <int kTableA, int kTableB, uint32_t kGeneric>
+__global__ void __launch_bounds__(kBlock)
+sweep_follow_up_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr,
+                       int thr_per_scenario, unsigned policy_mask, int n_pol,
+                       double* __restrict__ t_done, Workspace w, unsigned long long call) {
+  constexpr size_t kBytes_ = max_bytes(max_bytes(table_lds_bytes<kTableA>(), table_lds_bytes<kTableB>()),
+                                       kGeneric == kNoGeneric ? 0u : generic_lds_bytes(kGeneric));
+  __shared__ double lds_block[kBytes_ ? (kBytes_ + 7u) / 8u : 1u];
+  if (nothing_marked(call)) return;
+  if constexpr (kTableA >= 0)
+    sweep_table_pass<kTableA>(b, n_thr, thr, thr_per_scenario, policy_mask, n_pol, t_done, lds_block);
+  if constexpr (kTableB >= 0) {
+    __syncthreads();
+    sweep_table_pass<kTableB>(b, n_thr, thr, thr_per_scenario, policy_mask, n_pol, t_done, lds_block);
+  }
+  if constexpr (kGeneric != kNoGeneric) {
+    __syncthreads();
+    sweep_generic_pass<kGeneric>(b, n_thr, thr, thr_per_scenario, policy_mask, n_pol, t_done, w,
+                                 lds_block);
   }
 }
 
@@ -1241,39 +1316,54 @@ static int simulate_batch_impl(const themis_batch_t* batch, const uint8_t* order
   SimKernel kernel = pick_simulate_kernel(cap, mode, busy != nullptr,
                                           batch->fixed_delay != nullptr);
   if (!kernel) return THEMIS_ERR_DEVICE;
-  // scenarios outside the LDS path (marked in t_done) are redone by the generic
-  // kernel: with its arrays in LDS up to 64 chunks, from the workspace beyond
-  auto generic = cap <= 16u ? simulate_generic_kernel<16> : cap <= 64u ? simulate_generic_kernel<64>
-                                                                       : simulate_generic_kernel<0>;
-  // follow-up kernels always come: the table kernels need no workspace, and
-  // beyond 64 chunks the generic kernel without one only closes what they left
+  // Scenarios outside the LDS path (marked in t_done) go through the table
+  // passes and what those leave through the generic pass: its arrays in LDS up
+  // to 64 chunks, in the workspace beyond.  One launch for all of it where that
+  // costs nothing: beyond 64 chunks (the generic pass needs no LDS there), with
+  // a workspace (the same), and on batches small enough for every wavefront to
+  // be resident whatever the LDS block (there the launches are what counts).
+  // A large batch of up to 64 chunks without a workspace keeps the generic pass
+  // and its 80 KiB of LDS apart from the table passes.
   const unsigned long long call = next_call_number();
   go(kernel, blocks_for(batch->n), kBlock, *batch, orders, t_done, queue_order, entry_bytes, busy,
      call);
-  if (cap <= 64u) {
-    auto table = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 0>
-               : mode == kWords ? simulate_table_kernel<kWords, 0>
-                                : simulate_table_kernel<kBytes, 0>;
-    auto wide = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 1>
-              : mode == kWords ? simulate_table_kernel<kWords, 1>
-                               : simulate_table_kernel<kBytes, 1>;
-    go(table, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, busy, call);
-    go(wide, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, busy, call);
-  } else if (cap == 128u) {
-    auto wide = mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 2>
-              : mode == kWords ? simulate_table_kernel<kWords, 2>
-              : mode == kShorts ? simulate_table_kernel<kShorts, 2>
-                                : simulate_table_kernel<kBytes, 2>;
-    go(wide, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, busy, call);
-  } else {
-    auto packed = cap == 256u ? (mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 3>
-                                                       : simulate_table_kernel<kShorts, 3>)
-                              : (mode == kNoQueueOrder ? simulate_table_kernel<kNoQueueOrder, 4>
-                                                       : simulate_table_kernel<kShorts, 4>);
-    go(packed, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, busy, call);
+  const unsigned fb = follow_up_blocks(batch->n);
+  const Workspace ws = have_ws ? w : Workspace{};
+#define THEMIS_FOLLOW_UP(MODE, A, B, G) \
+  go(simulate_follow_up_kernel<MODE, A, B, G>, fb, kBlock, *batch, orders, t_done, queue_order, \
+     entry_bytes, busy, ws, call)
+  // (8-bit entries up to 64 chunks, either up to 128, 16-bit entries beyond)
+#define THEMIS_FOLLOW_UP_MODES(A, B, G)                                  \
+  switch (mode) {                                                        \
+    case kNoQueueOrder: THEMIS_FOLLOW_UP(kNoQueueOrder, A, B, G); break; \
+    case kWords: THEMIS_FOLLOW_UP(kWords, A, B, G); break;               \
+    default: THEMIS_FOLLOW_UP(kBytes, A, B, G); break;                   \
   }
-  go(generic, follow_up_blocks(batch->n), kBlock, *batch, orders, t_done, queue_order, entry_bytes,
-     busy, have_ws ? w : Workspace{}, call);
+  if (cap <= 64u) {
+    const bool small = blocks_for(batch->n) <= 2u * compute_units();
+    if (have_ws) {
+      THEMIS_FOLLOW_UP_MODES(0, 1, 0u)
+    } else if (small && cap <= 16u) {
+      THEMIS_FOLLOW_UP_MODES(0, 1, 16u)
+    } else if (small) {
+      THEMIS_FOLLOW_UP_MODES(0, 1, 64u)
+    } else {
+      THEMIS_FOLLOW_UP_MODES(0, 1, kNoGeneric)
+      auto generic = cap <= 16u ? simulate_generic_kernel<16> : simulate_generic_kernel<64>;
+      go(generic, fb, kBlock, *batch, orders, t_done, queue_order, entry_bytes, busy, ws, call);
+    }
+  } else if (cap == 128u) {
+    if (mode == kShorts) THEMIS_FOLLOW_UP(kShorts, 2, -1, 0u);
+    else THEMIS_FOLLOW_UP_MODES(2, -1, 0u)
+  } else if (cap == 256u) {
+    if (mode == kNoQueueOrder) THEMIS_FOLLOW_UP(kNoQueueOrder, 3, -1, 0u);
+    else THEMIS_FOLLOW_UP(kShorts, 3, -1, 0u);
+  } else {
+    if (mode == kNoQueueOrder) THEMIS_FOLLOW_UP(kNoQueueOrder, 4, -1, 0u);
+    else THEMIS_FOLLOW_UP(kShorts, 4, -1, 0u);
+  }
+#undef THEMIS_FOLLOW_UP_MODES
+#undef THEMIS_FOLLOW_UP
   return go.status();
 }
 
@@ -1346,26 +1436,38 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
               : cap == 128u ? (fix ? sweep_kernel<Layout128, true> : sweep_kernel<Layout128, false>)
               : cap == 256u ? (fix ? sweep_kernel<LayoutPacked<256>, true> : sweep_kernel<LayoutPacked<256>, false>)
                             : (fix ? sweep_kernel<LayoutPacked<512>, true> : sweep_kernel<LayoutPacked<512>, false>);
-  auto generic = cap <= 16u ? sweep_generic_kernel<16> : cap <= 64u ? sweep_generic_kernel<64>
-                                                                    : sweep_generic_kernel<0>;
   const unsigned long long call = next_call_number();
   Launcher go(stream);
   go(kernel, blocks_for(batch->n) * (unsigned)(n_thr * n_pol), kBlock, *batch, n_thr, thr,
      thr_per_scenario, policy_mask, n_pol, t_done, call);
+  // the follow-up passes, in one launch where themis_simulate_batch does the same
+  const unsigned fb = follow_up_blocks(evals);
+  const Workspace ws = have_ws ? w : Workspace{};
+#define THEMIS_FOLLOW_UP(A, B, G)                                                            \
+  go(sweep_follow_up_kernel<A, B, G>, fb, kBlock, *batch, n_thr, thr, thr_per_scenario,      \
+     policy_mask, n_pol, t_done, ws, call)
   if (cap <= 64u) {
-    go(sweep_table_kernel<0>, follow_up_blocks(evals), kBlock, *batch, n_thr, thr,
-       thr_per_scenario, policy_mask, n_pol, t_done, call);
-    go(sweep_table_kernel<1>, follow_up_blocks(evals), kBlock, *batch, n_thr, thr,
-       thr_per_scenario, policy_mask, n_pol, t_done, call);
+    const bool small = blocks_for(evals) <= 2u * compute_units();
+    if (have_ws) {
+      THEMIS_FOLLOW_UP(0, 1, 0u);
+    } else if (small && cap <= 16u) {
+      THEMIS_FOLLOW_UP(0, 1, 16u);
+    } else if (small) {
+      THEMIS_FOLLOW_UP(0, 1, 64u);
+    } else {
+      THEMIS_FOLLOW_UP(0, 1, kNoGeneric);
+      auto generic = cap <= 16u ? sweep_generic_kernel<16> : sweep_generic_kernel<64>;
+      go(generic, fb, kBlock, *batch, n_thr, thr, thr_per_scenario, policy_mask, n_pol, t_done,
+         ws, call);
+    }
   } else if (cap == 128u) {
-    go(sweep_table_kernel<2>, follow_up_blocks(evals), kBlock, *batch, n_thr, thr,
-       thr_per_scenario, policy_mask, n_pol, t_done, call);
+    THEMIS_FOLLOW_UP(2, -1, 0u);
+  } else if (cap == 256u) {
+    THEMIS_FOLLOW_UP(3, -1, 0u);
   } else {
-    go(cap == 256u ? sweep_table_kernel<3> : sweep_table_kernel<4>, follow_up_blocks(evals),
-       kBlock, *batch, n_thr, thr, thr_per_scenario, policy_mask, n_pol, t_done, call);
+    THEMIS_FOLLOW_UP(4, -1, 0u);
   }
-  go(generic, follow_up_blocks(evals), kBlock, *batch, n_thr, thr, thr_per_scenario, policy_mask,
-     n_pol, t_done, have_ws ? w : Workspace{}, call);
+#undef THEMIS_FOLLOW_UP
   return go.status();
 }
 
