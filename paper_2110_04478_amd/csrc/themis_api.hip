@@ -2,6 +2,8 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <cstdlib>
+#include <cstring>
 #include <tuple>
 #include <utility>
 
@@ -11,6 +13,7 @@
 #include "themis_generic.hpp"
 #include "themis_packed.hpp"
 #include "themis_ring.hpp"
+#include "themis_quad.hpp"
 #include "themis_table.hpp"
 #include "themis_trace.hpp"
 
@@ -793,6 +796,53 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
   else t_done[e] = nan64();
 }
 
+// The same with four lanes per evaluation (themis_quad.hpp): a wavefront takes
+// 16 consecutive scenarios under one threshold and one scheduler.
+template <bool kFix>
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(LayoutQuad::kWavesPerSimd)))
+sweep_quad_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
+                  unsigned policy_mask, int n_pol, double* __restrict__ t_done,
+                  unsigned long long hand_over) {
+  using L = LayoutQuad;
+  __shared__ uint32_t lds_block[L::kBlockWords];
+  const uint32_t per = (uint32_t)n_thr * (uint32_t)n_pol;   // evaluations per scenario
+  const uint32_t quad = threadIdx.x >> 2;
+  const uint64_t i = (uint64_t)(blockIdx.x / per) * L::kQuads + quad;
+  // a quad without a scenario stays: the wavefront leaves the event loop as a whole
+  const bool exists = i < b.n;
+  const uint64_t e = (exists ? i : 0u) * per + blockIdx.x % per;
+  const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
+  const bool writer = exists && (threadIdx.x & 3u) == 0u;   // one lane of the quad stores the result
+
+  Scenario s = load_scenario(b, it.i);
+  s.ctype = THEMIS_COLL_ALL_REDUCE;  // sweeps evaluate All-Reduce only
+  const bool rel = b.threshold_mode == THEMIS_THR_REL;
+  const double S = b.size_bytes[it.i];
+  const bool ok = s.valid && finite_positive(S) && threshold_ok(it.th, rel);
+  const double chunk = S / (double)s.C;
+  FastScenario fs;
+  const bool eligible = fast_eligible(s, chunk, L::kCap, fs);
+  // (a quad without a valid scenario only keeps the others company: no chunks, no events)
+  const bool fast = exists && ok && eligible;
+  uint8_t* base = (uint8_t*)lds_block + 2u * quad;
+  if (fast) {
+    // every lane of the quad plans (the same arithmetic, the same result) and
+    // writes the records of the chunks whose id ends in its own two bits
+    double load[kMaxDims];
+    plan_fast(s, fs, it.themis_on, rel, it.th, load, [&](uint32_t c, uint32_t code) {
+      if ((c & 3u) == (threadIdx.x & 3u)) L::init_chunk(base, c, code, 0u, (uint32_t)s.D);
+    });
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const QuadResult r = simulate_quad<kFix>(s, Pow2Model(s, fs, it.scf), base, fast);
+  if (!writer) return;
+  if (!ok) t_done[e] = nan64();
+  else if (fast && r.ok) t_done[e] = r.t_done;
+  else if (hand_over) mark_left_to_generic(t_done + e, hand_over);
+  else t_done[e] = nan64();
+}
+
 // The generic pass of themis_sweep: the evaluations still marked (kLdsSlots
 // as in simulate_generic_pass).
 template <uint32_t kLdsSlots>
@@ -1230,6 +1280,21 @@ static unsigned follow_up_blocks(uint64_t items) {
   return all < cap ? all : cap;
 }
 
+// Which mapping themis_sweep's LDS kernel uses for a layout capacity: four
+// lanes per evaluation from kQuadFromCap chunks on, one lane below.
+// THEMIS_SWEEP_MAPPING=lane or =quad in the environment (read once) forces one
+// of them for every capacity, for measurements.
+constexpr uint32_t kQuadFromCap = 256;
+static bool sweep_mapping_is_quad(uint32_t cap) {
+  static const int forced = [] {
+    const char* v = getenv("THEMIS_SWEEP_MAPPING");
+    if (v && !strcmp(v, "lane")) return 1;
+    if (v && !strcmp(v, "quad")) return 2;
+    return 0;
+  }();
+  return forced ? forced == 2 : cap >= kQuadFromCap;
+}
+
 }  // namespace themis
 
 using namespace themis;
@@ -1438,8 +1503,16 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
                             : (fix ? sweep_kernel<LayoutPacked<512>, true> : sweep_kernel<LayoutPacked<512>, false>);
   const unsigned long long call = next_call_number();
   Launcher go(stream);
-  go(kernel, blocks_for(batch->n) * (unsigned)(n_thr * n_pol), kBlock, *batch, n_thr, thr,
-     thr_per_scenario, policy_mask, n_pol, t_done, call);
+  if (sweep_mapping_is_quad(cap)) {
+    const uint64_t groups = (batch->n + LayoutQuad::kQuads - 1u) / LayoutQuad::kQuads;
+    if (groups * (uint64_t)(n_thr * n_pol) > 0x7fffffffull) return THEMIS_ERR_UNSUPPORTED;
+    go(fix ? sweep_quad_kernel<true> : sweep_quad_kernel<false>,
+       (unsigned)groups * (unsigned)(n_thr * n_pol), kBlock, *batch, n_thr, thr, thr_per_scenario,
+       policy_mask, n_pol, t_done, call);
+  } else {
+    go(kernel, blocks_for(batch->n) * (unsigned)(n_thr * n_pol), kBlock, *batch, n_thr, thr,
+       thr_per_scenario, policy_mask, n_pol, t_done, call);
+  }
   // the follow-up passes, in one launch where themis_simulate_batch does the same
   const unsigned fb = follow_up_blocks(evals);
   const Workspace ws = have_ws ? w : Workspace{};
