@@ -98,7 +98,7 @@ def other_workload(args, np, torch, binding, workloads):
         def step():
             binding.themis_sweep(d, thr, mask, t_done=out)
         name = ("config4: %d scenarios x 8 thresholds x {FIFO,SCF}, 4-D P_k=2^U{1..6}, C=512, "
-                "themis_sweep" % n)
+                "themis_sweep, %s mapping" % (n, args.sweep_mapping))
         kernel = "sweep"
     else:
         n = args.scenarios if args.scenarios != 1 << 20 else 16384
@@ -300,6 +300,8 @@ def main():
     ap.add_argument("--no-queue-order", action="store_true",
                     help="do not request the per-dimension queue orders")
     ap.add_argument("--workload", choices=("config3", "config4", "config5", "extras", "small"), default="config3")
+    ap.add_argument("--sweep-mapping", choices=("auto", "lane", "quad"), default="auto",
+                    help="lane mapping of themis_sweep's LDS kernel (auto: the library's choice)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB MiB "
                          "(known traffic, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
@@ -316,6 +318,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     ensure_built()          # compiles only when no library is in the tree
     torch.cuda.set_device(0)
+    binding.themis_set_sweep_mapping({"auto": 0, "lane": 1, "quad": 2}[args.sweep_mapping])
     if args.copy_probe:
         src = torch.full((args.copy_probe << 20,), 7, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)

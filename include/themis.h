@@ -290,6 +290,24 @@ int themis_sweep(const themis_batch_t *batch, int n_thr, const double *thr,
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * themis_set_sweep_mapping -- how themis_sweep's LDS kernel spreads the
+ * evaluations over the lanes of a wavefront.  The simulation of Sec. 4.6.2 /
+ * Sec. 4.3 is the same either way and so are the results; the mappings differ
+ * in speed only.
+ *   THEMIS_MAPPING_AUTO : the faster one for the batch's chunk capacity (the
+ *                         library's choice, the default)
+ *   THEMIS_MAPPING_LANE : one lane per evaluation
+ *   THEMIS_MAPPING_QUAD : four lanes per evaluation, one per dimension
+ * Process-wide, takes effect with the next call of themis_sweep; meant for
+ * measurements and tests.  Returns THEMIS_ERR_INVALID_ARGUMENT for any other
+ * value.
+ */
+#define THEMIS_MAPPING_AUTO 0
+#define THEMIS_MAPPING_LANE 1
+#define THEMIS_MAPPING_QUAD 2
+int themis_set_sweep_mapping(int mapping);
+
+/*
  * themis_sweep_best -- what a parameter study reports per scenario and
  * scheduler: the threshold that gives the smallest completion time (Sec. 5.3
  * fixes one Threshold for all experiments; this finds the best one per

@@ -70,6 +70,8 @@ def lib():
         L.themis_classify_batch.argtypes = [C.POINTER(_Batch), _vp, _vp]
         L.themis_sweep_best.restype = C.c_int
         L.themis_sweep_best.argtypes = [C.c_uint64, C.c_int, C.c_int, _vp, C.c_int, _vp, _vp, _vp, _vp]
+        L.themis_set_sweep_mapping.restype = C.c_int
+        L.themis_set_sweep_mapping.argtypes = [C.c_int]
         L.themis_sweep.restype = C.c_int
         L.themis_sweep.argtypes = [C.POINTER(_Batch), C.c_int, _vp, C.c_int, C.c_uint, _vp,
                                    _vp, C.c_size_t, _vp]
@@ -232,6 +234,14 @@ def themis_sweep(b: DeviceBatch, thr: torch.Tensor, policy_mask: int,
     _check(lib().themis_sweep(C.byref(s), n_thr, _ptr(thr), 1 if thr_per_scenario else 0,
                               policy_mask, _ptr(t_done), _ptr(workspace), ws_bytes, _stream()))
     return t_done
+
+
+MAPPING_AUTO, MAPPING_LANE, MAPPING_QUAD = 0, 1, 2
+
+
+def themis_set_sweep_mapping(mapping: int) -> None:
+    """Lane mapping of themis_sweep's LDS kernel (MAPPING_AUTO / _LANE / _QUAD), process-wide."""
+    _check(lib().themis_set_sweep_mapping(int(mapping)))
 
 
 def themis_metrics_batch(b: DeviceBatch, t_done: torch.Tensor, transfer: torch.Tensor,

@@ -1281,18 +1281,13 @@ static unsigned follow_up_blocks(uint64_t items) {
 }
 
 // Which mapping themis_sweep's LDS kernel uses for a layout capacity: four
-// lanes per evaluation from kQuadFromCap chunks on, one lane below.
-// THEMIS_SWEEP_MAPPING=lane or =quad in the environment (read once) forces one
-// of them for every capacity, for measurements.
+// lanes per evaluation from kQuadFromCap chunks on, one lane below, unless
+// themis_set_sweep_mapping() has fixed one of them.
 constexpr uint32_t kQuadFromCap = 256;
+static std::atomic<int> sweep_mapping{THEMIS_MAPPING_AUTO};
 static bool sweep_mapping_is_quad(uint32_t cap) {
-  static const int forced = [] {
-    const char* v = getenv("THEMIS_SWEEP_MAPPING");
-    if (v && !strcmp(v, "lane")) return 1;
-    if (v && !strcmp(v, "quad")) return 2;
-    return 0;
-  }();
-  return forced ? forced == 2 : cap >= kQuadFromCap;
+  const int forced = sweep_mapping.load(std::memory_order_relaxed);
+  return forced != THEMIS_MAPPING_AUTO ? forced == THEMIS_MAPPING_QUAD : cap >= kQuadFromCap;
 }
 
 }  // namespace themis
@@ -1542,6 +1537,14 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   }
 #undef THEMIS_FOLLOW_UP
   return go.status();
+}
+
+int themis_set_sweep_mapping(int mapping) {
+  if (mapping != THEMIS_MAPPING_AUTO && mapping != THEMIS_MAPPING_LANE &&
+      mapping != THEMIS_MAPPING_QUAD)
+    return THEMIS_ERR_INVALID_ARGUMENT;
+  sweep_mapping.store(mapping, std::memory_order_relaxed);
+  return THEMIS_OK;
 }
 
 size_t themis_search_workspace_bytes(uint64_t n, uint64_t max_assignments) {

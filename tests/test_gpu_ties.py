@@ -188,3 +188,29 @@ def test_tie_rich_networks_with_other_npu_counts(gpu, oracle):
         b.bw = np.ascontiguousarray(a * ((b.npus - 1.0) / b.npus))
         b.size_bytes = b.size_bytes * 81.0
         check_batch(gpu, oracle, _with_collective_types(b, 2), workspace=False)
+
+
+@pytest.mark.parametrize("mapping", ["lane", "quad"])
+def test_sweep_mappings_agree_with_the_oracle(gpu, oracle, mapping):
+    """themis_sweep under each of its two lane mappings (one lane per evaluation;
+    four lanes per evaluation, lane j owning dimension j), forced for every
+    chunk capacity: the tie-rich networks reach the quad mapping's loop that
+    appends the chunks of several stages ending at one instant one at a time,
+    lowest chunk id first; the ragged batches (D 1..4, any C, scenarios without
+    a fast path, a last wavefront with empty quads) its hand-over to the
+    follow-up passes."""
+    import torch
+    W = w()
+    thr = torch.tensor([0.0, 1.0 / 16.0, 0.5], dtype=torch.float64, device="cuda")
+    gpu.themis_set_sweep_mapping({"lane": gpu.MAPPING_LANE, "quad": gpu.MAPPING_QUAD}[mapping])
+    try:
+        for mc, n in ((16, 150), (64, 150), (200, 90), (512, 70)):
+            for b in (W.dyadic_ties(n, seed=7600 + mc, max_chunks=mc),
+                      W.mixed(n + 3, seed=7700 + mc, max_chunks=mc, pow2=(mc != 200))):
+                d = gpu.to_device(b)
+                sw = gpu.themis_sweep(d, thr, 7)
+                torch.cuda.synchronize()
+                assert_close("sweep (%s, %d chunks)" % (mapping, mc), sw.cpu().numpy(),
+                             oracle.sweep(b, thr.cpu().numpy(), 7, threads=8))
+    finally:
+        gpu.themis_set_sweep_mapping(gpu.MAPPING_AUTO)
