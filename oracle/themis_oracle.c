@@ -27,7 +27,13 @@
  * schedule checker under its own policy, ragged traces with rows longer than
  * the chunk count replayed with rationals and checked operation by operation,
  * the 1-D sum of closed forms over a trace, hand values for the trace totals
- * of the metrics, per-scenario delays and collective types.  The completion time
+ * of the metrics, per-scenario delays and collective types.  The beam search
+ * (tests/test_oracle_beam_pins.py): equality with the exhaustive search when
+ * nothing is dropped, a restatement of the procedure in Python whose scores the
+ * rational checker confirms (ties by assignment number on dyadic networks,
+ * delays as long as the stages for the size a partial schedule is scored at),
+ * the bounds by the greedy plan and by the optimum, a width-1 step by hand.
+ * The completion time
  * that the paper's timing figure would show for Themis on the worked example
  * is "parity unpinned": the figure is not available in text form.
  */
@@ -702,6 +708,162 @@ void to_search_batch(uint64_t n, uint64_t begin, uint64_t end,
                      collective_type ? (int)collective_type[i] : TO_ALL_REDUCE,
                      size_bytes[i], C, (int)intra_policy[i], max_assign, &T, row,
                      NULL);
+    if (!ok) { T = NAN; memset(row, 0xFF, max_chunks); }
+    best_t[i] = T;
+  }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Beam search over per-chunk orders (Sec. 4.1, observation 2 names the space
+ * of per-chunk schedules; Sec. 4.2 settles for a greedy walk through it).
+ * The chunks are given their orders one after the other, chunk 0 first.  A
+ * partial schedule of m chunks is scored by the completion time of a
+ * collective of just those m chunks -- of size_bytes if m == C, else of
+ * (size_bytes / C) * m bytes -- simulated under intra_policy.  Every kept
+ * partial schedule is extended by each of the D! orders for the next chunk,
+ * and the `width` best extensions are kept: smaller time first, equal times in
+ * ascending assignment number (chunk c's order has the lexicographic index
+ * digit_c among the permutations of (0..D-1); the number of a partial
+ * schedule is sum_c digit_c * (D!)^c, so the newest chunk's digit is the most
+ * significant).  With width >= (D!)^C nothing is ever dropped and the result
+ * is that of to_search.  The result of the search is the better of the best
+ * full schedule of the beam and the schedule Alg. 1 gives under inter_policy /
+ * threshold (the beam's on equal times), so it is never worse than the greedy
+ * scheduler.
+ * Returns 1 on success, 0 on invalid inputs or width outside 1..TO_MAX_BEAM. */
+/* ------------------------------------------------------------------------ */
+#define TO_MAX_BEAM 64
+
+typedef struct {
+  double t;
+  uint32_t parent; /* position in the previous beam */
+  uint32_t digit;  /* order of the newest chunk */
+  uint32_t rank;   /* position of the parent's number among the previous beam's numbers */
+} to_candidate;
+
+/* a before b: smaller time, then smaller assignment number */
+static int candidate_before(const to_candidate *a, const to_candidate *b)
+{
+  if (a->t != b->t) return a->t < b->t;
+  if (a->digit != b->digit) return a->digit < b->digit;
+  return a->rank < b->rank;
+}
+
+int to_beam_search(int ndims, const uint32_t *npus, const double *bw,
+                   const double *fixed_delay, int ctype, double size_bytes,
+                   uint32_t C, int inter_policy, int intra_policy,
+                   int threshold_mode, double threshold, uint32_t width,
+                   double *best_t, uint8_t *best_orders)
+{
+  if (!to_network_valid(ndims, npus, bw) || C < 1u) return 0;
+  if (width < 1u || width > TO_MAX_BEAM) return 0;
+  uint32_t F = 1;
+  for (int j = 2; j <= ndims; ++j) F *= (uint32_t)j;
+
+  /* beam[r]: digits of the r-th best partial schedule; numrank[r]: how many
+   * of the beam's schedules have a smaller assignment number */
+  uint8_t *beam = (uint8_t *)calloc((size_t)width * C, 1);
+  uint8_t *next = (uint8_t *)calloc((size_t)width * C, 1);
+  uint8_t *od = (uint8_t *)malloc(C);
+  to_candidate *cand = (to_candidate *)malloc(sizeof(to_candidate) * width * F);
+  uint32_t numrank[TO_MAX_BEAM], newrank[TO_MAX_BEAM];
+  double beam_t[TO_MAX_BEAM];
+  uint32_t live = 1; /* the empty schedule */
+  numrank[0] = 0;
+  int ok = 1;
+  for (uint32_t m = 1; ok && m <= C; ++m) {
+    double size_m = (m == C) ? size_bytes : (size_bytes / (double)C) * (double)m;
+    uint32_t nc = 0;
+    for (uint32_t p = 0; ok && p < live; ++p) {
+      for (uint32_t c = 0; c + 1 < m; ++c) {
+        int dims[TO_MAX_DIMS];
+        nth_permutation(ndims, beam[(size_t)p * C + c], dims);
+        od[c] = encode_order(ndims, dims);
+      }
+      for (uint32_t j = 0; ok && j < F; ++j) {
+        int dims[TO_MAX_DIMS];
+        nth_permutation(ndims, j, dims);
+        od[m - 1] = encode_order(ndims, dims);
+        double T;
+        ok = to_simulate(ndims, npus, bw, fixed_delay, ctype, 1u, &size_m, NULL, m,
+                         intra_policy, od, &T, NULL, NULL, NULL);
+        cand[nc].t = T;
+        cand[nc].parent = p;
+        cand[nc].digit = j;
+        cand[nc].rank = numrank[p];
+        ++nc;
+      }
+    }
+    if (!ok) break;
+    /* the `width` best, by selection: candidate x is taken at position
+     * (number of candidates before it) if that is below width */
+    uint32_t kept = nc < width ? nc : width;
+    for (uint32_t x = 0; x < nc; ++x) {
+      uint32_t before = 0;
+      for (uint32_t y = 0; y < nc; ++y) before += (uint32_t)candidate_before(&cand[y], &cand[x]);
+      if (before >= kept) continue;
+      uint8_t *row = next + (size_t)before * C;
+      memcpy(row, beam + (size_t)cand[x].parent * C, C);
+      row[m - 1] = (uint8_t)cand[x].digit;
+      beam_t[before] = cand[x].t;
+      /* its number among the kept ones: newest digit first, then the parent's */
+      newrank[before] = cand[x].digit * TO_MAX_BEAM + cand[x].rank;
+    }
+    for (uint32_t r = 0; r < kept; ++r) {
+      uint32_t smaller = 0;
+      for (uint32_t q = 0; q < kept; ++q) smaller += (uint32_t)(newrank[q] < newrank[r]);
+      numrank[r] = smaller;
+    }
+    uint8_t *sw = beam; beam = next; next = sw;
+    live = kept;
+  }
+  if (ok) {
+    for (uint32_t c = 0; c < C; ++c) {
+      int dims[TO_MAX_DIMS];
+      nth_permutation(ndims, beam[c], dims);
+      best_orders[c] = encode_order(ndims, dims);
+    }
+    *best_t = beam_t[0];
+    /* the greedy scheduler's plan, if it is strictly better */
+    double ld[TO_MAX_DIMS] = {0, 0, 0, 0}, Tg;
+    ok = to_plan(ndims, npus, bw, fixed_delay, ctype, size_bytes, C, inter_policy,
+                 threshold_mode, threshold, od, ld, NULL) &&
+         to_simulate(ndims, npus, bw, fixed_delay, ctype, 1u, &size_bytes, NULL, C,
+                     intra_policy, od, &Tg, NULL, NULL, NULL);
+    if (ok && Tg < *best_t) {
+      *best_t = Tg;
+      memcpy(best_orders, od, C);
+    }
+  }
+  free(beam); free(next); free(od); free(cand);
+  return ok;
+}
+
+/* best_t [n], best_orders [n][max_chunks] (0xFF padded / on failure) */
+void to_beam_search_batch(uint64_t n, uint64_t begin, uint64_t end,
+                          uint32_t max_chunks, int threshold_mode,
+                          const uint8_t *ndims, const uint32_t *npus,
+                          const double *bw, const double *size_bytes,
+                          const uint32_t *chunks, const uint8_t *inter_policy,
+                          const uint8_t *intra_policy, const double *threshold,
+                          const double *fixed_delay, const uint8_t *collective_type,
+                          uint32_t width, double *best_t, uint8_t *best_orders)
+{
+  for (uint64_t i = begin; i < end; ++i) {
+    uint32_t p[TO_MAX_DIMS];
+    double b[TO_MAX_DIMS], fx[TO_MAX_DIMS];
+    gather_network(n, i, npus, bw, p, b);
+    const double *fixed = gather_fixed(n, i, fixed_delay, fx);
+    uint8_t *row = best_orders + (size_t)i * max_chunks;
+    memset(row, 0xFF, max_chunks);
+    uint32_t C = chunks[i];
+    double T = NAN;
+    int ok = (C >= 1u && C <= max_chunks);
+    if (ok)
+      ok = to_beam_search((int)ndims[i], p, b, fixed,
+                          collective_type ? (int)collective_type[i] : TO_ALL_REDUCE,
+                          size_bytes[i], C, (int)inter_policy[i], (int)intra_policy[i],
+                          threshold_mode, threshold[i], width, &T, row);
     if (!ok) { T = NAN; memset(row, 0xFF, max_chunks); }
     best_t[i] = T;
   }

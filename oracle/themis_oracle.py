@@ -57,6 +57,10 @@ def lib():
         L.to_search_batch.argtypes = [
             C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, _u8p, _u32p, _f64p,
             _f64p, _u32p, _u8p, _f64p, _u8p, C.c_uint64, _f64p, _u8p]
+        L.to_beam_search_batch.restype = None
+        L.to_beam_search_batch.argtypes = [
+            C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, C.c_int, _u8p, _u32p, _f64p,
+            _f64p, _u32p, _u8p, _u8p, _f64p, _f64p, _u8p, C.c_uint32, _f64p, _u8p]
         L.to_classify_batch.restype = None
         L.to_classify_batch.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, _u8p, _u32p, _f64p, _u8p]
         L.to_sweep_best.restype = None
@@ -281,6 +285,28 @@ def search_batch(b, max_assignments, threads=1):
             b.n, lo, hi, b.max_chunks, _p(a["ndims"], _u8p), _p(a["npus"], _u32p),
             _p(a["bw"], _f64p), _p(a["size"], _f64p), _p(a["chunks"], _u32p),
             _p(a["intra"], _u8p), _p(fx, _f64p), _p(ct, _u8p), int(max_assignments),
+            _p(best_t, _f64p), _p(best_orders, _u8p))
+    _fan_out(run, b.n, threads)
+    return best_t, best_orders
+
+
+def beam_search_batch(b, width, threads=1):
+    """Beam search over per-chunk orders, seeded with the greedy plan ->
+    (best_t f64[n], best_orders u8[n, max_chunks])."""
+    best_t = np.empty(b.n)
+    best_orders = np.empty((b.n, b.max_chunks), np.uint8)
+    a = dict(ndims=_arr(b.ndims, np.uint8), npus=_arr(b.npus, np.uint32),
+             bw=_arr(b.bw, np.float64), size=_arr(b.size_bytes, np.float64),
+             chunks=_arr(b.chunks, np.uint32), inter=_arr(b.inter_policy, np.uint8),
+             intra=_arr(b.intra_policy, np.uint8), thr=_arr(b.threshold, np.float64))
+    fx, ct = _fixed(b), _ctype(b)
+
+    def run(lo, hi):
+        lib().to_beam_search_batch(
+            b.n, lo, hi, b.max_chunks, int(b.threshold_mode), _p(a["ndims"], _u8p),
+            _p(a["npus"], _u32p), _p(a["bw"], _f64p), _p(a["size"], _f64p),
+            _p(a["chunks"], _u32p), _p(a["inter"], _u8p), _p(a["intra"], _u8p),
+            _p(a["thr"], _f64p), _p(fx, _f64p), _p(ct, _u8p), int(width),
             _p(best_t, _f64p), _p(best_orders, _u8p))
     _fan_out(run, b.n, threads)
     return best_t, best_orders
