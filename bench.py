@@ -270,6 +270,19 @@ def extras_workload(args, np, torch, binding, workloads):
     ds = binding.to_device(small, dev)
     timed("search: %d scenarios x 1,296 schedules (schedules/s)" % ns, ns * 1296.0,
           lambda: binding.themis_search_batch(ds, 1296))
+    # beam search at the paper's default chunk count: width 4 on the 4-D bench networks,
+    # 64 steps x 4 x 24 partial schedules per scenario
+    nb = max(1, n // 256)
+    beam_host = workloads.config3(n=nb)
+    db = binding.to_device(beam_host, dev)
+    beam_ws = binding.alloc_workspace(binding.lib().themis_beam_workspace_bytes(nb, db.max_chunks, 4), dev)
+    timed("beam search: %d scenarios, 64 chunks, width 4 (partial schedules/s)" % nb,
+          nb * 64.0 * 4 * 24, lambda: binding.themis_beam_search_batch(db, 4, beam_ws))
+    beam_t, _ = binding.themis_beam_search_batch(db, 4, beam_ws)
+    g_orders, _ = binding.themis_plan_batch(db)
+    greedy_t, _, _ = binding.themis_simulate_batch(db, g_orders, want_queue_order=False)
+    torch.cuda.synchronize()
+    gain = (greedy_t / beam_t).cpu().numpy()
     # best threshold of a sweep
     thr = torch.from_numpy(workloads.CONFIG4_THRESHOLDS).to(dev)
     sweep = binding.themis_sweep(d0, thr, 7)
@@ -283,6 +296,9 @@ def extras_workload(args, np, torch, binding, workloads):
             "dtype": "f64", "data": "synthetic",
             "config": {"workload": "extras: %d scenarios of the 4-D bench networks" % n},
             "rows": rows,
+            "beam_width4_over_greedy_themis": {"mean": float(np.mean(gain)), "max": float(np.max(gain)),
+                                               "scenarios_improved": int((gain > 1.0).sum()),
+                                               "scenarios": int(nb)},
             "speedup_over_baseline_best_threshold": {
                 "themis_fifo_mean": float(np.mean(sp[:, 1])), "themis_scf_mean": float(np.mean(sp[:, 2])),
                 "themis_scf_max": float(np.max(sp[:, 2]))}}

@@ -373,6 +373,42 @@ int themis_search_batch(const themis_batch_t *batch, uint64_t max_assignments,
                         size_t workspace_bytes, void *stream);
 
 /*
+ * themis_beam_search_batch -- beam search over per-chunk dimension orders for
+ * up to 64 chunks (Sec. 4.1, observation 2 names the space of per-chunk
+ * schedules; Alg. 1 walks it greedily, keeping one schedule; Sec. 4.2's note
+ * leaves better searches open).  The chunks are given their orders one after
+ * the other, chunk 0 first.  A partial schedule of m chunks is scored by the
+ * completion time of a collective of just those m chunks -- of size_bytes if
+ * m == chunks, else of (size_bytes / chunks) * m bytes -- under the scenario's
+ * intra_policy (and fixed_delay / collective_type, if given).  Every kept
+ * partial schedule is extended by each of the D! orders for the next chunk and
+ * the `width` best extensions are kept: smaller time first, equal times in
+ * ascending assignment number (numbering of themis_search_batch: the newest
+ * chunk's digit is the most significant).  With width >= (D!)^chunks nothing
+ * is dropped and the result is that of themis_search_batch.  The answer is the
+ * better of the beam's best full schedule and the plan of themis_plan_batch
+ * under the scenario's inter_policy / threshold (the beam's on equal times), so
+ * it is never worse than the greedy scheduler.
+ *
+ *   width       : 1..64 schedules kept per step.
+ *   best_t      : [n] completion time of the schedule found.
+ *   best_orders : [n][max_chunks] its order codes; slots >= chunks[i] are
+ *                 0xFF.  May be NULL.
+ *   workspace   : themis_beam_workspace_bytes(n, max_chunks, width) bytes,
+ *                 64-byte aligned, required (the kept schedules, one time per
+ *                 scenario and candidate, the greedy plan).
+ * Covers single collectives (n_coll == NULL) with max_chunks <= 64, any NPU
+ * counts (power-of-two counts on the fast path, others on per-order tables).
+ * Invalid scenarios, and scenarios one of whose partial schedules neither
+ * path can simulate, come back as NaN / all-ones.  Launches 3 kernels per
+ * chunk slot; the work is n * width * D! simulations per step.
+ */
+size_t themis_beam_workspace_bytes(uint64_t n, uint32_t max_chunks, uint32_t width);
+int themis_beam_search_batch(const themis_batch_t *batch, uint32_t width, double *best_t,
+                             uint8_t *best_orders, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
+/*
  * themis_classify_batch -- bandwidth provisioning class of every dimension
  * pair of each scenario's network (Sec. 6.3, balance condition of Sec. 3.3).
  * For K < L the baseline keeps dimK and dimL equally busy when

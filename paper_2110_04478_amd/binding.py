@@ -66,6 +66,11 @@ def lib():
         L.themis_search_batch.restype = C.c_int
         L.themis_search_batch.argtypes = [C.POINTER(_Batch), C.c_uint64, _vp, _vp, _vp,
                                           C.c_size_t, _vp]
+        L.themis_beam_workspace_bytes.restype = C.c_size_t
+        L.themis_beam_workspace_bytes.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
+        L.themis_beam_search_batch.restype = C.c_int
+        L.themis_beam_search_batch.argtypes = [C.POINTER(_Batch), C.c_uint32, _vp, _vp, _vp,
+                                               C.c_size_t, _vp]
         L.themis_classify_batch.restype = C.c_int
         L.themis_classify_batch.argtypes = [C.POINTER(_Batch), _vp, _vp]
         L.themis_sweep_best.restype = C.c_int
@@ -256,6 +261,20 @@ def themis_metrics_batch(b: DeviceBatch, t_done: torch.Tensor, transfer: torch.T
     _check(lib().themis_metrics_batch(C.byref(s), _ptr(t_done), _ptr(transfer), _ptr(utilization),
                                       _ptr(ideal), _stream()))
     return utilization, ideal
+
+
+def themis_beam_search_batch(b: DeviceBatch, width: int, workspace: Optional[torch.Tensor] = None):
+    """Beam search over per-chunk orders -> (best_t f64[n], best_orders u8[n, max_chunks])."""
+    best_t = torch.empty(b.n, dtype=torch.float64, device=b.device)
+    best_orders = torch.empty((b.n, b.max_chunks), dtype=torch.uint8, device=b.device)
+    if workspace is None:
+        workspace = alloc_workspace(lib().themis_beam_workspace_bytes(b.n, b.max_chunks, width),
+                                    b.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    s = b.c_struct()
+    _check(lib().themis_beam_search_batch(C.byref(s), int(width), _ptr(best_t), _ptr(best_orders),
+                                          _ptr(workspace), ws_bytes, _stream()))
+    return best_t, best_orders
 
 
 def themis_search_workspace_bytes(n: int, max_assignments: int) -> int:

@@ -1094,6 +1094,182 @@ search_reduce_kernel(themis_batch_t b, uint64_t max_assign, const double* __rest
 }
 
 // ---------------------------------------------------------------------------
+// themis_beam_search_batch: the chunks get their orders one after the other,
+// and after every chunk the `width` best partial schedules are kept (Sec. 4.1,
+// observation 2, names the space; Alg. 1 walks it keeping one).
+// ---------------------------------------------------------------------------
+constexpr uint32_t kBeamMaxWidth = 64;
+constexpr uint32_t kBeamOrders = 24;  // D! <= 24 candidates per kept schedule
+
+// One scenario's part of the workspace is found through these offsets.
+struct BeamLayout {
+  uint64_t n;
+  uint32_t width, mc;
+  size_t off_digits[2], off_rank[2], off_live, off_times, off_best, off_greedy_orders,
+      off_greedy_t, bytes;
+};
+__host__ __device__ inline BeamLayout beam_layout(uint64_t n, uint32_t mc, uint32_t width) {
+  BeamLayout l;
+  l.n = n; l.width = width; l.mc = mc;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = (o + bytes + 63u) & ~(size_t)63u; return at; };
+  l.off_times = take((size_t)n * width * kBeamOrders * sizeof(double));
+  l.off_best = take((size_t)n * sizeof(double));
+  l.off_greedy_t = take((size_t)n * sizeof(double));
+  l.off_live = take((size_t)n * sizeof(uint32_t));
+  for (int h = 0; h < 2; ++h) {
+    l.off_digits[h] = take((size_t)n * width * mc);
+    l.off_rank[h] = take((size_t)n * width);
+  }
+  l.off_greedy_orders = take((size_t)n * mc);
+  l.bytes = o;
+  return l;
+}
+
+// Collective of the first m chunks of a C-chunk schedule: m chunks of size / m bytes.
+__device__ __forceinline__ double beam_partial_size(double S, uint32_t C, uint32_t m) {
+  return m == C ? S : (S / (double)C) * (double)m;
+}
+
+__global__ void __launch_bounds__(256)
+beam_init_kernel(themis_batch_t b, BeamLayout l, uint8_t* __restrict__ ws) {
+  const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= b.n) return;
+  const Scenario s = load_scenario(b, i);
+  const bool ok = s.valid && finite_positive(b.size_bytes[i]) && s.C <= 64u;
+  ((uint32_t*)(ws + l.off_live))[i] = ok ? 1u : 0u;   // the empty schedule
+  (ws + l.off_rank[0])[i * l.width] = 0u;
+}
+
+// One lane per (scenario, kept schedule, order of chunk m - 1): its time into
+// times[i][p * 24 + j], +inf where there is no such candidate, NaN where the
+// simulation gave up.  kTable: the scenarios the power-of-two path does not
+// take (other NPU counts), on per-order tables; each kernel leaves the other's
+// scenarios alone.
+template <bool kTable, bool kFix>
+__global__ void __launch_bounds__(kBlock)
+    __attribute__((amdgpu_waves_per_eu(kTable ? LayoutTableWide::kWavesPerSimd : LayoutRing::kWavesPerSimd)))
+beam_eval_kernel(themis_batch_t b, BeamLayout l, uint8_t* __restrict__ ws, uint32_t m, int half) {
+  using L = typename std::conditional<kTable, LayoutTableWide, LayoutRing>::type;
+  __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
+  const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  const uint32_t per = l.width * kBeamOrders;
+  if (e >= b.n * per) return;
+  const uint64_t i = e / per;
+  const uint32_t cand = (uint32_t)(e - i * per);
+  const uint32_t p = cand / kBeamOrders, j = cand - p * kBeamOrders;
+  double* times = (double*)(ws + l.off_times);
+  Scenario s = load_scenario(b, i);
+  const uint32_t live = ((const uint32_t*)(ws + l.off_live))[i];
+  const uint32_t C = s.C;
+  if (live == 0u || m > C) return;                       // nothing to do for this scenario
+  const uint32_t F = factorial_u32((uint32_t)s.D);
+  const double chunk = beam_partial_size(b.size_bytes[i], C, m) / (double)m;
+  s.C = m;
+  FastScenario fs;
+  const bool pow2 = fast_eligible(s, chunk, LayoutRing::kCap, fs);
+  if (pow2 == kTable) return;                            // the other kernel's scenario
+  if (p >= live || j >= F) { times[e] = inf64(); return; }
+  const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
+  const uint8_t* digits = ws + l.off_digits[half] + (i * l.width + p) * l.mc;
+  auto code_at = [&](uint32_t c) {
+    return nth_permutation_code((uint32_t)s.D, c + 1u == m ? j : (uint32_t)digits[c]);
+  };
+  FastOut fo;
+  fo.queue_order = nullptr;
+  fo.slots = b.max_chunks;
+  FastResult r;
+  if constexpr (kTable) {
+    LaneLds lds;
+    lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+    DivModelT<L> model(s, lds, chunk, scf);
+    table_setup_wide<L>(s, scf, lds, code_at, model);
+    r = simulate_fast<L, kNoQueueOrder, false, true>(s, model, lds, fo);
+  } else {
+    const LaneLds lds = lane_lds<L>(lds_block);
+    for (uint32_t c = 0; c < m; ++c) L::init_chunk(lds, c, stored_code(s, fs, code_at(c)), fs.state0);
+    r = simulate_pow2<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
+  }
+  times[e] = r.ok ? r.t_done : nan64();
+}
+
+// One wavefront per scenario keeps the `width` best candidates: smaller time
+// first, equal times in ascending assignment number (the newest chunk's digit
+// is the most significant, then the kept schedule's own number, known by its
+// rank among the kept ones).
+__global__ void __launch_bounds__(kBlock)
+beam_select_kernel(themis_batch_t b, BeamLayout l, uint8_t* __restrict__ ws, uint32_t m, int half) {
+  __shared__ uint32_t new_key[kBeamMaxWidth];
+  const uint64_t i = blockIdx.x;
+  uint32_t* live_p = (uint32_t*)(ws + l.off_live) + i;
+  const uint32_t live = *live_p;
+  const uint32_t D = b.ndims[i], C = b.chunks[i];
+  if (live == 0u || m > C) return;
+  const uint32_t F = factorial_u32(D);
+  const double* times = (const double*)(ws + l.off_times) + i * l.width * kBeamOrders;
+  const uint8_t* rank_in = ws + l.off_rank[half] + i * l.width;
+  uint8_t* rank_out = ws + l.off_rank[half ^ 1] + i * l.width;
+  const uint8_t* digits_in = ws + l.off_digits[half] + i * l.width * l.mc;
+  uint8_t* digits_out = ws + l.off_digits[half ^ 1] + i * l.width * l.mc;
+  const uint32_t nc = live * F;
+  const uint32_t kept = nc < l.width ? nc : l.width;
+  bool bad = false;
+  for (uint32_t x = threadIdx.x; x < nc; x += kBlock) {
+    const uint32_t px = x / F, jx = x - px * F;
+    const double tx = times[px * kBeamOrders + jx];
+    bad |= !(tx == tx);
+    const uint32_t kx = jx * kBeamMaxWidth + rank_in[px];
+    uint32_t before = 0;
+    for (uint32_t y = 0; y < nc; ++y) {
+      const uint32_t py = y / F, jy = y - py * F;
+      const double ty = times[py * kBeamOrders + jy];
+      const uint32_t ky = jy * kBeamMaxWidth + rank_in[py];
+      before += (ty < tx || (ty == tx && ky < kx)) ? 1u : 0u;
+    }
+    if (before < kept) {
+      uint8_t* row = digits_out + before * l.mc;
+      for (uint32_t c = 0; c + 1u < m; ++c) row[c] = digits_in[px * l.mc + c];
+      row[m - 1u] = (uint8_t)jx;
+      new_key[before] = kx;
+      if (before == 0u) ((double*)(ws + l.off_best))[i] = tx;
+    }
+  }
+  const bool any_bad = __syncthreads_or(bad ? 1 : 0) != 0;
+  if (threadIdx.x < kept) {
+    uint32_t smaller = 0;
+    for (uint32_t q = 0; q < kept; ++q) smaller += new_key[q] < new_key[threadIdx.x] ? 1u : 0u;
+    rank_out[threadIdx.x] = (uint8_t)smaller;
+  }
+  // a simulation that gave up: the scenario has no answer
+  if (threadIdx.x == 0) *live_p = any_bad ? 0u : kept;
+}
+
+// The better of the beam's best schedule and the greedy plan (the beam's on
+// equal times); NaN / all-ones for scenarios without an answer.
+__global__ void __launch_bounds__(256)
+beam_finish_kernel(themis_batch_t b, BeamLayout l, const uint8_t* __restrict__ ws,
+                   double* __restrict__ best_t, uint8_t* __restrict__ best_orders) {
+  const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= b.n) return;
+  const uint32_t live = ((const uint32_t*)(ws + l.off_live))[i];
+  const uint32_t D = b.ndims[i], C = b.chunks[i];
+  const double tb = ((const double*)(ws + l.off_best))[i];
+  const double tg = ((const double*)(ws + l.off_greedy_t))[i];
+  const bool ok = live != 0u && tg == tg;
+  const bool greedy = ok && tg < tb;
+  best_t[i] = ok ? (greedy ? tg : tb) : nan64();
+  if (!best_orders) return;
+  // step m reads buffer (m - 1) & 1 and writes the other: a scenario's last step is m = C
+  const uint8_t* digits = ws + l.off_digits[C & 1u] + i * l.width * l.mc;
+  const uint8_t* plan = ws + l.off_greedy_orders + i * l.mc;
+  for (uint32_t c = 0; c < b.max_chunks; ++c) {
+    uint32_t code = 0xFFu;
+    if (ok && c < C) code = greedy ? plan[c] : nth_permutation_code(D, digits[c]);
+    best_orders[i * b.max_chunks + c] = (uint8_t)code;
+  }
+}
+
+// ---------------------------------------------------------------------------
 // themis_metrics_batch: average bandwidth utilisation (Sec. 3) and Ideal
 // (Table 3) per scenario.
 // ---------------------------------------------------------------------------
@@ -1575,6 +1751,50 @@ int themis_search_batch(const themis_batch_t* batch, uint64_t max_assignments, d
   go(eval, blocks_for(evals), kBlock, *batch, max_assignments, times);
   go(search_reduce_kernel, (unsigned)batch->n, kBlock, *batch, max_assignments, times, best_t,
      best_orders);
+  return go.status();
+}
+
+size_t themis_beam_workspace_bytes(uint64_t n, uint32_t max_chunks, uint32_t width) {
+  if (width < 1u || width > kBeamMaxWidth) return 0;
+  return beam_layout(n, max_chunks, width).bytes;
+}
+
+int themis_beam_search_batch(const themis_batch_t* batch, uint32_t width, double* best_t,
+                             uint8_t* best_orders, void* workspace, size_t workspace_bytes_given,
+                             void* stream) {
+  int st = check_batch(batch, false, true);
+  if (st != THEMIS_OK) return st;
+  if (batch->n_coll) return THEMIS_ERR_UNSUPPORTED;  // single collectives only
+  if (width < 1u || width > kBeamMaxWidth) return THEMIS_ERR_INVALID_ARGUMENT;
+  if (batch->max_chunks > 64u) return THEMIS_ERR_UNSUPPORTED;
+  if (batch->n == 0) return THEMIS_OK;
+  if (!best_t || !batch->intra_policy) return THEMIS_ERR_INVALID_ARGUMENT;
+  const BeamLayout l = beam_layout(batch->n, batch->max_chunks, width);
+  const uint64_t lanes = batch->n * (uint64_t)width * kBeamOrders;
+  if (lanes > (uint64_t)0x7fffffff * kBlock || batch->n > 0x7fffffffull) return THEMIS_ERR_UNSUPPORTED;
+  if (!workspace || ((uintptr_t)workspace & 63u) || workspace_bytes_given < l.bytes)
+    return THEMIS_ERR_WORKSPACE;
+  uint8_t* ws = (uint8_t*)workspace;
+  // the greedy plan and its time (every scenario up to 64 chunks runs without a workspace)
+  uint8_t* plan = ws + l.off_greedy_orders;
+  double* plan_t = (double*)(ws + l.off_greedy_t);
+  st = themis_plan_batch(batch, plan, nullptr, stream);
+  if (st != THEMIS_OK) return st;
+  st = simulate_batch_impl(batch, plan, plan_t, nullptr, nullptr, nullptr, 0, stream);
+  if (st != THEMIS_OK) return st;
+  const bool fix = batch->fixed_delay != nullptr;
+  Launcher go(stream);
+  const unsigned per_scenario = (unsigned)((batch->n + 255) / 256);
+  go(beam_init_kernel, per_scenario, 256, *batch, l, ws);
+  int half = 0;
+  for (uint32_t m = 1; m <= batch->max_chunks; ++m) {
+    go(fix ? beam_eval_kernel<false, true> : beam_eval_kernel<false, false>, blocks_for(lanes),
+       kBlock, *batch, l, ws, m, half);
+    go(beam_eval_kernel<true, true>, blocks_for(lanes), kBlock, *batch, l, ws, m, half);
+    go(beam_select_kernel, (unsigned)batch->n, kBlock, *batch, l, ws, m, half);
+    half ^= 1;
+  }
+  go(beam_finish_kernel, per_scenario, 256, *batch, l, (const uint8_t*)ws, best_t, best_orders);
   return go.status();
 }
 
