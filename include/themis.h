@@ -364,8 +364,9 @@ int themis_metrics_batch(const themis_batch_t *batch, const double *t_done,
  *                 a) that reaches it; slots >= chunks[i] are 0xFF.  May be NULL.
  *   workspace   : themis_search_workspace_bytes(n, max_assignments) bytes
  *                 (one time per scenario and assignment), required.
- * Covers single collectives (n_coll == NULL) of at most 64 chunks with
- * power-of-two NPU counts; other scenarios come back as NaN / all-ones.
+ * Covers single collectives (n_coll == NULL) of at most 64 chunks, any NPU
+ * counts (power-of-two counts on the fast path, others on per-order tables);
+ * other scenarios come back as NaN / all-ones.
  */
 size_t themis_search_workspace_bytes(uint64_t n, uint64_t max_assignments);
 int themis_search_batch(const themis_batch_t *batch, uint64_t max_assignments,

@@ -1016,7 +1016,10 @@ __device__ __forceinline__ uint64_t assignment_count(uint32_t D, uint32_t C, uin
 
 // One lane per (scenario, assignment): times[i * max_assign + a].  Slots past
 // a scenario's own count hold +inf; NaN marks a scenario that cannot be searched.
-template <typename L, bool kFix>
+// kTable (L = LayoutTableWide): the scenarios whose NPU counts are not powers
+// of two, on per-order tables; each of the two kernels leaves the other's
+// scenarios alone (the one without tables also answers for the invalid ones).
+template <bool kTable, typename L, bool kFix>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
 search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ times) {
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
@@ -1027,26 +1030,46 @@ search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ t
   Scenario s = load_scenario(b, i);
   const bool scf = b.intra_policy[i] == THEMIS_INTRA_SCF;
   const double S = b.size_bytes[i];
+  const double chunk = S / (double)s.C;
   FastScenario fs;
-  const bool ok = s.valid && finite_positive(S) &&
-                  fast_eligible(s, S / (double)s.C, L::kCap, fs);
-  const uint64_t count = ok ? assignment_count((uint32_t)s.D, s.C, max_assign) : 0;
-  if (count == 0) { times[e] = nan64(); return; }
-  if (a >= count) { times[e] = inf64(); return; }
-  const LaneLds lds = lane_lds<L>(lds_block);
-  const uint32_t F = factorial_u32((uint32_t)s.D);
-  uint64_t rest = a;
-  for (uint32_t c = 0; c < s.C; ++c) {
-    const uint64_t q = rest / F;
-    const uint32_t digit = (uint32_t)(rest - q * F);
-    rest = q;
-    L::init_chunk(lds, c, stored_code(s, fs, nth_permutation_code((uint32_t)s.D, digit)),
-                         fs.state0);
+  const bool valid = s.valid && finite_positive(S) && s.C <= 64u;
+  const bool pow2 = valid && fast_eligible(s, chunk, 64u, fs);   // (the same in both kernels)
+  const uint64_t count = valid ? assignment_count((uint32_t)s.D, s.C, max_assign) : 0;
+  if (count == 0) {
+    if (!kTable) times[e] = nan64();
+    return;
   }
+  if (pow2 == kTable) return;
+  if (a >= count) { times[e] = inf64(); return; }
+  const uint32_t F = factorial_u32((uint32_t)s.D);
+  // digit c of the assignment number, base D!
+  auto code_at = [&](uint32_t c) {
+    uint64_t rest = a;
+    for (uint32_t j = 0; j < c; ++j) rest /= F;
+    return nth_permutation_code((uint32_t)s.D, (uint32_t)(rest % F));
+  };
   FastOut fo;
   fo.queue_order = nullptr;
   fo.slots = b.max_chunks;
-  FastResult r = simulate_pow2<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
+  FastResult r;
+  if constexpr (kTable) {
+    LaneLds lds;
+    lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
+    DivModelT<L> model(s, lds, chunk, scf);
+    table_setup_wide<L>(s, scf, lds, code_at, model);
+    r = simulate_fast<L, kNoQueueOrder, false, true>(s, model, lds, fo);
+  } else {
+    const LaneLds lds = lane_lds<L>(lds_block);
+    uint64_t rest = a;
+    for (uint32_t c = 0; c < s.C; ++c) {
+      const uint64_t q = rest / F;
+      const uint32_t digit = (uint32_t)(rest - q * F);
+      rest = q;
+      L::init_chunk(lds, c, stored_code(s, fs, nth_permutation_code((uint32_t)s.D, digit)),
+                    fs.state0);
+    }
+    r = simulate_pow2<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
+  }
   times[e] = r.ok ? r.t_done : nan64();
 }
 
@@ -1746,9 +1769,11 @@ int themis_search_batch(const themis_batch_t* batch, uint64_t max_assignments, d
   const bool fix = batch->fixed_delay != nullptr;
   Launcher go(stream);
   auto eval = batch->max_chunks <= 16u
-      ? (fix ? search_eval_kernel<Layout16, true> : search_eval_kernel<Layout16, false>)
-      : (fix ? search_eval_kernel<LayoutRing, true> : search_eval_kernel<LayoutRing, false>);
+      ? (fix ? search_eval_kernel<false, Layout16, true> : search_eval_kernel<false, Layout16, false>)
+      : (fix ? search_eval_kernel<false, LayoutRing, true> : search_eval_kernel<false, LayoutRing, false>);
   go(eval, blocks_for(evals), kBlock, *batch, max_assignments, times);
+  go(search_eval_kernel<true, LayoutTableWide, true>, blocks_for(evals), kBlock, *batch,
+     max_assignments, times);
   go(search_reduce_kernel, (unsigned)batch->n, kBlock, *batch, max_assignments, times, best_t,
      best_orders);
   return go.status();

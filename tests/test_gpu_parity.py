@@ -750,6 +750,16 @@ def test_exhaustive_search_matches_oracle(gpu, oracle):
     torch.cuda.synchronize()
     assert_close("best_t (fixed delay)", g2_t.cpu().numpy(), w2_t)
     assert np.array_equal(g2_od.cpu().numpy(), w2_od)
+    # NPU counts that are not powers of two: the same search on per-order tables
+    P3 = [[int(rng.choice([3, 5, 6, 12, 4])) for _ in range(d_)] for d_ in D]
+    b3 = W.make_batch(D, P3, bw, b.size_bytes, C, 1, b.intra_policy, 0.0, max_chunks=8)
+    b3.collective_type = b.collective_type
+    w3_t, w3_od = oracle.search_batch(b3, bound, threads=8)
+    g3_t, g3_od = gpu.themis_search_batch(gpu.to_device(b3), bound)
+    torch.cuda.synchronize()
+    assert np.isfinite(w3_t).sum() >= n - 2
+    assert_close("best_t (other NPU counts)", g3_t.cpu().numpy(), w3_t)
+    assert np.array_equal(g3_od.cpu().numpy(), w3_od)
     # the greedy plan can never beat the exhaustive optimum
     orders, _ = gpu.themis_plan_batch(d)
     t, _, _ = gpu.themis_simulate_batch(d, orders, want_queue_order=False)
