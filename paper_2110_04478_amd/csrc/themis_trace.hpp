@@ -33,7 +33,7 @@ struct TraceLayout {
   uint32_t G;   // chunk slots (max_chunks * max_coll)
   uint32_t Q;   // collectives the region is sized for
   uint32_t R;   // ranks per dimension = Q * 16
-  uint32_t off_ht, off_bm, off_col, off_sz, off_sq, off_sq2, off_rq;
+  uint32_t off_ht, off_bm, off_col, off_sq, off_sq2, off_rq;
   uint32_t bytes;  // multiple of 16; 0 if the batch cannot use this path
 };
 
@@ -49,7 +49,6 @@ __host__ __device__ inline TraceLayout trace_layout(uint32_t max_chunks, uint32_
   // one 64-byte record per collective: the size rank of each of the 16 masks
   // (u16, one 32-byte row), the chunk bytes and the release time (f64 each)
   t.off_col = (o + 63u) & ~63u; o = t.off_col + t.Q * kTraceCollBytes;
-  t.off_sz = o;  o += t.R * 8u;            // resident bytes of every size rank (f64)
   t.off_sq = o;  o += ((t.Q + 1u) & ~1u) * 2u;   // collectives sorted by chunk size
   t.off_sq2 = o; o += ((t.Q + 1u) & ~1u) * 2u;   // the merge sort's second buffer
   t.off_rq = o;  o += ((t.Q + 1u) & ~1u) * 2u;   // collectives sorted by release time
@@ -80,9 +79,6 @@ struct TraceRegion {
   // the 16 ranks of collective q as eight dwords
   __device__ __forceinline__ const uint4* SRrow(uint32_t q) const {
     return (const uint4*)(base + t.off_col + min(q, t.Q - 1u) * kTraceCollBytes);
-  }
-  __device__ __forceinline__ double& SZ(uint32_t r) const {
-    return ((double*)(base + t.off_sz))[min(r, t.R - 1u)];
   }
   __device__ __forceinline__ uint16_t& SQ(uint32_t j) const {
     return ((uint16_t*)(base + t.off_sq))[min(j, t.Q - 1u)];
@@ -165,7 +161,6 @@ __device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, 
       if (v < vb) { vb = v; mb = m; }
     }
     if (out > 0u && vb > prev) ++rank;
-    if (out == 0u || vb > prev) rg.SZ(rank) = vb;
     prev = vb;
     const uint32_t p = *(const uint32_t*)lds.dword(32u + mb);
     rg.SR(rg.SQ(p), mb) = (uint16_t)rank;
@@ -339,17 +334,19 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     const uint32_t leaf = sw * 32u + ((uint32_t)__builtin_ctz(sumw | 0x80000000u));
     const uint32_t lw = BM(k, leaf);
     const uint32_t r = leaf * 32u + ((uint32_t)__builtin_ctz(lw | 0x80000000u));
-    // (the size and rank tables are read whatever the policy: a load nobody
-    // uses costs less here than a branch around it)
+    // (the rank table is read whatever the policy: a load nobody uses costs
+    // less here than a branch around it)
     const uint32_t ht = rg.HT(k, r);
-    size = rg.SZ(r);
     const uint32_t h = ht & 0xffffu, tl = ht >> 16;
     w = rg.W(h);
-    const uint4* row = rg.SRrow(coll_of(h));
+    const uint32_t q = coll_of(h);
+    const uint4* row = rg.SRrow(q);
     row_lo = row[0];
     row_hi = row[1];
-    // FIFO, one list per dimension: the size comes from the chunk's collective
-    if (!scf) size = scale_down(rg.CH(coll_of(h)), esum(epack, w & 15u));
+    // the resident size from the chunk bytes of the collective, which sit in
+    // the same 64 bytes as its rank row (the per-rank size table would be one
+    // more line to fetch)
+    size = scale_down(rg.CH(q), esum(epack, w & 15u));
     at = 4u * rg.t.R;
     new_entry = 0u;
     if (h == tl) {
