@@ -178,7 +178,7 @@ def small_workload(args, np, torch, binding, workloads):
     two entry points, and the host's wall time per step with one synchronisation at the end."""
     dev = "cuda:0"
     rows = {}
-    for name, host in (("config1: 1 scenario, 2-D P=(4,8), C=64", workloads.config1()),
+    for name, host in (("config1: 1 scenario, 2-D P=(4,8), C=4", workloads.config1()),
                        ("64 scenarios of config3 (one wavefront)", workloads.config3(n=64))):
         n = host.n
         d = binding.to_device(host, dev)
