@@ -1016,15 +1016,20 @@ __device__ __forceinline__ uint64_t assignment_count(uint32_t D, uint32_t C, uin
 
 // One lane per (scenario, assignment): times[i * max_assign + a].  Slots past
 // a scenario's own count hold +inf; NaN marks a scenario that cannot be searched.
-// kTable (L = LayoutTableWide): the scenarios whose NPU counts are not powers
-// of two, on per-order tables; each of the two kernels leaves the other's
-// scenarios alone (the one without tables also answers for the invalid ones).
+// kTable (L = LayoutTableWide): the follow-up kernel for the scenarios whose
+// NPU counts are not powers of two, on per-order tables: the first kernel
+// marks their slots (see g_marked_call), this one strides over all slots with
+// a grid that just fills the device and returns at once if nothing is marked.
 template <bool kTable, typename L, bool kFix>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
-search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ times) {
+search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ times,
+                   unsigned long long call) {
   __shared__ uint32_t lds_block[L::kLaneWords * kBlock];
-  const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (e >= b.n * max_assign) return;
+  if (kTable && nothing_marked(call)) return;
+  const uint64_t total = b.n * max_assign;
+  for (uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x; e < total;
+       e += (uint64_t)gridDim.x * kBlock) {
+  if (kTable && !is_left_to_generic(times[e])) continue;
   const uint64_t i = e / max_assign;
   const uint64_t a = e - i * max_assign;
   Scenario s = load_scenario(b, i);
@@ -1035,12 +1040,9 @@ search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ t
   const bool valid = s.valid && finite_positive(S) && s.C <= 64u;
   const bool pow2 = valid && fast_eligible(s, chunk, 64u, fs);   // (the same in both kernels)
   const uint64_t count = valid ? assignment_count((uint32_t)s.D, s.C, max_assign) : 0;
-  if (count == 0) {
-    if (!kTable) times[e] = nan64();
-    return;
-  }
-  if (pow2 == kTable) return;
-  if (a >= count) { times[e] = inf64(); return; }
+  if (count == 0) { times[e] = nan64(); continue; }
+  if (a >= count) { times[e] = inf64(); continue; }
+  if (!kTable && !pow2) { mark_left_to_generic(times + e, call); continue; }
   const uint32_t F = factorial_u32((uint32_t)s.D);
   // digit c of the assignment number, base D!
   auto code_at = [&](uint32_t c) {
@@ -1071,6 +1073,7 @@ search_eval_kernel(themis_batch_t b, uint64_t max_assign, double* __restrict__ t
     r = simulate_pow2<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, scf), lds, fo);
   }
   times[e] = r.ok ? r.t_done : nan64();
+  }
 }
 
 // One wavefront per scenario: smallest time and the lowest assignment number
@@ -1771,9 +1774,10 @@ int themis_search_batch(const themis_batch_t* batch, uint64_t max_assignments, d
   auto eval = batch->max_chunks <= 16u
       ? (fix ? search_eval_kernel<false, Layout16, true> : search_eval_kernel<false, Layout16, false>)
       : (fix ? search_eval_kernel<false, LayoutRing, true> : search_eval_kernel<false, LayoutRing, false>);
-  go(eval, blocks_for(evals), kBlock, *batch, max_assignments, times);
-  go(search_eval_kernel<true, LayoutTableWide, true>, blocks_for(evals), kBlock, *batch,
-     max_assignments, times);
+  const unsigned long long call = next_call_number();
+  go(eval, blocks_for(evals), kBlock, *batch, max_assignments, times, call);
+  go(search_eval_kernel<true, LayoutTableWide, true>, follow_up_blocks(evals), kBlock, *batch,
+     max_assignments, times, call);
   go(search_reduce_kernel, (unsigned)batch->n, kBlock, *batch, max_assignments, times, best_t,
      best_orders);
   return go.status();
