@@ -103,6 +103,11 @@ def other_workload(args, np, torch, binding, workloads):
     else:
         n = args.scenarios if args.scenarios != 1 << 20 else 16384
         host = workloads.config5(n=n)
+        if args.workload == "config5fifo6":
+            # the same traces on P = (6, 12, 24) under first-in-first-out: NPU counts that are
+            # not powers of two on the list path (Smallest-Chunk-First would take the generic one)
+            host.npus = np.ascontiguousarray(np.array([[6], [12], [24], [1]], dtype=np.uint32).repeat(n, axis=1))
+            host.intra_policy[:] = 0
         D, C, Q = 3, 64, host.max_coll
         d = binding.to_device(host, dev)
         evals = n
@@ -117,6 +122,8 @@ def other_workload(args, np, torch, binding, workloads):
             binding.themis_simulate_batch(d, orders, out, None, busy, ws, want_queue_order=False)
         name = ("config5: %d traces of %d All-Reduces, 3-D P=(8,16,32), C=64, Themis+SCF, "
                 "plan + simulate (times and busy)" % (n, Q))
+        if args.workload == "config5fifo6":
+            name = name.replace("P=(8,16,32)", "P=(6,12,24)").replace("Themis+SCF", "Themis+FIFO").replace("config5", "config5fifo6")
         kernel = "simulate_trace"
     for _ in range(args.warmup):
         step()
@@ -315,7 +322,7 @@ def main():
                     help="scenarios the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-queue-order", action="store_true",
                     help="do not request the per-dimension queue orders")
-    ap.add_argument("--workload", choices=("config3", "config4", "config5", "extras", "small"), default="config3")
+    ap.add_argument("--workload", choices=("config3", "config4", "config5", "config5fifo6", "extras", "small"), default="config3")
     ap.add_argument("--sweep-mapping", choices=("auto", "lane", "quad"), default="auto",
                     help="lane mapping of themis_sweep's LDS kernel (auto: the library's choice)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",

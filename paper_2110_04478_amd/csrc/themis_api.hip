@@ -660,13 +660,21 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     TraceRegion rg;
     rg.base = trace_area + (size_t)i * tl.bytes;
     rg.t = tl;
-    // every collective must be in the range where halvings are exact
-    bool has_release = false;
+    // Every collective in the range where halvings are exact: sizes by
+    // exponent arithmetic.  Otherwise (NPU counts that are not powers of two)
+    // one division at a time, which the first-in-first-out policy can do here
+    // as well; Smallest-Chunk-First then goes to the generic path.
+    bool has_release = false, divide = false;
     for (uint32_t q = 0; q < Q; ++q) {
       const double chunk = collective_size(b, tv, i, q) / (double)s.C;
-      fast = fast && fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs0);
+      divide = divide || !fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs0);
+    }
+    fast = fast && (!divide || !scf);
+    for (uint32_t q = 0; q < Q; ++q) {
+      const double chunk = collective_size(b, tv, i, q) / (double)s.C;
+      fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs0);   // (collective type, initial state; base and epack if exact)
       epack = fs0.epack;
-      rg.CH(q) = fs0.base;  // resident size at mask 0
+      rg.CH(q) = divide ? chunk : fs0.base;  // resident size at mask 0
       if (kExtras) {
         const double release = collective_release(b, tv, i, q);
         rg.REL(q) = release;
@@ -687,7 +695,7 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       double T, z[kMaxDims];
       uint32_t ex[kMaxDims];
       if (simulate_trace_fast<kLdsBitmaps, kExtras, kExtras, kExtras>(s, Q, epack, fs0.state0, fs0.rs_only, scf,
-                                                      has_release, rg, lds, out, T, z, ex)) {
+                                                      divide, has_release, rg, lds, out, T, z, ex)) {
         t_done[i] = T;
         if (busy) {
 #pragma unroll

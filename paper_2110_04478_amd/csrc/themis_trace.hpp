@@ -12,10 +12,12 @@
 // chunk-stage event then costs a bounded number of memory operations instead
 // of a scan over all waiting chunks.
 //
-// Covered: power-of-two NPU counts, up to kTraceMaxColl collectives, any
-// release times (a release that falls on the very instant of a completion is
-// left to the generic path, which orders the arrivals of both kinds by chunk
-// id).  Everything else stays on the generic path.
+// Covered: power-of-two NPU counts under either queue policy, any NPU counts
+// under first-in-first-out (stage times by the order's own divisions); up to
+// kTraceMaxColl collectives, any release times (a release that falls on the
+// very instant of a completion is left to the generic path, which orders the
+// arrivals of both kinds by chunk id).  Everything else stays on the generic
+// path.
 #pragma once
 
 #include "themis_fast.hpp"
@@ -242,9 +244,36 @@ __device__ __forceinline__ double start_stage_trace(uint32_t k, uint32_t val, ui
   return t;
 }
 
+// Bytes a stage moves when the NPU counts are not powers of two: the chunk's
+// size divided step by step by the NPU counts of the dimensions before `pos` in
+// its order, as the latency model of Sec. 4.5 walks it (a stand-alone
+// All-Gather: grown step by step from the order's last dimension down to pos;
+// its stored code is the reversed one).  The same operations in the same order
+// as a scenario evaluated one division at a time, so the result is the same
+// to the last bit.
+__device__ __forceinline__ double trace_divided_bytes(const Scenario& s, double chunk, uint32_t code,
+                                                      uint32_t pos, bool gather) {
+  double x = chunk;
+  if (gather) {
+    for (uint32_t j = (uint32_t)s.D; j-- > pos;) {
+      const uint32_t kj = (code >> (2u * j)) & 3u;
+      x = x * (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+    }
+    return x;
+  }
+  for (uint32_t j = 0; j < pos; ++j) {
+    const uint32_t kj = (code >> (2u * j)) & 3u;
+    x = x / (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+  }
+  return x;
+}
+
+// divide: NPU counts that are not powers of two (FIFO only: the size ranks of
+// Smallest-Chunk-First are built on exact halvings); CH[q] then holds the
+// plain chunk bytes and every stage time comes from trace_divided_bytes().
 template <bool kLdsBitmaps, bool kReleases, bool kFix, bool kQueue>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
-                                           uint32_t state0, bool rs_only, bool scf,
+                                           uint32_t state0, bool rs_only, bool scf, bool divide,
                                            bool has_release,
                                            const TraceRegion& rg, const LaneLds& lds,
                                            const SimOut& out, double& t_done,
@@ -346,7 +375,8 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     // the resident size from the chunk bytes of the collective, which sit in
     // the same 64 bytes as its rank row (the per-rank size table would be one
     // more line to fetch)
-    size = scale_down(rg.CH(q), esum(epack, w & 15u));
+    size = rg.CH(q);
+    if (!divide) size = scale_down(size, esum(epack, w & 15u));
     at = 4u * rg.t.R;
     new_entry = 0u;
     if (h == tl) {
@@ -433,8 +463,13 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       uint32_t pos = 0u;
       // bytes moved on k: the resident size before the chunk's Reduce-Scatter
       // on k, which an All-Gather on k finds 2^ek times smaller
-      const double t = start_stage_trace<kQueue>(k, sv, nx, now, scale_up(size, phase ? ek : 0u),
-                                                 s.coef, s.fix, d, pos);
+      double bytes = scale_up(size, phase ? ek : 0u);
+      if (divide) {
+        // k's place in the chunk's order: the dimensions reduced before it
+        const uint32_t place = ((uint32_t)__builtin_popcount(mask) - phase) & 3u;
+        bytes = trace_divided_bytes(s, size, code, place, (state0 & 16u) != 0u);
+      }
+      const double t = start_stage_trace<kQueue>(k, sv, nx, now, bytes, s.coef, s.fix, d, pos);
       const double fin = now + t;
       // a stage that does not move the clock, or overflows it: generic path decides
       stalled |= !(fin > now && fin < kInf);

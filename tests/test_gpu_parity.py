@@ -412,6 +412,29 @@ def test_traces_ranked_list_path(gpu, oracle):
     check_batch(gpu, oracle, b, threads=16)
 
 
+def test_traces_on_networks_with_other_npu_counts(gpu, oracle):
+    """NPU counts that are not powers of two in traces: under first-in-first-out
+    the ranked-list loop takes them too, every stage time by the order's own
+    divisions (and, for a stand-alone All-Gather, multiplications), one at a
+    time as the latency model walks them; Smallest-Chunk-First still goes to the
+    generic path.  Ragged D, C and collective counts, all collective types,
+    with and without release times, fixed delays and queue orders."""
+    rng = np.random.default_rng(15)
+    for seed, mc, ncoll in ((61, 8, 5), (62, 12, 9), (63, 64, 4)):
+        b = _add_trace(w().mixed(160, seed=seed, max_chunks=mc, pow2=False), rng, ncoll, pow2_sizes=False)
+        b.intra_policy[:] = 0                     # all first-in-first-out: the list path
+        b.intra_policy[::5] = 1                   # a fifth Smallest-Chunk-First: the generic path
+        check_batch(gpu, oracle, _with_collective_types(b, seed))
+        check_batch(gpu, oracle, b, queue=False)
+        b.release_time = np.ascontiguousarray(rng.integers(0, 5, b.coll_size.shape) * 2e-4)
+        check_batch(gpu, oracle, _with_fixed_delay(b, seed + 1))
+    # the config-5 shape on P = (6, 12, 24)
+    b = w().config5(n=80, n_coll=12)
+    b.npus = np.ascontiguousarray(np.array([[6], [12], [24], [1]], dtype=np.uint32).repeat(b.n, axis=1))
+    b.intra_policy[:] = 0
+    check_batch(gpu, oracle, b)
+
+
 def test_traces_without_queue_orders(gpu, oracle):
     """Traces with neither release times, fixed delays nor queue orders asked
     for run a kernel compiled without those steps: times and busy times against
