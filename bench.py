@@ -103,11 +103,12 @@ def other_workload(args, np, torch, binding, workloads):
     else:
         n = args.scenarios if args.scenarios != 1 << 20 else 16384
         host = workloads.config5(n=n)
-        if args.workload == "config5fifo6":
-            # the same traces on P = (6, 12, 24) under first-in-first-out: NPU counts that are
-            # not powers of two on the list path (Smallest-Chunk-First would take the generic one)
+        if args.workload in ("config5fifo6", "config5scf6"):
+            # the same traces on P = (6, 12, 24): NPU counts that are not powers of two on the
+            # list path, under first-in-first-out or Smallest-Chunk-First
             host.npus = np.ascontiguousarray(np.array([[6], [12], [24], [1]], dtype=np.uint32).repeat(n, axis=1))
-            host.intra_policy[:] = 0
+            if args.workload == "config5fifo6":
+                host.intra_policy[:] = 0
         D, C, Q = 3, 64, host.max_coll
         d = binding.to_device(host, dev)
         evals = n
@@ -124,6 +125,8 @@ def other_workload(args, np, torch, binding, workloads):
                 "plan + simulate (times and busy)" % (n, Q))
         if args.workload == "config5fifo6":
             name = name.replace("P=(8,16,32)", "P=(6,12,24)").replace("Themis+SCF", "Themis+FIFO").replace("config5", "config5fifo6")
+        if args.workload == "config5scf6":
+            name = name.replace("P=(8,16,32)", "P=(6,12,24)").replace("config5", "config5scf6")
         kernel = "simulate_trace"
     for _ in range(args.warmup):
         step()
@@ -322,7 +325,7 @@ def main():
                     help="scenarios the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-queue-order", action="store_true",
                     help="do not request the per-dimension queue orders")
-    ap.add_argument("--workload", choices=("config3", "config4", "config5", "config5fifo6", "extras", "small"), default="config3")
+    ap.add_argument("--workload", choices=("config3", "config4", "config5", "config5fifo6", "config5scf6", "extras", "small"), default="config3")
     ap.add_argument("--sweep-mapping", choices=("auto", "lane", "quad"), default="auto",
                     help="lane mapping of themis_sweep's LDS kernel (auto: the library's choice)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",

@@ -182,7 +182,12 @@ int themis_queue_entry_bytes(uint32_t max_chunks, uint32_t max_coll);
  *     times that leave the binary64 range on the way) goes to a slower generic
  *     path, whose per-chunk state sits in LDS up to 64 chunks and in the
  *     workspace beyond;
- *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace.
+ *   - traces (n_coll != NULL) keep their per-scenario queues in the workspace
+ *     (up to 256 collectives on the fast path, whatever the NPU counts; with
+ *     NPU counts that are not powers of two under Smallest-Chunk-First up to
+ *     4096 / (D! * 2) collectives -- 341 on three dimensions, 85 on four --,
+ *     D! for a stand-alone Reduce-Scatter or All-Gather; beyond that the
+ *     generic path, same results, far slower).
  * For themis_sweep pass n * n_thr * n_pol as n and max_coll = 0.
  * Passing a smaller or NULL workspace is allowed: every scenario that would
  * have needed it then comes back as NaN / all-ones, like an invalid one (the

@@ -662,14 +662,16 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
     rg.t = tl;
     // Every collective in the range where halvings are exact: sizes by
     // exponent arithmetic.  Otherwise (NPU counts that are not powers of two)
-    // one division at a time, which the first-in-first-out policy can do here
-    // as well; Smallest-Chunk-First then goes to the generic path.
+    // one division at a time, with size ranks per (dimension, phase, order)
+    // under Smallest-Chunk-First as long as they fit the lists.
     bool has_release = false, divide = false;
     for (uint32_t q = 0; q < Q; ++q) {
       const double chunk = collective_size(b, tv, i, q) / (double)s.C;
       divide = divide || !fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs0);
     }
-    fast = fast && (!divide || !scf);
+    // (division mode ranks every (phase, order) of a dimension: more lists than the masks of halving mode)
+    fast = fast && (!divide || !scf ||
+                    Q * trace_division_lists((uint32_t)s.D, s.ctype != THEMIS_COLL_ALL_REDUCE) <= tl.R);
     for (uint32_t q = 0; q < Q; ++q) {
       const double chunk = collective_size(b, tv, i, q) / (double)s.C;
       fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs0);   // (collective type, initial state; base and epack if exact)
@@ -991,26 +993,6 @@ sweep_best_kernel(uint64_t n, uint32_t n_thr, uint32_t n_pol, const double* __re
 // ---------------------------------------------------------------------------
 // themis_search_batch: every assignment of dimension orders to chunks.
 // ---------------------------------------------------------------------------
-// Order code of the permutation of (0..D-1) with lexicographic index idx.
-__device__ __forceinline__ uint32_t nth_permutation_code(uint32_t D, uint32_t idx) {
-  uint32_t pool = 0x3210u;  // remaining dimensions, one nibble each, ascending
-  uint32_t code = 0;
-  uint32_t fact = D >= 4u ? 6u : D == 3u ? 2u : 1u;  // (D-1)!
-  for (uint32_t j = 0; j < D; ++j) {
-    const uint32_t pick = idx / fact;
-    idx -= pick * fact;
-    code |= ((pool >> (4u * pick)) & 3u) << (2u * j);
-    pool = (pool & ((1u << (4u * pick)) - 1u)) | ((pool >> (4u * (pick + 1u))) << (4u * pick));
-    const uint32_t left = D - 1u - j;
-    if (left > 1u) fact /= left;
-  }
-  return code;
-}
-
-__device__ __forceinline__ uint32_t factorial_u32(uint32_t D) {
-  return D >= 4u ? 24u : D == 3u ? 6u : D == 2u ? 2u : 1u;
-}
-
 // (D!)^C if it does not exceed bound, else 0.
 __device__ __forceinline__ uint64_t assignment_count(uint32_t D, uint32_t C, uint64_t bound) {
   const uint64_t F = factorial_u32(D);

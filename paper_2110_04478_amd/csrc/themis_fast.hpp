@@ -207,6 +207,26 @@ __device__ __forceinline__ uint32_t stored_code(const Scenario& s, const FastSce
   return fs.gather ? reverse_code(code, s.D) : code;
 }
 
+// Order code of the permutation of (0..D-1) with lexicographic index idx.
+__device__ __forceinline__ uint32_t nth_permutation_code(uint32_t D, uint32_t idx) {
+  uint32_t pool = 0x3210u;  // remaining dimensions, one nibble each, ascending
+  uint32_t code = 0;
+  uint32_t fact = D >= 4u ? 6u : D == 3u ? 2u : 1u;  // (D-1)!
+  for (uint32_t j = 0; j < D; ++j) {
+    const uint32_t pick = idx / fact;
+    idx -= pick * fact;
+    code |= ((pool >> (4u * pick)) & 3u) << (2u * j);
+    pool = (pool & ((1u << (4u * pick)) - 1u)) | ((pool >> (4u * (pick + 1u))) << (4u * pick));
+    const uint32_t left = D - 1u - j;
+    if (left > 1u) fact /= left;
+  }
+  return code;
+}
+
+__device__ __forceinline__ uint32_t factorial_u32(uint32_t D) {
+  return D >= 4u ? 24u : D == 3u ? 6u : D == 2u ? 2u : 1u;
+}
+
 // ---------------------------------------------------------------------------
 // Planner (Alg. 1) with static register indexing.  emit(c, code) receives
 // every chunk's order code; load[] holds the Dim Load Tracker on return.

@@ -29,13 +29,18 @@ constexpr uint32_t kTraceLeafWords = kTraceMaxColl * 16 / 32;
 constexpr uint32_t kTraceSumWords = 4;
 constexpr uint32_t kNoChunk = 0xffffu;
 constexpr uint32_t kTraceCollBytes = 64;
+// NPU counts that are not powers of two (division mode): a chunk's resident
+// size depends on its whole order, so a collective has one size rank per
+// (dimension, phase, order): 4 x 2 x 24 16-bit ranks.
+constexpr uint32_t kTraceStates = 48;
+constexpr uint32_t kTraceMaxRanks = kTraceMaxColl * 16;
 
 // Byte offsets inside one scenario's region of the workspace.
 struct TraceLayout {
   uint32_t G;   // chunk slots (max_chunks * max_coll)
   uint32_t Q;   // collectives the region is sized for
-  uint32_t R;   // ranks per dimension = Q * 16
-  uint32_t off_ht, off_bm, off_col, off_sq, off_sq2, off_rq;
+  uint32_t R;   // ranks per dimension: Q * 16 in halving mode, up to Q * 48 in division mode, 4096 at most
+  uint32_t off_ht, off_bm, off_col, off_sq, off_sq2, off_rq, off_srd, off_mh;
   uint32_t bytes;  // multiple of 16; 0 if the batch cannot use this path
 };
 
@@ -43,7 +48,7 @@ __host__ __device__ inline TraceLayout trace_layout(uint32_t max_chunks, uint32_
   TraceLayout t;
   t.G = max_chunks * max_coll;
   t.Q = max_coll;
-  t.R = max_coll * 16u;
+  t.R = max_coll * kTraceStates < kTraceMaxRanks ? max_coll * kTraceStates : kTraceMaxRanks;
   if (max_coll == 0u || max_coll > kTraceMaxColl) { t.bytes = 0; return t; }
   uint32_t o = t.G * 4u;                   // W: one dword per chunk
   t.off_ht = o;  o += 4u * t.R * 4u;       // head | tail << 16 per (dimension, rank)
@@ -54,6 +59,9 @@ __host__ __device__ inline TraceLayout trace_layout(uint32_t max_chunks, uint32_
   t.off_sq = o;  o += ((t.Q + 1u) & ~1u) * 2u;   // collectives sorted by chunk size
   t.off_sq2 = o; o += ((t.Q + 1u) & ~1u) * 2u;   // the merge sort's second buffer
   t.off_rq = o;  o += ((t.Q + 1u) & ~1u) * 2u;   // collectives sorted by release time
+  // division mode: the ranks of every collective, and the heads of the merge that builds them
+  t.off_srd = (o + 15u) & ~15u; o = t.off_srd + t.Q * 4u * kTraceStates * 2u;
+  t.off_mh = (o + 15u) & ~15u;  o = t.off_mh + kTraceStates * 16u;
   t.bytes = (o + 63u) & ~63u;
   return t;
 }
@@ -89,6 +97,21 @@ struct TraceRegion {
   __device__ __forceinline__ uint16_t& SQbuf(uint32_t which, uint32_t j) const {
     const uint32_t off = which == 0u ? t.off_sq : which == 1u ? t.off_sq2 : t.off_rq;
     return ((uint16_t*)(base + off))[min(j, t.Q - 1u)];
+  }
+  // division mode: rank of collective q's chunks waiting for dimension k in state st
+  __device__ __forceinline__ uint16_t& SRD(uint32_t q, uint32_t k, uint32_t st) const {
+    return ((uint16_t*)(base + t.off_srd))[(min(q, t.Q - 1u) * 4u + (k & 3u)) * kTraceStates +
+                                           min(st, kTraceStates - 1u)];
+  }
+  // heads of the merge: value (f64), position (u32), what the list is (u32)
+  __device__ __forceinline__ double& MHV(uint32_t l) const {
+    return ((double*)(base + t.off_mh))[min(l, kTraceStates - 1u)];
+  }
+  __device__ __forceinline__ uint32_t& MHP(uint32_t l) const {
+    return ((uint32_t*)(base + t.off_mh + kTraceStates * 8u))[min(l, kTraceStates - 1u)];
+  }
+  __device__ __forceinline__ uint32_t& MHL(uint32_t l) const {
+    return ((uint32_t*)(base + t.off_mh + kTraceStates * 12u))[min(l, kTraceStates - 1u)];
   }
   __device__ __forceinline__ double& REL(uint32_t q) const {
     return *(double*)(base + t.off_col + min(q, t.Q - 1u) * kTraceCollBytes + 40u);
@@ -173,6 +196,97 @@ __device__ inline uint32_t trace_build_ranks(const TraceRegion& rg, uint32_t Q, 
     *(uint32_t*)lds.dword(32u + mb) = pn;
   }
   return rank + 1u;
+}
+
+// Division mode ----------------------------------------------------------
+// Lexicographic rank (0..23) of an order code read as a permutation of all
+// four dimensions (the unused fields take their own index).
+__device__ __forceinline__ uint32_t trace_order_rank(uint32_t code, uint32_t D) {
+  const uint32_t c8 = code | (0xe4u & ~((1u << (2u * D)) - 1u));
+  const uint32_t o0 = c8 & 3u, o1 = (c8 >> 2) & 3u, o2 = (c8 >> 4) & 3u, o3 = (c8 >> 6) & 3u;
+  const uint32_t r1 = o1 - (o1 > o0 ? 1u : 0u);
+  return 6u * o0 + 2u * r1 + (o2 > o3 ? 1u : 0u);
+}
+// The state a chunk with stored order `code` is in while it waits in phase
+// `phase` (its dimension follows from both): index into a collective's ranks.
+__device__ __forceinline__ uint32_t trace_state(uint32_t code, uint32_t phase, uint32_t D) {
+  return (phase & 1u) * 24u + trace_order_rank(code, D);
+}
+
+// Resident bytes of a chunk that waits for the dimension at `place` of its
+// stored order, one division or multiplication at a time in the order the
+// stages run (Sec. 2.1: a Reduce-Scatter stage leaves 1/P of the data, an
+// All-Gather stage P times as much): the Smallest-Chunk-First key.
+__device__ __forceinline__ double trace_resident_bytes(const Scenario& s, double chunk, uint32_t code,
+                                                       uint32_t place, uint32_t phase, bool gather) {
+  double x = chunk;
+  const uint32_t D = (uint32_t)s.D;
+  if (!gather) {
+    const uint32_t divisions = phase ? D : place;
+    for (uint32_t j = 0; j < divisions; ++j) {
+      const uint32_t kj = (code >> (2u * j)) & 3u;
+      x = x / (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+    }
+  }
+  if (phase) {
+    for (uint32_t j = D; j-- > place + 1u;) {
+      const uint32_t kj = (code >> (2u * j)) & 3u;
+      x = x * (double)sel4((int)kj, s.P[0], s.P[1], s.P[2], s.P[3]);
+    }
+  }
+  return x;
+}
+
+// Lists per dimension that the ranks of division mode are merged from.
+__device__ __forceinline__ uint32_t trace_division_lists(uint32_t D, bool one_phase) {
+  return factorial_u32(D) * (one_phase ? 1u : 2u);
+}
+
+// Ranks of all resident sizes in division mode, per dimension: for every
+// (phase, order) the sizes over the collectives in ascending chunk order are
+// ascending (a rounded division or multiplication by a constant keeps the
+// order), so the ranks of dimension k come from a merge of those lists, equal
+// sizes sharing a rank.  Needs Q * trace_division_lists() <= R.
+__device__ inline void trace_build_ranks_divided(const TraceRegion& rg, const Scenario& s, uint32_t Q,
+                                                 bool gather, bool rs_only) {
+  const uint32_t D = (uint32_t)s.D;
+  trace_sort_collectives(rg, Q, 0u, [&](uint32_t q) { return (double)rg.CH(q); });
+  const uint32_t F = factorial_u32(D);
+  for (uint32_t k = 0; k < D; ++k) {
+    uint32_t nl = 0;
+    for (uint32_t idx = 0; idx < F; ++idx) {
+      const uint32_t code = nth_permutation_code(D, idx);
+      uint32_t place = 0;
+      for (uint32_t j = 0; j < D; ++j) place = ((code >> (2u * j)) & 3u) == k ? j : place;
+      for (uint32_t phase = gather ? 1u : 0u; phase < (rs_only ? 1u : 2u); ++phase) {
+        rg.MHL(nl) = code | (phase << 8) | (place << 9);
+        rg.MHP(nl) = 0u;
+        rg.MHV(nl) = trace_resident_bytes(s, rg.CH(rg.SQ(0)), code, place, phase, gather);
+        ++nl;
+      }
+    }
+    uint32_t rank = 0;
+    double prev = -1.0;
+    const uint32_t total = Q * nl;
+    for (uint32_t out = 0; out < total; ++out) {
+      uint32_t lb = 0;
+      double vb = inf64();
+      for (uint32_t l = 0; l < nl; ++l) {
+        const double v = rg.MHV(l);
+        if (v < vb) { vb = v; lb = l; }
+      }
+      if (out > 0u && vb > prev) ++rank;
+      prev = vb;
+      const uint32_t what = rg.MHL(lb);
+      const uint32_t code = what & 0xffu, phase = (what >> 8) & 1u, place = (what >> 9) & 3u;
+      const uint32_t p = rg.MHP(lb);
+      rg.SRD(rg.SQ(p), k, trace_state(code, phase, D)) = (uint16_t)rank;
+      const uint32_t pn = p + 1u;
+      rg.MHP(lb) = pn;
+      rg.MHV(lb) = pn < Q ? trace_resident_bytes(s, rg.CH(rg.SQ(pn)), code, place, phase, gather)
+                          : inf64();
+    }
+  }
 }
 
 // Per-lane LDS of the trace path: 48 dwords for trace_build_ranks, reused
@@ -268,9 +382,9 @@ __device__ __forceinline__ double trace_divided_bytes(const Scenario& s, double 
   return x;
 }
 
-// divide: NPU counts that are not powers of two (FIFO only: the size ranks of
-// Smallest-Chunk-First are built on exact halvings); CH[q] then holds the
-// plain chunk bytes and every stage time comes from trace_divided_bytes().
+// divide: NPU counts that are not powers of two; CH[q] then holds the plain
+// chunk bytes, every stage time comes from trace_divided_bytes() and the size
+// ranks of Smallest-Chunk-First from trace_build_ranks_divided().
 template <bool kLdsBitmaps, bool kReleases, bool kFix, bool kQueue>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
                                            uint32_t state0, bool rs_only, bool scf, bool divide,
@@ -285,7 +399,10 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   const uint32_t full = (1u << D) - 1u;
   const double kInf = inf64();
 
-  if (scf) trace_build_ranks(rg, Q, D, epack, lds);
+  if (scf) {
+    if (divide) trace_build_ranks_divided(rg, s, Q, (state0 & 16u) != 0u, rs_only);
+    else trace_build_ranks(rg, Q, D, epack, lds);
+  }
   // non-empty bitmaps: one summary word per 32 leaves, one leaf bit per rank
   auto SUM = [&](uint32_t k, uint32_t sw) -> uint32_t& {
     return *(uint32_t*)lds.dword((k & 3u) * kTraceSumWords + (sw & (kTraceSumWords - 1u)));
@@ -324,8 +441,11 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   const uint32_t c_inv = C == 1u ? 0u : (uint32_t)((0x100000000ull + C - 1u) / C);
   const uint32_t c_one = C == 1u ? ~0u : 0u;
   auto coll_of = [&](uint32_t g) -> uint32_t { return __umulhi(g, c_inv) + (g & c_one); };
-  auto rank_of = [&](uint32_t g, uint32_t mask) -> uint32_t {
-    return scf ? (uint32_t)rg.SR(coll_of(g), mask) : 0u;
+  // rank of chunk g (word w) once it waits for dimension k with the given mask and phase
+  auto rank_of = [&](uint32_t g, uint32_t w, uint32_t k, uint32_t mask, uint32_t phase) -> uint32_t {
+    if (!scf) return 0u;
+    if (divide) return (uint32_t)rg.SRD(coll_of(g), k, trace_state((w >> 8) & 0xffu, phase, D));
+    return (uint32_t)rg.SR(coll_of(g), mask);
   };
   // Memory operations of one wavefront retire in order, so waiting for a load
   // also waits for every store issued before it: push and pop read first and
@@ -412,7 +532,9 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       const uint32_t q = has_release ? (uint32_t)rg.SQbuf(2u, rel_next) : rel_next;
       for (uint32_t c = 0; c < C; ++c) {
         const uint32_t g = q * C + c;
-        push((rg.W(g) >> (8u + pos0)) & 3u, rank_of(g, mask0), g, false, 0u);
+        const uint32_t w0 = rg.W(g);
+        const uint32_t k0 = (w0 >> (8u + pos0)) & 3u;
+        push(k0, rank_of(g, w0, k0, mask0, phase0), g, false, 0u);
       }
       ++rel_next;
       rel_time = rel_next >= Q ? kInf : has_release ? (double)rg.REL(rg.SQbuf(2u, rel_next)) : 0.0;
@@ -425,8 +547,11 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   } else {
     const uint32_t mask0 = state0 & 15u, phase0 = state0 >> 4;
     const uint32_t pos0 = 2u * ((uint32_t)__builtin_popcount(mask0) - phase0);
-    for (uint32_t g = 0; g < G; ++g)
-      push((rg.W(g) >> (8u + pos0)) & 3u, rank_of(g, mask0), g, false, 0u);
+    for (uint32_t g = 0; g < G; ++g) {
+      const uint32_t w0 = rg.W(g);
+      const uint32_t k0 = (w0 >> (8u + pos0)) & 3u;
+      push(k0, rank_of(g, w0, k0, mask0, phase0), g, false, 0u);
+    }
   }
 
   // One pass starts at most one stage and, once no idle dimension has chunks
@@ -457,7 +582,9 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       const bool upper = (mask2 & 8u) != 0u;
       const uint32_t pair = sel4((int)(mask2 >> 1), upper ? row_hi.x : row_lo.x, upper ? row_hi.y : row_lo.y,
                                  upper ? row_hi.z : row_lo.z, upper ? row_hi.w : row_lo.w);
-      const uint32_t rk = scf ? (pair >> (16u * (mask2 & 1u))) & 0xffffu : 0u;
+      uint32_t rk = scf ? (pair >> (16u * (mask2 & 1u))) & 0xffffu : 0u;
+      // division mode: the rank row is per (dimension, phase, order), known only now
+      if (divide && scf && !finished) rk = rg.SRD(coll_of(h), kn, trace_state(code, phase2, D));
       const uint32_t sv = (h << 2) | k;
       const uint32_t nx = mask2 | (phase2 << 4) | (code << 8) | (kn << 16) | (rk << 19);
       uint32_t pos = 0u;

@@ -397,7 +397,7 @@ def test_traces_ranked_list_path(gpu, oracle):
     b = w().config5(n=64, n_coll=24)
     b.intra_policy[::2] = 0           # half FIFO
     check_batch(gpu, oracle, b)
-    # non-power-of-two NPU counts in a trace stay on the generic path
+    # NPU counts that are not powers of two: the same path in division mode
     b = _add_trace(w().mixed(100, seed=43, max_chunks=8, pow2=False), rng, 5, pow2_sizes=False)
     check_batch(gpu, oracle, b)
     # the largest trace the ranked lists take (256 collectives) and one beyond it (generic path)
@@ -413,26 +413,34 @@ def test_traces_ranked_list_path(gpu, oracle):
 
 
 def test_traces_on_networks_with_other_npu_counts(gpu, oracle):
-    """NPU counts that are not powers of two in traces: under first-in-first-out
-    the ranked-list loop takes them too, every stage time by the order's own
-    divisions (and, for a stand-alone All-Gather, multiplications), one at a
-    time as the latency model walks them; Smallest-Chunk-First still goes to the
-    generic path.  Ragged D, C and collective counts, all collective types,
-    with and without release times, fixed delays and queue orders."""
+    """NPU counts that are not powers of two in traces: the ranked-list loop
+    takes them too, every stage time by the order's own divisions (and, for a
+    stand-alone All-Gather, multiplications), one at a time as the latency model
+    walks them, and under Smallest-Chunk-First with one size rank per
+    (dimension, phase, order) of every collective.  Ragged D, C and collective
+    counts, both policies, all collective types, with and without release times,
+    fixed delays and queue orders; a trace with too many collectives for the
+    ranks of a 4-D network goes to the generic path."""
     rng = np.random.default_rng(15)
     for seed, mc, ncoll in ((61, 8, 5), (62, 12, 9), (63, 64, 4)):
         b = _add_trace(w().mixed(160, seed=seed, max_chunks=mc, pow2=False), rng, ncoll, pow2_sizes=False)
-        b.intra_policy[:] = 0                     # all first-in-first-out: the list path
-        b.intra_policy[::5] = 1                   # a fifth Smallest-Chunk-First: the generic path
+        b.intra_policy[::2] = 0                   # half first-in-first-out
         check_batch(gpu, oracle, _with_collective_types(b, seed))
         check_batch(gpu, oracle, b, queue=False)
         b.release_time = np.ascontiguousarray(rng.integers(0, 5, b.coll_size.shape) * 2e-4)
         check_batch(gpu, oracle, _with_fixed_delay(b, seed + 1))
-    # the config-5 shape on P = (6, 12, 24)
+    # the config-5 shape on P = (6, 12, 24), both policies
     b = w().config5(n=80, n_coll=12)
     b.npus = np.ascontiguousarray(np.array([[6], [12], [24], [1]], dtype=np.uint32).repeat(b.n, axis=1))
-    b.intra_policy[:] = 0
+    b.intra_policy[::2] = 0
     check_batch(gpu, oracle, b)
+    # 4-D, 100 collectives: 100 x 48 ranks per dimension do not fit the lists (generic path), 80 do
+    for ncoll in (100, 80):
+        b = _add_trace(w().mixed(12, seed=64, max_chunks=4, pow2=False), rng, ncoll, pow2_sizes=False)
+        b.ndims[:] = 4
+        b.n_coll[:] = ncoll
+        b.intra_policy[:] = 1
+        check_batch(gpu, oracle, b, threads=16)
 
 
 def test_traces_without_queue_orders(gpu, oracle):

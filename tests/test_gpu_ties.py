@@ -190,6 +190,33 @@ def test_tie_rich_networks_with_other_npu_counts(gpu, oracle):
         check_batch(gpu, oracle, _with_collective_types(b, 2), workspace=False)
 
 
+def test_tie_rich_traces_with_other_npu_counts(gpu, oracle):
+    """Traces on networks with NPU counts 3, 6 and 12 under both queue policies
+    (division mode of the ranked-list path: one size rank per (dimension, phase,
+    order) and collective, equal sizes sharing a rank): bandwidths 2^a * (P-1)/P
+    keep the per-byte latencies powers of two and sizes that are multiples of
+    3^4 * 2^m divide evenly, so equal resident sizes across orders, phases and
+    collectives abound, as do equal times; with collectives released at one
+    instant and at coinciding instants."""
+    W = w()
+    rng = np.random.default_rng(34)
+    for max_chunks, max_coll, n in ((8, 6, 300), (16, 10, 120), (64, 3, 70)):
+        b = W.dyadic_ties(n, seed=7900 + max_chunks, max_chunks=max_chunks)
+        scale = (b.npus - 1.0) / b.npus
+        a = b.bw / scale
+        b.npus = np.ascontiguousarray(rng.choice([3, 6, 12, 4], (4, n)).astype(np.uint32))
+        b.bw = np.ascontiguousarray(a * ((b.npus - 1.0) / b.npus))
+        b.max_coll = max_coll
+        b.n_coll = rng.integers(1, max_coll + 1, n).astype(np.uint32)
+        b.coll_size = np.ascontiguousarray(
+            (b.size_bytes * 81.0)[None, :] * 2.0 ** rng.integers(-2, 3, (max_coll, n)))
+        b.release_time = None
+        check_batch(gpu, oracle, _with_collective_types(b, 3))
+        b.release_time = np.ascontiguousarray(rng.integers(0, 4, (max_coll, n)) * 2.0 ** -12)
+        t = check_batch(gpu, oracle, b)
+        assert np.isfinite(t).all()
+
+
 @pytest.mark.parametrize("mapping", ["lane", "quad"])
 def test_sweep_mappings_agree_with_the_oracle(gpu, oracle, mapping):
     """themis_sweep under each of its two lane mappings (one lane per evaluation;
