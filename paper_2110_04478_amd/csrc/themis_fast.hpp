@@ -78,7 +78,9 @@ struct Classes16 {
 
 // Per-lane LDS layouts with 8-bit chunk ids (kChunks <= 128; 0xFF ends a list).
 //
-// Layout64 (80 dwords, 20 KiB per wavefront, 8 wavefronts per CU):
+// Layout64 (80 dwords, 20 KiB per wavefront, 8 wavefronts per CU; the table
+// layouts for other NPU counts build on it, power-of-two scenarios of up to 64
+// chunks run on the ring layout of themis_ring.hpp instead):
 //   dword c (0..63), one per chunk c AND per list q = 16*dim + class:
 //     byte 0  chunk c: reduced-dims mask | phase << 4
 //     byte 1  chunk c: next chunk in its list (0xFF = last)
@@ -483,10 +485,11 @@ __device__ __forceinline__ uint32_t stages_ending(double now, Dims& d, uint32_t&
 // of slots).  Either way every lane appends to its own four rows, so the
 // stores of a wavefront never share a cache line.  kStagedBytes (8-bit
 // entries, whole wavefronts) stores each entry into a staging order inside
-// the wavefront's own block of the output: dword w of lane L's rows (four
-// entries) at byte (w * 64 + L) * 4, so that the entries the 64 lanes store at
-// about the same time share cache lines; whoever asks for it puts the rows in
-// place afterwards.
+// the wavefront's own block of the output, so that the entries the 64 lanes
+// store at about the same time share cache lines; whoever asks for it puts
+// the rows in place afterwards.  The order is the event loop's own: here dword
+// w of lane L's rows (four entries) sits at byte (w * 64 + L) * 4, the ring
+// loop keeps single bytes 64 apart (themis_ring.hpp).
 enum QueueOrderMode { kNoQueueOrder = 0, kBytes = 1, kWords = 2, kShorts = 3, kStagedBytes = 4 };
 
 // What the event loop needs to know about sizes and times, for scenarios with
