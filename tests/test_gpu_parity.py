@@ -898,6 +898,59 @@ def test_entry_points_replay_inside_a_hip_graph(gpu, oracle):
             assert same, f"replay {rep}: {name} differs from the eager run"
 
 
+def test_kernel_launches_per_call(gpu):
+    """How many kernels a call launches, counted as the nodes of a HIP graph
+    captured around it: the planner one; the simulation and the sweep two (the
+    LDS kernel and one follow-up kernel that holds the table passes and the
+    generic pass), whatever the chunk capacity; three only for a batch of more
+    than 2 x CUs wavefronts with up to 64 chunks and no workspace, whose generic
+    pass keeps its 80 KiB of LDS to itself."""
+    import ctypes as C
+    import torch
+    hip = C.CDLL("libamdhip64.so")
+
+    def nodes(fn):
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()                                             # warm-up: nothing lazy left to load
+            side.synchronize()
+            handle = C.c_void_p(side.cuda_stream)
+            assert hip.hipStreamBeginCapture(handle, 2) == 0     # relaxed: other threads may call HIP
+            try:
+                fn()
+            finally:
+                graph = C.c_void_p()
+                rc = hip.hipStreamEndCapture(handle, C.byref(graph))
+            assert rc == 0 and graph.value
+            count = C.c_size_t(0)
+            assert hip.hipGraphGetNodes(graph, None, C.byref(count)) == 0
+            hip.hipGraphDestroy(graph)
+        torch.cuda.synchronize()
+        return count.value
+
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    thr = torch.tensor([0.0, 0.25], dtype=torch.float64, device="cuda")
+    for max_chunks, n, with_ws, want in ((64, 3000, False, 2), (64, 3000, True, 2), (16, 500, False, 2),
+                                         (128, 700, True, 2), (512, 300, True, 2),
+                                         (64, 2 * cus * 64 + 64, True, 2), (64, 2 * cus * 64 + 64, False, 3)):
+        b = w().mixed(n, seed=500 + max_chunks, max_chunks=max_chunks, pow2=(max_chunks != 128))
+        d = gpu.to_device(b)
+        orders = torch.empty((n, d.slots), dtype=torch.uint8, device="cuda")
+        loads = torch.empty((4, n), dtype=torch.float64, device="cuda")
+        t_done = torch.empty(n, dtype=torch.float64, device="cuda")
+        busy = torch.empty((4, n), dtype=torch.float64, device="cuda")
+        qo = torch.empty((n, 4, 2 * d.slots), dtype=torch.uint8 if max_chunks <= 127 else torch.int16,
+                         device="cuda")
+        sw = torch.empty((n, 2, 3), dtype=torch.float64, device="cuda")
+        ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(n * 6, d.max_chunks)) if with_ws else None
+        assert nodes(lambda: gpu.themis_plan_batch(d, orders, loads)) == 1
+        assert nodes(lambda: gpu.themis_simulate_batch(d, orders, t_done, qo, busy, ws)) == want, \
+            (max_chunks, n, with_ws)
+        assert nodes(lambda: gpu.themis_sweep(d, thr, 7, t_done=sw, workspace=ws)) == want, \
+            (max_chunks, n, with_ws)
+
+
 @pytest.mark.parametrize("max_chunks,pow2,thr_mode", [(2, True, 0), (64, True, 1), (64, False, 0),
                                                       (100, True, 1)])
 def test_special_values(gpu, oracle, max_chunks, pow2, thr_mode):
