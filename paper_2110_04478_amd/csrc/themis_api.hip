@@ -696,8 +696,15 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
       double T, z[kMaxDims];
       uint32_t ex[kMaxDims];
-      if (simulate_trace_fast<kLdsBitmaps, kExtras, kExtras, kExtras>(s, Q, epack, fs0.state0, fs0.rs_only, scf,
-                                                      divide, has_release, rg, lds, out, T, z, ex)) {
+      // the common case gets a loop of its own when the whole wavefront is in it
+      const bool other = divide || !scf || fs0.rs_only || fs0.state0 != 0u;
+      const bool plain = __builtin_amdgcn_ballot_w64(other) == 0ull;
+      const bool done = plain
+          ? simulate_trace_fast<kLdsBitmaps, kExtras, kExtras, kExtras, true>(
+                s, Q, epack, fs0.state0, fs0.rs_only, scf, divide, has_release, rg, lds, out, T, z, ex)
+          : simulate_trace_fast<kLdsBitmaps, kExtras, kExtras, kExtras, false>(
+                s, Q, epack, fs0.state0, fs0.rs_only, scf, divide, has_release, rg, lds, out, T, z, ex);
+      if (done) {
         t_done[i] = T;
         if (busy) {
 #pragma unroll

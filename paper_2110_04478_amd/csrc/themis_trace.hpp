@@ -333,29 +333,53 @@ struct TraceDims {
 #define THEMIS_N_OPERANDS [n0] "+v"(d.n0), [n1] "+v"(d.n1), [n2] "+v"(d.n2), [n3] "+v"(d.n3)
 #define THEMIS_E_OPERANDS [e0] "+v"(d.e0), [e1] "+v"(d.e1), [e2] "+v"(d.e2), [e3] "+v"(d.e3)
 
+// three: not zero, in every lane of the wavefront alike, when no lane has a
+// fourth dimension: its turn is jumped over.
+#define THEMIS_TRACE_TURNS(BODY)                                                       \
+  "s_mov_b64 %[act], exec\n\t" BODY(0) BODY(1) BODY(2)                                 \
+  "v_cmp_ne_u32_e32 vcc, 0, %[three]\n\t" "s_cbranch_vccnz .Lthree_dims_%=\n\t" BODY(3) ".Lthree_dims_%=:\n\t"
 template <bool kFixAndQueue>
 __device__ __forceinline__ double start_stage_trace(uint32_t k, uint32_t val, uint32_t nx,
                                                     double now, double x,
                                                     const double (&c)[kMaxDims],
                                                     const double (&a)[kMaxDims], TraceDims& d,
-                                                    uint32_t& pos) {
+                                                    uint32_t& pos, uint32_t three) {
   uint64_t act;
   double t;
   if (kFixAndQueue) {
-    asm volatile(THEMIS_FOUR(THEMIS_TRACE_FULL)
+    asm volatile(THEMIS_TRACE_TURNS(THEMIS_TRACE_FULL)
         : [act] "=&s"(act), [t] "=&v"(t), [pos] "+v"(pos), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS,
           THEMIS_S_OPERANDS, THEMIS_N_OPERANDS, THEMIS_E_OPERANDS
         : [k] "v"(k), [val] "v"(val), [nx] "v"(nx), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
-          THEMIS_A_OPERANDS
+          THEMIS_A_OPERANDS, [three] "v"(three)
         : "vcc");
   } else {
-    asm volatile(THEMIS_FOUR(THEMIS_TRACE_PLAIN)
+    asm volatile(THEMIS_TRACE_TURNS(THEMIS_TRACE_PLAIN)
         : [act] "=&s"(act), [t] "=&v"(t), THEMIS_F_OPERANDS, THEMIS_Z_OPERANDS, THEMIS_S_OPERANDS,
           THEMIS_N_OPERANDS
-        : [k] "v"(k), [val] "v"(val), [nx] "v"(nx), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS
+        : [k] "v"(k), [val] "v"(val), [nx] "v"(nx), [now] "v"(now), [x] "v"(x), THEMIS_C_OPERANDS,
+          [three] "v"(three)
         : "vcc");
   }
   return t;
+}
+
+// The stages that end now, as stages_ending(), with the fourth dimension's
+// turn jumped over where no lane has one.
+__device__ __forceinline__ uint32_t trace_stages_ending(double now, TraceDims& d, uint32_t& first,
+                                                        uint32_t three) {
+  uint64_t act;
+  uint32_t done = 0u;
+  first = ~0u;
+  asm volatile("s_mov_b64 %[act], exec\n\t"
+      THEMIS_ENDS_NOW(0, 1) THEMIS_ENDS_NOW(1, 2) THEMIS_ENDS_NOW(2, 4)
+      "v_cmp_ne_u32_e32 vcc, 0, %[three]\n\t" "s_cbranch_vccnz .Lthree_dims_%=\n\t"
+      THEMIS_ENDS_NOW(3, 8) ".Lthree_dims_%=:\n\t" THEMIS_PAD1
+      : [act] "=&s"(act), [done] "+v"(done), [first] "+v"(first), THEMIS_F_OPERANDS
+      : [now] "v"(now), [nan] "v"(nan64()), [s0] "v"(d.s0), [s1] "v"(d.s1), [s2] "v"(d.s2),
+        [s3] "v"(d.s3), [three] "v"(three)
+      : "vcc");
+  return done;
 }
 
 // Bytes a stage moves when the NPU counts are not powers of two: the chunk's
@@ -385,19 +409,38 @@ __device__ __forceinline__ double trace_divided_bytes(const Scenario& s, double 
 // divide: NPU counts that are not powers of two; CH[q] then holds the plain
 // chunk bytes, every stage time comes from trace_divided_bytes() and the size
 // ranks of Smallest-Chunk-First from trace_build_ranks_divided().
-template <bool kLdsBitmaps, bool kReleases, bool kFix, bool kQueue>
+// kPlain: the caller has seen that every lane of the wavefront runs All-Reduces
+// under Smallest-Chunk-First on NPU counts that are powers of two (state0 = 0,
+// rs_only = divide = false, scf = true); the loop is compiled for that.
+template <bool kLdsBitmaps, bool kReleases, bool kFix, bool kQueue, bool kPlain>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
-                                           uint32_t state0, bool rs_only, bool scf, bool divide,
-                                           bool has_release,
+                                           uint32_t state0_given, bool rs_only_given, bool scf_given,
+                                           bool divide_given, bool has_release,
                                            const TraceRegion& rg, const LaneLds& lds,
                                            const SimOut& out, double& t_done,
                                            double (&busy)[kMaxDims],
                                            uint32_t (&executed_out)[kMaxDims]) {
+  const uint32_t state0 = kPlain ? 0u : state0_given;
+  const bool rs_only = kPlain ? false : rs_only_given;
+  const bool scf = kPlain ? true : scf_given;
+  const bool divide = kPlain ? false : divide_given;
   const uint32_t D = (uint32_t)s.D;
   const uint32_t C = s.C;
   const uint32_t G = Q * C;
   const uint32_t full = (1u << D) - 1u;
   const double kInf = inf64();
+  // no lane of the wavefront has a fourth dimension: its turns are left out
+  const uint32_t three = __builtin_amdgcn_ballot_w64(D > 3u) == 0ull ? 1u : 0u;
+  // The list entry of (dimension, rank), clamped like TraceRegion::HT, from
+  // local copies of the table's origin and size (read through the region, the
+  // compiler fetches them from the kernel arguments again inside the loop, and
+  // a lone wavefront waits for every such fetch).
+  const uint32_t ranks = rg.t.R, last_rank = rg.t.R - 1u;
+  uint32_t* const ht_origin = (uint32_t*)(rg.base + rg.t.off_ht);
+  auto ht_index = [&](uint32_t k, uint32_t r) -> uint32_t {
+    return __umul24(k & 3u, ranks) + min(r, last_rank);
+  };
+  auto HT = [&](uint32_t k, uint32_t r) -> uint32_t& { return ht_origin[ht_index(k, r)]; };
 
   if (scf) {
     if (divide) trace_build_ranks_divided(rg, s, Q, (state0 & 16u) != 0u, rs_only);
@@ -450,54 +493,88 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   // Memory operations of one wavefront retire in order, so waiting for a load
   // also waits for every store issued before it: push and pop read first and
   // store last (word: the chunk's new word, stored here for that reason).
+  // (a half of a chunk word, written in place: may alias the whole word)
+  typedef uint16_t __attribute__((may_alias)) HalfOfWord;
   auto push = [&](uint32_t k, uint32_t r, uint32_t g, bool has_word, uint32_t word) {
     const uint32_t leaf = r >> 5, bit = 1u << (r & 31u);
     const uint32_t lw = BM(k, leaf);
     if (lw & bit) {
-      const uint32_t ht = rg.HT(k, r);
+      const uint32_t ht = HT(k, r);
       const uint32_t tl = ht >> 16;
       if (has_word) rg.W(g) = word;
-      ((uint16_t*)&rg.W(tl))[1] = (uint16_t)g;  // the old tail's next field
-      rg.HT(k, r) = (ht & 0xffffu) | (g << 16);
+      ((HalfOfWord*)&rg.W(tl))[1] = (uint16_t)g;  // the old tail's next field
+      HT(k, r) = (ht & 0xffffu) | (g << 16);
     } else {
       if (has_word) rg.W(g) = word;
-      rg.HT(k, r) = g | (g << 16);
+      HT(k, r) = g | (g << 16);
       BM(k, leaf) = lw | bit;
       SUM(k, leaf >> 5) |= 1u << (leaf & 31u);
     }
     tops |= 1u << (4u * (k & 3u) + ((leaf >> 5) & 3u));
     work |= 1u << (k & 3u);
   };
-  // first chunk of the lowest non-empty rank (smallest resident size); w
-  // receives its chunk word, size the resident bytes of a chunk of that rank
-  // and row the size ranks of the chunk's collective.  The loads that do not
-  // depend on each other are issued together: list head and size of the rank,
-  // then chunk word and rank row, two round trips to memory instead of three.
-  // new_entry / at: the list's entry once its head is gone, for the caller to
-  // store (at = 4 * R: nothing to store, the list is empty now)
-  auto pop = [&](uint32_t k, uint32_t& w, double& size, uint4& row_lo, uint4& row_hi,
-                 uint32_t& new_entry, uint32_t& at) -> uint32_t {
-    // work bit k is set: one of k's summary words is not zero
-    const uint32_t sw = (uint32_t)__builtin_ctz(((tops >> (4u * k)) & 15u) | 16u) & 3u;
-    const uint32_t sumw = SUM(k, sw);
-    const uint32_t leaf = sw * 32u + ((uint32_t)__builtin_ctz(sumw | 0x80000000u));
+  // The two halves of a push for the caller that overlaps its list read with
+  // another one: the bitmap part (true: the rank's list has chunks already) ...
+  auto push_mark = [&](uint32_t k, uint32_t r) -> bool {
+    const uint32_t leaf = r >> 5, bit = 1u << (r & 31u);
     const uint32_t lw = BM(k, leaf);
-    const uint32_t r = leaf * 32u + ((uint32_t)__builtin_ctz(lw | 0x80000000u));
-    // (the rank table is read whatever the policy: a load nobody uses costs
-    // less here than a branch around it)
-    const uint32_t ht = rg.HT(k, r);
+    const bool had = (lw & bit) != 0u;
+    if (!had) {
+      BM(k, leaf) = lw | bit;
+      SUM(k, leaf >> 5) |= 1u << (leaf & 31u);
+    }
+    tops |= 1u << (4u * (k & 3u) + ((leaf >> 5) & 3u));
+    work |= 1u << (k & 3u);
+    return had;
+  };
+  // ... and the stores, given the list's entry as read before (ht, used when
+  // had); returns the entry it stored
+  auto push_link = [&](uint32_t k, uint32_t r, uint32_t g, uint32_t word, bool had, uint32_t ht) -> uint32_t {
+    rg.W(g) = word;
+    uint32_t entry = g | (g << 16);
+    if (had) {
+      ((HalfOfWord*)&rg.W(ht >> 16))[1] = (uint16_t)g;  // the old tail's next field
+      entry = (ht & 0xffffu) | (g << 16);
+    }
+    HT(k, r) = entry;
+    return entry;
+  };
+  // The lowest non-empty rank of dimension k (smallest resident size) and the
+  // bitmap words that lead to it.  Work bit k is set: one of k's summary words
+  // is not zero.
+  struct Pick { uint32_t r, leaf, lw, sw, sumw; };
+  auto pick = [&](uint32_t k) -> Pick {
+    Pick p;
+    p.sw = (uint32_t)__builtin_ctz(((tops >> (4u * k)) & 15u) | 16u) & 3u;
+    p.sumw = SUM(k, p.sw);
+    p.leaf = p.sw * 32u + ((uint32_t)__builtin_ctz(p.sumw | 0x80000000u));
+    p.lw = BM(k, p.leaf);
+    p.r = p.leaf * 32u + ((uint32_t)__builtin_ctz(p.lw | 0x80000000u));
+    return p;
+  };
+  // first chunk of the picked rank, given the rank's list entry ht; w
+  // receives its chunk word, size the resident bytes of a chunk of that rank
+  // and row the size ranks of the chunk's collective.  Chunk word and rank row
+  // are loaded together.
+  // new_entry / at: the list's entry once its head is gone, for the caller to
+  // store (at = all-ones: nothing to store, the list is empty now)
+  auto pop = [&](uint32_t k, const Pick& p, uint32_t ht, uint32_t& w, double& size, uint4& row_lo,
+                 uint4& row_hi, uint32_t& new_entry, uint32_t& at) -> uint32_t {
+    const uint32_t r = p.r, leaf = p.leaf, lw = p.lw, sw = p.sw, sumw = p.sumw;
     const uint32_t h = ht & 0xffffu, tl = ht >> 16;
     w = rg.W(h);
     const uint32_t q = coll_of(h);
+    // (the rank table is read whatever the policy: a load nobody uses costs
+    // less here than a branch around it)
     const uint4* row = rg.SRrow(q);
     row_lo = row[0];
-    row_hi = row[1];
+    if (!three) row_hi = row[1];  // (masks with the fourth dimension's bit)
     // the resident size from the chunk bytes of the collective, which sit in
     // the same 64 bytes as its rank row (the per-rank size table would be one
     // more line to fetch)
     size = rg.CH(q);
     if (!divide) size = scale_down(size, esum(epack, w & 15u));
-    at = 4u * rg.t.R;
+    at = ~0u;
     new_entry = 0u;
     if (h == tl) {
       const uint32_t nlw = lw & ~(1u << (r & 31u));
@@ -512,7 +589,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       }
     } else {
       new_entry = (w >> 16) | (tl << 16);
-      at = (k & 3u) * rg.t.R + min(r, rg.t.R - 1u);  // clamped as in HT()
+      at = ht_index(k, r);
     }
     return h;
   };
@@ -554,20 +631,34 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     }
   }
 
-  // One pass starts at most one stage and, once no idle dimension has chunks
-  // waiting, advances the clock (as in simulate_fast: a lane with two stages to
-  // start at one instant takes two passes, the other lanes of the wavefront go
-  // on meanwhile).
+  // One pass has three parts, and a wavefront waits for memory once in the
+  // first and once in the last, whatever its lanes are doing:
+  //   start   the stage picked by the previous pass starts (chunk word and
+  //           collective record are read here, the list entry is at hand);
+  //   advance once no idle dimension has chunks waiting and no completion of
+  //           the instant is left over, the clock moves to the earliest
+  //           completion (or release); one completion is delivered per pass,
+  //           lowest chunk id first;
+  //   pick    the next stage to start is chosen (none while completions of
+  //           the instant are left: all of them are delivered before any stage
+  //           starts), and its list entry is read together with the entry of
+  //           the list the completed chunk joins.
+  // A lane with two stages to start at one instant takes two passes, the other
+  // lanes of the wavefront go on meanwhile.
   const uint64_t max_steps = (uint64_t)4u * D * G + Q + 16u;
+  bool picked = false;
+  Pick pk = {0u, 0u, 0u, 0u, 0u};
+  uint32_t pk_k = 0u, pk_ht = 0u;
+  uint32_t done = 0u;  // stages that ended at this instant and are not delivered yet
   for (uint64_t step = 0; step <= max_steps; ++step) {
     // a7: an idle dimension with waiting chunks starts its first one
-    if (const uint32_t need = idle & work) {
-      const uint32_t k = (uint32_t)__builtin_ctz(need);
+    if (picked) {
+      const uint32_t k = pk_k;
       uint32_t w;
       double size;
       uint4 row_lo = {0u, 0u, 0u, 0u}, row_hi = {0u, 0u, 0u, 0u};
       uint32_t new_entry, entry_at;
-      const uint32_t h = pop(k, w, size, row_lo, row_hi, new_entry, entry_at);
+      const uint32_t h = pop(k, pk, pk_ht, w, size, row_lo, row_hi, new_entry, entry_at);
       const uint32_t mask = w & 15u, phase = (w >> 4) & 1u;
       const uint32_t ek = (epack >> (8u * k)) & 0xffu;
       // the chunk's state after this stage: a Reduce-Scatter sets the
@@ -596,47 +687,67 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
         const uint32_t place = ((uint32_t)__builtin_popcount(mask) - phase) & 3u;
         bytes = trace_divided_bytes(s, size, code, place, (state0 & 16u) != 0u);
       }
-      const double t = start_stage_trace<kQueue>(k, sv, nx, now, bytes, s.coef, s.fix, d, pos);
+      const double t = start_stage_trace<kQueue>(k, sv, nx, now, bytes, s.coef, s.fix, d, pos, three);
       const double fin = now + t;
       // a stage that does not move the clock, or overflows it: generic path decides
       stalled |= !(fin > now && fin < kInf);
       idle &= ~(1u << k);
       if (kQueue && out.queue_order && pos < 2u * out.slots) put_entry(out, (int)k, pos, (h << 1) | phase);
-      if (entry_at < 4u * rg.t.R) ((uint32_t*)(rg.base + rg.t.off_ht))[entry_at] = new_entry;
+      if (entry_at != ~0u) ht_origin[entry_at] = new_entry;
     }
     if (stalled) break;
-    if ((idle & work) != 0u) continue;  // all stages of an instant start before the clock moves
 
     // a8: advance to the earliest completion, or to the next release if that
     // comes first
-    const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));  // NaN: nothing runs
-    if (!kReleases) {
-      if (!(next < kInf)) break;
-    } else if (!(next < rel_time)) {
-      if (!(rel_time < kInf)) break;  // nothing running, nothing left to release
-      // chunks arriving at one instant from a release and from a completion
-      // would have to be merged by id: the generic path does that
-      if (rel_time == next) { stalled = true; break; }
-      now = rel_time;
-      release_due();
-      continue;
-    }
-    now = next;
-    // deliver all completions of this instant, lowest chunk id first: the
-    // smallest chunk << 2 | dimension among the dimensions that completed
-    uint32_t key;
-    uint32_t done = stages_ending(now, d, key);
-    idle |= done;
-    for (;;) {
-      const uint32_t k = key & 3u;
-      const uint32_t nx = sel4((int)k, d.n0, d.n1, d.n2, d.n3);
-      const uint32_t kn = (nx >> 16) & 7u;
-      if (kn < 4u) push(kn, nx >> 19, key >> 2, true, (nx & 0xffffu) | (kNoChunk << 16));
-      done &= ~(1u << k);
-      if (done == 0u) break;
-      // one more stage ends at this very instant (rare): the smallest one left
+    bool moves = false, had = false;
+    uint32_t kn = 0u, r = 0u, g = 0u, word = 0u;
+    // the smallest chunk << 2 | dimension among the stages that ended and are
+    // not delivered (rarely more than one at an instant)
+    uint32_t key = ~0u;
+    if (done != 0u)
       key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
                 min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
+    if (done == 0u && (idle & work) == 0u) {
+      const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));  // NaN: nothing runs
+      if (!kReleases) {
+        if (!(next < kInf)) break;
+        now = next;
+        done = trace_stages_ending(now, d, key, three);
+      } else if (!(next < rel_time)) {
+        if (!(rel_time < kInf)) break;  // nothing running, nothing left to release
+        // chunks arriving at one instant from a release and from a completion
+        // would have to be merged by id: the generic path does that
+        if (rel_time == next) { stalled = true; break; }
+        now = rel_time;
+        release_due();
+      } else {
+        now = next;
+        done = trace_stages_ending(now, d, key, three);
+      }
+      idle |= done;
+    }
+    if (done != 0u) {
+      const uint32_t k = key & 3u;
+      const uint32_t nx = sel4((int)k, d.n0, d.n1, d.n2, d.n3);
+      kn = (nx >> 16) & 7u;
+      r = nx >> 19;
+      g = key >> 2;
+      word = (nx & 0xffffu) | (kNoChunk << 16);
+      done &= ~(1u << k);
+      moves = kn < 4u;
+      had = moves && push_mark(kn, r);
+    }
+    // (both addresses are clamped into the table, so the loads need no branch
+    // around them)
+    const uint32_t need = done ? 0u : idle & work;
+    picked = need != 0u;
+    pk_k = picked ? (uint32_t)__builtin_ctz(need) : 0u;
+    if (picked) pk = pick(pk_k);
+    const uint32_t ht_to = HT(kn, r);
+    pk_ht = HT(pk_k, picked ? pk.r : 0u);
+    if (moves) {
+      const uint32_t entry = push_link(kn, r, g, word, had, ht_to);
+      if (pk_k == kn && pk.r == r) pk_ht = entry;  // the very list just appended to
     }
   }
 
