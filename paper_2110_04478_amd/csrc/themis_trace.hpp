@@ -635,21 +635,18 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   // first and once in the last, whatever its lanes are doing:
   //   start   the stage picked by the previous pass starts (chunk word and
   //           collective record are read here, the list entry is at hand);
-  //   advance once no idle dimension has chunks waiting and no completion of
-  //           the instant is left over, the clock moves to the earliest
-  //           completion (or release); one completion is delivered per pass,
-  //           lowest chunk id first;
-  //   pick    the next stage to start is chosen (none while completions of
-  //           the instant are left: all of them are delivered before any stage
-  //           starts), and its list entry is read together with the entry of
-  //           the list the completed chunk joins.
+  //   advance once no idle dimension has chunks waiting, the clock moves to
+  //           the earliest completion (or release) and the stages that end
+  //           there are delivered, lowest chunk id first;
+  //   pick    the next stage to start is chosen, and its list entry is read
+  //           together with the entry of the list the (last) completed chunk
+  //           joins.
   // A lane with two stages to start at one instant takes two passes, the other
   // lanes of the wavefront go on meanwhile.
   const uint64_t max_steps = (uint64_t)4u * D * G + Q + 16u;
   bool picked = false;
   Pick pk = {0u, 0u, 0u, 0u, 0u};
   uint32_t pk_k = 0u, pk_ht = 0u;
-  uint32_t done = 0u;  // stages that ended at this instant and are not delivered yet
   for (uint64_t step = 0; step <= max_steps; ++step) {
     // a7: an idle dimension with waiting chunks starts its first one
     if (picked) {
@@ -701,13 +698,10 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     // comes first
     bool moves = false, had = false;
     uint32_t kn = 0u, r = 0u, g = 0u, word = 0u;
-    // the smallest chunk << 2 | dimension among the stages that ended and are
-    // not delivered (rarely more than one at an instant)
-    uint32_t key = ~0u;
-    if (done != 0u)
-      key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
-                min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
-    if (done == 0u && (idle & work) == 0u) {
+    // the stages that end at the new instant, and the smallest
+    // chunk << 2 | dimension among them
+    uint32_t done = 0u, key = ~0u;
+    if ((idle & work) == 0u) {
       const double next = min_f64(min_f64(d.f0, d.f1), min_f64(d.f2, d.f3));  // NaN: nothing runs
       if (!kReleases) {
         if (!(next < kInf)) break;
@@ -726,6 +720,17 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       }
       idle |= done;
     }
+    // more than one stage ends at this very instant (rare): all but the last
+    // are delivered here, lowest chunk id first, each with a wait of its own
+    while ((done & (done - 1u)) != 0u) {
+      const uint32_t k = key & 3u;
+      const uint32_t nx = sel4((int)k, d.n0, d.n1, d.n2, d.n3);
+      if (((nx >> 16) & 7u) < 4u)
+        push((nx >> 16) & 7u, nx >> 19, key >> 2, true, (nx & 0xffffu) | (kNoChunk << 16));
+      done &= ~(1u << k);
+      key = min(min((done & 1u) ? d.s0 : ~0u, (done & 2u) ? d.s1 : ~0u),
+                min((done & 4u) ? d.s2 : ~0u, (done & 8u) ? d.s3 : ~0u));
+    }
     if (done != 0u) {
       const uint32_t k = key & 3u;
       const uint32_t nx = sel4((int)k, d.n0, d.n1, d.n2, d.n3);
@@ -733,13 +738,12 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       r = nx >> 19;
       g = key >> 2;
       word = (nx & 0xffffu) | (kNoChunk << 16);
-      done &= ~(1u << k);
       moves = kn < 4u;
       had = moves && push_mark(kn, r);
     }
     // (both addresses are clamped into the table, so the loads need no branch
     // around them)
-    const uint32_t need = done ? 0u : idle & work;
+    const uint32_t need = idle & work;
     picked = need != 0u;
     pk_k = picked ? (uint32_t)__builtin_ctz(need) : 0u;
     if (picked) pk = pick(pk_k);
