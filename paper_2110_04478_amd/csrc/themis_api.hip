@@ -696,14 +696,28 @@ simulate_trace_kernel(themis_batch_t b, const uint8_t* __restrict__ orders,
       lds.base = (uint8_t*)lds_block + 4u * threadIdx.x;
       double T, z[kMaxDims];
       uint32_t ex[kMaxDims];
-      // the common case gets a loop of its own when the whole wavefront is in it
-      const bool other = divide || !scf || fs0.rs_only || fs0.state0 != 0u;
-      const bool plain = __builtin_amdgcn_ballot_w64(other) == 0ull;
-      const bool done = plain
-          ? simulate_trace_fast<kLdsBitmaps, kExtras, kExtras, kExtras, true>(
-                s, Q, epack, fs0.state0, fs0.rs_only, scf, divide, has_release, rg, lds, out, T, z, ex)
-          : simulate_trace_fast<kLdsBitmaps, kExtras, kExtras, kExtras, false>(
-                s, Q, epack, fs0.state0, fs0.rs_only, scf, divide, has_release, rg, lds, out, T, z, ex);
+      // All-Reduces under one policy on one kind of NPU counts get a loop
+      // compiled for exactly that when the whole wavefront is in the case
+      const bool all_reduce = __builtin_amdgcn_ballot_w64(fs0.rs_only || fs0.state0 != 0u) == 0ull;
+      const uint64_t lanes_scf = __builtin_amdgcn_ballot_w64(scf);
+      const uint64_t lanes_divide = __builtin_amdgcn_ballot_w64(divide);
+      const uint64_t lanes = __builtin_amdgcn_ballot_w64(true);
+      int known = kTraceAnyLane;
+      if (all_reduce && (lanes_scf == 0ull || lanes_scf == lanes) &&
+          (lanes_divide == 0ull || lanes_divide == lanes))
+        known = (lanes_scf ? kTraceKnownScf : 0) | (lanes_divide ? kTraceKnownDivide : 0);
+      bool done;
+#define THEMIS_TRACE_RUN(KNOWN)                                                                  \
+  done = simulate_trace_fast<kLdsBitmaps, kExtras, kExtras, kExtras, KNOWN>(                     \
+      s, Q, epack, fs0.state0, fs0.rs_only, scf, divide, has_release, rg, lds, out, T, z, ex)
+      switch (known) {
+        case 0: THEMIS_TRACE_RUN(0); break;
+        case kTraceKnownScf: THEMIS_TRACE_RUN(kTraceKnownScf); break;
+        case kTraceKnownDivide: THEMIS_TRACE_RUN(kTraceKnownDivide); break;
+        case kTraceKnownScf | kTraceKnownDivide: THEMIS_TRACE_RUN(kTraceKnownScf | kTraceKnownDivide); break;
+        default: THEMIS_TRACE_RUN(kTraceAnyLane); break;
+      }
+#undef THEMIS_TRACE_RUN
       if (done) {
         t_done[i] = T;
         if (busy) {

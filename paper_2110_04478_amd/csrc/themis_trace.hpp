@@ -409,10 +409,12 @@ __device__ __forceinline__ double trace_divided_bytes(const Scenario& s, double 
 // divide: NPU counts that are not powers of two; CH[q] then holds the plain
 // chunk bytes, every stage time comes from trace_divided_bytes() and the size
 // ranks of Smallest-Chunk-First from trace_build_ranks_divided().
-// kPlain: the caller has seen that every lane of the wavefront runs All-Reduces
-// under Smallest-Chunk-First on NPU counts that are powers of two (state0 = 0,
-// rs_only = divide = false, scf = true); the loop is compiled for that.
-template <bool kLdsBitmaps, bool kReleases, bool kFix, bool kQueue, bool kPlain>
+// kKnown: what the caller has seen to hold for every lane of the wavefront,
+// so that the loop is compiled for it instead of testing per-lane flags
+// (kTraceAnyLane: nothing; else All-Reduces (state0 = 0, rs_only = false) with
+// scf and divide as the two bits say).
+enum : int { kTraceAnyLane = -1, kTraceKnownScf = 1, kTraceKnownDivide = 2 };
+template <bool kLdsBitmaps, bool kReleases, bool kFix, bool kQueue, int kKnown>
 __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32_t epack,
                                            uint32_t state0_given, bool rs_only_given, bool scf_given,
                                            bool divide_given, bool has_release,
@@ -420,10 +422,11 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
                                            const SimOut& out, double& t_done,
                                            double (&busy)[kMaxDims],
                                            uint32_t (&executed_out)[kMaxDims]) {
-  const uint32_t state0 = kPlain ? 0u : state0_given;
-  const bool rs_only = kPlain ? false : rs_only_given;
-  const bool scf = kPlain ? true : scf_given;
-  const bool divide = kPlain ? false : divide_given;
+  constexpr bool kAny = kKnown == kTraceAnyLane;
+  const uint32_t state0 = kAny ? state0_given : 0u;
+  const bool rs_only = kAny ? rs_only_given : false;
+  const bool scf = kAny ? scf_given : (kKnown & kTraceKnownScf) != 0;
+  const bool divide = kAny ? divide_given : (kKnown & kTraceKnownDivide) != 0;
   const uint32_t D = (uint32_t)s.D;
   const uint32_t C = s.C;
   const uint32_t G = Q * C;
