@@ -101,6 +101,11 @@ __device__ __forceinline__ bool nothing_marked(unsigned long long call) {
 template <bool kPerCollective>
 __global__ void __launch_bounds__(kBlock)
 plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__ loads) {
+  // the planner's order table, one entry per lane of the workgroup
+  static_assert(kBlock == kPlanOrders, "one table entry per lane");
+  __shared__ uint32_t plan_orders[kPlanOrders];
+  plan_orders[threadIdx.x] = plan_order_entry(threadIdx.x);
+  __syncthreads();
   const TraceView tv = trace_view(b);
   const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   const uint64_t i = kPerCollective ? e / tv.mc : e;
@@ -129,14 +134,14 @@ plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__
         FastScenario fs;
         if (fast_eligible(s, chunk, THEMIS_MAX_CHUNKS, fs)) {
           uint32_t acc = 0;
-          plan_fast(s, fs, themis_on, rel, thr, load, [&](uint32_t c, uint32_t code) {
+          plan_fast<true>(s, fs, themis_on, rel, thr, load, [&](uint32_t c, uint32_t code) {
             if (words) {
               acc |= code << (8u * (c & 3u));
               if ((c & 3u) == 3u) { ((uint32_t*)r)[c >> 2] = acc; acc = 0; }
             } else {
               r[c] = (uint8_t)code;
             }
-          });
+          }, plan_orders);
           if (words && (s.C & 3u)) {  // pad the last partial word with unused-slot marks
             acc |= 0xFFFFFFFFu << (8u * (s.C & 3u));
             ((uint32_t*)r)[s.C >> 2] = acc;

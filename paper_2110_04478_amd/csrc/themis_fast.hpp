@@ -233,10 +233,35 @@ __device__ __forceinline__ uint32_t factorial_u32(uint32_t D) {
 // Planner (Alg. 1) with static register indexing.  emit(c, code) receives
 // every chunk's order code; load[] holds the Dim Load Tracker on return.
 // ---------------------------------------------------------------------------
-template <typename Emit>
+// The ascending stable order of four loads is a function of the six
+// comparisons load[a] > load[b] (a < b).  One table entry per outcome
+// (bit 0: 0>1, 1: 0>2, 2: 0>3, 3: 1>2, 4: 1>3, 5: 2>3): the order code of four
+// dimensions in bits 0-7 and, for dimension k, the mask of the dimensions
+// that come before it in bits 8 + 4k .. 11 + 4k.
+constexpr uint32_t kPlanOrders = 64;
+__device__ __forceinline__ uint32_t plan_order_entry(uint32_t outcome) {
+  const bool after01 = (outcome & 1u) != 0u, after02 = (outcome & 2u) != 0u;
+  const bool after03 = (outcome & 4u) != 0u, after12 = (outcome & 8u) != 0u;
+  const bool after13 = (outcome & 16u) != 0u, after23 = (outcome & 32u) != 0u;
+  // rank of a dimension: how many come before it
+  const uint32_t r1 = (uint32_t)!after01 + after12 + after13;
+  const uint32_t r2 = (uint32_t)!after02 + !after12 + after23;
+  const uint32_t r3 = (uint32_t)!after03 + !after13 + !after23;
+  const uint32_t code = (1u << (2u * r1)) | (2u << (2u * r2)) | (3u << (2u * r3));
+  const uint32_t before0 = (after01 ? 2u : 0u) | (after02 ? 4u : 0u) | (after03 ? 8u : 0u);
+  const uint32_t before1 = (after01 ? 0u : 1u) | (after12 ? 4u : 0u) | (after13 ? 8u : 0u);
+  const uint32_t before2 = (after02 ? 0u : 1u) | (after12 ? 0u : 2u) | (after23 ? 8u : 0u);
+  const uint32_t before3 = (after03 ? 0u : 1u) | (after13 ? 0u : 2u) | (after23 ? 0u : 4u);
+  return (code & 0xffu) | (before0 << 8) | (before1 << 12) | (before2 << 16) | (before3 << 20);
+}
+
+// kTable: orders points to kPlanOrders entries of plan_order_entry() in LDS;
+// the order and the sizes then come from one table read instead of the
+// comparisons' arithmetic (the results are the same).
+template <bool kTable = false, typename Emit>
 __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario& fs, bool themis,
                                           bool rel, double thr, double (&load)[kMaxDims],
-                                          Emit emit) {
+                                          Emit emit, const uint32_t* orders = nullptr) {
   const int D = s.D;
   uint32_t e[kMaxDims];
   double coef[kMaxDims];
@@ -270,20 +295,31 @@ __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario&
     bool after01 = sort && load[0] > load[1], after02 = sort && load[0] > load[2];
     bool after03 = sort && load[0] > load[3], after12 = sort && load[1] > load[2];
     bool after13 = sort && load[1] > load[3], after23 = sort && load[2] > load[3];
-    // before[j][k]: j precedes k
-    const bool b10 = after01, b20 = after02, b30 = after03;
-    const bool b01 = !after01, b21 = after12, b31 = after13;
-    const bool b02 = !after02, b12 = !after12, b32 = after23;
-    const bool b03 = !after03, b13 = !after13, b23 = !after23;
-    uint32_t r0 = (uint32_t)b10 + b20 + b30, r1 = (uint32_t)b01 + b21 + b31;
-    uint32_t r2 = (uint32_t)b02 + b12 + b32, r3 = (uint32_t)b03 + b13 + b23;
-    uint32_t code = ((1u << (2 * r1)) | (2u << (2 * r2)) | (3u << (2 * r3))) & field_mask;
-    (void)r0;
-    // resident size before the Reduce-Scatter on k: chunk / prod of P_j, j before k
-    uint32_t E0 = (b10 ? e[1] : 0u) + (b20 ? e[2] : 0u) + (b30 ? e[3] : 0u);
-    uint32_t E1 = (b01 ? e[0] : 0u) + (b21 ? e[2] : 0u) + (b31 ? e[3] : 0u);
-    uint32_t E2 = (b02 ? e[0] : 0u) + (b12 ? e[1] : 0u) + (b32 ? e[3] : 0u);
-    uint32_t E3 = (b03 ? e[0] : 0u) + (b13 ? e[1] : 0u) + (b23 ? e[2] : 0u);
+    uint32_t code, E0, E1, E2, E3;
+    if (kTable) {
+      const uint32_t outcome = (after01 ? 1u : 0u) | (after02 ? 2u : 0u) | (after03 ? 4u : 0u) |
+                               (after12 ? 8u : 0u) | (after13 ? 16u : 0u) | (after23 ? 32u : 0u);
+      const uint32_t entry = orders[outcome];
+      code = entry & field_mask;
+      E0 = esum(fs.epack, (entry >> 8) & 15u);
+      E1 = esum(fs.epack, (entry >> 12) & 15u);
+      E2 = esum(fs.epack, (entry >> 16) & 15u);
+      E3 = esum(fs.epack, (entry >> 20) & 15u);
+    } else {
+      // before[j][k]: j precedes k
+      const bool b10 = after01, b20 = after02, b30 = after03;
+      const bool b01 = !after01, b21 = after12, b31 = after13;
+      const bool b02 = !after02, b12 = !after12, b32 = after23;
+      const bool b03 = !after03, b13 = !after13, b23 = !after23;
+      uint32_t r1 = (uint32_t)b01 + b21 + b31;
+      uint32_t r2 = (uint32_t)b02 + b12 + b32, r3 = (uint32_t)b03 + b13 + b23;
+      code = ((1u << (2 * r1)) | (2u << (2 * r2)) | (3u << (2 * r3))) & field_mask;
+      // resident size before the Reduce-Scatter on k: chunk / prod of P_j, j before k
+      E0 = (b10 ? e[1] : 0u) + (b20 ? e[2] : 0u) + (b30 ? e[3] : 0u);
+      E1 = (b01 ? e[0] : 0u) + (b21 ? e[2] : 0u) + (b31 ? e[3] : 0u);
+      E2 = (b02 ? e[0] : 0u) + (b12 ? e[1] : 0u) + (b32 ? e[3] : 0u);
+      E3 = (b03 ? e[0] : 0u) + (b13 ? e[1] : 0u) + (b23 ? e[2] : 0u);
+    }
     double t0, t1, t2, t3;
     if (fs.gather) {
       // the All-Gather visits the dimensions in the reverse order: the ones
