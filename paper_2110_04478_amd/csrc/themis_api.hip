@@ -103,8 +103,8 @@ __global__ void __launch_bounds__(kBlock)
 plan_kernel(themis_batch_t b, uint8_t* __restrict__ orders, double* __restrict__ loads) {
   // the planner's order table, one entry per lane of the workgroup
   static_assert(kBlock == kPlanOrders, "one table entry per lane");
-  __shared__ uint32_t plan_orders[kPlanOrders];
-  plan_orders[threadIdx.x] = plan_order_entry(threadIdx.x);
+  __shared__ __attribute__((aligned(16))) uint32_t plan_orders[kPlanOrders * kPlanOrderWords];
+  plan_order_entry(threadIdx.x, plan_orders + kPlanOrderWords * threadIdx.x);
   __syncthreads();
   const TraceView tv = trace_view(b);
   const uint64_t e = (uint64_t)blockIdx.x * kBlock + threadIdx.x;

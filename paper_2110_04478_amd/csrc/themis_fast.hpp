@@ -234,12 +234,14 @@ __device__ __forceinline__ uint32_t factorial_u32(uint32_t D) {
 // every chunk's order code; load[] holds the Dim Load Tracker on return.
 // ---------------------------------------------------------------------------
 // The ascending stable order of four loads is a function of the six
-// comparisons load[a] > load[b] (a < b).  One table entry per outcome
-// (bit 0: 0>1, 1: 0>2, 2: 0>3, 3: 1>2, 4: 1>3, 5: 2>3): the order code of four
-// dimensions in bits 0-7 and, for dimension k, the mask of the dimensions
-// that come before it in bits 8 + 4k .. 11 + 4k.
+// comparisons load[a] > load[b] (a < b).  One table entry of eight dwords per
+// outcome (bit 0: 0>1, 1: 0>2, 2: 0>3, 3: 1>2, 4: 1>3, 5: 2>3): dword k < 4
+// holds the dimensions that come before dimension k, dimension j as a one in
+// byte j (so that a byte-wise dot product with the packed exponents sums the
+// exponents of those dimensions); dword 4 the order code of four dimensions.
 constexpr uint32_t kPlanOrders = 64;
-__device__ __forceinline__ uint32_t plan_order_entry(uint32_t outcome) {
+constexpr uint32_t kPlanOrderWords = 8;
+__device__ __forceinline__ void plan_order_entry(uint32_t outcome, uint32_t* entry) {
   const bool after01 = (outcome & 1u) != 0u, after02 = (outcome & 2u) != 0u;
   const bool after03 = (outcome & 4u) != 0u, after12 = (outcome & 8u) != 0u;
   const bool after13 = (outcome & 16u) != 0u, after23 = (outcome & 32u) != 0u;
@@ -247,15 +249,16 @@ __device__ __forceinline__ uint32_t plan_order_entry(uint32_t outcome) {
   const uint32_t r1 = (uint32_t)!after01 + after12 + after13;
   const uint32_t r2 = (uint32_t)!after02 + !after12 + after23;
   const uint32_t r3 = (uint32_t)!after03 + !after13 + !after23;
-  const uint32_t code = (1u << (2u * r1)) | (2u << (2u * r2)) | (3u << (2u * r3));
-  const uint32_t before0 = (after01 ? 2u : 0u) | (after02 ? 4u : 0u) | (after03 ? 8u : 0u);
-  const uint32_t before1 = (after01 ? 0u : 1u) | (after12 ? 4u : 0u) | (after13 ? 8u : 0u);
-  const uint32_t before2 = (after02 ? 0u : 1u) | (after12 ? 0u : 2u) | (after23 ? 8u : 0u);
-  const uint32_t before3 = (after03 ? 0u : 1u) | (after13 ? 0u : 2u) | (after23 ? 0u : 4u);
-  return (code & 0xffu) | (before0 << 8) | (before1 << 12) | (before2 << 16) | (before3 << 20);
+  entry[0] = (after01 ? 0x100u : 0u) | (after02 ? 0x10000u : 0u) | (after03 ? 0x1000000u : 0u);
+  entry[1] = (after01 ? 0u : 1u) | (after12 ? 0x10000u : 0u) | (after13 ? 0x1000000u : 0u);
+  entry[2] = (after02 ? 0u : 1u) | (after12 ? 0u : 0x100u) | (after23 ? 0x1000000u : 0u);
+  entry[3] = (after03 ? 0u : 1u) | (after13 ? 0u : 0x100u) | (after23 ? 0u : 0x10000u);
+  entry[4] = ((1u << (2u * r1)) | (2u << (2u * r2)) | (3u << (2u * r3))) & 0xffu;
+  entry[5] = entry[6] = entry[7] = 0u;
 }
 
-// kTable: orders points to kPlanOrders entries of plan_order_entry() in LDS;
+// kTable: orders points to kPlanOrders entries of plan_order_entry() in LDS
+// (16-byte aligned);
 // the order and the sizes then come from one table read instead of the
 // comparisons' arithmetic (the results are the same).
 template <bool kTable = false, typename Emit>
@@ -299,12 +302,13 @@ __device__ __forceinline__ void plan_fast(const Scenario& s, const FastScenario&
     if (kTable) {
       const uint32_t outcome = (after01 ? 1u : 0u) | (after02 ? 2u : 0u) | (after03 ? 4u : 0u) |
                                (after12 ? 8u : 0u) | (after13 ? 16u : 0u) | (after23 ? 32u : 0u);
-      const uint32_t entry = orders[outcome];
-      code = entry & field_mask;
-      E0 = esum(fs.epack, (entry >> 8) & 15u);
-      E1 = esum(fs.epack, (entry >> 12) & 15u);
-      E2 = esum(fs.epack, (entry >> 16) & 15u);
-      E3 = esum(fs.epack, (entry >> 20) & 15u);
+      const uint32_t* entry = orders + kPlanOrderWords * outcome;
+      const uint4 before = *(const uint4*)entry;
+      code = entry[4] & field_mask;
+      E0 = __builtin_amdgcn_udot4(before.x, fs.epack, 0u, false);
+      E1 = __builtin_amdgcn_udot4(before.y, fs.epack, 0u, false);
+      E2 = __builtin_amdgcn_udot4(before.z, fs.epack, 0u, false);
+      E3 = __builtin_amdgcn_udot4(before.w, fs.epack, 0u, false);
     } else {
       // before[j][k]: j precedes k
       const bool b10 = after01, b20 = after02, b30 = after03;
