@@ -296,7 +296,8 @@ def extras_workload(args, np, torch, binding, workloads):
     # best threshold of a sweep
     thr = torch.from_numpy(workloads.CONFIG4_THRESHOLDS).to(dev)
     sweep = binding.themis_sweep(d0, thr, 7)
-    timed("sweep: 8 thresholds x 3 schedulers (evaluations/s)", n * 24.0,
+    timed("sweep: 8 thresholds x 3 schedulers (results/s; 17 simulations per scenario, "
+          "the baseline's once)", n * 24.0,
           lambda: binding.themis_sweep(d0, thr, 7, t_done=sweep))
     timed("sweep_best", n, lambda: binding.themis_sweep_best(sweep, 0))
     best_t, best_thr, speedup = binding.themis_sweep_best(sweep, 0)

@@ -288,7 +288,9 @@ int themis_simulate_batch_noalloc(const themis_batch_t *batch, const uint8_t *or
  *                per scenario ([n_thr][n], thr_per_scenario != 0).
  *   t_done     : [n][n_thr][n_pol], n_pol = popcount(policy_mask), schedulers
  *                in ascending bit order.  THEMIS_SWEEP_BASELINE ignores the
- *                threshold (its value repeats along n_thr).
+ *                threshold: it is simulated once per scenario and its value
+ *                repeats along n_thr (NaN under a threshold that is itself
+ *                not valid, as in the other columns).
  */
 int themis_sweep(const themis_batch_t *batch, int n_thr, const double *thr,
                  int thr_per_scenario, unsigned policy_mask, double *t_done,

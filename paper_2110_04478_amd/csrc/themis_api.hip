@@ -791,6 +791,47 @@ __device__ __forceinline__ SweepItem sweep_item(const themis_batch_t& b, uint64_
   return it;
 }
 
+// The baseline order does not look at Alg. 1's threshold, so its column of a
+// sweep needs one simulation per scenario, under the first threshold; the
+// result is stored under every threshold.  A group of scenarios therefore has
+// one workgroup per (threshold, scheduler) pair except the baseline's pairs
+// beyond the first threshold: sweep_roles() of them.
+__host__ __device__ __forceinline__ uint32_t sweep_roles(uint32_t n_thr, uint32_t n_pol,
+                                                         unsigned policy_mask) {
+  return n_thr * n_pol - ((policy_mask & THEMIS_SWEEP_BASELINE) ? n_thr - 1u : 0u);
+}
+// The pair a workgroup takes, as threshold * n_pol + column: the roles in turn,
+// starting one further with every group (consecutive workgroups go to
+// consecutive XCDs, and the number of roles is often a multiple of the eight
+// XCDs: without the shift every XCD would see the same schedulers for every
+// group, and they differ in cost).  Every workgroup of the grid has work, so
+// the XCDs fill evenly -- workgroups are handed out in order, and a grid in
+// which every eighth one returns at once keeps an eighth of the GPU idle.
+__device__ __forceinline__ uint32_t sweep_block_role(uint32_t block, uint32_t n_thr, uint32_t n_pol,
+                                                     unsigned policy_mask) {
+  const uint32_t roles = sweep_roles(n_thr, n_pol, policy_mask);
+  const uint32_t group = block / roles;
+  const uint32_t r = (block - group * roles + group) % roles;
+  if (!(policy_mask & THEMIS_SWEEP_BASELINE) || r < n_pol) return r;
+  const uint32_t beyond = r - n_pol, others = n_pol - 1u;   // (others >= 1: r >= n_pol exists)
+  return (1u + beyond / others) * n_pol + 1u + beyond % others;
+}
+
+// Stores the baseline's result under every threshold (NaN where that
+// threshold itself is not valid).  e: the evaluation of the first threshold.
+__device__ __forceinline__ void sweep_store_for_all_thresholds(
+    const themis_batch_t& b, uint64_t i, uint64_t e, int n_thr, const double* thr,
+    int thr_per_scenario, int n_pol, bool rel, double* t_done, double value,
+    unsigned long long hand_over) {
+  for (int a = 0; a < n_thr; ++a) {
+    const double th = thr_per_scenario ? thr[(size_t)a * b.n + i] : thr[a];
+    double* at = t_done + e + (uint64_t)a * (uint64_t)n_pol;
+    if (!threshold_ok(th, rel)) *at = nan64();
+    else if (hand_over) mark_left_to_generic(at, hand_over);
+    else *at = value;
+  }
+}
+
 template <typename L, bool kFix>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
 sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
@@ -801,17 +842,27 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
   // scheduler: its lanes read consecutive inputs, and on a batch that keeps to
   // one network they all take the same path through the event loop.
   const uint32_t per = (uint32_t)n_thr * (uint32_t)n_pol;   // evaluations per scenario
-  const uint64_t i = (uint64_t)(blockIdx.x / per) * kBlock + threadIdx.x;
+  const uint32_t roles = sweep_roles((uint32_t)n_thr, (uint32_t)n_pol, policy_mask);
+  const uint64_t i = (uint64_t)(blockIdx.x / roles) * kBlock + threadIdx.x;
   if (i >= b.n) return;
-  const uint64_t e = i * per + blockIdx.x % per;
+  const uint64_t e = i * per + sweep_block_role(blockIdx.x, (uint32_t)n_thr, (uint32_t)n_pol, policy_mask);
   const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
+  const bool every_threshold = !it.themis_on;   // (the same for the whole wavefront)
 
   Scenario s = load_scenario(b, it.i);
   s.ctype = THEMIS_COLL_ALL_REDUCE;  // sweeps evaluate All-Reduce only
   const bool rel = b.threshold_mode == THEMIS_THR_REL;
   const double S = b.size_bytes[it.i];
-  bool ok = s.valid && finite_positive(S) && threshold_ok(it.th, rel);
-  if (!ok) { t_done[e] = nan64(); return; }
+  const bool input_ok = s.valid && finite_positive(S);
+  if (every_threshold) {
+    if (!input_ok) {
+      for (int a = 0; a < n_thr; ++a) t_done[e + (uint64_t)a * (uint64_t)n_pol] = nan64();
+      return;
+    }
+  } else if (!(input_ok && threshold_ok(it.th, rel))) {
+    t_done[e] = nan64();
+    return;
+  }
 
   const double chunk = S / (double)s.C;
   FastScenario fs;
@@ -826,9 +877,18 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
     // times only
     FastResult r =
         simulate_pow2<L, kNoQueueOrder, false, kFix>(s, Pow2Model(s, fs, it.scf), lds, fo);
-    if (r.ok) { t_done[e] = r.t_done; return; }
+    if (r.ok) {
+      if (every_threshold)
+        sweep_store_for_all_thresholds(b, it.i, e, n_thr, thr, thr_per_scenario, n_pol, rel, t_done,
+                                       r.t_done, 0ull);
+      else t_done[e] = r.t_done;
+      return;
+    }
   }
-  if (hand_over) mark_left_to_generic(t_done + e, hand_over);
+  if (every_threshold)
+    sweep_store_for_all_thresholds(b, it.i, e, n_thr, thr, thr_per_scenario, n_pol, rel, t_done,
+                                   nan64(), hand_over);
+  else if (hand_over) mark_left_to_generic(t_done + e, hand_over);
   else t_done[e] = nan64();
 }
 
@@ -842,19 +902,22 @@ sweep_quad_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, i
   using L = LayoutQuad;
   __shared__ uint32_t lds_block[L::kBlockWords];
   const uint32_t per = (uint32_t)n_thr * (uint32_t)n_pol;   // evaluations per scenario
+  const uint32_t roles = sweep_roles((uint32_t)n_thr, (uint32_t)n_pol, policy_mask);
   const uint32_t quad = threadIdx.x >> 2;
-  const uint64_t i = (uint64_t)(blockIdx.x / per) * L::kQuads + quad;
+  const uint64_t i = (uint64_t)(blockIdx.x / roles) * L::kQuads + quad;
   // a quad without a scenario stays: the wavefront leaves the event loop as a whole
   const bool exists = i < b.n;
-  const uint64_t e = (exists ? i : 0u) * per + blockIdx.x % per;
+  const uint64_t e = (exists ? i : 0u) * per +
+                     sweep_block_role(blockIdx.x, (uint32_t)n_thr, (uint32_t)n_pol, policy_mask);
   const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
   const bool writer = exists && (threadIdx.x & 3u) == 0u;   // one lane of the quad stores the result
+  const bool every_threshold = !it.themis_on;   // (the same for the whole wavefront)
 
   Scenario s = load_scenario(b, it.i);
   s.ctype = THEMIS_COLL_ALL_REDUCE;  // sweeps evaluate All-Reduce only
   const bool rel = b.threshold_mode == THEMIS_THR_REL;
   const double S = b.size_bytes[it.i];
-  const bool ok = s.valid && finite_positive(S) && threshold_ok(it.th, rel);
+  const bool ok = s.valid && finite_positive(S) && (every_threshold || threshold_ok(it.th, rel));
   const double chunk = S / (double)s.C;
   FastScenario fs;
   const bool eligible = fast_eligible(s, chunk, L::kCap, fs);
@@ -873,6 +936,16 @@ sweep_quad_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, i
   __builtin_amdgcn_wave_barrier();
   const QuadResult r = simulate_quad<kFix>(s, Pow2Model(s, fs, it.scf), base, fast);
   if (!writer) return;
+  if (every_threshold) {
+    if (!ok) {
+      for (int a = 0; a < n_thr; ++a) t_done[e + (uint64_t)a * (uint64_t)n_pol] = nan64();
+    } else {
+      const bool have = fast && r.ok;
+      sweep_store_for_all_thresholds(b, it.i, e, n_thr, thr, thr_per_scenario, n_pol, rel, t_done,
+                                     have ? r.t_done : nan64(), have ? 0ull : hand_over);
+    }
+    return;
+  }
   if (!ok) t_done[e] = nan64();
   else if (fast && r.ok) t_done[e] = r.t_done;
   else if (hand_over) mark_left_to_generic(t_done + e, hand_over);
@@ -1716,15 +1789,16 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
                             : (fix ? sweep_kernel<LayoutPacked<512>, true> : sweep_kernel<LayoutPacked<512>, false>);
   const unsigned long long call = next_call_number();
   Launcher go(stream);
+  // (one workgroup per group of scenarios and pair, the baseline once: see sweep_roles)
+  const unsigned roles = sweep_roles((uint32_t)n_thr, (uint32_t)n_pol, policy_mask);
   if (sweep_mapping_is_quad(cap)) {
     const uint64_t groups = (batch->n + LayoutQuad::kQuads - 1u) / LayoutQuad::kQuads;
     if (groups * (uint64_t)(n_thr * n_pol) > 0x7fffffffull) return THEMIS_ERR_UNSUPPORTED;
-    go(fix ? sweep_quad_kernel<true> : sweep_quad_kernel<false>,
-       (unsigned)groups * (unsigned)(n_thr * n_pol), kBlock, *batch, n_thr, thr, thr_per_scenario,
-       policy_mask, n_pol, t_done, call);
+    go(fix ? sweep_quad_kernel<true> : sweep_quad_kernel<false>, (unsigned)groups * roles, kBlock,
+       *batch, n_thr, thr, thr_per_scenario, policy_mask, n_pol, t_done, call);
   } else {
-    go(kernel, blocks_for(batch->n) * (unsigned)(n_thr * n_pol), kBlock, *batch, n_thr, thr,
-       thr_per_scenario, policy_mask, n_pol, t_done, call);
+    go(kernel, blocks_for(batch->n) * roles, kBlock, *batch, n_thr, thr, thr_per_scenario,
+       policy_mask, n_pol, t_done, call);
   }
   // the follow-up passes, in one launch where themis_simulate_batch does the same
   const unsigned fb = follow_up_blocks(evals);

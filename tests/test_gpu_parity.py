@@ -531,6 +531,27 @@ def test_sweep_matches_oracle(gpu, oracle):
     got = gpu.themis_sweep(d, torch.from_numpy(thr).cuda(), 6, thr_per_scenario=True, workspace=ws)
     torch.cuda.synchronize()
     assert_close("sweep t_done (per-scenario thr)", got.cpu().numpy(), want)
+    # The baseline column is the same under every threshold (Alg. 1 looks at the
+    # threshold only when Themis is on) and NaN exactly where the threshold
+    # itself is not valid, whatever the first threshold is.
+    for b in (W.config3(n=200), W.mixed(333, seed=33, max_chunks=512, pow2=False)):
+        n = b.n
+        for thr, per_scenario in ((np.array([1 / 16, -1.0, 0.5, float("nan")]), False),
+                                  (np.array([-1.0, 0.25]), False),
+                                  (np.where(np.random.default_rng(2).random((3, n)) < 0.3, -1.0, 0.1), True)):
+            thr = np.ascontiguousarray(thr, dtype=np.float64)
+            want = oracle.sweep(b, thr, 7, thr_per_scenario=per_scenario, threads=8)
+            d = gpu.to_device(b)
+            ws = gpu.alloc_workspace(gpu.themis_workspace_bytes(d.n * len(thr) * 3, d.max_chunks))
+            got = gpu.themis_sweep(d, torch.from_numpy(thr).cuda(), 7,
+                                   thr_per_scenario=per_scenario, workspace=ws)
+            torch.cuda.synchronize()
+            got = got.cpu().numpy()
+            assert_close("sweep with thresholds that are not valid", got, want)
+            base = got[:, :, 0]
+            ok = ~np.isnan(base)
+            first = np.where(ok.any(axis=1), base[np.arange(n), ok.argmax(axis=1)], np.nan)
+            assert np.array_equal(np.where(ok, base, 0.0), np.where(ok, first[:, None], 0.0))
 
 
 def test_sweep_best_matches_oracle(gpu, oracle):
