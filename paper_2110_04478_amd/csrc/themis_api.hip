@@ -832,7 +832,9 @@ __device__ __forceinline__ void sweep_store_for_all_thresholds(
   }
 }
 
-template <typename L, bool kFix>
+// kBaseline: the sweep has a baseline column (compiled apart: what that
+// column keeps alive across the event loop costs the other columns time).
+template <typename L, bool kFix, bool kBaseline>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(L::kWavesPerSimd)))
 sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
              unsigned policy_mask, int n_pol, double* __restrict__ t_done,
@@ -847,7 +849,7 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
   if (i >= b.n) return;
   const uint64_t e = i * per + sweep_block_role(blockIdx.x, (uint32_t)n_thr, (uint32_t)n_pol, policy_mask);
   const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
-  const bool every_threshold = !it.themis_on;   // (the same for the whole wavefront)
+  const bool every_threshold = kBaseline && !it.themis_on;   // (the same for the whole wavefront)
 
   Scenario s = load_scenario(b, it.i);
   s.ctype = THEMIS_COLL_ALL_REDUCE;  // sweeps evaluate All-Reduce only
@@ -894,7 +896,7 @@ sweep_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int th
 
 // The same with four lanes per evaluation (themis_quad.hpp): a wavefront takes
 // 16 consecutive scenarios under one threshold and one scheduler.
-template <bool kFix>
+template <bool kFix, bool kBaseline>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(LayoutQuad::kWavesPerSimd)))
 sweep_quad_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, int thr_per_scenario,
                   unsigned policy_mask, int n_pol, double* __restrict__ t_done,
@@ -911,7 +913,7 @@ sweep_quad_kernel(themis_batch_t b, int n_thr, const double* __restrict__ thr, i
                      sweep_block_role(blockIdx.x, (uint32_t)n_thr, (uint32_t)n_pol, policy_mask);
   const SweepItem it = sweep_item(b, e, n_thr, thr, thr_per_scenario, policy_mask, n_pol);
   const bool writer = exists && (threadIdx.x & 3u) == 0u;   // one lane of the quad stores the result
-  const bool every_threshold = !it.themis_on;   // (the same for the whole wavefront)
+  const bool every_threshold = kBaseline && !it.themis_on;   // (the same for the whole wavefront)
 
   Scenario s = load_scenario(b, it.i);
   s.ctype = THEMIS_COLL_ALL_REDUCE;  // sweeps evaluate All-Reduce only
@@ -1782,11 +1784,18 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   Workspace w = carve_workspace(workspace, evals, batch->max_chunks);
   const uint32_t cap = layout_capacity(batch->max_chunks);
   const bool fix = batch->fixed_delay != nullptr;
-  auto kernel = cap == 16u ? (fix ? sweep_kernel<Layout16, true> : sweep_kernel<Layout16, false>)
-              : cap == 64u ? (fix ? sweep_kernel<LayoutRing, true> : sweep_kernel<LayoutRing, false>)
-              : cap == 128u ? (fix ? sweep_kernel<Layout128, true> : sweep_kernel<Layout128, false>)
-              : cap == 256u ? (fix ? sweep_kernel<LayoutPacked<256>, true> : sweep_kernel<LayoutPacked<256>, false>)
-                            : (fix ? sweep_kernel<LayoutPacked<512>, true> : sweep_kernel<LayoutPacked<512>, false>);
+  const bool base = (policy_mask & THEMIS_SWEEP_BASELINE) != 0u;
+#define THEMIS_SWEEP_KERNEL(L)                                                          \
+  (fix ? (base ? sweep_kernel<L, true, true> : sweep_kernel<L, true, false>)            \
+       : (base ? sweep_kernel<L, false, true> : sweep_kernel<L, false, false>))
+  auto kernel = cap == 16u ? THEMIS_SWEEP_KERNEL(Layout16)
+              : cap == 64u ? THEMIS_SWEEP_KERNEL(LayoutRing)
+              : cap == 128u ? THEMIS_SWEEP_KERNEL(Layout128)
+              : cap == 256u ? THEMIS_SWEEP_KERNEL(LayoutPacked<256>)
+                            : THEMIS_SWEEP_KERNEL(LayoutPacked<512>);
+#undef THEMIS_SWEEP_KERNEL
+  auto quad_kernel = fix ? (base ? sweep_quad_kernel<true, true> : sweep_quad_kernel<true, false>)
+                         : (base ? sweep_quad_kernel<false, true> : sweep_quad_kernel<false, false>);
   const unsigned long long call = next_call_number();
   Launcher go(stream);
   // (one workgroup per group of scenarios and pair, the baseline once: see sweep_roles)
@@ -1794,7 +1803,7 @@ int themis_sweep(const themis_batch_t* batch, int n_thr, const double* thr, int 
   if (sweep_mapping_is_quad(cap)) {
     const uint64_t groups = (batch->n + LayoutQuad::kQuads - 1u) / LayoutQuad::kQuads;
     if (groups * (uint64_t)(n_thr * n_pol) > 0x7fffffffull) return THEMIS_ERR_UNSUPPORTED;
-    go(fix ? sweep_quad_kernel<true> : sweep_quad_kernel<false>, (unsigned)groups * roles, kBlock,
+    go(quad_kernel, (unsigned)groups * roles, kBlock,
        *batch, n_thr, thr, thr_per_scenario, policy_mask, n_pol, t_done, call);
   } else {
     go(kernel, blocks_for(batch->n) * roles, kBlock, *batch, n_thr, thr, thr_per_scenario,
