@@ -86,9 +86,11 @@ struct TraceRegion {
   __device__ __forceinline__ uint16_t& SR(uint32_t q, uint32_t mask) const {
     return ((uint16_t*)(base + t.off_col + min(q, t.Q - 1u) * kTraceCollBytes))[mask & 15u];
   }
-  // the 16 ranks of collective q as eight dwords
-  __device__ __forceinline__ const uint4* SRrow(uint32_t q) const {
-    return (const uint4*)(base + t.off_col + min(q, t.Q - 1u) * kTraceCollBytes);
+  // the 16 ranks of collective q as eight dwords (read as whole dwords what
+  // SR() wrote as halves: the type says that it may alias them)
+  typedef uint4 __attribute__((may_alias)) RankRow;
+  __device__ __forceinline__ const RankRow* SRrow(uint32_t q) const {
+    return (const RankRow*)(base + t.off_col + min(q, t.Q - 1u) * kTraceCollBytes);
   }
   __device__ __forceinline__ uint16_t& SQ(uint32_t j) const {
     return ((uint16_t*)(base + t.off_sq))[min(j, t.Q - 1u)];
@@ -569,7 +571,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     const uint32_t q = coll_of(h);
     // (the rank table is read whatever the policy: a load nobody uses costs
     // less here than a branch around it)
-    const uint4* row = rg.SRrow(q);
+    const TraceRegion::RankRow* row = rg.SRrow(q);
     row_lo = row[0];
     if (!three) row_hi = row[1];  // (masks with the fourth dimension's bit)
     // the resident size from the chunk bytes of the collective, which sit in
