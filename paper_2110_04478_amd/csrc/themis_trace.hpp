@@ -518,21 +518,8 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     tops |= 1u << (4u * (k & 3u) + ((leaf >> 5) & 3u));
     work |= 1u << (k & 3u);
   };
-  // The two halves of a push for the caller that overlaps its list read with
-  // another one: the bitmap part (true: the rank's list has chunks already) ...
-  auto push_mark = [&](uint32_t k, uint32_t r) -> bool {
-    const uint32_t leaf = r >> 5, bit = 1u << (r & 31u);
-    const uint32_t lw = BM(k, leaf);
-    const bool had = (lw & bit) != 0u;
-    if (!had) {
-      BM(k, leaf) = lw | bit;
-      SUM(k, leaf >> 5) |= 1u << (leaf & 31u);
-    }
-    tops |= 1u << (4u * (k & 3u) + ((leaf >> 5) & 3u));
-    work |= 1u << (k & 3u);
-    return had;
-  };
-  // ... and the stores, given the list's entry as read before (ht, used when
+  // The stores of a push whose bitmap part the caller has done (had: the
+  // rank's list had chunks already), given the list's entry as read before (ht, used when
   // had); returns the entry it stored
   auto push_link = [&](uint32_t k, uint32_t r, uint32_t g, uint32_t word, bool had, uint32_t ht) -> uint32_t {
     rg.W(g) = word;
@@ -544,19 +531,9 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     HT(k, r) = entry;
     return entry;
   };
-  // The lowest non-empty rank of dimension k (smallest resident size) and the
-  // bitmap words that lead to it.  Work bit k is set: one of k's summary words
-  // is not zero.
+  // The lowest non-empty rank of a dimension (smallest resident size) and the
+  // bitmap words that lead to it.
   struct Pick { uint32_t r, leaf, lw, sw, sumw; };
-  auto pick = [&](uint32_t k) -> Pick {
-    Pick p;
-    p.sw = (uint32_t)__builtin_ctz(((tops >> (4u * k)) & 15u) | 16u) & 3u;
-    p.sumw = SUM(k, p.sw);
-    p.leaf = p.sw * 32u + ((uint32_t)__builtin_ctz(p.sumw | 0x80000000u));
-    p.lw = BM(k, p.leaf);
-    p.r = p.leaf * 32u + ((uint32_t)__builtin_ctz(p.lw | 0x80000000u));
-    return p;
-  };
   // first chunk of the picked rank, given the rank's list entry ht; w
   // receives its chunk word, size the resident bytes of a chunk of that rank
   // and row the size ranks of the chunk's collective.  Chunk word and rank row
@@ -744,14 +721,41 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       g = key >> 2;
       word = (nx & 0xffffu) | (kNoChunk << 16);
       moves = kn < 4u;
-      had = moves && push_mark(kn, r);
     }
-    // (both addresses are clamped into the table, so the loads need no branch
-    // around them)
-    const uint32_t need = idle & work;
-    picked = need != 0u;
-    pk_k = picked ? (uint32_t)__builtin_ctz(need) : 0u;
-    if (picked) pk = pick(pk_k);
+    // The bitmap work of the push and of the pick, with the reads that do not
+    // depend on each other issued together: the leaf word and the summary word
+    // of the push's rank and the summary word the pick starts from, then the
+    // pick's leaf word (two LDS round trips where one after the other they
+    // take four).
+    {
+      const uint32_t leaf_r = r >> 5, bit_r = 1u << (r & 31u), sw_r = (leaf_r >> 5) & 3u;
+      const uint32_t in_sum_r = 1u << (leaf_r & 31u);
+      if (moves) {
+        tops |= 1u << (4u * kn + sw_r);
+        work |= 1u << kn;
+      }
+      const uint32_t need = idle & work;
+      picked = need != 0u;
+      pk_k = picked ? (uint32_t)__builtin_ctz(need) : 0u;
+      const uint32_t sw2 = (uint32_t)__builtin_ctz(((tops >> (4u * pk_k)) & 15u) | 16u) & 3u;
+      const uint32_t lw_r = BM(kn, leaf_r);
+      const uint32_t sum_r = SUM(kn, sw_r);
+      uint32_t sumw2 = SUM(pk_k, sw2);
+      had = moves && (lw_r & bit_r) != 0u;
+      if (moves && !had) {
+        BM(kn, leaf_r) = lw_r | bit_r;
+        SUM(kn, sw_r) = sum_r | in_sum_r;
+        // (the pick's summary word was read before this store)
+        if (kn == pk_k && sw_r == sw2) sumw2 |= in_sum_r;
+      }
+      if (picked) {
+        pk.sw = sw2;
+        pk.sumw = sumw2;
+        pk.leaf = sw2 * 32u + ((uint32_t)__builtin_ctz(sumw2 | 0x80000000u));
+        pk.lw = BM(pk_k, pk.leaf);   // (after the store above: LDS operations keep their order)
+        pk.r = pk.leaf * 32u + ((uint32_t)__builtin_ctz(pk.lw | 0x80000000u));
+      }
+    }
     const uint32_t ht_to = HT(kn, r);
     pk_ht = HT(pk_k, picked ? pk.r : 0u);
     if (moves) {
