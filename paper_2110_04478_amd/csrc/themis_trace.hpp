@@ -296,8 +296,9 @@ __device__ inline void trace_build_ranks_divided(const TraceRegion& rg, const Sc
 // followed by the bitmap leaves of all four dimensions.  The large variant
 // (132 KiB per wavefront, one wavefront per CU) is for batches of no more
 // wavefronts than CUs, where nothing else could have used the LDS anyway.
-constexpr uint32_t kTraceLdsWords = 48;
-constexpr uint32_t kTraceLdsWordsBitmaps = 16 + 4 * kTraceLeafWords;
+// (the last four dwords: per dimension the lowest non-empty rank)
+constexpr uint32_t kTraceLdsWords = 48 + 4;
+constexpr uint32_t kTraceLdsWordsBitmaps = 16 + 4 * kTraceLeafWords + 4;
 
 // Runs the simulation of one trace.  The region must hold CH[q] (resident
 // bytes at mask 0 of a chunk of collective q), REL[q] (its release time; read
@@ -460,9 +461,17 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       return *(uint32_t*)lds.dword(16u + (k & 3u) * kTraceLeafWords + (leaf & (kTraceLeafWords - 1u)));
     return rg.BM(k, leaf);
   };
+  // the lowest non-empty rank of a dimension (kNoRank: nothing waits for it),
+  // kept beside the bitmaps: a push lowers it, and when its list runs empty the
+  // bitmaps say which rank is next
+  constexpr uint32_t kNoRank = ~0u;
+  auto LOW = [&](uint32_t k) -> uint32_t& {
+    return *(uint32_t*)lds.dword((kLdsBitmaps ? 16u + 4u * kTraceLeafWords : 48u) + (k & 3u));
+  };
   for (uint32_t k = 0; k < 4u; ++k) {
     for (uint32_t l = 0; l < kTraceLeafWords; ++l) BM(k, l) = 0u;
     for (uint32_t l = 0; l < kTraceSumWords; ++l) SUM(k, l) = 0u;
+    LOW(k) = kNoRank;
   }
 
   // Per dimension (TraceDims): finish and busy time, the chunk it serves
@@ -517,6 +526,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     }
     tops |= 1u << (4u * (k & 3u) + ((leaf >> 5) & 3u));
     work |= 1u << (k & 3u);
+    LOW(k) = min(LOW(k), r);
   };
   // The stores of a push whose bitmap part the caller has done (had: the
   // rank's list had chunks already), given the list's entry as read before (ht, used when
@@ -531,18 +541,17 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     HT(k, r) = entry;
     return entry;
   };
-  // The lowest non-empty rank of a dimension (smallest resident size) and the
-  // bitmap words that lead to it.
-  struct Pick { uint32_t r, leaf, lw, sw, sumw; };
-  // first chunk of the picked rank, given the rank's list entry ht; w
-  // receives its chunk word, size the resident bytes of a chunk of that rank
-  // and row the size ranks of the chunk's collective.  Chunk word and rank row
-  // are loaded together.
+  // first chunk of the list of rank r, the lowest of dimension k, given the
+  // list's entry ht; w receives its chunk word, size the resident bytes of a
+  // chunk of that rank and row the size ranks of the chunk's collective.  Chunk
+  // word and collective record are loaded together, and while they are on
+  // their way the bitmaps are brought up to date: if the list runs empty its bit
+  // goes and the dimension's next lowest rank is looked up (LDS round trips
+  // that the wait on memory hides).
   // new_entry / at: the list's entry once its head is gone, for the caller to
   // store (at = all-ones: nothing to store, the list is empty now)
-  auto pop = [&](uint32_t k, const Pick& p, uint32_t ht, uint32_t& w, double& size, uint4& row_lo,
+  auto pop = [&](uint32_t k, uint32_t r, uint32_t ht, uint32_t& w, double& size, uint4& row_lo,
                  uint4& row_hi, uint32_t& new_entry, uint32_t& at) -> uint32_t {
-    const uint32_t r = p.r, leaf = p.leaf, lw = p.lw, sw = p.sw, sumw = p.sumw;
     const uint32_t h = ht & 0xffffu, tl = ht >> 16;
     w = rg.W(h);
     const uint32_t q = coll_of(h);
@@ -555,21 +564,34 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
     // the same 64 bytes as its rank row (the per-rank size table would be one
     // more line to fetch)
     size = rg.CH(q);
+    if (h == tl) {
+      const uint32_t leaf = r >> 5, sw = (leaf >> 5) & 3u;
+      const uint32_t nlw = BM(k, leaf) & ~(1u << (r & 31u));
+      BM(k, leaf) = nlw;
+      uint32_t next = leaf * 32u + ((uint32_t)__builtin_ctz(nlw | 0x80000000u));
+      if (!nlw) {
+        const uint32_t rest = SUM(k, sw) & ~(1u << (leaf & 31u));
+        SUM(k, sw) = rest;
+        uint32_t sw2 = sw, sumw2 = rest;
+        if (!rest) {
+          tops &= ~(1u << (4u * k + sw));
+          const uint32_t left = (tops >> (4u * k)) & 15u;
+          if (left == 0u) work &= ~(1u << k);
+          sw2 = (uint32_t)__builtin_ctz(left | 16u) & 3u;
+          sumw2 = left ? SUM(k, sw2) : 0u;
+        }
+        next = kNoRank;
+        if (sumw2) {
+          const uint32_t leaf2 = sw2 * 32u + (uint32_t)__builtin_ctz(sumw2);
+          next = leaf2 * 32u + ((uint32_t)__builtin_ctz(BM(k, leaf2) | 0x80000000u));
+        }
+      }
+      LOW(k) = next;
+    }
     if (!divide) size = scale_down(size, esum(epack, w & 15u));
     at = ~0u;
     new_entry = 0u;
-    if (h == tl) {
-      const uint32_t nlw = lw & ~(1u << (r & 31u));
-      BM(k, leaf) = nlw;
-      if (!nlw) {
-        const uint32_t rest = sumw & ~(1u << (leaf & 31u));
-        SUM(k, sw) = rest;
-        if (!rest) {
-          tops &= ~(1u << (4u * k + sw));
-          if (((tops >> (4u * k)) & 15u) == 0u) work &= ~(1u << k);
-        }
-      }
-    } else {
+    if (h != tl) {
       new_entry = (w >> 16) | (tl << 16);
       at = ht_index(k, r);
     }
@@ -627,8 +649,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
   // lanes of the wavefront go on meanwhile.
   const uint64_t max_steps = (uint64_t)4u * D * G + Q + 16u;
   bool picked = false;
-  Pick pk = {0u, 0u, 0u, 0u, 0u};
-  uint32_t pk_k = 0u, pk_ht = 0u;
+  uint32_t pk_k = 0u, pk_r = 0u, pk_ht = 0u;
   for (uint64_t step = 0; step <= max_steps; ++step) {
     // a7: an idle dimension with waiting chunks starts its first one
     if (picked) {
@@ -637,7 +658,7 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       double size;
       uint4 row_lo = {0u, 0u, 0u, 0u}, row_hi = {0u, 0u, 0u, 0u};
       uint32_t new_entry, entry_at;
-      const uint32_t h = pop(k, pk, pk_ht, w, size, row_lo, row_hi, new_entry, entry_at);
+      const uint32_t h = pop(k, pk_r, pk_ht, w, size, row_lo, row_hi, new_entry, entry_at);
       const uint32_t mask = w & 15u, phase = (w >> 4) & 1u;
       const uint32_t ek = (epack >> (8u * k)) & 0xffu;
       // the chunk's state after this stage: a Reduce-Scatter sets the
@@ -722,11 +743,9 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       word = (nx & 0xffffu) | (kNoChunk << 16);
       moves = kn < 4u;
     }
-    // The bitmap work of the push and of the pick, with the reads that do not
-    // depend on each other issued together: the leaf word and the summary word
-    // of the push's rank and the summary word the pick starts from, then the
-    // pick's leaf word (two LDS round trips where one after the other they
-    // take four).
+    // The bitmap part of the push and the pick, with the LDS reads issued
+    // together: the leaf word and the summary word of the push's rank, and the
+    // lowest rank of the dimension that starts a stage next.
     {
       const uint32_t leaf_r = r >> 5, bit_r = 1u << (r & 31u), sw_r = (leaf_r >> 5) & 3u;
       const uint32_t in_sum_r = 1u << (leaf_r & 31u);
@@ -737,30 +756,25 @@ __device__ inline bool simulate_trace_fast(const Scenario& s, uint32_t Q, uint32
       const uint32_t need = idle & work;
       picked = need != 0u;
       pk_k = picked ? (uint32_t)__builtin_ctz(need) : 0u;
-      const uint32_t sw2 = (uint32_t)__builtin_ctz(((tops >> (4u * pk_k)) & 15u) | 16u) & 3u;
       const uint32_t lw_r = BM(kn, leaf_r);
       const uint32_t sum_r = SUM(kn, sw_r);
-      uint32_t sumw2 = SUM(pk_k, sw2);
+      pk_r = LOW(pk_k);
       had = moves && (lw_r & bit_r) != 0u;
-      if (moves && !had) {
-        BM(kn, leaf_r) = lw_r | bit_r;
-        SUM(kn, sw_r) = sum_r | in_sum_r;
-        // (the pick's summary word was read before this store)
-        if (kn == pk_k && sw_r == sw2) sumw2 |= in_sum_r;
-      }
-      if (picked) {
-        pk.sw = sw2;
-        pk.sumw = sumw2;
-        pk.leaf = sw2 * 32u + ((uint32_t)__builtin_ctz(sumw2 | 0x80000000u));
-        pk.lw = BM(pk_k, pk.leaf);   // (after the store above: LDS operations keep their order)
-        pk.r = pk.leaf * 32u + ((uint32_t)__builtin_ctz(pk.lw | 0x80000000u));
+      if (moves) {
+        if (!had) {
+          BM(kn, leaf_r) = lw_r | bit_r;
+          SUM(kn, sw_r) = sum_r | in_sum_r;
+        }
+        // (the dimension's lowest rank was read before it is lowered here)
+        atomicMin(&LOW(kn), r);
+        if (kn == pk_k) pk_r = min(pk_r, r);
       }
     }
     const uint32_t ht_to = HT(kn, r);
-    pk_ht = HT(pk_k, picked ? pk.r : 0u);
+    pk_ht = HT(pk_k, pk_r);
     if (moves) {
       const uint32_t entry = push_link(kn, r, g, word, had, ht_to);
-      if (pk_k == kn && pk.r == r) pk_ht = entry;  // the very list just appended to
+      if (pk_k == kn && pk_r == r) pk_ht = entry;  // the very list just appended to
     }
   }
 
